@@ -1,0 +1,259 @@
+"""CPU fp64 oracle of the Union-of-Experts layer forward pass -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper over ``uoe_oracle.c`` (plain C, double precision, written
+from the paper's Sec. III).  Only ``tests/``, the smoke check and the
+``cpu_baseline`` leg of the benchmark may import this package; the GPU library
+never does, and the two share no code.
+
+Every function takes NumPy arrays, widens them to float64 and returns float64 /
+int32 arrays.  The composition of a whole layer (Sec. III-C: SMHA block, then
+UoME block) is written here, step by step, in the paper's order.
+
+Parity pins: every function here is pinned by ``tests/test_oracle_*.py``
+against closed forms, invariants, brute-force NumPy restatements of the
+definitions and the two lossless-decomposition equivalences of Sec. III-A.  The
+paper prints no worked numeric example of the layer, so absolute output values
+beyond those pins are "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "uoe_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_uoe.so")
+
+RESIDUAL = 1
+GATE_EXPERT = 2
+GATE_PATCH = 4
+
+NEAR_TIE_REL = 1e-5  # a selection whose kept/dropped margin is below this is a near-tie
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no GPU toolchain involved)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        P = ctypes.c_void_p
+        I = ctypes.c_int
+        lib.uoe_oracle_set_threads.argtypes = [I]
+        lib.uoe_oracle_get_threads.restype = I
+        lib.uoe_oracle_data_router_logits.argtypes = [I, I, I, I, I, P, P, P, P, P]
+        lib.uoe_oracle_patch_gate.argtypes = [I, I, I, P, P]
+        lib.uoe_oracle_top_c.argtypes = [I, I, I, I, P, P, P]
+        lib.uoe_oracle_expert_router.argtypes = [I, ctypes.c_long, I, P, P, P, P, P]
+        lib.uoe_oracle_top_k.argtypes = [I, I, I, P, P, P]
+        lib.uoe_oracle_expert_lists.argtypes = [I, I, I, P, P, P]
+        lib.uoe_oracle_smha.argtypes = [I] * 8 + [ctypes.c_uint] + [P] * 10
+        lib.uoe_oracle_uome.argtypes = [I] * 6 + [ctypes.c_uint] + [P] * 6
+        for f in ("data_router_logits", "patch_gate", "top_c", "expert_router", "top_k",
+                  "expert_lists", "smha", "uome", "set_threads"):
+            getattr(lib, "uoe_oracle_" + f).restype = None
+        _lib = lib
+    return _lib
+
+
+def set_threads(t: int) -> None:
+    _L().uoe_oracle_set_threads(int(t))
+
+
+def get_threads() -> int:
+    return int(_L().uoe_oracle_get_threads())
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+# --------------------------------------------------------------------------- routing
+def data_router_logits(x, w_b, w_a, noise=None) -> np.ndarray:
+    """Eq. 13: g'[b,i,j]; x [b,l,d], w_b [d,n], w_a [l,m]."""
+    x, w_b, w_a = _f64(x), _f64(w_b), _f64(w_a)
+    b, l, d = x.shape
+    n, m = w_b.shape[1], w_a.shape[1]
+    assert w_b.shape == (d, n) and w_a.shape == (l, m)
+    nz = None if noise is None else _f64(noise)
+    out = np.empty((b, n, m), np.float64)
+    _L().uoe_oracle_data_router_logits(b, l, d, n, m, _p(x), _p(w_b), _p(w_a), _p(nz), _p(out))
+    return out
+
+
+def patch_gate(gprime) -> np.ndarray:
+    """Eq. 14: softmax over the expert axis for each patch; [b,n,m] -> [b,n,m]."""
+    gprime = _f64(gprime)
+    b, n, m = gprime.shape
+    out = np.empty_like(gprime)
+    _L().uoe_oracle_patch_gate(b, n, m, _p(gprime), _p(out))
+    return out
+
+
+def top_c(g, c: int):
+    """Eq. 17 (+ ascending sort): returns (id [b,n,c] int32, margin [b,n])."""
+    g = _f64(g)
+    b, n, m = g.shape
+    assert 1 <= c <= m
+    idx = np.empty((b, n, c), np.int32)
+    margin = np.empty((b, n), np.float64)
+    _L().uoe_oracle_top_c(b, n, m, c, _p(g), _p(idx), _p(margin))
+    return idx, margin
+
+
+def expert_router(x, w_e, noise=None):
+    """Eq. 21: returns (z [b,n] logits, g [b,n] gates); x [b,l,d], w_e [n, l*d]."""
+    x, w_e = _f64(x), _f64(w_e)
+    b = x.shape[0]
+    ld = int(np.prod(x.shape[1:]))
+    n = w_e.shape[0]
+    assert w_e.shape == (n, ld)
+    nz = None if noise is None else _f64(noise)
+    z = np.empty((b, n), np.float64)
+    g = np.empty((b, n), np.float64)
+    _L().uoe_oracle_expert_router(b, ld, n, _p(x), _p(w_e), _p(nz), _p(z), _p(g))
+    return z, g
+
+
+def top_k(g, k: int):
+    """Eq. 22: returns (id [b,k] int32 ascending, margin [b])."""
+    g = _f64(g)
+    b, n = g.shape
+    assert 1 <= k <= n
+    idx = np.empty((b, k), np.int32)
+    margin = np.empty((b,), np.float64)
+    _L().uoe_oracle_top_k(b, n, k, _p(g), _p(idx), _p(margin))
+    return idx, margin
+
+
+def expert_lists(expert_id, n: int):
+    """Eq. 23: per-expert sample lists; returns (counts [n], lists: list of arrays)."""
+    expert_id = _i32(expert_id)
+    b, k = expert_id.shape
+    counts = np.empty((n,), np.int32)
+    lists = np.zeros((n, b), np.int32)
+    _L().uoe_oracle_expert_lists(b, n, k, _p(expert_id), _p(counts), _p(lists))
+    return counts, [lists[i, :counts[i]].copy() for i in range(n)]
+
+
+@dataclass
+class Routing:
+    expert_id: np.ndarray              # [b,k] int32 ascending
+    expert_gate: np.ndarray            # [b,n]
+    patch_id: np.ndarray               # [b,n,c] int32 ascending
+    patch_gate: np.ndarray             # [b,n,m]
+    expert_margin: np.ndarray          # [b]   (-1: nothing dropped)
+    patch_margin: np.ndarray           # [b,n] (-1: nothing dropped)
+
+    def near_ties(self, rel: float = NEAR_TIE_REL):
+        """Rows whose kept/dropped margin is within `rel`: (expert rows [b], patch rows [b,n])."""
+        e = (self.expert_margin >= 0) & (self.expert_margin <= rel)
+        p = (self.patch_margin >= 0) & (self.patch_margin <= rel)
+        return e, p
+
+
+def route(x, n: int, k: int, m: int, c: int, w_expert=None, w_b=None, w_a=None,
+          noise_expert=None, noise_patch=None) -> Routing:
+    """Both routers of one block, reading the block input (Sec. III-B).
+
+    k == n with no w_expert: every expert active with gate 1.  c == m with no
+    w_b/w_a: every patch kept with gate 1.
+    """
+    x = _f64(x)
+    b, l, d = x.shape
+    if w_expert is None:
+        assert k == n
+        g_e = np.ones((b, n), np.float64)
+    else:
+        _, g_e = expert_router(x, w_expert, noise_expert)
+    e_id, e_margin = top_k(g_e, k)
+    if w_b is None:
+        assert w_a is None and c == m
+        g_d = np.ones((b, n, m), np.float64)
+    else:
+        g_d = patch_gate(data_router_logits(x, w_b, w_a, noise_patch))
+    p_id, p_margin = top_c(g_d, c)
+    return Routing(e_id, g_e, p_id, g_d, e_margin, p_margin)
+
+
+# --------------------------------------------------------------------------- blocks
+def smha(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: int,
+         flags: int = RESIDUAL) -> np.ndarray:
+    """Eq. 27-36 on given routing results; returns u [b,l,d]."""
+    x, wq, wk, wv, wo = _f64(x), _f64(wq), _f64(wk), _f64(wv), _f64(wo)
+    b, l, d = x.shape
+    n, _, d_h = wq.shape
+    expert_id, patch_id = _i32(expert_id), _i32(patch_id)
+    k, c = expert_id.shape[1], patch_id.shape[2]
+    assert wq.shape == wk.shape == wv.shape == (n, d, d_h) and wo.shape == (n, d_h, d)
+    assert l % m == 0 and patch_id.shape == (b, n, c)
+    g_e, g_d = _f64(expert_gate), _f64(patch_gate_)
+    assert g_e.shape == (b, n) and g_d.shape == (b, n, m)
+    out = np.empty((b, l, d), np.float64)
+    _L().uoe_oracle_smha(b, l, d, n, k, m, c, d_h, flags, _p(x), _p(wq), _p(wk), _p(wv), _p(wo),
+                         _p(expert_id), _p(g_e), _p(patch_id), _p(g_d), _p(out))
+    return out
+
+
+def uome(u, a_in, a_out, expert_id, expert_gate, flags: int = RESIDUAL) -> np.ndarray:
+    """Eq. 38-40 (expert-selection mode) on given routing results; returns h [b,l,d]."""
+    u, a_in, a_out = _f64(u), _f64(a_in), _f64(a_out)
+    b, l, d = u.shape
+    n, _, d_e = a_in.shape
+    assert a_in.shape == (n, d, d_e) and a_out.shape == (n, d_e, d)
+    expert_id = _i32(expert_id)
+    k = expert_id.shape[1]
+    g_e = _f64(expert_gate)
+    assert g_e.shape == (b, n)
+    out = np.empty((b, l, d), np.float64)
+    _L().uoe_oracle_uome(b, l, d, n, k, d_e, flags, _p(u), _p(a_in), _p(a_out), _p(expert_id),
+                         _p(g_e), _p(out))
+    return out
+
+
+@dataclass
+class LayerResult:
+    routing_a: Routing
+    u: np.ndarray
+    routing_m: Routing
+    out: np.ndarray
+
+
+def layer_forward(inp, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
+                  flags_m: int = RESIDUAL | GATE_EXPERT) -> LayerResult:
+    """One UoE layer (Sec. III-C): out = UoME(SMHA(x)); `inp` is a LayerInputs-like object.
+
+    The UoME router reads u, the finished SMHA output.
+    """
+    cfg = inp.cfg
+    ra = route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+               inp.noise_a_expert, inp.noise_a_patch)
+    u = smha(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ra.expert_gate, ra.patch_id,
+             ra.patch_gate, cfg.m, flags_a)
+    rm = route(u, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
+    out = uome(u, inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, flags_m)
+    return LayerResult(ra, u, rm, out)
