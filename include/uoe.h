@@ -1,0 +1,170 @@
+/*
+ * uoe.h -- C ABI of the MI355X (gfx950) forward pass of one Union-of-Experts layer
+ * (arXiv 2503.02495, Sec. III).
+ *
+ * Notation is the paper's: b batch, l sequence length, d model dim, n experts,
+ * k experts kept per sample, m patches per sample, l_p = l/m tokens per patch,
+ * c patches kept per expert, l_a = c*l_p tokens one attention expert sees,
+ * `width` = d_h (SMHA head-expert dim) or d_e (UoME expert hidden dim).
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller, row-major,
+ *     contiguous, 16-byte aligned.  The library allocates no device memory,
+ *     keeps no state between calls and never retains a pointer.  Scratch space
+ *     is the caller's `ws` buffer of at least uoe_workspace_bytes() bytes.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and return without waiting.  Calls on distinct
+ *     streams with distinct workspaces may run concurrently.
+ *   - Return value: a uoe_status.  Argument validation happens first, on the
+ *     host, and touches no device state; a rejected call has launched nothing.
+ *     No exceptions, no abort, nothing printed.
+ *   - Storage dtype (x, weights, outputs) is fp32 or bf16; all accumulation is
+ *     fp32; gates are fp32; indices are int32.
+ *   - Inputs must be finite; behaviour on NaN/Inf is unspecified.
+ *   - Shape limits: d % 8 == 0, width % 8 == 0, l % m == 0, 1 <= n <= 32,
+ *     1 <= k <= n, 1 <= c <= m, m <= 1024, width <= 128 for SMHA.  Valid but
+ *     unsupported requests return UOE_ERR_UNSUPPORTED.
+ */
+#ifndef UOE_H
+#define UOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    UOE_OK = 0,
+    UOE_ERR_INVALID_ARG = 1, /* NULL where not allowed, bad sizes, misaligned pointer, aliasing   */
+    UOE_ERR_UNSUPPORTED = 2, /* a valid request outside this build (see shape limits, flags)      */
+    UOE_ERR_WORKSPACE = 3,   /* ws is NULL or ws_bytes is below uoe_workspace_bytes()             */
+    UOE_ERR_DEVICE = 4       /* a kernel launch was refused by the runtime                        */
+} uoe_status;
+
+enum { UOE_F32 = 0, UOE_BF16 = 1 }; /* storage dtype of activations, weights and outputs */
+
+enum {
+    UOE_FLAG_RESIDUAL = 1u << 0,    /* out = in + sum(...)  (Eq. 20/26/36/40); off: out = sum(...)  */
+    UOE_FLAG_GATE_EXPERT = 1u << 1, /* weight an expert's contribution by its Eq. 21 gate g[b,i]    */
+    UOE_FLAG_GATE_PATCH = 1u << 2,  /* weight a patch's contribution by its Eq. 14 gate g[b,i,j]    */
+    UOE_FLAG_CAUSAL = 1u << 3       /* reserved (shared causal mask of Sec. III-C.3): UNSUPPORTED   */
+};
+
+/* One block (SMHA or UoME) of the layer. */
+typedef struct {
+    int32_t b, l, d;     /* batch, sequence length, model dim                                        */
+    int32_t n, k;        /* experts; experts kept per sample (k == n: expert selection off)          */
+    int32_t m, c;        /* patches per sample; patches kept per expert (c == m: data selection off) */
+    int32_t width;       /* d_h (SMHA) or d_e (UoME)                                                  */
+    int32_t dtype;       /* UOE_F32 | UOE_BF16                                                        */
+    uint32_t flags;      /* UOE_FLAG_*                                                                */
+    int32_t rope_dim;    /* reserved (partial RoPE of Eq. 32): must be 0                              */
+    int32_t reserved[5]; /* must be 0                                                                 */
+} uoe_block_desc;
+
+/* Bytes of workspace that any call on these blocks needs (either may be NULL).
+ * Returns 0 if a given descriptor is invalid. */
+size_t uoe_workspace_bytes(const uoe_block_desc *smha, const uoe_block_desc *uome);
+
+/* Static text for a uoe_status value. */
+const char *uoe_status_string(int status);
+
+/*
+ * Routing of one block (Sec. III-B): expert selection, Eq. 21-22, and
+ * patch-wise data selection, Eq. 13, 14 and 17, both reading the block input x.
+ *
+ *   x            [b,l,d]   block input (device, dtype)
+ *   w_expert     [n, l*d]  expert router weights; NULL iff k == n and the gate is to be 1
+ *   w_b, w_a     [d,n], [l,m]  data router: per-token map d->n, then map l->m over the
+ *                          transposed result (Eq. 13); both NULL iff c == m and gate 1
+ *   noise_expert [b,n] fp32, noise_patch [b,n,m] fp32: optional additive logit noise, or NULL
+ * Outputs (device, caller-owned):
+ *   expert_idx   [b,k] int32   the k experts with the largest gate, ascending index;
+ *                              ties go to the lower index
+ *   expert_gate  [b,n] fp32    softmax over experts of the Eq. 21 logits
+ *   patch_idx    [b,n,c] int32 for EVERY expert the c patches with the largest Eq. 14 gate
+ *                              (ranked on the gate value, not the logit), ascending index
+ *   patch_gate   [b,n,m] fp32  Eq. 14: softmax over the n experts for each patch
+ * For a UoME block in expert-selection mode pass m = c = 1 and w_b = w_a = NULL.
+ */
+int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, const void *w_b,
+              const void *w_a, const float *noise_expert, const float *noise_patch,
+              int32_t *expert_idx, float *expert_gate, int32_t *patch_idx, float *patch_gate,
+              void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Index selection of Eq. 18 / 24 as a standalone copy: for every active unit
+ * (sample b, slot s < k, expert i = expert_idx[b,s]) the l_a selected token rows
+ * of x, in ascending position, into h[b,s,:,:].
+ *   h   [b,k,l_a,d]  (device, dtype).  Needs no workspace.
+ * (The SMHA call below does this selection inside its projection kernel; this
+ * entry point exists for callers that want the compacted buffer itself.)
+ */
+int uoe_gather(const uoe_block_desc *blk, const void *x, const int32_t *expert_idx,
+               const int32_t *patch_idx, void *h, void *hip_stream);
+
+/*
+ * Selective Multi-Head Attention on given routing results (Eq. 27-36):
+ * for every active unit gather its l_a tokens, project with W^q_i, W^k_i, W^v_i
+ * (Eq. 28-30), softmax(q k^T / sqrt(d_h)) v jointly over the l_a tokens
+ * (Eq. 33-34), project with W^o_i (Eq. 35), and add the rows back at the
+ * positions they came from (Eq. 36), weighted per the gate flags.
+ *   wq, wk, wv [n,d,d_h]; wo [n,d_h,d]; routing tensors as written by uoe_route
+ *   (expert_gate / patch_gate may be NULL when the matching gate flag is off)
+ *   out [b,l,d] must not alias x.  Rows of patches no active expert selected are
+ *   x (or 0 without UOE_FLAG_RESIDUAL) exactly.  Deterministic: no atomics.
+ */
+int uoe_smha_forward(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
+                     const void *wv, const void *wo, const int32_t *expert_idx,
+                     const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
+                     void *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Union-of-MLP-Experts in expert-selection mode on given routing results
+ * (Eq. 38-40 with Eq. 24-26): out[b] = u[b] + sum over the sample's k experts of
+ * gate * SiLU(u[b] A^I_i) A^O_i.  The second layer is linear.
+ *   a_in [n,d,d_e]; a_out [n,d_e,d]; expert_idx [b,k]; expert_gate [b,n] or NULL
+ *   patch_idx / patch_gate must be NULL and blk->c == blk->m (data-selection UoME
+ *   is not in this build: UOE_ERR_UNSUPPORTED).
+ *   out [b,l,d] must not alias u.  Deterministic: no atomics.
+ */
+int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
+                     const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
+                     const float *patch_gate, void *out, void *ws, size_t ws_bytes,
+                     void *hip_stream);
+
+typedef struct {
+    const void *w_expert, *w_b, *w_a, *wq, *wk, *wv, *wo;
+} uoe_smha_weights;
+
+typedef struct {
+    const void *w_expert, *a_in, *a_out;
+} uoe_uome_weights;
+
+/* Optional copies of a block's routing results; any member may be NULL. */
+typedef struct {
+    int32_t *expert_idx;
+    float *expert_gate;
+    int32_t *patch_idx;
+    float *patch_gate;
+} uoe_routing_out;
+
+/*
+ * One UoE layer (Sec. III-C): route on x, SMHA -> u; route on u with the UoME
+ * router, UoME -> out.  `smha` and `uome` must agree on b, l, d and dtype; the
+ * UoME descriptor has m == c (expert-selection mode; the patch members of
+ * `routing_m` are not written).  out must not alias x.
+ */
+int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
+                      const float *noise_a_expert, const float *noise_a_patch,
+                      const uoe_block_desc *uome, const uoe_uome_weights *wm,
+                      const float *noise_m_expert, const void *x, void *out,
+                      const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, void *ws,
+                      size_t ws_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UOE_H */

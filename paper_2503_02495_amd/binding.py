@@ -1,0 +1,174 @@
+"""ctypes binding of libuoe.so: same names as the C ABI (include/uoe.h), argument marshalling only.
+
+Tensor arguments may be torch tensors (anything with ``data_ptr()``), raw integer device
+addresses, or None.  Nothing here computes: every step of the layer runs in the library's HIP
+kernels.  There is no fallback -- if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libuoe.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, 1, 2, 3, 4
+F32, BF16 = 0, 1
+FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
+
+EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_gather", "uoe_smha_forward",
+           "uoe_uome_forward", "uoe_layer_forward")
+
+
+class UoeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (uoe_status {status})")
+
+
+class BlockDesc(ctypes.Structure):
+    _fields_ = [("b", ctypes.c_int32), ("l", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("n", ctypes.c_int32), ("k", ctypes.c_int32), ("m", ctypes.c_int32),
+                ("c", ctypes.c_int32), ("width", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("flags", ctypes.c_uint32), ("rope_dim", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 5)]
+
+
+class SmhaWeights(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_void_p) for f in ("w_expert", "w_b", "w_a", "wq", "wk", "wv", "wo")]
+
+
+class UomeWeights(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_void_p) for f in ("w_expert", "a_in", "a_out")]
+
+
+class RoutingOut(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_void_p) for f in ("expert_idx", "expert_gate", "patch_idx", "patch_gate")]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (there is no CPU fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2503_02495_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        P, S = ctypes.c_void_p, ctypes.c_size_t
+        D = ctypes.POINTER(BlockDesc)
+        L.uoe_workspace_bytes.argtypes = [D, D]
+        L.uoe_workspace_bytes.restype = S
+        L.uoe_status_string.argtypes = [ctypes.c_int]
+        L.uoe_status_string.restype = ctypes.c_char_p
+        L.uoe_route.argtypes = [D] + [P] * 10 + [P, S, P]
+        L.uoe_gather.argtypes = [D, P, P, P, P, P]
+        L.uoe_smha_forward.argtypes = [D] + [P] * 10 + [P, S, P]
+        L.uoe_uome_forward.argtypes = [D] + [P] * 8 + [P, S, P]
+        L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
+                                        P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
+                                        P, S, P]
+        for f in ("uoe_route", "uoe_gather", "uoe_smha_forward", "uoe_uome_forward", "uoe_layer_forward"):
+            getattr(L, f).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _nbytes(t) -> int:
+    return int(t.numel() * t.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def _ref(d: Optional[BlockDesc]):
+    return None if d is None else ctypes.byref(d)
+
+
+def _done(status: int, where: str, check: bool) -> int:
+    if check and status != OK:
+        raise UoeError(status, where)
+    return status
+
+
+def block_desc(b, l, d, n, k, m, c, width, dtype, flags, rope_dim=0) -> BlockDesc:
+    return BlockDesc(b, l, d, n, k, m, c, width, dtype, flags, rope_dim, (ctypes.c_int32 * 5)())
+
+
+def status_string(status: int) -> str:
+    return lib().uoe_status_string(int(status)).decode()
+
+
+def workspace_bytes(smha: Optional[BlockDesc], uome: Optional[BlockDesc]) -> int:
+    return int(lib().uoe_workspace_bytes(_ref(smha), _ref(uome)))
+
+
+def route(blk, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx, expert_gate, patch_idx,
+          patch_gate, ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_route(_ref(blk), _ptr(x), _ptr(w_expert), _ptr(w_b), _ptr(w_a), _ptr(noise_expert),
+                         _ptr(noise_patch), _ptr(expert_idx), _ptr(expert_gate), _ptr(patch_idx),
+                         _ptr(patch_gate), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+                         _stream(stream))
+    return _done(st, "uoe_route", check)
+
+
+def gather(blk, x, expert_idx, patch_idx, h, stream=None, check=True) -> int:
+    st = lib().uoe_gather(_ref(blk), _ptr(x), _ptr(expert_idx), _ptr(patch_idx), _ptr(h), _stream(stream))
+    return _done(st, "uoe_gather", check)
+
+
+def smha_forward(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, out, ws,
+                 stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_smha_forward(_ref(blk), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo), _ptr(expert_idx),
+                                _ptr(expert_gate), _ptr(patch_idx), _ptr(patch_gate), _ptr(out), _ptr(ws),
+                                _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_smha_forward", check)
+
+
+def uome_forward(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_gate, out, ws,
+                 stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_uome_forward(_ref(blk), _ptr(u), _ptr(a_in), _ptr(a_out), _ptr(expert_idx),
+                                _ptr(expert_gate), _ptr(patch_idx), _ptr(patch_gate), _ptr(out), _ptr(ws),
+                                _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_uome_forward", check)
+
+
+def smha_weights(w_expert, w_b, w_a, wq, wk, wv, wo) -> SmhaWeights:
+    return SmhaWeights(*(_ptr(t) for t in (w_expert, w_b, w_a, wq, wk, wv, wo)))
+
+
+def uome_weights(w_expert, a_in, a_out) -> UomeWeights:
+    return UomeWeights(*(_ptr(t) for t in (w_expert, a_in, a_out)))
+
+
+def routing_out(expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None) -> RoutingOut:
+    return RoutingOut(*(_ptr(t) for t in (expert_idx, expert_gate, patch_idx, patch_gate)))
+
+
+def layer_forward(smha, wa: SmhaWeights, noise_a_expert, noise_a_patch, uome, wm: UomeWeights,
+                  noise_m_expert, x, out, routing_a: Optional[RoutingOut], routing_m: Optional[RoutingOut],
+                  ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_layer_forward(_ref(smha), ctypes.byref(wa) if wa is not None else None, _ptr(noise_a_expert),
+                                 _ptr(noise_a_patch), _ref(uome), ctypes.byref(wm) if wm is not None else None,
+                                 _ptr(noise_m_expert), _ptr(x), _ptr(out),
+                                 ctypes.byref(routing_a) if routing_a is not None else None,
+                                 ctypes.byref(routing_m) if routing_m is not None else None, _ptr(ws),
+                                 _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_layer_forward", check)

@@ -1,0 +1,326 @@
+// C ABI of libuoe: host-side argument validation, workspace carving and kernel dispatch.
+// Nothing here allocates or synchronises; every entry point validates, then enqueues.
+#include "../../include/uoe.h"
+#include "common.h"
+
+using namespace uoe;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t v) { return (v + ALIGN - 1) & ~(ALIGN - 1); }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_size(int dtype) { return dtype == UOE_BF16 ? 2 : 4; }
+
+// Generic descriptor checks shared by every call.  `smha` additionally bounds the head dim.
+int check_desc(const uoe_block_desc *d, bool smha)
+{
+    if (!d) return UOE_ERR_INVALID_ARG;
+    if (d->b < 1 || d->l < 1 || d->d < 1 || d->n < 1 || d->k < 1 || d->k > d->n || d->m < 1 ||
+        d->c < 1 || d->c > d->m || d->width < 1 || (d->l % d->m) != 0)
+        return UOE_ERR_INVALID_ARG;
+    if (d->dtype != UOE_F32 && d->dtype != UOE_BF16) return UOE_ERR_INVALID_ARG;
+    if (d->flags & ~(uint32_t)(UOE_FLAG_RESIDUAL | UOE_FLAG_GATE_EXPERT | UOE_FLAG_GATE_PATCH | UOE_FLAG_CAUSAL))
+        return UOE_ERR_INVALID_ARG;
+    for (int i = 0; i < 5; ++i)
+        if (d->reserved[i] != 0) return UOE_ERR_INVALID_ARG;
+    if (d->rope_dim < 0) return UOE_ERR_INVALID_ARG;
+    if (d->rope_dim != 0 || (d->flags & UOE_FLAG_CAUSAL)) return UOE_ERR_UNSUPPORTED;
+    if (d->n > 32 || (d->d % 8) != 0 || (d->width % 8) != 0 || d->m > 1024) return UOE_ERR_UNSUPPORTED;
+    if ((long)d->n * d->m > 8192) return UOE_ERR_UNSUPPORTED;
+    if ((long)d->b * d->m > 65535 || (long)d->b * d->k > 65535) return UOE_ERR_UNSUPPORTED;
+    const long wide = (long)d->k * d->width > d->d ? (long)d->k * d->width : d->d;
+    if ((double)d->b * d->l * (double)wide > 1.0e12) return UOE_ERR_UNSUPPORTED;  // keeps all index math in range
+    if (smha && d->width > 128) return UOE_ERR_UNSUPPORTED;
+    return UOE_OK;
+}
+
+struct RouteWs {
+    int tc, nchunks;
+    size_t zpart, gpart, zred, gred, total;
+};
+RouteWs route_ws(int b, int l, int n, int m)
+{
+    RouteWs w;
+    w.tc = route_tokens_per_chunk(b, l);
+    w.nchunks = (l + w.tc - 1) / w.tc;
+    size_t off = 0;
+    w.zpart = off; off += up((size_t)w.nchunks * b * n * sizeof(float));
+    w.gpart = off; off += up((size_t)w.nchunks * b * n * m * sizeof(float));
+    w.zred = off;  off += up((size_t)b * n * sizeof(float));
+    w.gred = off;  off += up((size_t)b * n * m * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+struct SmhaWs {
+    size_t q, k, v, o, inv_cnt, inv_ent, total;
+};
+SmhaWs smha_ws(const uoe_block_desc *d)
+{
+    SmhaWs w;
+    const size_t l_a = (size_t)d->c * (d->l / d->m);
+    const size_t one = up((size_t)d->b * d->k * l_a * d->width * elem_size(d->dtype));
+    size_t off = 0;
+    w.q = off; off += one;
+    w.k = off; off += one;
+    w.v = off; off += one;
+    w.o = off; off += one;
+    w.inv_cnt = off; off += up((size_t)d->b * d->m * sizeof(int32_t));
+    w.inv_ent = off; off += up((size_t)d->b * d->m * d->k * sizeof(int32_t));
+    w.total = off;
+    return w;
+}
+
+size_t uome_ws(const uoe_block_desc *d)
+{
+    return up((size_t)d->b * d->l * d->k * d->width * elem_size(d->dtype));
+}
+
+struct RoutingBuf {
+    size_t expert_idx, expert_gate, patch_idx, patch_gate, total;
+};
+RoutingBuf routing_buf(const uoe_block_desc *d, int m, int c)
+{
+    RoutingBuf r;
+    size_t off = 0;
+    r.expert_idx = off;  off += up((size_t)d->b * d->k * sizeof(int32_t));
+    r.expert_gate = off; off += up((size_t)d->b * d->n * sizeof(float));
+    r.patch_idx = off;   off += up((size_t)d->b * d->n * c * sizeof(int32_t));
+    r.patch_gate = off;  off += up((size_t)d->b * d->n * m * sizeof(float));
+    r.total = off;
+    return r;
+}
+
+inline char *at(void *ws, size_t off) { return static_cast<char *>(ws) + off; }
+
+// validated routing launch; `m`/`c` are passed separately so a UoME block routes with m = c = 1
+int do_route(const uoe_block_desc *blk, int m, int c, const void *x, const void *w_expert, const void *w_b,
+             const void *w_a, const float *noise_expert, const float *noise_patch, int32_t *expert_idx,
+             float *expert_gate, int32_t *patch_idx, float *patch_gate, void *ws, size_t ws_bytes,
+             hipStream_t st)
+{
+    if (!x || !aligned16(x) || !aligned16(w_expert) || !aligned16(w_b) || !aligned16(w_a))
+        return UOE_ERR_INVALID_ARG;
+    if ((w_b == nullptr) != (w_a == nullptr)) return UOE_ERR_INVALID_ARG;
+    if (!w_expert && blk->k != blk->n) return UOE_ERR_INVALID_ARG;
+    if (!w_b && c != m) return UOE_ERR_INVALID_ARG;
+    if ((!w_expert && noise_expert) || (!w_b && noise_patch)) return UOE_ERR_INVALID_ARG;
+    // the data router stages W_B (n*d elements) in LDS
+    if (w_b && (size_t)blk->n * blk->d * elem_size(blk->dtype) > 48 * 1024) return UOE_ERR_UNSUPPORTED;
+    const RouteWs w = route_ws(blk->b, blk->l, blk->n, m);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+
+    RouteArgs a{};
+    a.x = x; a.w_e = w_expert; a.w_b = w_b; a.w_a = w_a;
+    a.noise_e = noise_expert; a.noise_p = noise_patch;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = m; a.c = c;
+    a.tc = w.tc; a.nchunks = w.nchunks;
+    a.zpart = reinterpret_cast<float *>(at(ws, w.zpart));
+    a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
+    a.zred = reinterpret_cast<float *>(at(ws, w.zred));
+    a.gred = reinterpret_cast<float *>(at(ws, w.gred));
+    a.expert_idx = expert_idx; a.patch_idx = patch_idx;
+    a.expert_gate = expert_gate; a.patch_gate = patch_gate;
+    return launch_route(a, blk->dtype == UOE_BF16, st) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+int do_smha(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk, const void *wv,
+            const void *wo, const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
+            const float *patch_gate, void *out, void *ws, size_t ws_bytes, hipStream_t st)
+{
+    if (!x || !wq || !wk || !wv || !wo || !expert_idx || !patch_idx || !out) return UOE_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(wo) || !aligned16(out))
+        return UOE_ERR_INVALID_ARG;
+    if (out == x) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_EXPERT) && !expert_gate) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_PATCH) && !patch_gate) return UOE_ERR_INVALID_ARG;
+    const SmhaWs w = smha_ws(blk);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+
+    SmhaArgs a{};
+    a.x = x; a.wq = wq; a.wk = wk; a.wv = wv; a.wo = wo;
+    a.expert_idx = expert_idx; a.patch_idx = patch_idx;
+    a.expert_gate = expert_gate; a.patch_gate = patch_gate;
+    a.out = out;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = blk->m; a.c = blk->c;
+    a.d_h = blk->width; a.flags = blk->flags;
+    a.q = at(ws, w.q); a.kk = at(ws, w.k); a.v = at(ws, w.v); a.o = at(ws, w.o);
+    a.inv_cnt = reinterpret_cast<int32_t *>(at(ws, w.inv_cnt));
+    a.inv_ent = reinterpret_cast<int32_t *>(at(ws, w.inv_ent));
+    return launch_smha(a, blk->dtype == UOE_BF16, st) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+int do_uome(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
+            const int32_t *expert_idx, const float *expert_gate, void *out, void *ws, size_t ws_bytes,
+            hipStream_t st)
+{
+    if (!u || !a_in || !a_out || !expert_idx || !out) return UOE_ERR_INVALID_ARG;
+    if (!aligned16(u) || !aligned16(a_in) || !aligned16(a_out) || !aligned16(out)) return UOE_ERR_INVALID_ARG;
+    if (out == u) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_EXPERT) && !expert_gate) return UOE_ERR_INVALID_ARG;
+    if (blk->flags & UOE_FLAG_GATE_PATCH) return UOE_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < uome_ws(blk) || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+
+    UomeArgs a{};
+    a.u = u; a.a_in = a_in; a.a_out = a_out;
+    a.expert_idx = expert_idx; a.expert_gate = expert_gate;
+    a.out = out;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.d_e = blk->width;
+    a.flags = blk->flags;
+    a.hidden = ws;
+    return launch_uome(a, blk->dtype == UOE_BF16, st) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *uoe_status_string(int status)
+{
+    switch (status) {
+        case UOE_OK: return "ok";
+        case UOE_ERR_INVALID_ARG: return "invalid argument";
+        case UOE_ERR_UNSUPPORTED: return "valid request not supported by this build";
+        case UOE_ERR_WORKSPACE: return "workspace missing or too small";
+        case UOE_ERR_DEVICE: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t uoe_workspace_bytes(const uoe_block_desc *smha, const uoe_block_desc *uome)
+{
+    size_t total = 0;
+    if (smha) {
+        if (check_desc(smha, true) != UOE_OK) return 0;
+        total += route_ws(smha->b, smha->l, smha->n, smha->m).total + smha_ws(smha).total +
+                 routing_buf(smha, smha->m, smha->c).total;
+    }
+    if (uome) {
+        if (check_desc(uome, false) != UOE_OK) return 0;
+        total += route_ws(uome->b, uome->l, uome->n, uome->m).total + uome_ws(uome) +
+                 routing_buf(uome, uome->m, uome->c).total;
+    }
+    if (smha && uome) total += up((size_t)smha->b * smha->l * smha->d * elem_size(smha->dtype));  // u
+    return total;
+}
+
+int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, const void *w_b,
+              const void *w_a, const float *noise_expert, const float *noise_patch,
+              int32_t *expert_idx, float *expert_gate, int32_t *patch_idx, float *patch_gate,
+              void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_desc(blk, false);
+    if (rc != UOE_OK) return rc;
+    return do_route(blk, blk->m, blk->c, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx,
+                    expert_gate, patch_idx, patch_gate, ws, ws_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int uoe_gather(const uoe_block_desc *blk, const void *x, const int32_t *expert_idx,
+               const int32_t *patch_idx, void *h, void *hip_stream)
+{
+    const int rc = check_desc(blk, false);
+    if (rc != UOE_OK) return rc;
+    if (!x || !expert_idx || !patch_idx || !h || !aligned16(x) || !aligned16(h) || h == x)
+        return UOE_ERR_INVALID_ARG;
+    GatherArgs a{};
+    a.x = x; a.expert_idx = expert_idx; a.patch_idx = patch_idx; a.h = h;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = blk->m; a.c = blk->c;
+    return launch_gather(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+int uoe_smha_forward(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
+                     const void *wv, const void *wo, const int32_t *expert_idx,
+                     const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
+                     void *out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_desc(blk, true);
+    if (rc != UOE_OK) return rc;
+    return do_smha(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, out, ws, ws_bytes,
+                   static_cast<hipStream_t>(hip_stream));
+}
+
+int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
+                     const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
+                     const float *patch_gate, void *out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_desc(blk, false);
+    if (rc != UOE_OK) return rc;
+    if (blk->c != blk->m || patch_idx || patch_gate) return UOE_ERR_UNSUPPORTED;  // data-selection UoME
+    return do_uome(blk, u, a_in, a_out, expert_idx, expert_gate, out, ws, ws_bytes,
+                   static_cast<hipStream_t>(hip_stream));
+}
+
+int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
+                      const float *noise_a_expert, const float *noise_a_patch,
+                      const uoe_block_desc *uome, const uoe_uome_weights *wm,
+                      const float *noise_m_expert, const void *x, void *out,
+                      const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, void *ws,
+                      size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_desc(smha, true);
+    if (rc != UOE_OK) return rc;
+    rc = check_desc(uome, false);
+    if (rc != UOE_OK) return rc;
+    if (!wa || !wm || !x || !out || out == x) return UOE_ERR_INVALID_ARG;
+    if (smha->b != uome->b || smha->l != uome->l || smha->d != uome->d || smha->dtype != uome->dtype)
+        return UOE_ERR_INVALID_ARG;
+    if (uome->c != uome->m) return UOE_ERR_UNSUPPORTED;
+    // everything the per-block launches would reject is rejected here, before the first launch
+    if (!wa->wq || !wa->wk || !wa->wv || !wa->wo || !wm->a_in || !wm->a_out) return UOE_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(out) || !aligned16(wa->w_expert) || !aligned16(wa->w_b) || !aligned16(wa->w_a) ||
+        !aligned16(wa->wq) || !aligned16(wa->wk) || !aligned16(wa->wv) || !aligned16(wa->wo) ||
+        !aligned16(wm->w_expert) || !aligned16(wm->a_in) || !aligned16(wm->a_out))
+        return UOE_ERR_INVALID_ARG;
+    if ((wa->w_b == nullptr) != (wa->w_a == nullptr)) return UOE_ERR_INVALID_ARG;
+    if ((!wa->w_expert && smha->k != smha->n) || (!wa->w_b && smha->c != smha->m) ||
+        (!wm->w_expert && uome->k != uome->n))
+        return UOE_ERR_INVALID_ARG;
+    if ((!wa->w_expert && noise_a_expert) || (!wa->w_b && noise_a_patch) || (!wm->w_expert && noise_m_expert))
+        return UOE_ERR_INVALID_ARG;
+    if (wa->w_b && (size_t)smha->n * smha->d * elem_size(smha->dtype) > 48 * 1024) return UOE_ERR_UNSUPPORTED;
+    if (uome->flags & UOE_FLAG_GATE_PATCH) return UOE_ERR_UNSUPPORTED;
+    const size_t need = uoe_workspace_bytes(smha, uome);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    // workspace: [u][routing A][routing M][route scratch A][smha scratch][route scratch M][uome scratch]
+    size_t off = 0;
+    void *u = at(ws, off);
+    off += up((size_t)smha->b * smha->l * smha->d * elem_size(smha->dtype));
+    const RoutingBuf ra = routing_buf(smha, smha->m, smha->c);
+    char *rabuf = at(ws, off); off += ra.total;
+    const RoutingBuf rm = routing_buf(uome, uome->m, uome->c);
+    char *rmbuf = at(ws, off); off += rm.total;
+    const size_t route_a_bytes = route_ws(smha->b, smha->l, smha->n, smha->m).total;
+    void *route_a_ws = at(ws, off); off += route_a_bytes;
+    const size_t smha_bytes = smha_ws(smha).total;
+    void *smha_scratch = at(ws, off); off += smha_bytes;
+    const size_t route_m_bytes = route_ws(uome->b, uome->l, uome->n, uome->m).total;
+    void *route_m_ws = at(ws, off); off += route_m_bytes;
+    void *uome_scratch = at(ws, off);
+    const size_t uome_bytes = uome_ws(uome);
+
+    auto pick = [](void *user, char *base, size_t o) -> void * { return user ? user : base + o; };
+    int32_t *a_eidx = static_cast<int32_t *>(pick(routing_a ? routing_a->expert_idx : nullptr, rabuf, ra.expert_idx));
+    float *a_egate = static_cast<float *>(pick(routing_a ? routing_a->expert_gate : nullptr, rabuf, ra.expert_gate));
+    int32_t *a_pidx = static_cast<int32_t *>(pick(routing_a ? routing_a->patch_idx : nullptr, rabuf, ra.patch_idx));
+    float *a_pgate = static_cast<float *>(pick(routing_a ? routing_a->patch_gate : nullptr, rabuf, ra.patch_gate));
+    int32_t *m_eidx = static_cast<int32_t *>(pick(routing_m ? routing_m->expert_idx : nullptr, rmbuf, rm.expert_idx));
+    float *m_egate = static_cast<float *>(pick(routing_m ? routing_m->expert_gate : nullptr, rmbuf, rm.expert_gate));
+
+    rc = do_route(smha, smha->m, smha->c, x, wa->w_expert, wa->w_b, wa->w_a, noise_a_expert, noise_a_patch,
+                  a_eidx, a_egate, a_pidx, a_pgate, route_a_ws, route_a_bytes, st);
+    if (rc != UOE_OK) return rc;
+    rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, a_eidx, a_egate, a_pidx, a_pgate, u, smha_scratch,
+                 smha_bytes, st);
+    if (rc != UOE_OK) return rc;
+    // the UoME router reads u, the finished SMHA output (expert-selection mode: one patch = the sample)
+    rc = do_route(uome, 1, 1, u, wm->w_expert, nullptr, nullptr, noise_m_expert, nullptr, m_eidx, m_egate,
+                  nullptr, nullptr, route_m_ws, route_m_bytes, st);
+    if (rc != UOE_OK) return rc;
+    return do_uome(uome, u, wm->a_in, wm->a_out, m_eidx, m_egate, out, uome_scratch, uome_bytes, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Shared device helpers and the internal launcher interface of libuoe (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace uoe {
+
+// ---------------------------------------------------------------- storage types
+struct bf16_t {
+    uint16_t v;
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.v) << 16); }
+
+// round to nearest, ties to even (inputs are finite by contract)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ T from_f32(float f);
+template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f)
+{
+    bf16_t r;
+    r.v = f32_to_bf16_bits(f);
+    return r;
+}
+
+// 8 consecutive elements (16-byte aligned for bf16, 32-byte span for fp32) -> fp32
+__device__ __forceinline__ void load8(const float *p, float (&o)[8])
+{
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t *p, float (&o)[8])
+{
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    o[0] = __uint_as_float(a.x << 16); o[1] = __uint_as_float(a.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(a.y << 16); o[3] = __uint_as_float(a.y & 0xFFFF0000u);
+    o[4] = __uint_as_float(a.z << 16); o[5] = __uint_as_float(a.z & 0xFFFF0000u);
+    o[6] = __uint_as_float(a.w << 16); o[7] = __uint_as_float(a.w & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Routing indices are caller data: clamp them into [0, count) so that a corrupt index can read the
+// wrong row but never leave the tensor.
+__device__ __forceinline__ int clampi(int v, int count) { return min(max(v, 0), count - 1); }
+
+__device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---------------------------------------------------------------- flags (mirror of the ABI values)
+constexpr uint32_t F_RESIDUAL = 1u, F_GATE_EXPERT = 2u, F_GATE_PATCH = 4u;
+
+// ---------------------------------------------------------------- launcher arguments
+struct RouteArgs {
+    const void *x, *w_e, *w_b, *w_a;          // w_e NULL: no expert router; w_b NULL: no data router
+    const float *noise_e, *noise_p;
+    int b, l, d, n, k, m, c;
+    int tc, nchunks;                          // tokens per chunk, chunks per sample
+    float *zpart, *gpart;                     // [nchunks, b, n], [nchunks, b, n*m]
+    float *zred, *gred;                       // [b, n], [b, n*m]
+    int32_t *expert_idx, *patch_idx;          // outputs (any may be NULL)
+    float *expert_gate, *patch_gate;
+};
+
+struct SmhaArgs {
+    const void *x, *wq, *wk, *wv, *wo;
+    const int32_t *expert_idx, *patch_idx;
+    const float *expert_gate, *patch_gate;    // NULL when the matching flag is off
+    void *out;
+    int b, l, d, n, k, m, c, d_h;
+    uint32_t flags;
+    // workspace
+    void *q, *kk, *v, *o;                     // [b*k, l_a, d_h] each, storage dtype
+    int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k]: which (slot s, pick t) chose patch p
+};
+
+struct UomeArgs {
+    const void *u, *a_in, *a_out;
+    const int32_t *expert_idx;
+    const float *expert_gate;                 // NULL when GATE_EXPERT is off
+    void *out;
+    int b, l, d, n, k, d_e;
+    uint32_t flags;
+    void *hidden;                             // [b, l, k*d_e], storage dtype
+};
+
+struct GatherArgs {
+    const void *x;
+    const int32_t *expert_idx, *patch_idx;
+    void *h;
+    int b, l, d, n, k, m, c;
+};
+
+// Launchers: enqueue on `st`, return the runtime's launch status.
+hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_gather(const GatherArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_uome(const UomeArgs &a, bool bf16, hipStream_t st);
+
+// host-side sizing shared by api.cpp and the launchers
+int route_tokens_per_chunk(int b, int l);
+
+}  // namespace uoe

@@ -1,0 +1,158 @@
+// The four contractions of the layer, each stated as a grouped GEMM "problem":
+// for a group g, C[M(g), N] = A[M(g), K(g)] * B[K(g), N] with an epilogue, where the rows of A and
+// the rows/columns of B are resolved through the routing indices.  A problem is a small POD
+// passed by value to a GEMM engine; engines ask it for
+//   rows(g), kdim(g), ncols()            problem extents
+//   a_ptr(g, m, kk)  pointer to A[m][kk..kk+8)   (kk % 8 == 0; 8 elements contiguous)
+//   b_ptr(g, kk, nn) pointer to B[kk][nn..nn+8)  (nn % 8 == 0; 8 elements contiguous)
+//   store(g, m, nn, v) epilogue for one element
+// K and N are concatenations of per-expert segments of length `width`; since width % 8 == 0 an
+// 8-element run never straddles two experts.
+#pragma once
+#include "common.h"
+
+namespace uoe {
+
+// ---------------------------------------------------------------------------------------------
+// SMHA Eq. 28-30 with the index selection of Eq. 18 folded into the A-row lookup.
+// group = active unit (b, slot s); M = l_a; K = d; N = 3*d_h laid out [q | k | v].
+template <typename T> struct QkvProblem {
+    const T *x, *wq, *wk, *wv;
+    const int32_t *expert_idx, *patch_idx;
+    T *q, *k, *v;  // [units, l_a, d_h]
+    int l, d, n, kact, m, c, l_p, l_a, d_h;
+
+    __device__ int rows(int) const { return l_a; }
+    __device__ int kdim(int) const { return d; }
+    __device__ int ncols() const { return 3 * d_h; }
+    __device__ int expert(int g) const { return clampi(expert_idx[g], n); }
+    __device__ int token(int g, int r) const
+    {
+        const int bb = g / kact;
+        const int i = expert(g);
+        const int t = r / l_p;
+        return clampi(patch_idx[((size_t)bb * n + i) * c + t], m) * l_p + (r - t * l_p);
+    }
+    __device__ const T *a_ptr(int g, int r, int kk) const
+    {
+        const int bb = g / kact;
+        return x + ((size_t)bb * l + token(g, r)) * d + kk;
+    }
+    __device__ const T *b_ptr(int g, int kk, int nn) const
+    {
+        const int i = expert(g);
+        const int which = nn / d_h, col = nn - which * d_h;
+        const T *w = which == 0 ? wq : (which == 1 ? wk : wv);
+        return w + ((size_t)i * d + kk) * d_h + col;
+    }
+    __device__ void store(int g, int r, int nn, float val) const
+    {
+        const int which = nn / d_h, col = nn - which * d_h;
+        T *o = which == 0 ? q : (which == 1 ? k : v);
+        o[((size_t)g * l_a + r) * d_h + col] = from_f32<T>(val);
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// SMHA Eq. 35 + Eq. 36, output-stationary: group = (b, patch p); M = l_p; N = d;
+// K = (number of active experts that picked p) * d_h.  The per-expert products o_i W^o_i that land
+// on the same patch are summed as one contraction over the concatenated K, so each output row is
+// written exactly once (residual added in the epilogue) and no atomics are needed.
+// o already carries the gate weight of its row.
+template <typename T> struct OutProjProblem {
+    const T *o, *wo, *x;
+    const int32_t *expert_idx, *inv_cnt, *inv_ent;
+    T *out;
+    int l, d, n, kact, m, c, l_p, l_a, d_h;
+    uint32_t flags;
+
+    __device__ int rows(int) const { return l_p; }
+    __device__ int kdim(int g) const { return inv_cnt[g] * d_h; }
+    __device__ int ncols() const { return d; }
+    __device__ const T *a_ptr(int g, int r, int kk) const
+    {
+        const int bb = g / m;
+        const int e = kk / d_h;
+        const int ent = inv_ent[(size_t)g * kact + e];  // slot s * c + pick t
+        const int s = ent / c, t = ent - s * c;
+        return o + (((size_t)bb * kact + s) * l_a + t * l_p + r) * d_h + (kk - e * d_h);
+    }
+    __device__ const T *b_ptr(int g, int kk, int nn) const
+    {
+        const int bb = g / m;
+        const int e = kk / d_h;
+        const int s = inv_ent[(size_t)g * kact + e] / c;
+        const int i = clampi(expert_idx[bb * kact + s], n);
+        return wo + ((size_t)i * d_h + (kk - e * d_h)) * d + nn;
+    }
+    __device__ void store(int g, int r, int nn, float val) const
+    {
+        const int bb = g / m, p = g - bb * m;
+        const size_t at = ((size_t)bb * l + p * l_p + r) * d + nn;
+        if (flags & F_RESIDUAL) val += to_f32(x[at]);
+        out[at] = from_f32<T>(val);
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// UoME Eq. 38: group = sample b; M = l; K = d; N = k*d_e (the sample's active experts side by
+// side); epilogue SiLU and the expert's gate.
+template <typename T> struct UomeUpProblem {
+    const T *u, *a_in;
+    const int32_t *expert_idx;
+    const float *expert_gate;  // NULL: weight 1
+    T *hidden;                 // [b, l, k*d_e]
+    int l, d, n, kact, d_e;
+
+    __device__ int rows(int) const { return l; }
+    __device__ int kdim(int) const { return d; }
+    __device__ int ncols() const { return kact * d_e; }
+    __device__ const T *a_ptr(int g, int r, int kk) const { return u + ((size_t)g * l + r) * d + kk; }
+    __device__ const T *b_ptr(int g, int kk, int nn) const
+    {
+        const int s = nn / d_e;
+        const int i = clampi(expert_idx[g * kact + s], n);
+        return a_in + ((size_t)i * d + kk) * d_e + (nn - s * d_e);
+    }
+    __device__ float gate(int g, int nn) const
+    {
+        if (!expert_gate) return 1.0f;
+        return expert_gate[(size_t)g * n + clampi(expert_idx[g * kact + nn / d_e], n)];
+    }
+    __device__ void store(int g, int r, int nn, float val) const
+    {
+        hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate(g, nn));
+    }
+};
+
+// UoME Eq. 39 + Eq. 40: group = sample b; M = l; K = k*d_e (row slices of A^O of the active
+// experts stacked); N = d; epilogue adds the residual.  One write per output element.
+template <typename T> struct UomeDownProblem {
+    const T *hidden, *a_out, *u;
+    const int32_t *expert_idx;
+    T *out;
+    int l, d, n, kact, d_e;
+    uint32_t flags;
+
+    __device__ int rows(int) const { return l; }
+    __device__ int kdim(int) const { return kact * d_e; }
+    __device__ int ncols() const { return d; }
+    __device__ const T *a_ptr(int g, int r, int kk) const
+    {
+        return hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + kk;
+    }
+    __device__ const T *b_ptr(int g, int kk, int nn) const
+    {
+        const int s = kk / d_e;
+        const int i = clampi(expert_idx[g * kact + s], n);
+        return a_out + ((size_t)i * d_e + (kk - s * d_e)) * d + nn;
+    }
+    __device__ void store(int g, int r, int nn, float val) const
+    {
+        const size_t at = ((size_t)g * l + r) * d + nn;
+        if (flags & F_RESIDUAL) val += to_f32(u[at]);
+        out[at] = from_f32<T>(val);
+    }
+};
+
+}  // namespace uoe

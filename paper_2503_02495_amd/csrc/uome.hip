@@ -1,0 +1,39 @@
+// Union-of-MLP-Experts, expert-selection mode (Eq. 38-40 with Eq. 24-26), sample-major:
+// a sample's k active experts are column slices of A^I and row slices of A^O, so together they
+// are ONE two-layer MLP of hidden width k*d_e for that sample.  GEMM-1 writes the gated
+// SiLU hidden activations [l, k*d_e]; GEMM-2 contracts over the stacked K = k*d_e and writes every
+// output row once with the residual added: no per-expert partial outputs, no atomics.
+#include "common.h"
+#include "problems.h"
+#include "gemm_generic.h"
+
+namespace uoe {
+
+template <typename T> static hipError_t uome_generic(const UomeArgs &a, hipStream_t st)
+{
+    UomeUpProblem<T> up;
+    up.u = static_cast<const T *>(a.u);
+    up.a_in = static_cast<const T *>(a.a_in);
+    up.expert_idx = a.expert_idx;
+    up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
+    up.hidden = static_cast<T *>(a.hidden);
+    up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
+    hipError_t err = launch_gemm_generic<T>(up, a.b, a.l, a.k * a.d_e, st);
+    if (err != hipSuccess) return err;
+
+    UomeDownProblem<T> dn;
+    dn.hidden = static_cast<const T *>(a.hidden);
+    dn.a_out = static_cast<const T *>(a.a_out);
+    dn.u = static_cast<const T *>(a.u);
+    dn.expert_idx = a.expert_idx;
+    dn.out = static_cast<T *>(a.out);
+    dn.l = a.l; dn.d = a.d; dn.n = a.n; dn.kact = a.k; dn.d_e = a.d_e; dn.flags = a.flags;
+    return launch_gemm_generic<T>(dn, a.b, a.l, a.d, st);
+}
+
+hipError_t launch_uome(const UomeArgs &a, bool bf16, hipStream_t st)
+{
+    return bf16 ? uome_generic<bf16_t>(a, st) : uome_generic<float>(a, st);
+}
+
+}  // namespace uoe

@@ -1,0 +1,97 @@
+"""Device-side plumbing for tests and the benchmark: upload a synthetic input set, allocate
+outputs and workspace with torch, and call the C ABI through ``binding``.  No arithmetic."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import synth
+
+
+def to_device(a: Optional[np.ndarray], dtype: str, device) -> Optional[torch.Tensor]:
+    """float32 host array -> device tensor of the storage dtype (bf16 values must be bf16-exact)."""
+    if a is None:
+        return None
+    if dtype == synth.BF16:
+        bits = synth.bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """device tensor -> float64 / int32 host array."""
+    if t.dtype in (torch.int32, torch.int64):
+        return t.cpu().numpy().astype(np.int32)
+    return t.to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+class DeviceLayer:
+    """One UoE layer's tensors resident on the GPU, plus descriptors, outputs and workspace."""
+
+    def __init__(self, inp: synth.LayerInputs, flags_a: int, flags_m: int, device="cuda:0"):
+        cfg = inp.cfg
+        self.cfg, self.device = cfg, torch.device(device)
+        dt = cfg.dtype
+        self.tdtype = torch.bfloat16 if dt == synth.BF16 else torch.float32
+        code = B.BF16 if dt == synth.BF16 else B.F32
+        up = lambda a: to_device(a, dt, self.device)
+        f32 = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(self.device)
+        self.x = up(inp.x)
+        self.a_w_expert, self.a_w_b, self.a_w_a = up(inp.a_w_expert), up(inp.a_w_b), up(inp.a_w_a)
+        self.wq, self.wk, self.wv, self.wo = up(inp.wq), up(inp.wk), up(inp.wv), up(inp.wo)
+        self.m_w_expert, self.a_in, self.a_out = up(inp.m_w_expert), up(inp.a_in), up(inp.a_out)
+        self.noise_a_expert, self.noise_a_patch = f32(inp.noise_a_expert), f32(inp.noise_a_patch)
+        self.noise_m_expert = f32(inp.noise_m_expert)
+
+        self.smha = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_a, cfg.k_a, cfg.m, cfg.c, cfg.d_h, code, flags_a)
+        self.uome = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_m, cfg.k_m, 1, 1, cfg.d_e, code, flags_m)
+        nbytes = B.workspace_bytes(self.smha, self.uome)
+        if nbytes == 0:
+            raise B.UoeError(B.ERR_INVALID_ARG, "uoe_workspace_bytes")
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+
+        i32 = dict(dtype=torch.int32, device=self.device)
+        f = dict(dtype=torch.float32, device=self.device)
+        self.a_expert_idx = torch.full((cfg.b, cfg.k_a), -1, **i32)
+        self.a_expert_gate = torch.zeros((cfg.b, cfg.n_a), **f)
+        self.a_patch_idx = torch.full((cfg.b, cfg.n_a, cfg.c), -1, **i32)
+        self.a_patch_gate = torch.zeros((cfg.b, cfg.n_a, cfg.m), **f)
+        self.m_expert_idx = torch.full((cfg.b, cfg.k_m), -1, **i32)
+        self.m_expert_gate = torch.zeros((cfg.b, cfg.n_m), **f)
+        self.u = torch.zeros((cfg.b, cfg.l, cfg.d), dtype=self.tdtype, device=self.device)
+        self.out = torch.zeros((cfg.b, cfg.l, cfg.d), dtype=self.tdtype, device=self.device)
+        self.wa = B.smha_weights(self.a_w_expert, self.a_w_b, self.a_w_a, self.wq, self.wk, self.wv, self.wo)
+        self.wm = B.uome_weights(self.m_w_expert, self.a_in, self.a_out)
+        self.ra = B.routing_out(self.a_expert_idx, self.a_expert_gate, self.a_patch_idx, self.a_patch_gate)
+        self.rm = B.routing_out(self.m_expert_idx, self.m_expert_gate, None, None)
+
+    # each method is one C-ABI call on the current stream
+    def route_a(self):
+        B.route(self.smha, self.x, self.a_w_expert, self.a_w_b, self.a_w_a, self.noise_a_expert,
+                self.noise_a_patch, self.a_expert_idx, self.a_expert_gate, self.a_patch_idx,
+                self.a_patch_gate, self.ws)
+
+    def smha_forward(self, expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None, x=None, out=None):
+        B.smha_forward(self.smha, self.x if x is None else x, self.wq, self.wk, self.wv, self.wo,
+                       self.a_expert_idx if expert_idx is None else expert_idx,
+                       self.a_expert_gate if expert_gate is None else expert_gate,
+                       self.a_patch_idx if patch_idx is None else patch_idx,
+                       self.a_patch_gate if patch_gate is None else patch_gate,
+                       self.u if out is None else out, self.ws)
+
+    def route_m(self, u=None):
+        B.route(self.uome, self.u if u is None else u, self.m_w_expert, None, None, self.noise_m_expert, None,
+                self.m_expert_idx, self.m_expert_gate, None, None, self.ws)
+
+    def uome_forward(self, expert_idx=None, expert_gate=None, u=None, out=None):
+        B.uome_forward(self.uome, self.u if u is None else u, self.a_in, self.a_out,
+                       self.m_expert_idx if expert_idx is None else expert_idx,
+                       self.m_expert_gate if expert_gate is None else expert_gate, None, None,
+                       self.out if out is None else out, self.ws)
+
+    def layer_forward(self):
+        B.layer_forward(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
+                        self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws)

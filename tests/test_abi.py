@@ -1,0 +1,128 @@
+"""The C-ABI boundary without a GPU: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before touching any device state (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_02495_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a 16-byte-aligned non-NULL address that is never dereferenced by validation
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "uoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(uoe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    syms = header_symbols()
+    assert set(syms) == set(B.EXPORTS)
+    L = B.lib()
+    for s in syms:
+        assert getattr(L, s) is not None
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(B.BlockDesc) == 16 * 4
+    assert ctypes.sizeof(B.SmhaWeights) == 7 * 8 and ctypes.sizeof(B.UomeWeights) == 3 * 8
+    assert ctypes.sizeof(B.RoutingOut) == 4 * 8
+
+
+def good(**kw):
+    base = dict(b=2, l=64, d=64, n=4, k=2, m=8, c=2, width=16, dtype=B.F32,
+                flags=B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | B.FLAG_GATE_PATCH)
+    base.update(kw)
+    return B.block_desc(**base)
+
+
+def test_status_strings():
+    assert B.status_string(B.OK) == "ok"
+    for s in (1, 2, 3, 4, 99):
+        assert isinstance(B.status_string(s), str) and B.status_string(s)
+
+
+def test_workspace_bytes():
+    a = B.workspace_bytes(good(), None)
+    m = B.workspace_bytes(None, good(m=1, c=1, width=64))
+    both = B.workspace_bytes(good(), good(m=1, c=1, width=64))
+    assert a > 0 and m > 0 and both >= a + m
+    assert B.workspace_bytes(good(l=63), None) == 0       # invalid descriptor -> 0
+    assert B.workspace_bytes(None, None) == 0
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(l=63), B.ERR_INVALID_ARG),             # l % m != 0
+    (dict(k=5), B.ERR_INVALID_ARG),              # k > n
+    (dict(c=9), B.ERR_INVALID_ARG),              # c > m
+    (dict(c=0), B.ERR_INVALID_ARG),
+    (dict(b=0), B.ERR_INVALID_ARG),
+    (dict(dtype=7), B.ERR_INVALID_ARG),
+    (dict(flags=1 << 9), B.ERR_INVALID_ARG),
+    (dict(flags=B.FLAG_CAUSAL), B.ERR_UNSUPPORTED),
+    (dict(rope_dim=8), B.ERR_UNSUPPORTED),
+    (dict(d=60), B.ERR_UNSUPPORTED),             # d % 8 != 0
+    (dict(width=12), B.ERR_UNSUPPORTED),
+    (dict(n=33, k=2), B.ERR_UNSUPPORTED),
+])
+def test_descriptor_validation(kw, want):
+    d = good(**kw)
+    args = [FAKE] * 10
+    assert B.route(d, *args, FAKE, stream=0, check=False, ws_bytes=1 << 30) == want
+    assert B.smha_forward(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE,
+                          stream=0, check=False, ws_bytes=1 << 30) == want
+
+
+def test_reserved_fields_must_be_zero():
+    d = good()
+    d.reserved[2] = 1
+    assert B.route(d, *([FAKE] * 10), FAKE, stream=0, check=False, ws_bytes=1 << 30) == B.ERR_INVALID_ARG
+
+
+def test_route_argument_validation():
+    d = good()
+    big = 1 << 30
+    call = lambda *a, **k: B.route(d, *a, stream=0, check=False, **k)
+    outs = [FAKE] * 4
+    assert call(None, FAKE, FAKE, FAKE, None, None, *outs, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # x NULL
+    assert call(FAKE + 2, FAKE, FAKE, FAKE, None, None, *outs, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # misaligned
+    assert call(FAKE, FAKE, FAKE, None, None, None, *outs, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # w_a without w_b
+    assert call(FAKE, None, FAKE, FAKE, None, None, *outs, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # no w_expert, k<n
+    assert call(FAKE, FAKE, None, None, None, None, *outs, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # no data router, c<m
+    assert call(FAKE, FAKE, FAKE, FAKE, None, None, *outs, None, ws_bytes=big) == B.ERR_WORKSPACE
+    assert call(FAKE, FAKE, FAKE, FAKE, None, None, *outs, FAKE, ws_bytes=16) == B.ERR_WORKSPACE
+    with pytest.raises(B.UoeError) as e:
+        B.route(d, None, FAKE, FAKE, FAKE, None, None, *outs, FAKE, stream=0, ws_bytes=big)
+    assert e.value.status == B.ERR_INVALID_ARG
+
+
+def test_smha_uome_layer_argument_validation():
+    d = good()
+    big = 1 << 30
+    sm = lambda *a, **k: B.smha_forward(d, *a, stream=0, check=False, **k)
+    assert sm(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # out aliases x
+    assert sm(FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # wo NULL
+    assert sm(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # gate flag, no gate
+    assert sm(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
+
+    u = good(m=1, c=1, width=64, flags=B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT)
+    um = lambda desc, *a, **k: B.uome_forward(desc, *a, stream=0, check=False, **k)
+    assert um(u, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # out aliases u
+    assert um(u, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # gate missing
+    assert um(u, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
+    ds = good(m=8, c=2, width=64, flags=B.FLAG_RESIDUAL)                    # data-selection UoME
+    assert um(ds, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_UNSUPPORTED
+    assert um(u, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_UNSUPPORTED
+
+    wa = B.smha_weights(*([FAKE] * 7))
+    wm = B.uome_weights(FAKE, FAKE, FAKE)
+    ly = lambda a, m_, x, out, **k: B.layer_forward(a, wa, None, None, m_, wm, None, x, out, None, None, FAKE,
+                                                    stream=0, check=False, **k)
+    assert ly(d, u, FAKE, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG                      # out aliases x
+    assert ly(d, good(b=3, m=1, c=1, width=64), FAKE, FAKE + 16, ws_bytes=big) == B.ERR_INVALID_ARG  # b mismatch
+    assert ly(d, u, FAKE, FAKE + 16, ws_bytes=64) == B.ERR_WORKSPACE
+    assert B.gather(d, FAKE, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG   # h aliases x
+    assert B.gather(d, None, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG

@@ -1,0 +1,301 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the same
+seeded inputs.  Selection indices must be bit-exact (rows the oracle flags as near-ties, kept vs
+dropped gate within 1e-5 relative, are counted and reported, not failed); outputs must be within
+max |y-r| / max(|r|, rms(r)) <= 1e-4 for fp32 storage and 2e-2 for bf16 storage with fp32
+accumulation.  Stage tests feed each GPU stage the exact tensors the oracle stage sees, and are
+run without the residual and without gates so every expert's contribution is checked at full
+size; the layer test runs the benchmark's own call (uoe_layer_forward, all flags on).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_02495_amd import binding as B
+from paper_2503_02495_amd import synth
+from paper_2503_02495_amd.harness import DeviceLayer, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+R, GE, GP = B.FLAG_RESIDUAL, B.FLAG_GATE_EXPERT, B.FLAG_GATE_PATCH
+assert (R, GE, GP) == (oracle.RESIDUAL, oracle.GATE_EXPERT, oracle.GATE_PATCH)
+TOL = {synth.F32: 1e-4, synth.BF16: 2e-2}
+GATE_RTOL = 1e-3      # fp32 router arithmetic against fp64, relative, on the gate values
+
+
+def scaled_err(y, r):
+    r = np.asarray(r, np.float64)
+    rms = float(np.sqrt(np.mean(r * r)))
+    den = np.maximum(np.abs(r), rms if rms > 0 else 1.0)
+    return float(np.max(np.abs(np.asarray(y, np.float64) - r) / den))
+
+
+def check_indices(name, got, want, margin):
+    """Bit-exact except on rows the oracle flags as near-ties; returns (#mismatch, #flagged)."""
+    got, want = np.asarray(got), np.asarray(want)
+    rows_differ = np.any(got != want, axis=-1)
+    flagged = (margin >= 0) & (margin <= oracle.NEAR_TIE_REL)
+    bad = rows_differ & ~flagged
+    print(f"[{name}] rows={rows_differ.size} near-ties flagged={int(flagged.sum())} "
+          f"mismatching rows={int(rows_differ.sum())} (all must be flagged)")
+    assert not bad.any(), f"{name}: selection differs on unflagged rows {np.argwhere(bad)[:5].tolist()}"
+    return int(rows_differ.sum()), int(flagged.sum())
+
+
+def check_valid_selection(idx, upper):
+    idx = np.asarray(idx)
+    assert idx.min() >= 0 and idx.max() < upper
+    assert np.all(np.diff(idx, axis=-1) > 0) or idx.shape[-1] == 1     # ascending and distinct
+
+
+def small(**kw):
+    return synth.small_config(**kw)
+
+
+EDGE_CONFIGS = {
+    "ragged_lp14": small(b=3, l=56, d=24, n_a=3, d_h=8, m=4, c=3, k_a=2, n_m=3, d_e=16, k_m=2),
+    "lp1_c1": small(b=2, l=6, d=8, n_a=2, d_h=8, m=6, c=1, k_a=1, n_m=2, d_e=8, k_m=1),
+    "all_selected": small(b=2, l=32, d=16, n_a=4, d_h=8, m=4, c=4, k_a=4, n_m=4, d_e=8, k_m=4),
+    "b1_n1": small(b=1, l=16, d=8, n_a=1, d_h=8, m=2, c=1, k_a=1, n_m=1, d_e=8, k_m=1),
+    "n32_dh24": small(b=2, l=40, d=40, n_a=32, d_h=24, m=5, c=2, k_a=7, n_m=32, d_e=24, k_m=5),
+    "dh128_multi_tile": small(b=2, l=300, d=72, n_a=3, d_h=128, m=2, c=2, k_a=2, n_m=2, d_e=136, k_m=1),
+    "bf16_ragged": small(b=3, l=140, d=64, n_a=4, d_h=32, m=10, c=3, k_a=3, n_m=4, d_e=64, k_m=2,
+                         dtype=synth.BF16),
+    "bf16_noise": small(b=2, l=96, d=128, n_a=8, d_h=64, m=12, c=5, k_a=3, n_m=8, d_e=128, k_m=3,
+                        dtype=synth.BF16, router_noise=True),
+}
+
+
+def get_cfg(name):
+    return synth.CONFIGS[name] if name in synth.CONFIGS else EDGE_CONFIGS[name]
+
+
+def w_std_for(name):
+    # the edge shapes use larger weights so that expert outputs are not dwarfed by rounding
+    return 0.02 if name in synth.CONFIGS else 0.2
+
+
+ALL_NAMES = list(EDGE_CONFIGS) + synth.CONFIG_ORDER
+
+
+# --------------------------------------------------------------------------- routing
+@pytest.mark.parametrize("name", ALL_NAMES)
+def test_route_parity(name):
+    cfg = get_cfg(name)
+    print(f"route parity {name} seed={cfg.seed} b={cfg.b} l={cfg.l} d={cfg.d}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    dev = DeviceLayer(inp, R | GE | GP, R | GE)
+    dev.route_a()
+    torch.cuda.synchronize()
+    ref = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                       inp.noise_a_expert, inp.noise_a_patch)
+    e_idx, p_idx = to_host(dev.a_expert_idx), to_host(dev.a_patch_idx)
+    check_valid_selection(e_idx, cfg.n_a)
+    check_valid_selection(p_idx, cfg.m)
+    check_indices(name + ":expert", e_idx, ref.expert_id, ref.expert_margin)
+    check_indices(name + ":patch", p_idx, ref.patch_id, ref.patch_margin)
+    np.testing.assert_allclose(to_host(dev.a_expert_gate), ref.expert_gate, rtol=GATE_RTOL, atol=1e-30)
+    np.testing.assert_allclose(to_host(dev.a_patch_gate), ref.patch_gate, rtol=GATE_RTOL, atol=1e-30)
+    # the UoME-style call: expert selection only, one patch
+    dev.route_m(u=dev.x)
+    torch.cuda.synchronize()
+    refm = oracle.route(inp.x, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
+    check_indices(name + ":uome-expert", to_host(dev.m_expert_idx), refm.expert_id, refm.expert_margin)
+    np.testing.assert_allclose(to_host(dev.m_expert_gate), refm.expert_gate, rtol=GATE_RTOL, atol=1e-30)
+
+
+def test_route_degenerate_modes_and_ties():
+    """No routers: everything selected, gates 1.  Exact ties (x = 0): lowest indices win."""
+    cfg = small(b=2, l=32, d=16, n_a=4, d_h=8, m=4, c=4, k_a=4, n_m=4, d_e=8, k_m=4)
+    inp = synth.make_inputs(cfg)
+    dev = DeviceLayer(inp, R, R)
+    B.route(dev.smha, dev.x, None, None, None, None, None, dev.a_expert_idx, dev.a_expert_gate,
+            dev.a_patch_idx, dev.a_patch_gate, dev.ws)
+    torch.cuda.synchronize()
+    assert to_host(dev.a_expert_idx).tolist() == [[0, 1, 2, 3]] * 2
+    assert to_host(dev.a_patch_idx).tolist() == [[[0, 1, 2, 3]] * 4] * 2
+    assert np.all(to_host(dev.a_expert_gate) == 1.0) and np.all(to_host(dev.a_patch_gate) == 1.0)
+
+    cfg = small(b=2, l=32, d=16, n_a=5, d_h=8, m=8, c=3, k_a=2, n_m=4, d_e=8, k_m=2)
+    inp = synth.make_inputs(cfg)
+    inp.x[:] = 0.0                                   # all logits equal -> all gates equal -> pure tie-break
+    dev = DeviceLayer(inp, R, R)
+    dev.route_a()
+    torch.cuda.synchronize()
+    assert to_host(dev.a_expert_idx).tolist() == [[0, 1]] * 2
+    assert to_host(dev.a_patch_idx).tolist() == [[[0, 1, 2]] * 5] * 2
+    np.testing.assert_allclose(to_host(dev.a_patch_gate), 0.2, rtol=1e-6)
+    ref = oracle.route(inp.x, 5, 2, 8, 3, inp.a_w_expert, inp.a_w_b, inp.a_w_a)
+    assert ref.expert_id.tolist() == [[0, 1]] * 2 and ref.patch_id.tolist() == [[[0, 1, 2]] * 5] * 2
+
+
+# --------------------------------------------------------------------------- gather
+@pytest.mark.parametrize("name", ["ragged_lp14", "bf16_ragged", "tiny", "lm", "vit"])
+def test_gather_bit_exact(name):
+    cfg = get_cfg(name)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    dev = DeviceLayer(inp, R, R)
+    ref = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                       inp.noise_a_expert, inp.noise_a_patch)
+    e_idx = torch.from_numpy(ref.expert_id).to(dev.device)
+    p_idx = torch.from_numpy(ref.patch_id).to(dev.device)
+    h = torch.zeros((cfg.b, cfg.k_a, cfg.l_a, cfg.d), dtype=dev.tdtype, device=dev.device)
+    B.gather(dev.smha, dev.x, e_idx, p_idx, h)
+    torch.cuda.synchronize()
+    got = to_host(h)
+    xp = inp.x.astype(np.float64).reshape(cfg.b, cfg.m, cfg.l_p, cfg.d)
+    for bb in range(cfg.b):
+        for s in range(cfg.k_a):
+            want = xp[bb, ref.patch_id[bb, ref.expert_id[bb, s]]].reshape(cfg.l_a, cfg.d)   # Eq. 18
+            assert np.array_equal(got[bb, s], want)
+
+
+# --------------------------------------------------------------------------- SMHA stage
+def run_smha_stage(name, flags, samples=None):
+    cfg = get_cfg(name)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    dev = DeviceLayer(inp, flags, R)
+    ref = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                       inp.noise_a_expert, inp.noise_a_patch)
+    # the oracle's routing results are the inputs of both sides
+    dev.smha_forward(expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
+                     expert_gate=to_device(ref.expert_gate.astype(np.float32), synth.F32, dev.device),
+                     patch_idx=torch.from_numpy(ref.patch_id).to(dev.device),
+                     patch_gate=to_device(ref.patch_gate.astype(np.float32), synth.F32, dev.device))
+    torch.cuda.synchronize()
+    got = to_host(dev.u)
+    sel = slice(None) if samples is None else samples
+    want = oracle.smha(inp.x[sel], inp.wq, inp.wk, inp.wv, inp.wo, ref.expert_id[sel],
+                       ref.expert_gate.astype(np.float32)[sel], ref.patch_id[sel],
+                       ref.patch_gate.astype(np.float32)[sel], cfg.m, flags)
+    err = scaled_err(got[sel], want)
+    print(f"[smha {name} flags={flags}] scaled err {err:.3e} (tol {TOL[cfg.dtype]:.0e})", flush=True)
+    assert err <= TOL[cfg.dtype]
+    if flags & R:   # rows of patches nobody selected are x exactly
+        x64 = inp.x.astype(np.float64)
+        for bb in (range(cfg.b) if samples is None else range(samples.start, samples.stop)):
+            used = set(int(p) for i in ref.expert_id[bb] for p in ref.patch_id[bb, i])
+            for p in set(range(cfg.m)) - used:
+                rows = slice(p * cfg.l_p, (p + 1) * cfg.l_p)
+                assert np.array_equal(got[bb, rows], x64[bb, rows])
+    return err
+
+
+@pytest.mark.parametrize("name", list(EDGE_CONFIGS) + ["tiny", "lm", "longrange", "vit"])
+@pytest.mark.parametrize("flags", [0, R | GE | GP])
+def test_smha_stage_parity(name, flags):
+    run_smha_stage(name, flags)
+
+
+@pytest.mark.parametrize("flags", [0, R | GE | GP])
+def test_smha_stage_parity_large_sampled(flags):
+    run_smha_stage("large", flags, samples=slice(1, 2))      # full-size launch, oracle on one sample
+
+
+# --------------------------------------------------------------------------- UoME stage
+def run_uome_stage(name, flags, rows=None):
+    cfg = get_cfg(name)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    dev = DeviceLayer(inp, R, flags)
+    ref = oracle.route(inp.x, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
+    dev.uome_forward(expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
+                     expert_gate=to_device(ref.expert_gate.astype(np.float32), synth.F32, dev.device),
+                     u=dev.x)
+    torch.cuda.synchronize()
+    got = to_host(dev.out)
+    if rows is None:
+        pick = np.arange(cfg.l)
+    else:   # every token row is independent in the MLP, so the oracle can take a sample of rows
+        pick = np.sort(np.random.default_rng(5).choice(cfg.l, rows, replace=False))
+        pick[0], pick[-1] = 0, cfg.l - 1
+    want = oracle.uome(inp.x[:, pick], inp.a_in, inp.a_out, ref.expert_id,
+                       ref.expert_gate.astype(np.float32), flags)
+    err = scaled_err(got[:, pick], want)
+    print(f"[uome {name} flags={flags}] rows={len(pick)} scaled err {err:.3e} (tol {TOL[cfg.dtype]:.0e})", flush=True)
+    assert err <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("name", list(EDGE_CONFIGS) + ["tiny", "lm", "vit"])
+@pytest.mark.parametrize("flags", [0, R | GE])
+def test_uome_stage_parity(name, flags):
+    run_uome_stage(name, flags)
+
+
+@pytest.mark.parametrize("name", ["longrange", "large"])
+@pytest.mark.parametrize("flags", [0, R | GE])
+def test_uome_stage_parity_sampled_rows(name, flags):
+    run_uome_stage(name, flags, rows=192)
+
+
+# --------------------------------------------------------------------------- whole layer
+@pytest.mark.parametrize("name", ALL_NAMES)
+def test_layer_parity(name):
+    """uoe_layer_forward exactly as the benchmark launches it (all gate flags, residual on)."""
+    cfg = get_cfg(name)
+    print(f"layer parity {name} seed={cfg.seed}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    fa, fm = R | GE | GP, R | GE
+    dev = DeviceLayer(inp, fa, fm)
+    dev.layer_forward()
+    torch.cuda.synchronize()
+    ref = oracle.layer_forward(inp, fa, fm) if name != "large" else None
+    if ref is None:
+        # large: the oracle runs the SMHA block in full (the UoME router needs all of u) and the
+        # MLP on sampled rows
+        ra = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                          inp.noise_a_expert, inp.noise_a_patch)
+        u = oracle.smha(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ra.expert_gate, ra.patch_id,
+                        ra.patch_gate, cfg.m, fa)
+        rm = oracle.route(u, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
+    else:
+        ra, u, rm = ref.routing_a, ref.u, ref.routing_m
+    check_indices(name + ":smha-expert", to_host(dev.a_expert_idx), ra.expert_id, ra.expert_margin)
+    check_indices(name + ":smha-patch", to_host(dev.a_patch_idx), ra.patch_id, ra.patch_margin)
+
+    # UoME routing, stage-exact: the oracle router on the very u the GPU router read.  The layer
+    # call keeps u in its workspace; the path is deterministic, so the SMHA call on the layer's own
+    # routing results reproduces it bit for bit.
+    m_idx, m_gate = to_host(dev.m_expert_idx), to_host(dev.m_expert_gate)
+    out_layer = dev.out.clone()
+    dev.smha_forward()
+    torch.cuda.synchronize()
+    u_gpu = to_host(dev.u)
+    err_u = scaled_err(u_gpu, u)
+    print(f"[layer {name}] u scaled err {err_u:.3e}", flush=True)
+    assert err_u <= TOL[cfg.dtype]
+    rm_on_gpu_u = oracle.route(u_gpu, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None,
+                               inp.noise_m_expert, None)
+    check_indices(name + ":uome-expert(on GPU u)", m_idx, rm_on_gpu_u.expert_id, rm_on_gpu_u.expert_margin)
+    np.testing.assert_allclose(m_gate, rm_on_gpu_u.expert_gate, rtol=GATE_RTOL, atol=1e-30)
+
+    # end to end: only meaningful where rounding of u did not flip the UoME top-k
+    same = np.all(m_idx == rm.expert_id, axis=-1)
+    print(f"[layer {name}] UoME top-k equal to the all-fp64 chain on {int(same.sum())}/{cfg.b} samples", flush=True)
+    got = to_host(out_layer)
+    if ref is not None:
+        want = ref.out
+        pick = np.arange(cfg.l)
+    else:
+        pick = np.sort(np.random.default_rng(6).choice(cfg.l, 128, replace=False))
+        want = oracle.uome(u[:, pick], inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, fm)
+    if same.any():
+        err = scaled_err(got[same][:, pick], want[same])
+        print(f"[layer {name}] out scaled err {err:.3e} (tol {TOL[cfg.dtype]:.0e})", flush=True)
+        assert err <= TOL[cfg.dtype]
+    if cfg.dtype == synth.F32:
+        assert same.all()
+
+
+def test_layer_is_deterministic_and_reusable():
+    """Two calls on the same buffers give bit-identical results (no atomics, no stale scratch)."""
+    cfg = get_cfg("bf16_ragged")
+    inp = synth.make_inputs(cfg, w_std=0.2)
+    dev = DeviceLayer(inp, R | GE | GP, R | GE)
+    dev.layer_forward()
+    torch.cuda.synchronize()
+    first = dev.out.clone()
+    dev.ws.fill_(0xFF)
+    dev.out.zero_()
+    dev.layer_forward()
+    torch.cuda.synchronize()
+    assert torch.equal(first.view(torch.int16), dev.out.view(torch.int16))
