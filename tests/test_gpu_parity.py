@@ -71,8 +71,14 @@ def get_cfg(name):
 
 
 def w_std_for(name):
-    # the edge shapes use larger weights so that expert outputs are not dwarfed by rounding
-    return 0.02 if name in synth.CONFIGS else 0.2
+    # The edge shapes use larger weights than the workloads' 0.02 so that expert outputs are not
+    # dwarfed by rounding.  For bf16 storage q, k, v and the attention probabilities are themselves
+    # rounded to bf16, so the weights are kept where attention logits stay O(1) as in the workload
+    # shapes (at std 0.2 the logits reach std 2.5 and bf16 rounding of q and k alone moves the
+    # probabilities by percents, which is the format's resolution, not the kernel's).
+    if name in synth.CONFIGS:
+        return 0.02
+    return 0.2 if EDGE_CONFIGS[name].dtype == synth.F32 else 0.06
 
 
 ALL_NAMES = list(EDGE_CONFIGS) + synth.CONFIG_ORDER
@@ -289,7 +295,7 @@ def test_layer_parity(name):
 def test_layer_is_deterministic_and_reusable():
     """Two calls on the same buffers give bit-identical results (no atomics, no stale scratch)."""
     cfg = get_cfg("bf16_ragged")
-    inp = synth.make_inputs(cfg, w_std=0.2)
+    inp = synth.make_inputs(cfg, w_std=0.06)
     dev = DeviceLayer(inp, R | GE | GP, R | GE)
     dev.layer_forward()
     torch.cuda.synchronize()
