@@ -172,14 +172,23 @@ __global__ __launch_bounds__(256) void route_select_kernel(RouteArgs a, int has_
             for (int i = 0; i < n; ++i) mx = fmaxf(mx, g[i * m + j]);
             float den = 0.f;
             for (int i = 0; i < n; ++i) den += expf(g[i * m + j] - mx);
-            for (int i = 0; i < n; ++i) g[i * m + j] = expf(g[i * m + j] - mx) / den;
+            const float lden = logf(den);
+            for (int i = 0; i < n; ++i) {
+                const float sh = g[i * m + j] - mx;
+                if (a.patch_gate) a.patch_gate[(size_t)bb * nm + i * m + j] = expf(sh) / den;
+                // ranking key: the log of the gate.  Same order as the gate itself, but a gate too
+                // small for fp32 keeps its rank instead of collapsing into a tie at zero.
+                g[i * m + j] = sh - lden;
+            }
         }
     } else {
-        for (int o = tid; o < nm; o += 256) g[o] = 1.0f;
+        for (int o = tid; o < nm; o += 256) {
+            g[o] = 0.0f;
+            if (a.patch_gate) a.patch_gate[(size_t)bb * nm + o] = 1.0f;
+        }
     }
     __syncthreads();
     for (int o = tid; o < nm; o += 256) {
-        if (a.patch_gate) a.patch_gate[(size_t)bb * nm + o] = g[o];
         const int i = o / m, j = o - i * m;
         const float v = g[o];
         int rank = 0;
@@ -201,8 +210,10 @@ __global__ __launch_bounds__(256) void route_select_kernel(RouteArgs a, int has_
     }
 
     // ---- expert selection: Eq. 21 logits (+noise) -> softmax -> Eq. 22 top-k
+    // The softmax is strictly increasing in the logit within a sample, so the k largest gates are
+    // the k largest logits: rank on the logits, which cannot underflow.
+    float z = 0.f;
     if (tid < n) {
-        float z = 0.f;
         if (has_e) {
             z = a.zred[(size_t)bb * n + tid];
             if (a.noise_e) z += a.noise_e[(size_t)bb * n + tid];
@@ -210,24 +221,18 @@ __global__ __launch_bounds__(256) void route_select_kernel(RouteArgs a, int has_
         ge[tid] = z;
     }
     __syncthreads();
-    float gv = 1.0f;
-    if (tid < n && has_e) {
-        float mx = -INFINITY;
-        for (int i = 0; i < n; ++i) mx = fmaxf(mx, ge[i]);
-        float den = 0.f;
-        for (int i = 0; i < n; ++i) den += expf(ge[i] - mx);
-        gv = expf(ge[tid] - mx) / den;
-    }
-    __syncthreads();
     if (tid < n) {
-        ge[tid] = gv;
+        float gv = 1.0f;
+        if (has_e) {
+            float mx = -INFINITY;
+            for (int i = 0; i < n; ++i) mx = fmaxf(mx, ge[i]);
+            float den = 0.f;
+            for (int i = 0; i < n; ++i) den += expf(ge[i] - mx);
+            gv = expf(z - mx) / den;
+        }
         if (a.expert_gate) a.expert_gate[(size_t)bb * n + tid] = gv;
-    }
-    __syncthreads();
-    if (tid < n) {
-        const float v = ge[tid];
         int rank = 0;
-        for (int i = 0; i < n; ++i) rank += (ge[i] > v || (ge[i] == v && i < tid)) ? 1 : 0;
+        for (int i = 0; i < n; ++i) rank += (ge[i] > z || (ge[i] == z && i < tid)) ? 1 : 0;
         ekept[tid] = rank < k;
     }
     __syncthreads();

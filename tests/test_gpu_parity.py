@@ -24,10 +24,23 @@ GATE_RTOL = 1e-3      # fp32 router arithmetic against fp64, relative, on the ga
 
 
 def scaled_err(y, r):
+    """max |y - r| / max(|r|, rms(r)): relative error with the typical magnitude as the floor.
+
+    rms(r) is taken over the rows the block actually writes (reference rows that are not all zero):
+    without the residual, rows of patches nobody selected are exactly zero on both sides, and
+    counting them would shrink the floor by the selection ratio instead of measuring the arithmetic.
+    Those zero rows must match exactly.
+    """
     r = np.asarray(r, np.float64)
-    rms = float(np.sqrt(np.mean(r * r)))
-    den = np.maximum(np.abs(r), rms if rms > 0 else 1.0)
-    return float(np.max(np.abs(np.asarray(y, np.float64) - r) / den))
+    y = np.asarray(y, np.float64)
+    written = np.any(r != 0.0, axis=-1)
+    assert np.array_equal(y[~written], r[~written])
+    if not written.any():
+        return 0.0
+    rw = r[written]
+    rms = float(np.sqrt(np.mean(rw * rw)))
+    den = np.maximum(np.abs(rw), rms)
+    return float(np.max(np.abs(y[written] - rw) / den))
 
 
 def check_indices(name, got, want, margin):
