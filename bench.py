@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Throughput of one Union-of-Experts layer forward (uoe_layer_forward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lm|longrange|vit|large|tiny]
+
+A step is one pass of the whole hot path (route -> SMHA -> route -> UoME) over one batch of seeded
+synthetic input that is already resident in HBM.  Prints ONE JSON line with the whole-job
+tokens/s, a roofline entry for the dominant kernel (timed live with events on the launch stream)
+and the CPU oracle timed on this machine's host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector/matrix
+PEAK_HBM_GBS = 8000.0
+
+
+def layer_flops(c) -> dict:
+    """Algorithmic FLOPs of one layer call: active units only, no padding."""
+    routers = 2 * c.b * c.l * c.d * (2 * c.n_a + c.n_m) + 2 * c.b * c.n_a * c.l * c.m
+    qkv = c.b * c.k_a * 6 * c.l_a * c.d * c.d_h
+    attn = c.b * c.k_a * 4 * c.l_a * c.l_a * c.d_h
+    outp = c.b * c.k_a * 2 * c.l_a * c.d_h * c.d
+    uome = c.b * c.k_m * 4 * c.l * c.d * c.d_e
+    return dict(routers=routers, qkv=qkv, attention=attn, out_proj=outp, uome=uome,
+                total=routers + qkv + attn + outp + uome)
+
+
+def describe(c) -> str:
+    return (f"{c.name}: b{c.b} l{c.l} d{c.d}; SMHA n{c.n_a} d_h{c.d_h} m{c.m} c{c.c} k{c.k_a}; "
+            f"UoME n{c.n_m} d_e{c.d_e} k{c.k_m}; {c.dtype}")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="lm")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2503_02495_amd import binding as B
+    from paper_2503_02495_amd import synth
+    from paper_2503_02495_amd.harness import DeviceLayer
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    B.lib()  # fail loudly if the HIP library is not built
+    cfg = synth.CONFIGS[args.workload]
+    inp = synth.make_inputs(cfg)
+    fa = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | B.FLAG_GATE_PATCH
+    fm = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT
+    dev = DeviceLayer(inp, fa, fm, device="cuda:0")
+    torch.cuda.set_device(0)
+
+    # ---- whole-path throughput
+    for _ in range(args.warmup):
+        dev.layer_forward()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dev.layer_forward()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = cfg.tokens / (ms_per_step * 1e-3)
+    fl = layer_flops(cfg)
+
+    # ---- dominant kernel: the UoME up-projection grouped GEMM (half of the UoME FLOPs, which are
+    # 84-90% of the layer).  Timed alone with events on the stream it is launched on.
+    hidden = torch.empty((cfg.b, cfg.l, cfg.k_m * cfg.d_e), dtype=dev.tdtype, device=dev.device)
+    up = lambda: B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden)
+    dev.smha_forward()          # u, then the UoME routing the GEMM reads
+    dev.route_m()
+    for _ in range(max(3, args.warmup)):
+        up()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(args.steps):
+        up()
+    ev1.record()
+    torch.cuda.synchronize()
+    up_ms = ev0.elapsed_time(ev1) / args.steps
+    up_flops = 2.0 * cfg.b * cfg.l * cfg.d * cfg.k_m * cfg.d_e
+    is_bf16 = cfg.dtype == synth.BF16
+    peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
+    achieved = up_flops / (up_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"uome_up:{cfg.name}")
+    roofline = {"kernel": "uome_up (Eq. 38 grouped GEMM + SiLU + gate)", "bound": "mfma",
+                "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 5), "traffic": traffic,
+                "flops_per_launch": up_flops, "ms_per_launch": round(up_ms, 5)}
+
+    # ---- CPU oracle on this machine's host cores, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nb = cfg.b
+        # keep the sample to a few GFLOP-fp64-seconds: whole batch for the small shapes, else 1 sample
+        if fl["total"] > 4e10:
+            nb = 1
+
+        class _Sub:   # the first nb samples of the same inputs
+            pass
+        sub = _Sub()
+        sub.__dict__.update(inp.__dict__)
+        sub.x = inp.x[:nb]
+        for f in ("noise_a_expert", "noise_a_patch", "noise_m_expert"):
+            v = getattr(inp, f)
+            setattr(sub, f, None if v is None else v[:nb])
+        oracle.layer_forward(sub, fa, fm) if fl["total"] * nb / cfg.b < 2e10 else None   # warm the pages
+        c0 = time.perf_counter()
+        oracle.layer_forward(sub, fa, fm)
+        c1 = time.perf_counter()
+        cpu = {"value": round(nb * cfg.l / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.get_threads(),
+               "kind": "oracle", "sample": f"{nb} of {cfg.b} samples of the {cfg.name} workload, one fp64 pass "
+                                           f"({c1 - c0:.2f} s)"}
+
+    line = {
+        "metric": "UoE layer fwd tokens/sec (SMHA+UoME) at 1 GPU",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
+        "config": {"workload": describe(cfg), "flags": "residual+expert gate+patch gate",
+                   "seed": cfg.seed},
+        "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 3),
+        "flops_per_step": fl["total"],
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

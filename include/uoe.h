@@ -135,6 +135,21 @@ int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in,
                      const float *patch_gate, void *out, void *ws, size_t ws_bytes,
                      void *hip_stream);
 
+/*
+ * The two contractions of uoe_uome_forward as separate calls (same kernels), for callers that
+ * keep the hidden activations or time the steps one by one.
+ *   uoe_uome_up   (Eq. 38): hidden[b,l,s*d_e + j] = gate * SiLU(u[b] A^I_i)[.,j] for the sample's
+ *                 s-th active expert i = expert_idx[b,s]; hidden is [b,l,k*d_e] in the storage
+ *                 dtype, written in full.  expert_gate may be NULL without UOE_FLAG_GATE_EXPERT.
+ *   uoe_uome_down (Eq. 39-40): out[b] = (u[b] +) hidden[b] * [A^O_i rows of the active experts,
+ *                 stacked]; out must not alias u or hidden.
+ * Neither needs a workspace.
+ */
+int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, const int32_t *expert_idx,
+                const float *expert_gate, void *hidden, void *hip_stream);
+int uoe_uome_down(const uoe_block_desc *blk, const void *hidden, const void *a_out, const void *u,
+                  const int32_t *expert_idx, void *out, void *hip_stream);
+
 typedef struct {
     const void *w_expert, *w_b, *w_a, *wq, *wk, *wv, *wo;
 } uoe_smha_weights;

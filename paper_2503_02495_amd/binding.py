@@ -18,7 +18,7 @@ F32, BF16 = 0, 1
 FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
 EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_gather", "uoe_smha_forward",
-           "uoe_uome_forward", "uoe_layer_forward")
+           "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward")
 
 
 class UoeError(RuntimeError):
@@ -68,10 +68,13 @@ def lib():
         L.uoe_gather.argtypes = [D, P, P, P, P, P]
         L.uoe_smha_forward.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_uome_forward.argtypes = [D] + [P] * 8 + [P, S, P]
+        L.uoe_uome_up.argtypes = [D, P, P, P, P, P, P]
+        L.uoe_uome_down.argtypes = [D, P, P, P, P, P, P]
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
-        for f in ("uoe_route", "uoe_gather", "uoe_smha_forward", "uoe_uome_forward", "uoe_layer_forward"):
+        for f in ("uoe_route", "uoe_gather", "uoe_smha_forward", "uoe_uome_forward", "uoe_uome_up",
+                  "uoe_uome_down", "uoe_layer_forward"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -148,6 +151,18 @@ def uome_forward(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_
                                 _ptr(expert_gate), _ptr(patch_idx), _ptr(patch_gate), _ptr(out), _ptr(ws),
                                 _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_uome_forward", check)
+
+
+def uome_up(blk, u, a_in, expert_idx, expert_gate, hidden, stream=None, check=True) -> int:
+    st = lib().uoe_uome_up(_ref(blk), _ptr(u), _ptr(a_in), _ptr(expert_idx), _ptr(expert_gate), _ptr(hidden),
+                           _stream(stream))
+    return _done(st, "uoe_uome_up", check)
+
+
+def uome_down(blk, hidden, a_out, u, expert_idx, out, stream=None, check=True) -> int:
+    st = lib().uoe_uome_down(_ref(blk), _ptr(hidden), _ptr(a_out), _ptr(u), _ptr(expert_idx), _ptr(out),
+                             _stream(stream))
+    return _done(st, "uoe_uome_down", check)
 
 
 def smha_weights(w_expert, w_b, w_a, wq, wk, wv, wo) -> SmhaWeights:

@@ -252,6 +252,40 @@ int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in,
                    static_cast<hipStream_t>(hip_stream));
 }
 
+int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, const int32_t *expert_idx,
+                const float *expert_gate, void *hidden, void *hip_stream)
+{
+    const int rc = check_desc(blk, false);
+    if (rc != UOE_OK) return rc;
+    if (blk->c != blk->m || (blk->flags & UOE_FLAG_GATE_PATCH)) return UOE_ERR_UNSUPPORTED;
+    if (!u || !a_in || !expert_idx || !hidden || hidden == u) return UOE_ERR_INVALID_ARG;
+    if (!aligned16(u) || !aligned16(a_in) || !aligned16(hidden)) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_EXPERT) && !expert_gate) return UOE_ERR_INVALID_ARG;
+    UomeArgs a{};
+    a.u = u; a.a_in = a_in; a.expert_idx = expert_idx; a.expert_gate = expert_gate; a.hidden = hidden;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.d_e = blk->width;
+    a.flags = blk->flags;
+    return launch_uome_up(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+int uoe_uome_down(const uoe_block_desc *blk, const void *hidden, const void *a_out, const void *u,
+                  const int32_t *expert_idx, void *out, void *hip_stream)
+{
+    const int rc = check_desc(blk, false);
+    if (rc != UOE_OK) return rc;
+    if (blk->c != blk->m) return UOE_ERR_UNSUPPORTED;
+    if (!hidden || !a_out || !expert_idx || !out || out == hidden || out == u) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_RESIDUAL) && !u) return UOE_ERR_INVALID_ARG;
+    if (!aligned16(hidden) || !aligned16(a_out) || !aligned16(u) || !aligned16(out)) return UOE_ERR_INVALID_ARG;
+    UomeArgs a{};
+    a.u = u; a.a_out = a_out; a.expert_idx = expert_idx; a.hidden = const_cast<void *>(hidden); a.out = out;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.d_e = blk->width;
+    a.flags = blk->flags;
+    return launch_uome_down(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? UOE_OK : UOE_ERR_DEVICE;
+}
+
 int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
                       const float *noise_a_expert, const float *noise_a_patch,
                       const uoe_block_desc *uome, const uoe_uome_weights *wm,

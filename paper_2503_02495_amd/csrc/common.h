@@ -110,6 +110,8 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_gather(const GatherArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome(const UomeArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st);    // Eq. 38 only
+hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // Eq. 39-40 only
 
 // host-side sizing shared by api.cpp and the launchers
 int route_tokens_per_chunk(int b, int l);

@@ -9,7 +9,7 @@
 
 namespace uoe {
 
-template <typename T> static hipError_t uome_generic(const UomeArgs &a, hipStream_t st)
+template <typename T> static hipError_t uome_up_generic(const UomeArgs &a, hipStream_t st)
 {
     UomeUpProblem<T> up;
     up.u = static_cast<const T *>(a.u);
@@ -18,9 +18,11 @@ template <typename T> static hipError_t uome_generic(const UomeArgs &a, hipStrea
     up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
     up.hidden = static_cast<T *>(a.hidden);
     up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
-    hipError_t err = launch_gemm_generic<T>(up, a.b, a.l, a.k * a.d_e, st);
-    if (err != hipSuccess) return err;
+    return launch_gemm_generic<T>(up, a.b, a.l, a.k * a.d_e, st);
+}
 
+template <typename T> static hipError_t uome_down_generic(const UomeArgs &a, hipStream_t st)
+{
     UomeDownProblem<T> dn;
     dn.hidden = static_cast<const T *>(a.hidden);
     dn.a_out = static_cast<const T *>(a.a_out);
@@ -31,9 +33,20 @@ template <typename T> static hipError_t uome_generic(const UomeArgs &a, hipStrea
     return launch_gemm_generic<T>(dn, a.b, a.l, a.d, st);
 }
 
+hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st)
+{
+    return bf16 ? uome_up_generic<bf16_t>(a, st) : uome_up_generic<float>(a, st);
+}
+
+hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st)
+{
+    return bf16 ? uome_down_generic<bf16_t>(a, st) : uome_down_generic<float>(a, st);
+}
+
 hipError_t launch_uome(const UomeArgs &a, bool bf16, hipStream_t st)
 {
-    return bf16 ? uome_generic<bf16_t>(a, st) : uome_generic<float>(a, st);
+    const hipError_t err = launch_uome_up(a, bf16, st);
+    return err != hipSuccess ? err : launch_uome_down(a, bf16, st);
 }
 
 }  // namespace uoe
