@@ -62,13 +62,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(P p)
         __syncthreads();
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = m0 + ty * 4 + i;
-        if (r >= M) continue;
+    for (int j = 0; j < 4; ++j) {
+        const int nn = n0 + tx * 4 + j;
+        if (nn >= N) continue;
+        const auto cc = p.col_ctx(g, nn);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int nn = n0 + tx * 4 + j;
-            if (nn < N) p.store(g, r, nn, acc[i][j]);
+        for (int i = 0; i < 4; ++i) {
+            const int r = m0 + ty * 4 + i;
+            if (r < M) p.store(g, r, nn, acc[i][j], cc);
         }
     }
 }

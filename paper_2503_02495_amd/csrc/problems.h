@@ -5,7 +5,8 @@
 //   rows(g), kdim(g), ncols()            problem extents
 //   a_ptr(g, m, kk)  pointer to A[m][kk..kk+8)   (kk % 8 == 0; 8 elements contiguous)
 //   b_ptr(g, kk, nn) pointer to B[kk][nn..nn+8)  (nn % 8 == 0; 8 elements contiguous)
-//   store(g, m, nn, v) epilogue for one element
+//   col_ctx(g, nn)   whatever the epilogue needs that depends on the column only
+//   store(g, m, nn, v, ctx) epilogue for one element
 // K and N are concatenations of per-expert segments of length `width`; since width % 8 == 0 an
 // 8-element run never straddles two experts.
 #pragma once
@@ -19,8 +20,10 @@ namespace uoe {
 template <typename T> struct QkvProblem {
     const T *x, *wq, *wk, *wv;
     const int32_t *expert_idx, *patch_idx;
-    T *q, *k, *v;  // [units, l_a, d_h]
+    T *q, *k, *v;  // [units, l_a, d_h]; v is [units, d_h, l_a_pad] when v_transposed
     int l, d, n, kact, m, c, l_p, l_a, d_h;
+    int v_transposed, l_a_pad;
+    float q_scale;  // folded into q on the way out (1 for the plain layout)
 
     __device__ int rows(int) const { return l_a; }
     __device__ int kdim(int) const { return d; }
@@ -45,11 +48,22 @@ template <typename T> struct QkvProblem {
         const T *w = which == 0 ? wq : (which == 1 ? wk : wv);
         return w + ((size_t)i * d + kk) * d_h + col;
     }
-    __device__ void store(int g, int r, int nn, float val) const
+    struct ColCtx {
+        int which, col;
+    };
+    __device__ ColCtx col_ctx(int, int nn) const
     {
-        const int which = nn / d_h, col = nn - which * d_h;
-        T *o = which == 0 ? q : (which == 1 ? k : v);
-        o[((size_t)g * l_a + r) * d_h + col] = from_f32<T>(val);
+        ColCtx cc;
+        cc.which = nn / d_h;
+        cc.col = nn - cc.which * d_h;
+        return cc;
+    }
+    __device__ void store(int g, int r, int, float val, const ColCtx &cc) const
+    {
+        if (cc.which == 0) q[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val * q_scale);
+        else if (cc.which == 1) k[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
+        else if (v_transposed) v[((size_t)g * d_h + cc.col) * l_a_pad + r] = from_f32<T>(val);
+        else v[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
     }
 };
 
@@ -85,7 +99,9 @@ template <typename T> struct OutProjProblem {
         const int i = clampi(expert_idx[bb * kact + s], n);
         return wo + ((size_t)i * d_h + (kk - e * d_h)) * d + nn;
     }
-    __device__ void store(int g, int r, int nn, float val) const
+    typedef int ColCtx;
+    __device__ ColCtx col_ctx(int, int) const { return 0; }
+    __device__ void store(int g, int r, int nn, float val, const ColCtx &) const
     {
         const int bb = g / m, p = g - bb * m;
         const size_t at = ((size_t)bb * l + p * l_p + r) * d + nn;
@@ -114,14 +130,15 @@ template <typename T> struct UomeUpProblem {
         const int i = clampi(expert_idx[g * kact + s], n);
         return a_in + ((size_t)i * d + kk) * d_e + (nn - s * d_e);
     }
-    __device__ float gate(int g, int nn) const
+    typedef float ColCtx;  // the gate of the column's expert
+    __device__ ColCtx col_ctx(int g, int nn) const
     {
         if (!expert_gate) return 1.0f;
         return expert_gate[(size_t)g * n + clampi(expert_idx[g * kact + nn / d_e], n)];
     }
-    __device__ void store(int g, int r, int nn, float val) const
+    __device__ void store(int g, int r, int nn, float val, const ColCtx &gate) const
     {
-        hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate(g, nn));
+        hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate);
     }
 };
 
@@ -147,7 +164,9 @@ template <typename T> struct UomeDownProblem {
         const int i = clampi(expert_idx[g * kact + s], n);
         return a_out + ((size_t)i * d_e + (kk - s * d_e)) * d + nn;
     }
-    __device__ void store(int g, int r, int nn, float val) const
+    typedef int ColCtx;
+    __device__ ColCtx col_ctx(int, int) const { return 0; }
+    __device__ void store(int g, int r, int nn, float val, const ColCtx &) const
     {
         const size_t at = ((size_t)g * l + r) * d + nn;
         if (flags & F_RESIDUAL) val += to_f32(u[at]);

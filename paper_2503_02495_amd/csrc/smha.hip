@@ -12,6 +12,7 @@
 #include "common.h"
 #include "problems.h"
 #include "gemm_generic.h"
+#include "gemm_mfma.h"
 
 namespace uoe {
 
@@ -112,13 +113,8 @@ template <typename T> static hipError_t launch_attention_generic(const SmhaArgs 
     return hipGetLastError();
 }
 
-template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStream_t st)
+template <typename T> static QkvProblem<T> make_qkv(const SmhaArgs &a)
 {
-    const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
-    hipError_t err;
-    hipLaunchKernelGGL(smha_inverse_map_kernel, dim3((a.b * a.m + 255) / 256), dim3(256), 0, st, a);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
-
     QkvProblem<T> qp;
     qp.x = static_cast<const T *>(a.x);
     qp.wq = static_cast<const T *>(a.wq);
@@ -130,11 +126,13 @@ template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStrea
     qp.k = static_cast<T *>(a.kk);
     qp.v = static_cast<T *>(a.v);
     qp.l = a.l; qp.d = a.d; qp.n = a.n; qp.kact = a.k; qp.m = a.m; qp.c = a.c;
-    qp.l_p = l_p; qp.l_a = l_a; qp.d_h = a.d_h;
-    if ((err = launch_gemm_generic<T>(qp, units, l_a, 3 * a.d_h, st)) != hipSuccess) return err;
+    qp.l_p = a.l / a.m; qp.l_a = a.c * qp.l_p; qp.d_h = a.d_h;
+    qp.v_transposed = 0; qp.l_a_pad = qp.l_a; qp.q_scale = 1.0f;
+    return qp;
+}
 
-    if ((err = launch_attention_generic<T>(a, st)) != hipSuccess) return err;
-
+template <typename T> static OutProjProblem<T> make_outproj(const SmhaArgs &a)
+{
     OutProjProblem<T> op;
     op.o = static_cast<const T *>(a.o);
     op.wo = static_cast<const T *>(a.wo);
@@ -144,12 +142,48 @@ template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStrea
     op.inv_ent = a.inv_ent;
     op.out = static_cast<T *>(a.out);
     op.l = a.l; op.d = a.d; op.n = a.n; op.kact = a.k; op.m = a.m; op.c = a.c;
-    op.l_p = l_p; op.l_a = l_a; op.d_h = a.d_h; op.flags = a.flags;
-    return launch_gemm_generic<T>(op, a.b * a.m, l_p, a.d, st);
+    op.l_p = a.l / a.m; op.l_a = a.c * op.l_p; op.d_h = a.d_h; op.flags = a.flags;
+    return op;
+}
+
+template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStream_t st)
+{
+    const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
+    hipError_t err;
+    hipLaunchKernelGGL(smha_inverse_map_kernel, dim3((a.b * a.m + 255) / 256), dim3(256), 0, st, a);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    if ((err = launch_gemm_generic<T>(make_qkv<T>(a), units, l_a, 3 * a.d_h, st)) != hipSuccess) return err;
+    if ((err = launch_attention_generic<T>(a, st)) != hipSuccess) return err;
+    return launch_gemm_generic<T>(make_outproj<T>(a), a.b * a.m, l_p, a.d, st);
+}
+
+// MFMA path: bf16 storage, d and d_h multiples of 32 (the K segments of the two projections)
+static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
+{
+    typedef QkvProblem<bf16_t> QP;
+    typedef OutProjProblem<bf16_t> OP;
+    const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
+    hipError_t err;
+    hipLaunchKernelGGL(smha_inverse_map_kernel, dim3((a.b * a.m + 255) / 256), dim3(256), 0, st, a);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+
+    const QP qp = make_qkv<bf16_t>(a);
+    // one workgroup row-tile computes q, k and v together so the gathered rows are read once
+    if (a.d_h == 32) err = launch_gemm_mfma<QP, 128, 96, 4, 1>(qp, units, l_a, 96, st);
+    else if (a.d_h == 64) err = launch_gemm_mfma<QP, 128, 192, 4, 1>(qp, units, l_a, 192, st);
+    else err = launch_gemm_mfma<QP, 128, 128, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
+    if (err != hipSuccess) return err;
+
+    if ((err = launch_attention_generic<bf16_t>(a, st)) != hipSuccess) return err;
+
+    const OP op = make_outproj<bf16_t>(a);
+    if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 1, 4>(op, a.b * a.m, l_p, a.d, st);
+    return launch_gemm_mfma<OP, 64, 128, 2, 2>(op, a.b * a.m, l_p, a.d, st);
 }
 
 hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st)
 {
+    if (bf16 && a.d % 32 == 0 && a.d_h % 32 == 0) return smha_mfma(a, st);
     return bf16 ? smha_generic<bf16_t>(a, st) : smha_generic<float>(a, st);
 }
 

@@ -6,6 +6,7 @@
 #include "common.h"
 #include "problems.h"
 #include "gemm_generic.h"
+#include "gemm_mfma.h"
 
 namespace uoe {
 
@@ -33,13 +34,45 @@ template <typename T> static hipError_t uome_down_generic(const UomeArgs &a, hip
     return launch_gemm_generic<T>(dn, a.b, a.l, a.d, st);
 }
 
+// MFMA path: bf16 storage, and every K segment (d for GEMM-1, d_e for GEMM-2) a multiple of 32
+static bool uome_mfma_ok(const UomeArgs &a, bool bf16) { return bf16 && a.d % 32 == 0 && a.d_e % 32 == 0; }
+
+static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
+{
+    UomeUpProblem<bf16_t> up;
+    up.u = static_cast<const bf16_t *>(a.u);
+    up.a_in = static_cast<const bf16_t *>(a.a_in);
+    up.expert_idx = a.expert_idx;
+    up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
+    up.hidden = static_cast<bf16_t *>(a.hidden);
+    up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
+    const int N = a.k * a.d_e;
+    if (a.l > 64) return launch_gemm_mfma<UomeUpProblem<bf16_t>, 128, 128, 2, 2>(up, a.b, a.l, N, st);
+    return launch_gemm_mfma<UomeUpProblem<bf16_t>, 64, 64, 2, 2>(up, a.b, a.l, N, st);
+}
+
+static hipError_t uome_down_mfma(const UomeArgs &a, hipStream_t st)
+{
+    UomeDownProblem<bf16_t> dn;
+    dn.hidden = static_cast<const bf16_t *>(a.hidden);
+    dn.a_out = static_cast<const bf16_t *>(a.a_out);
+    dn.u = static_cast<const bf16_t *>(a.u);
+    dn.expert_idx = a.expert_idx;
+    dn.out = static_cast<bf16_t *>(a.out);
+    dn.l = a.l; dn.d = a.d; dn.n = a.n; dn.kact = a.k; dn.d_e = a.d_e; dn.flags = a.flags;
+    if (a.l > 64) return launch_gemm_mfma<UomeDownProblem<bf16_t>, 128, 128, 2, 2>(dn, a.b, a.l, a.d, st);
+    return launch_gemm_mfma<UomeDownProblem<bf16_t>, 64, 64, 2, 2>(dn, a.b, a.l, a.d, st);
+}
+
 hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st)
 {
+    if (uome_mfma_ok(a, bf16)) return uome_up_mfma(a, st);
     return bf16 ? uome_up_generic<bf16_t>(a, st) : uome_up_generic<float>(a, st);
 }
 
 hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st)
 {
+    if (uome_mfma_ok(a, bf16)) return uome_down_mfma(a, st);
     return bf16 ? uome_down_generic<bf16_t>(a, st) : uome_down_generic<float>(a, st);
 }
 
