@@ -54,18 +54,19 @@ RouteWs route_ws(int b, int l, int n, int m)
 }
 
 struct SmhaWs {
-    size_t q, k, v, o, inv_cnt, inv_ent, total;
+    size_t q, k, v, o, o_lo, inv_cnt, inv_ent, total;
 };
 SmhaWs smha_ws(const uoe_block_desc *d)
 {
     SmhaWs w;
-    const size_t l_a = (size_t)d->c * (d->l / d->m);
+    const size_t l_a = (((size_t)d->c * (d->l / d->m)) + 7) & ~(size_t)7;  // v may be stored transposed, rows padded to 8
     const size_t one = up((size_t)d->b * d->k * l_a * d->width * elem_size(d->dtype));
     size_t off = 0;
     w.q = off; off += one;
     w.k = off; off += one;
     w.v = off; off += one;
     w.o = off; off += one;
+    w.o_lo = off; off += one;
     w.inv_cnt = off; off += up((size_t)d->b * d->m * sizeof(int32_t));
     w.inv_ent = off; off += up((size_t)d->b * d->m * d->k * sizeof(int32_t));
     w.total = off;
@@ -145,7 +146,7 @@ int do_smha(const uoe_block_desc *blk, const void *x, const void *wq, const void
     a.out = out;
     a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = blk->m; a.c = blk->c;
     a.d_h = blk->width; a.flags = blk->flags;
-    a.q = at(ws, w.q); a.kk = at(ws, w.k); a.v = at(ws, w.v); a.o = at(ws, w.o);
+    a.q = at(ws, w.q); a.kk = at(ws, w.k); a.v = at(ws, w.v); a.o = at(ws, w.o); a.o_lo = at(ws, w.o_lo);
     a.inv_cnt = reinterpret_cast<int32_t *>(at(ws, w.inv_cnt));
     a.inv_ent = reinterpret_cast<int32_t *>(at(ws, w.inv_ent));
     return launch_smha(a, blk->dtype == UOE_BF16, st) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;

@@ -84,7 +84,7 @@ struct SmhaArgs {
     int b, l, d, n, k, m, c, d_h;
     uint32_t flags;
     // workspace
-    void *q, *kk, *v, *o;                     // [b*k, l_a, d_h] each, storage dtype
+    void *q, *kk, *v, *o, *o_lo;              // [b*k, l_a, d_h] each, storage dtype (o_lo: low part of o, MFMA path)
     int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k]: which (slot s, pick t) chose patch p
 };
 

@@ -72,32 +72,38 @@ template <typename T> struct QkvProblem {
 // K = (number of active experts that picked p) * d_h.  The per-expert products o_i W^o_i that land
 // on the same patch are summed as one contraction over the concatenated K, so each output row is
 // written exactly once (residual added in the epilogue) and no atomics are needed.
-// o already carries the gate weight of its row.
+// o already carries the gate weight of its row.  In the bf16 MFMA path o arrives as two bf16
+// buffers, o = hi + lo, so that the attention output enters this contraction with ~16 significant
+// bits instead of 8 (the rows of W^o are simply visited twice).
 template <typename T> struct OutProjProblem {
-    const T *o, *wo, *x;
+    const T *o, *o_lo, *wo, *x;
     const int32_t *expert_idx, *inv_cnt, *inv_ent;
     T *out;
     int l, d, n, kact, m, c, l_p, l_a, d_h;
+    int parts;  // 1: o only; 2: o is a (hi, lo) pair of buffers, contracted as [hi | lo] x [W^o ; W^o]
     uint32_t flags;
 
     __device__ int rows(int) const { return l_p; }
-    __device__ int kdim(int g) const { return inv_cnt[g] * d_h; }
+    __device__ int kdim(int g) const { return inv_cnt[g] * parts * d_h; }
     __device__ int ncols() const { return d; }
     __device__ const T *a_ptr(int g, int r, int kk) const
     {
         const int bb = g / m;
-        const int e = kk / d_h;
+        const int seg = kk / d_h;
+        const int e = parts == 2 ? seg >> 1 : seg;
+        const T *src = (parts == 2 && (seg & 1)) ? o_lo : o;
         const int ent = inv_ent[(size_t)g * kact + e];  // slot s * c + pick t
         const int s = ent / c, t = ent - s * c;
-        return o + (((size_t)bb * kact + s) * l_a + t * l_p + r) * d_h + (kk - e * d_h);
+        return src + (((size_t)bb * kact + s) * l_a + t * l_p + r) * d_h + (kk - seg * d_h);
     }
     __device__ const T *b_ptr(int g, int kk, int nn) const
     {
         const int bb = g / m;
-        const int e = kk / d_h;
+        const int seg = kk / d_h;
+        const int e = parts == 2 ? seg >> 1 : seg;
         const int s = inv_ent[(size_t)g * kact + e] / c;
         const int i = clampi(expert_idx[bb * kact + s], n);
-        return wo + ((size_t)i * d_h + (kk - e * d_h)) * d + nn;
+        return wo + ((size_t)i * d_h + (kk - seg * d_h)) * d + nn;
     }
     typedef int ColCtx;
     __device__ ColCtx col_ctx(int, int) const { return 0; }

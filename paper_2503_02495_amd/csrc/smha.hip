@@ -113,6 +113,229 @@ template <typename T> static hipError_t launch_attention_generic(const SmhaArgs 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// MFMA attention (bf16, d_h in {32, 64, 128}).  One wave owns 32 query rows of one unit and walks
+// the unit's keys in tiles of 64, online softmax in fp32 (base 2: q arrives pre-scaled by
+// log2(e)/sqrt(d_h)).  The scores are computed TRANSPOSED, S^T = K Q^T, so that an accumulator
+// lane holds one query column: the row max / row sum of the softmax are then in-lane reductions
+// plus one exchange with the partner lane (lane ^ 32), and the probabilities, converted to bf16
+// in place, already ARE the B operand of the second product O^T = V^T P^T (the k-slots of an MFMA
+// operand may hold any permutation of K as long as both operands agree, so V^T is read with the
+// accumulator's key order: keys 16s+4h..+4 and 16s+8+4h..+4 for k-step s, half-wave h).
+// K tiles [key][d_h] and V^T tiles [d_h][key] are staged through double-buffered LDS; the
+// projection kernel writes v transposed so both tiles are plain 16-byte row copies.
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a, int l_a_pad)
+{
+    constexpr int BKV = 64, KP = DH + 8, VP = BKV + 8, NT = NW * 64;
+    constexpr int K_CHUNKS = BKV * DH / 8, V_CHUNKS = DH * BKV / 8;
+    constexpr int K_PER_T = (K_CHUNKS + NT - 1) / NT, V_PER_T = (V_CHUNKS + NT - 1) / NT;
+    __shared__ __align__(16) uint16_t Ks[2][BKV][KP];
+    __shared__ __align__(16) uint16_t Vs[2][DH][VP];
+
+    const int g = blockIdx.y;
+    const int l_p = a.l / a.m, l_a = a.c * l_p;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lr = lane & 31, lh = lane >> 5;
+    const int qrow = blockIdx.x * (32 * NW) + wave * 32 + lr;
+    const bf16_t *Q = static_cast<const bf16_t *>(a.q) + (size_t)g * l_a * DH;
+    const bf16_t *Kg = static_cast<const bf16_t *>(a.kk) + (size_t)g * l_a * DH;
+    const bf16_t *Vt = static_cast<const bf16_t *>(a.v) + (size_t)g * DH * l_a_pad;
+
+    bf16x8_t qf[DH / 16];
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (qrow < l_a) v = *reinterpret_cast<const uint4 *>(Q + (size_t)qrow * DH + ks * 16 + lh * 8);
+        qf[ks] = __builtin_bit_cast(bf16x8_t, v);
+    }
+
+    f32x16_t oacc[DH / 32];
+#pragma unroll
+    for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) oacc[t][q] = 0.f;
+    float mrun = -INFINITY, lsum = 0.f;
+
+    uint4 kreg[K_PER_T], vreg[V_PER_T];
+    auto load_global = [&](int key0) {
+#pragma unroll
+        for (int i = 0; i < K_PER_T; ++i) {
+            const int c = tid + i * NT;
+            const int row = c / (DH / 8), kc = c % (DH / 8);
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (c < K_CHUNKS && key0 + row < l_a)
+                v = *reinterpret_cast<const uint4 *>(Kg + (size_t)(key0 + row) * DH + kc * 8);
+            kreg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < V_PER_T; ++i) {
+            const int c = tid + i * NT;
+            const int row = c / (BKV / 8), kc = c % (BKV / 8);
+            const int key = key0 + kc * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (c < V_CHUNKS && key < l_a) {
+                v = *reinterpret_cast<const uint4 *>(Vt + (size_t)row * l_a_pad + key);
+                if (key + 8 > l_a) {  // chunk straddles the end: zero the padding columns
+                    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (key + e >= l_a) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+                    v = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+            vreg[i] = v;
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < K_PER_T; ++i) {
+            const int c = tid + i * NT;
+            if (c < K_CHUNKS) *reinterpret_cast<uint4 *>(&Ks[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < V_PER_T; ++i) {
+            const int c = tid + i * NT;
+            if (c < V_CHUNKS) *reinterpret_cast<uint4 *>(&Vs[buf][c / (BKV / 8)][(c % (BKV / 8)) * 8]) = vreg[i];
+        }
+    };
+
+    const int nkt = (l_a + BKV - 1) / BKV;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nkt) load_global((kt + 1) * BKV);
+
+        // S^T tile: [64 keys x 32 queries] as two 32x32 accumulators
+        f32x16_t sacc[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) sacc[t][q] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < DH / 16; ++ks)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(&Ks[buf][t * 32 + lr][ks * 16 + lh * 8]);
+                sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
+            }
+        // accumulator register q of tile t is key kt*64 + t*32 + (q/4)*8 + lh*4 + q%4
+        if ((kt + 1) * BKV > l_a) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int key = kt * BKV + t * 32 + (q >> 2) * 8 + lh * 4 + (q & 3);
+                    if (key >= l_a) sacc[t][q] = -INFINITY;
+                }
+        }
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, sacc[t][q]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float mnew = fmaxf(mrun, tmax);
+        const float corr = __builtin_amdgcn_exp2f(mrun - mnew);  // 0 on the first tile
+        mrun = mnew;
+        float psum = 0.f;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const float pv = __builtin_amdgcn_exp2f(sacc[t][q] - mnew);
+                sacc[t][q] = pv;
+                psum += pv;
+            }
+        lsum = lsum * corr + psum;
+#pragma unroll
+        for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) oacc[t][q] *= corr;
+
+        // O^T += V^T P^T over the 64 keys of the tile: four k-steps of 16 keys
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const int t = s4 >> 1, r0 = (s4 & 1) * 8;
+            // probabilities as a (hi, lo) bf16 pair: P V = P_hi V + P_lo V keeps ~16 bits of P
+            uint32_t hi[8], lo[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float pv = sacc[t][r0 + e];
+                hi[e] = f32_to_bf16_bits(pv);
+                lo[e] = f32_to_bf16_bits(pv - __uint_as_float(hi[e] << 16));
+            }
+            const bf16x8_t pf_hi = __builtin_bit_cast(
+                bf16x8_t, make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)));
+            const bf16x8_t pf_lo = __builtin_bit_cast(
+                bf16x8_t, make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)));
+#pragma unroll
+            for (int td = 0; td < DH / 32; ++td) {
+                const uint2 v0 = *reinterpret_cast<const uint2 *>(&Vs[buf][td * 32 + lr][s4 * 16 + lh * 4]);
+                const uint2 v1 = *reinterpret_cast<const uint2 *>(&Vs[buf][td * 32 + lr][s4 * 16 + 8 + lh * 4]);
+                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_hi, oacc[td], 0, 0, 0);
+                oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, oacc[td], 0, 0, 0);
+            }
+        }
+        if (kt + 1 < nkt) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    if (qrow >= l_a) return;
+    lsum += __shfl_xor(lsum, 32, 64);
+    // gate weight of this row (Eq. 36 with the optional gate flags)
+    const int bb = g / a.k, i = clampi(a.expert_idx[g], a.n);
+    float w = 1.0f;
+    if ((a.flags & F_GATE_EXPERT) && a.expert_gate) w *= a.expert_gate[(size_t)bb * a.n + i];
+    if ((a.flags & F_GATE_PATCH) && a.patch_gate) {
+        const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + qrow / l_p], a.m);
+        w *= a.patch_gate[((size_t)bb * a.n + i) * a.m + p];
+    }
+    const float inv = w / lsum;
+    bf16_t *o = static_cast<bf16_t *>(a.o) + ((size_t)g * l_a + qrow) * DH;
+    bf16_t *o_lo = static_cast<bf16_t *>(a.o_lo) + ((size_t)g * l_a + qrow) * DH;
+    // accumulator register q of tile td is head-dim index td*32 + (q/4)*8 + lh*4 + q%4.
+    // o is written as hi = bf16(o) and lo = bf16(o - hi): the out-projection contracts both.
+#pragma unroll
+    for (int td = 0; td < DH / 32; ++td)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float val = oacc[td][i4 * 4 + e] * inv;
+                hi[e] = f32_to_bf16_bits(val);
+                lo[e] = f32_to_bf16_bits(val - __uint_as_float(hi[e] << 16));
+            }
+            *reinterpret_cast<uint2 *>(o + td * 32 + i4 * 8 + lh * 4) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+            *reinterpret_cast<uint2 *>(o_lo + td * 32 + i4 * 8 + lh * 4) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+        }
+}
+
+template <int DH> static hipError_t launch_attention_mfma_dh(const SmhaArgs &a, int l_a_pad, hipStream_t st)
+{
+    const int l_a = a.c * (a.l / a.m), units = a.b * a.k;
+    // more waves per workgroup share K/V tiles; fewer give more workgroups: keep >= 512 if possible
+    if ((long)((l_a + 127) / 128) * units >= 512) {
+        hipLaunchKernelGGL((attention_mfma_kernel<DH, 4>), dim3((l_a + 127) / 128, units), dim3(256), 0, st, a, l_a_pad);
+    } else if ((long)((l_a + 63) / 64) * units >= 512) {
+        hipLaunchKernelGGL((attention_mfma_kernel<DH, 2>), dim3((l_a + 63) / 64, units), dim3(128), 0, st, a, l_a_pad);
+    } else {
+        hipLaunchKernelGGL((attention_mfma_kernel<DH, 1>), dim3((l_a + 31) / 32, units), dim3(64), 0, st, a, l_a_pad);
+    }
+    return hipGetLastError();
+}
+
+static hipError_t launch_attention_mfma(const SmhaArgs &a, int l_a_pad, hipStream_t st)
+{
+    if (a.d_h == 32) return launch_attention_mfma_dh<32>(a, l_a_pad, st);
+    if (a.d_h == 64) return launch_attention_mfma_dh<64>(a, l_a_pad, st);
+    return launch_attention_mfma_dh<128>(a, l_a_pad, st);
+}
+
 template <typename T> static QkvProblem<T> make_qkv(const SmhaArgs &a)
 {
     QkvProblem<T> qp;
@@ -135,6 +358,8 @@ template <typename T> static OutProjProblem<T> make_outproj(const SmhaArgs &a)
 {
     OutProjProblem<T> op;
     op.o = static_cast<const T *>(a.o);
+    op.o_lo = nullptr;
+    op.parts = 1;
     op.wo = static_cast<const T *>(a.wo);
     op.x = static_cast<const T *>(a.x);
     op.expert_idx = a.expert_idx;
@@ -167,16 +392,28 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     hipLaunchKernelGGL(smha_inverse_map_kernel, dim3((a.b * a.m + 255) / 256), dim3(256), 0, st, a);
     if ((err = hipGetLastError()) != hipSuccess) return err;
 
-    const QP qp = make_qkv<bf16_t>(a);
+    QP qp = make_qkv<bf16_t>(a);
+    const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
+    const int l_a_pad = (l_a + 7) & ~7;
+    if (mfma_attn) {  // layouts the MFMA attention kernel reads: v transposed, q pre-scaled (base-2 softmax)
+        qp.v_transposed = 1;
+        qp.l_a_pad = l_a_pad;
+        qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);
+    }
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
     if (a.d_h == 32) err = launch_gemm_mfma<QP, 128, 96, 4, 1>(qp, units, l_a, 96, st);
     else if (a.d_h == 64) err = launch_gemm_mfma<QP, 128, 192, 4, 1>(qp, units, l_a, 192, st);
     else err = launch_gemm_mfma<QP, 128, 128, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
     if (err != hipSuccess) return err;
 
-    if ((err = launch_attention_generic<bf16_t>(a, st)) != hipSuccess) return err;
+    err = mfma_attn ? launch_attention_mfma(a, l_a_pad, st) : launch_attention_generic<bf16_t>(a, st);
+    if (err != hipSuccess) return err;
 
-    const OP op = make_outproj<bf16_t>(a);
+    OP op = make_outproj<bf16_t>(a);
+    if (mfma_attn) {  // the MFMA attention kernel writes o as a (hi, lo) bf16 pair
+        op.o_lo = static_cast<const bf16_t *>(a.o_lo);
+        op.parts = 2;
+    }
     if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 1, 4>(op, a.b * a.m, l_p, a.d, st);
     return launch_gemm_mfma<OP, 64, 128, 2, 2>(op, a.b * a.m, l_p, a.d, st);
 }

@@ -74,6 +74,10 @@ EDGE_CONFIGS = {
     "dh128_multi_tile": small(b=2, l=300, d=72, n_a=3, d_h=128, m=2, c=2, k_a=2, n_m=2, d_e=136, k_m=1),
     "bf16_ragged": small(b=3, l=140, d=64, n_a=4, d_h=32, m=10, c=3, k_a=3, n_m=4, d_e=64, k_m=2,
                          dtype=synth.BF16),
+    "bf16_la21": small(b=2, l=70, d=64, n_a=4, d_h=32, m=10, c=3, k_a=2, n_m=4, d_e=32, k_m=2,
+                       dtype=synth.BF16),
+    "bf16_dh128": small(b=2, l=192, d=128, n_a=2, d_h=128, m=3, c=2, k_a=2, n_m=2, d_e=96, k_m=1,
+                        dtype=synth.BF16),
     "bf16_noise": small(b=2, l=96, d=128, n_a=8, d_h=64, m=12, c=5, k_a=3, n_m=8, d_e=128, k_m=3,
                         dtype=synth.BF16, router_noise=True),
 }
