@@ -25,26 +25,29 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(P p)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
+    const int kseg = p.kseg();
+    const long bstride = p.b_stride();
     for (int k0 = 0; k0 < K; k0 += BK) {
+        const int seg = k0 / kseg, off = k0 - seg * kseg;
         if (tid < 64) {  // A: one row of 8 k per thread
             float v[8];
             const int r = m0 + tid;
-            if (r < M) load8(p.a_ptr(g, r, k0), v);
+            if (r < M) load8(p.a_seg_ptr(g, r, seg) + off, v);
             else
 #pragma unroll
                 for (int q = 0; q < 8; ++q) v[q] = 0.f;
 #pragma unroll
             for (int q = 0; q < 8; ++q) As[q][tid] = v[q];
         } else if (tid < 128) {  // B: 8 k-rows x 8 column segments of 8
-            const int idx = tid - 64, kk = idx >> 3, seg = idx & 7;
+            const int idx = tid - 64, kk = idx >> 3, cseg = idx & 7;  // cseg: column chunk, not a K segment
             float v[8];
-            const int nn = n0 + seg * 8;
-            if (nn < N) load8(p.b_ptr(g, k0 + kk, nn), v);
+            const int nn = n0 + cseg * 8;
+            if (nn < N) load8(p.b_seg_ptr(g, seg, nn) + (long)(off + kk) * bstride, v);
             else
 #pragma unroll
                 for (int q = 0; q < 8; ++q) v[q] = 0.f;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) Bs[kk][seg * 8 + q] = v[q];
+            for (int q = 0; q < 8; ++q) Bs[kk][cseg * 8 + q] = v[q];
         }
         __syncthreads();
 #pragma unroll

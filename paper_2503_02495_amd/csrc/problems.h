@@ -3,8 +3,10 @@
 // the rows/columns of B are resolved through the routing indices.  A problem is a small POD
 // passed by value to a GEMM engine; engines ask it for
 //   rows(g), kdim(g), ncols()            problem extents
-//   a_ptr(g, m, kk)  pointer to A[m][kk..kk+8)   (kk % 8 == 0; 8 elements contiguous)
-//   b_ptr(g, kk, nn) pointer to B[kk][nn..nn+8)  (nn % 8 == 0; 8 elements contiguous)
+//   kseg()                               length of one K segment (one expert's slice, or all of K)
+//   a_seg_ptr(g, m, seg)   pointer to A[m][seg*kseg]; the segment's kseg elements are contiguous
+//   b_seg_ptr(g, seg, nn)  pointer to B[seg*kseg][nn..nn+8)  (nn % 8 == 0)
+//   b_stride()             elements between consecutive K rows of B inside a segment
 //   col_ctx(g, nn)   whatever the epilogue needs that depends on the column only
 //   store(g, m, nn, v, ctx) epilogue for one element
 // K and N are concatenations of per-expert segments of length `width`; since width % 8 == 0 an
@@ -36,17 +38,19 @@ template <typename T> struct QkvProblem {
         const int t = r / l_p;
         return clampi(patch_idx[((size_t)bb * n + i) * c + t], m) * l_p + (r - t * l_p);
     }
-    __device__ const T *a_ptr(int g, int r, int kk) const
+    __device__ int kseg() const { return d; }
+    __device__ long b_stride() const { return d_h; }
+    __device__ const T *a_seg_ptr(int g, int r, int) const
     {
         const int bb = g / kact;
-        return x + ((size_t)bb * l + token(g, r)) * d + kk;
+        return x + ((size_t)bb * l + token(g, r)) * d;
     }
-    __device__ const T *b_ptr(int g, int kk, int nn) const
+    __device__ const T *b_seg_ptr(int g, int, int nn) const
     {
         const int i = expert(g);
         const int which = nn / d_h, col = nn - which * d_h;
         const T *w = which == 0 ? wq : (which == 1 ? wk : wv);
-        return w + ((size_t)i * d + kk) * d_h + col;
+        return w + (size_t)i * d * d_h + col;
     }
     struct ColCtx {
         int which, col;
@@ -86,24 +90,24 @@ template <typename T> struct OutProjProblem {
     __device__ int rows(int) const { return l_p; }
     __device__ int kdim(int g) const { return inv_cnt[g] * parts * d_h; }
     __device__ int ncols() const { return d; }
-    __device__ const T *a_ptr(int g, int r, int kk) const
+    __device__ int kseg() const { return d_h; }
+    __device__ long b_stride() const { return d; }
+    __device__ const T *a_seg_ptr(int g, int r, int seg) const
     {
         const int bb = g / m;
-        const int seg = kk / d_h;
-        const int e = parts == 2 ? seg >> 1 : seg;
+        const int e = clampi(parts == 2 ? seg >> 1 : seg, kact);
         const T *src = (parts == 2 && (seg & 1)) ? o_lo : o;
-        const int ent = inv_ent[(size_t)g * kact + e];  // slot s * c + pick t
+        const int ent = clampi(inv_ent[(size_t)g * kact + e], kact * c);  // slot s * c + pick t
         const int s = ent / c, t = ent - s * c;
-        return src + (((size_t)bb * kact + s) * l_a + t * l_p + r) * d_h + (kk - seg * d_h);
+        return src + (((size_t)bb * kact + s) * l_a + t * l_p + r) * d_h;
     }
-    __device__ const T *b_ptr(int g, int kk, int nn) const
+    __device__ const T *b_seg_ptr(int g, int seg, int nn) const
     {
         const int bb = g / m;
-        const int seg = kk / d_h;
-        const int e = parts == 2 ? seg >> 1 : seg;
-        const int s = inv_ent[(size_t)g * kact + e] / c;
+        const int e = clampi(parts == 2 ? seg >> 1 : seg, kact);
+        const int s = clampi(inv_ent[(size_t)g * kact + e], kact * c) / c;
         const int i = clampi(expert_idx[bb * kact + s], n);
-        return wo + ((size_t)i * d_h + (kk - seg * d_h)) * d + nn;
+        return wo + (size_t)i * d_h * d + nn;
     }
     typedef int ColCtx;
     __device__ ColCtx col_ctx(int, int) const { return 0; }
@@ -129,12 +133,14 @@ template <typename T> struct UomeUpProblem {
     __device__ int rows(int) const { return l; }
     __device__ int kdim(int) const { return d; }
     __device__ int ncols() const { return kact * d_e; }
-    __device__ const T *a_ptr(int g, int r, int kk) const { return u + ((size_t)g * l + r) * d + kk; }
-    __device__ const T *b_ptr(int g, int kk, int nn) const
+    __device__ int kseg() const { return d; }
+    __device__ long b_stride() const { return d_e; }
+    __device__ const T *a_seg_ptr(int g, int r, int) const { return u + ((size_t)g * l + r) * d; }
+    __device__ const T *b_seg_ptr(int g, int, int nn) const
     {
         const int s = nn / d_e;
         const int i = clampi(expert_idx[g * kact + s], n);
-        return a_in + ((size_t)i * d + kk) * d_e + (nn - s * d_e);
+        return a_in + (size_t)i * d * d_e + (nn - s * d_e);
     }
     typedef float ColCtx;  // the gate of the column's expert
     __device__ ColCtx col_ctx(int g, int nn) const
@@ -160,15 +166,16 @@ template <typename T> struct UomeDownProblem {
     __device__ int rows(int) const { return l; }
     __device__ int kdim(int) const { return kact * d_e; }
     __device__ int ncols() const { return d; }
-    __device__ const T *a_ptr(int g, int r, int kk) const
+    __device__ int kseg() const { return d_e; }
+    __device__ long b_stride() const { return d; }
+    __device__ const T *a_seg_ptr(int g, int r, int seg) const
     {
-        return hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + kk;
+        return hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + (size_t)clampi(seg, kact) * d_e;
     }
-    __device__ const T *b_ptr(int g, int kk, int nn) const
+    __device__ const T *b_seg_ptr(int g, int seg, int nn) const
     {
-        const int s = kk / d_e;
-        const int i = clampi(expert_idx[g * kact + s], n);
-        return a_out + ((size_t)i * d_e + (kk - s * d_e)) * d + nn;
+        const int i = clampi(expert_idx[g * kact + clampi(seg, kact)], n);
+        return a_out + (size_t)i * d_e * d + nn;
     }
     typedef int ColCtx;
     __device__ ColCtx col_ctx(int, int) const { return 0; }

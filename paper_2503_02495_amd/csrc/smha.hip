@@ -401,9 +401,9 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
         qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);
     }
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
-    if (a.d_h == 32) err = launch_gemm_mfma<QP, 128, 96, 4, 1>(qp, units, l_a, 96, st);
-    else if (a.d_h == 64) err = launch_gemm_mfma<QP, 128, 192, 4, 1>(qp, units, l_a, 192, st);
-    else err = launch_gemm_mfma<QP, 128, 128, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
+    if (a.d_h == 32) err = launch_gemm_mfma<QP, 128, 96, 32, 4, 1>(qp, units, l_a, 96, st);
+    else if (a.d_h == 64) err = launch_gemm_mfma<QP, 128, 192, 32, 4, 1>(qp, units, l_a, 192, st);
+    else err = launch_gemm_mfma<QP, 128, 128, 32, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
     if (err != hipSuccess) return err;
 
     err = mfma_attn ? launch_attention_mfma(a, l_a_pad, st) : launch_attention_generic<bf16_t>(a, st);
@@ -414,8 +414,8 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
         op.o_lo = static_cast<const bf16_t *>(a.o_lo);
         op.parts = 2;
     }
-    if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 1, 4>(op, a.b * a.m, l_p, a.d, st);
-    return launch_gemm_mfma<OP, 64, 128, 2, 2>(op, a.b * a.m, l_p, a.d, st);
+    if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
+    return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
 }
 
 hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st)
