@@ -36,17 +36,19 @@ int check_desc(const uoe_block_desc *d, bool smha)
 }
 
 struct RouteWs {
-    int tc, nchunks;
+    int tc, nchunks, tc_d, nchunks_d;
     size_t zpart, gpart, zred, gred, total;
 };
-RouteWs route_ws(int b, int l, int n, int m)
+RouteWs route_ws(int b, int l, int d, int n, int m, bool bf16)
 {
     RouteWs w;
     w.tc = route_tokens_per_chunk(b, l);
     w.nchunks = (l + w.tc - 1) / w.tc;
+    w.tc_d = route_data_tokens_per_chunk(b, l, d, n, bf16);
+    w.nchunks_d = (l + w.tc_d - 1) / w.tc_d;
     size_t off = 0;
     w.zpart = off; off += up((size_t)w.nchunks * b * n * sizeof(float));
-    w.gpart = off; off += up((size_t)w.nchunks * b * n * m * sizeof(float));
+    w.gpart = off; off += up((size_t)w.nchunks_d * b * n * m * sizeof(float));
     w.zred = off;  off += up((size_t)b * n * sizeof(float));
     w.gred = off;  off += up((size_t)b * n * m * sizeof(float));
     w.total = off;
@@ -109,14 +111,14 @@ int do_route(const uoe_block_desc *blk, int m, int c, const void *x, const void 
     if ((!w_expert && noise_expert) || (!w_b && noise_patch)) return UOE_ERR_INVALID_ARG;
     // the data router stages W_B (n*d elements) in LDS
     if (w_b && (size_t)blk->n * blk->d * elem_size(blk->dtype) > 48 * 1024) return UOE_ERR_UNSUPPORTED;
-    const RouteWs w = route_ws(blk->b, blk->l, blk->n, m);
+    const RouteWs w = route_ws(blk->b, blk->l, blk->d, blk->n, m, blk->dtype == UOE_BF16);
     if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
 
     RouteArgs a{};
     a.x = x; a.w_e = w_expert; a.w_b = w_b; a.w_a = w_a;
     a.noise_e = noise_expert; a.noise_p = noise_patch;
     a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = m; a.c = c;
-    a.tc = w.tc; a.nchunks = w.nchunks;
+    a.tc = w.tc; a.nchunks = w.nchunks; a.tc_d = w.tc_d; a.nchunks_d = w.nchunks_d;
     a.zpart = reinterpret_cast<float *>(at(ws, w.zpart));
     a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
     a.zred = reinterpret_cast<float *>(at(ws, w.zred));
@@ -194,12 +196,12 @@ size_t uoe_workspace_bytes(const uoe_block_desc *smha, const uoe_block_desc *uom
     size_t total = 0;
     if (smha) {
         if (check_desc(smha, true) != UOE_OK) return 0;
-        total += route_ws(smha->b, smha->l, smha->n, smha->m).total + smha_ws(smha).total +
+        total += route_ws(smha->b, smha->l, smha->d, smha->n, smha->m, smha->dtype == UOE_BF16).total + smha_ws(smha).total +
                  routing_buf(smha, smha->m, smha->c).total;
     }
     if (uome) {
         if (check_desc(uome, false) != UOE_OK) return 0;
-        total += route_ws(uome->b, uome->l, uome->n, uome->m).total + uome_ws(uome) +
+        total += route_ws(uome->b, uome->l, uome->d, uome->n, uome->m, uome->dtype == UOE_BF16).total + uome_ws(uome) +
                  routing_buf(uome, uome->m, uome->c).total;
     }
     if (smha && uome) total += up((size_t)smha->b * smha->l * smha->d * elem_size(smha->dtype));  // u
@@ -328,11 +330,11 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
     char *rabuf = at(ws, off); off += ra.total;
     const RoutingBuf rm = routing_buf(uome, uome->m, uome->c);
     char *rmbuf = at(ws, off); off += rm.total;
-    const size_t route_a_bytes = route_ws(smha->b, smha->l, smha->n, smha->m).total;
+    const size_t route_a_bytes = route_ws(smha->b, smha->l, smha->d, smha->n, smha->m, smha->dtype == UOE_BF16).total;
     void *route_a_ws = at(ws, off); off += route_a_bytes;
     const size_t smha_bytes = smha_ws(smha).total;
     void *smha_scratch = at(ws, off); off += smha_bytes;
-    const size_t route_m_bytes = route_ws(uome->b, uome->l, uome->n, uome->m).total;
+    const size_t route_m_bytes = route_ws(uome->b, uome->l, uome->d, uome->n, uome->m, uome->dtype == UOE_BF16).total;
     void *route_m_ws = at(ws, off); off += route_m_bytes;
     void *uome_scratch = at(ws, off);
     const size_t uome_bytes = uome_ws(uome);

@@ -69,8 +69,9 @@ struct RouteArgs {
     const void *x, *w_e, *w_b, *w_a;          // w_e NULL: no expert router; w_b NULL: no data router
     const float *noise_e, *noise_p;
     int b, l, d, n, k, m, c;
-    int tc, nchunks;                          // tokens per chunk, chunks per sample
-    float *zpart, *gpart;                     // [nchunks, b, n], [nchunks, b, n*m]
+    int tc, nchunks;                          // expert router: tokens per chunk, chunks per sample
+    int tc_d, nchunks_d;                      // data router: the same
+    float *zpart, *gpart;                     // [nchunks, b, n], [nchunks_d, b, n*m]
     float *zred, *gred;                       // [b, n], [b, n*m]
     int32_t *expert_idx, *patch_idx;          // outputs (any may be NULL)
     float *expert_gate, *patch_gate;
@@ -115,5 +116,6 @@ hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // E
 
 // host-side sizing shared by api.cpp and the launchers
 int route_tokens_per_chunk(int b, int l);
+int route_data_tokens_per_chunk(int b, int l, int d, int n, bool bf16);
 
 }  // namespace uoe

@@ -1,19 +1,22 @@
 // Routing of one block (Sec. III-B): expert-selection router (Eq. 21-22) and patch-wise
 // data-selection router (Eq. 13, 14, 17).
 //
-// Three kernels:
-//   route_partial : one pass over x.  A workgroup owns (chunk of tokens, sample); it streams the
-//                   chunk of x once and, from the same registers, accumulates (a) the partial
-//                   expert-router dot products against the matching chunk of W_E and (b) the
-//                   per-token d->n map of the data router, which it then folds with the chunk's
-//                   rows of W_A into a partial [n,m] logit tile.  HBM-bound: x and W_E are each
-//                   read once (W_E chunks are shared by the b samples through L2).
-//   route_reduce  : sums the per-chunk partials in fixed chunk order (deterministic).
-//   route_select  : per sample: + noise, softmax over experts (Eq. 14 / 21), then top-c per
-//                   expert and top-k per sample by rank counting: rank(j) = #{j' : g_j' > g_j or
-//                   (g_j' == g_j and j' < j)}; keep rank < c.  The output slot of a kept index is
-//                   the number of kept lower indices, so the list comes out ascending with no
-//                   sort and ties go to the lower index by construction.
+// Kernels:
+//   route_partial<E>  : expert router.  A workgroup owns (chunk of tokens, sample); each wave
+//                       streams token rows of x and the matching rows of the n W_E slices with
+//                       16-byte loads and keeps n running dot products per lane.  HBM-bound: x and
+//                       W_E are read once (a W_E chunk is shared by the b samples through L2).
+//   route_data_mfma   : data router, bf16.  t1 = x W_B for 16 tokens per wave as
+//                       v_mfma_f32_16x16x32_bf16 (A fragments straight from global, W_B^T staged in
+//                       LDS), then the chunk's rows of W_A fold t1 into a partial [n,m] logit tile.
+//   route_partial<D>  : the same data router on the vector ALU (fp32 storage, or W_B too large
+//                       for LDS next to the MFMA staging).
+//   route_reduce      : sums the per-chunk partials in a fixed order (deterministic).
+//   route_select      : per (expert row, sample): + noise, softmax over experts (Eq. 14 / 21), then
+//                       top-c per expert and top-k per sample by rank counting: rank(j) = #{j' :
+//                       g_j' > g_j or (g_j' == g_j and j' < j)}; keep rank < c.  The output slot of
+//                       a kept index is the number of kept lower indices, so the list comes out
+//                       ascending with no sort and ties go to the lower index by construction.
 #include "common.h"
 
 namespace uoe {
@@ -29,6 +32,29 @@ int route_tokens_per_chunk(int b, int l)
     return (int)tc;
 }
 
+// Data router: tokens per chunk and whether the MFMA kernel applies.  waves*16 tokens per chunk for
+// the MFMA kernel (as many waves as still leave >= 256 workgroups), else the expert router's chunking.
+static int data_mfma_waves(int b, int l)
+{
+    if ((long)((l + 63) / 64) * b >= 256) return 4;
+    if ((long)((l + 31) / 32) * b >= 256) return 2;
+    return 1;
+}
+static size_t data_mfma_lds(int n, int d, int waves)
+{
+    const int np = (n + 15) & ~15, dp = ((d + 31) & ~31) + 8;
+    return (size_t)np * dp * 2 + (size_t)waves * 16 * np * sizeof(float);
+}
+bool route_data_uses_mfma(int b, int l, int d, int n, bool bf16)
+{
+    return bf16 && data_mfma_lds(n, d, data_mfma_waves(b, l)) <= 60 * 1024;
+}
+int route_data_tokens_per_chunk(int b, int l, int d, int n, bool bf16)
+{
+    if (route_data_uses_mfma(b, l, d, n, bf16)) return 16 * data_mfma_waves(b, l);
+    return route_tokens_per_chunk(b, l);
+}
+
 constexpr int ROUTE_THREADS = 256;
 constexpr int ROUTE_WAVES = ROUTE_THREADS / 64;
 
@@ -37,7 +63,12 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_partial_kernel(RouteArgs 
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = blockIdx.x, bb = blockIdx.y;
+    // Workgroup order: the b samples of one chunk are neighbours in time and sit on the same XCD
+    // (workgroup ids are dealt round-robin over the 8 XCDs), so a chunk of W_E is fetched from HBM
+    // once and found in that XCD's L2 by the other samples.
+    const int lin = blockIdx.x;
+    const int chunk = ((lin >> 3) / a.b) * 8 + (lin & 7), bb = (lin >> 3) % a.b;
+    if (chunk >= a.nchunks) return;
     const int n = a.n, d = a.d, l = a.l, m = a.m;
     const int t0 = chunk * a.tc;
     const int tcur = min(a.tc, l - t0);
@@ -63,7 +94,13 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_partial_kernel(RouteArgs 
 #pragma unroll
     for (int i = 0; i < NMAX; ++i) zacc[i] = 0.f;
 
+    // Rows i >= n of the unrolled NMAX loops re-read row n-1 and accumulate into slots that are
+    // never written out: the hot loop has no branches, so all NMAX+1 loads of an iteration are in
+    // flight together.
     const size_t ld = (size_t)l * d;
+    size_t wrow[NMAX];
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i) wrow[i] = (size_t)min(i, n - 1) * ld;
     for (int tl = wave; tl < tcur; tl += ROUTE_WAVES) {
         const int t = t0 + tl;
         const T *xr = x + ((size_t)bb * l + t) * d;
@@ -73,41 +110,39 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_partial_kernel(RouteArgs 
         for (int e = lane * 8; e < d; e += 64 * 8) {
             float xv[8];
             load8(xr + e, xv);
+            if (HAS_E) {
+                const T *wp = w_e + (size_t)t * d + e;
+                float wv[NMAX][8];
 #pragma unroll
-            for (int i = 0; i < NMAX; ++i) {
-                if (i < n) {
-                    if (HAS_E) {
-                        float wv[8];
-                        load8(w_e + (size_t)i * ld + (size_t)t * d + e, wv);
+                for (int i = 0; i < NMAX; ++i) load8(wp + wrow[i], wv[i]);
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) zacc[i] = fmaf(xv[q], wv[q], zacc[i]);
-                    }
-                    if (HAS_D) {
-                        float wv[8];
-                        load8(wb_t + i * d + e, wv);
+                for (int i = 0; i < NMAX; ++i)
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) tacc[i] = fmaf(xv[q], wv[q], tacc[i]);
-                    }
+                    for (int q = 0; q < 8; ++q) zacc[i] = fmaf(xv[q], wv[i][q], zacc[i]);
+            }
+            if (HAS_D) {
+#pragma unroll
+                for (int i = 0; i < NMAX; ++i) {
+                    float wv[8];
+                    load8(wb_t + min(i, n - 1) * d + e, wv);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) tacc[i] = fmaf(xv[q], wv[q], tacc[i]);
                 }
             }
         }
         if (HAS_D) {
 #pragma unroll
             for (int i = 0; i < NMAX; ++i) {
-                if (i < n) {
-                    const float s = wave_sum(tacc[i]);
-                    if (lane == 0) t1s[tl * NMAX + i] = s;
-                }
+                const float s = wave_sum(tacc[i]);
+                if (lane == 0) t1s[tl * NMAX + i] = s;
             }
         }
     }
     if (HAS_E) {
 #pragma unroll
         for (int i = 0; i < NMAX; ++i) {
-            if (i < n) {
-                const float s = wave_sum(zacc[i]);
-                if (lane == 0) zsh[wave * NMAX + i] = s;
-            }
+            const float s = wave_sum(zacc[i]);
+            if (lane == 0) zsh[wave * NMAX + i] = s;
         }
     }
     __syncthreads();
@@ -130,84 +165,170 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_partial_kernel(RouteArgs 
     }
 }
 
-// sums partials over chunks in chunk order; one thread per reduced value
-__global__ __launch_bounds__(256) void route_reduce_kernel(RouteArgs a, int has_e, int has_d)
+typedef __bf16 rt_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float rt_f32x4 __attribute__((ext_vector_type(4)));
+
+// Data router (Eq. 13), bf16, MFMA.  Workgroup = WAVES waves = WAVES*16 tokens of one sample.
+// MFMA 16x16x32 operand layout: lane = (row r = lane%16, k-slice 8*(lane/16)); accumulator register q
+// of a lane is output row 4*(lane/16)+q, column lane%16.
+template <int WAVES, int NTILE>
+__global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a)
 {
-    const long nz = has_e ? (long)a.b * a.n : 0;
-    const long ng = has_d ? (long)a.b * a.n * a.m : 0;
-    const long v = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < nz) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int NTHREADS = WAVES * 64, TC = WAVES * 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = blockIdx.x, bb = blockIdx.y;
+    const int n = a.n, d = a.d, l = a.l, m = a.m;
+    const int np = (n + 15) & ~15, dp = ((d + 31) & ~31) + 8;  // padded expert rows / row pitch
+    const int t0 = chunk * TC, tcur = min(TC, l - t0);
+    uint16_t *wb_t = reinterpret_cast<uint16_t *>(smem);        // [np][dp]: W_B transposed, zero padded
+    float *t1s = reinterpret_cast<float *>(smem + (size_t)np * dp * 2);  // [TC][np]
+
+    const uint16_t *w_b = static_cast<const uint16_t *>(a.w_b);
+    for (int idx = tid; idx < np * dp / 2; idx += NTHREADS) reinterpret_cast<uint32_t *>(wb_t)[idx] = 0u;
+    __syncthreads();
+    for (int idx = tid; idx < n * d; idx += NTHREADS) {  // coalesced read of W_B [d, n], transposed write
+        const int e = idx / n, i = idx - e * n;
+        wb_t[i * dp + e] = w_b[idx];
+    }
+    __syncthreads();
+
+    const int r = lane & 15, ksl = (lane >> 4) * 8;
+    const int trow = min(t0 + wave * 16 + r, l - 1);  // rows past the end repeat the last token; never used
+    const uint16_t *xr = static_cast<const uint16_t *>(a.x) + ((size_t)bb * l + trow) * d;
+    rt_f32x4 acc[NTILE];  // NTILE tiles of 16 experts
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[t][q] = 0.f;
+    constexpr int UN = 4;  // k-steps whose A fragments are in flight together
+    for (int k0 = 0; k0 < d; k0 += 32 * UN) {
+        uint4 av[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int kk = k0 + u * 32 + ksl;
+            const bool ok = kk < d;  // slices past d (d % 128 != 0) contribute zero
+            av[u] = *reinterpret_cast<const uint4 *>(xr + (ok ? kk : 0));
+            if (!ok) av[u] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int kk = min(k0 + u * 32 + ksl, dp - 8);  // stays inside the zero-padded LDS row
+            const rt_bf16x8 af = __builtin_bit_cast(rt_bf16x8, av[u]);
+#pragma unroll
+            for (int t = 0; t < NTILE; ++t) {
+                const rt_bf16x8 bfr = *reinterpret_cast<const rt_bf16x8 *>(wb_t + (size_t)(t * 16 + r) * dp + kk);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfr, acc[t], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t1s[(wave * 16 + (lane >> 4) * 4 + q) * np + t * 16 + r] = acc[t][q];
+    __syncthreads();
+
+    const uint16_t *w_a = static_cast<const uint16_t *>(a.w_a);
+    const int nm = n * m;
+    for (int o = tid; o < nm; o += NTHREADS) {
+        const int i = o / m, j = o - i * m;
         float s = 0.f;
-        for (int ch = 0; ch < a.nchunks; ++ch) s += a.zpart[(size_t)ch * nz + v];
-        a.zred[v] = s;
-    } else if (v - nz < ng) {
-        const long w = v - nz;
-        float s = 0.f;
-        for (int ch = 0; ch < a.nchunks; ++ch) s += a.gpart[(size_t)ch * ng + w];
-        a.gred[w] = s;
+        for (int tl = 0; tl < tcur; ++tl)
+            s = fmaf(t1s[tl * np + i], __uint_as_float((uint32_t)w_a[(size_t)(t0 + tl) * m + j] << 16), s);
+        a.gpart[((size_t)chunk * a.b + bb) * nm + o] = s;
     }
 }
 
-// One workgroup per sample.  LDS: gate tile [n*m] fp32 + kept flags [n*m] bytes.
-__global__ __launch_bounds__(256) void route_select_kernel(RouteArgs a, int has_e, int has_d)
+// Sums the per-chunk partials in a fixed order (deterministic).  A block owns 16 reduced values of
+// one sample; thread (value, chunk group) adds every 16th chunk, then the 16 group sums are added
+// in group order.
+__global__ __launch_bounds__(256) void route_reduce_kernel(RouteArgs a, int has_e, int has_d)
+{
+    __shared__ float part[16][17];
+    const int bb = blockIdx.y, vi = threadIdx.x & 15, cg = threadIdx.x >> 4;
+    const int nz = has_e ? a.n : 0, nm = a.n * a.m;
+    const int nvals = nz + (has_d ? nm : 0);
+    const int v = blockIdx.x * 16 + vi;
+    float s = 0.f;
+    if (v < nvals) {
+        const float *src;
+        size_t stride;
+        if (v < nz) {
+            src = a.zpart + (size_t)bb * a.n + v;
+            stride = (size_t)a.b * a.n;
+        } else {
+            src = a.gpart + (size_t)bb * nm + (v - nz);
+            stride = (size_t)a.b * nm;
+        }
+        const int nch = v < nz ? a.nchunks : a.nchunks_d;
+        for (int ch = cg; ch < nch; ch += 16) s += src[(size_t)ch * stride];
+    }
+    part[cg][vi] = s;
+    __syncthreads();
+    if (threadIdx.x < 16 && v < nvals) {
+        float t = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += part[q][vi];
+        if (v < nz) a.zred[(size_t)bb * a.n + v] = t;
+        else a.gred[(size_t)bb * nm + (v - nz)] = t;
+    }
+}
+
+// One workgroup per (expert i, sample): top-c of row i of the patch gate; the workgroup of expert 0
+// also does the sample's top-k over experts.  LDS: ranking keys of the row [m] + kept flags [m].
+constexpr int SELECT_THREADS = 128;
+__global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs a, int has_e, int has_d)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x, bb = blockIdx.x;
+    const int tid = threadIdx.x, i = blockIdx.x, bb = blockIdx.y;
     const int n = a.n, m = a.m, c = a.c, k = a.k, nm = n * m;
-    float *g = reinterpret_cast<float *>(smem);
-    unsigned char *kept = smem + (size_t)nm * sizeof(float);
+    float *key = reinterpret_cast<float *>(smem);
+    unsigned char *kept = smem + (size_t)m * sizeof(float);
     __shared__ float ge[32];
     __shared__ unsigned char ekept[32];
 
-    // ---- data selection: Eq. 13 logits (+noise) -> Eq. 14 gate -> Eq. 17 top-c
-    if (has_d) {
-        for (int o = tid; o < nm; o += 256) {
-            float v = a.gred[(size_t)bb * nm + o];
-            if (a.noise_p) v += a.noise_p[(size_t)bb * nm + o];
-            g[o] = v;
-        }
-        __syncthreads();
-        for (int j = tid; j < m; j += 256) {  // softmax over the n experts of patch j
-            float mx = -INFINITY;
-            for (int i = 0; i < n; ++i) mx = fmaxf(mx, g[i * m + j]);
-            float den = 0.f;
-            for (int i = 0; i < n; ++i) den += expf(g[i * m + j] - mx);
-            const float lden = logf(den);
-            for (int i = 0; i < n; ++i) {
-                const float sh = g[i * m + j] - mx;
-                if (a.patch_gate) a.patch_gate[(size_t)bb * nm + i * m + j] = expf(sh) / den;
-                // ranking key: the log of the gate.  Same order as the gate itself, but a gate too
-                // small for fp32 keeps its rank instead of collapsing into a tie at zero.
-                g[i * m + j] = sh - lden;
+    // ---- data selection: Eq. 13 logits (+noise) -> Eq. 14 gate -> Eq. 17 top-c of row i
+    for (int j = tid; j < m; j += SELECT_THREADS) {
+        float kv = 0.f, gate = 1.f;
+        if (has_d) {  // softmax over the n experts of patch j
+            const float *col = a.gred + (size_t)bb * nm + j;
+            const float *nz = a.noise_p ? a.noise_p + (size_t)bb * nm + j : nullptr;
+            float mx = -INFINITY, own = 0.f;
+            for (int ii = 0; ii < n; ++ii) {
+                const float v = col[(size_t)ii * m] + (nz ? nz[(size_t)ii * m] : 0.f);
+                mx = fmaxf(mx, v);
+                if (ii == i) own = v;
             }
+            float den = 0.f;
+            for (int ii = 0; ii < n; ++ii) den += expf(col[(size_t)ii * m] + (nz ? nz[(size_t)ii * m] : 0.f) - mx);
+            gate = expf(own - mx) / den;
+            // ranking key: the log of the gate.  Same order as the gate itself, but a gate too
+            // small for fp32 keeps its rank instead of collapsing into a tie at zero.
+            kv = (own - mx) - logf(den);
         }
-    } else {
-        for (int o = tid; o < nm; o += 256) {
-            g[o] = 0.0f;
-            if (a.patch_gate) a.patch_gate[(size_t)bb * nm + o] = 1.0f;
-        }
+        key[j] = kv;
+        if (a.patch_gate) a.patch_gate[(size_t)bb * nm + (size_t)i * m + j] = gate;
     }
     __syncthreads();
-    for (int o = tid; o < nm; o += 256) {
-        const int i = o / m, j = o - i * m;
-        const float v = g[o];
+    for (int j = tid; j < m; j += SELECT_THREADS) {
+        const float v = key[j];
         int rank = 0;
         for (int jj = 0; jj < m; ++jj) {
-            const float w = g[i * m + jj];
+            const float w = key[jj];
             rank += (w > v || (w == v && jj < j)) ? 1 : 0;
         }
-        kept[o] = rank < c;
+        kept[j] = rank < c;
     }
     __syncthreads();
     if (a.patch_idx) {
-        for (int o = tid; o < nm; o += 256) {
-            if (!kept[o]) continue;
-            const int i = o / m, j = o - i * m;
+        for (int j = tid; j < m; j += SELECT_THREADS) {
+            if (!kept[j]) continue;
             int pos = 0;
-            for (int jj = 0; jj < j; ++jj) pos += kept[i * m + jj];
+            for (int jj = 0; jj < j; ++jj) pos += kept[jj];
             a.patch_idx[((size_t)bb * n + i) * c + pos] = j;
         }
     }
+    if (i != 0) return;  // uniform per workgroup
 
     // ---- expert selection: Eq. 21 logits (+noise) -> softmax -> Eq. 22 top-k
     // The softmax is strictly increasing in the logit within a sample, so the k largest gates are
@@ -225,20 +346,20 @@ __global__ __launch_bounds__(256) void route_select_kernel(RouteArgs a, int has_
         float gv = 1.0f;
         if (has_e) {
             float mx = -INFINITY;
-            for (int i = 0; i < n; ++i) mx = fmaxf(mx, ge[i]);
+            for (int ii = 0; ii < n; ++ii) mx = fmaxf(mx, ge[ii]);
             float den = 0.f;
-            for (int i = 0; i < n; ++i) den += expf(ge[i] - mx);
+            for (int ii = 0; ii < n; ++ii) den += expf(ge[ii] - mx);
             gv = expf(z - mx) / den;
         }
         if (a.expert_gate) a.expert_gate[(size_t)bb * n + tid] = gv;
         int rank = 0;
-        for (int i = 0; i < n; ++i) rank += (ge[i] > z || (ge[i] == z && i < tid)) ? 1 : 0;
+        for (int ii = 0; ii < n; ++ii) rank += (ge[ii] > z || (ge[ii] == z && ii < tid)) ? 1 : 0;
         ekept[tid] = rank < k;
     }
     __syncthreads();
     if (tid < n && ekept[tid] && a.expert_idx) {
         int pos = 0;
-        for (int i = 0; i < tid; ++i) pos += ekept[i];
+        for (int ii = 0; ii < tid; ++ii) pos += ekept[ii];
         a.expert_idx[(size_t)bb * k + pos] = tid;
     }
 }
@@ -246,7 +367,7 @@ __global__ __launch_bounds__(256) void route_select_kernel(RouteArgs a, int has_
 template <typename T, int NMAX>
 static hipError_t launch_partial(const RouteArgs &a, bool has_e, bool has_d, hipStream_t st)
 {
-    dim3 grid(a.nchunks, a.b), block(ROUTE_THREADS);
+    dim3 grid(((a.nchunks + 7) / 8) * 8 * a.b), block(ROUTE_THREADS);
     size_t sh = 0;
     if (has_d) sh += (((size_t)a.n * a.d * sizeof(T) + 15) & ~(size_t)15) + (size_t)a.tc * NMAX * sizeof(float);
     sh += (size_t)ROUTE_WAVES * NMAX * sizeof(float);
@@ -262,9 +383,13 @@ static hipError_t launch_partial(const RouteArgs &a, bool has_e, bool has_d, hip
 template <typename T>
 static hipError_t launch_partial_n(const RouteArgs &a, bool has_e, bool has_d, hipStream_t st)
 {
+    if (a.n <= 2) return launch_partial<T, 2>(a, has_e, has_d, st);
     if (a.n <= 4) return launch_partial<T, 4>(a, has_e, has_d, st);
+    if (a.n <= 6) return launch_partial<T, 6>(a, has_e, has_d, st);
     if (a.n <= 8) return launch_partial<T, 8>(a, has_e, has_d, st);
+    if (a.n <= 12) return launch_partial<T, 12>(a, has_e, has_d, st);
     if (a.n <= 16) return launch_partial<T, 16>(a, has_e, has_d, st);
+    if (a.n <= 24) return launch_partial<T, 24>(a, has_e, has_d, st);
     return launch_partial<T, 32>(a, has_e, has_d, st);
 }
 
@@ -272,17 +397,43 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
 {
     const bool has_e = a.w_e != nullptr, has_d = a.w_b != nullptr;
     hipError_t err = hipSuccess;
-    if (has_e || has_d) {
-        err = bf16 ? launch_partial_n<bf16_t>(a, has_e, has_d, st) : launch_partial_n<float>(a, has_e, has_d, st);
+    if (has_e) {
+        err = bf16 ? launch_partial_n<bf16_t>(a, true, false, st) : launch_partial_n<float>(a, true, false, st);
         if (err != hipSuccess) return err;
-        const long total = (has_e ? (long)a.b * a.n : 0) + (has_d ? (long)a.b * a.n * a.m : 0);
-        hipLaunchKernelGGL(route_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a,
-                           (int)has_e, (int)has_d);
+    }
+    if (has_d) {
+        if (route_data_uses_mfma(a.b, a.l, a.d, a.n, bf16)) {
+            const int waves = data_mfma_waves(a.b, a.l);
+            const size_t sh = data_mfma_lds(a.n, a.d, waves);
+            const dim3 grid(a.nchunks_d, a.b);
+            if (a.n <= 16) {
+                if (waves == 4) hipLaunchKernelGGL((route_data_mfma_kernel<4, 1>), grid, dim3(256), sh, st, a);
+                else if (waves == 2) hipLaunchKernelGGL((route_data_mfma_kernel<2, 1>), grid, dim3(128), sh, st, a);
+                else hipLaunchKernelGGL((route_data_mfma_kernel<1, 1>), grid, dim3(64), sh, st, a);
+            } else {
+                if (waves == 4) hipLaunchKernelGGL((route_data_mfma_kernel<4, 2>), grid, dim3(256), sh, st, a);
+                else if (waves == 2) hipLaunchKernelGGL((route_data_mfma_kernel<2, 2>), grid, dim3(128), sh, st, a);
+                else hipLaunchKernelGGL((route_data_mfma_kernel<1, 2>), grid, dim3(64), sh, st, a);
+            }
+            err = hipGetLastError();
+        } else {
+            RouteArgs ad = a;  // the vector-ALU kernel takes its chunking from tc / nchunks
+            ad.tc = a.tc_d;
+            ad.nchunks = a.nchunks_d;
+            err = bf16 ? launch_partial_n<bf16_t>(ad, false, true, st) : launch_partial_n<float>(ad, false, true, st);
+        }
+        if (err != hipSuccess) return err;
+    }
+    if (has_e || has_d) {
+        const int nvals = (has_e ? a.n : 0) + (has_d ? a.n * a.m : 0);
+        hipLaunchKernelGGL(route_reduce_kernel, dim3((nvals + 15) / 16, a.b), dim3(256), 0, st, a, (int)has_e,
+                           (int)has_d);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    const size_t sh = (size_t)a.n * a.m * (sizeof(float) + 1);
-    hipLaunchKernelGGL(route_select_kernel, dim3(a.b), dim3(256), sh, st, a, (int)has_e, (int)has_d);
+    const size_t sh = (size_t)a.m * (sizeof(float) + 1);
+    hipLaunchKernelGGL(route_select_kernel, dim3(a.n, a.b), dim3(SELECT_THREADS), sh, st, a, (int)has_e,
+                       (int)has_d);
     return hipGetLastError();
 }
 

@@ -16,24 +16,41 @@
 
 namespace uoe {
 
-// one thread per (sample, patch); picks of an expert are ascending so a linear scan suffices
+// Inverse map, one workgroup per sample.  Phase 1: one thread per (active slot s, pick t) writes
+// t into an LDS table slot_of[s][patch].  Phase 2: one thread per patch walks the k slots in
+// order and lists the (s, t) pairs that chose it, so the list order (and with it the summation
+// order of the out-projection) is fixed.
 __global__ __launch_bounds__(256) void smha_inverse_map_kernel(SmhaArgs a)
 {
-    const int g = blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= a.b * a.m) return;
-    const int bb = g / a.m, p = g - bb * a.m;
-    int cnt = 0;
-    for (int s = 0; s < a.k; ++s) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    int16_t *slot_of = reinterpret_cast<int16_t *>(smem);  // [k][m], -1 = not picked
+    const int bb = blockIdx.x, tid = threadIdx.x;
+    const int km = a.k * a.m, kc = a.k * a.c;
+    for (int idx = tid; idx < km; idx += 256) slot_of[idx] = -1;
+    __syncthreads();
+    for (int idx = tid; idx < kc; idx += 256) {
+        const int s = idx / a.c, t = idx - s * a.c;
         const int i = clampi(a.expert_idx[bb * a.k + s], a.n);
-        const int32_t *pid = a.patch_idx + ((size_t)bb * a.n + i) * a.c;
-        for (int t = 0; t < a.c; ++t)
-            if (pid[t] == p) {
-                a.inv_ent[(size_t)g * a.k + cnt] = s * a.c + t;
-                ++cnt;
-                break;
-            }
+        const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + t], a.m);
+        slot_of[s * a.m + p] = (int16_t)t;
     }
-    a.inv_cnt[g] = cnt;
+    __syncthreads();
+    for (int p = tid; p < a.m; p += 256) {
+        const size_t g = (size_t)bb * a.m + p;
+        int cnt = 0;
+        for (int s = 0; s < a.k; ++s) {
+            const int t = slot_of[s * a.m + p];
+            if (t >= 0) a.inv_ent[g * a.k + cnt++] = s * a.c + t;
+        }
+        a.inv_cnt[g] = cnt;
+    }
+}
+
+static hipError_t launch_inverse_map(const SmhaArgs &a, hipStream_t st)
+{
+    const size_t sh = (size_t)a.k * a.m * sizeof(int16_t);  // <= 32 * 1024 * 2 = 64 KiB
+    hipLaunchKernelGGL(smha_inverse_map_kernel, dim3(a.b), dim3(256), sh, st, a);
+    return hipGetLastError();
 }
 
 // Vector-ALU attention: one thread per query row, keys/values staged through LDS in tiles,
@@ -375,8 +392,7 @@ template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStrea
 {
     const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
     hipError_t err;
-    hipLaunchKernelGGL(smha_inverse_map_kernel, dim3((a.b * a.m + 255) / 256), dim3(256), 0, st, a);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
+    if ((err = launch_inverse_map(a, st)) != hipSuccess) return err;
     if ((err = launch_gemm_generic<T>(make_qkv<T>(a), units, l_a, 3 * a.d_h, st)) != hipSuccess) return err;
     if ((err = launch_attention_generic<T>(a, st)) != hipSuccess) return err;
     return launch_gemm_generic<T>(make_outproj<T>(a), a.b * a.m, l_p, a.d, st);
@@ -389,8 +405,7 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     typedef OutProjProblem<bf16_t> OP;
     const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
     hipError_t err;
-    hipLaunchKernelGGL(smha_inverse_map_kernel, dim3((a.b * a.m + 255) / 256), dim3(256), 0, st, a);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
+    if ((err = launch_inverse_map(a, st)) != hipSuccess) return err;
 
     QP qp = make_qkv<bf16_t>(a);
     const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
