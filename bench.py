@@ -41,6 +41,35 @@ def describe(c) -> str:
             f"UoME n{c.n_m} d_e{c.d_e} k{c.k_m}; {c.dtype}")
 
 
+def run_stage(args, cfg, dev, B, torch) -> int:
+    """Loop one stage (its inputs produced once by the stages before it) and print its mean time."""
+    dev.layer_forward()      # fills routing results and u
+    dev.smha_forward()
+    dev.route_m()
+    hidden = torch.empty((cfg.b, cfg.l, cfg.k_m * cfg.d_e), dtype=dev.tdtype, device=dev.device)
+    h = torch.empty((cfg.b, cfg.k_a, cfg.l_a, cfg.d), dtype=dev.tdtype, device=dev.device)
+    B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden)
+    calls = {
+        "route_a": dev.route_a, "smha": dev.smha_forward, "route_m": dev.route_m, "uome": dev.uome_forward,
+        "uome_up": lambda: B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden),
+        "uome_down": lambda: B.uome_down(dev.uome, hidden, dev.a_out, dev.u, dev.m_expert_idx, dev.out),
+        "gather": lambda: B.gather(dev.smha, dev.x, dev.a_expert_idx, dev.a_patch_idx, h),
+    }
+    fn = calls[args.stage]
+    for _ in range(args.warmup):
+        fn()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(args.steps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    print(json.dumps({"stage": args.stage, "workload": cfg.name, "steps": args.steps,
+                      "us_per_call": round(ev0.elapsed_time(ev1) * 1e3 / args.steps, 3)}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +77,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="lm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage", default=None,
+                    choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather"],
+                    help="profiling aid: loop one C-ABI call of the path instead of the whole layer "
+                         "and print its time (no JSON contract line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -69,6 +102,9 @@ def main() -> int:
     fm = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT
     dev = DeviceLayer(inp, fa, fm, device="cuda:0")
     torch.cuda.set_device(0)
+
+    if args.stage:
+        return run_stage(args, cfg, dev, B, torch)
 
     # ---- whole-path throughput
     for _ in range(args.warmup):

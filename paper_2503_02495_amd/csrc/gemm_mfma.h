@@ -31,8 +31,17 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xFFFFu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xFFFF0000u); }
 
+// Workgroup order.  The grid is one-dimensional; hardware deals consecutive workgroup ids
+// round-robin over the 8 XCDs (each with its own L2).  Id L therefore maps to tile
+// (L % 8) * ceil(tiles / 8) + L / 8, with tiles numbered n-tile fastest, then m-tile, then group:
+// every XCD works on one contiguous run of tiles, i.e. a few row-tiles of A times all column
+// tiles, so an A row-tile and the group's weight slices are fetched into one L2 only.
+struct TileGrid {
+    int n_tiles, m_tiles, total, per_xcd;
+};
+
 template <typename P, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p)
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, TileGrid tg)
 {
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int PITCH = BK + 8;                      // LDS row pitch in elements
@@ -50,9 +59,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p)
     __shared__ __align__(16) uint16_t As[2][BM][PITCH];
     __shared__ __align__(16) uint16_t Bs[2][BN][PITCH];
 
-    const int g = blockIdx.z;
+    const int tile = (blockIdx.x & 7) * tg.per_xcd + (blockIdx.x >> 3);
+    if (tile >= tg.total) return;
+    const int g = tile / (tg.n_tiles * tg.m_tiles);
+    const int rem = tile - g * (tg.n_tiles * tg.m_tiles);
+    const int mt = rem / tg.n_tiles, nt = rem - mt * tg.n_tiles;
     const int M = p.rows(g), N = p.ncols(), K = p.kdim(g), KSEG = p.kseg();
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= M) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
@@ -195,8 +208,15 @@ template <typename P, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
 static hipError_t launch_gemm_mfma(const P &p, int groups, int max_rows, int ncols, hipStream_t st)
 {
     if (groups <= 0 || max_rows <= 0 || ncols <= 0) return hipSuccess;
-    dim3 grid((ncols + BN - 1) / BN, (max_rows + BM - 1) / BM, groups);
-    hipLaunchKernelGGL((gemm_mfma_kernel<P, BM, BN, BK, WAVES_M, WAVES_N>), grid, dim3(WAVES_M * WAVES_N * 64), 0, st, p);
+    TileGrid tg;
+    tg.n_tiles = (ncols + BN - 1) / BN;
+    tg.m_tiles = (max_rows + BM - 1) / BM;
+    const long total = (long)tg.n_tiles * tg.m_tiles * groups;
+    if (total > (1L << 28)) return hipErrorInvalidValue;
+    tg.total = (int)total;
+    tg.per_xcd = (tg.total + 7) / 8;
+    hipLaunchKernelGGL((gemm_mfma_kernel<P, BM, BN, BK, WAVES_M, WAVES_N>), dim3(tg.per_xcd * 8), dim3(WAVES_M * WAVES_N * 64), 0,
+                       st, p, tg);
     return hipGetLastError();
 }
 

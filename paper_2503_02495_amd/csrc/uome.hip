@@ -47,8 +47,11 @@ static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
     up.hidden = static_cast<bf16_t *>(a.hidden);
     up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
     const int N = a.k * a.d_e;
-    if (a.l > 64) return launch_gemm_mfma<UomeUpProblem<bf16_t>, 128, 128, 32, 2, 2>(up, a.b, a.l, N, st);
-    return launch_gemm_mfma<UomeUpProblem<bf16_t>, 64, 64, 32, 2, 2>(up, a.b, a.l, N, st);
+    typedef UomeUpProblem<bf16_t> P;
+    const bool k64 = a.d % 64 == 0;  // K segment = d
+    if (a.l > 64) return k64 ? launch_gemm_mfma<P, 128, 128, 64, 2, 2>(up, a.b, a.l, N, st)
+                             : launch_gemm_mfma<P, 128, 128, 32, 2, 2>(up, a.b, a.l, N, st);
+    return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(up, a.b, a.l, N, st);
 }
 
 static hipError_t uome_down_mfma(const UomeArgs &a, hipStream_t st)
@@ -60,8 +63,11 @@ static hipError_t uome_down_mfma(const UomeArgs &a, hipStream_t st)
     dn.expert_idx = a.expert_idx;
     dn.out = static_cast<bf16_t *>(a.out);
     dn.l = a.l; dn.d = a.d; dn.n = a.n; dn.kact = a.k; dn.d_e = a.d_e; dn.flags = a.flags;
-    if (a.l > 64) return launch_gemm_mfma<UomeDownProblem<bf16_t>, 128, 128, 32, 2, 2>(dn, a.b, a.l, a.d, st);
-    return launch_gemm_mfma<UomeDownProblem<bf16_t>, 64, 64, 32, 2, 2>(dn, a.b, a.l, a.d, st);
+    typedef UomeDownProblem<bf16_t> P;
+    const bool k64 = a.d_e % 64 == 0;  // K segment = d_e
+    if (a.l > 64) return k64 ? launch_gemm_mfma<P, 128, 128, 64, 2, 2>(dn, a.b, a.l, a.d, st)
+                             : launch_gemm_mfma<P, 128, 128, 32, 2, 2>(dn, a.b, a.l, a.d, st);
+    return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(dn, a.b, a.l, a.d, st);
 }
 
 hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st)
