@@ -10,12 +10,19 @@
 // K).  Row and column base pointers are resolved through the routing indices once per segment
 // and kept in registers; inside a segment a tile is base + offset.
 //
-// Operand layout.  The MFMA wants, per lane, 8 K-consecutive values of one A row and of one B
-// column.  A is [M,K] with K contiguous: a 16-byte global load is already an operand fragment.
-// B is [K,N] with N contiguous (the paper's [n,d,width] weight layout), so B is transposed on
-// the way into LDS: a thread loads two K-rows of 8 columns and interleaves them in registers into
-// eight dwords (k, k+1) per column, stored K-contiguous.  LDS rows are padded to BK+8 elements,
-// which makes the 16-byte fragment reads of 16 consecutive rows hit 64 distinct banks.
+// Operand layout.  The MFMA wants, per lane, 8 K-consecutive values of one row of its first
+// operand and of one column of its second.  Activations A are [M,K] with K contiguous: a 16-byte
+// LDS read of a row is already a fragment.  Weights B are [K,N] with N contiguous (the paper's
+// [n,d,width] layout); they are copied to LDS as they are, [k][n], and the fragments are taken
+// with the gfx950 transposing LDS read (ds_read_b64_tr_b16): in a group of 16 lanes, lane j points
+// at row k0 + j/4, columns c0 + 4*(j%4)..+3, and lane i receives column c0 + i, rows k0..k0+3.
+// The product is computed transposed, D = B^T A^T (weights as the first MFMA operand), so that an
+// accumulator lane is one output ROW and its registers run along N in groups of four: the
+// epilogue can then hand 8-byte row pieces to LDS and write 16-byte row pieces to memory.
+//
+// LDS pitches.  A rows are padded to BK+8 elements (16-byte fragment reads of 16 consecutive rows
+// hit 64 distinct banks).  B rows are padded so that the pitch in dwords is 16 or 48 mod 64: the
+// four 64-byte row pieces a half-wave touches in one transposing read are then bank-disjoint.
 //
 // Requirements (checked by the callers): kseg() % BK == 0, N segments multiples of 8.  M and N
 // tails are masked.
@@ -26,10 +33,28 @@ namespace uoe {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
 
-// low/high halves of two dwords -> one dword: (lo16 of a) | (lo16 of b) << 16, and the high pair
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xFFFFu) | (b << 16); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xFFFF0000u); }
+// 4 K-consecutive values of one column from a [k][n] LDS tile (see the header comment)
+__device__ __forceinline__ uint2 lds_read_tr4(const uint16_t *p)
+{
+    const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+    return __builtin_bit_cast(uint2, v);
+}
+
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b)
+{
+    return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+}
+
+// smallest pad (in dwords) that makes (cols/2 + pad) % 64 equal to 16 or 48
+__host__ __device__ constexpr int b_pitch_dwords(int cols)
+{
+    int p = cols / 2;
+    while ((p % 64) != 16 && (p % 64) != 48) p += 4;
+    return p;
+}
 
 // Workgroup order.  The grid is one-dimensional; hardware deals consecutive workgroup ids
 // round-robin over the 8 XCDs (each with its own L2).  Id L therefore maps to tile
@@ -44,20 +69,27 @@ template <typename P, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, TileGrid tg)
 {
     constexpr int NT = WAVES_M * WAVES_N * 64;
-    constexpr int PITCH = BK + 8;                      // LDS row pitch in elements
+    constexpr int APITCH = BK + 8;                     // A row pitch in elements
+    constexpr int BPITCH = 2 * b_pitch_dwords(BN);     // B row pitch in elements
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int KC = BK / 8;                         // 16-byte chunks per A row
     constexpr int A_CHUNKS = BM * KC;
     constexpr int A_PER_T = (A_CHUNKS + NT - 1) / NT;
-    constexpr int KPAIRS = BK / 2;
-    constexpr int B_JOBS = KPAIRS * (BN / 8);          // (k pair, 8 columns) jobs in a B tile
-    constexpr int B_PER_T = (B_JOBS + NT - 1) / NT;
+    constexpr int NC = BN / 8;                         // 16-byte chunks per B row
+    constexpr int B_CHUNKS = BK * NC;
+    constexpr int B_PER_T = (B_CHUNKS + NT - 1) / NT;
+    constexpr int SPITCH = WN + 8;                     // epilogue staging pitch in elements
+    constexpr int A_BYTES = 2 * BM * APITCH * 2, B_BYTES = 2 * BK * BPITCH * 2;
+    constexpr int S_BYTES = (NT / 64) * WM * SPITCH * 2;
+    constexpr int LDS_BYTES = (A_BYTES + B_BYTES) > S_BYTES ? (A_BYTES + B_BYTES) : S_BYTES;
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
     static_assert(BK == 32 || BK == 64, "BK is 32 or 64");
+    static_assert(BN % 8 == 0, "BN is a multiple of 8");
 
-    __shared__ __align__(16) uint16_t As[2][BM][PITCH];
-    __shared__ __align__(16) uint16_t Bs[2][BN][PITCH];
+    __shared__ __align__(16) unsigned char lds_raw[LDS_BYTES];
+    uint16_t(*As)[BM][APITCH] = reinterpret_cast<uint16_t(*)[BM][APITCH]>(lds_raw);
+    uint16_t(*Bs)[BK][BPITCH] = reinterpret_cast<uint16_t(*)[BK][BPITCH]>(lds_raw + A_BYTES);
 
     const int tile = (blockIdx.x & 7) * tg.per_xcd + (blockIdx.x >> 3);
     if (tile >= tg.total) return;
@@ -94,16 +126,15 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
         }
 #pragma unroll
         for (int i = 0; i < B_PER_T; ++i) {
-            const int job = tid + i * NT;
-            const int kp = job % KPAIRS, nc = job / KPAIRS;
-            b_base[i] = (job < B_JOBS && n0 + nc * 8 < N)
-                            ? reinterpret_cast<const uint16_t *>(p.b_seg_ptr(g, seg, n0 + nc * 8)) + (long)(2 * kp) * bstride
+            const int c = tid + i * NT;
+            const int row = c / NC, nc = c % NC;
+            b_base[i] = (c < B_CHUNKS && n0 + nc * 8 < N)
+                            ? reinterpret_cast<const uint16_t *>(p.b_seg_ptr(g, seg, n0 + nc * 8)) + (long)row * bstride
                             : nullptr;
         }
     };
 
-    uint4 a_reg[A_PER_T];
-    uint4 b_reg[B_PER_T][2];
+    uint4 a_reg[A_PER_T], b_reg[B_PER_T];
     auto load_global = [&](int off) {  // tile at offset `off` inside the current segment
 #pragma unroll
         for (int i = 0; i < A_PER_T; ++i) {
@@ -113,14 +144,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
         }
 #pragma unroll
         for (int i = 0; i < B_PER_T; ++i) {
-            uint4 r0 = make_uint4(0, 0, 0, 0), r1 = r0;
-            if (b_base[i]) {
-                const uint16_t *src = b_base[i] + (long)off * bstride;
-                r0 = *reinterpret_cast<const uint4 *>(src);
-                r1 = *reinterpret_cast<const uint4 *>(src + bstride);
-            }
-            b_reg[i][0] = r0;
-            b_reg[i][1] = r1;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (b_base[i]) v = *reinterpret_cast<const uint4 *>(b_base[i] + (long)off * bstride);
+            b_reg[i] = v;
         }
     };
     auto store_lds = [&](int buf) {
@@ -131,21 +157,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
         }
 #pragma unroll
         for (int i = 0; i < B_PER_T; ++i) {
-            const int job = tid + i * NT;
-            if (job < B_JOBS) {
-                const int kp = job % KPAIRS, nc = job / KPAIRS;
-                const uint4 r0 = b_reg[i][0], r1 = b_reg[i][1];
-                uint32_t *d0 = reinterpret_cast<uint32_t *>(&Bs[buf][nc * 8][2 * kp]);
-                constexpr int RP = PITCH / 2;  // row pitch in dwords
-                d0[0 * RP] = pack_lo(r0.x, r1.x);
-                d0[1 * RP] = pack_hi(r0.x, r1.x);
-                d0[2 * RP] = pack_lo(r0.y, r1.y);
-                d0[3 * RP] = pack_hi(r0.y, r1.y);
-                d0[4 * RP] = pack_lo(r0.z, r1.z);
-                d0[5 * RP] = pack_hi(r0.z, r1.z);
-                d0[6 * RP] = pack_lo(r0.w, r1.w);
-                d0[7 * RP] = pack_hi(r0.w, r1.w);
-            }
+            const int c = tid + i * NT;
+            if (c < B_CHUNKS) *reinterpret_cast<uint4 *>(&Bs[buf][c / NC][(c % NC) * 8]) = b_reg[i];
         }
     };
 
@@ -165,42 +178,61 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
         store_lds(0);
     }
     __syncthreads();
+    // transposing-read lane roles: group gl = lane/16 -> column half (gl & 1), k half (gl >> 1 == lh)
+    const int tr_row = lh * 8 + ((lane & 15) >> 2);
+    const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < KT) fetch_next();
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t af[TM], bf[TN];
+            bf16x8_t af[TM], wf[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 af[i] = *reinterpret_cast<const bf16x8_t *>(&As[buf][wm0 + i * 32 + lr][ks * 16 + lh * 8]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bf[j] = *reinterpret_cast<const bf16x8_t *>(&Bs[buf][wn0 + j * 32 + lr][ks * 16 + lh * 8]);
+            for (int j = 0; j < TN; ++j) {
+                const uint16_t *src = &Bs[buf][ks * 16 + tr_row][wn0 + j * 32 + tr_col];
+                const uint2 lo = lds_read_tr4(src);
+                const uint2 hi = lds_read_tr4(src + 4 * BPITCH);
+                wf[j] = __builtin_bit_cast(bf16x8_t, make_uint4(lo.x, lo.y, hi.x, hi.y));
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < KT) store_lds(buf ^ 1);
         __syncthreads();
     }
 
-    // epilogue: accumulator register q of lane (lr, lh) is row (q/4)*8 + lh*4 + q%4, column lr
+    // Epilogue.  Accumulator register q of lane (lr, lh) in tile (i, j) is output row
+    // wm0 + i*32 + lr, column wn0 + j*32 + (q/4)*8 + lh*4 + q%4.  Each wave stages its tile in LDS
+    // (the operand buffers are free now: the loop ended on a barrier) and writes 16-byte pieces.
+    uint16_t(*stage)[SPITCH] = reinterpret_cast<uint16_t(*)[SPITCH]>(lds_raw) + (size_t)wave * WM;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn0 + j * 32 + lr;
-        if (col >= N) continue;
-        const auto cc = p.col_ctx(g, col);
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+        for (int qg = 0; qg < 4; ++qg) {
+            const int cl = j * 32 + qg * 8 + lh * 4;  // first of 4 consecutive columns, wave-local
+            const int col = n0 + wn0 + cl;
+            const auto cc = p.col_ctx(g, col < N ? col : 0);
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int row = m0 + wm0 + i * 32 + (q >> 2) * 8 + lh * 4 + (q & 3);
-                if (row < M) p.store(g, row, col, acc[i][j][q], cc);
+            for (int i = 0; i < TM; ++i) {
+                const uint32_t w0 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 0], cc), p.epi(acc[i][j][qg * 4 + 1], cc));
+                const uint32_t w1 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 2], cc), p.epi(acc[i][j][qg * 4 + 3], cc));
+                *reinterpret_cast<uint2 *>(&stage[i * 32 + lr][cl]) = make_uint2(w0, w1);
             }
         }
+    __syncthreads();
+    constexpr int WC = WN / 8;  // 16-byte pieces per staged row
+#pragma unroll
+    for (int t = 0; t < (WM * WC) / 64; ++t) {
+        const int c = lane + t * 64;
+        const int row = c / WC, pc = c % WC;
+        const int grow = m0 + wm0 + row, gcol = n0 + wn0 + pc * 8;
+        if (grow < M && gcol < N) p.store8(g, grow, gcol, *reinterpret_cast<const uint4 *>(&stage[row][pc * 8]));
     }
 }
 

@@ -16,15 +16,28 @@
 
 namespace uoe {
 
+// 8 bf16 (one 16-byte piece of an output row) + 8 bf16 of a residual row, added in fp32
+__device__ __forceinline__ uint4 add8_bf16(uint4 v, uint4 r)
+{
+    const uint32_t a[4] = {v.x, v.y, v.z, v.w}, b[4] = {r.x, r.y, r.z, r.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = __uint_as_float(a[i] << 16) + __uint_as_float(b[i] << 16);
+        const float hi = __uint_as_float(a[i] & 0xFFFF0000u) + __uint_as_float(b[i] & 0xFFFF0000u);
+        o[i] = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // ---------------------------------------------------------------------------------------------
 // SMHA Eq. 28-30 with the index selection of Eq. 18 folded into the A-row lookup.
 // group = active unit (b, slot s); M = l_a; K = d; N = 3*d_h laid out [q | k | v].
 template <typename T> struct QkvProblem {
     const T *x, *wq, *wk, *wv;
     const int32_t *expert_idx, *patch_idx;
-    T *q, *k, *v;  // [units, l_a, d_h]; v is [units, d_h, l_a_pad] when v_transposed
+    T *q, *k, *v;  // [units, l_a, d_h]
     int l, d, n, kact, m, c, l_p, l_a, d_h;
-    int v_transposed, l_a_pad;
     float q_scale;  // folded into q on the way out (1 for the plain layout)
 
     __device__ int rows(int) const { return l_a; }
@@ -66,8 +79,15 @@ template <typename T> struct QkvProblem {
     {
         if (cc.which == 0) q[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val * q_scale);
         else if (cc.which == 1) k[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
-        else if (v_transposed) v[((size_t)g * d_h + cc.col) * l_a_pad + r] = from_f32<T>(val);
         else v[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
+    }
+    // vector epilogue (MFMA engine): per-element math, then one 16-byte piece of a row
+    __device__ float epi(float val, const ColCtx &cc) const { return cc.which == 0 ? val * q_scale : val; }
+    __device__ void store8(int g, int r, int nn, uint4 piece) const
+    {
+        const int which = nn / d_h, col = nn - which * d_h;
+        T *o = which == 0 ? q : (which == 1 ? k : v);
+        *reinterpret_cast<uint4 *>(o + ((size_t)g * l_a + r) * d_h + col) = piece;
     }
 };
 
@@ -118,6 +138,14 @@ template <typename T> struct OutProjProblem {
         if (flags & F_RESIDUAL) val += to_f32(x[at]);
         out[at] = from_f32<T>(val);
     }
+    __device__ float epi(float val, const ColCtx &) const { return val; }
+    __device__ void store8(int g, int r, int nn, uint4 piece) const
+    {
+        const int bb = g / m, p = g - bb * m;
+        const size_t at = ((size_t)bb * l + p * l_p + r) * d + nn;
+        if (flags & F_RESIDUAL) piece = add8_bf16(piece, *reinterpret_cast<const uint4 *>(x + at));
+        *reinterpret_cast<uint4 *>(out + at) = piece;
+    }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -152,6 +180,11 @@ template <typename T> struct UomeUpProblem {
     {
         hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate);
     }
+    __device__ float epi(float val, const ColCtx &gate) const { return silu(val) * gate; }
+    __device__ void store8(int g, int r, int nn, uint4 piece) const
+    {
+        *reinterpret_cast<uint4 *>(hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + nn) = piece;
+    }
 };
 
 // UoME Eq. 39 + Eq. 40: group = sample b; M = l; K = k*d_e (row slices of A^O of the active
@@ -184,6 +217,13 @@ template <typename T> struct UomeDownProblem {
         const size_t at = ((size_t)g * l + r) * d + nn;
         if (flags & F_RESIDUAL) val += to_f32(u[at]);
         out[at] = from_f32<T>(val);
+    }
+    __device__ float epi(float val, const ColCtx &) const { return val; }
+    __device__ void store8(int g, int r, int nn, uint4 piece) const
+    {
+        const size_t at = ((size_t)g * l + r) * d + nn;
+        if (flags & F_RESIDUAL) piece = add8_bf16(piece, *reinterpret_cast<const uint4 *>(u + at));
+        *reinterpret_cast<uint4 *>(out + at) = piece;
     }
 };
 

@@ -139,16 +139,16 @@ template <typename T> static hipError_t launch_attention_generic(const SmhaArgs 
 // in place, already ARE the B operand of the second product O^T = V^T P^T (the k-slots of an MFMA
 // operand may hold any permutation of K as long as both operands agree, so V^T is read with the
 // accumulator's key order: keys 16s+4h..+4 and 16s+8+4h..+4 for k-step s, half-wave h).
-// K tiles [key][d_h] and V^T tiles [d_h][key] are staged through double-buffered LDS; the
-// projection kernel writes v transposed so both tiles are plain 16-byte row copies.
+// K and V tiles [key][d_h] are staged through double-buffered LDS as plain 16-byte row copies;
+// the V^T fragments come out of the [key][d_h] tile through the transposing LDS read.
 template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a, int l_a_pad)
+__global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
 {
-    constexpr int BKV = 64, KP = DH + 8, VP = BKV + 8, NT = NW * 64;
+    constexpr int BKV = 64, KP = DH + 8, VP = 2 * b_pitch_dwords(DH), NT = NW * 64;
     constexpr int K_CHUNKS = BKV * DH / 8, V_CHUNKS = DH * BKV / 8;
     constexpr int K_PER_T = (K_CHUNKS + NT - 1) / NT, V_PER_T = (V_CHUNKS + NT - 1) / NT;
     __shared__ __align__(16) uint16_t Ks[2][BKV][KP];
-    __shared__ __align__(16) uint16_t Vs[2][DH][VP];
+    __shared__ __align__(16) uint16_t Vs[2][BKV][VP];  // [key][d_h], read with the transposing LDS read
 
     const int g = blockIdx.y;
     const int l_p = a.l / a.m, l_a = a.c * l_p;
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a, int
     const int qrow = blockIdx.x * (32 * NW) + wave * 32 + lr;
     const bf16_t *Q = static_cast<const bf16_t *>(a.q) + (size_t)g * l_a * DH;
     const bf16_t *Kg = static_cast<const bf16_t *>(a.kk) + (size_t)g * l_a * DH;
-    const bf16_t *Vt = static_cast<const bf16_t *>(a.v) + (size_t)g * DH * l_a_pad;
+    const bf16_t *Vg = static_cast<const bf16_t *>(a.v) + (size_t)g * l_a * DH;
 
     bf16x8_t qf[DH / 16];
 #pragma unroll
@@ -188,19 +188,10 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a, int
 #pragma unroll
         for (int i = 0; i < V_PER_T; ++i) {
             const int c = tid + i * NT;
-            const int row = c / (BKV / 8), kc = c % (BKV / 8);
-            const int key = key0 + kc * 8;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (c < V_CHUNKS && key < l_a) {
-                v = *reinterpret_cast<const uint4 *>(Vt + (size_t)row * l_a_pad + key);
-                if (key + 8 > l_a) {  // chunk straddles the end: zero the padding columns
-                    uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (key + e >= l_a) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
-                    v = make_uint4(w[0], w[1], w[2], w[3]);
-                }
-            }
+            const int row = c / (DH / 8), kc = c % (DH / 8);
+            uint4 v = make_uint4(0, 0, 0, 0);  // keys past l_a are zero rows: their probability is 0 as well
+            if (c < V_CHUNKS && key0 + row < l_a)
+                v = *reinterpret_cast<const uint4 *>(Vg + (size_t)(key0 + row) * DH + kc * 8);
             vreg[i] = v;
         }
     };
@@ -213,7 +204,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a, int
 #pragma unroll
         for (int i = 0; i < V_PER_T; ++i) {
             const int c = tid + i * NT;
-            if (c < V_CHUNKS) *reinterpret_cast<uint4 *>(&Vs[buf][c / (BKV / 8)][(c % (BKV / 8)) * 8]) = vreg[i];
+            if (c < V_CHUNKS) *reinterpret_cast<uint4 *>(&Vs[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = vreg[i];
         }
     };
 
@@ -290,8 +281,10 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a, int
                 bf16x8_t, make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)));
 #pragma unroll
             for (int td = 0; td < DH / 32; ++td) {
-                const uint2 v0 = *reinterpret_cast<const uint2 *>(&Vs[buf][td * 32 + lr][s4 * 16 + lh * 4]);
-                const uint2 v1 = *reinterpret_cast<const uint2 *>(&Vs[buf][td * 32 + lr][s4 * 16 + 8 + lh * 4]);
+                // V^T fragment for head-dim column td*32 + lr: keys 16*s4 + 4*lh + 0..3, then + 8
+                const uint16_t *vsrc = &Vs[buf][s4 * 16 + lh * 4 + ((lane & 15) >> 2)][td * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4];
+                const uint2 v0 = lds_read_tr4(vsrc);
+                const uint2 v1 = lds_read_tr4(vsrc + 8 * VP);
                 const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, make_uint4(v0.x, v0.y, v1.x, v1.y));
                 oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_hi, oacc[td], 0, 0, 0);
                 oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, oacc[td], 0, 0, 0);
@@ -332,25 +325,25 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a, int
         }
 }
 
-template <int DH> static hipError_t launch_attention_mfma_dh(const SmhaArgs &a, int l_a_pad, hipStream_t st)
+template <int DH> static hipError_t launch_attention_mfma_dh(const SmhaArgs &a, hipStream_t st)
 {
     const int l_a = a.c * (a.l / a.m), units = a.b * a.k;
     // more waves per workgroup share K/V tiles; fewer give more workgroups: keep >= 512 if possible
     if ((long)((l_a + 127) / 128) * units >= 512) {
-        hipLaunchKernelGGL((attention_mfma_kernel<DH, 4>), dim3((l_a + 127) / 128, units), dim3(256), 0, st, a, l_a_pad);
+        hipLaunchKernelGGL((attention_mfma_kernel<DH, 4>), dim3((l_a + 127) / 128, units), dim3(256), 0, st, a);
     } else if ((long)((l_a + 63) / 64) * units >= 512) {
-        hipLaunchKernelGGL((attention_mfma_kernel<DH, 2>), dim3((l_a + 63) / 64, units), dim3(128), 0, st, a, l_a_pad);
+        hipLaunchKernelGGL((attention_mfma_kernel<DH, 2>), dim3((l_a + 63) / 64, units), dim3(128), 0, st, a);
     } else {
-        hipLaunchKernelGGL((attention_mfma_kernel<DH, 1>), dim3((l_a + 31) / 32, units), dim3(64), 0, st, a, l_a_pad);
+        hipLaunchKernelGGL((attention_mfma_kernel<DH, 1>), dim3((l_a + 31) / 32, units), dim3(64), 0, st, a);
     }
     return hipGetLastError();
 }
 
-static hipError_t launch_attention_mfma(const SmhaArgs &a, int l_a_pad, hipStream_t st)
+static hipError_t launch_attention_mfma(const SmhaArgs &a, hipStream_t st)
 {
-    if (a.d_h == 32) return launch_attention_mfma_dh<32>(a, l_a_pad, st);
-    if (a.d_h == 64) return launch_attention_mfma_dh<64>(a, l_a_pad, st);
-    return launch_attention_mfma_dh<128>(a, l_a_pad, st);
+    if (a.d_h == 32) return launch_attention_mfma_dh<32>(a, st);
+    if (a.d_h == 64) return launch_attention_mfma_dh<64>(a, st);
+    return launch_attention_mfma_dh<128>(a, st);
 }
 
 template <typename T> static QkvProblem<T> make_qkv(const SmhaArgs &a)
@@ -367,7 +360,7 @@ template <typename T> static QkvProblem<T> make_qkv(const SmhaArgs &a)
     qp.v = static_cast<T *>(a.v);
     qp.l = a.l; qp.d = a.d; qp.n = a.n; qp.kact = a.k; qp.m = a.m; qp.c = a.c;
     qp.l_p = a.l / a.m; qp.l_a = a.c * qp.l_p; qp.d_h = a.d_h;
-    qp.v_transposed = 0; qp.l_a_pad = qp.l_a; qp.q_scale = 1.0f;
+    qp.q_scale = 1.0f;
     return qp;
 }
 
@@ -409,19 +402,14 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
 
     QP qp = make_qkv<bf16_t>(a);
     const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
-    const int l_a_pad = (l_a + 7) & ~7;
-    if (mfma_attn) {  // layouts the MFMA attention kernel reads: v transposed, q pre-scaled (base-2 softmax)
-        qp.v_transposed = 1;
-        qp.l_a_pad = l_a_pad;
-        qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);
-    }
+    if (mfma_attn) qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);  // base-2 softmax in the MFMA kernel
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
     if (a.d_h == 32) err = launch_gemm_mfma<QP, 128, 96, 32, 4, 1>(qp, units, l_a, 96, st);
     else if (a.d_h == 64) err = launch_gemm_mfma<QP, 128, 192, 32, 4, 1>(qp, units, l_a, 192, st);
     else err = launch_gemm_mfma<QP, 128, 128, 32, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
     if (err != hipSuccess) return err;
 
-    err = mfma_attn ? launch_attention_mfma(a, l_a_pad, st) : launch_attention_generic<bf16_t>(a, st);
+    err = mfma_attn ? launch_attention_mfma(a, st) : launch_attention_generic<bf16_t>(a, st);
     if (err != hipSuccess) return err;
 
     OP op = make_outproj<bf16_t>(a);

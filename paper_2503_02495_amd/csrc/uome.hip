@@ -37,6 +37,12 @@ template <typename T> static hipError_t uome_down_generic(const UomeArgs &a, hip
 // MFMA path: bf16 storage, and every K segment (d for GEMM-1, d_e for GEMM-2) a multiple of 32
 static bool uome_mfma_ok(const UomeArgs &a, bool bf16) { return bf16 && a.d % 32 == 0 && a.d_e % 32 == 0; }
 
+// 256x128 tiles (8 waves) pay off once they still fill the chip a few times over
+static bool uome_big(int b, int l, int ncols)
+{
+    return l >= 512 && (long)b * ((l + 255) / 256) * ((ncols + 127) / 128) >= 1024;
+}
+
 static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
 {
     UomeUpProblem<bf16_t> up;
@@ -49,6 +55,7 @@ static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
     const int N = a.k * a.d_e;
     typedef UomeUpProblem<bf16_t> P;
     const bool k64 = a.d % 64 == 0;  // K segment = d
+    if (uome_big(a.b, a.l, N)) return launch_gemm_mfma<P, 256, 128, 32, 4, 2>(up, a.b, a.l, N, st);
     if (a.l > 64) return k64 ? launch_gemm_mfma<P, 128, 128, 64, 2, 2>(up, a.b, a.l, N, st)
                              : launch_gemm_mfma<P, 128, 128, 32, 2, 2>(up, a.b, a.l, N, st);
     return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(up, a.b, a.l, N, st);
@@ -65,6 +72,7 @@ static hipError_t uome_down_mfma(const UomeArgs &a, hipStream_t st)
     dn.l = a.l; dn.d = a.d; dn.n = a.n; dn.kact = a.k; dn.d_e = a.d_e; dn.flags = a.flags;
     typedef UomeDownProblem<bf16_t> P;
     const bool k64 = a.d_e % 64 == 0;  // K segment = d_e
+    if (uome_big(a.b, a.l, a.d)) return launch_gemm_mfma<P, 256, 128, 32, 4, 2>(dn, a.b, a.l, a.d, st);
     if (a.l > 64) return k64 ? launch_gemm_mfma<P, 128, 128, 64, 2, 2>(dn, a.b, a.l, a.d, st)
                              : launch_gemm_mfma<P, 128, 128, 32, 2, 2>(dn, a.b, a.l, a.d, st);
     return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(dn, a.b, a.l, a.d, st);
