@@ -55,6 +55,10 @@ def run_stage(args, cfg, dev, B, torch) -> int:
         "uome_down": lambda: B.uome_down(dev.uome, hidden, dev.a_out, dev.u, dev.m_expert_idx, dev.out),
         "gather": lambda: B.gather(dev.smha, dev.x, dev.a_expert_idx, dev.a_patch_idx, h),
     }
+    if args.stage == "copy":   # a plain copy of known size (1 GiB read + 1 GiB written): counter calibration
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).normal_()
+        dst = torch.empty_like(src)
+        calls["copy"] = lambda: dst.copy_(src)
     fn = calls[args.stage]
     for _ in range(args.warmup):
         fn()
@@ -77,8 +81,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="lm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
-                    choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather"],
+                    choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather", "copy"],
                     help="profiling aid: loop one C-ABI call of the path instead of the whole layer "
                          "and print its time (no JSON contract line)")
     args = ap.parse_args()
@@ -106,16 +112,33 @@ def main() -> int:
     if args.stage:
         return run_stage(args, cfg, dev, B, torch)
 
-    # ---- whole-path throughput
-    for _ in range(args.warmup):
-        dev.layer_forward()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        dev.layer_forward()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # ---- whole-path throughput.  The layer call only enqueues kernels (no allocation, no memset, no
+    # synchronisation), so it can also be captured into a HIP graph (--graph: a step is one replay).
+    # Either way every kernel of the path runs in every step.
+    def timed(step):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    eager_ms = timed(dev.layer_forward)
+    launch = "eager"
+    ms_per_step = eager_ms
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            dev.layer_forward()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            dev.layer_forward()
+        ms_per_step = timed(graph.replay)
+        launch = "hip graph replay"
     tokens_per_s = cfg.tokens / (ms_per_step * 1e-3)
     fl = layer_flops(cfg)
 
@@ -179,7 +202,8 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
         "config": {"workload": describe(cfg), "flags": "residual+expert gate+patch gate",
-                   "seed": cfg.seed},
+                   "seed": cfg.seed, "launch": launch},
+        "ms_per_step_eager": round(eager_ms, 5),
         "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 3),
         "flops_per_step": fl["total"],
         "roofline": roofline,

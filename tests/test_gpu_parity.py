@@ -322,3 +322,32 @@ def test_layer_is_deterministic_and_reusable():
     dev.layer_forward()
     torch.cuda.synchronize()
     assert torch.equal(first.view(torch.int16), dev.out.view(torch.int16))
+
+
+def test_layer_under_hip_graph_replay():
+    """The layer call is capturable (kernel launches only); every replay reproduces the eager result,
+    with eager work and synchronisations between replays."""
+    cfg = get_cfg("lm")
+    inp = synth.make_inputs(cfg)
+    dev = DeviceLayer(inp, R | GE | GP, R | GE)
+    dev.layer_forward()
+    torch.cuda.synchronize()
+    want = dev.out.clone()
+    want_idx = dev.a_patch_idx.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dev.layer_forward()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dev.layer_forward()
+    for rep in range(4):
+        dev.out.zero_()                       # eager work between replays
+        dev.a_patch_idx.fill_(-1)
+        dev.ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dev.out.view(torch.int16), want.view(torch.int16)), f"replay {rep}"
+        assert torch.equal(dev.a_patch_idx, want_idx), f"replay {rep}"
