@@ -404,9 +404,19 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
     if (mfma_attn) qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);  // base-2 softmax in the MFMA kernel
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
-    if (a.d_h == 32) err = launch_gemm_mfma<QP, 128, 96, 32, 4, 1>(qp, units, l_a, 96, st);
-    else if (a.d_h == 64) err = launch_gemm_mfma<QP, 128, 192, 32, 4, 1>(qp, units, l_a, 192, st);
-    else err = launch_gemm_mfma<QP, 128, 128, 32, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
+    // 128-row tiles for long units (measured faster from l_a = 512 up), 32-row tiles for short ones
+    const bool tall = l_a >= 256 && (long)units * ((l_a + 127) / 128) >= 128, k64 = a.d % 64 == 0;
+    if (a.d_h == 32) {
+        if (tall) err = launch_gemm_mfma<QP, 128, 96, 32, 4, 1>(qp, units, l_a, 96, st);
+        else if (k64) err = launch_gemm_mfma<QP, 32, 96, 64, 1, 1>(qp, units, l_a, 96, st);
+        else err = launch_gemm_mfma<QP, 32, 96, 32, 1, 1>(qp, units, l_a, 96, st);
+    } else if (a.d_h == 64) {
+        if (tall) err = launch_gemm_mfma<QP, 128, 192, 32, 4, 1>(qp, units, l_a, 192, st);
+        else if (k64) err = launch_gemm_mfma<QP, 32, 192, 64, 1, 2>(qp, units, l_a, 192, st);
+        else err = launch_gemm_mfma<QP, 32, 192, 32, 1, 2>(qp, units, l_a, 192, st);
+    } else {
+        err = launch_gemm_mfma<QP, 128, 128, 32, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
+    }
     if (err != hipSuccess) return err;
 
     err = mfma_attn ? launch_attention_mfma(a, st) : launch_attention_generic<bf16_t>(a, st);
