@@ -37,7 +37,7 @@ int check_desc(const uoe_block_desc *d, bool smha)
 
 struct RouteWs {
     int tc, nchunks, tc_d, nchunks_d;
-    size_t zpart, gpart, zred, gred, total;
+    size_t zpart, gpart, gred, total;
 };
 RouteWs route_ws(int b, int l, int d, int n, int m, bool bf16)
 {
@@ -49,7 +49,6 @@ RouteWs route_ws(int b, int l, int d, int n, int m, bool bf16)
     size_t off = 0;
     w.zpart = off; off += up((size_t)w.nchunks * b * n * sizeof(float));
     w.gpart = off; off += up((size_t)w.nchunks_d * b * n * m * sizeof(float));
-    w.zred = off;  off += up((size_t)b * n * sizeof(float));
     w.gred = off;  off += up((size_t)b * n * m * sizeof(float));
     w.total = off;
     return w;
@@ -121,7 +120,6 @@ int do_route(const uoe_block_desc *blk, int m, int c, const void *x, const void 
     a.tc = w.tc; a.nchunks = w.nchunks; a.tc_d = w.tc_d; a.nchunks_d = w.nchunks_d;
     a.zpart = reinterpret_cast<float *>(at(ws, w.zpart));
     a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
-    a.zred = reinterpret_cast<float *>(at(ws, w.zred));
     a.gred = reinterpret_cast<float *>(at(ws, w.gred));
     a.expert_idx = expert_idx; a.patch_idx = patch_idx;
     a.expert_gate = expert_gate; a.patch_gate = patch_gate;

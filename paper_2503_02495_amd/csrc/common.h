@@ -60,6 +60,12 @@ __device__ __forceinline__ float wave_sum(float v)
 __device__ __forceinline__ int clampi(int v, int count) { return min(max(v, 0), count - 1); }
 
 __device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
+// SiLU with the hardware exp2 and reciprocal (about 1 ulp each): for epilogues that round the
+// result to bf16 anyway
+__device__ __forceinline__ float silu_fast(float z)
+{
+    return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
 
 // ---------------------------------------------------------------- flags (mirror of the ABI values)
 constexpr uint32_t F_RESIDUAL = 1u, F_GATE_EXPERT = 2u, F_GATE_PATCH = 4u;
@@ -72,7 +78,7 @@ struct RouteArgs {
     int tc, nchunks;                          // expert router: tokens per chunk, chunks per sample
     int tc_d, nchunks_d;                      // data router: the same
     float *zpart, *gpart;                     // [nchunks, b, n], [nchunks_d, b, n*m]
-    float *zred, *gred;                       // [b, n], [b, n*m]
+    float *gred;                              // [b, n*m]
     int32_t *expert_idx, *patch_idx;          // outputs (any may be NULL)
     float *expert_gate, *patch_gate;
 };

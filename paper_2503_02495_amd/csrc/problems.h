@@ -180,7 +180,7 @@ template <typename T> struct UomeUpProblem {
     {
         hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate);
     }
-    __device__ float epi(float val, const ColCtx &gate) const { return silu(val) * gate; }
+    __device__ float epi(float val, const ColCtx &gate) const { return silu_fast(val) * gate; }
     __device__ void store8(int g, int r, int nn, uint4 piece) const
     {
         *reinterpret_cast<uint4 *>(hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + nn) = piece;

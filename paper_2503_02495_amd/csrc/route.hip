@@ -11,7 +11,7 @@
 //                       LDS), then the chunk's rows of W_A fold t1 into a partial [n,m] logit tile.
 //   route_partial<D>  : the same data router on the vector ALU (fp32 storage, or W_B too large
 //                       for LDS next to the MFMA staging).
-//   route_reduce      : sums the per-chunk partials in a fixed order (deterministic).
+//   route_reduce      : sums the data router's per-chunk partials in a fixed order (deterministic).
 //   route_select      : per (expert row, sample): + noise, softmax over experts (Eq. 14 / 21), then
 //                       top-c per expert and top-k per sample by rank counting: rank(j) = #{j' :
 //                       g_j' > g_j or (g_j' == g_j and j' < j)}; keep rank < c.  The output slot of
@@ -241,38 +241,29 @@ __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a
     }
 }
 
-// Sums the per-chunk partials in a fixed order (deterministic).  A block owns 16 reduced values of
-// one sample; thread (value, chunk group) adds every 16th chunk, then the 16 group sums are added
-// in group order.
-__global__ __launch_bounds__(256) void route_reduce_kernel(RouteArgs a, int has_e, int has_d)
+// Sums the data router's per-chunk partials in a fixed order (deterministic).  A block owns 16
+// reduced values of one sample; thread (value, chunk group) adds every 16th chunk, then the 16
+// group sums are added in group order.  (The expert router's n values per sample are summed by
+// route_select itself.)
+__global__ __launch_bounds__(256) void route_reduce_kernel(RouteArgs a)
 {
     __shared__ float part[16][17];
     const int bb = blockIdx.y, vi = threadIdx.x & 15, cg = threadIdx.x >> 4;
-    const int nz = has_e ? a.n : 0, nm = a.n * a.m;
-    const int nvals = nz + (has_d ? nm : 0);
+    const int nm = a.n * a.m;
     const int v = blockIdx.x * 16 + vi;
     float s = 0.f;
-    if (v < nvals) {
-        const float *src;
-        size_t stride;
-        if (v < nz) {
-            src = a.zpart + (size_t)bb * a.n + v;
-            stride = (size_t)a.b * a.n;
-        } else {
-            src = a.gpart + (size_t)bb * nm + (v - nz);
-            stride = (size_t)a.b * nm;
-        }
-        const int nch = v < nz ? a.nchunks : a.nchunks_d;
-        for (int ch = cg; ch < nch; ch += 16) s += src[(size_t)ch * stride];
+    if (v < nm) {
+        const float *src = a.gpart + (size_t)bb * nm + v;
+        const size_t stride = (size_t)a.b * nm;
+        for (int ch = cg; ch < a.nchunks_d; ch += 16) s += src[(size_t)ch * stride];
     }
     part[cg][vi] = s;
     __syncthreads();
-    if (threadIdx.x < 16 && v < nvals) {
+    if (threadIdx.x < 16 && v < nm) {
         float t = 0.f;
 #pragma unroll
         for (int q = 0; q < 16; ++q) t += part[q][vi];
-        if (v < nz) a.zred[(size_t)bb * a.n + v] = t;
-        else a.gred[(size_t)bb * nm + (v - nz)] = t;
+        a.gred[(size_t)bb * nm + v] = t;
     }
 }
 
@@ -287,8 +278,9 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     float *key = reinterpret_cast<float *>(smem);
     unsigned char *kept = smem + (size_t)m * sizeof(float);
     __shared__ float ge[32];
+    __shared__ float zpart_sum[4][32];
     __shared__ unsigned char ekept[32];
-    const float *gsrc = a.gred + (size_t)bb * nm, *zsrc = a.zred + (size_t)bb * n;
+    const float *gsrc = a.gred + (size_t)bb * nm;
 
     // ---- data selection: Eq. 13 logits (+noise) -> Eq. 14 gate -> Eq. 17 top-c of row i
     for (int j = tid; j < m; j += SELECT_THREADS) {
@@ -336,10 +328,18 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     // ---- expert selection: Eq. 21 logits (+noise) -> softmax -> Eq. 22 top-k
     // The softmax is strictly increasing in the logit within a sample, so the k largest gates are
     // the k largest logits: rank on the logits, which cannot underflow.
+    if (has_e) {  // sum the expert router's per-chunk partials: 4 chunk groups x up to 32 experts
+        const int vi = tid & 31, cg = tid >> 5;
+        float s = 0.f;
+        if (vi < n)
+            for (int ch = cg; ch < a.nchunks; ch += 4) s += a.zpart[((size_t)ch * a.b + bb) * n + vi];
+        zpart_sum[cg][vi] = s;
+    }
+    __syncthreads();
     float z = 0.f;
     if (tid < n) {
         if (has_e) {
-            z = zsrc[tid];
+            z = (zpart_sum[0][tid] + zpart_sum[1][tid]) + (zpart_sum[2][tid] + zpart_sum[3][tid]);
             if (a.noise_e) z += a.noise_e[(size_t)bb * n + tid];
         }
         ge[tid] = z;
@@ -427,10 +427,8 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
         }
         if (err != hipSuccess) return err;
     }
-    if (has_e || has_d) {
-        const int nvals = (has_e ? a.n : 0) + (has_d ? a.n * a.m : 0);
-        hipLaunchKernelGGL(route_reduce_kernel, dim3((nvals + 15) / 16, a.b), dim3(256), 0, st, a, (int)has_e,
-                           (int)has_d);
+    if (has_d) {
+        hipLaunchKernelGGL(route_reduce_kernel, dim3((a.n * a.m + 15) / 16, a.b), dim3(256), 0, st, a);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }

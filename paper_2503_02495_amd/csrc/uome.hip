@@ -40,7 +40,7 @@ static bool uome_mfma_ok(const UomeArgs &a, bool bf16) { return bf16 && a.d % 32
 // 256x128 tiles (8 waves) pay off once they still fill the chip a few times over
 static bool uome_big(int b, int l, int ncols)
 {
-    return l >= 512 && (long)b * ((l + 255) / 256) * ((ncols + 127) / 128) >= 1024;
+    return l > 128 && (long)b * ((l + 255) / 256) * ((ncols + 127) / 128) >= 512;
 }
 
 static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
