@@ -232,12 +232,33 @@ __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a
 
     const uint16_t *w_a = static_cast<const uint16_t *>(a.w_a);
     const int nm = n * m;
-    for (int o = tid; o < nm; o += NTHREADS) {
-        const int i = o / m, j = o - i * m;
-        float s = 0.f;
-        for (int tl = 0; tl < tcur; ++tl)
-            s = fmaf(t1s[tl * np + i], __uint_as_float((uint32_t)w_a[(size_t)(t0 + tl) * m + j] << 16), s);
-        a.gpart[((size_t)chunk * a.b + bb) * nm + o] = s;
+    float *gout = a.gpart + ((size_t)chunk * a.b + bb) * nm;
+    if ((m & 7) == 0) {
+        // one thread per (expert i, 8 consecutive patches): 16-byte loads of the W_A rows
+        const int m8 = m >> 3;
+        for (int o = tid; o < n * m8; o += NTHREADS) {
+            const int i = o / m8, j0 = (o - i * m8) * 8;
+            float s[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) s[q] = 0.f;
+            for (int tl = 0; tl < tcur; ++tl) {
+                float wv[8];
+                load8(reinterpret_cast<const bf16_t *>(w_a) + (size_t)(t0 + tl) * m + j0, wv);
+                const float t1 = t1s[tl * np + i];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) s[q] = fmaf(t1, wv[q], s[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) gout[i * m + j0 + q] = s[q];
+        }
+    } else {
+        for (int o = tid; o < nm; o += NTHREADS) {
+            const int i = o / m, j = o - i * m;
+            float s = 0.f;
+            for (int tl = 0; tl < tcur; ++tl)
+                s = fmaf(t1s[tl * np + i], __uint_as_float((uint32_t)w_a[(size_t)(t0 + tl) * m + j] << 16), s);
+            gout[o] = s;
+        }
     }
 }
 

@@ -140,8 +140,6 @@ def test_smha_matches_definition_on_random_routing(seed, l_p):
                 assert not np.array_equal(got[bb, rows], x[bb, rows])
     # inactive experts' weights and patch picks are never read
     wq2 = wq.copy()
-    for bb in range(b):
-        pass
     inactive = [i for i in range(n) if all(i not in eid[bb] for bb in range(b))]
     for i in inactive:
         wq2[i] += 100.0
@@ -280,3 +278,22 @@ def test_layer_with_full_selection_is_dense_transformer_block():
     u = dense_mha(x, *(w.astype(np.float64) for w in (inp.wq, inp.wk, inp.wv, inp.wo)))
     want = dense_mlp(u, inp.a_in.astype(np.float64), inp.a_out.astype(np.float64))
     np.testing.assert_allclose(res.out, want, rtol=1e-10, atol=1e-12)
+
+
+def test_oracle_reproduces_golden_fixture():
+    """Regression pin: tests/golden/tiny_layer.json was written by tests/golden/make_golden.py from
+    the oracle alone (the paper prints no worked example)."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_layer.json")
+    fx = json.load(open(path))
+    cfg = synth.CONFIGS["tiny"]
+    inp = synth.make_inputs(cfg)
+    res = oracle.layer_forward(inp, R | GE | GP, R | GE)
+    assert res.routing_a.expert_id.tolist() == fx["smha_expert_id"]
+    assert res.routing_a.patch_id.tolist() == fx["smha_patch_id"]
+    assert res.routing_m.expert_id.tolist() == fx["uome_expert_id"]
+    np.testing.assert_allclose(res.routing_a.expert_gate[0], fx["smha_expert_gate_sample0"], rtol=1e-10)
+    for pos, val in fx["out_at"]:
+        np.testing.assert_allclose(res.out[tuple(pos)], val, rtol=1e-10)
+    np.testing.assert_allclose(np.abs(res.out - inp.x).sum(), fx["out_minus_x_abs_sum"], rtol=1e-8)
