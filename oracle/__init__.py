@@ -32,6 +32,7 @@ _LIB = os.path.join(_HERE, "liboracle_uoe.so")
 RESIDUAL = 1
 GATE_EXPERT = 2
 GATE_PATCH = 4
+CAUSAL = 8
 
 NEAR_TIE_REL = 1e-5  # a selection whose kept/dropped margin is below this is a near-tie
 
@@ -63,7 +64,7 @@ def _L():
         lib.uoe_oracle_expert_router.argtypes = [I, ctypes.c_long, I, P, P, P, P, P]
         lib.uoe_oracle_top_k.argtypes = [I, I, I, P, P, P]
         lib.uoe_oracle_expert_lists.argtypes = [I, I, I, P, P, P]
-        lib.uoe_oracle_smha.argtypes = [I] * 8 + [ctypes.c_uint] + [P] * 10
+        lib.uoe_oracle_smha.argtypes = [I] * 8 + [ctypes.c_uint] + [P] * 9 + [I, P, P]
         lib.uoe_oracle_uome.argtypes = [I] * 6 + [ctypes.c_uint] + [P] * 6
         for f in ("data_router_logits", "patch_gate", "top_c", "expert_router", "top_k",
                   "expert_lists", "smha", "uome", "set_threads"):
@@ -202,8 +203,11 @@ def route(x, n: int, k: int, m: int, c: int, w_expert=None, w_b=None, w_a=None,
 
 # --------------------------------------------------------------------------- blocks
 def smha(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: int,
-         flags: int = RESIDUAL) -> np.ndarray:
-    """Eq. 27-36 on given routing results; returns u [b,l,d]."""
+         flags: int = RESIDUAL, rope_dim: int = 0, pad_mask=None) -> np.ndarray:
+    """Eq. 27-36 on given routing results; returns u [b,l,d].
+
+    Optional: CAUSAL in flags (shared mask of Sec. III-C.3), rope_dim (Eq. 32, last rope_dim dims of a
+    head, compacted positions), pad_mask [b,l] (1 = token, 0 = padding; Eq. 41)."""
     x, wq, wk, wv, wo = _f64(x), _f64(wq), _f64(wk), _f64(wv), _f64(wo)
     b, l, d = x.shape
     n, _, d_h = wq.shape
@@ -213,9 +217,14 @@ def smha(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: in
     assert l % m == 0 and patch_id.shape == (b, n, c)
     g_e, g_d = _f64(expert_gate), _f64(patch_gate_)
     assert g_e.shape == (b, n) and g_d.shape == (b, n, m)
+    assert rope_dim % 2 == 0 and 0 <= rope_dim <= d_h
+    pm = None
+    if pad_mask is not None:
+        pm = np.ascontiguousarray(pad_mask, dtype=np.uint8)
+        assert pm.shape == (b, l)
     out = np.empty((b, l, d), np.float64)
     _L().uoe_oracle_smha(b, l, d, n, k, m, c, d_h, flags, _p(x), _p(wq), _p(wk), _p(wv), _p(wo),
-                         _p(expert_id), _p(g_e), _p(patch_id), _p(g_d), _p(out))
+                         _p(expert_id), _p(g_e), _p(patch_id), _p(g_d), int(rope_dim), _p(pm), _p(out))
     return out
 
 
@@ -244,7 +253,7 @@ class LayerResult:
 
 
 def layer_forward(inp, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
-                  flags_m: int = RESIDUAL | GATE_EXPERT) -> LayerResult:
+                  flags_m: int = RESIDUAL | GATE_EXPERT, rope_dim: int = 0) -> LayerResult:
     """One UoE layer (Sec. III-C): out = UoME(SMHA(x)); `inp` is a LayerInputs-like object.
 
     The UoME router reads u, the finished SMHA output.
@@ -253,7 +262,7 @@ def layer_forward(inp, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
     ra = route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
                inp.noise_a_expert, inp.noise_a_patch)
     u = smha(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ra.expert_gate, ra.patch_id,
-             ra.patch_gate, cfg.m, flags_a)
+             ra.patch_gate, cfg.m, flags_a, rope_dim)
     rm = route(u, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
     out = uome(u, inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, flags_m)
     return LayerResult(ra, u, rm, out)

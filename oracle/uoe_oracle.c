@@ -28,6 +28,16 @@
  *     the first layer), as the lossless split of Sec. III-A requires.
  *   - Eq. 20/26/36/40 add unweighted expert outputs; gate weighting is an
  *     option (flags below) and uses the softmax gate values un-renormalised.
+ *   - Eq. 32 (Eq. 31 is a misprint of the perplexity formula): q' = [q^c, RoPE(q^r)],
+ *     k' = [k^c, RoPE(k^r)]; the rotary part is the LAST rope_dim dims of a head, rotated in
+ *     adjacent pairs (2i, 2i+1) by the angle p * 10000^(-2i/rope_dim), where p is the token's
+ *     position in the COMPACTED sequence of its expert (0..l_a-1): Sec. III-B says selection keeps
+ *     relative order while changing absolute position, and the shared mask of Fig. 4 treats the
+ *     compacted sequence the same way.
+ *   - Sec. III-C.3: the causal mask is the leading l_a x l_a lower-triangular block for every
+ *     expert (key position <= query position in the compacted sequence); the padding mask is
+ *     gathered with the same indices (Eq. 41) and removes padded KEYS from the softmax.  A query
+ *     with no admissible key contributes nothing.
  *   - Both selections in one block (Sec. III-B, last paragraph): both routers
  *     read the block input; only patches selected by an ACTIVE expert are
  *     processed; the weight is the product of the two gates.
@@ -44,6 +54,7 @@
 #define ORACLE_RESIDUAL 1u     /* out = in + sum(...)   (Eq. 20/26); off: out = sum(...) */
 #define ORACLE_GATE_EXPERT 2u  /* weight contributions by the Eq. 21 gate of the expert   */
 #define ORACLE_GATE_PATCH 4u   /* weight contributions by the Eq. 14 gate of the patch    */
+#define ORACLE_CAUSAL 8u       /* shared causal mask of Sec. III-C.3 (Fig. 4)             */
 
 void uoe_oracle_set_threads(int t)
 {
@@ -201,14 +212,31 @@ void uoe_oracle_expert_lists(int b, int n, int k, const int32_t *id, int32_t *co
 }
 
 /* ------------------------------------------------------------------------- */
-/* Selective Multi-Head Attention, Eq. 27-36 (RoPE of Eq. 31-32 and the masks
- * of Eq. 41 are not part of this build).
+/* Eq. 32: rotate the last rope_dim dims of every row of X [rows, d_h]; row r is at position r. */
+static void rope_rows(double *X, int rows, int d_h, int rope_dim)
+{
+    const int first = d_h - rope_dim;
+    for (int r = 0; r < rows; ++r)
+        for (int i = 0; i < rope_dim / 2; ++i) {
+            const double theta = pow(10000.0, -2.0 * i / rope_dim);
+            const double cs = cos(r * theta), sn = sin(r * theta);
+            double *p = X + (long)r * d_h + first + 2 * i;
+            const double a = p[0], b = p[1];
+            p[0] = a * cs - b * sn;
+            p[1] = a * sn + b * cs;
+        }
+}
+
+/* Selective Multi-Head Attention, Eq. 27-36, with the optional partial RoPE of Eq. 32 and the
+ * masks of Sec. III-C.3.
  * x [b,l,d]; Wq,Wk,Wv [n,d,d_h]; Wo [n,d_h,d]; expert_id [b,k] (Eq. 22);
- * gE [b,n] (Eq. 21); patch_id [b,n,c] (Eq. 17); gD [b,n,m] (Eq. 14); u [b,l,d]. */
+ * gE [b,n] (Eq. 21); patch_id [b,n,c] (Eq. 17); gD [b,n,m] (Eq. 14); u [b,l,d];
+ * rope_dim even, 0 = none; pad_mask [b,l] bytes (1 = token, 0 = padding) or NULL. */
 void uoe_oracle_smha(int b, int l, int d, int n, int k, int m, int c, int d_h, unsigned flags,
                      const double *x, const double *Wq, const double *Wk, const double *Wv,
                      const double *Wo, const int32_t *expert_id, const double *gE,
-                     const int32_t *patch_id, const double *gD, double *u)
+                     const int32_t *patch_id, const double *gD, int rope_dim,
+                     const unsigned char *pad_mask, double *u)
 {
     const int l_p = l / m, l_a = c * l_p;
     double *H = (double *)malloc(sizeof(double) * (size_t)l_a * d);
@@ -238,22 +266,34 @@ void uoe_oracle_smha(int b, int l, int d, int n, int k, int m, int c, int d_h, u
             matmul(l_a, d, d_h, H, d, Wq + (long)i * d * d_h, d_h, Q, d_h);
             matmul(l_a, d, d_h, H, d, Wk + (long)i * d * d_h, d_h, K, d_h);
             matmul(l_a, d, d_h, H, d, Wv + (long)i * d * d_h, d_h, V, d_h);
-            /* Eq. 33: s = softmax(q k^T / sqrt(d_h)) along keys */
+            /* Eq. 32 */
+            if (rope_dim > 0) {
+                rope_rows(Q, l_a, d_h, rope_dim);
+                rope_rows(K, l_a, d_h, rope_dim);
+            }
+            /* Eq. 33: s = softmax(q k^T / sqrt(d_h)) along the admissible keys */
 #pragma omp parallel for schedule(static)
             for (int r = 0; r < l_a; ++r) {
                 double *Sr = S + (long)r * l_a;
                 double mx = -INFINITY, den = 0.0;
                 for (int j = 0; j < l_a; ++j) {
+                    int ok = 1;
+                    if ((flags & ORACLE_CAUSAL) && j > r) ok = 0;                    /* Fig. 4 */
+                    if (pad_mask && !pad_mask[(long)bb * l + T[j]]) ok = 0;          /* Eq. 41 */
+                    if (!ok) {
+                        Sr[j] = -INFINITY;
+                        continue;
+                    }
                     double a = 0.0;
                     for (int e = 0; e < d_h; ++e) a += Q[(long)r * d_h + e] * K[(long)j * d_h + e];
                     Sr[j] = a * scale;
                     if (Sr[j] > mx) mx = Sr[j];
                 }
                 for (int j = 0; j < l_a; ++j) {
-                    Sr[j] = exp(Sr[j] - mx);
+                    Sr[j] = (Sr[j] == -INFINITY) ? 0.0 : exp(Sr[j] - mx);
                     den += Sr[j];
                 }
-                for (int j = 0; j < l_a; ++j) Sr[j] /= den;
+                for (int j = 0; j < l_a; ++j) Sr[j] = den > 0.0 ? Sr[j] / den : 0.0;
             }
             /* Eq. 34, Eq. 35 */
             matmul(l_a, l_a, d_h, S, l_a, V, d_h, O, d_h);
