@@ -81,6 +81,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="lm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--causal", action="store_true", help="SMHA with the shared causal mask (Sec. III-C.3)")
+    ap.add_argument("--rope-dim", type=int, default=0, help="SMHA with partial RoPE on the last N dims (Eq. 32)")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
@@ -104,9 +106,9 @@ def main() -> int:
     B.lib()  # fail loudly if the HIP library is not built
     cfg = synth.CONFIGS[args.workload]
     inp = synth.make_inputs(cfg)
-    fa = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | B.FLAG_GATE_PATCH
+    fa = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | B.FLAG_GATE_PATCH | (B.FLAG_CAUSAL if args.causal else 0)
     fm = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT
-    dev = DeviceLayer(inp, fa, fm, device="cuda:0")
+    dev = DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim)
     torch.cuda.set_device(0)
 
     if args.stage:
@@ -188,9 +190,9 @@ def main() -> int:
         for f in ("noise_a_expert", "noise_a_patch", "noise_m_expert"):
             v = getattr(inp, f)
             setattr(sub, f, None if v is None else v[:nb])
-        oracle.layer_forward(sub, fa, fm) if fl["total"] * nb / cfg.b < 2e10 else None   # warm the pages
+        oracle.layer_forward(sub, fa, fm, args.rope_dim) if fl["total"] * nb / cfg.b < 2e10 else None   # warm the pages
         c0 = time.perf_counter()
-        oracle.layer_forward(sub, fa, fm)
+        oracle.layer_forward(sub, fa, fm, args.rope_dim)
         c1 = time.perf_counter()
         cpu = {"value": round(nb * cfg.l / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.get_threads(),
                "kind": "oracle", "sample": f"{nb} of {cfg.b} samples of the {cfg.name} workload, one fp64 pass "
@@ -201,7 +203,9 @@ def main() -> int:
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
-        "config": {"workload": describe(cfg), "flags": "residual+expert gate+patch gate",
+        "config": {"workload": describe(cfg),
+                   "flags": "residual+expert gate+patch gate" + ("+causal" if args.causal else "") +
+                            (f"+rope{args.rope_dim}" if args.rope_dim else ""),
                    "seed": cfg.seed, "launch": launch},
         "ms_per_step_eager": round(eager_ms, 5),
         "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 3),

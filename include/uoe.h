@@ -23,7 +23,8 @@
  *   - Inputs must be finite; behaviour on NaN/Inf is unspecified.
  *   - Shape limits: d % 8 == 0, width % 8 == 0, l % m == 0, 1 <= n <= 32,
  *     1 <= k <= n, 1 <= c <= m, m <= 1024, width <= 128 for SMHA.  Valid but
- *     unsupported requests return UOE_ERR_UNSUPPORTED.
+ *     unsupported requests return UOE_ERR_UNSUPPORTED (also: UOE_FLAG_CAUSAL or rope_dim on a
+ *     UoME call; uoe_route and uoe_gather ignore them).
  */
 #ifndef UOE_H
 #define UOE_H
@@ -49,7 +50,7 @@ enum {
     UOE_FLAG_RESIDUAL = 1u << 0,    /* out = in + sum(...)  (Eq. 20/26/36/40); off: out = sum(...)  */
     UOE_FLAG_GATE_EXPERT = 1u << 1, /* weight an expert's contribution by its Eq. 21 gate g[b,i]    */
     UOE_FLAG_GATE_PATCH = 1u << 2,  /* weight a patch's contribution by its Eq. 14 gate g[b,i,j]    */
-    UOE_FLAG_CAUSAL = 1u << 3       /* reserved (shared causal mask of Sec. III-C.3): UNSUPPORTED   */
+    UOE_FLAG_CAUSAL = 1u << 3       /* SMHA only: shared causal mask of Sec. III-C.3 / Fig. 4       */
 };
 
 /* One block (SMHA or UoME) of the layer. */
@@ -60,7 +61,7 @@ typedef struct {
     int32_t width;       /* d_h (SMHA) or d_e (UoME)                                                  */
     int32_t dtype;       /* UOE_F32 | UOE_BF16                                                        */
     uint32_t flags;      /* UOE_FLAG_*                                                                */
-    int32_t rope_dim;    /* reserved (partial RoPE of Eq. 32): must be 0                              */
+    int32_t rope_dim;    /* SMHA only: rotary dims at the end of each head (Eq. 32); even, 0 = none   */
     int32_t reserved[5]; /* must be 0                                                                 */
 } uoe_block_desc;
 
@@ -115,11 +116,29 @@ int uoe_gather(const uoe_block_desc *blk, const void *x, const int32_t *expert_i
  *   (expert_gate / patch_gate may be NULL when the matching gate flag is off)
  *   out [b,l,d] must not alias x.  Rows of patches no active expert selected are
  *   x (or 0 without UOE_FLAG_RESIDUAL) exactly.  Deterministic: no atomics.
+ * Optional (Sec. III-C.1/3):
+ *   blk->rope_dim > 0   partial RoPE (Eq. 32): the last rope_dim dims of each head of q and k are
+ *                       rotated in adjacent pairs (2i, 2i+1) by position * 10000^(-2i/rope_dim); the
+ *                       position of a token is its index in its expert's compacted sequence
+ *   UOE_FLAG_CAUSAL     every expert uses the leading l_a x l_a lower-triangular mask: key
+ *                       position <= query position in the compacted sequence (Fig. 4)
+ * A query row with no admissible key contributes nothing.
  */
 int uoe_smha_forward(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
                      const void *wv, const void *wo, const int32_t *expert_idx,
                      const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
                      void *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * uoe_smha_forward with a padding mask (Eq. 41): pad_mask [b,l] bytes on the device, 1 = token,
+ * 0 = padding, gathered with each expert's indices; padded KEYS are removed from the softmax
+ * (rows of padded queries are still computed).  pad_mask == NULL is uoe_smha_forward.
+ */
+int uoe_smha_forward_masked(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
+                            const void *wv, const void *wo, const int32_t *expert_idx,
+                            const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
+                            const uint8_t *pad_mask, void *out, void *ws, size_t ws_bytes,
+                            void *hip_stream);
 
 /*
  * Union-of-MLP-Experts in expert-selection mode on given routing results

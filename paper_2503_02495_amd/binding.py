@@ -18,6 +18,7 @@ F32, BF16 = 0, 1
 FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
 EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_gather", "uoe_smha_forward",
+           "uoe_smha_forward_masked",
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward")
 
 
@@ -67,13 +68,14 @@ def lib():
         L.uoe_route.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_gather.argtypes = [D, P, P, P, P, P]
         L.uoe_smha_forward.argtypes = [D] + [P] * 10 + [P, S, P]
+        L.uoe_smha_forward_masked.argtypes = [D] + [P] * 11 + [P, S, P]
         L.uoe_uome_forward.argtypes = [D] + [P] * 8 + [P, S, P]
         L.uoe_uome_up.argtypes = [D, P, P, P, P, P, P]
         L.uoe_uome_down.argtypes = [D, P, P, P, P, P, P]
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
-        for f in ("uoe_route", "uoe_gather", "uoe_smha_forward", "uoe_uome_forward", "uoe_uome_up",
+        for f in ("uoe_route", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
                   "uoe_uome_down", "uoe_layer_forward"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
@@ -143,6 +145,15 @@ def smha_forward(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, pat
                                 _ptr(expert_gate), _ptr(patch_idx), _ptr(patch_gate), _ptr(out), _ptr(ws),
                                 _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_smha_forward", check)
+
+
+def smha_forward_masked(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, pad_mask, out,
+                        ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_smha_forward_masked(_ref(blk), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+                                       _ptr(expert_idx), _ptr(expert_gate), _ptr(patch_idx), _ptr(patch_gate),
+                                       _ptr(pad_mask), _ptr(out), _ptr(ws),
+                                       _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_smha_forward_masked", check)
 
 
 def uome_forward(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_gate, out, ws,

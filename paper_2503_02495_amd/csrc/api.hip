@@ -12,9 +12,11 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) & ~(ALIGN - 1); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t elem_size(int dtype) { return dtype == UOE_BF16 ? 2 : 4; }
 
-// Generic descriptor checks shared by every call.  `smha` additionally bounds the head dim.
-int check_desc(const uoe_block_desc *d, bool smha)
+// Generic descriptor checks shared by every call.  kind: what the descriptor is used for.
+enum DescKind { DESC_ROUTE, DESC_SMHA, DESC_UOME };
+int check_desc(const uoe_block_desc *d, DescKind kind)
 {
+    const bool smha = kind == DESC_SMHA;
     if (!d) return UOE_ERR_INVALID_ARG;
     if (d->b < 1 || d->l < 1 || d->d < 1 || d->n < 1 || d->k < 1 || d->k > d->n || d->m < 1 ||
         d->c < 1 || d->c > d->m || d->width < 1 || (d->l % d->m) != 0)
@@ -24,8 +26,9 @@ int check_desc(const uoe_block_desc *d, bool smha)
         return UOE_ERR_INVALID_ARG;
     for (int i = 0; i < 5; ++i)
         if (d->reserved[i] != 0) return UOE_ERR_INVALID_ARG;
-    if (d->rope_dim < 0) return UOE_ERR_INVALID_ARG;
-    if (d->rope_dim != 0 || (d->flags & UOE_FLAG_CAUSAL)) return UOE_ERR_UNSUPPORTED;
+    if (d->rope_dim < 0 || (d->rope_dim & 1) || d->rope_dim > d->width) return UOE_ERR_INVALID_ARG;
+    // the causal mask and RoPE belong to the attention block (routing and gathering ignore them)
+    if (kind == DESC_UOME && (d->rope_dim != 0 || (d->flags & UOE_FLAG_CAUSAL))) return UOE_ERR_UNSUPPORTED;
     if (d->n > 32 || (d->d % 8) != 0 || (d->width % 8) != 0 || d->m > 1024) return UOE_ERR_UNSUPPORTED;
     if ((long)d->n * d->m > 8192) return UOE_ERR_UNSUPPORTED;
     if ((long)d->b * d->m > 65535 || (long)d->b * d->k > 65535) return UOE_ERR_UNSUPPORTED;
@@ -128,7 +131,7 @@ int do_route(const uoe_block_desc *blk, int m, int c, const void *x, const void 
 
 int do_smha(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk, const void *wv,
             const void *wo, const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
-            const float *patch_gate, void *out, void *ws, size_t ws_bytes, hipStream_t st)
+            const float *patch_gate, const uint8_t *pad_mask, void *out, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if (!x || !wq || !wk || !wv || !wo || !expert_idx || !patch_idx || !out) return UOE_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(wo) || !aligned16(out))
@@ -146,6 +149,7 @@ int do_smha(const uoe_block_desc *blk, const void *x, const void *wq, const void
     a.out = out;
     a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = blk->m; a.c = blk->c;
     a.d_h = blk->width; a.flags = blk->flags;
+    a.rope_dim = blk->rope_dim; a.pad_mask = pad_mask;
     a.q = at(ws, w.q); a.kk = at(ws, w.k); a.v = at(ws, w.v); a.o = at(ws, w.o); a.o_lo = at(ws, w.o_lo);
     a.inv_cnt = reinterpret_cast<int32_t *>(at(ws, w.inv_cnt));
     a.inv_ent = reinterpret_cast<int32_t *>(at(ws, w.inv_ent));
@@ -193,12 +197,12 @@ size_t uoe_workspace_bytes(const uoe_block_desc *smha, const uoe_block_desc *uom
 {
     size_t total = 0;
     if (smha) {
-        if (check_desc(smha, true) != UOE_OK) return 0;
+        if (check_desc(smha, DESC_SMHA) != UOE_OK) return 0;
         total += route_ws(smha->b, smha->l, smha->d, smha->n, smha->m, smha->dtype == UOE_BF16).total + smha_ws(smha).total +
                  routing_buf(smha, smha->m, smha->c).total;
     }
     if (uome) {
-        if (check_desc(uome, false) != UOE_OK) return 0;
+        if (check_desc(uome, DESC_UOME) != UOE_OK) return 0;
         total += route_ws(uome->b, uome->l, uome->d, uome->n, uome->m, uome->dtype == UOE_BF16).total + uome_ws(uome) +
                  routing_buf(uome, uome->m, uome->c).total;
     }
@@ -211,7 +215,7 @@ int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, co
               int32_t *expert_idx, float *expert_gate, int32_t *patch_idx, float *patch_gate,
               void *ws, size_t ws_bytes, void *hip_stream)
 {
-    const int rc = check_desc(blk, false);
+    const int rc = check_desc(blk, DESC_ROUTE);
     if (rc != UOE_OK) return rc;
     return do_route(blk, blk->m, blk->c, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx,
                     expert_gate, patch_idx, patch_gate, ws, ws_bytes, static_cast<hipStream_t>(hip_stream));
@@ -220,7 +224,7 @@ int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, co
 int uoe_gather(const uoe_block_desc *blk, const void *x, const int32_t *expert_idx,
                const int32_t *patch_idx, void *h, void *hip_stream)
 {
-    const int rc = check_desc(blk, false);
+    const int rc = check_desc(blk, DESC_ROUTE);
     if (rc != UOE_OK) return rc;
     if (!x || !expert_idx || !patch_idx || !h || !aligned16(x) || !aligned16(h) || h == x)
         return UOE_ERR_INVALID_ARG;
@@ -236,17 +240,28 @@ int uoe_smha_forward(const uoe_block_desc *blk, const void *x, const void *wq, c
                      const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
                      void *out, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    const int rc = check_desc(blk, true);
+    const int rc = check_desc(blk, DESC_SMHA);
     if (rc != UOE_OK) return rc;
-    return do_smha(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, out, ws, ws_bytes,
+    return do_smha(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, nullptr, out, ws, ws_bytes,
                    static_cast<hipStream_t>(hip_stream));
+}
+
+int uoe_smha_forward_masked(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
+                            const void *wv, const void *wo, const int32_t *expert_idx,
+                            const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
+                            const uint8_t *pad_mask, void *out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_desc(blk, DESC_SMHA);
+    if (rc != UOE_OK) return rc;
+    return do_smha(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, pad_mask, out, ws,
+                   ws_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
                      const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
                      const float *patch_gate, void *out, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    const int rc = check_desc(blk, false);
+    const int rc = check_desc(blk, DESC_UOME);
     if (rc != UOE_OK) return rc;
     if (blk->c != blk->m || patch_idx || patch_gate) return UOE_ERR_UNSUPPORTED;  // data-selection UoME
     return do_uome(blk, u, a_in, a_out, expert_idx, expert_gate, out, ws, ws_bytes,
@@ -256,7 +271,7 @@ int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in,
 int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, const int32_t *expert_idx,
                 const float *expert_gate, void *hidden, void *hip_stream)
 {
-    const int rc = check_desc(blk, false);
+    const int rc = check_desc(blk, DESC_UOME);
     if (rc != UOE_OK) return rc;
     if (blk->c != blk->m || (blk->flags & UOE_FLAG_GATE_PATCH)) return UOE_ERR_UNSUPPORTED;
     if (!u || !a_in || !expert_idx || !hidden || hidden == u) return UOE_ERR_INVALID_ARG;
@@ -273,7 +288,7 @@ int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, cons
 int uoe_uome_down(const uoe_block_desc *blk, const void *hidden, const void *a_out, const void *u,
                   const int32_t *expert_idx, void *out, void *hip_stream)
 {
-    const int rc = check_desc(blk, false);
+    const int rc = check_desc(blk, DESC_UOME);
     if (rc != UOE_OK) return rc;
     if (blk->c != blk->m) return UOE_ERR_UNSUPPORTED;
     if (!hidden || !a_out || !expert_idx || !out || out == hidden || out == u) return UOE_ERR_INVALID_ARG;
@@ -294,9 +309,9 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
                       const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, void *ws,
                       size_t ws_bytes, void *hip_stream)
 {
-    int rc = check_desc(smha, true);
+    int rc = check_desc(smha, DESC_SMHA);
     if (rc != UOE_OK) return rc;
-    rc = check_desc(uome, false);
+    rc = check_desc(uome, DESC_UOME);
     if (rc != UOE_OK) return rc;
     if (!wa || !wm || !x || !out || out == x) return UOE_ERR_INVALID_ARG;
     if (smha->b != uome->b || smha->l != uome->l || smha->d != uome->d || smha->dtype != uome->dtype)
@@ -348,7 +363,7 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
     rc = do_route(smha, smha->m, smha->c, x, wa->w_expert, wa->w_b, wa->w_a, noise_a_expert, noise_a_patch,
                   a_eidx, a_egate, a_pidx, a_pgate, route_a_ws, route_a_bytes, st);
     if (rc != UOE_OK) return rc;
-    rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, a_eidx, a_egate, a_pidx, a_pgate, u, smha_scratch,
+    rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, a_eidx, a_egate, a_pidx, a_pgate, nullptr, u, smha_scratch,
                  smha_bytes, st);
     if (rc != UOE_OK) return rc;
     // the UoME router reads u, the finished SMHA output (expert-selection mode: one patch = the sample)

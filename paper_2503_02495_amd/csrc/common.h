@@ -68,7 +68,7 @@ __device__ __forceinline__ float silu_fast(float z)
 }
 
 // ---------------------------------------------------------------- flags (mirror of the ABI values)
-constexpr uint32_t F_RESIDUAL = 1u, F_GATE_EXPERT = 2u, F_GATE_PATCH = 4u;
+constexpr uint32_t F_RESIDUAL = 1u, F_GATE_EXPERT = 2u, F_GATE_PATCH = 4u, F_CAUSAL = 8u;
 
 // ---------------------------------------------------------------- launcher arguments
 struct RouteArgs {
@@ -90,6 +90,8 @@ struct SmhaArgs {
     void *out;
     int b, l, d, n, k, m, c, d_h;
     uint32_t flags;
+    int rope_dim;                             // rotary dims at the end of a head (Eq. 32), 0 = none
+    const unsigned char *pad_mask;            // [b,l] 1 = token, 0 = padding (Eq. 41), or NULL
     // workspace
     void *q, *kk, *v, *o, *o_lo;              // [b*k, l_a, d_h] each, storage dtype (o_lo: low part of o, MFMA path)
     int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k]: which (slot s, pick t) chose patch p

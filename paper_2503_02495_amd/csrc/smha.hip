@@ -53,6 +53,46 @@ static hipError_t launch_inverse_map(const SmhaArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
+// Partial RoPE of Eq. 32, in place on the q and k workspaces: the last rope_dim dims of a head are
+// rotated in adjacent pairs (2i, 2i+1) by position * 10000^(-2i/rope_dim); the position of a row
+// is its index in the unit's compacted sequence.  One thread per (unit row, pair).
+template <typename T> __global__ __launch_bounds__(256) void smha_rope_kernel(SmhaArgs a)
+{
+    const int l_a = a.c * (a.l / a.m), half = a.rope_dim >> 1;
+    const long total = (long)a.b * a.k * l_a * half;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx % half);
+    const long row = idx / half;              // unit * l_a + r
+    const int r = (int)(row % l_a);
+    const float theta = exp2f(-(2.0f * (float)i / (float)a.rope_dim) * 13.287712379549449f);  // log2(10000)
+    float sn, cs;
+    sincosf((float)r * theta, &sn, &cs);
+    const size_t at = (size_t)row * a.d_h + (a.d_h - a.rope_dim) + 2 * i;
+    T *q = static_cast<T *>(a.q) + at, *k = static_cast<T *>(a.kk) + at;
+    const float q0 = to_f32(q[0]), q1 = to_f32(q[1]), k0 = to_f32(k[0]), k1 = to_f32(k[1]);
+    q[0] = from_f32<T>(q0 * cs - q1 * sn);
+    q[1] = from_f32<T>(q0 * sn + q1 * cs);
+    k[0] = from_f32<T>(k0 * cs - k1 * sn);
+    k[1] = from_f32<T>(k0 * sn + k1 * cs);
+}
+
+template <typename T> static hipError_t launch_rope(const SmhaArgs &a, hipStream_t st)
+{
+    if (a.rope_dim <= 0) return hipSuccess;
+    const long total = (long)a.b * a.k * a.c * (a.l / a.m) * (a.rope_dim >> 1);
+    hipLaunchKernelGGL((smha_rope_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// padding flag of key `key` of unit g (Eq. 41: the mask is gathered with the unit's indices)
+__device__ __forceinline__ bool key_is_token(const SmhaArgs &a, int g, int key, int l_p)
+{
+    const int bb = g / a.k, i = clampi(a.expert_idx[g], a.n);
+    const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + key / l_p], a.m);
+    return a.pad_mask[(size_t)bb * a.l + p * l_p + key % l_p] != 0;
+}
+
 // Vector-ALU attention: one thread per query row, keys/values staged through LDS in tiles,
 // online softmax in fp32.  DH is d_h rounded up to a supported register-array size.
 template <typename T, int DH>
@@ -61,6 +101,7 @@ __global__ __launch_bounds__(128) void attention_generic_kernel(SmhaArgs a)
     constexpr int KT = 32;  // keys per LDS tile
     __shared__ float ks[KT][DH + 1];
     __shared__ float vs[KT][DH + 1];
+    __shared__ unsigned char km[KT];  // key admissible under the padding mask
     const int g = blockIdx.y;  // unit
     const int l_p = a.l / a.m, l_a = a.c * l_p, d_h = a.d_h;
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
@@ -77,9 +118,14 @@ __global__ __launch_bounds__(128) void attention_generic_kernel(SmhaArgs a)
         acc[e] = 0.f;
     }
     float mx = -INFINITY, den = 0.f;
+    const bool causal = (a.flags & F_CAUSAL) != 0;
+    // under the causal mask no row of this block sees keys past the block's last row
+    const int key_end = causal ? min(l_a, (int)((blockIdx.x + 1) * blockDim.x)) : l_a;
 
-    for (int j0 = 0; j0 < l_a; j0 += KT) {
+    for (int j0 = 0; j0 < key_end; j0 += KT) {
         const int jn = min(KT, l_a - j0);
+        if (threadIdx.x < KT)
+            km[threadIdx.x] = (threadIdx.x < jn) && (!a.pad_mask || key_is_token(a, g, j0 + threadIdx.x, l_p));
         for (int idx = threadIdx.x; idx < KT * DH; idx += blockDim.x) {
             const int jj = idx / DH, e = idx - jj * DH;
             const bool ok = jj < jn && e < d_h;
@@ -89,6 +135,7 @@ __global__ __launch_bounds__(128) void attention_generic_kernel(SmhaArgs a)
         __syncthreads();
         if (live) {
             for (int jj = 0; jj < jn; ++jj) {
+                if (!km[jj] || (causal && j0 + jj > r)) continue;  // masked key
                 float s = 0.f;
 #pragma unroll
                 for (int e = 0; e < DH; ++e) s = fmaf(qr[e], ks[jj][e], s);
@@ -112,7 +159,7 @@ __global__ __launch_bounds__(128) void attention_generic_kernel(SmhaArgs a)
         const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + r / l_p], a.m);
         w *= a.patch_gate[((size_t)bb * a.n + i) * a.m + p];
     }
-    const float inv = w / den;
+    const float inv = den > 0.f ? w / den : 0.f;  // a row with no admissible key contributes nothing
     T *o = static_cast<T *>(a.o) + ((size_t)g * l_a + r) * d_h;
 #pragma unroll
     for (int e = 0; e < DH; ++e)
@@ -149,6 +196,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
     constexpr int K_PER_T = (K_CHUNKS + NT - 1) / NT, V_PER_T = (V_CHUNKS + NT - 1) / NT;
     __shared__ __align__(16) uint16_t Ks[2][BKV][KP];
     __shared__ __align__(16) uint16_t Vs[2][BKV][VP];  // [key][d_h], read with the transposing LDS read
+    __shared__ unsigned char Km[2][BKV];                // key admissible under the padding mask
 
     const int g = blockIdx.y;
     const int l_p = a.l / a.m, l_a = a.c * l_p;
@@ -174,8 +222,11 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
         for (int q = 0; q < 16; ++q) oacc[t][q] = 0.f;
     float mrun = -INFINITY, lsum = 0.f;
 
+    const bool causal = (a.flags & F_CAUSAL) != 0, masked = a.pad_mask != nullptr;
     uint4 kreg[K_PER_T], vreg[V_PER_T];
+    unsigned char kmreg = 1;
     auto load_global = [&](int key0) {
+        if (masked && tid < BKV) kmreg = (key0 + tid < l_a) && key_is_token(a, g, min(key0 + tid, l_a - 1), l_p);
 #pragma unroll
         for (int i = 0; i < K_PER_T; ++i) {
             const int c = tid + i * NT;
@@ -196,6 +247,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
         }
     };
     auto store_lds = [&](int buf) {
+        if (masked && tid < BKV) Km[buf][tid] = kmreg;
 #pragma unroll
         for (int i = 0; i < K_PER_T; ++i) {
             const int c = tid + i * NT;
@@ -208,7 +260,9 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
         }
     };
 
-    const int nkt = (l_a + BKV - 1) / BKV;
+    // under the causal mask no query of this workgroup sees keys past the workgroup's last row
+    const int key_end = causal ? min(l_a, (int)(blockIdx.x + 1) * 32 * NW) : l_a;
+    const int nkt = (key_end + BKV - 1) / BKV;
     load_global(0);
     store_lds(0);
     __syncthreads();
@@ -230,13 +284,13 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
                 sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
             }
         // accumulator register q of tile t is key kt*64 + t*32 + (q/4)*8 + lh*4 + q%4
-        if ((kt + 1) * BKV > l_a) {
+        if ((kt + 1) * BKV > l_a || masked || (causal && (kt + 1) * BKV > qrow)) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
-                    const int key = kt * BKV + t * 32 + (q >> 2) * 8 + lh * 4 + (q & 3);
-                    if (key >= l_a) sacc[t][q] = -INFINITY;
+                    const int kl = t * 32 + (q >> 2) * 8 + lh * 4 + (q & 3), key = kt * BKV + kl;
+                    if (key >= l_a || (causal && key > qrow) || (masked && !Km[buf][kl])) sacc[t][q] = -INFINITY;
                 }
         }
         float tmax = -INFINITY;
@@ -246,14 +300,15 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
             for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, sacc[t][q]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
         const float mnew = fmaxf(mrun, tmax);
-        const float corr = __builtin_amdgcn_exp2f(mrun - mnew);  // 0 on the first tile
+        const float msafe = mnew == -INFINITY ? 0.f : mnew;      // every key so far masked: all p = 0
+        const float corr = __builtin_amdgcn_exp2f(mrun - msafe);  // 0 on the first tile
         mrun = mnew;
         float psum = 0.f;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
-                const float pv = __builtin_amdgcn_exp2f(sacc[t][q] - mnew);
+                const float pv = __builtin_amdgcn_exp2f(sacc[t][q] - msafe);
                 sacc[t][q] = pv;
                 psum += pv;
             }
@@ -304,7 +359,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
         const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + qrow / l_p], a.m);
         w *= a.patch_gate[((size_t)bb * a.n + i) * a.m + p];
     }
-    const float inv = w / lsum;
+    const float inv = lsum > 0.f ? w / lsum : 0.f;  // a row with no admissible key contributes nothing
     bf16_t *o = static_cast<bf16_t *>(a.o) + ((size_t)g * l_a + qrow) * DH;
     bf16_t *o_lo = static_cast<bf16_t *>(a.o_lo) + ((size_t)g * l_a + qrow) * DH;
     // accumulator register q of tile td is head-dim index td*32 + (q/4)*8 + lh*4 + q%4.
@@ -387,6 +442,7 @@ template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStrea
     hipError_t err;
     if ((err = launch_inverse_map(a, st)) != hipSuccess) return err;
     if ((err = launch_gemm_generic<T>(make_qkv<T>(a), units, l_a, 3 * a.d_h, st)) != hipSuccess) return err;
+    if ((err = launch_rope<T>(a, st)) != hipSuccess) return err;
     if ((err = launch_attention_generic<T>(a, st)) != hipSuccess) return err;
     return launch_gemm_generic<T>(make_outproj<T>(a), a.b * a.m, l_p, a.d, st);
 }
@@ -418,6 +474,7 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
         err = launch_gemm_mfma<QP, 128, 128, 32, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
     }
     if (err != hipSuccess) return err;
+    if ((err = launch_rope<bf16_t>(a, st)) != hipSuccess) return err;
 
     err = mfma_attn ? launch_attention_mfma(a, st) : launch_attention_generic<bf16_t>(a, st);
     if (err != hipSuccess) return err;

@@ -31,7 +31,7 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 class DeviceLayer:
     """One UoE layer's tensors resident on the GPU, plus descriptors, outputs and workspace."""
 
-    def __init__(self, inp: synth.LayerInputs, flags_a: int, flags_m: int, device="cuda:0"):
+    def __init__(self, inp: synth.LayerInputs, flags_a: int, flags_m: int, device="cuda:0", rope_dim: int = 0):
         cfg = inp.cfg
         self.cfg, self.device = cfg, torch.device(device)
         dt = cfg.dtype
@@ -46,7 +46,7 @@ class DeviceLayer:
         self.noise_a_expert, self.noise_a_patch = f32(inp.noise_a_expert), f32(inp.noise_a_patch)
         self.noise_m_expert = f32(inp.noise_m_expert)
 
-        self.smha = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_a, cfg.k_a, cfg.m, cfg.c, cfg.d_h, code, flags_a)
+        self.smha = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_a, cfg.k_a, cfg.m, cfg.c, cfg.d_h, code, flags_a, rope_dim)
         self.uome = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_m, cfg.k_m, 1, 1, cfg.d_e, code, flags_m)
         nbytes = B.workspace_bytes(self.smha, self.uome)
         if nbytes == 0:
@@ -74,13 +74,17 @@ class DeviceLayer:
                 self.noise_a_patch, self.a_expert_idx, self.a_expert_gate, self.a_patch_idx,
                 self.a_patch_gate, self.ws)
 
-    def smha_forward(self, expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None, x=None, out=None):
-        B.smha_forward(self.smha, self.x if x is None else x, self.wq, self.wk, self.wv, self.wo,
-                       self.a_expert_idx if expert_idx is None else expert_idx,
-                       self.a_expert_gate if expert_gate is None else expert_gate,
-                       self.a_patch_idx if patch_idx is None else patch_idx,
-                       self.a_patch_gate if patch_gate is None else patch_gate,
-                       self.u if out is None else out, self.ws)
+    def smha_forward(self, expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None, x=None, out=None,
+                     pad_mask=None):
+        args = (self.smha, self.x if x is None else x, self.wq, self.wk, self.wv, self.wo,
+                self.a_expert_idx if expert_idx is None else expert_idx,
+                self.a_expert_gate if expert_gate is None else expert_gate,
+                self.a_patch_idx if patch_idx is None else patch_idx,
+                self.a_patch_gate if patch_gate is None else patch_gate)
+        if pad_mask is None:
+            B.smha_forward(*args, self.u if out is None else out, self.ws)
+        else:
+            B.smha_forward_masked(*args, pad_mask, self.u if out is None else out, self.ws)
 
     def route_m(self, u=None):
         B.route(self.uome, self.u if u is None else u, self.m_w_expert, None, None, self.noise_m_expert, None,

@@ -62,8 +62,8 @@ def test_workspace_bytes():
     (dict(b=0), B.ERR_INVALID_ARG),
     (dict(dtype=7), B.ERR_INVALID_ARG),
     (dict(flags=1 << 9), B.ERR_INVALID_ARG),
-    (dict(flags=B.FLAG_CAUSAL), B.ERR_UNSUPPORTED),
-    (dict(rope_dim=8), B.ERR_UNSUPPORTED),
+    (dict(rope_dim=3), B.ERR_INVALID_ARG),       # odd
+    (dict(rope_dim=18), B.ERR_INVALID_ARG),      # > width
     (dict(d=60), B.ERR_UNSUPPORTED),             # d % 8 != 0
     (dict(width=12), B.ERR_UNSUPPORTED),
     (dict(n=33, k=2), B.ERR_UNSUPPORTED),
@@ -74,6 +74,21 @@ def test_descriptor_validation(kw, want):
     assert B.route(d, *args, FAKE, stream=0, check=False, ws_bytes=1 << 30) == want
     assert B.smha_forward(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE,
                           stream=0, check=False, ws_bytes=1 << 30) == want
+
+
+def test_causal_and_rope_belong_to_the_attention_block():
+    for kw in (dict(flags=B.FLAG_CAUSAL), dict(rope_dim=8)):
+        d = good(**kw)
+        # routing ignores them (same descriptor serves uoe_route and uoe_smha_forward)
+        assert B.route(d, *([FAKE] * 10), FAKE, stream=0, check=False, ws_bytes=8) == B.ERR_WORKSPACE
+        u = good(m=1, c=1, width=64, **kw)
+        assert B.uome_forward(u, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE, stream=0, check=False,
+                              ws_bytes=1 << 30) == B.ERR_UNSUPPORTED
+        # accepted by the attention call (fails later, on the too-small workspace)
+        assert B.smha_forward(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, stream=0,
+                              check=False, ws_bytes=8) == B.ERR_WORKSPACE
+        assert B.smha_forward_masked(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE,
+                                     stream=0, check=False, ws_bytes=8) == B.ERR_WORKSPACE
 
 
 def test_reserved_fields_must_be_zero():
