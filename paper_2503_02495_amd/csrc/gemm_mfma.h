@@ -43,9 +43,91 @@ __device__ __forceinline__ uint2 lds_read_tr4(const uint16_t *p)
     return __builtin_bit_cast(uint2, v);
 }
 
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack2_bf16(float a, float b)
 {
-    return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+__host__ __device__ constexpr int largest_divisor_upto(int n, int cap)
+{
+    int b = cap < n ? cap : n;
+    while (n % b) --b;
+    return b;
+}
+
+// Per-column factors of a tile, one per 8-column group, fetched by the whole workgroup before the
+// K loop (the lookups behind col_scale are dependent global loads: taken per column group inside
+// the epilogue they would serialise their latency).  The caller's next barrier publishes them.
+template <typename P, int BN>
+__device__ __forceinline__ void fill_col_scale(const P &p, float *coltab, int g, int n0, int N, int tid, int nthreads)
+{
+    if constexpr (P::kColScale) {
+        for (int c = tid; c < BN / 8; c += nthreads) {
+            const int col = n0 + c * 8;
+            coltab[c] = p.col_scale(g, col < N ? col : 0);
+        }
+    }
+}
+
+// Epilogue of one wave.  acc is the transposed-product accumulator of a TM x TN grid of 32x32
+// tiles: register q of lane (lr, lh) in tile (i, j) is output row i*32 + lr, column
+// j*32 + (q/4)*8 + lh*4 + q%4 of the wave tile.  The wave stages its tile in LDS (stage: WM rows
+// of SPITCH elements, private to the wave) and then moves 16-byte pieces of rows to memory,
+// residual pieces loaded a batch ahead of the stores.  wcol0 = first column of the wave tile
+// inside the workgroup tile (indexes coltab); (grow0, gcol0) = its global position.
+template <typename P, int TM, int TN, int SPITCH>
+__device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN], uint16_t (*stage)[SPITCH], const float *coltab,
+                                              int g, int grow0, int gcol0, int wcol0, int M, int N, int lane)
+{
+    constexpr int WM = TM * 32, WN = TN * 32;
+    const int lr = lane & 31, lh = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int qg = 0; qg < 4; ++qg) {
+            const int cl = j * 32 + qg * 8 + lh * 4;  // first of 4 consecutive columns, wave-local
+            float sc = 1.0f;
+            if constexpr (P::kColScale) sc = coltab[(wcol0 + cl) >> 3];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const uint32_t w0 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 0], sc), p.epi(acc[i][j][qg * 4 + 1], sc));
+                const uint32_t w1 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 2], sc), p.epi(acc[i][j][qg * 4 + 3], sc));
+                *reinterpret_cast<uint2 *>(&stage[i * 32 + lr][cl]) = make_uint2(w0, w1);
+            }
+        }
+    // no workgroup barrier: a wave reads back only what it staged itself, and the LDS executes one
+    // wave's instructions in order
+    __builtin_amdgcn_wave_barrier();
+    constexpr int WC = WN / 8;           // 16-byte pieces per staged row
+    constexpr int NPIECE = (WM * WC) / 64;
+    constexpr int BATCH = largest_divisor_upto(NPIECE, 8);
+    const bool res = p.has_residual();
+#pragma unroll
+    for (int t0 = 0; t0 < NPIECE; t0 += BATCH) {
+        uint4 r[BATCH];
+        if (res) {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int c = lane + (t0 + u) * 64;
+                const int grow = grow0 + c / WC, gcol = gcol0 + (c % WC) * 8;
+                r[u] = (grow < M && gcol < N) ? p.res8(g, grow, gcol) : make_uint4(0, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int c = lane + (t0 + u) * 64;
+            const int row = c / WC, pc = c % WC;
+            const int grow = grow0 + row, gcol = gcol0 + pc * 8;
+            uint4 piece = *reinterpret_cast<const uint4 *>(&stage[row][pc * 8]);
+            if (res) piece = add8_bf16(piece, r[u]);
+            if (grow < M && gcol < N) p.put8(g, grow, gcol, piece);
+        }
+    }
 }
 
 // smallest pad (in dwords) that makes (cols/2 + pad) % 64 equal to 16 or 48
@@ -90,6 +172,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
     __shared__ __align__(16) unsigned char lds_raw[LDS_BYTES];
     uint16_t(*As)[BM][APITCH] = reinterpret_cast<uint16_t(*)[BM][APITCH]>(lds_raw);
     uint16_t(*Bs)[BK][BPITCH] = reinterpret_cast<uint16_t(*)[BK][BPITCH]>(lds_raw + A_BYTES);
+    __shared__ float coltab[BN / 8];
 
     const int tile = (blockIdx.x & 7) * tg.per_xcd + (blockIdx.x >> 3);
     if (tile >= tg.total) return;
@@ -103,6 +186,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
     const int lr = lane & 31, lh = lane >> 5;
     const long bstride = p.b_stride();
+
+    fill_col_scale<P, BN>(p, coltab, g, n0, N, tid, NT);  // published by the barrier before the K loop
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -207,33 +292,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
         __syncthreads();
     }
 
-    // Epilogue.  Accumulator register q of lane (lr, lh) in tile (i, j) is output row
-    // wm0 + i*32 + lr, column wn0 + j*32 + (q/4)*8 + lh*4 + q%4.  Each wave stages its tile in LDS
-    // (the operand buffers are free now: the loop ended on a barrier) and writes 16-byte pieces.
+    // Epilogue: the operand buffers are free now (the loop ended on a barrier); each wave stages its
+    // own tile there.
     uint16_t(*stage)[SPITCH] = reinterpret_cast<uint16_t(*)[SPITCH]>(lds_raw) + (size_t)wave * WM;
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int qg = 0; qg < 4; ++qg) {
-            const int cl = j * 32 + qg * 8 + lh * 4;  // first of 4 consecutive columns, wave-local
-            const int col = n0 + wn0 + cl;
-            const auto cc = p.col_ctx(g, col < N ? col : 0);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const uint32_t w0 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 0], cc), p.epi(acc[i][j][qg * 4 + 1], cc));
-                const uint32_t w1 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 2], cc), p.epi(acc[i][j][qg * 4 + 3], cc));
-                *reinterpret_cast<uint2 *>(&stage[i * 32 + lr][cl]) = make_uint2(w0, w1);
-            }
-        }
-    __syncthreads();
-    constexpr int WC = WN / 8;  // 16-byte pieces per staged row
-#pragma unroll
-    for (int t = 0; t < (WM * WC) / 64; ++t) {
-        const int c = lane + t * 64;
-        const int row = c / WC, pc = c % WC;
-        const int grow = m0 + wm0 + row, gcol = n0 + wn0 + pc * 8;
-        if (grow < M && gcol < N) p.store8(g, grow, gcol, *reinterpret_cast<const uint4 *>(&stage[row][pc * 8]));
-    }
+    wave_epilogue<P, TM, TN, SPITCH>(p, acc, stage, coltab, g, m0 + wm0, n0 + wn0, wn0, M, N, lane);
 }
 
 template <typename P, int BM, int BN, int BK, int WAVES_M, int WAVES_N>

@@ -9,6 +9,12 @@
 //   b_stride()             elements between consecutive K rows of B inside a segment
 //   col_ctx(g, nn)   whatever the epilogue needs that depends on the column only
 //   store(g, m, nn, v, ctx) epilogue for one element
+// and, for the MFMA engines (which write 16-byte pieces of output rows),
+//   kColScale / col_scale(g, nn)  a per-column factor (constant over 8-column groups), fetched
+//                                 once per tile before the K loop
+//   epi(v, scale)                 per-element math
+//   has_residual() / res8(g, m, nn)  the 16-byte piece of the residual row, loaded in batches
+//   put8(g, m, nn, piece)         plain store of a finished piece
 // K and N are concatenations of per-expert segments of length `width`; since width % 8 == 0 an
 // 8-element run never straddles two experts.
 #pragma once
@@ -81,9 +87,13 @@ template <typename T> struct QkvProblem {
         else if (cc.which == 1) k[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
         else v[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
     }
-    // vector epilogue (MFMA engine): per-element math, then one 16-byte piece of a row
-    __device__ float epi(float val, const ColCtx &cc) const { return cc.which == 0 ? val * q_scale : val; }
-    __device__ void store8(int g, int r, int nn, uint4 piece) const
+    // vector epilogue (MFMA engines)
+    static constexpr bool kColScale = true;
+    __device__ float col_scale(int, int nn) const { return nn < d_h ? q_scale : 1.0f; }
+    __device__ float epi(float val, float scale) const { return val * scale; }
+    __device__ bool has_residual() const { return false; }
+    __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const
     {
         const int which = nn / d_h, col = nn - which * d_h;
         T *o = which == 0 ? q : (which == 1 ? k : v);
@@ -138,14 +148,17 @@ template <typename T> struct OutProjProblem {
         if (flags & F_RESIDUAL) val += to_f32(x[at]);
         out[at] = from_f32<T>(val);
     }
-    __device__ float epi(float val, const ColCtx &) const { return val; }
-    __device__ void store8(int g, int r, int nn, uint4 piece) const
+    static constexpr bool kColScale = false;
+    __device__ float col_scale(int, int) const { return 1.0f; }
+    __device__ float epi(float val, float) const { return val; }
+    __device__ size_t at8(int g, int r, int nn) const
     {
         const int bb = g / m, p = g - bb * m;
-        const size_t at = ((size_t)bb * l + p * l_p + r) * d + nn;
-        if (flags & F_RESIDUAL) piece = add8_bf16(piece, *reinterpret_cast<const uint4 *>(x + at));
-        *reinterpret_cast<uint4 *>(out + at) = piece;
+        return ((size_t)bb * l + p * l_p + r) * d + nn;
     }
+    __device__ bool has_residual() const { return flags & F_RESIDUAL; }
+    __device__ uint4 res8(int g, int r, int nn) const { return *reinterpret_cast<const uint4 *>(x + at8(g, r, nn)); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const { *reinterpret_cast<uint4 *>(out + at8(g, r, nn)) = piece; }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -170,6 +183,11 @@ template <typename T> struct UomeUpProblem {
         const int i = clampi(expert_idx[g * kact + s], n);
         return a_in + (size_t)i * d * d_e + (nn - s * d_e);
     }
+    // pipelined engine: no per-segment lookups (K is one segment; the column's expert is resolved
+    // once, before the loop)
+    __device__ uint32_t seg_ctx(int, int) const { return 0; }
+    __device__ const T *a_ptr_ctx(int g, int r, int seg, uint32_t) const { return a_seg_ptr(g, r, seg); }
+    __device__ const T *b_ptr_ctx(int g, int seg, int nn, uint32_t) const { return b_seg_ptr(g, seg, nn); }
     typedef float ColCtx;  // the gate of the column's expert
     __device__ ColCtx col_ctx(int g, int nn) const
     {
@@ -180,8 +198,12 @@ template <typename T> struct UomeUpProblem {
     {
         hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate);
     }
-    __device__ float epi(float val, const ColCtx &gate) const { return silu_fast(val) * gate; }
-    __device__ void store8(int g, int r, int nn, uint4 piece) const
+    static constexpr bool kColScale = true;
+    __device__ float col_scale(int g, int nn) const { return col_ctx(g, nn); }
+    __device__ float epi(float val, float gate) const { return silu_fast(val) * gate; }
+    __device__ bool has_residual() const { return false; }
+    __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const
     {
         *reinterpret_cast<uint4 *>(hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + nn) = piece;
     }
@@ -210,6 +232,10 @@ template <typename T> struct UomeDownProblem {
         const int i = clampi(expert_idx[g * kact + clampi(seg, kact)], n);
         return a_out + (size_t)i * d_e * d + nn;
     }
+    // pipelined engine: the segment's expert, looked up once before the loop
+    __device__ uint32_t seg_ctx(int g, int seg) const { return (uint32_t)clampi(expert_idx[g * kact + clampi(seg, kact)], n); }
+    __device__ const T *a_ptr_ctx(int g, int r, int seg, uint32_t) const { return a_seg_ptr(g, r, seg); }
+    __device__ const T *b_ptr_ctx(int, int, int nn, uint32_t i) const { return a_out + (size_t)i * d_e * d + nn; }
     typedef int ColCtx;
     __device__ ColCtx col_ctx(int, int) const { return 0; }
     __device__ void store(int g, int r, int nn, float val, const ColCtx &) const
@@ -218,13 +244,12 @@ template <typename T> struct UomeDownProblem {
         if (flags & F_RESIDUAL) val += to_f32(u[at]);
         out[at] = from_f32<T>(val);
     }
-    __device__ float epi(float val, const ColCtx &) const { return val; }
-    __device__ void store8(int g, int r, int nn, uint4 piece) const
-    {
-        const size_t at = ((size_t)g * l + r) * d + nn;
-        if (flags & F_RESIDUAL) piece = add8_bf16(piece, *reinterpret_cast<const uint4 *>(u + at));
-        *reinterpret_cast<uint4 *>(out + at) = piece;
-    }
+    static constexpr bool kColScale = false;
+    __device__ float col_scale(int, int) const { return 1.0f; }
+    __device__ float epi(float val, float) const { return val; }
+    __device__ bool has_residual() const { return flags & F_RESIDUAL; }
+    __device__ uint4 res8(int g, int r, int nn) const { return *reinterpret_cast<const uint4 *>(u + ((size_t)g * l + r) * d + nn); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const { *reinterpret_cast<uint4 *>(out + ((size_t)g * l + r) * d + nn) = piece; }
 };
 
 }  // namespace uoe

@@ -7,6 +7,7 @@
 #include "problems.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
+#include "gemm_dma.h"
 
 namespace uoe {
 
@@ -37,10 +38,20 @@ template <typename T> static hipError_t uome_down_generic(const UomeArgs &a, hip
 // MFMA path: bf16 storage, and every K segment (d for GEMM-1, d_e for GEMM-2) a multiple of 32
 static bool uome_mfma_ok(const UomeArgs &a, bool bf16) { return bf16 && a.d % 32 == 0 && a.d_e % 32 == 0; }
 
-// 256x128 tiles (8 waves) pay off once they still fill the chip a few times over
+// Tile choice for the pipelined engine.  256x128 tiles (wave tile 128x64, two workgroups per CU so
+// that one's SiLU/store epilogue runs under the other's MFMAs) once they fill the chip's 512
+// workgroup slots; 128x128 tiles with a 64-deep K-step otherwise.
 static bool uome_big(int b, int l, int ncols)
 {
     return l > 128 && (long)b * ((l + 255) / 256) * ((ncols + 127) / 128) >= 512;
+}
+
+template <typename P> static hipError_t uome_gemm(const P &p, int b, int l, int ncols, int kseg, hipStream_t st)
+{
+    if (uome_big(b, l, ncols)) return launch_gemm_dma<P, 256, 128, 32, 2, 2, 3, 2>(p, b, l, ncols, st);
+    if (l > 64) return kseg % 64 == 0 ? launch_gemm_dma<P, 128, 128, 64, 2, 2, 2, 2>(p, b, l, ncols, st)
+                                      : launch_gemm_dma<P, 128, 128, 32, 2, 2, 4, 2>(p, b, l, ncols, st);
+    return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(p, b, l, ncols, st);
 }
 
 static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
@@ -52,13 +63,7 @@ static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
     up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
     up.hidden = static_cast<bf16_t *>(a.hidden);
     up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
-    const int N = a.k * a.d_e;
-    typedef UomeUpProblem<bf16_t> P;
-    const bool k64 = a.d % 64 == 0;  // K segment = d
-    if (uome_big(a.b, a.l, N)) return launch_gemm_mfma<P, 256, 128, 32, 4, 2>(up, a.b, a.l, N, st);
-    if (a.l > 64) return k64 ? launch_gemm_mfma<P, 128, 128, 64, 2, 2>(up, a.b, a.l, N, st)
-                             : launch_gemm_mfma<P, 128, 128, 32, 2, 2>(up, a.b, a.l, N, st);
-    return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(up, a.b, a.l, N, st);
+    return uome_gemm(up, a.b, a.l, a.k * a.d_e, a.d, st);  // K segment = d
 }
 
 static hipError_t uome_down_mfma(const UomeArgs &a, hipStream_t st)
@@ -70,12 +75,7 @@ static hipError_t uome_down_mfma(const UomeArgs &a, hipStream_t st)
     dn.expert_idx = a.expert_idx;
     dn.out = static_cast<bf16_t *>(a.out);
     dn.l = a.l; dn.d = a.d; dn.n = a.n; dn.kact = a.k; dn.d_e = a.d_e; dn.flags = a.flags;
-    typedef UomeDownProblem<bf16_t> P;
-    const bool k64 = a.d_e % 64 == 0;  // K segment = d_e
-    if (uome_big(a.b, a.l, a.d)) return launch_gemm_mfma<P, 256, 128, 32, 4, 2>(dn, a.b, a.l, a.d, st);
-    if (a.l > 64) return k64 ? launch_gemm_mfma<P, 128, 128, 64, 2, 2>(dn, a.b, a.l, a.d, st)
-                             : launch_gemm_mfma<P, 128, 128, 32, 2, 2>(dn, a.b, a.l, a.d, st);
-    return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(dn, a.b, a.l, a.d, st);
+    return uome_gemm(dn, a.b, a.l, a.d, a.d_e, st);  // K segments = the active experts' d_e rows
 }
 
 hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st)
