@@ -13,9 +13,12 @@
 //      A tile [BM][BK]:  slot (r, pos) holds chunk pos ^ ((r / (16/CA)) % CA),  CA = BK/8 chunks/row;
 //                        the 16 rows a 16-lane phase of a 16-byte fragment read touches then cover
 //                        all 64 banks once.
-//      B tile [BK][BN]:  slot (r, pos) holds chunk pos ^ ((r & 3) << 2); the four 64-byte row
-//                        pieces (rows k0..k0+3) a half-wave touches in one transposing read land
-//                        in four different 16-bank groups.
+//      B tile [BK][BN]:  the four 64-byte row pieces (rows k0..k0+3) a half-wave touches in one
+//                        transposing read must land in four different 16-bank groups.  With a row
+//                        of 256*i bytes (BN % 128 == 0) slot (r, pos) holds chunk
+//                        pos ^ ((r & 3) << 2); with a row of 256*i + 128 bytes (BN % 128 == 64)
+//                        odd and even rows already differ by 32 banks and slot (r, pos) holds
+//                        chunk pos ^ (((r >> 1) & 1) << 2).
 //  * The compiler cannot see these loads (they are inline assembly), so their completion is
 //    waited for by hand: loads complete in issue order, and at the top of K-step t the wave waits
 //    until at most the loads of the STAGES-2 younger steps are outstanding (s_waitcnt vmcnt), then
@@ -25,8 +28,8 @@
 //    K loop: a compiler-inserted wait for it would drain the whole pipeline.  Per-segment routing
 //    lookups are therefore taken once, before the loop, into a small LDS table (seg_ctx).
 //
-// Requirements (checked by the callers): kseg() % BK == 0, BN in {128, 256}, N % 8 == 0, at most
-// 64 K segments.  M and N tails are handled by clamping the load addresses to a valid row / chunk
+// Requirements (checked by the callers): kseg() % BK == 0, N % 8 == 0, at most 64 K segments; BN a
+// multiple of 64 and both operand tiles a whole number of load instructions per wave.  M and N tails are handled by clamping the load addresses to a valid row / chunk
 // of the same tile (the results of clamped rows and columns are never stored).
 #pragma once
 #include "gemm_mfma.h"
@@ -57,8 +60,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int CA = BK / 8, CB = BN / 8;              // 16-byte chunks per A row / B row
-    constexpr int ARD = 64 / CA, BRD = 64 / CB;          // rows covered by one load instruction
-    constexpr int A_DMA = BM / (ARD * NW), B_DMA = BK / (BRD * NW);  // instructions per wave per step
+    constexpr int ARD = 64 / CA;                         // A rows covered by one load instruction
+    constexpr int A_INSTR = BM * CA / 64;                // load instructions that make up the A tile
+    // instructions per wave per step; when the A tile has fewer instructions than waves the surplus
+    // waves repeat one (same bytes to the same place), so that every wave counts the same loads
+    constexpr int A_DMA = (A_INSTR + NW - 1) / NW, B_DMA = BK * CB / (64 * NW);
     constexpr int A_STAGE = BM * BK * 2, B_STAGE = BK * BN * 2, STAGE_BYTES = A_STAGE + B_STAGE;
     constexpr int SPITCH = WN + 8;                       // epilogue staging pitch in elements
     constexpr int S_BYTES = NW * WM * SPITCH * 2;
@@ -67,9 +73,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     constexpr int MAX_SEG = 64;
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
     static_assert(BK == 32 || BK == 64, "BK is 32 or 64");
-    static_assert(BN == 128 || BN == 256, "BN is 128 or 256");
-    static_assert(BM % (ARD * NW) == 0 && BK % (BRD * NW) == 0, "tile does not divide into whole load instructions");
-    static_assert((NW * BRD) % 4 == 0 && (NW * ARD) % 16 == 0, "per-lane chunk permutation must not depend on the instruction");
+    static_assert(BN % 64 == 0, "BN is a multiple of 64");
+    static_assert((BM * CA) % 64 == 0 && (BK * CB) % (64 * NW) == 0, "tile does not divide into whole load instructions");
+    static_assert(A_DMA == 1 || ((NW * ARD) % 16 == 0 && A_INSTR % NW == 0), "the A chunk permutation must not depend on the instruction");
     static_assert(STAGES >= 2 && (STAGES - 2) * (A_DMA + B_DMA) < 64, "vmcnt range");
 
     __shared__ __align__(1024) unsigned char lds_raw[LDS_BYTES];
@@ -107,13 +113,17 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
 
     // Load roles.  Instruction i of this wave fills block (i*NW + wave) of 1 KiB in the A (or B)
     // part of a stage; lane -> slot (row, pos) inside the block.
-    const int a_row0 = wave * ARD + lane / CA, a_pos = lane % CA;   // + i*NW*ARD rows
-    const int b_row0 = wave * BRD + lane / CB, b_pos = lane % CB;   // + i*NW*BRD rows
+    const int a_blk0 = wave % A_INSTR;                              // + i*NW blocks
+    const int a_row0 = a_blk0 * ARD + lane / CA, a_pos = lane % CA; // + i*NW*ARD rows
     const int a_chunk = a_pos ^ ((a_row0 / (16 / CA)) % CA);        // independent of i: NW*ARD % 16 == 0
-    int b_chunk = b_pos ^ ((b_row0 & 3) << 2);                      // independent of i: NW*BRD % 4 == 0
-    if (n0 + b_chunk * 8 >= N) b_chunk = 0;                         // N tail: any valid chunk
     const uint16_t *a_ptr[A_DMA];
-    const uint16_t *b_ptr;
+    // When a B row is a whole fraction of one load instruction (and the permutation does not depend
+    // on the instruction) a lane keeps one column for all its instructions: one base pointer.
+    constexpr bool B_UNIFORM = 64 % CB == 0 && (NW * (64 / CB)) % 4 == 0;
+    constexpr int B_PTRS = B_UNIFORM ? 1 : B_DMA;
+    constexpr int BRD = B_UNIFORM ? 64 / CB : 0;         // B rows covered by one load instruction
+    const uint16_t *b_ptr[B_PTRS];
+    auto b_swizzle = [](int row) { return (BN % 128 == 0 ? (row & 3) : ((row >> 1) & 1)) << 2; };
     auto resolve_segment = [&](int seg) {
         const uint32_t ctx = segtab[seg < MAX_SEG ? seg : 0];
 #pragma unroll
@@ -122,15 +132,23 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
             row = row < M ? row : M - 1;
             a_ptr[i] = reinterpret_cast<const uint16_t *>(p.a_ptr_ctx(g, row, seg, ctx)) + a_chunk * 8;
         }
-        b_ptr = reinterpret_cast<const uint16_t *>(p.b_ptr_ctx(g, seg, n0 + b_chunk * 8, ctx)) + (long)b_row0 * bstride;
+#pragma unroll
+        for (int i = 0; i < B_PTRS; ++i) {  // B slots in row-major order: slot -> (row, pos)
+            const int slot = (i * NW + wave) * 64 + lane;
+            const int row = slot / CB, pos = slot - row * CB;
+            int col = n0 + (pos ^ b_swizzle(row)) * 8;
+            col = col < N ? col : n0;  // N tail: any valid chunk
+            b_ptr[i] = reinterpret_cast<const uint16_t *>(p.b_ptr_ctx(g, seg, col, ctx)) + (long)row * bstride;
+        }
     };
     auto issue = [&](int buf, int off) {  // K-step at offset `off` of the current segment -> stage buffer buf
         const uint32_t sbase = lds_base + buf * STAGE_BYTES + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < A_DMA; ++i) dma_load16(a_ptr[i] + off, sbase + i * NW * 1024);
+        for (int i = 0; i < A_DMA; ++i) dma_load16(a_ptr[i] + off, sbase + (a_blk0 - wave + i * NW) * 1024);
 #pragma unroll
         for (int i = 0; i < B_DMA; ++i)
-            dma_load16(b_ptr + (long)(off + i * NW * BRD) * bstride, sbase + A_STAGE + i * NW * 1024);
+            dma_load16(b_ptr[B_UNIFORM ? 0 : i] + (long)(off + (B_UNIFORM ? i * NW * BRD : 0)) * bstride,
+                       sbase + A_STAGE + i * NW * 1024);
     };
 
     const int KT = K / BK;
@@ -159,7 +177,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int chunk = (wn0 + j * 32) / 8 + colhalf * 2 + ((lane & 3) >> 1);
-            b_off[j] = A_STAGE + (lh * 8 + x) * (BN * 2) + ((chunk ^ (x << 2)) * 16) + (lane & 1) * 8;
+            b_off[j] = A_STAGE + (lh * 8 + x) * (BN * 2) + ((chunk ^ b_swizzle(x)) * 16) + (lane & 1) * 8;
         }
     }
 
@@ -217,9 +235,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
 #pragma unroll
                     for (int u = 0; u < PPS; ++u) {
                         const int q = (ks * TM + i) * PPS + u;  // compile-time after unrolling
-                        if (q < A_DMA) dma_load16(a_ptr[q < A_DMA ? q : 0] + f_off, f_base + q * NW * 1024);
+                        if (q < A_DMA) dma_load16(a_ptr[q < A_DMA ? q : 0] + f_off, f_base + (a_blk0 - wave + q * NW) * 1024);
                         else if (q < PIECES)
-                            dma_load16(b_ptr + (long)(f_off + (q - A_DMA) * NW * BRD) * bstride,
+                            dma_load16(b_ptr[!B_UNIFORM && q >= A_DMA && q < PIECES ? q - A_DMA : 0] +
+                                           (long)(f_off + (B_UNIFORM ? (q - A_DMA) * NW * BRD : 0)) * bstride,
                                        f_base + A_STAGE + (q - A_DMA) * NW * 1024);
                     }
                     __builtin_amdgcn_sched_barrier(0);

@@ -87,6 +87,10 @@ template <typename T> struct QkvProblem {
         else if (cc.which == 1) k[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
         else v[((size_t)g * l_a + r) * d_h + cc.col] = from_f32<T>(val);
     }
+    // pipelined engine: K is one segment, rows and columns are resolved once before the loop
+    __device__ uint32_t seg_ctx(int, int) const { return 0; }
+    __device__ const T *a_ptr_ctx(int g, int r, int seg, uint32_t) const { return a_seg_ptr(g, r, seg); }
+    __device__ const T *b_ptr_ctx(int g, int seg, int nn, uint32_t) const { return b_seg_ptr(g, seg, nn); }
     // vector epilogue (MFMA engines)
     static constexpr bool kColScale = true;
     __device__ float col_scale(int, int nn) const { return nn < d_h ? q_scale : 1.0f; }
@@ -148,6 +152,25 @@ template <typename T> struct OutProjProblem {
         if (flags & F_RESIDUAL) val += to_f32(x[at]);
         out[at] = from_f32<T>(val);
     }
+    // pipelined engine: per K segment, (slot*c + pick) in bits 0-19, the expert in bits 20-25 and the
+    // hi/lo part in bit 26, looked up once before the loop (needs kact*c < 2^20)
+    __device__ uint32_t seg_ctx(int g, int seg) const
+    {
+        const int bb = g / m;
+        const int e = clampi(parts == 2 ? seg >> 1 : seg, kact);
+        const int ent = clampi(inv_ent[(size_t)g * kact + e], kact * c);
+        const int i = clampi(expert_idx[bb * kact + ent / c], n);
+        return (uint32_t)ent | ((uint32_t)i << 20) | ((parts == 2 && (seg & 1)) ? 1u << 26 : 0u);
+    }
+    __device__ const T *a_ptr_ctx(int g, int r, int, uint32_t ctx) const
+    {
+        const int bb = g / m;
+        const int ent = (int)(ctx & 0xFFFFFu);
+        const int s = ent / c, t = ent - s * c;
+        const T *src = (ctx >> 26) & 1u ? o_lo : o;
+        return src + (((size_t)bb * kact + s) * l_a + t * l_p + r) * d_h;
+    }
+    __device__ const T *b_ptr_ctx(int, int, int nn, uint32_t ctx) const { return wo + (size_t)((ctx >> 20) & 0x3Fu) * d_h * d + nn; }
     static constexpr bool kColScale = false;
     __device__ float col_scale(int, int) const { return 1.0f; }
     __device__ float epi(float val, float) const { return val; }

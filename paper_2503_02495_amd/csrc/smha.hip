@@ -13,6 +13,7 @@
 #include "problems.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
+#include "gemm_dma.h"
 
 namespace uoe {
 
@@ -462,16 +463,17 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
     // 128-row tiles for long units (measured faster from l_a = 512 up), 32-row tiles for short ones
     const bool tall = l_a >= 256 && (long)units * ((l_a + 127) / 128) >= 128, k64 = a.d % 64 == 0;
-    if (a.d_h == 32) {
-        if (tall) err = launch_gemm_mfma<QP, 128, 96, 32, 4, 1>(qp, units, l_a, 96, st);
-        else if (k64) err = launch_gemm_mfma<QP, 32, 96, 64, 1, 1>(qp, units, l_a, 96, st);
-        else err = launch_gemm_mfma<QP, 32, 96, 32, 1, 1>(qp, units, l_a, 96, st);
+    if (a.d_h == 32) {  // N = 96: 128-column tiles with the tail columns clamped
+        if (tall) err = launch_gemm_dma<QP, 128, 128, 32, 2, 2, 4, 2>(qp, units, l_a, 96, st);
+        else if (k64) err = launch_gemm_dma<QP, 32, 128, 64, 1, 2, 4>(qp, units, l_a, 96, st);
+        else err = launch_gemm_dma<QP, 32, 128, 32, 1, 2, 4>(qp, units, l_a, 96, st);
     } else if (a.d_h == 64) {
-        if (tall) err = launch_gemm_mfma<QP, 128, 192, 32, 4, 1>(qp, units, l_a, 192, st);
-        else if (k64) err = launch_gemm_mfma<QP, 32, 192, 64, 1, 2>(qp, units, l_a, 192, st);
-        else err = launch_gemm_mfma<QP, 32, 192, 32, 1, 2>(qp, units, l_a, 192, st);
+        if (tall) err = k64 ? launch_gemm_dma<QP, 128, 192, 64, 2, 2, 3>(qp, units, l_a, 192, st)
+                            : launch_gemm_dma<QP, 128, 192, 32, 2, 2, 4>(qp, units, l_a, 192, st);
+        else if (k64) err = launch_gemm_dma<QP, 32, 192, 64, 1, 2, 4>(qp, units, l_a, 192, st);
+        else err = launch_gemm_dma<QP, 32, 192, 32, 1, 2, 4>(qp, units, l_a, 192, st);
     } else {
-        err = launch_gemm_mfma<QP, 128, 128, 32, 2, 2>(qp, units, l_a, 3 * a.d_h, st);
+        err = launch_gemm_dma<QP, 128, 128, 32, 2, 2, 4, 2>(qp, units, l_a, 3 * a.d_h, st);
     }
     if (err != hipSuccess) return err;
     if ((err = launch_rope<bf16_t>(a, st)) != hipSuccess) return err;
@@ -484,8 +486,12 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
         op.o_lo = static_cast<const bf16_t *>(a.o_lo);
         op.parts = 2;
     }
-    if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
-    return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
+    if ((long)a.k * a.c >= (1L << 20)) {  // segment context of the pipelined engine would not fit
+        if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
+        return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
+    }
+    if (l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 4, 4, 2>(op, a.b * a.m, l_p, a.d, st);
+    return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, a.b * a.m, l_p, a.d, st);
 }
 
 hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st)

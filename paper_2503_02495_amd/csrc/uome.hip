@@ -49,6 +49,9 @@ static bool uome_big(int b, int l, int ncols)
 template <typename P> static hipError_t uome_gemm(const P &p, int b, int l, int ncols, int kseg, hipStream_t st)
 {
     if (uome_big(b, l, ncols)) return launch_gemm_dma<P, 256, 128, 32, 2, 2, 3, 2>(p, b, l, ncols, st);
+    // 64-row tiles while 128x128 tiles would leave CUs without work
+    if (l > 64 && kseg % 64 == 0 && (long)b * ((l + 127) / 128) * ((ncols + 127) / 128) < 256)
+        return launch_gemm_dma<P, 64, 128, 64, 2, 2, 3, 2>(p, b, l, ncols, st);
     if (l > 64) return kseg % 64 == 0 ? launch_gemm_dma<P, 128, 128, 64, 2, 2, 2, 2>(p, b, l, ncols, st)
                                       : launch_gemm_dma<P, 128, 128, 32, 2, 2, 4, 2>(p, b, l, ncols, st);
     return launch_gemm_mfma<P, 64, 64, 32, 2, 2>(p, b, l, ncols, st);
