@@ -2,10 +2,15 @@
 // data-selection router (Eq. 13, 14, 17).
 //
 // Kernels:
-//   route_partial<E>  : expert router.  A workgroup owns (chunk of tokens, sample); each wave
-//                       streams token rows of x and the matching rows of the n W_E slices with
-//                       16-byte loads and keeps n running dot products per lane.  HBM-bound: x and
-//                       W_E are read once (a W_E chunk is shared by the b samples through L2).
+//   route_expert_mfma : expert router, bf16.  Eq. 21 is a [b, l*d] x [l*d, n] product with a huge
+//                       inner dimension: a workgroup owns a chunk of the flat l*d axis for up to
+//                       64 samples and all experts, its waves stream x and W_E straight from
+//                       global memory into v_mfma_f32_16x16x32_bf16 fragments (rows = samples,
+//                       columns = experts).  Every byte of x and of W_E is requested once.
+//   route_partial<E>  : expert router on the vector ALU (fp32 storage).  A workgroup owns (chunk
+//                       of tokens, sample); each wave streams token rows of x and the matching rows
+//                       of the n W_E slices and keeps n running dot products per lane (a W_E chunk
+//                       is shared by the b samples through L2).
 //   route_data_mfma   : data router, bf16.  t1 = x W_B for 16 tokens per wave as
 //                       v_mfma_f32_16x16x32_bf16 (A fragments straight from global, W_B^T staged in
 //                       LDS), then the chunk's rows of W_A fold t1 into a partial [n,m] logit tile.
@@ -32,6 +37,14 @@ int route_tokens_per_chunk(int b, int l)
     if (tc > 64) tc = 64;
     if (tc > l) tc = l;
     return (int)tc;
+}
+
+// Expert router, MFMA kernel: tokens per chunk.  The chunk count does not depend on b (a workgroup
+// takes all samples of its chunk), so aim for ~512 chunks.
+int route_expert_mfma_tokens_per_chunk(int l)
+{
+    const int tc = l / 512;
+    return tc < 1 ? 1 : tc;
 }
 
 // Data router: tokens per chunk and whether the MFMA kernel applies.  waves*16 tokens per chunk for
@@ -262,6 +275,81 @@ __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a
     }
 }
 
+// Expert router (Eq. 21), bf16, MFMA.  Workgroup = 4 waves = (chunk of a.tc tokens, i.e. a.tc*d
+// consecutive elements of the flat l*d axis; group of RT*16 samples).  The chunk is cut into steps of
+// 32 elements; wave w takes a contiguous quarter of the steps.  In one step lane (r = lane%16,
+// q = lane/16) loads elements [32*step + 8*q, +8) of sample row r (one A fragment per 16 samples)
+// and of expert row r (one B fragment per 16 experts); rows past b or n repeat the last valid row
+// (they only produce output rows / columns that are never stored).  The last step of a chunk may
+// be partial (multiples of 8 elements): its missing slices are zeroed.  Accumulator register v of
+// a lane is Z[sample 4*q + v][expert r].  The four waves' tiles are summed in wave order.
+template <int RT, int CT>
+__global__ __launch_bounds__(256) void route_expert_mfma_kernel(RouteArgs a)
+{
+    __shared__ float zsh[4][RT * 16][CT * 16 + 1];
+    constexpr int U = 4;  // steps whose loads are in flight together
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int chunk = blockIdx.x, b0 = blockIdx.y * RT * 16;
+    const int b = a.b, n = a.n;
+    const long ld = (long)a.l * a.d;
+    const long c0 = (long)chunk * a.tc * a.d;
+    const long c1 = min(ld, c0 + (long)a.tc * a.d);
+    const int steps = (int)((c1 - c0 + 31) / 32);
+    const int per = (steps + 3) / 4;
+    const int s0 = wave * per, s1 = min(steps, s0 + per);
+
+    const uint16_t *xp[RT], *wp[CT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) xp[t] = static_cast<const uint16_t *>(a.x) + (size_t)min(b0 + t * 16 + r, b - 1) * ld;
+#pragma unroll
+    for (int t = 0; t < CT; ++t) wp[t] = static_cast<const uint16_t *>(a.w_e) + (size_t)min(t * 16 + r, n - 1) * ld;
+    rt_f32x4 acc[RT][CT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int u = 0; u < CT; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.f;
+
+    for (int s = s0; s < s1; s += U) {
+        uint4 xa[U][RT], wb[U][CT];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long e = c0 + (long)(s + u) * 32 + q * 8;
+            const bool ok = s + u < s1 && e < c1;
+            const long ec = ok ? e : c0;  // any valid address
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
+                xa[u][t] = *reinterpret_cast<const uint4 *>(xp[t] + ec);
+                if (!ok) xa[u][t] = make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int t = 0; t < CT; ++t) wb[u][t] = *reinterpret_cast<const uint4 *>(wp[t] + ec);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+#pragma unroll
+                for (int v = 0; v < CT; ++v)
+                    acc[t][v] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(rt_bf16x8, xa[u][t]),
+                                                                        __builtin_bit_cast(rt_bf16x8, wb[u][v]), acc[t][v], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int u = 0; u < CT; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) zsh[wave][t * 16 + q * 4 + v][u * 16 + r] = acc[t][u][v];
+    __syncthreads();
+    for (int o = tid; o < RT * 16 * CT * 16; o += 256) {
+        const int row = o / (CT * 16), col = o - row * (CT * 16);
+        if (b0 + row < b && col < n)
+            a.zpart[((size_t)chunk * b + b0 + row) * n + col] = (zsh[0][row][col] + zsh[1][row][col]) + (zsh[2][row][col] + zsh[3][row][col]);
+    }
+}
+
 // Sums the data router's per-chunk partials in a fixed order (deterministic).  A block owns 16
 // reduced values of one sample; thread (value, chunk group) adds every 16th chunk, then the 16
 // group sums are added in group order.  (The expert router's n values per sample are summed by
@@ -289,24 +377,54 @@ __global__ __launch_bounds__(256) void route_reduce_kernel(RouteArgs a)
 }
 
 // One workgroup per (expert i, sample): top-c of row i of the patch gate; the workgroup of expert 0
-// also does the sample's top-k over experts.  LDS: ranking keys of the row [m] + kept flags [m].
+// also does the sample's top-k over experts.  LDS: ranking keys of the row [m] + kept flags [m]
+// (+ the sample's n*m noisy logits when they fit: `staged`).  The kernel is a chain of small
+// dependent steps, so everything it needs from global memory is fetched up front by loops whose
+// loads do not depend on each other (unrolled: several in flight), never inside the chains.
 constexpr int SELECT_THREADS = 128;
-__global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs a, int has_e, int has_d)
+constexpr size_t SELECT_STAGE_MAX = 32 * 1024;  // bytes of logits staged in LDS
+__global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs a, int has_e, int has_d, int staged)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, i = blockIdx.x, bb = blockIdx.y;
     const int n = a.n, m = a.m, c = a.c, k = a.k, nm = n * m;
     float *key = reinterpret_cast<float *>(smem);
     unsigned char *kept = smem + (size_t)m * sizeof(float);
+    float *glog = reinterpret_cast<float *>(smem + (((size_t)m * 5 + 15) & ~(size_t)15));  // [n*m] when staged
     __shared__ float ge[32];
-    __shared__ float zpart_sum[4][32];
+    __shared__ float zpart_sum[SELECT_THREADS];
     __shared__ unsigned char ekept[32];
     const float *gsrc = a.gred + (size_t)bb * nm;
+
+    // the expert router's per-chunk partials, summed in a fixed order: thread = (chunk group, expert)
+    const int groups = SELECT_THREADS / n;  // >= 4
+    float zs = 0.f;
+    if (has_e && i == 0 && tid < groups * n) {
+        const int vi = tid % n, cg = tid / n;
+        const float *src = a.zpart + (size_t)bb * n + vi;
+        const size_t stride = (size_t)a.b * n;
+#pragma unroll 8
+        for (int ch = cg; ch < a.nchunks; ch += groups) zs += src[(size_t)ch * stride];
+    }
+    if (has_d && staged) {
+        const float *nzs = a.noise_p ? a.noise_p + (size_t)bb * nm : nullptr;
+#pragma unroll 8
+        for (int idx = tid; idx < nm; idx += SELECT_THREADS) glog[idx] = gsrc[idx] + (nzs ? nzs[idx] : 0.f);
+        __syncthreads();
+    }
 
     // ---- data selection: Eq. 13 logits (+noise) -> Eq. 14 gate -> Eq. 17 top-c of row i
     for (int j = tid; j < m; j += SELECT_THREADS) {
         float kv = 0.f, gate = 1.f;
-        if (has_d) {  // softmax over the n experts of patch j
+        if (has_d && staged) {  // softmax over the n experts of patch j, logits from LDS
+            float mx = -INFINITY;
+            for (int ii = 0; ii < n; ++ii) mx = fmaxf(mx, glog[ii * m + j]);
+            float den = 0.f;
+            for (int ii = 0; ii < n; ++ii) den += expf(glog[ii * m + j] - mx);
+            const float own = glog[i * m + j];
+            gate = expf(own - mx) / den;
+            kv = (own - mx) - logf(den);  // ranking key: see below
+        } else if (has_d) {  // the same straight from global memory
             const float *col = gsrc + j;
             const float *nz = a.noise_p ? a.noise_p + (size_t)bb * nm + j : nullptr;
             float mx = -INFINITY, own = 0.f;
@@ -349,18 +467,12 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     // ---- expert selection: Eq. 21 logits (+noise) -> softmax -> Eq. 22 top-k
     // The softmax is strictly increasing in the logit within a sample, so the k largest gates are
     // the k largest logits: rank on the logits, which cannot underflow.
-    if (has_e) {  // sum the expert router's per-chunk partials: 4 chunk groups x up to 32 experts
-        const int vi = tid & 31, cg = tid >> 5;
-        float s = 0.f;
-        if (vi < n)
-            for (int ch = cg; ch < a.nchunks; ch += 4) s += a.zpart[((size_t)ch * a.b + bb) * n + vi];
-        zpart_sum[cg][vi] = s;
-    }
+    if (has_e && tid < groups * n) zpart_sum[tid] = zs;  // index = group * n + expert
     __syncthreads();
     float z = 0.f;
     if (tid < n) {
         if (has_e) {
-            z = (zpart_sum[0][tid] + zpart_sum[1][tid]) + (zpart_sum[2][tid] + zpart_sum[3][tid]);
+            for (int cg = 0; cg < groups; ++cg) z += zpart_sum[cg * n + tid];
             if (a.noise_e) z += a.noise_e[(size_t)bb * n + tid];
         }
         ge[tid] = z;
@@ -421,9 +533,21 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
 {
     const bool has_e = a.w_e != nullptr, has_d = a.w_b != nullptr;
     hipError_t err = hipSuccess;
-    if (has_e) {
-        err = bf16 ? launch_partial_n<bf16_t>(a, true, false, st) : launch_partial_n<float>(a, true, false, st);
-        if (err != hipSuccess) return err;
+    if (has_e && bf16) {  // a.tc / a.nchunks follow route_expert_mfma_tokens_per_chunk
+        const int rt = a.b > 32 ? 4 : (a.b > 16 ? 2 : 1);
+        const dim3 grid(a.nchunks, (a.b + rt * 16 - 1) / (rt * 16));
+        if (a.n <= 16) {
+            if (rt == 4) hipLaunchKernelGGL((route_expert_mfma_kernel<4, 1>), grid, dim3(256), 0, st, a);
+            else if (rt == 2) hipLaunchKernelGGL((route_expert_mfma_kernel<2, 1>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((route_expert_mfma_kernel<1, 1>), grid, dim3(256), 0, st, a);
+        } else {
+            if (rt == 4) hipLaunchKernelGGL((route_expert_mfma_kernel<4, 2>), grid, dim3(256), 0, st, a);
+            else if (rt == 2) hipLaunchKernelGGL((route_expert_mfma_kernel<2, 2>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((route_expert_mfma_kernel<1, 2>), grid, dim3(256), 0, st, a);
+        }
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    } else if (has_e) {
+        if ((err = launch_partial_n<float>(a, true, false, st)) != hipSuccess) return err;
     }
     if (has_d) {
         if (route_data_uses_mfma(a.b, a.l, a.d, a.n, bf16)) {
@@ -453,9 +577,12 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    const size_t sh = (size_t)a.m * (sizeof(float) + 1);
+    size_t sh = (size_t)a.m * (sizeof(float) + 1);
+    const size_t stage_bytes = (size_t)a.n * a.m * sizeof(float);
+    const bool staged = has_d && stage_bytes <= SELECT_STAGE_MAX;
+    if (staged) sh = ((sh + 15) & ~(size_t)15) + stage_bytes;
     hipLaunchKernelGGL(route_select_kernel, dim3(a.n, a.b), dim3(SELECT_THREADS), sh, st, a, (int)has_e,
-                       (int)has_d);
+                       (int)has_d, (int)staged);
     return hipGetLastError();
 }
 
