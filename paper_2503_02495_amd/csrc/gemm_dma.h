@@ -76,6 +76,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     static_assert(BN % 64 == 0, "BN is a multiple of 64");
     static_assert((BM * CA) % 64 == 0 && (BK * CB) % (64 * NW) == 0, "tile does not divide into whole load instructions");
     static_assert(A_DMA == 1 || ((NW * ARD) % 16 == 0 && A_INSTR % NW == 0), "the A chunk permutation must not depend on the instruction");
+    static_assert(BN / 8 <= NW * 64, "one column-scale entry per thread");
     static_assert(STAGES >= 2 && (STAGES - 2) * (A_DMA + B_DMA) < 64, "vmcnt range");
 
     __shared__ __align__(1024) unsigned char lds_raw[LDS_BYTES];
@@ -97,11 +98,15 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     const long bstride = p.b_stride();
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
 
-    // routing lookups of every K segment, once
     const int nseg = K / KSEG;
-    if (tid < nseg && tid < MAX_SEG) segtab[tid] = p.seg_ctx(g, tid);
-    fill_col_scale<P, BN>(p, coltab, g, n0, N, tid, NW * 64);
-    __syncthreads();
+    // table entries of this thread (at most one of each), requested now and stored after the first
+    // operand loads have been issued
+    uint32_t my_seg = 0;
+    float my_scale = 1.0f;
+    if (tid < nseg && tid < MAX_SEG) my_seg = p.seg_ctx(g, tid);
+    if constexpr (P::kColScale) {
+        if (tid < BN / 8) my_scale = p.col_scale(g, n0 + tid * 8 < N ? n0 + tid * 8 : 0);
+    }
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -124,8 +129,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     constexpr int BRD = B_UNIFORM ? 64 / CB : 0;         // B rows covered by one load instruction
     const uint16_t *b_ptr[B_PTRS];
     auto b_swizzle = [](int row) { return (BN % 128 == 0 ? (row & 3) : ((row >> 1) & 1)) << 2; };
-    auto resolve_segment = [&](int seg) {
-        const uint32_t ctx = segtab[seg < MAX_SEG ? seg : 0];
+    auto resolve_segment = [&](int seg, uint32_t ctx) {
 #pragma unroll
         for (int i = 0; i < A_DMA; ++i) {
             int row = m0 + a_row0 + i * NW * ARD;
@@ -153,8 +157,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
 
     const int KT = K / BK;
     int nseg_next = 0, noff = 0, nbuf = 0;  // segment / offset / buffer of the next K-step to fetch
+    // The first STAGES-1 K-steps are fetched before anything else: their segments' contexts are
+    // looked up directly (every lane the same address), so that the first operand bytes are only one
+    // dependent load away from the kernel's start.  The lookup tables the loop and the epilogue use
+    // are filled afterwards, under those loads, and published by the loop's first barrier.
     auto fetch_next = [&]() {
-        if (noff == 0) resolve_segment(nseg_next);
+        if (noff == 0) resolve_segment(nseg_next, p.seg_ctx(g, nseg_next));
         issue(nbuf, noff);
         nbuf = nbuf + 1 == STAGES ? 0 : nbuf + 1;
         noff += BK;
@@ -166,6 +174,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < KT) fetch_next();
+    if (tid < nseg && tid < MAX_SEG) segtab[tid] = my_seg;
+    if (P::kColScale && tid < BN / 8) coltab[tid] = my_scale;
 
     // fragment read offsets (bytes inside a stage)
     uint32_t a_off[BK / 16], b_off[TN];
@@ -193,7 +203,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
         int f_off = 0;
         uint32_t f_base = 0;
         if constexpr (FETCH) {
-            if (noff == 0) resolve_segment(nseg_next);
+            if (noff == 0) resolve_segment(nseg_next, segtab[nseg_next < MAX_SEG ? nseg_next : 0]);
             f_off = noff;
             f_base = lds_base + nbuf * STAGE_BYTES + wave * 1024;
             nbuf = nbuf + 1 == STAGES ? 0 : nbuf + 1;
