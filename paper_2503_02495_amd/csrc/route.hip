@@ -55,10 +55,16 @@ static int data_mfma_waves(int b, int l)
     if ((long)((l + 31) / 32) * b >= 256) return 2;
     return 1;
 }
+// LDS of the MFMA data router: W_B as it is, [d][np] in blocks of 8 rows (see the kernel), then t1.
+static size_t data_mfma_wb_bytes(int n, int d)
+{
+    const int np = (n + 15) & ~15;
+    return (size_t)((d + 7) / 8) * (8 * np * 2 + (np == 16 ? 128 : 32));
+}
 static size_t data_mfma_lds(int n, int d, int waves)
 {
-    const int np = (n + 15) & ~15, dp = ((d + 31) & ~31) + 8;
-    return (size_t)np * dp * 2 + (size_t)waves * 16 * np * sizeof(float);
+    const int np = (n + 15) & ~15;
+    return data_mfma_wb_bytes(n, d) + (size_t)waves * 16 * np * sizeof(float);
 }
 bool route_data_uses_mfma(int b, int l, int d, int n, bool bf16)
 {
@@ -183,42 +189,38 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_partial_kernel(RouteArgs 
 typedef __bf16 rt_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float rt_f32x4 __attribute__((ext_vector_type(4)));
 
+typedef short rt_s16x4 __attribute__((ext_vector_type(4)));
+typedef rt_s16x4 __attribute__((address_space(3))) * rt_lds_s16x4_ptr;
+
 // Data router (Eq. 13), bf16, MFMA.  Workgroup = WAVES waves = WAVES*16 tokens of one sample.
 // MFMA 16x16x32 operand layout: lane = (row r = lane%16, k-slice 8*(lane/16)); accumulator register q
 // of a lane is output row 4*(lane/16)+q, column lane%16.
+// W_B [d, n] is copied to LDS as it is (rows of np = 16 or 32 columns; columns >= n are left as
+// they are: they only feed output columns that are never read) and the B fragments (8 consecutive k
+// of one expert column) are taken with the transposing LDS read: in a group of 16 lanes, lane j
+// points at row k0 + j/4, columns 4*(j%4)..+3, and lane i receives column i, rows k0..k0+3.  Rows are
+// stored in blocks of 8 with a pad after each block (128 bytes for 32-byte rows, 32 bytes for
+// 64-byte rows) so that the row groups of the four k-slices fall into different banks.
 template <int WAVES, int NTILE>
 __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NTHREADS = WAVES * 64, TC = WAVES * 16;
+    constexpr int NP = NTILE * 16, ROWB = NP * 2, BLK = 8 * ROWB + (NP == 16 ? 128 : 32);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = blockIdx.x, bb = blockIdx.y;
     const int n = a.n, d = a.d, l = a.l, m = a.m;
-    const int np = (n + 15) & ~15, dp = ((d + 31) & ~31) + 8;  // padded expert rows / row pitch
+    const int np = NP;
     const int t0 = chunk * TC, tcur = min(TC, l - t0);
-    uint16_t *wb_t = reinterpret_cast<uint16_t *>(smem);        // [np][dp]: W_B transposed, zero padded
-    float *t1s = reinterpret_cast<float *>(smem + (size_t)np * dp * 2);  // [TC][np]
+    unsigned char *wb = smem;                                   // W_B rows, blocked
+    float *t1s = reinterpret_cast<float *>(smem + (size_t)((d + 7) / 8) * BLK);  // [TC][np]
 
-    const uint16_t *w_b = static_cast<const uint16_t *>(a.w_b);
-    for (int idx = tid; idx < np * dp / 2; idx += NTHREADS) reinterpret_cast<uint32_t *>(wb_t)[idx] = 0u;
-    __syncthreads();
-    for (int idx = tid; idx < n * d; idx += NTHREADS) {  // coalesced read of W_B [d, n], transposed write
-        const int e = idx / n, i = idx - e * n;
-        wb_t[i * dp + e] = w_b[idx];
-    }
-    __syncthreads();
-
+    // A fragments of the first steps are requested before the staging copy so both are in flight together
     const int r = lane & 15, ksl = (lane >> 4) * 8;
     const int trow = min(t0 + wave * 16 + r, l - 1);  // rows past the end repeat the last token; never used
     const uint16_t *xr = static_cast<const uint16_t *>(a.x) + ((size_t)bb * l + trow) * d;
-    rt_f32x4 acc[NTILE];  // NTILE tiles of 16 experts
-#pragma unroll
-    for (int t = 0; t < NTILE; ++t)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc[t][q] = 0.f;
     constexpr int UN = 4;  // k-steps whose A fragments are in flight together
-    for (int k0 = 0; k0 < d; k0 += 32 * UN) {
-        uint4 av[UN];
+    auto load_a = [&](int k0, uint4 (&av)[UN]) {
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int kk = k0 + u * 32 + ksl;
@@ -226,16 +228,62 @@ __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a
             av[u] = *reinterpret_cast<const uint4 *>(xr + (ok ? kk : 0));
             if (!ok) av[u] = make_uint4(0, 0, 0, 0);
         }
+    };
+    uint4 av[UN];
+    load_a(0, av);
+
+    const uint16_t *w_b = static_cast<const uint16_t *>(a.w_b);
+    auto row_at = [&](int e) { return wb + (size_t)(e >> 3) * BLK + (e & 7) * ROWB; };
+    if ((n & 7) == 0) {  // 16-byte pieces never straddle a row
+        const int pr = n >> 3;
+#pragma unroll 4
+        for (int idx = tid; idx < d * pr; idx += NTHREADS) {
+            const int e = idx / pr, pc = idx - e * pr;
+            *reinterpret_cast<uint4 *>(row_at(e) + pc * 16) = *reinterpret_cast<const uint4 *>(w_b + (size_t)idx * 8);
+        }
+    } else if ((n & 1) == 0) {
+        const int pr = n >> 1;
+#pragma unroll 4
+        for (int idx = tid; idx < d * pr; idx += NTHREADS) {
+            const int e = idx / pr, pc = idx - e * pr;
+            *reinterpret_cast<uint32_t *>(row_at(e) + pc * 4) = *reinterpret_cast<const uint32_t *>(w_b + (size_t)idx * 2);
+        }
+    } else {
+#pragma unroll 4
+        for (int idx = tid; idx < d * n; idx += NTHREADS) {
+            const int e = idx / n, i = idx - e * n;
+            *reinterpret_cast<uint16_t *>(row_at(e) + i * 2) = w_b[idx];
+        }
+    }
+    __syncthreads();
+
+    rt_f32x4 acc[NTILE];  // NTILE tiles of 16 experts
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[t][q] = 0.f;
+    // transposing-read lane roles: k-slice group lane/16, row (lane%16)/4 of the group's 4, 4 columns
+    const int tr_row = (lane >> 4) * 8 + ((lane & 15) >> 2), tr_col = (lane & 3) * 4;
+    for (int k0 = 0; k0 < d; k0 += 32 * UN) {
+        uint4 nv[UN] = {};
+        if (k0 + 32 * UN < d) load_a(k0 + 32 * UN, nv);
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
-            const int kk = min(k0 + u * 32 + ksl, dp - 8);  // stays inside the zero-padded LDS row
+            // rows past d: the A side is zero; read a valid row so that the product stays finite
+            const int kr = min(k0 + u * 32 + tr_row, d - 8 + ((lane & 15) >> 2));
             const rt_bf16x8 af = __builtin_bit_cast(rt_bf16x8, av[u]);
 #pragma unroll
             for (int t = 0; t < NTILE; ++t) {
-                const rt_bf16x8 bfr = *reinterpret_cast<const rt_bf16x8 *>(wb_t + (size_t)(t * 16 + r) * dp + kk);
+                const unsigned char *src = row_at(kr) + (t * 16 + tr_col) * 2;
+                const rt_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((rt_lds_s16x4_ptr)(src));
+                const rt_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((rt_lds_s16x4_ptr)(row_at(kr + 4) + (t * 16 + tr_col) * 2));
+                const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+                const rt_bf16x8 bfr = __builtin_bit_cast(rt_bf16x8, make_uint4(l2.x, l2.y, h2.x, h2.y));
                 acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfr, acc[t], 0, 0, 0);
             }
         }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) av[u] = nv[u];
     }
 #pragma unroll
     for (int t = 0; t < NTILE; ++t)
@@ -254,6 +302,7 @@ __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a
             float s[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) s[q] = 0.f;
+#pragma unroll 4
             for (int tl = 0; tl < tcur; ++tl) {
                 float wv[8];
                 load8(reinterpret_cast<const bf16_t *>(w_a) + (size_t)(t0 + tl) * m + j0, wv);
