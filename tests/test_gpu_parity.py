@@ -82,6 +82,12 @@ EDGE_CONFIGS = {
                         dtype=synth.BF16),
     "bf16_noise": small(b=2, l=96, d=128, n_a=8, d_h=64, m=12, c=5, k_a=3, n_m=8, d_e=128, k_m=3,
                         dtype=synth.BF16, router_noise=True),
+    # more than 16 experts (two expert tiles in the MFMA routers), K segments of 32
+    "bf16_n32": small(b=3, l=96, d=64, n_a=32, d_h=32, m=8, c=2, k_a=5, n_m=24, d_e=32, k_m=3,
+                      dtype=synth.BF16),
+    # more than 32 samples, not a multiple of 16 (sample tiles of the MFMA expert router)
+    "bf16_b40": small(b=40, l=80, d=32, n_a=4, d_h=32, m=5, c=2, k_a=2, n_m=6, d_e=64, k_m=2,
+                      dtype=synth.BF16),
 }
 
 
