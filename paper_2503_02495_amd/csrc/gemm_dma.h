@@ -88,10 +88,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     const int g = tile / (tg.n_tiles * tg.m_tiles);
     const int rem = tile - g * (tg.n_tiles * tg.m_tiles);
     const int mt = rem / tg.n_tiles, nt = rem - mt * tg.n_tiles;
-    const int M = p.rows(g), N = p.ncols(), K = p.kdim(g), KSEG = p.kseg();
+    const int M = p.rows(g), N = p.ncols(), KSEG = p.kseg();
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= M) return;
     const int tid = threadIdx.x, lane = tid & 63;
+    int K;  // problems whose K segments are found by the workgroup itself fill segtab here
+    if constexpr (P::kPrepare) K = p.prepare(g, segtab, tid, NW * 64);
+    else K = p.kdim(g);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
     const int lr = lane & 31, lh = lane >> 5;
@@ -103,7 +106,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     // operand loads have been issued
     uint32_t my_seg = 0;
     float my_scale = 1.0f;
-    if (tid < nseg && tid < MAX_SEG) my_seg = p.seg_ctx(g, tid);
+    if constexpr (!P::kPrepare) {
+        if (tid < nseg && tid < MAX_SEG) my_seg = p.seg_ctx(g, tid);
+    }
     if constexpr (P::kColScale) {
         if (tid < BN / 8) my_scale = p.col_scale(g, n0 + tid * 8 < N ? n0 + tid * 8 : 0);
     }
@@ -162,7 +167,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     // dependent load away from the kernel's start.  The lookup tables the loop and the epilogue use
     // are filled afterwards, under those loads, and published by the loop's first barrier.
     auto fetch_next = [&]() {
-        if (noff == 0) resolve_segment(nseg_next, p.seg_ctx(g, nseg_next));
+        if (noff == 0) {
+            if constexpr (P::kPrepare) resolve_segment(nseg_next, segtab[nseg_next < MAX_SEG ? nseg_next : 0]);
+            else resolve_segment(nseg_next, p.seg_ctx(g, nseg_next));
+        }
         issue(nbuf, noff);
         nbuf = nbuf + 1 == STAGES ? 0 : nbuf + 1;
         noff += BK;
@@ -174,7 +182,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < KT) fetch_next();
-    if (tid < nseg && tid < MAX_SEG) segtab[tid] = my_seg;
+    if (!P::kPrepare && tid < nseg && tid < MAX_SEG) segtab[tid] = my_seg;
     if (P::kColScale && tid < BN / 8) coltab[tid] = my_scale;
 
     // fragment read offsets (bytes inside a stage)

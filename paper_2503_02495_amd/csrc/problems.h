@@ -92,6 +92,7 @@ template <typename T> struct QkvProblem {
     __device__ const T *a_ptr_ctx(int g, int r, int seg, uint32_t) const { return a_seg_ptr(g, r, seg); }
     __device__ const T *b_ptr_ctx(int g, int seg, int nn, uint32_t) const { return b_seg_ptr(g, seg, nn); }
     // vector epilogue (MFMA engines)
+    static constexpr bool kPrepare = false;
     static constexpr bool kColScale = true;
     __device__ float col_scale(int, int nn) const { return nn < d_h ? q_scale : 1.0f; }
     __device__ float epi(float val, float scale) const { return val * scale; }
@@ -115,7 +116,7 @@ template <typename T> struct QkvProblem {
 // bits instead of 8 (the rows of W^o are simply visited twice).
 template <typename T> struct OutProjProblem {
     const T *o, *o_lo, *wo, *x;
-    const int32_t *expert_idx, *inv_cnt, *inv_ent;
+    const int32_t *expert_idx, *patch_idx, *inv_cnt, *inv_ent;  // inv_*: engines without prepare()
     T *out;
     int l, d, n, kact, m, c, l_p, l_a, d_h;
     int parts;  // 1: o only; 2: o is a (hi, lo) pair of buffers, contracted as [hi | lo] x [W^o ; W^o]
@@ -153,7 +154,36 @@ template <typename T> struct OutProjProblem {
         out[at] = from_f32<T>(val);
     }
     // pipelined engine: per K segment, (slot*c + pick) in bits 0-19, the expert in bits 20-25 and the
-    // hi/lo part in bit 26, looked up once before the loop (needs kact*c < 2^20)
+    // hi/lo part in bit 26 (needs kact*c < 2^20).  The workgroup builds the list of its group's
+    // segments itself (prepare), straight from the routing indices: thread (slot s, pick t) looks
+    // whether slot s picked this patch (at most one t per slot does), then the slots that did are
+    // listed in slot order, which fixes the summation order.  Returns K; ends on a barrier.
+    static constexpr bool kPrepare = true;
+    __device__ int prepare(int g, uint32_t *segtab, int tid, int nthreads) const
+    {
+        __shared__ int slot_t[32], slot_e[32];
+        const int bb = g / m, pp = g - bb * m;
+        if (tid < kact) slot_t[tid] = -1;
+        __syncthreads();
+        for (int idx = tid; idx < kact * c; idx += nthreads) {
+            const int s = idx / c, t = idx - s * c;
+            const int i = clampi(expert_idx[bb * kact + s], n);
+            if (t == 0) slot_e[s] = i;
+            if (clampi(patch_idx[((size_t)bb * n + i) * c + t], m) == pp) slot_t[s] = t;
+        }
+        __syncthreads();
+        int cnt = 0;
+        for (int s = 0; s < kact; ++s) {  // every thread walks the (at most 32) slots: cnt is uniform
+            const int t = slot_t[s];
+            if (t < 0) continue;
+            if (tid == 0)
+                for (int part = 0; part < parts; ++part)
+                    segtab[cnt * parts + part] = (uint32_t)(s * c + t) | ((uint32_t)slot_e[s] << 20) | ((uint32_t)part << 26);
+            ++cnt;
+        }
+        __syncthreads();
+        return cnt * parts * d_h;
+    }
     __device__ uint32_t seg_ctx(int g, int seg) const
     {
         const int bb = g / m;
@@ -221,6 +251,7 @@ template <typename T> struct UomeUpProblem {
     {
         hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate);
     }
+    static constexpr bool kPrepare = false;
     static constexpr bool kColScale = true;
     __device__ float col_scale(int g, int nn) const { return col_ctx(g, nn); }
     __device__ float epi(float val, float gate) const { return silu_fast(val) * gate; }
@@ -267,6 +298,7 @@ template <typename T> struct UomeDownProblem {
         if (flags & F_RESIDUAL) val += to_f32(u[at]);
         out[at] = from_f32<T>(val);
     }
+    static constexpr bool kPrepare = false;
     static constexpr bool kColScale = false;
     __device__ float col_scale(int, int) const { return 1.0f; }
     __device__ float epi(float val, float) const { return val; }

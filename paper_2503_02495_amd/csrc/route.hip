@@ -432,7 +432,10 @@ __global__ __launch_bounds__(256) void route_reduce_kernel(RouteArgs a)
 // loads do not depend on each other (unrolled: several in flight), never inside the chains.
 constexpr int SELECT_THREADS = 128;
 constexpr size_t SELECT_STAGE_MAX = 32 * 1024;  // bytes of logits staged in LDS
-__global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs a, int has_e, int has_d, int staged)
+// fuse_reduce: the data router's per-chunk partials are summed here (each of the n workgroups of
+// a sample repeats the sum: worth it only while n*m*chunks is small) instead of by route_reduce.
+__global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs a, int has_e, int has_d, int staged,
+                                                                      int fuse_reduce)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, i = blockIdx.x, bb = blockIdx.y;
@@ -457,8 +460,19 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     }
     if (has_d && staged) {
         const float *nzs = a.noise_p ? a.noise_p + (size_t)bb * nm : nullptr;
+        if (fuse_reduce) {
+            const float *src = a.gpart + (size_t)bb * nm;
+            const size_t stride = (size_t)a.b * nm;
+            for (int idx = tid; idx < nm; idx += SELECT_THREADS) {
+                float s = 0.f;
 #pragma unroll 8
-        for (int idx = tid; idx < nm; idx += SELECT_THREADS) glog[idx] = gsrc[idx] + (nzs ? nzs[idx] : 0.f);
+                for (int ch = 0; ch < a.nchunks_d; ++ch) s += src[(size_t)ch * stride + idx];
+                glog[idx] = s + (nzs ? nzs[idx] : 0.f);
+            }
+        } else {
+#pragma unroll 8
+            for (int idx = tid; idx < nm; idx += SELECT_THREADS) glog[idx] = gsrc[idx] + (nzs ? nzs[idx] : 0.f);
+        }
         __syncthreads();
     }
 
@@ -621,17 +635,18 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
         }
         if (err != hipSuccess) return err;
     }
-    if (has_d) {
-        hipLaunchKernelGGL(route_reduce_kernel, dim3((a.n * a.m + 15) / 16, a.b), dim3(256), 0, st, a);
-        err = hipGetLastError();
-        if (err != hipSuccess) return err;
-    }
     size_t sh = (size_t)a.m * (sizeof(float) + 1);
     const size_t stage_bytes = (size_t)a.n * a.m * sizeof(float);
     const bool staged = has_d && stage_bytes <= SELECT_STAGE_MAX;
     if (staged) sh = ((sh + 15) & ~(size_t)15) + stage_bytes;
+    const bool fuse_reduce = staged && (long)a.n * a.m * a.nchunks_d <= 8192;
+    if (has_d && !fuse_reduce) {
+        hipLaunchKernelGGL(route_reduce_kernel, dim3((a.n * a.m + 15) / 16, a.b), dim3(256), 0, st, a);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
     hipLaunchKernelGGL(route_select_kernel, dim3(a.n, a.b), dim3(SELECT_THREADS), sh, st, a, (int)has_e,
-                       (int)has_d, (int)staged);
+                       (int)has_d, (int)staged, (int)fuse_reduce);
     return hipGetLastError();
 }
 

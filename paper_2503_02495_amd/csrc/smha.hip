@@ -429,6 +429,7 @@ template <typename T> static OutProjProblem<T> make_outproj(const SmhaArgs &a)
     op.wo = static_cast<const T *>(a.wo);
     op.x = static_cast<const T *>(a.x);
     op.expert_idx = a.expert_idx;
+    op.patch_idx = a.patch_idx;
     op.inv_cnt = a.inv_cnt;
     op.inv_ent = a.inv_ent;
     op.out = static_cast<T *>(a.out);
@@ -455,7 +456,10 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     typedef OutProjProblem<bf16_t> OP;
     const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
     hipError_t err;
-    if ((err = launch_inverse_map(a, st)) != hipSuccess) return err;
+    // the pipelined out-projection finds each patch's segments itself; the other engines read the
+    // inverse map
+    const bool out_dma = (long)a.k * a.c < (1L << 20);
+    if (!out_dma && (err = launch_inverse_map(a, st)) != hipSuccess) return err;
 
     QP qp = make_qkv<bf16_t>(a);
     const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
@@ -486,7 +490,7 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
         op.o_lo = static_cast<const bf16_t *>(a.o_lo);
         op.parts = 2;
     }
-    if ((long)a.k * a.c >= (1L << 20)) {  // segment context of the pipelined engine would not fit
+    if (!out_dma) {  // segment context of the pipelined engine would not fit
         if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
         return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
     }
