@@ -208,6 +208,18 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
     const bf16_t *Kg = static_cast<const bf16_t *>(a.kk) + (size_t)g * l_a * DH;
     const bf16_t *Vg = static_cast<const bf16_t *>(a.v) + (size_t)g * l_a * DH;
 
+    // gate weight of this row (Eq. 36 with the optional gate flags): two dependent lookups, started
+    // here so that they complete under the key loop instead of in front of the output stores
+    float w = 1.0f;
+    {
+        const int bb = g / a.k, i = clampi(a.expert_idx[g], a.n);
+        if ((a.flags & F_GATE_EXPERT) && a.expert_gate) w *= a.expert_gate[(size_t)bb * a.n + i];
+        if ((a.flags & F_GATE_PATCH) && a.patch_gate) {
+            const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + min(qrow, l_a - 1) / l_p], a.m);
+            w *= a.patch_gate[((size_t)bb * a.n + i) * a.m + p];
+        }
+    }
+
     bf16x8_t qf[DH / 16];
 #pragma unroll
     for (int ks = 0; ks < DH / 16; ++ks) {
@@ -324,17 +336,15 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
         for (int s4 = 0; s4 < 4; ++s4) {
             const int t = s4 >> 1, r0 = (s4 & 1) * 8;
             // probabilities as a (hi, lo) bf16 pair: P V = P_hi V + P_lo V keeps ~16 bits of P
-            uint32_t hi[8], lo[8];
+            uint32_t hi[4], lo[4];  // two values per word
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float pv = sacc[t][r0 + e];
-                hi[e] = f32_to_bf16_bits(pv);
-                lo[e] = f32_to_bf16_bits(pv - __uint_as_float(hi[e] << 16));
+            for (int e = 0; e < 4; ++e) {
+                const float p0 = sacc[t][r0 + 2 * e], p1 = sacc[t][r0 + 2 * e + 1];
+                hi[e] = pack2_bf16(p0, p1);
+                lo[e] = pack2_bf16(p0 - __uint_as_float(hi[e] << 16), p1 - __uint_as_float(hi[e] & 0xFFFF0000u));
             }
-            const bf16x8_t pf_hi = __builtin_bit_cast(
-                bf16x8_t, make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)));
-            const bf16x8_t pf_lo = __builtin_bit_cast(
-                bf16x8_t, make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)));
+            const bf16x8_t pf_hi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+            const bf16x8_t pf_lo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
 #pragma unroll
             for (int td = 0; td < DH / 32; ++td) {
                 // V^T fragment for head-dim column td*32 + lr: keys 16*s4 + 4*lh + 0..3, then + 8
@@ -352,14 +362,6 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
 
     if (qrow >= l_a) return;
     lsum += __shfl_xor(lsum, 32, 64);
-    // gate weight of this row (Eq. 36 with the optional gate flags)
-    const int bb = g / a.k, i = clampi(a.expert_idx[g], a.n);
-    float w = 1.0f;
-    if ((a.flags & F_GATE_EXPERT) && a.expert_gate) w *= a.expert_gate[(size_t)bb * a.n + i];
-    if ((a.flags & F_GATE_PATCH) && a.patch_gate) {
-        const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + qrow / l_p], a.m);
-        w *= a.patch_gate[((size_t)bb * a.n + i) * a.m + p];
-    }
     const float inv = lsum > 0.f ? w / lsum : 0.f;  // a row with no admissible key contributes nothing
     bf16_t *o = static_cast<bf16_t *>(a.o) + ((size_t)g * l_a + qrow) * DH;
     bf16_t *o_lo = static_cast<bf16_t *>(a.o_lo) + ((size_t)g * l_a + qrow) * DH;
@@ -369,15 +371,15 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
     for (int td = 0; td < DH / 32; ++td)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-            uint32_t hi[4], lo[4];
+            uint32_t hi[2], lo[2];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float val = oacc[td][i4 * 4 + e] * inv;
-                hi[e] = f32_to_bf16_bits(val);
-                lo[e] = f32_to_bf16_bits(val - __uint_as_float(hi[e] << 16));
+            for (int e = 0; e < 2; ++e) {
+                const float v0 = oacc[td][i4 * 4 + 2 * e] * inv, v1 = oacc[td][i4 * 4 + 2 * e + 1] * inv;
+                hi[e] = pack2_bf16(v0, v1);
+                lo[e] = pack2_bf16(v0 - __uint_as_float(hi[e] << 16), v1 - __uint_as_float(hi[e] & 0xFFFF0000u));
             }
-            *reinterpret_cast<uint2 *>(o + td * 32 + i4 * 8 + lh * 4) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
-            *reinterpret_cast<uint2 *>(o_lo + td * 32 + i4 * 8 + lh * 4) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+            *reinterpret_cast<uint2 *>(o + td * 32 + i4 * 8 + lh * 4) = make_uint2(hi[0], hi[1]);
+            *reinterpret_cast<uint2 *>(o_lo + td * 32 + i4 * 8 + lh * 4) = make_uint2(lo[0], lo[1]);
         }
 }
 
@@ -385,9 +387,9 @@ template <int DH> static hipError_t launch_attention_mfma_dh(const SmhaArgs &a, 
 {
     const int l_a = a.c * (a.l / a.m), units = a.b * a.k;
     // more waves per workgroup share K/V tiles; fewer give more workgroups: keep >= 512 if possible
-    if ((long)((l_a + 127) / 128) * units >= 512) {
+    if ((long)((l_a + 127) / 128) * units >= 128) {
         hipLaunchKernelGGL((attention_mfma_kernel<DH, 4>), dim3((l_a + 127) / 128, units), dim3(256), 0, st, a);
-    } else if ((long)((l_a + 63) / 64) * units >= 512) {
+    } else if ((long)((l_a + 63) / 64) * units >= 64) {
         hipLaunchKernelGGL((attention_mfma_kernel<DH, 2>), dim3((l_a + 63) / 64, units), dim3(128), 0, st, a);
     } else {
         hipLaunchKernelGGL((attention_mfma_kernel<DH, 1>), dim3((l_a + 31) / 32, units), dim3(64), 0, st, a);
