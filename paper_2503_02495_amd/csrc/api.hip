@@ -45,7 +45,7 @@ struct RouteWs {
 RouteWs route_ws(int b, int l, int d, int n, int m, bool bf16)
 {
     RouteWs w;
-    w.tc = bf16 ? route_expert_mfma_tokens_per_chunk(l) : route_tokens_per_chunk(b, l);
+    w.tc = bf16 ? route_expert_mfma_tokens_per_chunk(b, l, d, n) : route_tokens_per_chunk(b, l);
     w.nchunks = (l + w.tc - 1) / w.tc;
     w.tc_d = route_data_tokens_per_chunk(b, l, d, n, bf16);
     w.nchunks_d = (l + w.tc_d - 1) / w.tc_d;

@@ -124,7 +124,7 @@ hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // E
 
 // host-side sizing shared by api.cpp and the launchers
 int route_tokens_per_chunk(int b, int l);
-int route_expert_mfma_tokens_per_chunk(int l);
+int route_expert_mfma_tokens_per_chunk(int b, int l, int d, int n);
 int route_data_tokens_per_chunk(int b, int l, int d, int n, bool bf16);
 
 }  // namespace uoe

@@ -41,8 +41,9 @@ int route_tokens_per_chunk(int b, int l)
 
 // Expert router, MFMA kernel: tokens per chunk.  The chunk count does not depend on b (a workgroup
 // takes all samples of its chunk), so aim for ~512 chunks.
-int route_expert_mfma_tokens_per_chunk(int l)
+int route_expert_mfma_tokens_per_chunk(int b, int l, int d, int n)
 {
+    (void)b; (void)d; (void)n;  // ~512 chunks whatever the shape: measured best from `lm` to `large`
     const int tc = l / 512;
     return tc < 1 ? 1 : tc;
 }
@@ -430,7 +431,7 @@ __global__ __launch_bounds__(256) void route_reduce_kernel(RouteArgs a)
 // (+ the sample's n*m noisy logits when they fit: `staged`).  The kernel is a chain of small
 // dependent steps, so everything it needs from global memory is fetched up front by loops whose
 // loads do not depend on each other (unrolled: several in flight), never inside the chains.
-constexpr int SELECT_THREADS = 128;
+constexpr int SELECT_THREADS = 512;
 constexpr size_t SELECT_STAGE_MAX = 32 * 1024;  // bytes of logits staged in LDS
 // fuse_reduce: the data router's per-chunk partials are summed here (each of the n workgroups of
 // a sample repeats the sum: worth it only while n*m*chunks is small) instead of by route_reduce.
@@ -445,11 +446,12 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     float *glog = reinterpret_cast<float *>(smem + (((size_t)m * 5 + 15) & ~(size_t)15));  // [n*m] when staged
     __shared__ float ge[32];
     __shared__ float zpart_sum[SELECT_THREADS];
+    __shared__ float dpart[SELECT_THREADS];
     __shared__ unsigned char ekept[32];
     const float *gsrc = a.gred + (size_t)bb * nm;
 
     // the expert router's per-chunk partials, summed in a fixed order: thread = (chunk group, expert)
-    const int groups = SELECT_THREADS / n;  // >= 4
+    const int groups = SELECT_THREADS / n;  // >= 16
     float zs = 0.f;
     if (has_e && i == 0 && tid < groups * n) {
         const int vi = tid % n, cg = tid / n;
@@ -460,14 +462,21 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     }
     if (has_d && staged) {
         const float *nzs = a.noise_p ? a.noise_p + (size_t)bb * nm : nullptr;
-        if (fuse_reduce) {
+        if (fuse_reduce) {  // nm <= SELECT_THREADS: thread = (chunk group, value), groups summed in order
             const float *src = a.gpart + (size_t)bb * nm;
             const size_t stride = (size_t)a.b * nm;
-            for (int idx = tid; idx < nm; idx += SELECT_THREADS) {
-                float s = 0.f;
+            const int dgroups = SELECT_THREADS / nm, v = tid % nm, cg = tid / nm;
+            float s = 0.f;
+            if (cg < dgroups) {
 #pragma unroll 8
-                for (int ch = 0; ch < a.nchunks_d; ++ch) s += src[(size_t)ch * stride + idx];
-                glog[idx] = s + (nzs ? nzs[idx] : 0.f);
+                for (int ch = cg; ch < a.nchunks_d; ch += dgroups) s += src[(size_t)ch * stride + v];
+                dpart[tid] = s;
+            }
+            __syncthreads();
+            if (tid < nm) {
+                float t = nzs ? nzs[tid] : 0.f;
+                for (int q = 0; q < dgroups; ++q) t += dpart[q * nm + tid];
+                glog[tid] = t;
             }
         } else {
 #pragma unroll 8
@@ -639,7 +648,7 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
     const size_t stage_bytes = (size_t)a.n * a.m * sizeof(float);
     const bool staged = has_d && stage_bytes <= SELECT_STAGE_MAX;
     if (staged) sh = ((sh + 15) & ~(size_t)15) + stage_bytes;
-    const bool fuse_reduce = staged && (long)a.n * a.m * a.nchunks_d <= 8192;
+    const bool fuse_reduce = staged && a.n * a.m <= SELECT_THREADS && (long)a.n * a.m * a.nchunks_d <= 16384;
     if (has_d && !fuse_reduce) {
         hipLaunchKernelGGL(route_reduce_kernel, dim3((a.n * a.m + 15) / 16, a.b), dim3(256), 0, st, a);
         err = hipGetLastError();
