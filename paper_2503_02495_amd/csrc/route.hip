@@ -49,12 +49,10 @@ int route_expert_mfma_tokens_per_chunk(int b, int l, int d, int n)
 }
 
 // Data router: tokens per chunk and whether the MFMA kernel applies.  waves*16 tokens per chunk for
-// the MFMA kernel (as many waves as still leave >= 256 workgroups), else the expert router's chunking.
-static int data_mfma_waves(int b, int l)
+// the MFMA kernel, else the expert router's chunking.
+static int data_mfma_waves(int, int)
 {
-    if ((long)((l + 63) / 64) * b >= 256) return 4;
-    if ((long)((l + 31) / 32) * b >= 256) return 2;
-    return 1;
+    return 4;  // 64 tokens per workgroup: the W_B staging is shared by four waves
 }
 // LDS of the MFMA data router: W_B as it is, [d][np] in blocks of 8 rows (see the kernel), then t1.
 static size_t data_mfma_wb_bytes(int n, int d)
@@ -65,7 +63,8 @@ static size_t data_mfma_wb_bytes(int n, int d)
 static size_t data_mfma_lds(int n, int d, int waves)
 {
     const int np = (n + 15) & ~15;
-    return data_mfma_wb_bytes(n, d) + (size_t)waves * 16 * np * sizeof(float);
+    // W_B, t1 [waves*16][np], and the fold's per-token-group partial sums (at most 8 per thread)
+    return data_mfma_wb_bytes(n, d) + (size_t)waves * 16 * np * sizeof(float) + (size_t)waves * 64 * 8 * sizeof(float);
 }
 bool route_data_uses_mfma(int b, int l, int d, int n, bool bf16)
 {
@@ -203,13 +202,11 @@ typedef rt_s16x4 __attribute__((address_space(3))) * rt_lds_s16x4_ptr;
 // stored in blocks of 8 with a pad after each block (128 bytes for 32-byte rows, 32 bytes for
 // 64-byte rows) so that the row groups of the four k-slices fall into different banks.
 template <int WAVES, int NTILE>
-__global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a)
+__device__ __forceinline__ void route_data_mfma_body(const RouteArgs &a, int chunk, int bb, unsigned char *smem)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NTHREADS = WAVES * 64, TC = WAVES * 16;
     constexpr int NP = NTILE * 16, ROWB = NP * 2, BLK = 8 * ROWB + (NP == 16 ? 128 : 32);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = blockIdx.x, bb = blockIdx.y;
     const int n = a.n, d = a.d, l = a.l, m = a.m;
     const int np = NP;
     const int t0 = chunk * TC, tcur = min(TC, l - t0);
@@ -292,37 +289,57 @@ __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a
         for (int q = 0; q < 4; ++q) t1s[(wave * 16 + (lane >> 4) * 4 + q) * np + t * 16 + r] = acc[t][q];
     __syncthreads();
 
+    // Fold with the chunk's rows of W_A: g[i][j] = sum_t t1[t][i] * W_A[t0 + t][j].  A thread owns
+    // (token group tg, output group og): one expert i and VEC consecutive patches, for the tokens
+    // tg, tg + TG, ...; the TG partial sums of an output are then added in group order.  (With few
+    // outputs per sample, one thread per output would leave most of the workgroup idle behind a
+    // serial walk over all the chunk's tokens.)
     const uint16_t *w_a = static_cast<const uint16_t *>(a.w_a);
     const int nm = n * m;
     float *gout = a.gpart + ((size_t)chunk * a.b + bb) * nm;
-    if ((m & 7) == 0) {
-        // one thread per (expert i, 8 consecutive patches): 16-byte loads of the W_A rows
-        const int m8 = m >> 3;
-        for (int o = tid; o < n * m8; o += NTHREADS) {
-            const int i = o / m8, j0 = (o - i * m8) * 8;
-            float s[8];
+    const int vec = (m & 7) == 0 ? 8 : 1, mv = m / vec, og_n = n * mv;
+    const int tg_n = og_n >= NTHREADS ? 1 : NTHREADS / og_n;
+    float *part = t1s + TC * np;  // [tg_n][nm], at most NTHREADS * 8 floats
+    auto fold = [&](int og, int tl0, int tstep, float *dst) {
+        const int i = og / mv, j0 = (og - i * mv) * vec;
+        float sacc[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) s[q] = 0.f;
+        for (int q = 0; q < 8; ++q) sacc[q] = 0.f;
+        if (vec == 8) {
 #pragma unroll 4
-            for (int tl = 0; tl < tcur; ++tl) {
+            for (int tl = tl0; tl < tcur; tl += tstep) {
                 float wv[8];
                 load8(reinterpret_cast<const bf16_t *>(w_a) + (size_t)(t0 + tl) * m + j0, wv);
                 const float t1 = t1s[tl * np + i];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) s[q] = fmaf(t1, wv[q], s[q]);
+                for (int q = 0; q < 8; ++q) sacc[q] = fmaf(t1, wv[q], sacc[q]);
             }
-#pragma unroll
-            for (int q = 0; q < 8; ++q) gout[i * m + j0 + q] = s[q];
+        } else {
+#pragma unroll 4
+            for (int tl = tl0; tl < tcur; tl += tstep)
+                sacc[0] = fmaf(t1s[tl * np + i], __uint_as_float((uint32_t)w_a[(size_t)(t0 + tl) * m + j0] << 16), sacc[0]);
+        }
+        for (int q = 0; q < vec; ++q) dst[i * m + j0 + q] = sacc[q];
+    };
+    if (tg_n > 1) {
+        const int og = tid % og_n, tg = tid / og_n;
+        if (tg < tg_n) fold(og, tg, tg_n, part + (size_t)tg * nm);
+        __syncthreads();
+        for (int o = tid; o < nm; o += NTHREADS) {
+            float t = 0.f;
+            for (int q = 0; q < tg_n; ++q) t += part[(size_t)q * nm + o];
+            gout[o] = t;
         }
     } else {
-        for (int o = tid; o < nm; o += NTHREADS) {
-            const int i = o / m, j = o - i * m;
-            float s = 0.f;
-            for (int tl = 0; tl < tcur; ++tl)
-                s = fmaf(t1s[tl * np + i], __uint_as_float((uint32_t)w_a[(size_t)(t0 + tl) * m + j] << 16), s);
-            gout[o] = s;
-        }
+        for (int og = tid; og < og_n; og += NTHREADS) fold(og, 0, 1, gout);
     }
+}
+
+template <int WAVES, int NTILE>
+__global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    route_data_mfma_body<WAVES, NTILE>(a, blockIdx.x, blockIdx.y, smem);
 }
 
 // Expert router (Eq. 21), bf16, MFMA.  Workgroup = 4 waves = (chunk of a.tc tokens, i.e. a.tc*d
@@ -333,14 +350,15 @@ __global__ __launch_bounds__(WAVES * 64) void route_data_mfma_kernel(RouteArgs a
 // (they only produce output rows / columns that are never stored).  The last step of a chunk may
 // be partial (multiples of 8 elements): its missing slices are zeroed.  Accumulator register v of
 // a lane is Z[sample 4*q + v][expert r].  The four waves' tiles are summed in wave order.
+template <int RT, int CT> constexpr size_t route_expert_mfma_lds() { return sizeof(float) * 4 * RT * 16 * (CT * 16 + 1); }
+
 template <int RT, int CT>
-__global__ __launch_bounds__(256) void route_expert_mfma_kernel(RouteArgs a)
+__device__ __forceinline__ void route_expert_mfma_body(const RouteArgs &a, int chunk, int b0, unsigned char *smem)
 {
-    __shared__ float zsh[4][RT * 16][CT * 16 + 1];
+    float(*zsh)[RT * 16][CT * 16 + 1] = reinterpret_cast<float(*)[RT * 16][CT * 16 + 1]>(smem);  // [4 waves]
     constexpr int U = 4;  // steps whose loads are in flight together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, q = lane >> 4;
-    const int chunk = blockIdx.x, b0 = blockIdx.y * RT * 16;
     const int b = a.b, n = a.n;
     const long ld = (long)a.l * a.d;
     const long c0 = (long)chunk * a.tc * a.d;
@@ -397,6 +415,30 @@ __global__ __launch_bounds__(256) void route_expert_mfma_kernel(RouteArgs a)
         const int row = o / (CT * 16), col = o - row * (CT * 16);
         if (b0 + row < b && col < n)
             a.zpart[((size_t)chunk * b + b0 + row) * n + col] = (zsh[0][row][col] + zsh[1][row][col]) + (zsh[2][row][col] + zsh[3][row][col]);
+    }
+}
+
+template <int RT, int CT>
+__global__ __launch_bounds__(256) void route_expert_mfma_kernel(RouteArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    route_expert_mfma_body<RT, CT>(a, blockIdx.x, blockIdx.y * RT * 16, smem);
+}
+
+// Both routers of a block in one launch (they are independent and both stream x): workgroups
+// [0, n_data) run the data router with four waves (chunk = id % nchunks_d, sample = id / nchunks_d) -
+// first, because each is a longer chain of dependent steps - and the rest the expert router
+// (chunk = id' % nchunks, sample group = id' / nchunks).
+template <int RT, int CT>
+__global__ __launch_bounds__(256) void route_expert_data_kernel(RouteArgs a, int n_data)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int id = blockIdx.x;
+    if (id < n_data) {
+        route_data_mfma_body<4, CT>(a, id % a.nchunks_d, id / a.nchunks_d, smem);
+    } else {
+        const int f = id - n_data;
+        route_expert_mfma_body<RT, CT>(a, f % a.nchunks, (f / a.nchunks) * RT * 16, smem);
     }
 }
 
@@ -605,44 +647,61 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
 {
     const bool has_e = a.w_e != nullptr, has_d = a.w_b != nullptr;
     hipError_t err = hipSuccess;
-    if (has_e && bf16) {  // a.tc / a.nchunks follow route_expert_mfma_tokens_per_chunk
-        const int rt = a.b > 32 ? 4 : (a.b > 16 ? 2 : 1);
-        const dim3 grid(a.nchunks, (a.b + rt * 16 - 1) / (rt * 16));
+    const bool data_mfma = has_d && route_data_uses_mfma(a.b, a.l, a.d, a.n, bf16);
+    const int rt = a.b > 32 ? 4 : (a.b > 16 ? 2 : 1);
+    const int groups_e = (a.b + rt * 16 - 1) / (rt * 16);
+    // one launch for both routers while x is small enough that the two do not simply queue up on HBM
+    if (has_e && bf16 && data_mfma && (double)a.b * a.l * a.d * 2 <= 48e6) {
+        const int n_data = a.nchunks_d * a.b;
+        const dim3 grid(n_data + a.nchunks * groups_e);
+        const size_t shd = data_mfma_lds(a.n, a.d, 4);
+#define UOE_FUSED(RT, CT)                                                                                         \
+    do {                                                                                                          \
+        const size_t she = route_expert_mfma_lds<RT, CT>();                                                       \
+        hipLaunchKernelGGL((route_expert_data_kernel<RT, CT>), grid, dim3(256), she > shd ? she : shd, st, a, n_data);   \
+    } while (0)
         if (a.n <= 16) {
-            if (rt == 4) hipLaunchKernelGGL((route_expert_mfma_kernel<4, 1>), grid, dim3(256), 0, st, a);
-            else if (rt == 2) hipLaunchKernelGGL((route_expert_mfma_kernel<2, 1>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((route_expert_mfma_kernel<1, 1>), grid, dim3(256), 0, st, a);
+            if (rt == 4) UOE_FUSED(4, 1);
+            else if (rt == 2) UOE_FUSED(2, 1);
+            else UOE_FUSED(1, 1);
         } else {
-            if (rt == 4) hipLaunchKernelGGL((route_expert_mfma_kernel<4, 2>), grid, dim3(256), 0, st, a);
-            else if (rt == 2) hipLaunchKernelGGL((route_expert_mfma_kernel<2, 2>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((route_expert_mfma_kernel<1, 2>), grid, dim3(256), 0, st, a);
+            if (rt == 4) UOE_FUSED(4, 2);
+            else if (rt == 2) UOE_FUSED(2, 2);
+            else UOE_FUSED(1, 2);
         }
+#undef UOE_FUSED
         if ((err = hipGetLastError()) != hipSuccess) return err;
-    } else if (has_e) {
-        if ((err = launch_partial_n<float>(a, true, false, st)) != hipSuccess) return err;
-    }
-    if (has_d) {
-        if (route_data_uses_mfma(a.b, a.l, a.d, a.n, bf16)) {
-            const int waves = data_mfma_waves(a.b, a.l);
-            const size_t sh = data_mfma_lds(a.n, a.d, waves);
-            const dim3 grid(a.nchunks_d, a.b);
+    } else {
+        if (has_e && bf16) {  // a.tc / a.nchunks follow route_expert_mfma_tokens_per_chunk
+            const dim3 grid(a.nchunks, groups_e);
+#define UOE_EXPERT(RT, CT) hipLaunchKernelGGL((route_expert_mfma_kernel<RT, CT>), grid, dim3(256), (route_expert_mfma_lds<RT, CT>()), st, a)
             if (a.n <= 16) {
-                if (waves == 4) hipLaunchKernelGGL((route_data_mfma_kernel<4, 1>), grid, dim3(256), sh, st, a);
-                else if (waves == 2) hipLaunchKernelGGL((route_data_mfma_kernel<2, 1>), grid, dim3(128), sh, st, a);
-                else hipLaunchKernelGGL((route_data_mfma_kernel<1, 1>), grid, dim3(64), sh, st, a);
+                if (rt == 4) UOE_EXPERT(4, 1);
+                else if (rt == 2) UOE_EXPERT(2, 1);
+                else UOE_EXPERT(1, 1);
             } else {
-                if (waves == 4) hipLaunchKernelGGL((route_data_mfma_kernel<4, 2>), grid, dim3(256), sh, st, a);
-                else if (waves == 2) hipLaunchKernelGGL((route_data_mfma_kernel<2, 2>), grid, dim3(128), sh, st, a);
-                else hipLaunchKernelGGL((route_data_mfma_kernel<1, 2>), grid, dim3(64), sh, st, a);
+                if (rt == 4) UOE_EXPERT(4, 2);
+                else if (rt == 2) UOE_EXPERT(2, 2);
+                else UOE_EXPERT(1, 2);
             }
-            err = hipGetLastError();
-        } else {
+#undef UOE_EXPERT
+            if ((err = hipGetLastError()) != hipSuccess) return err;
+        } else if (has_e) {
+            if ((err = launch_partial_n<float>(a, true, false, st)) != hipSuccess) return err;
+        }
+        if (data_mfma) {
+            const size_t sh = data_mfma_lds(a.n, a.d, 4);
+            const dim3 grid(a.nchunks_d, a.b);
+            if (a.n <= 16) hipLaunchKernelGGL((route_data_mfma_kernel<4, 1>), grid, dim3(256), sh, st, a);
+            else hipLaunchKernelGGL((route_data_mfma_kernel<4, 2>), grid, dim3(256), sh, st, a);
+            if ((err = hipGetLastError()) != hipSuccess) return err;
+        } else if (has_d) {
             RouteArgs ad = a;  // the vector-ALU kernel takes its chunking from tc / nchunks
             ad.tc = a.tc_d;
             ad.nchunks = a.nchunks_d;
             err = bf16 ? launch_partial_n<bf16_t>(ad, false, true, st) : launch_partial_n<float>(ad, false, true, st);
+            if (err != hipSuccess) return err;
         }
-        if (err != hipSuccess) return err;
     }
     size_t sh = (size_t)a.m * (sizeof(float) + 1);
     const size_t stage_bytes = (size_t)a.n * a.m * sizeof(float);
