@@ -66,6 +66,7 @@ def _L():
         lib.uoe_oracle_expert_lists.argtypes = [I, I, I, P, P, P]
         lib.uoe_oracle_smha.argtypes = [I] * 8 + [ctypes.c_uint] + [P] * 9 + [I, P, P]
         lib.uoe_oracle_uome.argtypes = [I] * 6 + [ctypes.c_uint] + [P] * 6
+        lib.uoe_oracle_uome_ds.argtypes = [I] * 8 + [ctypes.c_uint] + [P] * 8
         for f in ("data_router_logits", "patch_gate", "top_c", "expert_router", "top_k",
                   "expert_lists", "smha", "uome", "set_threads"):
             getattr(lib, "uoe_oracle_" + f).restype = None
@@ -228,8 +229,12 @@ def smha(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: in
     return out
 
 
-def uome(u, a_in, a_out, expert_id, expert_gate, flags: int = RESIDUAL) -> np.ndarray:
-    """Eq. 38-40 (expert-selection mode) on given routing results; returns h [b,l,d]."""
+def uome(u, a_in, a_out, expert_id, expert_gate, flags: int = RESIDUAL, patch_id=None, patch_gate_=None,
+         m: int = 1) -> np.ndarray:
+    """Eq. 37-40 on given routing results; returns h [b,l,d].
+
+    Without patch_id: expert-selection mode (every active expert sees the whole sample).  With
+    patch_id [b,n,c] (and patch_gate_ [b,n,m]): each active expert sees only its c selected patches."""
     u, a_in, a_out = _f64(u), _f64(a_in), _f64(a_out)
     b, l, d = u.shape
     n, _, d_e = a_in.shape
@@ -239,8 +244,17 @@ def uome(u, a_in, a_out, expert_id, expert_gate, flags: int = RESIDUAL) -> np.nd
     g_e = _f64(expert_gate)
     assert g_e.shape == (b, n)
     out = np.empty((b, l, d), np.float64)
-    _L().uoe_oracle_uome(b, l, d, n, k, d_e, flags, _p(u), _p(a_in), _p(a_out), _p(expert_id),
-                         _p(g_e), _p(out))
+    if patch_id is None:
+        assert not (flags & GATE_PATCH)
+        _L().uoe_oracle_uome(b, l, d, n, k, d_e, flags, _p(u), _p(a_in), _p(a_out), _p(expert_id),
+                             _p(g_e), _p(out))
+        return out
+    patch_id = _i32(patch_id)
+    c = patch_id.shape[2]
+    g_d = _f64(patch_gate_)
+    assert l % m == 0 and patch_id.shape == (b, n, c) and g_d.shape == (b, n, m)
+    _L().uoe_oracle_uome_ds(b, l, d, n, k, m, c, d_e, flags, _p(u), _p(a_in), _p(a_out), _p(expert_id),
+                            _p(g_e), _p(patch_id), _p(g_d), _p(out))
     return out
 
 
@@ -263,6 +277,11 @@ def layer_forward(inp, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
                inp.noise_a_expert, inp.noise_a_patch)
     u = smha(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ra.expert_gate, ra.patch_id,
              ra.patch_gate, cfg.m, flags_a, rope_dim)
-    rm = route(u, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
-    out = uome(u, inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, flags_m)
+    if getattr(cfg, "m_m", 1) > 1:  # UoME with patch-wise data selection (Eq. 37)
+        rm = route(u, cfg.n_m, cfg.k_m, cfg.m_m, cfg.c_m, inp.m_w_expert, inp.m_w_b, inp.m_w_a,
+                   inp.noise_m_expert, inp.noise_m_patch)
+        out = uome(u, inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, flags_m, rm.patch_id, rm.patch_gate, cfg.m_m)
+    else:
+        rm = route(u, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
+        out = uome(u, inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, flags_m)
     return LayerResult(ra, u, rm, out)

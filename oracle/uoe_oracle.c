@@ -337,3 +337,48 @@ void uoe_oracle_uome(int b, int l, int d, int n, int k, int d_e, unsigned flags,
     }
     free(Vh); free(Hp);
 }
+
+/* ------------------------------------------------------------------------- */
+/* Union-of-MLP-Experts with patch-wise data selection (Eq. 37-40 in full: u' = f_DS(u) per expert).
+ * Expert i of an active slot sees only its c selected patches (ascending, as routing returns
+ * them): u'_i [l_a,d] gathered (Eq. 18), v_i = SiLU(u'_i A^I_i) (Eq. 38), h'_i = v_i A^O_i
+ * (Eq. 39, linear second layer), and the rows of h'_i are index-added onto the tokens they were
+ * gathered from (Eq. 40), weighted by the expert gate and/or the patch gate as the flags say.
+ * u [b,l,d]; A_I [n,d,d_e]; A_O [n,d_e,d]; expert_id [b,k]; gE [b,n]; patch_id [b,n,c];
+ * gD [b,n,m]; h [b,l,d]. */
+void uoe_oracle_uome_ds(int b, int l, int d, int n, int k, int m, int c, int d_e, unsigned flags,
+                        const double *u, const double *A_I, const double *A_O,
+                        const int32_t *expert_id, const double *gE, const int32_t *patch_id,
+                        const double *gD, double *h)
+{
+    const int l_p = l / m, l_a = c * l_p;
+    double *Up = (double *)malloc(sizeof(double) * (size_t)l_a * d);
+    double *Vh = (double *)malloc(sizeof(double) * (size_t)l_a * d_e);
+    double *Hp = (double *)malloc(sizeof(double) * (size_t)l_a * d);
+    for (int bb = 0; bb < b; ++bb) {
+        const double *ub = u + (long)bb * l * d;
+        double *hb = h + (long)bb * l * d;
+        for (long q = 0; q < (long)l * d; ++q) hb[q] = (flags & ORACLE_RESIDUAL) ? ub[q] : 0.0;
+        for (int s = 0; s < k; ++s) {
+            const int i = expert_id[(long)bb * k + s];
+            const int32_t *pid = patch_id + ((long)bb * n + i) * c;
+            /* Eq. 18: the expert's patches, in the order routing returned them */
+            for (int t = 0; t < c; ++t)
+                for (int r = 0; r < l_p; ++r)
+                    for (int e = 0; e < d; ++e)
+                        Up[((long)t * l_p + r) * d + e] = ub[((long)pid[t] * l_p + r) * d + e];
+            matmul(l_a, d, d_e, Up, d, A_I + (long)i * d * d_e, d_e, Vh, d_e);
+            for (long q = 0; q < (long)l_a * d_e; ++q) Vh[q] = Vh[q] / (1.0 + exp(-Vh[q]));
+            matmul(l_a, d_e, d, Vh, d_e, A_O + (long)i * d_e * d, d, Hp, d);
+            for (int t = 0; t < c; ++t) {
+                double w = 1.0;
+                if (flags & ORACLE_GATE_EXPERT) w *= gE[(long)bb * n + i];
+                if (flags & ORACLE_GATE_PATCH) w *= gD[((long)bb * n + i) * m + pid[t]];
+                for (int r = 0; r < l_p; ++r)
+                    for (int e = 0; e < d; ++e)
+                        hb[((long)pid[t] * l_p + r) * d + e] += w * Hp[((long)t * l_p + r) * d + e];
+            }
+        }
+    }
+    free(Up); free(Vh); free(Hp);
+}

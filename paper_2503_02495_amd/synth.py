@@ -11,7 +11,8 @@ tokens, c patches kept per expert, k_a experts kept per sample; UoME block:
 n_m MLP experts of hidden dim d_e, k_m kept per sample.
 
 Draw order is fixed (x; SMHA W_E, W_B, W_A, W^q, W^k, W^v, W^o; UoME W_E, A^I,
-A^O; then the optional router-noise tensors) so a (config, seed) pair names one
+A^O; then the optional router-noise tensors; then, for configs with UoME data
+selection, its W_B, W_A and patch noise) so a (config, seed) pair names one
 input set.  x ~ N(0,1); every weight ~ N(0, std 0.02).  For bf16 configs each
 tensor is rounded once to bfloat16 (round to nearest, ties to even) here on
 the host; both sides consume exactly those rounded values.
@@ -46,6 +47,9 @@ class LayerConfig:
     dtype: str = BF16
     seed: int = 0
     router_noise: bool = False
+    # UoME patch-wise data selection (Eq. 37): m_m patches, c_m kept per expert; 1/1 = expert selection only
+    m_m: int = 1
+    c_m: int = 1
 
     @property
     def l_p(self) -> int:
@@ -118,6 +122,10 @@ class LayerInputs:
     noise_a_expert: Optional[np.ndarray] = None    # [b, n_a]
     noise_a_patch: Optional[np.ndarray] = None     # [b, n_a, m]
     noise_m_expert: Optional[np.ndarray] = None    # [b, n_m]
+    # UoME data-selection router (only when cfg.m_m > 1)
+    m_w_b: Optional[np.ndarray] = None             # [d, n_m]
+    m_w_a: Optional[np.ndarray] = None             # [l, m_m]
+    noise_m_patch: Optional[np.ndarray] = None     # [b, n_m, m_m]
     extras: dict = field(default_factory=dict)
 
 
@@ -151,12 +159,17 @@ def make_inputs(cfg: LayerConfig, seed: Optional[int] = None, w_std: float = 0.0
         inp.noise_a_expert = rng.standard_normal(size=(b, cfg.n_a), dtype=np.float32)
         inp.noise_a_patch = rng.standard_normal(size=(b, cfg.n_a, cfg.m), dtype=np.float32)
         inp.noise_m_expert = rng.standard_normal(size=(b, cfg.n_m), dtype=np.float32)
+    if cfg.m_m > 1:
+        inp.m_w_b = _draw(rng, (d, cfg.n_m), w_std, dt)
+        inp.m_w_a = _draw(rng, (l, cfg.m_m), w_std, dt)
+        if cfg.router_noise:
+            inp.noise_m_patch = rng.standard_normal(size=(b, cfg.n_m, cfg.m_m), dtype=np.float32)
     return inp
 
 
 def small_config(name: str = "small", **kw) -> LayerConfig:
     """A config with every size overridable, for randomly drawn tiny shapes in tests."""
     base = dict(b=2, l=24, d=16, n_a=3, d_h=8, m=4, c=2, k_a=2, n_m=3, d_e=8, k_m=2,
-                dtype=F32, seed=0, router_noise=False)
+                dtype=F32, seed=0, router_noise=False, m_m=1, c_m=1)
     base.update(kw)
     return LayerConfig(name, **base)
