@@ -31,14 +31,15 @@ def layer_flops(c) -> dict:
     qkv = c.b * c.k_a * 6 * c.l_a * c.d * c.d_h
     attn = c.b * c.k_a * 4 * c.l_a * c.l_a * c.d_h
     outp = c.b * c.k_a * 2 * c.l_a * c.d_h * c.d
-    uome = c.b * c.k_m * 4 * c.l * c.d * c.d_e
+    uome = c.b * c.k_m * 4 * (c.c_m * (c.l // c.m_m)) * c.d * c.d_e   # rows an MLP expert sees: all of l unless data-selected
     return dict(routers=routers, qkv=qkv, attention=attn, out_proj=outp, uome=uome,
                 total=routers + qkv + attn + outp + uome)
 
 
 def describe(c) -> str:
+    ds = f" m{c.m_m} c{c.c_m}" if c.m_m > 1 else ""
     return (f"{c.name}: b{c.b} l{c.l} d{c.d}; SMHA n{c.n_a} d_h{c.d_h} m{c.m} c{c.c} k{c.k_a}; "
-            f"UoME n{c.n_m} d_e{c.d_e} k{c.k_m}; {c.dtype}")
+            f"UoME n{c.n_m} d_e{c.d_e} k{c.k_m}{ds}; {c.dtype}")
 
 
 def run_stage(args, cfg, dev, B, torch) -> int:
@@ -48,7 +49,8 @@ def run_stage(args, cfg, dev, B, torch) -> int:
     dev.route_m()
     hidden = torch.empty((cfg.b, cfg.l, cfg.k_m * cfg.d_e), dtype=dev.tdtype, device=dev.device)
     h = torch.empty((cfg.b, cfg.k_a, cfg.l_a, cfg.d), dtype=dev.tdtype, device=dev.device)
-    B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden)
+    if cfg.m_m == 1:
+        B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden)
     calls = {
         "route_a": dev.route_a, "smha": dev.smha_forward, "route_m": dev.route_m, "uome": dev.uome_forward,
         "uome_up": lambda: B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden),
@@ -83,6 +85,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--causal", action="store_true", help="SMHA with the shared causal mask (Sec. III-C.3)")
     ap.add_argument("--rope-dim", type=int, default=0, help="SMHA with partial RoPE on the last N dims (Eq. 32)")
+    ap.add_argument("--uome-data-selection", default=None, metavar="M,C",
+                    help="UoME with patch-wise data selection (Eq. 37): M patches, C kept per expert")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
@@ -105,9 +109,15 @@ def main() -> int:
         return 2
     B.lib()  # fail loudly if the HIP library is not built
     cfg = synth.CONFIGS[args.workload]
+    uome_ds = args.uome_data_selection is not None
+    if uome_ds:
+        import dataclasses
+        m_m, c_m = (int(v) for v in args.uome_data_selection.split(","))
+        cfg = dataclasses.replace(cfg, m_m=m_m, c_m=c_m)
     inp = synth.make_inputs(cfg)
+    inp.noise_m_patch = None   # the layer call takes no noise on the UoME patch logits
     fa = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | B.FLAG_GATE_PATCH | (B.FLAG_CAUSAL if args.causal else 0)
-    fm = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT
+    fm = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | (B.FLAG_GATE_PATCH if uome_ds else 0)
     dev = DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim)
     torch.cuda.set_device(0)
 
@@ -150,6 +160,8 @@ def main() -> int:
     up = lambda: B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden)
     dev.smha_forward()          # u, then the UoME routing the GEMM reads
     dev.route_m()
+    if uome_ds:                 # no separate entry point for the first layer: time the block's two GEMMs together
+        up = dev.uome_forward
     for _ in range(max(3, args.warmup)):
         up()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -160,15 +172,16 @@ def main() -> int:
     ev1.record()
     torch.cuda.synchronize()
     up_ms = ev0.elapsed_time(ev1) / args.steps
-    up_flops = 2.0 * cfg.b * cfg.l * cfg.d * cfg.k_m * cfg.d_e
+    up_flops = float(fl["uome"]) if uome_ds else 2.0 * cfg.b * cfg.l * cfg.d * cfg.k_m * cfg.d_e
     is_bf16 = cfg.dtype == synth.BF16
     peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
     achieved = up_flops / (up_ms * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not uome_ds:
         traffic = json.load(open(tpath)).get(f"uome_up:{cfg.name}")
-    roofline = {"kernel": "uome_up (Eq. 38 grouped GEMM + SiLU + gate)", "bound": "mfma",
+    roofline = {"kernel": "uome_forward, data selection (Eq. 37-40: both grouped GEMMs)" if uome_ds
+                else "uome_up (Eq. 38 grouped GEMM + SiLU + gate)", "bound": "mfma",
                 "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 5), "traffic": traffic,
                 "flops_per_launch": up_flops, "ms_per_launch": round(up_ms, 5)}
@@ -205,7 +218,8 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
         "config": {"workload": describe(cfg),
                    "flags": "residual+expert gate+patch gate" + ("+causal" if args.causal else "") +
-                            (f"+rope{args.rope_dim}" if args.rope_dim else ""),
+                            (f"+rope{args.rope_dim}" if args.rope_dim else "") +
+                            ("; UoME data selection, +patch gate" if uome_ds else ""),
                    "seed": cfg.seed, "launch": launch},
         "ms_per_step_eager": round(eager_ms, 5),
         "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 3),

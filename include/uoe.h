@@ -141,12 +141,15 @@ int uoe_smha_forward_masked(const uoe_block_desc *blk, const void *x, const void
                             void *hip_stream);
 
 /*
- * Union-of-MLP-Experts in expert-selection mode on given routing results
- * (Eq. 38-40 with Eq. 24-26): out[b] = u[b] + sum over the sample's k experts of
- * gate * SiLU(u[b] A^I_i) A^O_i.  The second layer is linear.
+ * Union-of-MLP-Experts on given routing results (Eq. 37-40).  The second layer is linear.
  *   a_in [n,d,d_e]; a_out [n,d_e,d]; expert_idx [b,k]; expert_gate [b,n] or NULL
- *   patch_idx / patch_gate must be NULL and blk->c == blk->m (data-selection UoME
- *   is not in this build: UOE_ERR_UNSUPPORTED).
+ * Expert-selection mode (patch_idx NULL; needs blk->c == blk->m and no UOE_FLAG_GATE_PATCH, with
+ * Eq. 24-26): out[b] = u[b] + sum over the sample's k experts of gate * SiLU(u[b] A^I_i) A^O_i.
+ * Data-selection mode (patch_idx [b,n,c] given, ascending per (b,i); Eq. 37 with Eq. 12-18):
+ * active expert i processes only the tokens of its c selected patches, and its rows are added
+ * back onto those tokens, weighted by expert_gate[b,i] and/or patch_gate[b,i,patch] as the flags
+ * say (patch_gate [b,n,m], required with UOE_FLAG_GATE_PATCH).  Tokens nobody selected keep the
+ * residual only.  Wrong pointer combinations: UOE_ERR_INVALID_ARG.
  *   out [b,l,d] must not alias u.  Deterministic: no atomics.
  */
 int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
@@ -173,8 +176,10 @@ typedef struct {
     const void *w_expert, *w_b, *w_a, *wq, *wk, *wv, *wo;
 } uoe_smha_weights;
 
+/* w_b [d,n] / w_a [l,m]: the UoME block's data-selection router (Eq. 13), both NULL for
+ * expert selection only */
 typedef struct {
-    const void *w_expert, *a_in, *a_out;
+    const void *w_expert, *w_b, *w_a, *a_in, *a_out;
 } uoe_uome_weights;
 
 /* Optional copies of a block's routing results; any member may be NULL. */
@@ -187,9 +192,11 @@ typedef struct {
 
 /*
  * One UoE layer (Sec. III-C): route on x, SMHA -> u; route on u with the UoME
- * router, UoME -> out.  `smha` and `uome` must agree on b, l, d and dtype; the
- * UoME descriptor has m == c (expert-selection mode; the patch members of
- * `routing_m` are not written).  out must not alias x.
+ * router(s), UoME -> out.  `smha` and `uome` must agree on b, l, d and dtype.  A
+ * UoME descriptor with m == c runs in expert-selection mode (the patch members of
+ * `routing_m` are not written); with c < m it needs wm->w_b / wm->w_a and runs in
+ * data-selection mode (no additive noise on the UoME patch logits in this call).
+ * out must not alias x.
  */
 int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
                       const float *noise_a_expert, const float *noise_a_patch,

@@ -41,7 +41,7 @@ class SmhaWeights(ctypes.Structure):
 
 
 class UomeWeights(ctypes.Structure):
-    _fields_ = [(f, ctypes.c_void_p) for f in ("w_expert", "a_in", "a_out")]
+    _fields_ = [(f, ctypes.c_void_p) for f in ("w_expert", "w_b", "w_a", "a_in", "a_out")]
 
 
 class RoutingOut(ctypes.Structure):
@@ -180,8 +180,8 @@ def smha_weights(w_expert, w_b, w_a, wq, wk, wv, wo) -> SmhaWeights:
     return SmhaWeights(*(_ptr(t) for t in (w_expert, w_b, w_a, wq, wk, wv, wo)))
 
 
-def uome_weights(w_expert, a_in, a_out) -> UomeWeights:
-    return UomeWeights(*(_ptr(t) for t in (w_expert, a_in, a_out)))
+def uome_weights(w_expert, a_in, a_out, w_b=None, w_a=None) -> UomeWeights:
+    return UomeWeights(*(_ptr(t) for t in (w_expert, w_b, w_a, a_in, a_out)))
 
 
 def routing_out(expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None) -> RoutingOut:

@@ -77,10 +77,22 @@ SmhaWs smha_ws(const uoe_block_desc *d)
     return w;
 }
 
-size_t uome_ws(const uoe_block_desc *d)
+// hidden activations: [b, l, k*d_e] (expert selection) or [b*k, l_a, d_e] (data selection, never
+// larger); behind them the inverse map of the data-selection mode
+struct UomeWs {
+    size_t hidden, inv_cnt, inv_ent, total;
+};
+UomeWs uome_ws_layout(const uoe_block_desc *d)
 {
-    return up((size_t)d->b * d->l * d->k * d->width * elem_size(d->dtype));
+    UomeWs w;
+    size_t off = 0;
+    w.hidden = off; off += up((size_t)d->b * d->l * d->k * d->width * elem_size(d->dtype));
+    w.inv_cnt = off; off += up((size_t)d->b * d->m * sizeof(int32_t));
+    w.inv_ent = off; off += up((size_t)d->b * d->m * d->k * sizeof(int32_t));
+    w.total = off;
+    return w;
 }
+size_t uome_ws(const uoe_block_desc *d) { return uome_ws_layout(d).total; }
 
 struct RoutingBuf {
     size_t expert_idx, expert_gate, patch_idx, patch_gate, total;
@@ -156,16 +168,34 @@ int do_smha(const uoe_block_desc *blk, const void *x, const void *wq, const void
     return launch_smha(a, blk->dtype == UOE_BF16, st) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
 }
 
+// patch_idx NULL: expert-selection mode (needs c == m and no patch gate).  Otherwise the
+// data-selection mode of Eq. 37: every active expert processes its c selected patches.
 int do_uome(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
-            const int32_t *expert_idx, const float *expert_gate, void *out, void *ws, size_t ws_bytes,
-            hipStream_t st)
+            const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
+            const float *patch_gate, void *out, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if (!u || !a_in || !a_out || !expert_idx || !out) return UOE_ERR_INVALID_ARG;
     if (!aligned16(u) || !aligned16(a_in) || !aligned16(a_out) || !aligned16(out)) return UOE_ERR_INVALID_ARG;
     if (out == u) return UOE_ERR_INVALID_ARG;
     if ((blk->flags & UOE_FLAG_GATE_EXPERT) && !expert_gate) return UOE_ERR_INVALID_ARG;
-    if (blk->flags & UOE_FLAG_GATE_PATCH) return UOE_ERR_UNSUPPORTED;
+    if (!patch_idx && (blk->c != blk->m || (blk->flags & UOE_FLAG_GATE_PATCH))) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_PATCH) && !patch_gate) return UOE_ERR_INVALID_ARG;
     if (!ws || ws_bytes < uome_ws(blk) || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+    if (patch_idx) {
+        const UomeWs w = uome_ws_layout(blk);
+        UomeDsArgs a{};
+        a.u = u; a.a_in = a_in; a.a_out = a_out;
+        a.expert_idx = expert_idx; a.patch_idx = patch_idx;
+        a.expert_gate = expert_gate; a.patch_gate = patch_gate;
+        a.out = out;
+        a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = blk->m; a.c = blk->c;
+        a.d_e = blk->width;
+        a.flags = blk->flags;
+        a.hidden = at(ws, w.hidden);
+        a.inv_cnt = reinterpret_cast<int32_t *>(at(ws, w.inv_cnt));
+        a.inv_ent = reinterpret_cast<int32_t *>(at(ws, w.inv_ent));
+        return launch_uome_ds(a, blk->dtype == UOE_BF16, st) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+    }
 
     UomeArgs a{};
     a.u = u; a.a_in = a_in; a.a_out = a_out;
@@ -263,8 +293,7 @@ int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in,
 {
     const int rc = check_desc(blk, DESC_UOME);
     if (rc != UOE_OK) return rc;
-    if (blk->c != blk->m || patch_idx || patch_gate) return UOE_ERR_UNSUPPORTED;  // data-selection UoME
-    return do_uome(blk, u, a_in, a_out, expert_idx, expert_gate, out, ws, ws_bytes,
+    return do_uome(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_gate, out, ws, ws_bytes,
                    static_cast<hipStream_t>(hip_stream));
 }
 
@@ -316,21 +345,25 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
     if (!wa || !wm || !x || !out || out == x) return UOE_ERR_INVALID_ARG;
     if (smha->b != uome->b || smha->l != uome->l || smha->d != uome->d || smha->dtype != uome->dtype)
         return UOE_ERR_INVALID_ARG;
-    if (uome->c != uome->m) return UOE_ERR_UNSUPPORTED;
+    const bool uome_ds = uome->c != uome->m;
+    if (uome_ds && (!wm->w_b || !wm->w_a)) return UOE_ERR_INVALID_ARG;
     // everything the per-block launches would reject is rejected here, before the first launch
     if (!wa->wq || !wa->wk || !wa->wv || !wa->wo || !wm->a_in || !wm->a_out) return UOE_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(out) || !aligned16(wa->w_expert) || !aligned16(wa->w_b) || !aligned16(wa->w_a) ||
         !aligned16(wa->wq) || !aligned16(wa->wk) || !aligned16(wa->wv) || !aligned16(wa->wo) ||
-        !aligned16(wm->w_expert) || !aligned16(wm->a_in) || !aligned16(wm->a_out))
+        !aligned16(wm->w_expert) || !aligned16(wm->w_b) || !aligned16(wm->w_a) || !aligned16(wm->a_in) ||
+        !aligned16(wm->a_out))
         return UOE_ERR_INVALID_ARG;
-    if ((wa->w_b == nullptr) != (wa->w_a == nullptr)) return UOE_ERR_INVALID_ARG;
+    if ((wa->w_b == nullptr) != (wa->w_a == nullptr) || (wm->w_b == nullptr) != (wm->w_a == nullptr))
+        return UOE_ERR_INVALID_ARG;
     if ((!wa->w_expert && smha->k != smha->n) || (!wa->w_b && smha->c != smha->m) ||
         (!wm->w_expert && uome->k != uome->n))
         return UOE_ERR_INVALID_ARG;
     if ((!wa->w_expert && noise_a_expert) || (!wa->w_b && noise_a_patch) || (!wm->w_expert && noise_m_expert))
         return UOE_ERR_INVALID_ARG;
     if (wa->w_b && (size_t)smha->n * smha->d * elem_size(smha->dtype) > 48 * 1024) return UOE_ERR_UNSUPPORTED;
-    if (uome->flags & UOE_FLAG_GATE_PATCH) return UOE_ERR_UNSUPPORTED;
+    if (uome_ds && (size_t)uome->n * uome->d * elem_size(uome->dtype) > 48 * 1024) return UOE_ERR_UNSUPPORTED;
+    if (!uome_ds && (uome->flags & UOE_FLAG_GATE_PATCH)) return UOE_ERR_INVALID_ARG;
     const size_t need = uoe_workspace_bytes(smha, uome);
     if (!ws || ws_bytes < need || !aligned16(ws)) return UOE_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -359,6 +392,8 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
     float *a_pgate = static_cast<float *>(pick(routing_a ? routing_a->patch_gate : nullptr, rabuf, ra.patch_gate));
     int32_t *m_eidx = static_cast<int32_t *>(pick(routing_m ? routing_m->expert_idx : nullptr, rmbuf, rm.expert_idx));
     float *m_egate = static_cast<float *>(pick(routing_m ? routing_m->expert_gate : nullptr, rmbuf, rm.expert_gate));
+    int32_t *m_pidx = static_cast<int32_t *>(pick(routing_m ? routing_m->patch_idx : nullptr, rmbuf, rm.patch_idx));
+    float *m_pgate = static_cast<float *>(pick(routing_m ? routing_m->patch_gate : nullptr, rmbuf, rm.patch_gate));
 
     rc = do_route(smha, smha->m, smha->c, x, wa->w_expert, wa->w_b, wa->w_a, noise_a_expert, noise_a_patch,
                   a_eidx, a_egate, a_pidx, a_pgate, route_a_ws, route_a_bytes, st);
@@ -366,11 +401,18 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
     rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, a_eidx, a_egate, a_pidx, a_pgate, nullptr, u, smha_scratch,
                  smha_bytes, st);
     if (rc != UOE_OK) return rc;
-    // the UoME router reads u, the finished SMHA output (expert-selection mode: one patch = the sample)
+    // the UoME routers read u, the finished SMHA output
+    if (uome_ds) {
+        rc = do_route(uome, uome->m, uome->c, u, wm->w_expert, wm->w_b, wm->w_a, noise_m_expert, nullptr, m_eidx,
+                      m_egate, m_pidx, m_pgate, route_m_ws, route_m_bytes, st);
+        if (rc != UOE_OK) return rc;
+        return do_uome(uome, u, wm->a_in, wm->a_out, m_eidx, m_egate, m_pidx, m_pgate, out, uome_scratch, uome_bytes, st);
+    }
+    // expert-selection mode: one patch = the sample
     rc = do_route(uome, 1, 1, u, wm->w_expert, nullptr, nullptr, noise_m_expert, nullptr, m_eidx, m_egate,
                   nullptr, nullptr, route_m_ws, route_m_bytes, st);
     if (rc != UOE_OK) return rc;
-    return do_uome(uome, u, wm->a_in, wm->a_out, m_eidx, m_egate, out, uome_scratch, uome_bytes, st);
+    return do_uome(uome, u, wm->a_in, wm->a_out, m_eidx, m_egate, nullptr, nullptr, out, uome_scratch, uome_bytes, st);
 }
 
 }  // extern "C"

@@ -107,6 +107,18 @@ struct UomeArgs {
     void *hidden;                             // [b, l, k*d_e], storage dtype
 };
 
+// UoME with patch-wise data selection (Eq. 37-40): routing as for SMHA, hidden per active unit
+struct UomeDsArgs {
+    const void *u, *a_in, *a_out;
+    const int32_t *expert_idx, *patch_idx;
+    const float *expert_gate, *patch_gate;    // NULL when the matching flag is off
+    void *out;
+    int b, l, d, n, k, m, c, d_e;
+    uint32_t flags;
+    void *hidden;                             // [b*k, l_a, d_e], storage dtype
+    int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k] (engines without in-kernel segment lists)
+};
+
 struct GatherArgs {
     const void *x;
     const int32_t *expert_idx, *patch_idx;
@@ -121,6 +133,7 @@ hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome(const UomeArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st);    // Eq. 38 only
 hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // Eq. 39-40 only
+hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st);
 
 // host-side sizing shared by api.cpp and the launchers
 int route_tokens_per_chunk(int b, int l);

@@ -112,6 +112,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     if constexpr (P::kColScale) {
         if (tid < BN / 8) my_scale = p.col_scale(g, n0 + tid * 8 < N ? n0 + tid * 8 : 0);
     }
+    float rs[TM];
+    load_row_scale<P, TM>(p, rs, g, m0 + wm0, M, lane);
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     __syncthreads();  // every wave has finished reading operands: LDS is free for the epilogue
 
     uint16_t(*stage)[SPITCH] = reinterpret_cast<uint16_t(*)[SPITCH]>(lds_raw) + (size_t)wave * WM;
-    wave_epilogue<P, TM, TN, SPITCH>(p, acc, stage, coltab, g, m0 + wm0, n0 + wn0, wn0, M, N, lane);
+    wave_epilogue<P, TM, TN, SPITCH>(p, acc, stage, coltab, rs, g, m0 + wm0, n0 + wn0, wn0, M, N, lane);
 }
 
 template <typename P, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC = 1>

@@ -80,9 +80,25 @@ __device__ __forceinline__ void fill_col_scale(const P &p, float *coltab, int g,
 // of SPITCH elements, private to the wave) and then moves 16-byte pieces of rows to memory,
 // residual pieces loaded a batch ahead of the stores.  wcol0 = first column of the wave tile
 // inside the workgroup tile (indexes coltab); (grow0, gcol0) = its global position.
+// Per-row factors of the rows this lane owns in the epilogue (rows i*32 + lane%32 of the wave tile),
+// fetched before the K loop like the column factors.
+template <typename P, int TM>
+__device__ __forceinline__ void load_row_scale(const P &p, float (&rs)[TM], int g, int grow0, int M, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        rs[i] = 1.0f;
+        if constexpr (P::kRowScale) {
+            const int row = grow0 + i * 32 + (lane & 31);
+            rs[i] = p.row_scale(g, row < M ? row : M - 1);
+        }
+    }
+}
+
 template <typename P, int TM, int TN, int SPITCH>
 __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN], uint16_t (*stage)[SPITCH], const float *coltab,
-                                              int g, int grow0, int gcol0, int wcol0, int M, int N, int lane)
+                                              const float (&rs)[TM], int g, int grow0, int gcol0, int wcol0, int M, int N,
+                                              int lane)
 {
     constexpr int WM = TM * 32, WN = TN * 32;
     const int lr = lane & 31, lh = lane >> 5;
@@ -95,8 +111,9 @@ __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN
             if constexpr (P::kColScale) sc = coltab[(wcol0 + cl) >> 3];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const uint32_t w0 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 0], sc), p.epi(acc[i][j][qg * 4 + 1], sc));
-                const uint32_t w1 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 2], sc), p.epi(acc[i][j][qg * 4 + 3], sc));
+                const float s2 = P::kRowScale ? sc * rs[i] : sc;
+                const uint32_t w0 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 0], s2), p.epi(acc[i][j][qg * 4 + 1], s2));
+                const uint32_t w1 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 2], s2), p.epi(acc[i][j][qg * 4 + 3], s2));
                 *reinterpret_cast<uint2 *>(&stage[i * 32 + lr][cl]) = make_uint2(w0, w1);
             }
         }
@@ -188,6 +205,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
     const long bstride = p.b_stride();
 
     fill_col_scale<P, BN>(p, coltab, g, n0, N, tid, NT);  // published by the barrier before the K loop
+    float rs[TM];
+    load_row_scale<P, TM>(p, rs, g, m0 + wm0, M, lane);
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -295,7 +314,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(P p, T
     // Epilogue: the operand buffers are free now (the loop ended on a barrier); each wave stages its
     // own tile there.
     uint16_t(*stage)[SPITCH] = reinterpret_cast<uint16_t(*)[SPITCH]>(lds_raw) + (size_t)wave * WM;
-    wave_epilogue<P, TM, TN, SPITCH>(p, acc, stage, coltab, g, m0 + wm0, n0 + wn0, wn0, M, N, lane);
+    wave_epilogue<P, TM, TN, SPITCH>(p, acc, stage, coltab, rs, g, m0 + wm0, n0 + wn0, wn0, M, N, lane);
 }
 
 template <typename P, int BM, int BN, int BK, int WAVES_M, int WAVES_N>

@@ -13,6 +13,8 @@
 //   kColScale / col_scale(g, nn)  a per-column factor (constant over 8-column groups), fetched
 //                                 once per tile before the K loop
 //   epi(v, scale)                 per-element math
+//   kRowScale / row_scale(g, m)   a per-row factor, fetched once per tile before the K loop; the
+//                                 epilogue passes col_scale * row_scale to epi
 //   has_residual() / res8(g, m, nn)  the 16-byte piece of the residual row, loaded in batches
 //   put8(g, m, nn, piece)         plain store of a finished piece
 // K and N are concatenations of per-expert segments of length `width`; since width % 8 == 0 an
@@ -93,6 +95,7 @@ template <typename T> struct QkvProblem {
     __device__ const T *b_ptr_ctx(int g, int seg, int nn, uint32_t) const { return b_seg_ptr(g, seg, nn); }
     // vector epilogue (MFMA engines)
     static constexpr bool kPrepare = false;
+    static constexpr bool kRowScale = false;
     static constexpr bool kColScale = true;
     __device__ float col_scale(int, int nn) const { return nn < d_h ? q_scale : 1.0f; }
     __device__ float epi(float val, float scale) const { return val * scale; }
@@ -159,6 +162,7 @@ template <typename T> struct OutProjProblem {
     // whether slot s picked this patch (at most one t per slot does), then the slots that did are
     // listed in slot order, which fixes the summation order.  Returns K; ends on a barrier.
     static constexpr bool kPrepare = true;
+    static constexpr bool kRowScale = false;
     __device__ int prepare(int g, uint32_t *segtab, int tid, int nthreads) const
     {
         __shared__ int slot_t[32], slot_e[32];
@@ -252,6 +256,7 @@ template <typename T> struct UomeUpProblem {
         hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate);
     }
     static constexpr bool kPrepare = false;
+    static constexpr bool kRowScale = false;
     static constexpr bool kColScale = true;
     __device__ float col_scale(int g, int nn) const { return col_ctx(g, nn); }
     __device__ float epi(float val, float gate) const { return silu_fast(val) * gate; }
@@ -260,6 +265,62 @@ template <typename T> struct UomeUpProblem {
     __device__ void put8(int g, int r, int nn, uint4 piece) const
     {
         *reinterpret_cast<uint4 *>(hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + nn) = piece;
+    }
+};
+
+// UoME with patch-wise data selection, first layer (Eq. 37-38): group = active unit (b, slot s);
+// M = l_a rows gathered through the unit's patch indices (Eq. 18 folded into the A-row lookup, as
+// for QKV); K = d; N = d_e.  Epilogue: SiLU, times the weight of the row's contribution (expert
+// gate and/or the gate of the row's patch): the second layer is linear, so the weight can ride on
+// the hidden activations and the output-stationary second GEMM needs no per-segment scale.
+template <typename T> struct UomeDsUpProblem {
+    const T *u, *a_in;
+    const int32_t *expert_idx, *patch_idx;
+    const float *expert_gate, *patch_gate;  // NULL: weight 1
+    T *hidden;                              // [units, l_a, d_e]
+    int l, d, n, kact, m, c, l_p, l_a, d_e;
+
+    __device__ int rows(int) const { return l_a; }
+    __device__ int kdim(int) const { return d; }
+    __device__ int ncols() const { return d_e; }
+    __device__ int kseg() const { return d; }
+    __device__ long b_stride() const { return d_e; }
+    __device__ int expert(int g) const { return clampi(expert_idx[g], n); }
+    __device__ int patch(int g, int r) const
+    {
+        return clampi(patch_idx[((size_t)(g / kact) * n + expert(g)) * c + r / l_p], m);
+    }
+    __device__ const T *a_seg_ptr(int g, int r, int) const
+    {
+        return u + ((size_t)(g / kact) * l + patch(g, r) * l_p + r % l_p) * d;
+    }
+    __device__ const T *b_seg_ptr(int g, int, int nn) const { return a_in + (size_t)expert(g) * d * d_e + nn; }
+    __device__ float row_scale(int g, int r) const
+    {
+        const int bb = g / kact, i = expert(g);
+        float w = expert_gate ? expert_gate[(size_t)bb * n + i] : 1.0f;
+        if (patch_gate) w *= patch_gate[((size_t)bb * n + i) * m + patch(g, r)];
+        return w;
+    }
+    typedef int ColCtx;
+    __device__ ColCtx col_ctx(int, int) const { return 0; }
+    __device__ void store(int g, int r, int nn, float val, const ColCtx &) const
+    {
+        hidden[((size_t)g * l_a + r) * d_e + nn] = from_f32<T>(silu(val) * row_scale(g, r));
+    }
+    __device__ uint32_t seg_ctx(int, int) const { return 0; }
+    __device__ const T *a_ptr_ctx(int g, int r, int seg, uint32_t) const { return a_seg_ptr(g, r, seg); }
+    __device__ const T *b_ptr_ctx(int g, int seg, int nn, uint32_t) const { return b_seg_ptr(g, seg, nn); }
+    static constexpr bool kPrepare = false;
+    static constexpr bool kRowScale = true;
+    static constexpr bool kColScale = false;
+    __device__ float col_scale(int, int) const { return 1.0f; }
+    __device__ float epi(float val, float w) const { return silu_fast(val) * w; }
+    __device__ bool has_residual() const { return false; }
+    __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const
+    {
+        *reinterpret_cast<uint4 *>(hidden + ((size_t)g * l_a + r) * d_e + nn) = piece;
     }
 };
 
@@ -299,6 +360,7 @@ template <typename T> struct UomeDownProblem {
         out[at] = from_f32<T>(val);
     }
     static constexpr bool kPrepare = false;
+    static constexpr bool kRowScale = false;
     static constexpr bool kColScale = false;
     __device__ float col_scale(int, int) const { return 1.0f; }
     __device__ float epi(float val, float) const { return val; }

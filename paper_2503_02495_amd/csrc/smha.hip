@@ -500,6 +500,94 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, a.b * a.m, l_p, a.d, st);
 }
 
+// ---------------------------------------------------------------------------------------------
+// UoME with patch-wise data selection (Eq. 37-40).  Same skeleton as SMHA without the attention:
+// first layer per active unit on its gathered rows (UomeDsUpProblem), second layer + index add as
+// the output-stationary contraction over the experts that picked each patch (OutProjProblem with
+// A^O in the place of W^o and the hidden activations in the place of o).
+template <typename T> static UomeDsUpProblem<T> make_ds_up(const UomeDsArgs &a)
+{
+    UomeDsUpProblem<T> up;
+    up.u = static_cast<const T *>(a.u);
+    up.a_in = static_cast<const T *>(a.a_in);
+    up.expert_idx = a.expert_idx;
+    up.patch_idx = a.patch_idx;
+    up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
+    up.patch_gate = (a.flags & F_GATE_PATCH) ? a.patch_gate : nullptr;
+    up.hidden = static_cast<T *>(a.hidden);
+    up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.m = a.m; up.c = a.c;
+    up.l_p = a.l / a.m; up.l_a = a.c * up.l_p; up.d_e = a.d_e;
+    return up;
+}
+
+template <typename T> static OutProjProblem<T> make_ds_down(const UomeDsArgs &a)
+{
+    OutProjProblem<T> op;
+    op.o = static_cast<const T *>(a.hidden);
+    op.o_lo = nullptr;
+    op.parts = 1;
+    op.wo = static_cast<const T *>(a.a_out);
+    op.x = static_cast<const T *>(a.u);
+    op.expert_idx = a.expert_idx;
+    op.patch_idx = a.patch_idx;
+    op.inv_cnt = a.inv_cnt;
+    op.inv_ent = a.inv_ent;
+    op.out = static_cast<T *>(a.out);
+    op.l = a.l; op.d = a.d; op.n = a.n; op.kact = a.k; op.m = a.m; op.c = a.c;
+    op.l_p = a.l / a.m; op.l_a = a.c * op.l_p; op.d_h = a.d_e; op.flags = a.flags;
+    return op;
+}
+
+static hipError_t launch_inverse_map_ds(const UomeDsArgs &a, hipStream_t st)
+{
+    SmhaArgs s{};  // the inverse map only reads the routing fields
+    s.expert_idx = a.expert_idx; s.patch_idx = a.patch_idx;
+    s.b = a.b; s.n = a.n; s.k = a.k; s.m = a.m; s.c = a.c;
+    s.inv_cnt = a.inv_cnt; s.inv_ent = a.inv_ent;
+    return launch_inverse_map(s, st);
+}
+
+template <typename T> static hipError_t uome_ds_generic(const UomeDsArgs &a, hipStream_t st)
+{
+    const int l_p = a.l / a.m, l_a = a.c * l_p;
+    hipError_t err;
+    if ((err = launch_inverse_map_ds(a, st)) != hipSuccess) return err;
+    if ((err = launch_gemm_generic<T>(make_ds_up<T>(a), a.b * a.k, l_a, a.d_e, st)) != hipSuccess) return err;
+    return launch_gemm_generic<T>(make_ds_down<T>(a), a.b * a.m, l_p, a.d, st);
+}
+
+static hipError_t uome_ds_mfma(const UomeDsArgs &a, hipStream_t st)
+{
+    typedef UomeDsUpProblem<bf16_t> UP;
+    typedef OutProjProblem<bf16_t> OP;
+    const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
+    hipError_t err;
+    const bool out_dma = (long)a.k * a.c < (1L << 20);
+    if (!out_dma && (err = launch_inverse_map_ds(a, st)) != hipSuccess) return err;
+    const UP up = make_ds_up<bf16_t>(a);
+    const long tiles256 = (long)units * ((l_a + 255) / 256) * ((a.d_e + 127) / 128);
+    const long tiles128 = (long)units * ((l_a + 127) / 128) * ((a.d_e + 127) / 128);
+    if (l_a > 128 && tiles256 >= 512) err = launch_gemm_dma<UP, 256, 128, 32, 2, 2, 3, 2>(up, units, l_a, a.d_e, st);
+    else if (l_a > 64 && a.d % 64 == 0 && tiles128 < 256) err = launch_gemm_dma<UP, 64, 128, 64, 2, 2, 3, 2>(up, units, l_a, a.d_e, st);
+    else if (l_a > 64) err = a.d % 64 == 0 ? launch_gemm_dma<UP, 128, 128, 64, 2, 2, 2, 2>(up, units, l_a, a.d_e, st)
+                                           : launch_gemm_dma<UP, 128, 128, 32, 2, 2, 4, 2>(up, units, l_a, a.d_e, st);
+    else err = launch_gemm_mfma<UP, 64, 64, 32, 2, 2>(up, units, l_a, a.d_e, st);
+    if (err != hipSuccess) return err;
+    const OP op = make_ds_down<bf16_t>(a);
+    if (!out_dma) {
+        if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
+        return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
+    }
+    if (l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 4, 4, 2>(op, a.b * a.m, l_p, a.d, st);
+    return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, a.b * a.m, l_p, a.d, st);
+}
+
+hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st)
+{
+    if (bf16 && a.d % 32 == 0 && a.d_e % 32 == 0) return uome_ds_mfma(a, st);
+    return bf16 ? uome_ds_generic<bf16_t>(a, st) : uome_ds_generic<float>(a, st);
+}
+
 hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st)
 {
     if (bf16 && a.d % 32 == 0 && a.d_h % 32 == 0) return smha_mfma(a, st);

@@ -45,9 +45,12 @@ class DeviceLayer:
         self.m_w_expert, self.a_in, self.a_out = up(inp.m_w_expert), up(inp.a_in), up(inp.a_out)
         self.noise_a_expert, self.noise_a_patch = f32(inp.noise_a_expert), f32(inp.noise_a_patch)
         self.noise_m_expert = f32(inp.noise_m_expert)
+        self.m_w_b, self.m_w_a = up(getattr(inp, "m_w_b", None)), up(getattr(inp, "m_w_a", None))
+        self.noise_m_patch = f32(getattr(inp, "noise_m_patch", None))
+        self.uome_ds = cfg.m_m > 1
 
         self.smha = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_a, cfg.k_a, cfg.m, cfg.c, cfg.d_h, code, flags_a, rope_dim)
-        self.uome = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_m, cfg.k_m, 1, 1, cfg.d_e, code, flags_m)
+        self.uome = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_m, cfg.k_m, cfg.m_m, cfg.c_m, cfg.d_e, code, flags_m)
         nbytes = B.workspace_bytes(self.smha, self.uome)
         if nbytes == 0:
             raise B.UoeError(B.ERR_INVALID_ARG, "uoe_workspace_bytes")
@@ -61,12 +64,14 @@ class DeviceLayer:
         self.a_patch_gate = torch.zeros((cfg.b, cfg.n_a, cfg.m), **f)
         self.m_expert_idx = torch.full((cfg.b, cfg.k_m), -1, **i32)
         self.m_expert_gate = torch.zeros((cfg.b, cfg.n_m), **f)
+        self.m_patch_idx = torch.full((cfg.b, cfg.n_m, cfg.c_m), -1, **i32) if self.uome_ds else None
+        self.m_patch_gate = torch.zeros((cfg.b, cfg.n_m, cfg.m_m), **f) if self.uome_ds else None
         self.u = torch.zeros((cfg.b, cfg.l, cfg.d), dtype=self.tdtype, device=self.device)
         self.out = torch.zeros((cfg.b, cfg.l, cfg.d), dtype=self.tdtype, device=self.device)
         self.wa = B.smha_weights(self.a_w_expert, self.a_w_b, self.a_w_a, self.wq, self.wk, self.wv, self.wo)
-        self.wm = B.uome_weights(self.m_w_expert, self.a_in, self.a_out)
+        self.wm = B.uome_weights(self.m_w_expert, self.a_in, self.a_out, self.m_w_b, self.m_w_a)
         self.ra = B.routing_out(self.a_expert_idx, self.a_expert_gate, self.a_patch_idx, self.a_patch_gate)
-        self.rm = B.routing_out(self.m_expert_idx, self.m_expert_gate, None, None)
+        self.rm = B.routing_out(self.m_expert_idx, self.m_expert_gate, self.m_patch_idx, self.m_patch_gate)
 
     # each method is one C-ABI call on the current stream
     def route_a(self):
@@ -87,13 +92,15 @@ class DeviceLayer:
             B.smha_forward_masked(*args, pad_mask, self.u if out is None else out, self.ws)
 
     def route_m(self, u=None):
-        B.route(self.uome, self.u if u is None else u, self.m_w_expert, None, None, self.noise_m_expert, None,
-                self.m_expert_idx, self.m_expert_gate, None, None, self.ws)
+        B.route(self.uome, self.u if u is None else u, self.m_w_expert, self.m_w_b, self.m_w_a, self.noise_m_expert,
+                self.noise_m_patch, self.m_expert_idx, self.m_expert_gate, self.m_patch_idx, self.m_patch_gate, self.ws)
 
-    def uome_forward(self, expert_idx=None, expert_gate=None, u=None, out=None):
+    def uome_forward(self, expert_idx=None, expert_gate=None, u=None, out=None, patch_idx=None, patch_gate=None):
+        if self.uome_ds and patch_idx is None:
+            patch_idx, patch_gate = self.m_patch_idx, self.m_patch_gate
         B.uome_forward(self.uome, self.u if u is None else u, self.a_in, self.a_out,
                        self.m_expert_idx if expert_idx is None else expert_idx,
-                       self.m_expert_gate if expert_gate is None else expert_gate, None, None,
+                       self.m_expert_gate if expert_gate is None else expert_gate, patch_idx, patch_gate,
                        self.out if out is None else out, self.ws)
 
     def layer_forward(self):

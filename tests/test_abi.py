@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.BlockDesc) == 16 * 4
-    assert ctypes.sizeof(B.SmhaWeights) == 7 * 8 and ctypes.sizeof(B.UomeWeights) == 3 * 8
+    assert ctypes.sizeof(B.SmhaWeights) == 7 * 8 and ctypes.sizeof(B.UomeWeights) == 5 * 8
     assert ctypes.sizeof(B.RoutingOut) == 4 * 8
 
 
@@ -129,8 +129,13 @@ def test_smha_uome_layer_argument_validation():
     assert um(u, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # gate missing
     assert um(u, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
     ds = good(m=8, c=2, width=64, flags=B.FLAG_RESIDUAL)                    # data-selection UoME
-    assert um(ds, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_UNSUPPORTED
-    assert um(u, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_UNSUPPORTED
+    assert um(ds, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # c < m, no patch_idx
+    assert um(ds, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE + 16, FAKE, ws_bytes=8) == B.ERR_WORKSPACE      # accepted
+    dsg = good(m=8, c=2, width=64, flags=B.FLAG_RESIDUAL | B.FLAG_GATE_PATCH)
+    assert um(dsg, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # patch gate missing
+    assert um(dsg, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
+    ug = good(m=1, c=1, width=64, flags=B.FLAG_RESIDUAL | B.FLAG_GATE_PATCH)
+    assert um(ug, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # patch gate flag, no patches
 
     wa = B.smha_weights(*([FAKE] * 7))
     wm = B.uome_weights(FAKE, FAKE, FAKE)

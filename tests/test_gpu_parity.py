@@ -258,6 +258,119 @@ def test_uome_stage_parity_sampled_rows(name, flags):
     run_uome_stage(name, flags, rows=192)
 
 
+# --------------------------------------------------------------------------- UoME, data selection
+import dataclasses
+
+DS_CONFIGS = {
+    # fp32 (vector-ALU path), ragged patch length
+    "ds_f32_lp14": small(b=3, l=56, d=24, n_a=3, d_h=8, m=4, c=3, k_a=2, n_m=3, d_e=16, k_m=2, m_m=4, c_m=3),
+    "ds_f32_lp1": small(b=2, l=12, d=8, n_a=2, d_h=8, m=6, c=1, k_a=1, n_m=4, d_e=8, k_m=4, m_m=12, c_m=5),
+    # bf16: units of 128 rows, patches of 32 rows
+    "ds_bf16_lp32": small(b=3, l=192, d=64, n_a=4, d_h=32, m=6, c=2, k_a=2, n_m=4, d_e=64, k_m=2, m_m=6, c_m=4,
+                          dtype=synth.BF16),
+    # bf16: patches of 80 rows (not a tile multiple), K of the first layer not a multiple of 64
+    "ds_bf16_lp80": small(b=2, l=320, d=96, n_a=4, d_h=32, m=4, c=2, k_a=2, n_m=5, d_e=32, k_m=3, m_m=4, c_m=2,
+                          dtype=synth.BF16),
+    # bf16: units of at most 64 rows (register-staged engine for the first layer), noise on the routers
+    "ds_bf16_small_units": small(b=4, l=96, d=128, n_a=4, d_h=32, m=6, c=2, k_a=2, n_m=8, d_e=96, k_m=5, m_m=12,
+                                 c_m=3, dtype=synth.BF16, router_noise=True),
+    # the language-modeling shape with half of the patches kept per MLP expert
+    "ds_lm": dataclasses.replace(synth.CONFIGS["lm"], name="ds_lm", m_m=16, c_m=8),
+    # the large shape: 8 of 16 experts per sample, each on a quarter of the 128 patches
+    "ds_large": dataclasses.replace(synth.CONFIGS["large"], name="ds_large", m_m=128, c_m=32),
+}
+
+
+def ds_w_std(name):
+    cfg = DS_CONFIGS[name]
+    if name in ("ds_lm", "ds_large"):
+        return 0.02
+    return 0.2 if cfg.dtype == synth.F32 else 0.06
+
+
+@pytest.mark.parametrize("name", list(DS_CONFIGS))
+@pytest.mark.parametrize("flags", [0, R | GE, R | GE | GP])
+def test_uome_data_selection_stage_parity(name, flags):
+    """uoe_route + uoe_uome_forward in data-selection mode (Eq. 37-40) on the block input x."""
+    cfg = DS_CONFIGS[name]
+    print(f"uome data selection {name} flags={flags} seed={cfg.seed}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=ds_w_std(name))
+    dev = DeviceLayer(inp, R, flags)
+    dev.route_m(u=dev.x)
+    torch.cuda.synchronize()
+    ref = oracle.route(inp.x, cfg.n_m, cfg.k_m, cfg.m_m, cfg.c_m, inp.m_w_expert, inp.m_w_b, inp.m_w_a,
+                       inp.noise_m_expert, inp.noise_m_patch)
+    e_idx, p_idx = to_host(dev.m_expert_idx), to_host(dev.m_patch_idx)
+    check_valid_selection(e_idx, cfg.n_m)
+    check_valid_selection(p_idx, cfg.m_m)
+    check_indices(name + ":expert", e_idx, ref.expert_id, ref.expert_margin)
+    check_indices(name + ":patch", p_idx, ref.patch_id, ref.patch_margin)
+    np.testing.assert_allclose(to_host(dev.m_patch_gate), ref.patch_gate, rtol=GATE_RTOL, atol=1e-30)
+    # the block on the oracle's routing results
+    dev.uome_forward(expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
+                     expert_gate=to_device(ref.expert_gate.astype(np.float32), synth.F32, dev.device),
+                     patch_idx=torch.from_numpy(ref.patch_id).to(dev.device),
+                     patch_gate=to_device(ref.patch_gate.astype(np.float32), synth.F32, dev.device), u=dev.x)
+    torch.cuda.synchronize()
+    got = to_host(dev.out)
+    if name == "ds_large":  # tokens are independent in the MLP: the oracle takes whole sampled patches
+        keep = np.sort(np.random.default_rng(8).choice(cfg.m_m, 6, replace=False))
+        l_p = cfg.l // cfg.m_m
+        rows = np.concatenate([np.arange(p * l_p, (p + 1) * l_p) for p in keep])
+        want = np.zeros((cfg.b, len(rows), cfg.d))
+        for bb in range(cfg.b):
+            for t, pch in enumerate(keep):
+                sl = slice(t * l_p, (t + 1) * l_p)
+                # one patch at a time: the experts that selected it, as a 1-patch data selection
+                experts = [i for i in ref.expert_id[bb] if pch in ref.patch_id[bb, i]]
+                eid = np.array([experts], np.int32)
+                xs = inp.x[bb:bb + 1, pch * l_p:(pch + 1) * l_p]
+                if not experts:
+                    want[bb, sl] = xs[0] if flags & R else 0.0
+                    continue
+                pid1 = np.zeros((1, cfg.n_m, 1), np.int32)
+                gd1 = ref.patch_gate[bb:bb + 1, :, pch:pch + 1].astype(np.float32)
+                want[bb, sl] = oracle.uome(xs, inp.a_in, inp.a_out, eid, ref.expert_gate[bb:bb + 1].astype(np.float32),
+                                           flags, pid1, gd1, m=1)[0]
+        got = got[:, rows]
+    else:
+        want = oracle.uome(inp.x, inp.a_in, inp.a_out, ref.expert_id, ref.expert_gate.astype(np.float32), flags,
+                           ref.patch_id, ref.patch_gate.astype(np.float32), cfg.m_m)
+    err = scaled_err(got, want)
+    print(f"[uome-ds {name} flags={flags}] scaled err {err:.3e} (tol {TOL[cfg.dtype]:.0e})", flush=True)
+    assert err <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("name", ["ds_f32_lp14", "ds_bf16_lp32", "ds_lm"])
+def test_layer_with_data_selected_uome(name):
+    """uoe_layer_forward with a UoME descriptor that has c < m."""
+    cfg = DS_CONFIGS[name]
+    print(f"layer, data-selected UoME {name}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=ds_w_std(name))
+    inp.noise_m_patch = None  # the layer call has no input for it
+    fa, fm = R | GE | GP, R | GE | GP
+    dev = DeviceLayer(inp, fa, fm)
+    dev.layer_forward()
+    torch.cuda.synchronize()
+    out_layer = to_host(dev.out)
+    m_idx, m_pidx = to_host(dev.m_expert_idx), to_host(dev.m_patch_idx)
+    m_gate, m_pgate = to_host(dev.m_expert_gate), to_host(dev.m_patch_gate)
+    # stage-exact: reproduce u, route on it with the oracle, run the oracle's block on the GPU's u
+    dev.smha_forward()
+    torch.cuda.synchronize()
+    u_gpu = to_host(dev.u)
+    rm = oracle.route(u_gpu, cfg.n_m, cfg.k_m, cfg.m_m, cfg.c_m, inp.m_w_expert, inp.m_w_b, inp.m_w_a,
+                      inp.noise_m_expert, None)
+    check_indices(name + ":uome-expert", m_idx, rm.expert_id, rm.expert_margin)
+    check_indices(name + ":uome-patch", m_pidx, rm.patch_id, rm.patch_margin)
+    np.testing.assert_allclose(m_pgate, rm.patch_gate, rtol=GATE_RTOL, atol=1e-30)
+    want = oracle.uome(u_gpu, inp.a_in, inp.a_out, m_idx, m_gate.astype(np.float32), fm, m_pidx,
+                       m_pgate.astype(np.float32), cfg.m_m)
+    err = scaled_err(out_layer, want)
+    print(f"[layer-ds {name}] out scaled err {err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]
+
+
 # --------------------------------------------------------------------------- whole layer
 @pytest.mark.parametrize("name", ALL_NAMES)
 def test_layer_parity(name):
