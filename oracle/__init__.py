@@ -202,6 +202,42 @@ def route(x, n: int, k: int, m: int, c: int, w_expert=None, w_b=None, w_a=None,
     return Routing(e_id, g_e, p_id, g_d, e_margin, p_margin)
 
 
+@dataclass
+class Capacity:
+    capacity: np.ndarray      # [b] int32, Eq. 16
+    count: np.ndarray         # [b,n] int32: patches that put expert i among their top-k (Eq. 15)
+    load_f: np.ndarray        # [b,n] Eq. 43
+    load_p: np.ndarray        # [b,n] Eq. 44
+    margin: np.ndarray        # [b,m] relative gap between the k-th and (k+1)-th logit of a patch (inf if k == n)
+
+
+def capacity(gprime, k: int) -> Capacity:
+    """Dynamic capacity of the two-stage routing and the balance-loss statistics.
+
+    gprime [b,n,m]: data-router logits (Eq. 13, noise included).  Stage 1 (Eq. 15): every patch j
+    picks its k experts with the highest gate g_{i,j} (Eq. 14; ties -> lower expert index).  Eq. 16:
+    c = max_i #{j : i in id'_j}, per sample.  Eq. 43-44 with the patch as the routed unit:
+    f_i = n/(k m) * #{j : i in id'_j}, P_i = (1/m) sum_j g_{i,j}.
+    """
+    gp = _f64(gprime)
+    b, n, m = gp.shape
+    assert 1 <= k <= n
+    g = patch_gate(gp)
+    cap = np.zeros(b, np.int32)
+    cnt = np.zeros((b, n), np.int32)
+    margin = np.full((b, m), np.inf)
+    for bb in range(b):
+        for j in range(m):
+            col = gp[bb, :, j]                       # the gate is increasing in the logit for a fixed patch
+            order = np.argsort(-col, kind="stable")  # stable: equal values keep the lower index first
+            cnt[bb, order[:k]] += 1
+            if k < n:
+                hi, lo = col[order[k - 1]], col[order[k]]
+                margin[bb, j] = (hi - lo) / max(abs(hi), abs(lo), 1e-300)
+        cap[bb] = cnt[bb].max()
+    return Capacity(cap, cnt, n * cnt / float(k * m), g.mean(axis=2), margin)
+
+
 # --------------------------------------------------------------------------- blocks
 def smha(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: int,
          flags: int = RESIDUAL, rope_dim: int = 0, pad_mask=None) -> np.ndarray:
