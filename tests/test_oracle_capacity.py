@@ -32,7 +32,7 @@ def brute(gp, k):
 def test_capacity_matches_brute_force(seed, b, n, m, k):
     gp = np.random.default_rng(seed).standard_normal((b, n, m))
     res = oracle.capacity(gp, k)
-    cap, cnt = brute(gp.tolist(), k)
+    cap, cnt = brute(gp, k)
     np.testing.assert_array_equal(res.capacity, cap)
     np.testing.assert_array_equal(res.count, cnt)
 
