@@ -87,6 +87,9 @@ def main() -> int:
     ap.add_argument("--rope-dim", type=int, default=0, help="SMHA with partial RoPE on the last N dims (Eq. 32)")
     ap.add_argument("--uome-data-selection", default=None, metavar="M,C",
                     help="UoME with patch-wise data selection (Eq. 37): M patches, C kept per expert")
+    ap.add_argument("--dynamic-capacity", type=int, default=0, metavar="K",
+                    help="two-stage routing (Eq. 15-16): every step first computes the SMHA capacity with K experts per "
+                         "patch (uoe_route_capacity), reads it back and runs the layer with c = its maximum over the batch")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
@@ -137,7 +140,24 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / args.steps
 
-    eager_ms = timed(dev.layer_forward)
+    step_fn = dev.layer_forward
+    if args.dynamic_capacity:
+        import dataclasses
+        cap = torch.zeros((cfg.b,), dtype=torch.int32, device=dev.device)
+        by_c = {}
+
+        def dynamic_step():
+            B.route_capacity(dev.smha, dev.x, dev.a_w_b, dev.a_w_a, dev.noise_a_patch, args.dynamic_capacity, cap, None,
+                             None, dev.ws)
+            c_dyn = int(cap.max().item())          # the host needs c to size the call: one read-back per step
+            if c_dyn not in by_c:                  # same inputs, another descriptor / buffers for this c
+                by_c[c_dyn] = DeviceLayer(dataclasses.replace(inp, cfg=dataclasses.replace(cfg, c=c_dyn)), fa, fm,
+                                          device="cuda:0", rope_dim=args.rope_dim)
+            by_c[c_dyn].layer_forward()
+        dynamic_step()
+        cfg = next(iter(by_c.values())).cfg        # report the shape that actually ran
+        step_fn = dynamic_step
+    eager_ms = timed(step_fn)
     launch = "eager"
     ms_per_step = eager_ms
     if args.graph:
@@ -219,7 +239,9 @@ def main() -> int:
         "config": {"workload": describe(cfg),
                    "flags": "residual+expert gate+patch gate" + ("+causal" if args.causal else "") +
                             (f"+rope{args.rope_dim}" if args.rope_dim else "") +
-                            ("; UoME data selection, +patch gate" if uome_ds else ""),
+                            ("; UoME data selection, +patch gate" if uome_ds else "") +
+                            (f"; SMHA c from Eq. 15-16 with {args.dynamic_capacity} experts per patch, read back every step"
+                             if args.dynamic_capacity else ""),
                    "seed": cfg.seed, "launch": launch},
         "ms_per_step_eager": round(eager_ms, 5),
         "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 3),

@@ -96,6 +96,24 @@ int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, co
               void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Dynamic capacity of the two-stage routing (Eq. 15-16) and the statistics of the balance loss
+ * (Eq. 43-44), from the block's data router alone.  Stage 1: every patch names its patch_k experts
+ * with the highest Eq. 14 gate (ties to the lower expert index); count[b,i] = number of patches
+ * that named expert i; capacity[b] = max_i count[b,i] (Eq. 16, per sample);
+ * load_f[b,i] = n * count[b,i] / (patch_k * m) (Eq. 43 with the patch as the routed unit);
+ * load_p[b,i] = mean over patches of the gate (Eq. 44).
+ * A caller that wants the paper's dynamic allocation reads capacity back, takes c = the largest
+ * value over the batch (one c per call: the selected sequences of a batch share their length) and
+ * calls uoe_route / uoe_smha_forward with that c in the descriptor: c is a run-time value there.
+ *   x, w_b, w_a, noise_patch as for uoe_route (blk->k and blk->c are not used); 1 <= patch_k <= n
+ *   capacity [b] int32 (device); load_f, load_p [b,n] fp32 (device) or NULL
+ *   n*m <= 8192 (the logits of a sample are held in LDS), else UOE_ERR_UNSUPPORTED
+ */
+int uoe_route_capacity(const uoe_block_desc *blk, const void *x, const void *w_b, const void *w_a,
+                       const float *noise_patch, int32_t patch_k, int32_t *capacity, float *load_f,
+                       float *load_p, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Index selection of Eq. 18 / 24 as a standalone copy: for every active unit
  * (sample b, slot s < k, expert i = expert_idx[b,s]) the l_a selected token rows
  * of x, in ascending position, into h[b,s,:,:].

@@ -17,7 +17,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
-EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_gather", "uoe_smha_forward",
+EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward",
            "uoe_smha_forward_masked",
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward")
 
@@ -66,6 +66,7 @@ def lib():
         L.uoe_status_string.argtypes = [ctypes.c_int]
         L.uoe_status_string.restype = ctypes.c_char_p
         L.uoe_route.argtypes = [D] + [P] * 10 + [P, S, P]
+        L.uoe_route_capacity.argtypes = [D, P, P, P, P, ctypes.c_int32, P, P, P, P, S, P]
         L.uoe_gather.argtypes = [D, P, P, P, P, P]
         L.uoe_smha_forward.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_smha_forward_masked.argtypes = [D] + [P] * 11 + [P, S, P]
@@ -75,7 +76,7 @@ def lib():
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
-        for f in ("uoe_route", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
+        for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
                   "uoe_uome_down", "uoe_layer_forward"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
@@ -132,6 +133,14 @@ def route(blk, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx, exp
                          _ptr(patch_gate), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
                          _stream(stream))
     return _done(st, "uoe_route", check)
+
+
+def route_capacity(blk, x, w_b, w_a, noise_patch, patch_k, capacity, load_f, load_p, ws, stream=None, check=True,
+                   ws_bytes=None) -> int:
+    st = lib().uoe_route_capacity(_ref(blk), _ptr(x), _ptr(w_b), _ptr(w_a), _ptr(noise_patch), int(patch_k),
+                                  _ptr(capacity), _ptr(load_f), _ptr(load_p), _ptr(ws),
+                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_route_capacity", check)
 
 
 def gather(blk, x, expert_idx, patch_idx, h, stream=None, check=True) -> int:

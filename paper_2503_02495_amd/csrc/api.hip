@@ -265,6 +265,34 @@ int uoe_gather(const uoe_block_desc *blk, const void *x, const int32_t *expert_i
                ? UOE_OK : UOE_ERR_DEVICE;
 }
 
+int uoe_route_capacity(const uoe_block_desc *blk, const void *x, const void *w_b, const void *w_a,
+                       const float *noise_patch, int32_t patch_k, int32_t *capacity, float *load_f,
+                       float *load_p, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_desc(blk, DESC_ROUTE);
+    if (rc != UOE_OK) return rc;
+    if (!x || !w_b || !w_a || !capacity || !aligned16(x) || !aligned16(w_b) || !aligned16(w_a))
+        return UOE_ERR_INVALID_ARG;
+    if (patch_k < 1 || patch_k > blk->n) return UOE_ERR_INVALID_ARG;
+    if ((size_t)blk->n * blk->d * elem_size(blk->dtype) > 48 * 1024) return UOE_ERR_UNSUPPORTED;
+    if ((size_t)blk->n * blk->m * sizeof(float) > 32 * 1024) return UOE_ERR_UNSUPPORTED;  // logits staged in LDS
+    const RouteWs w = route_ws(blk->b, blk->l, blk->d, blk->n, blk->m, blk->dtype == UOE_BF16);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+
+    RouteArgs a{};
+    a.x = x; a.w_b = w_b; a.w_a = w_a;
+    a.noise_p = noise_patch;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->n; a.m = blk->m; a.c = blk->m;
+    a.tc = w.tc; a.nchunks = w.nchunks; a.tc_d = w.tc_d; a.nchunks_d = w.nchunks_d;
+    a.zpart = reinterpret_cast<float *>(at(ws, w.zpart));
+    a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
+    a.gred = reinterpret_cast<float *>(at(ws, w.gred));
+    a.patch_k = patch_k;
+    a.capacity = capacity; a.load_f = load_f; a.load_p = load_p;
+    return launch_route(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK
+                                                                                                         : UOE_ERR_DEVICE;
+}
+
 int uoe_smha_forward(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
                      const void *wv, const void *wo, const int32_t *expert_idx,
                      const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,

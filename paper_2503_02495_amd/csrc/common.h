@@ -81,6 +81,10 @@ struct RouteArgs {
     float *gred;                              // [b, n*m]
     int32_t *expert_idx, *patch_idx;          // outputs (any may be NULL)
     float *expert_gate, *patch_gate;
+    // dynamic capacity (Eq. 15-16) and balance statistics (Eq. 43-44): capacity NULL = not asked for
+    int patch_k;                              // experts each patch names in stage 1
+    int32_t *capacity;                        // [b]
+    float *load_f, *load_p;                   // [b,n] each, or NULL
 };
 
 struct SmhaArgs {

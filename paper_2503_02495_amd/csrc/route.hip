@@ -578,6 +578,47 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     }
     if (i != 0) return;  // uniform per workgroup
 
+    // ---- dynamic capacity (Eq. 15-16) and balance statistics (Eq. 43-44), from the staged logits.
+    // Stage 1: patch j names its patch_k best experts (rank counting on the logits, which order the
+    // experts of one patch exactly as the gates do; ties to the lower index); count_i = number of
+    // patches that named expert i (integer LDS adds: order-independent); c = max_i count_i.
+    if (a.capacity && has_d && staged) {  // uniform
+        __shared__ int ccount[32];
+        if (tid < n) ccount[tid] = 0;
+        __syncthreads();  // also: every thread is past its last read of glog as logits of row 0
+        for (int j = tid; j < m; j += SELECT_THREADS) {
+            float mx = -INFINITY;
+            for (int ii = 0; ii < n; ++ii) mx = fmaxf(mx, glog[ii * m + j]);
+            float den = 0.f;
+            for (int ii = 0; ii < n; ++ii) den += expf(glog[ii * m + j] - mx);
+            for (int ii = 0; ii < n; ++ii) {
+                const float v = glog[ii * m + j];
+                int rank = 0;
+                for (int t = 0; t < n; ++t) {
+                    const float w = glog[t * m + j];
+                    rank += (w > v || (w == v && t < ii)) ? 1 : 0;
+                }
+                if (rank < a.patch_k) atomicAdd(&ccount[ii], 1);
+            }
+            // this thread alone owns column j: the logits can now be replaced by the gates
+            for (int ii = 0; ii < n; ++ii) glog[ii * m + j] = expf(glog[ii * m + j] - mx) / den;
+        }
+        __syncthreads();
+        if (tid < n) {
+            if (a.load_f) a.load_f[(size_t)bb * n + tid] = (float)n * (float)ccount[tid] / ((float)a.patch_k * (float)m);
+            if (a.load_p) {
+                float sum = 0.f;
+                for (int j = 0; j < m; ++j) sum += glog[tid * m + j];  // fixed order
+                a.load_p[(size_t)bb * n + tid] = sum / (float)m;
+            }
+        }
+        if (tid == 0) {
+            int cmax = 0;
+            for (int ii = 0; ii < n; ++ii) cmax = max(cmax, ccount[ii]);
+            a.capacity[bb] = cmax;
+        }
+    }
+
     // ---- expert selection: Eq. 21 logits (+noise) -> softmax -> Eq. 22 top-k
     // The softmax is strictly increasing in the logit within a sample, so the k largest gates are
     // the k largest logits: rank on the logits, which cannot underflow.
@@ -713,7 +754,9 @@ hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st)
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    hipLaunchKernelGGL(route_select_kernel, dim3(a.n, a.b), dim3(SELECT_THREADS), sh, st, a, (int)has_e,
+    // rows other than 0 only produce patch lists and gates: skip them when neither is asked for
+    const int rows = (a.patch_idx || a.patch_gate) ? a.n : 1;
+    hipLaunchKernelGGL(route_select_kernel, dim3(rows, a.b), dim3(SELECT_THREADS), sh, st, a, (int)has_e,
                        (int)has_d, (int)staged, (int)fuse_reduce);
     return hipGetLastError();
 }

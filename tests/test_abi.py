@@ -91,6 +91,20 @@ def test_causal_and_rope_belong_to_the_attention_block():
                                      stream=0, check=False, ws_bytes=8) == B.ERR_WORKSPACE
 
 
+def test_route_capacity_argument_validation():
+    d = good()
+    big = 1 << 30
+    call = lambda *a, **k: B.route_capacity(d, *a, stream=0, check=False, **k)
+    assert call(FAKE, FAKE, FAKE, None, 2, FAKE, None, None, FAKE, ws_bytes=16) == B.ERR_WORKSPACE    # accepted
+    assert call(FAKE, None, FAKE, None, 2, FAKE, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # no data router
+    assert call(FAKE, FAKE, FAKE, None, 0, FAKE, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # patch_k < 1
+    assert call(FAKE, FAKE, FAKE, None, 5, FAKE, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # patch_k > n
+    assert call(FAKE, FAKE, FAKE, None, 2, None, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # no output
+    wide = good(n=32, k=2, m=512, c=2, l=512)
+    assert B.route_capacity(wide, FAKE, FAKE, FAKE, None, 2, FAKE, None, None, FAKE, stream=0, check=False,
+                            ws_bytes=big) == B.ERR_UNSUPPORTED                                        # n*m logits > LDS stage
+
+
 def test_reserved_fields_must_be_zero():
     d = good()
     d.reserved[2] = 1

@@ -258,6 +258,46 @@ def test_uome_stage_parity_sampled_rows(name, flags):
     run_uome_stage(name, flags, rows=192)
 
 
+# --------------------------------------------------------------------------- dynamic capacity
+@pytest.mark.parametrize("name", list(EDGE_CONFIGS) + ["tiny", "lm", "longrange", "vit", "large"])
+@pytest.mark.parametrize("patch_k", [1, 2])
+def test_route_capacity_parity(name, patch_k):
+    """Eq. 15-16 capacity and Eq. 43-44 statistics against the oracle, then one routing call with c = capacity."""
+    cfg = get_cfg(name)
+    patch_k = min(patch_k, cfg.n_a)
+    print(f"route capacity {name} patch_k={patch_k}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    dev = DeviceLayer(inp, R | GE | GP, R | GE)
+    cap = torch.full((cfg.b,), -1, dtype=torch.int32, device=dev.device)
+    lf = torch.zeros((cfg.b, cfg.n_a), dtype=torch.float32, device=dev.device)
+    lp = torch.zeros((cfg.b, cfg.n_a), dtype=torch.float32, device=dev.device)
+    B.route_capacity(dev.smha, dev.x, dev.a_w_b, dev.a_w_a, dev.noise_a_patch, patch_k, cap, lf, lp, dev.ws)
+    torch.cuda.synchronize()
+    gp = oracle.data_router_logits(inp.x, inp.a_w_b, inp.a_w_a, inp.noise_a_patch)
+    ref = oracle.capacity(gp, patch_k)
+    got_cap, got_f, got_p = to_host(cap), to_host(lf), to_host(lp)
+    near = ref.margin < oracle.NEAR_TIE_REL                      # patches whose k-th / (k+1)-th experts nearly tie
+    for bb in range(cfg.b):
+        slack = int(near[bb].sum())
+        assert abs(int(got_cap[bb]) - int(ref.capacity[bb])) <= slack, (bb, got_cap[bb], ref.capacity[bb], slack)
+        if slack == 0:
+            np.testing.assert_array_equal(got_f[bb], (cfg.n_a * ref.count[bb] / (patch_k * cfg.m)).astype(np.float32))
+    np.testing.assert_allclose(got_p, ref.load_p, rtol=GATE_RTOL, atol=1e-30)
+    print(f"[capacity {name} k={patch_k}] c per sample {got_cap.tolist()[:8]} near-tie patches {int(near.sum())}", flush=True)
+    # the protocol: one c for the call, routing with it
+    c_dyn = int(got_cap.max())
+    assert 1 <= c_dyn <= cfg.m
+    blk = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_a, cfg.k_a, cfg.m, c_dyn, cfg.d_h, dev.smha.dtype, R | GE | GP)
+    pidx = torch.full((cfg.b, cfg.n_a, c_dyn), -1, dtype=torch.int32, device=dev.device)
+    B.route(blk, dev.x, dev.a_w_expert, dev.a_w_b, dev.a_w_a, dev.noise_a_expert, dev.noise_a_patch, dev.a_expert_idx,
+            dev.a_expert_gate, pidx, dev.a_patch_gate, dev.ws)
+    torch.cuda.synchronize()
+    r2 = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, c_dyn, inp.a_w_expert, inp.a_w_b, inp.a_w_a, inp.noise_a_expert,
+                      inp.noise_a_patch)
+    check_valid_selection(to_host(pidx), cfg.m)
+    check_indices(name + ":patch(c dynamic)", to_host(pidx), r2.patch_id, r2.patch_margin)
+
+
 # --------------------------------------------------------------------------- UoME, data selection
 import dataclasses
 
