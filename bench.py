@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 
 def layer_flops(c) -> dict:
     """Algorithmic FLOPs of one layer call: active units only, no padding."""
-    routers = 2 * c.b * c.l * c.d * (2 * c.n_a + c.n_m) + 2 * c.b * c.n_a * c.l * c.m
+    routers = 2 * c.b * c.l * c.d * (2 * c.n_a + c.n_m) + 2 * c.b * c.n_a * c.l * c.m   # both SMHA routers counted
     qkv = c.b * c.k_a * 6 * c.l_a * c.d * c.d_h
     attn = c.b * c.k_a * 4 * c.l_a * c.l_a * c.d_h
     outp = c.b * c.k_a * 2 * c.l_a * c.d_h * c.d
@@ -87,6 +87,9 @@ def main() -> int:
     ap.add_argument("--rope-dim", type=int, default=0, help="SMHA with partial RoPE on the last N dims (Eq. 32)")
     ap.add_argument("--uome-data-selection", default=None, metavar="M,C",
                     help="UoME with patch-wise data selection (Eq. 37): M patches, C kept per expert")
+    ap.add_argument("--smha-mode", default="both", choices=["both", "expert", "data"],
+                    help="selection modes of the SMHA block: both (default), expert selection only (c = m, no data "
+                         "router) or data selection only (k = n, no expert router)")
     ap.add_argument("--dynamic-capacity", type=int, default=0, metavar="K",
                     help="two-stage routing (Eq. 15-16): every step first computes the SMHA capacity with K experts per "
                          "patch (uoe_route_capacity), reads it back and runs the layer with c = its maximum over the batch")
@@ -117,9 +120,17 @@ def main() -> int:
         import dataclasses
         m_m, c_m = (int(v) for v in args.uome_data_selection.split(","))
         cfg = dataclasses.replace(cfg, m_m=m_m, c_m=c_m)
+    if args.smha_mode != "both":
+        import dataclasses
+        cfg = dataclasses.replace(cfg, c=cfg.m) if args.smha_mode == "expert" else dataclasses.replace(cfg, k_a=cfg.n_a)
     inp = synth.make_inputs(cfg)
     inp.noise_m_patch = None   # the layer call takes no noise on the UoME patch logits
-    fa = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | B.FLAG_GATE_PATCH | (B.FLAG_CAUSAL if args.causal else 0)
+    if args.smha_mode == "expert":
+        inp.a_w_b = inp.a_w_a = inp.noise_a_patch = None
+    elif args.smha_mode == "data":
+        inp.a_w_expert = inp.noise_a_expert = None
+    fa = B.FLAG_RESIDUAL | (B.FLAG_CAUSAL if args.causal else 0)
+    fa |= (B.FLAG_GATE_EXPERT if args.smha_mode != "data" else 0) | (B.FLAG_GATE_PATCH if args.smha_mode != "expert" else 0)
     fm = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT | (B.FLAG_GATE_PATCH if uome_ds else 0)
     dev = DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim)
     torch.cuda.set_device(0)
@@ -237,8 +248,10 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
         "config": {"workload": describe(cfg),
-                   "flags": "residual+expert gate+patch gate" + ("+causal" if args.causal else "") +
+                   "flags": "residual" + ("+expert gate" if fa & B.FLAG_GATE_EXPERT else "") +
+                            ("+patch gate" if fa & B.FLAG_GATE_PATCH else "") + ("+causal" if args.causal else "") +
                             (f"+rope{args.rope_dim}" if args.rope_dim else "") +
+                            (f"; SMHA {args.smha_mode} selection only" if args.smha_mode != "both" else "") +
                             ("; UoME data selection, +patch gate" if uome_ds else "") +
                             (f"; SMHA c from Eq. 15-16 with {args.dynamic_capacity} experts per patch, read back every step"
                              if args.dynamic_capacity else ""),

@@ -258,6 +258,45 @@ def test_uome_stage_parity_sampled_rows(name, flags):
     run_uome_stage(name, flags, rows=192)
 
 
+# --------------------------------------------------------------------------- single-mode SMHA blocks
+@pytest.mark.parametrize("mode", ["expert_only", "data_only"])
+@pytest.mark.parametrize("name", ["bf16_ragged", "lm"])
+def test_layer_with_single_mode_smha(name, mode):
+    """The paper's default is ONE selection mode per block (Sec. III-B): expert selection only
+    (no data router: every active expert sees the whole sample) or data selection only (no expert
+    router: every expert is active on its own patches)."""
+    import dataclasses
+    base = get_cfg(name)
+    cfg = dataclasses.replace(base, c=base.m) if mode == "expert_only" else dataclasses.replace(base, k_a=base.n_a)
+    print(f"layer, {mode} SMHA, {name}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    if mode == "expert_only":
+        inp.a_w_b = inp.a_w_a = inp.noise_a_patch = None
+        fa = R | GE
+    else:
+        inp.a_w_expert = inp.noise_a_expert = None
+        fa = R | GP
+    fm = R | GE
+    dev = DeviceLayer(inp, fa, fm)
+    dev.layer_forward()
+    torch.cuda.synchronize()
+    ref = oracle.layer_forward(inp, fa, fm)
+    check_indices(name + ":smha-expert", to_host(dev.a_expert_idx), ref.routing_a.expert_id, ref.routing_a.expert_margin)
+    check_indices(name + ":smha-patch", to_host(dev.a_patch_idx), ref.routing_a.patch_id, ref.routing_a.patch_margin)
+    out_layer = to_host(dev.out)
+    m_idx = to_host(dev.m_expert_idx)
+    dev.smha_forward()
+    torch.cuda.synchronize()
+    err_u = scaled_err(to_host(dev.u), ref.u)
+    print(f"[layer {mode} {name}] u scaled err {err_u:.3e}", flush=True)
+    assert err_u <= TOL[cfg.dtype]
+    same = np.all(m_idx == ref.routing_m.expert_id, axis=-1)
+    if same.any():
+        err = scaled_err(out_layer[same], ref.out[same])
+        print(f"[layer {mode} {name}] out scaled err {err:.3e} on {int(same.sum())}/{cfg.b} samples", flush=True)
+        assert err <= TOL[cfg.dtype]
+
+
 # --------------------------------------------------------------------------- dynamic capacity
 @pytest.mark.parametrize("name", list(EDGE_CONFIGS) + ["tiny", "lm", "longrange", "vit", "large"])
 @pytest.mark.parametrize("patch_k", [1, 2])
