@@ -380,8 +380,11 @@ __device__ __forceinline__ void route_expert_mfma_body(const RouteArgs &a, int c
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.f;
 
-    for (int s = s0; s < s1; s += U) {
-        uint4 xa[U][RT], wb[U][CT];
+    // Two register sets: the loads of the next U steps are issued before the MFMAs of the current
+    // ones, so a wave always has loads in flight (the kernel is a pure stream: bytes in flight are
+    // its throughput).
+    uint4 xa[2][U][RT], wb[2][U][CT];
+    auto load_steps = [&](int s, int set) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const long e = c0 + (long)(s + u) * 32 + q * 8;
@@ -389,20 +392,31 @@ __device__ __forceinline__ void route_expert_mfma_body(const RouteArgs &a, int c
             const long ec = ok ? e : c0;  // any valid address
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
-                xa[u][t] = *reinterpret_cast<const uint4 *>(xp[t] + ec);
-                if (!ok) xa[u][t] = make_uint4(0, 0, 0, 0);
+                xa[set][u][t] = *reinterpret_cast<const uint4 *>(xp[t] + ec);
+                if (!ok) xa[set][u][t] = make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
-            for (int t = 0; t < CT; ++t) wb[u][t] = *reinterpret_cast<const uint4 *>(wp[t] + ec);
+            for (int t = 0; t < CT; ++t) wb[set][u][t] = *reinterpret_cast<const uint4 *>(wp[t] + ec);
         }
+    };
+    auto mfma_steps = [&](int set) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int t = 0; t < RT; ++t)
 #pragma unroll
                 for (int v = 0; v < CT; ++v)
-                    acc[t][v] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(rt_bf16x8, xa[u][t]),
-                                                                        __builtin_bit_cast(rt_bf16x8, wb[u][v]), acc[t][v], 0, 0, 0);
+                    acc[t][v] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(rt_bf16x8, xa[set][u][t]),
+                                                                        __builtin_bit_cast(rt_bf16x8, wb[set][u][v]), acc[t][v], 0, 0, 0);
+    };
+    if (s0 < s1) load_steps(s0, 0);
+    for (int s = s0; s < s1; s += 2 * U) {
+        if (s + U < s1) load_steps(s + U, 1);
+        mfma_steps(0);
+        if (s + U < s1) {
+            if (s + 2 * U < s1) load_steps(s + 2 * U, 0);
+            mfma_steps(1);
+        }
     }
 #pragma unroll
     for (int t = 0; t < RT; ++t)
