@@ -451,6 +451,17 @@ template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStrea
     return launch_gemm_generic<T>(make_outproj<T>(a), a.b * a.m, l_p, a.d, st);
 }
 
+// Tile choice of the pipelined output-stationary contraction (out-projection of SMHA, second layer
+// of the data-selected UoME).  With many short (sample, patch) groups and d = 384 one workgroup takes
+// the whole row width: the group's segment list is built once and its A rows are fetched once
+// (measured 10 % faster on the ViT shape; for d = 256 with 64-row patches the narrower tiles win).
+template <typename OP> static hipError_t launch_outproj_dma(const OP &op, int groups, int l_p, int d, hipStream_t st)
+{
+    if (groups >= 512 && d == 384 && l_p <= 32) return launch_gemm_dma<OP, 32, 384, 32, 1, 4, 2, 2>(op, groups, l_p, d, st);
+    if (l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 4, 4, 2>(op, groups, l_p, d, st);
+    return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, groups, l_p, d, st);
+}
+
 // MFMA path: bf16 storage, d and d_h multiples of 32 (the K segments of the two projections)
 static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
 {
@@ -496,8 +507,7 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
         if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
         return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
     }
-    if (l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 4, 4, 2>(op, a.b * a.m, l_p, a.d, st);
-    return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, a.b * a.m, l_p, a.d, st);
+    return launch_outproj_dma(op, a.b * a.m, l_p, a.d, st);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -578,8 +588,7 @@ static hipError_t uome_ds_mfma(const UomeDsArgs &a, hipStream_t st)
         if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
         return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
     }
-    if (l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 4, 4, 2>(op, a.b * a.m, l_p, a.d, st);
-    return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, a.b * a.m, l_p, a.d, st);
+    return launch_outproj_dma(op, a.b * a.m, l_p, a.d, st);
 }
 
 hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st)
