@@ -487,6 +487,8 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     } else if (a.d_h == 64) {
         if (tall) err = k64 ? launch_gemm_dma<QP, 128, 192, 64, 2, 2, 3>(qp, units, l_a, 192, st)
                             : launch_gemm_dma<QP, 128, 192, 32, 2, 2, 4>(qp, units, l_a, 192, st);
+        else if (k64 && l_a > 32 && (long)units * ((l_a + 63) / 64) >= 256)
+            err = launch_gemm_dma<QP, 64, 192, 64, 2, 2, 3>(qp, units, l_a, 192, st);
         else if (k64) err = launch_gemm_dma<QP, 32, 192, 64, 1, 2, 4>(qp, units, l_a, 192, st);
         else err = launch_gemm_dma<QP, 32, 192, 32, 1, 2, 4>(qp, units, l_a, 192, st);
     } else {
