@@ -17,6 +17,12 @@
 //                                 epilogue passes col_scale * row_scale to epi
 //   has_residual() / res8(g, m, nn)  the 16-byte piece of the residual row, loaded in batches
 //   put8(g, m, nn, piece)         plain store of a finished piece
+// and, for the pipelined engine (which may not touch global memory through the compiler inside
+// its K loop),
+//   seg_ctx(g, seg)               32 bits of routing context of a K segment, looked up once per tile
+//   a_ptr_ctx / b_ptr_ctx         a_seg_ptr / b_seg_ptr computed from that context, no lookups
+//   kPrepare / prepare(g, segtab, tid, nthreads)  the workgroup builds its segment list itself and
+//                                 returns K (out-projection: which experts picked this patch)
 // K and N are concatenations of per-expert segments of length `width`; since width % 8 == 0 an
 // 8-element run never straddles two experts.
 #pragma once
