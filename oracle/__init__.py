@@ -295,6 +295,44 @@ def uome(u, a_in, a_out, expert_id, expert_gate, flags: int = RESIDUAL, patch_id
 
 
 @dataclass
+class UomeGrads:
+    d_u: np.ndarray        # [b,l,d]
+    d_a_in: np.ndarray     # [n,d,d_e]
+    d_a_out: np.ndarray    # [n,d_e,d]
+    d_gate: np.ndarray     # [b,n]  (zero for experts a sample did not select, and without GATE_EXPERT)
+
+
+def uome_backward(u, a_in, a_out, expert_id, expert_gate, d_out, flags: int = RESIDUAL) -> UomeGrads:
+    """Gradients of the expert-selection UoME block (Eq. 38-40 with Eq. 24-26) for a given upstream
+    gradient d_out = dL/dh [b,l,d]: chain rule through h[b] = (u[b]) + sum_s w * SiLU(u[b] A^I_i) A^O_i.
+
+    The selection (expert_id) is a constant of the backward pass; the gate enters as a value
+    (d_gate is dL/dg, to be chained into the router by the caller)."""
+    u, a_in, a_out, d_out = _f64(u), _f64(a_in), _f64(a_out), _f64(d_out)
+    b, l, d = u.shape
+    n, _, d_e = a_in.shape
+    expert_id = _i32(expert_id)
+    g = _f64(expert_gate)
+    d_u = d_out.copy() if flags & RESIDUAL else np.zeros_like(u)
+    d_a_in, d_a_out, d_gate = np.zeros_like(a_in), np.zeros_like(a_out), np.zeros((b, n))
+    for bb in range(b):
+        for i in expert_id[bb]:
+            w = g[bb, i] if flags & GATE_EXPERT else 1.0
+            z = u[bb] @ a_in[i]                         # [l,d_e]
+            sig = 1.0 / (1.0 + np.exp(-z))
+            v = z * sig                                  # SiLU(z)
+            d_hp = d_out[bb]                             # dL/d(h'_i) before the weight
+            d_v = w * (d_hp @ a_out[i].T)                # [l,d_e]
+            if flags & GATE_EXPERT:
+                d_gate[bb, i] = np.sum((v @ a_out[i]) * d_hp)
+            d_a_out[i] += w * (v.T @ d_hp)
+            d_z = d_v * (sig * (1.0 + z * (1.0 - sig)))  # SiLU'(z)
+            d_a_in[i] += u[bb].T @ d_z
+            d_u[bb] += d_z @ a_in[i].T
+    return UomeGrads(d_u, d_a_in, d_a_out, d_gate)
+
+
+@dataclass
 class LayerResult:
     routing_a: Routing
     u: np.ndarray
