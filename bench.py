@@ -57,6 +57,11 @@ def run_stage(args, cfg, dev, B, torch) -> int:
         "uome_down": lambda: B.uome_down(dev.uome, hidden, dev.a_out, dev.u, dev.m_expert_idx, dev.out),
         "gather": lambda: B.gather(dev.smha, dev.x, dev.a_expert_idx, dev.a_patch_idx, h),
     }
+    if args.stage == "uome_bwd":   # backward of the expert-selection UoME block on a synthetic upstream gradient
+        from paper_2503_02495_amd import synth
+        from paper_2503_02495_amd.harness import to_device
+        d_out = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
+        calls["uome_bwd"] = lambda: dev.uome_backward(d_out)
     if args.stage == "copy":   # a plain copy of known size (1 GiB read + 1 GiB written): counter calibration
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).normal_()
         dst = torch.empty_like(src)
@@ -96,7 +101,8 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
-                    choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather", "copy"],
+                    choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather", "copy",
+                             "uome_bwd"],
                     help="profiling aid: loop one C-ABI call of the path instead of the whole layer "
                          "and print its time (no JSON contract line)")
     args = ap.parse_args()

@@ -190,6 +190,28 @@ int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, cons
 int uoe_uome_down(const uoe_block_desc *blk, const void *hidden, const void *a_out, const void *u,
                   const int32_t *expert_idx, void *out, void *hip_stream);
 
+/*
+ * Backward pass of uoe_uome_forward in expert-selection mode (the derivatives of Eq. 38-40 with
+ * Eq. 24-26; the selection of Eq. 22 is piecewise constant and passes no gradient).  Given
+ * d_out = dL/d(out) [b,l,d] and the forward inputs, writes
+ *   d_u     [b,l,d]     = (d_out, with UOE_FLAG_RESIDUAL) + sum_s (d_out A^O_i^T * gate * SiLU'(u A^I_i)) A^I_i^T
+ *   d_a_in  [n,d,d_e]   gradient of A^I, summed over the samples that selected the expert; zero
+ *                       for an expert no sample selected
+ *   d_a_out [n,d_e,d]   the same for A^O
+ *   d_gate  [b,n] fp32  dL/d(expert_gate[b,i]) for the sample's active experts, zero elsewhere and
+ *                       everywhere without UOE_FLAG_GATE_EXPERT; may be NULL
+ * all in full, in the storage dtype unless noted.  Intermediates (u A^I, d_out A^O^T) are kept in
+ * the storage dtype between the kernels.  This build: bf16 storage only, l, d and d_e multiples
+ * of 32, b <= 128; otherwise UOE_ERR_UNSUPPORTED.  Outputs must not alias inputs.  Deterministic:
+ * fixed summation order, no atomics.  ws: at least uoe_uome_backward_workspace_bytes(blk) bytes
+ * (0 = descriptor invalid or unsupported).
+ */
+size_t uoe_uome_backward_workspace_bytes(const uoe_block_desc *blk);
+int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
+                      const int32_t *expert_idx, const float *expert_gate, const void *d_out,
+                      void *d_u, void *d_a_in, void *d_a_out, float *d_gate, void *ws,
+                      size_t ws_bytes, void *hip_stream);
+
 typedef struct {
     const void *w_expert, *w_b, *w_a, *wq, *wk, *wv, *wo;
 } uoe_smha_weights;

@@ -19,7 +19,8 @@ FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
 EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward",
            "uoe_smha_forward_masked",
-           "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward")
+           "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward",
+           "uoe_uome_backward_workspace_bytes", "uoe_uome_backward")
 
 
 class UoeError(RuntimeError):
@@ -71,13 +72,16 @@ def lib():
         L.uoe_smha_forward.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_smha_forward_masked.argtypes = [D] + [P] * 11 + [P, S, P]
         L.uoe_uome_forward.argtypes = [D] + [P] * 8 + [P, S, P]
+        L.uoe_uome_backward_workspace_bytes.argtypes = [D]
+        L.uoe_uome_backward_workspace_bytes.restype = S
+        L.uoe_uome_backward.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_uome_up.argtypes = [D, P, P, P, P, P, P]
         L.uoe_uome_down.argtypes = [D, P, P, P, P, P, P]
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
         for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
-                  "uoe_uome_down", "uoe_layer_forward"):
+                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -171,6 +175,18 @@ def uome_forward(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_
                                 _ptr(expert_gate), _ptr(patch_idx), _ptr(patch_gate), _ptr(out), _ptr(ws),
                                 _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_uome_forward", check)
+
+
+def uome_backward_workspace_bytes(blk) -> int:
+    return int(lib().uoe_uome_backward_workspace_bytes(_ref(blk)))
+
+
+def uome_backward(blk, u, a_in, a_out, expert_idx, expert_gate, d_out, d_u, d_a_in, d_a_out, d_gate, ws,
+                  stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_uome_backward(_ref(blk), _ptr(u), _ptr(a_in), _ptr(a_out), _ptr(expert_idx), _ptr(expert_gate),
+                                 _ptr(d_out), _ptr(d_u), _ptr(d_a_in), _ptr(d_a_out), _ptr(d_gate), _ptr(ws),
+                                 _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_uome_backward", check)
 
 
 def uome_up(blk, u, a_in, expert_idx, expert_gate, hidden, stream=None, check=True) -> int:

@@ -94,6 +94,40 @@ UomeWs uome_ws_layout(const uoe_block_desc *d)
 }
 size_t uome_ws(const uoe_block_desc *d) { return uome_ws_layout(d).total; }
 
+// backward pass of the UoME block: Z, dH, dZ, H [b,l,k*d_e]; U^T [b,d,l]; H^T [b,k*d_e,l]; the two
+// transposed weight tensors; partial sums of the gate gradient
+struct UomeBwdWs {
+    size_t z, dh, dz, h, u_t, h_t, a_in_t, a_out_t, gpart, total;
+};
+UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
+{
+    UomeBwdWs w;
+    const size_t es = elem_size(d->dtype);
+    const size_t act = up((size_t)d->b * d->l * d->k * d->width * es);
+    const size_t wt = up((size_t)d->n * d->d * d->width * es);
+    size_t off = 0;
+    w.z = off; off += act;
+    w.dh = off; off += act;
+    w.dz = off; off += act;
+    w.h = off; off += act;
+    w.h_t = off; off += act;
+    w.u_t = off; off += up((size_t)d->b * d->l * d->d * es);
+    w.a_in_t = off; off += wt;
+    w.a_out_t = off; off += wt;
+    w.gpart = off; off += up((size_t)d->b * d->k * uome_backward_gate_chunks(d->l) * sizeof(float));
+    w.total = off;
+    return w;
+}
+int check_uome_bwd(const uoe_block_desc *blk)
+{
+    const int rc = check_desc(blk, DESC_UOME);
+    if (rc != UOE_OK) return rc;
+    if (blk->c != blk->m || (blk->flags & UOE_FLAG_GATE_PATCH)) return UOE_ERR_UNSUPPORTED;
+    if (blk->dtype != UOE_BF16) return UOE_ERR_UNSUPPORTED;
+    if (blk->l % 32 || blk->d % 32 || blk->width % 32 || blk->b > 128) return UOE_ERR_UNSUPPORTED;
+    return UOE_OK;
+}
+
 struct RoutingBuf {
     size_t expert_idx, expert_gate, patch_idx, patch_gate, total;
 };
@@ -323,6 +357,36 @@ int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in,
     if (rc != UOE_OK) return rc;
     return do_uome(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_gate, out, ws, ws_bytes,
                    static_cast<hipStream_t>(hip_stream));
+}
+
+size_t uoe_uome_backward_workspace_bytes(const uoe_block_desc *blk)
+{
+    return check_uome_bwd(blk) == UOE_OK ? uome_bwd_ws(blk).total : 0;
+}
+
+int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
+                      const int32_t *expert_idx, const float *expert_gate, const void *d_out, void *d_u,
+                      void *d_a_in, void *d_a_out, float *d_gate, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_uome_bwd(blk);
+    if (rc != UOE_OK) return rc;
+    if (!u || !a_in || !a_out || !expert_idx || !d_out || !d_u || !d_a_in || !d_a_out) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_EXPERT) && !expert_gate) return UOE_ERR_INVALID_ARG;
+    if (!aligned16(u) || !aligned16(a_in) || !aligned16(a_out) || !aligned16(d_out) || !aligned16(d_u) ||
+        !aligned16(d_a_in) || !aligned16(d_a_out))
+        return UOE_ERR_INVALID_ARG;
+    if (d_u == u || d_u == d_out || d_a_in == a_in || d_a_out == a_out) return UOE_ERR_INVALID_ARG;
+    const UomeBwdWs w = uome_bwd_ws(blk);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+    UomeBwdArgs a{};
+    a.u = u; a.a_in = a_in; a.a_out = a_out; a.d_out = d_out; a.expert_idx = expert_idx; a.expert_gate = expert_gate;
+    a.d_u = d_u; a.d_a_in = d_a_in; a.d_a_out = d_a_out; a.d_gate = d_gate;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.d_e = blk->width; a.flags = blk->flags;
+    a.z = at(ws, w.z); a.dh = at(ws, w.dh); a.dz = at(ws, w.dz); a.h = at(ws, w.h);
+    a.u_t = at(ws, w.u_t); a.h_t = at(ws, w.h_t); a.a_in_t = at(ws, w.a_in_t); a.a_out_t = at(ws, w.a_out_t);
+    a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
+    a.gchunks = uome_backward_gate_chunks(blk->l);
+    return launch_uome_backward(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
 }
 
 int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, const int32_t *expert_idx,

@@ -123,6 +123,23 @@ struct UomeDsArgs {
     int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k] (engines without in-kernel segment lists)
 };
 
+// Backward pass of the expert-selection UoME block (bf16 storage, MFMA shapes only)
+struct UomeBwdArgs {
+    const void *u, *a_in, *a_out, *d_out;
+    const int32_t *expert_idx;
+    const float *expert_gate;                 // NULL when GATE_EXPERT is off
+    void *d_u, *d_a_in, *d_a_out;             // [b,l,d], [n,d,d_e], [n,d_e,d], storage dtype
+    float *d_gate;                            // [b,n] or NULL
+    int b, l, d, n, k, d_e;
+    uint32_t flags;
+    // workspace, storage dtype unless noted
+    void *z, *dh, *dz, *h;                    // [b, l, k*d_e] each
+    void *u_t, *h_t;                          // [b, d, l], [b, k*d_e, l]
+    void *a_in_t, *a_out_t;                   // [n, d_e, d], [n, d, d_e]
+    float *gpart;                             // [b, k, chunks] partial sums of d_gate
+    int gchunks;
+};
+
 struct GatherArgs {
     const void *x;
     const int32_t *expert_idx, *patch_idx;
@@ -138,6 +155,8 @@ hipError_t launch_uome(const UomeArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st);    // Eq. 38 only
 hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // Eq. 39-40 only
 hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st);
+int uome_backward_gate_chunks(int l);
 
 // host-side sizing shared by api.cpp and the launchers
 int route_tokens_per_chunk(int b, int l);

@@ -28,7 +28,7 @@
 //    K loop: a compiler-inserted wait for it would drain the whole pipeline.  Per-segment routing
 //    lookups are therefore taken once, before the loop, into a small LDS table (seg_ctx).
 //
-// Requirements (checked by the callers): kseg() % BK == 0, N % 8 == 0, at most 64 K segments; BN a
+// Requirements (checked by the callers): kseg() % BK == 0, N % 8 == 0, at most 128 K segments; BN a
 // multiple of 64 and both operand tiles a whole number of load instructions per wave.  M and N tails are handled by clamping the load addresses to a valid row / chunk
 // of the same tile (the results of clamped rows and columns are never stored).
 #pragma once
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
     constexpr int S_BYTES = NW * WM * SPITCH * 2;
     constexpr int OPER_BYTES = STAGES * STAGE_BYTES;
     constexpr int LDS_BYTES = OPER_BYTES > S_BYTES ? OPER_BYTES : S_BYTES;
-    constexpr int MAX_SEG = 64;
+    constexpr int MAX_SEG = 128;
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
     static_assert(BK == 32 || BK == 64, "BK is 32 or 64");
     static_assert(BN % 64 == 0, "BN is a multiple of 64");

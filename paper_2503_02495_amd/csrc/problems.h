@@ -233,6 +233,7 @@ template <typename T> struct UomeUpProblem {
     const float *expert_gate;  // NULL: weight 1
     T *hidden;                 // [b, l, k*d_e]
     int l, d, n, kact, d_e;
+    int raw;                   // 1: store the plain product (backward pass), no SiLU, no gate
 
     __device__ int rows(int) const { return l; }
     __device__ int kdim(int) const { return d; }
@@ -254,18 +255,18 @@ template <typename T> struct UomeUpProblem {
     typedef float ColCtx;  // the gate of the column's expert
     __device__ ColCtx col_ctx(int g, int nn) const
     {
-        if (!expert_gate) return 1.0f;
+        if (!expert_gate || raw) return 1.0f;
         return expert_gate[(size_t)g * n + clampi(expert_idx[g * kact + nn / d_e], n)];
     }
     __device__ void store(int g, int r, int nn, float val, const ColCtx &gate) const
     {
-        hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(silu(val) * gate);
+        hidden[((size_t)g * l + r) * ((size_t)kact * d_e) + nn] = from_f32<T>(raw ? val : silu(val) * gate);
     }
     static constexpr bool kPrepare = false;
     static constexpr bool kRowScale = false;
     static constexpr bool kColScale = true;
     __device__ float col_scale(int g, int nn) const { return col_ctx(g, nn); }
-    __device__ float epi(float val, float gate) const { return silu_fast(val) * gate; }
+    __device__ float epi(float val, float gate) const { return raw ? val : silu_fast(val) * gate; }
     __device__ bool has_residual() const { return false; }
     __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
     __device__ void put8(int g, int r, int nn, uint4 piece) const
@@ -373,6 +374,71 @@ template <typename T> struct UomeDownProblem {
     __device__ bool has_residual() const { return flags & F_RESIDUAL; }
     __device__ uint4 res8(int g, int r, int nn) const { return *reinterpret_cast<const uint4 *>(u + ((size_t)g * l + r) * d + nn); }
     __device__ void put8(int g, int r, int nn, uint4 piece) const { *reinterpret_cast<uint4 *>(out + ((size_t)g * l + r) * d + nn) = piece; }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Weight gradients of the expert-selection UoME block: for expert i (the group),
+//   dW[M, N] = sum over the (sample b, slot s) pairs with expert_idx[b,s] == i of  L_b^T R_{b,s}
+// contracted over the l tokens of the sample.  The left factor is given TRANSPOSED
+// ([sample][rows][l], so that its rows are K-contiguous like every A operand), the right factor in
+// its natural token-major layout.  K segments = the pairs, found by the workgroup itself (prepare),
+// in sample order, which fixes the summation order.
+//   dA^O_i [d_e, d]:  left = H^T [b][k*d_e][l] (rows s*d_e + e of the pair), right = d_out [b][l][d]
+//   dA^I_i [d, d_e]:  left = U^T [b][d][l],  right = dZ [b][l][k*d_e], columns s*d_e + j of the pair
+template <typename T> struct WgradProblem {
+    const T *left_t, *right;
+    const int32_t *expert_idx;
+    T *dw;                 // [n, M, N]
+    int b, l, n, kact;
+    int M, N;              // rows and columns of one expert's gradient
+    int left_rows;         // rows of one sample in left_t (k*d_e or d)
+    int left_slot_rows;    // d_e if the left rows depend on the slot, else 0
+    int right_stride;      // elements between token rows of right (d or k*d_e)
+    int right_slot_cols;   // d_e if the right columns depend on the slot, else 0
+
+    __device__ int rows(int) const { return M; }
+    __device__ int ncols() const { return N; }
+    __device__ int kseg() const { return l; }
+    __device__ long b_stride() const { return right_stride; }
+    __device__ int kdim(int) const { return 0; }  // prepare() supplies K
+    static constexpr bool kPrepare = true;
+    __device__ int prepare(int g, uint32_t *segtab, int tid, int) const
+    {
+        __shared__ int cnt_sh;
+        if (tid == 0) {  // b*k small integers, L2 resident: one thread lists the pairs in order
+            int cnt = 0;
+            for (int bb = 0; bb < b && cnt < 128; ++bb)
+                for (int s = 0; s < kact; ++s)
+                    if (expert_idx[bb * kact + s] == g) {
+                        segtab[cnt++] = ((uint32_t)bb << 8) | (uint32_t)s;
+                        break;  // an expert appears at most once in a sample's list
+                    }
+            cnt_sh = cnt;
+        }
+        __syncthreads();
+        return cnt_sh * l;
+    }
+    __device__ uint32_t seg_ctx(int, int) const { return 0; }
+    __device__ const T *a_ptr_ctx(int, int r, int, uint32_t ctx) const
+    {
+        const int bb = (int)(ctx >> 8), s = (int)(ctx & 0xFFu);
+        return left_t + ((size_t)bb * left_rows + (size_t)s * left_slot_rows + r) * l;
+    }
+    __device__ const T *b_ptr_ctx(int, int, int nn, uint32_t ctx) const
+    {
+        const int bb = (int)(ctx >> 8), s = (int)(ctx & 0xFFu);
+        return right + (size_t)bb * l * right_stride + (size_t)s * right_slot_cols + nn;
+    }
+    static constexpr bool kRowScale = false;
+    static constexpr bool kColScale = false;
+    __device__ float col_scale(int, int) const { return 1.0f; }
+    __device__ float epi(float val, float) const { return val; }
+    __device__ bool has_residual() const { return false; }
+    __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const
+    {
+        *reinterpret_cast<uint4 *>(dw + ((size_t)g * M + r) * N + nn) = piece;
+    }
 };
 
 }  // namespace uoe

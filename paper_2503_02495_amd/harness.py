@@ -103,6 +103,22 @@ class DeviceLayer:
                        self.m_expert_gate if expert_gate is None else expert_gate, patch_idx, patch_gate,
                        self.out if out is None else out, self.ws)
 
+    def uome_backward(self, d_out, expert_idx=None, expert_gate=None, u=None):
+        """Gradients of the expert-selection UoME block; returns (d_u, d_a_in, d_a_out, d_gate)."""
+        if not hasattr(self, "bwd_ws"):
+            nbytes = B.uome_backward_workspace_bytes(self.uome)
+            if nbytes == 0:
+                raise B.UoeError(B.ERR_UNSUPPORTED, "uoe_uome_backward_workspace_bytes")
+            self.bwd_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self.d_u = torch.empty_like(self.x)
+            self.d_a_in, self.d_a_out = torch.empty_like(self.a_in), torch.empty_like(self.a_out)
+            self.d_gate = torch.empty(self.cfg.b, self.cfg.n_m, dtype=torch.float32, device=self.device)
+        B.uome_backward(self.uome, self.u if u is None else u, self.a_in, self.a_out,
+                        self.m_expert_idx if expert_idx is None else expert_idx,
+                        self.m_expert_gate if expert_gate is None else expert_gate, d_out,
+                        self.d_u, self.d_a_in, self.d_a_out, self.d_gate, self.bwd_ws)
+        return self.d_u, self.d_a_in, self.d_a_out, self.d_gate
+
     def layer_forward(self):
         B.layer_forward(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
                         self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws)

@@ -167,6 +167,13 @@ def make_inputs(cfg: LayerConfig, seed: Optional[int] = None, w_std: float = 0.0
     return inp
 
 
+def make_upstream_grad(cfg: LayerConfig, seed: Optional[int] = None) -> np.ndarray:
+    """A synthetic upstream gradient dL/d(out) [b,l,d] for backward-pass tests and timing: unit
+    normal, bf16-exact for bf16 configs, from a stream separate from make_inputs'."""
+    rng = np.random.default_rng((cfg.seed if seed is None else seed) + 7919)
+    return _draw(rng, (cfg.b, cfg.l, cfg.d), 1.0, cfg.dtype)
+
+
 def small_config(name: str = "small", **kw) -> LayerConfig:
     """A config with every size overridable, for randomly drawn tiny shapes in tests."""
     base = dict(b=2, l=24, d=16, n_a=3, d_h=8, m=4, c=2, k_a=2, n_m=3, d_e=8, k_m=2,

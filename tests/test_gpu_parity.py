@@ -258,6 +258,68 @@ def test_uome_stage_parity_sampled_rows(name, flags):
     run_uome_stage(name, flags, rows=192)
 
 
+# --------------------------------------------------------------------------- UoME backward
+BWD_CONFIGS = {
+    # ragged row tiles (l = 96, 160), an expert nobody selects (n = 6, b = 2, k = 2), d_e != d
+    "bwd_small": small(b=2, l=96, d=64, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=6, d_e=32, k_m=2, dtype=synth.BF16),
+    "bwd_ragged": small(b=5, l=160, d=96, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=4, d_e=160, k_m=3, dtype=synth.BF16),
+    "bwd_k1": small(b=3, l=32, d=32, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=3, d_e=32, k_m=1, dtype=synth.BF16),
+}
+
+
+def grad_err(y, r):
+    """max |y - r| / max(|r|, rms of r): a gradient tensor judged against its own magnitude."""
+    r = np.asarray(r, np.float64)
+    y = np.asarray(y, np.float64)
+    rms = np.sqrt(np.mean(r * r))
+    if rms == 0.0:
+        assert not np.any(y)
+        return 0.0
+    return float(np.max(np.abs(y - r) / np.maximum(np.abs(r), rms)))
+
+
+@pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["lm", "vit_bwd"])
+@pytest.mark.parametrize("flags", [0, R | GE])
+def test_uome_backward_parity(name, flags):
+    """uoe_uome_backward against the oracle's chain rule (itself pinned by finite differences of
+    the forward oracle) on the same routing, inputs and upstream gradient.  Every gradient is
+    compared in full; an expert no sample selected must get exactly zero."""
+    import dataclasses
+    if name == "vit_bwd":      # vit's shape with l padded to a multiple of 32 (196 is not)
+        cfg = dataclasses.replace(synth.CONFIGS["vit"], l=224, b=16)
+        w_std = 0.02
+    else:
+        cfg = BWD_CONFIGS[name] if name in BWD_CONFIGS else synth.CONFIGS[name]
+        w_std = 0.02 if name in synth.CONFIGS else 0.06
+    print(f"uome backward {name} flags={flags}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std)
+    d_out = synth.make_upstream_grad(cfg)
+    dev = DeviceLayer(inp, R, flags)
+    ref = oracle.route(inp.x, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
+    gate = ref.expert_gate.astype(np.float32)
+    d_u, d_a_in, d_a_out, d_gate = dev.uome_backward(
+        to_device(d_out, cfg.dtype, dev.device), expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
+        expert_gate=to_device(gate, synth.F32, dev.device), u=dev.x)
+    torch.cuda.synchronize()
+    want = oracle.uome_backward(inp.x, inp.a_in, inp.a_out, ref.expert_id, gate, d_out, flags)
+    unused = np.setdiff1d(np.arange(cfg.n_m), ref.expert_id.ravel())
+    got_in, got_out = to_host(d_a_in), to_host(d_a_out)
+    assert not np.any(got_in[unused]) and not np.any(got_out[unused])
+    errs = {"d_u": grad_err(to_host(d_u), want.d_u), "d_a_in": grad_err(got_in, want.d_a_in),
+            "d_a_out": grad_err(got_out, want.d_a_out), "d_gate": grad_err(to_host(d_gate), want.d_gate)}
+    print(f"[uome backward {name} flags={flags}] unused experts {unused.tolist()} " +
+          " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {TOL[cfg.dtype]:.0e})", flush=True)
+    assert max(errs.values()) <= TOL[cfg.dtype]
+
+
+def test_uome_backward_rejects_unsupported():
+    cfg = small(b=2, l=40, d=64, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16)
+    blk = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_m, cfg.k_m, 1, 1, cfg.d_e, B.BF16, R)
+    assert B.uome_backward_workspace_bytes(blk) == 0       # l % 32 != 0
+    blk = B.block_desc(2, 64, 64, 2, 1, 1, 1, 32, B.F32, R)
+    assert B.uome_backward_workspace_bytes(blk) == 0       # fp32 storage
+
+
 # --------------------------------------------------------------------------- single-mode SMHA blocks
 @pytest.mark.parametrize("mode", ["expert_only", "data_only"])
 @pytest.mark.parametrize("name", ["bf16_ragged", "lm"])
