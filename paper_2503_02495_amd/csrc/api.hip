@@ -94,10 +94,10 @@ UomeWs uome_ws_layout(const uoe_block_desc *d)
 }
 size_t uome_ws(const uoe_block_desc *d) { return uome_ws_layout(d).total; }
 
-// backward pass of the UoME block: Z, dH, dZ, H [b,l,k*d_e]; U^T [b,d,l]; H^T [b,k*d_e,l]; the two
-// transposed weight tensors; partial sums of the gate gradient
+// backward pass of the UoME block: Z, dH, dZ [b,l,k*d_e]; dZ^T, H^T [b,k*d_e,l]; the two transposed
+// weight tensors; split-K tiles of one weight gradient; partial sums of the gate gradient
 struct UomeBwdWs {
-    size_t z, dh, dz, h, u_t, h_t, a_in_t, a_out_t, gpart, total;
+    size_t z, dh, dz, dz_t, h_t, a_in_t, a_out_t, partial, gpart, total;
 };
 UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
 {
@@ -109,12 +109,13 @@ UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
     w.z = off; off += act;
     w.dh = off; off += act;
     w.dz = off; off += act;
-    w.h = off; off += act;
+    w.dz_t = off; off += act;
     w.h_t = off; off += act;
-    w.u_t = off; off += up((size_t)d->b * d->l * d->d * es);
     w.a_in_t = off; off += wt;
     w.a_out_t = off; off += wt;
-    w.gpart = off; off += up((size_t)d->b * d->k * uome_backward_gate_chunks(d->l) * sizeof(float));
+    w.partial = off;
+    off += up((size_t)d->n * uome_backward_splits(d->b, d->l, d->d, d->n, d->k, d->width) * d->d * d->width * sizeof(float));
+    w.gpart = off; off += up((size_t)d->b * d->k * uome_backward_gate_chunks(d->l, d->width) * sizeof(float));
     w.total = off;
     return w;
 }
@@ -382,10 +383,12 @@ int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in
     a.u = u; a.a_in = a_in; a.a_out = a_out; a.d_out = d_out; a.expert_idx = expert_idx; a.expert_gate = expert_gate;
     a.d_u = d_u; a.d_a_in = d_a_in; a.d_a_out = d_a_out; a.d_gate = d_gate;
     a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.d_e = blk->width; a.flags = blk->flags;
-    a.z = at(ws, w.z); a.dh = at(ws, w.dh); a.dz = at(ws, w.dz); a.h = at(ws, w.h);
-    a.u_t = at(ws, w.u_t); a.h_t = at(ws, w.h_t); a.a_in_t = at(ws, w.a_in_t); a.a_out_t = at(ws, w.a_out_t);
+    a.z = at(ws, w.z); a.dh = at(ws, w.dh); a.dz = at(ws, w.dz);
+    a.dz_t = at(ws, w.dz_t); a.h_t = at(ws, w.h_t); a.a_in_t = at(ws, w.a_in_t); a.a_out_t = at(ws, w.a_out_t);
     a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
-    a.gchunks = uome_backward_gate_chunks(blk->l);
+    a.partial = reinterpret_cast<float *>(at(ws, w.partial));
+    a.gchunks = uome_backward_gate_chunks(blk->l, blk->width);
+    a.splits = uome_backward_splits(blk->b, blk->l, blk->d, blk->n, blk->k, blk->width);
     return launch_uome_backward(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
 }
 

@@ -133,11 +133,12 @@ struct UomeBwdArgs {
     int b, l, d, n, k, d_e;
     uint32_t flags;
     // workspace, storage dtype unless noted
-    void *z, *dh, *dz, *h;                    // [b, l, k*d_e] each
-    void *u_t, *h_t;                          // [b, d, l], [b, k*d_e, l]
+    void *z, *dh, *dz;                        // [b, l, k*d_e] each
+    void *dz_t, *h_t;                         // [b, k*d_e, l] each
     void *a_in_t, *a_out_t;                   // [n, d_e, d], [n, d, d_e]
-    float *gpart;                             // [b, k, chunks] partial sums of d_gate
-    int gchunks;
+    float *gpart;                             // [b, k, gchunks] partial sums of d_gate
+    float *partial;                           // [n*splits, d_e, d] split-K tiles of a weight gradient
+    int gchunks, splits;
 };
 
 struct GatherArgs {
@@ -156,7 +157,8 @@ hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st);    // E
 hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // Eq. 39-40 only
 hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st);
-int uome_backward_gate_chunks(int l);
+int uome_backward_gate_chunks(int l, int d_e);
+int uome_backward_splits(int b, int l, int d, int n, int k, int d_e);
 
 // host-side sizing shared by api.cpp and the launchers
 int route_tokens_per_chunk(int b, int l);

@@ -27,6 +27,7 @@
 // Requirements (checked by the callers): kseg() % BK == 0, N segments multiples of 8.  M and N
 // tails are masked.
 #pragma once
+#include <type_traits>
 #include "common.h"
 
 namespace uoe {
@@ -95,6 +96,14 @@ __device__ __forceinline__ void load_row_scale(const P &p, float (&rs)[TM], int 
     }
 }
 
+// problems that store fp32 tiles straight from the accumulators declare kF32Out and put4_f32
+template <typename P, typename = void> struct writes_f32 {
+    static constexpr bool value = false;
+};
+template <typename P> struct writes_f32<P, std::void_t<decltype(P::kF32Out)>> {
+    static constexpr bool value = P::kF32Out;
+};
+
 template <typename P, int TM, int TN, int SPITCH>
 __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN], uint16_t (*stage)[SPITCH], const float *coltab,
                                               const float (&rs)[TM], int g, int grow0, int gcol0, int wcol0, int M, int N,
@@ -102,6 +111,24 @@ __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN
 {
     constexpr int WM = TM * 32, WN = TN * 32;
     const int lr = lane & 31, lh = lane >> 5;
+    if constexpr (writes_f32<P>::value) {
+        // a lane holds 4 consecutive columns of one row per register quad: 16-byte stores; the two
+        // half-waves and the four quads of a row complete its 128-byte line in L2
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int grow = grow0 + i * 32 + lr;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int qg = 0; qg < 4; ++qg) {
+                    const int gcol = gcol0 + j * 32 + qg * 8 + lh * 4;
+                    if (grow < M && gcol < N)
+                        p.put4_f32(g, grow, gcol, make_float4(acc[i][j][qg * 4 + 0], acc[i][j][qg * 4 + 1],
+                                                              acc[i][j][qg * 4 + 2], acc[i][j][qg * 4 + 3]));
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll

@@ -377,28 +377,30 @@ template <typename T> struct UomeDownProblem {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Weight gradients of the expert-selection UoME block: for expert i (the group),
-//   dW[M, N] = sum over the (sample b, slot s) pairs with expert_idx[b,s] == i of  L_b^T R_{b,s}
+// Weight gradients of the expert-selection UoME block: for expert i,
+//   dW[M, N] = sum over the (sample b, slot s) pairs with expert_idx[b,s] == i of  L_{b,s}^T R_{b,s}
 // contracted over the l tokens of the sample.  The left factor is given TRANSPOSED
 // ([sample][rows][l], so that its rows are K-contiguous like every A operand), the right factor in
 // its natural token-major layout.  K segments = the pairs, found by the workgroup itself (prepare),
-// in sample order, which fixes the summation order.
-//   dA^O_i [d_e, d]:  left = H^T [b][k*d_e][l] (rows s*d_e + e of the pair), right = d_out [b][l][d]
-//   dA^I_i [d, d_e]:  left = U^T [b][d][l],  right = dZ [b][l][k*d_e], columns s*d_e + j of the pair
+// in sample order, which fixes the summation order.  The token axis is cut into `splits` equal
+// ranges for parallelism: group = expert * splits + j contracts range j of every pair and stores
+// its fp32 partial tile [group][M][N]; a reduction kernel adds the ranges in order.
+//   dA^O_i   [d_e, d]:  left = H^T  [b][k*d_e][l] (rows s*d_e + e of the pair), right = d_out [b][l][d]
+//   dA^I_i^T [d_e, d]:  left = dZ^T [b][k*d_e][l] (the same rows),              right = u     [b][l][d]
 template <typename T> struct WgradProblem {
     const T *left_t, *right;
     const int32_t *expert_idx;
-    T *dw;                 // [n, M, N]
-    int b, l, n, kact;
+    float *partial;        // [n*splits, M, N]
+    int b, l, n, kact, splits;
     int M, N;              // rows and columns of one expert's gradient
-    int left_rows;         // rows of one sample in left_t (k*d_e or d)
-    int left_slot_rows;    // d_e if the left rows depend on the slot, else 0
-    int right_stride;      // elements between token rows of right (d or k*d_e)
-    int right_slot_cols;   // d_e if the right columns depend on the slot, else 0
+    int left_rows;         // rows of one sample in left_t (k*d_e)
+    int left_slot_rows;    // rows of one slot (d_e)
+    int right_stride;      // elements between token rows of right
 
+    static constexpr bool kF32Out = true;
     __device__ int rows(int) const { return M; }
     __device__ int ncols() const { return N; }
-    __device__ int kseg() const { return l; }
+    __device__ int kseg() const { return l / splits; }
     __device__ long b_stride() const { return right_stride; }
     __device__ int kdim(int) const { return 0; }  // prepare() supplies K
     static constexpr bool kPrepare = true;
@@ -406,28 +408,29 @@ template <typename T> struct WgradProblem {
     {
         __shared__ int cnt_sh;
         if (tid == 0) {  // b*k small integers, L2 resident: one thread lists the pairs in order
+            const int expert = g / splits;
             int cnt = 0;
             for (int bb = 0; bb < b && cnt < 128; ++bb)
                 for (int s = 0; s < kact; ++s)
-                    if (expert_idx[bb * kact + s] == g) {
+                    if (expert_idx[bb * kact + s] == expert) {
                         segtab[cnt++] = ((uint32_t)bb << 8) | (uint32_t)s;
                         break;  // an expert appears at most once in a sample's list
                     }
             cnt_sh = cnt;
         }
         __syncthreads();
-        return cnt_sh * l;
+        return cnt_sh * (l / splits);
     }
     __device__ uint32_t seg_ctx(int, int) const { return 0; }
-    __device__ const T *a_ptr_ctx(int, int r, int, uint32_t ctx) const
+    __device__ const T *a_ptr_ctx(int g, int r, int, uint32_t ctx) const
     {
         const int bb = (int)(ctx >> 8), s = (int)(ctx & 0xFFu);
-        return left_t + ((size_t)bb * left_rows + (size_t)s * left_slot_rows + r) * l;
+        return left_t + ((size_t)bb * left_rows + (size_t)s * left_slot_rows + r) * l + (g % splits) * (l / splits);
     }
-    __device__ const T *b_ptr_ctx(int, int, int nn, uint32_t ctx) const
+    __device__ const T *b_ptr_ctx(int g, int, int nn, uint32_t ctx) const
     {
-        const int bb = (int)(ctx >> 8), s = (int)(ctx & 0xFFu);
-        return right + (size_t)bb * l * right_stride + (size_t)s * right_slot_cols + nn;
+        const int bb = (int)(ctx >> 8);
+        return right + ((size_t)bb * l + (size_t)(g % splits) * (l / splits)) * right_stride + nn;
     }
     static constexpr bool kRowScale = false;
     static constexpr bool kColScale = false;
@@ -435,9 +438,10 @@ template <typename T> struct WgradProblem {
     __device__ float epi(float val, float) const { return val; }
     __device__ bool has_residual() const { return false; }
     __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
-    __device__ void put8(int g, int r, int nn, uint4 piece) const
+    __device__ void put8(int, int, int, uint4) const {}
+    __device__ void put4_f32(int g, int r, int nn, float4 v) const
     {
-        *reinterpret_cast<uint4 *>(dw + ((size_t)g * M + r) * N + nn) = piece;
+        *reinterpret_cast<float4 *>(partial + ((size_t)g * M + r) * N + nn) = v;
     }
 };
 

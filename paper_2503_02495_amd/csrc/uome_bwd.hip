@@ -10,9 +10,12 @@
 //   dA^O_i = sum_{(b,s): i(s) = i} H_{b,s}^T d_out_b     GEMM over the tokens of those samples
 //   dA^I_i = sum_{(b,s): i(s) = i} u_b^T dZ_{b,s}        GEMM over the tokens of those samples
 // All five contractions run on the pipelined MFMA engine through the forward problems (the raw
-// mode of UomeUpProblem, UomeDownProblem) and WgradProblem; operands the engine wants with K
-// contiguous are transposed by a plain tiled copy first (weights: small; u and H: one extra pass
-// over the activations).  Z and dH are kept in the storage dtype between the kernels.
+// mode of UomeUpProblem, UomeDownProblem) and WgradProblem.  The engine wants every left operand
+// K-contiguous: the two weight tensors are transposed by a plain tiled copy (small), the
+// elementwise kernel writes H and dZ directly in token-minor layout, and dA^I is formed as its
+// transpose (dZ^T u, so that u is the natural-layout right operand) and turned back by the
+// reduction that adds the split-K partials.  Z and dH are kept in the storage dtype between the
+// kernels.
 #include "common.h"
 #include "problems.h"
 #include "gemm_mfma.h"
@@ -20,52 +23,66 @@
 
 namespace uoe {
 
-// [batch][rows][cols] -> [batch][cols][rows], 2-byte elements, 32x32 tiles through LDS
-__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t *src, uint16_t *dst, int rows, int cols)
+// [rows][cols] -> [cols][rows] per expert, 2-byte elements, 32x32 tiles through LDS; both weight
+// tensors in one launch
+__global__ __launch_bounds__(256) void transpose_weights_kernel(const uint16_t *a_out, uint16_t *a_out_t, const uint16_t *a_in,
+                                                                uint16_t *a_in_t, int n, int d, int d_e)
 {
     __shared__ uint16_t tile[32][33];
-    const size_t base = (size_t)blockIdx.z * rows * cols;
-    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const bool second = (int)blockIdx.z >= n;
+    const int e = second ? blockIdx.z - n : blockIdx.z;
+    const int rows = second ? d : d_e, cols = second ? d_e : d;
+    const uint16_t *src = (second ? a_in : a_out) + (size_t)e * rows * cols;
+    uint16_t *dst = (second ? a_in_t : a_out_t) + (size_t)e * rows * cols;
+    const int ctiles = (cols + 31) / 32;
+    const int r0 = (blockIdx.x / ctiles) * 32, c0 = (blockIdx.x % ctiles) * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int i = ty; i < 32; i += 8)
-        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[base + (size_t)(r0 + i) * cols + c0 + tx];
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[(size_t)(r0 + i) * cols + c0 + tx];
     __syncthreads();
     for (int i = ty; i < 32; i += 8)
-        if (c0 + i < cols && r0 + tx < rows) dst[base + (size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+        if (c0 + i < cols && r0 + tx < rows) dst[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
 }
 
-static hipError_t launch_transpose(const void *src, void *dst, int batch, int rows, int cols, hipStream_t st)
+int uome_backward_gate_chunks(int l, int d_e) { return ((l + 63) / 64) * (d_e / 32); }
+int uome_backward_splits(int b, int l, int d, int n, int k, int d_e)
 {
-    const dim3 grid((cols + 31) / 32, (rows + 31) / 32, batch);
-    hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, st, static_cast<const uint16_t *>(src),
-                       static_cast<uint16_t *>(dst), rows, cols);
-    return hipGetLastError();
+    // cut the token axis until the launch has 512 large tiles, while a workgroup keeps on average
+    // >= 1024 of K and the ranges stay multiples of 64
+    int s = 1;
+    const long k_avg = (long)b * k * l / n, tiles = (long)n * ((d_e + 255) / 256) * ((d + 127) / 128);
+    while (s < 8 && tiles * s < 512 && l % (2 * s * 64) == 0 && k_avg / (2 * s) >= 1024) s *= 2;
+    return s;
 }
 
-int uome_backward_gate_chunks(int l) { return (l + 63) / 64; }
-
-// Elementwise middle of the backward pass.  Block = (chunk of 64 token rows, slot s, sample b);
-// a thread walks 8-element pieces of the slot's d_e columns.  Writes dZ and H, and the block's
-// partial sum of dH * SiLU(Z) (summed over the block in a fixed tree, then over chunks by
-// uome_bwd_gate_kernel in chunk order).
+// Elementwise middle of the backward pass.  Block = (64 token rows, 32 columns of one slot,
+// sample b), one 8-element piece per thread.  Writes dZ in token-major layout (the left operand of
+// the d_u contraction) and dZ^T, H^T in token-minor layout [b][k*d_e][l] (the left operands of the
+// weight gradients) through LDS tiles, and the block's partial sum of dH * SiLU(Z) (fixed tree;
+// the partials are then added in index order by uome_bwd_gate_kernel).
 __global__ __launch_bounds__(256) void uome_bwd_mid_kernel(UomeBwdArgs a)
 {
+    constexpr int TP = 72;  // tile pitch in elements: 16-byte aligned rows
     __shared__ float red[256];
-    const int chunk = blockIdx.x, s = blockIdx.y, bb = blockIdx.z, tid = threadIdx.x;
+    __shared__ __align__(16) uint16_t tz[32][TP], th[32][TP];
+    const int chunk = blockIdx.x, cb = blockIdx.y, bb = blockIdx.z, tid = threadIdx.x;
+    const int per_slot = a.d_e / 32, s = cb / per_slot;
     const int i = clampi(a.expert_idx[bb * a.k + s], a.n);
     const float w = ((a.flags & F_GATE_EXPERT) && a.expert_gate) ? a.expert_gate[(size_t)bb * a.n + i] : 1.0f;
-    const int t0 = chunk * 64, rows = min(64, a.l - t0), p8 = a.d_e / 8;
+    const int t0 = chunk * 64, rows = min(64, a.l - t0), c0 = cb * 32;
     const size_t width = (size_t)a.k * a.d_e;
     const bf16_t *z = static_cast<const bf16_t *>(a.z), *dh = static_cast<const bf16_t *>(a.dh);
-    bf16_t *dz = static_cast<bf16_t *>(a.dz), *h = static_cast<bf16_t *>(a.h);
+    bf16_t *dz = static_cast<bf16_t *>(a.dz);
     float part = 0.f;
-    for (int o = tid; o < rows * p8; o += 256) {
-        const int r = o / p8, pc = o - r * p8;
-        const size_t at = ((size_t)bb * a.l + t0 + r) * width + (size_t)s * a.d_e + pc * 8;
-        float zv[8], dv[8];
-        load8(z + at, zv);
-        load8(dh + at, dv);
-        uint32_t oz[4], oh[4];
+    {
+        const int r = tid >> 2, pc = tid & 3;
+        float zv[8] = {0, 0, 0, 0, 0, 0, 0, 0}, dv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        const size_t at = ((size_t)bb * a.l + t0 + r) * width + c0 + pc * 8;
+        if (r < rows) {
+            load8(z + at, zv);
+            load8(dh + at, dv);
+        }
+        uint32_t oz[4];
 #pragma unroll
         for (int q = 0; q < 8; q += 2) {
             float dzv[2], hv[2];
@@ -78,34 +95,79 @@ __global__ __launch_bounds__(256) void uome_bwd_mid_kernel(UomeBwdArgs a)
                 dzv[e] = dv[q + e] * w * (sig * (1.0f + zv[q + e] * (1.0f - sig)));
             }
             oz[q / 2] = pack2_bf16(dzv[0], dzv[1]);
-            oh[q / 2] = pack2_bf16(hv[0], hv[1]);
+            const uint32_t oh = pack2_bf16(hv[0], hv[1]);
+            tz[pc * 8 + q][r] = (uint16_t)(oz[q / 2] & 0xFFFFu);
+            tz[pc * 8 + q + 1][r] = (uint16_t)(oz[q / 2] >> 16);
+            th[pc * 8 + q][r] = (uint16_t)(oh & 0xFFFFu);
+            th[pc * 8 + q + 1][r] = (uint16_t)(oh >> 16);
         }
-        *reinterpret_cast<uint4 *>(dz + at) = make_uint4(oz[0], oz[1], oz[2], oz[3]);
-        *reinterpret_cast<uint4 *>(h + at) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+        if (r < rows) *reinterpret_cast<uint4 *>(dz + at) = make_uint4(oz[0], oz[1], oz[2], oz[3]);
     }
     red[tid] = part;
+    __syncthreads();
+    {
+        const int col = tid >> 3, tp = tid & 7;  // 8 consecutive tokens of one column
+        if (tp * 8 < rows) {
+            const size_t at = ((size_t)bb * width + c0 + col) * a.l + t0 + tp * 8;
+            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.dz_t) + at) = *reinterpret_cast<const uint4 *>(&tz[col][tp * 8]);
+            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.h_t) + at) = *reinterpret_cast<const uint4 *>(&th[col][tp * 8]);
+        }
+    }
+    for (int st = 128; st > 0; st >>= 1) {
+        if (tid < st) red[tid] += red[tid + st];
+        __syncthreads();
+    }
+    if (tid == 0) a.gpart[((size_t)bb * a.k + s) * a.gchunks + chunk * per_slot + (cb - s * per_slot)] = red[0];
+}
+
+// Adds the split-K partial tiles of a weight gradient in range order and stores the storage dtype,
+// as [n][M][N] or transposed as [n][N][M].  32x32 tiles through LDS.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *partial, uint16_t *dst, int M, int N, int splits,
+                                                           int transposed)
+{
+    __shared__ float tile[32][33];
+    const int e = blockIdx.z, r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8) {
+        float v = 0.f;
+        if (r0 + i < M && c0 + tx < N)
+            for (int j = 0; j < splits; ++j) v += partial[(((size_t)e * splits + j) * M + r0 + i) * N + c0 + tx];
+        tile[i][tx] = v;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        if (transposed) {
+            if (c0 + i < N && r0 + tx < M)
+                dst[((size_t)e * N + c0 + i) * M + r0 + tx] = (uint16_t)(pack2_bf16(tile[tx][i], 0.f) & 0xFFFFu);
+        } else if (r0 + i < M && c0 + tx < N)
+            dst[((size_t)e * M + r0 + i) * N + c0 + tx] = (uint16_t)(pack2_bf16(tile[i][tx], 0.f) & 0xFFFFu);
+    }
+}
+
+// d_gate [b,n]: block (slot s, sample b) adds the slot's partial sums (each thread a strided
+// subset in index order, then a fixed tree) into the entry of the slot's expert; the block of slot 0
+// also writes the zeros of the experts the sample did not select (all of them without the gate flag).
+__global__ __launch_bounds__(256) void uome_bwd_gate_kernel(UomeBwdArgs a)
+{
+    __shared__ float red[256];
+    const int s = blockIdx.x, bb = blockIdx.y, tid = threadIdx.x;
+    const bool gated = a.flags & F_GATE_EXPERT;
+    if (s == 0 && tid < a.n) {
+        bool chosen = false;
+        for (int q = 0; q < a.k; ++q) chosen |= clampi(a.expert_idx[bb * a.k + q], a.n) == tid;
+        if (!chosen || !gated) a.d_gate[(size_t)bb * a.n + tid] = 0.f;
+    }
+    if (!gated) return;
+    const float *src = a.gpart + ((size_t)bb * a.k + s) * a.gchunks;
+    float v = 0.f;
+    for (int c = tid; c < a.gchunks; c += 256) v += src[c];
+    red[tid] = v;
     __syncthreads();
     for (int st = 128; st > 0; st >>= 1) {
         if (tid < st) red[tid] += red[tid + st];
         __syncthreads();
     }
-    if (tid == 0) a.gpart[((size_t)bb * a.k + s) * a.gchunks + chunk] = red[0];
-}
-
-// d_gate [b,n]: zero for experts the sample did not select (and everywhere without the gate flag)
-__global__ __launch_bounds__(64) void uome_bwd_gate_kernel(UomeBwdArgs a)
-{
-    const int bb = blockIdx.x, i = threadIdx.x;
-    if (i >= a.n) return;
-    float v = 0.f;
-    if (a.flags & F_GATE_EXPERT)
-        for (int s = 0; s < a.k; ++s)
-            if (clampi(a.expert_idx[bb * a.k + s], a.n) == i) {
-                const float *src = a.gpart + ((size_t)bb * a.k + s) * a.gchunks;
-                for (int c = 0; c < a.gchunks; ++c) v += src[c];
-                break;
-            }
-    a.d_gate[(size_t)bb * a.n + i] = v;
+    if (tid == 0) a.d_gate[(size_t)bb * a.n + clampi(a.expert_idx[bb * a.k + s], a.n)] = red[0];
 }
 
 template <typename P> static hipError_t bwd_gemm(const P &p, int groups, int rows, int ncols, int kseg, hipStream_t st)
@@ -124,8 +186,13 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     hipError_t err;
     const int width = a.k * a.d_e;
     // weights with K contiguous for the two data-gradient GEMMs
-    if ((err = launch_transpose(a.a_out, a.a_out_t, a.n, a.d_e, a.d, st)) != hipSuccess) return err;  // -> [n, d, d_e]
-    if ((err = launch_transpose(a.a_in, a.a_in_t, a.n, a.d, a.d_e, st)) != hipSuccess) return err;    // -> [n, d_e, d]
+    {   // one launch: blocks z < n take A^O [d_e, d] -> [d, d_e], the others A^I [d, d_e] -> [d_e, d]
+        const int tiles = ((a.d + 31) / 32) * ((a.d_e + 31) / 32);
+        hipLaunchKernelGGL(transpose_weights_kernel, dim3(tiles, 1, 2 * a.n), dim3(256), 0, st,
+                           static_cast<const uint16_t *>(a.a_out), static_cast<uint16_t *>(a.a_out_t),
+                           static_cast<const uint16_t *>(a.a_in), static_cast<uint16_t *>(a.a_in_t), a.n, a.d, a.d_e);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
 
     UomeUpProblem<T> zp;  // Z = u W1_b
     zp.u = static_cast<const T *>(a.u); zp.a_in = static_cast<const T *>(a.a_in);
@@ -136,10 +203,10 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     hp.u = static_cast<const T *>(a.d_out); hp.a_in = static_cast<const T *>(a.a_out_t); hp.hidden = static_cast<T *>(a.dh);
     if ((err = bwd_gemm(hp, a.b, a.l, width, a.d, st)) != hipSuccess) return err;
 
-    hipLaunchKernelGGL(uome_bwd_mid_kernel, dim3(a.gchunks, a.k, a.b), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(uome_bwd_mid_kernel, dim3((a.l + 63) / 64, width / 32, a.b), dim3(256), 0, st, a);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     if (a.d_gate) {
-        hipLaunchKernelGGL(uome_bwd_gate_kernel, dim3(a.b), dim3(64), 0, st, a);
+        hipLaunchKernelGGL(uome_bwd_gate_kernel, dim3(a.k, a.b), dim3(256), 0, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
 
@@ -149,19 +216,23 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e; up.flags = a.flags;
     if ((err = bwd_gemm(up, a.b, a.l, a.d, a.d_e, st)) != hipSuccess) return err;
 
-    // weight gradients: left factors with the token axis contiguous
-    if ((err = launch_transpose(a.h, a.h_t, a.b, a.l, width, st)) != hipSuccess) return err;  // -> [b, k*d_e, l]
-    if ((err = launch_transpose(a.u, a.u_t, a.b, a.l, a.d, st)) != hipSuccess) return err;    // -> [b, d, l]
+    // weight gradients: [d_e, d] tiles per expert, token axis cut into a.splits ranges
+    const dim3 rgrid((a.d + 31) / 32, (a.d_e + 31) / 32, a.n);
     WgradProblem<T> wo;  // dA^O_i = sum H_{b,s}^T d_out_b
     wo.left_t = static_cast<const T *>(a.h_t); wo.right = static_cast<const T *>(a.d_out);
-    wo.expert_idx = a.expert_idx; wo.dw = static_cast<T *>(a.d_a_out);
-    wo.b = a.b; wo.l = a.l; wo.n = a.n; wo.kact = a.k;
-    wo.M = a.d_e; wo.N = a.d; wo.left_rows = width; wo.left_slot_rows = a.d_e; wo.right_stride = a.d; wo.right_slot_cols = 0;
-    if ((err = bwd_gemm(wo, a.n, a.d_e, a.d, a.l, st)) != hipSuccess) return err;
-    WgradProblem<T> wi = wo;  // dA^I_i = sum u_b^T dZ_{b,s}
-    wi.left_t = static_cast<const T *>(a.u_t); wi.right = static_cast<const T *>(a.dz); wi.dw = static_cast<T *>(a.d_a_in);
-    wi.M = a.d; wi.N = a.d_e; wi.left_rows = a.d; wi.left_slot_rows = 0; wi.right_stride = width; wi.right_slot_cols = a.d_e;
-    return bwd_gemm(wi, a.n, a.d, a.d_e, a.l, st);
+    wo.expert_idx = a.expert_idx; wo.partial = a.partial;
+    wo.b = a.b; wo.l = a.l; wo.n = a.n; wo.kact = a.k; wo.splits = a.splits;
+    wo.M = a.d_e; wo.N = a.d; wo.left_rows = width; wo.left_slot_rows = a.d_e; wo.right_stride = a.d;
+    if ((err = bwd_gemm(wo, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 0, st, a.partial, static_cast<uint16_t *>(a.d_a_out), a.d_e,
+                       a.d, a.splits, 0);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    WgradProblem<T> wi = wo;  // (dA^I_i)^T = sum dZ_{b,s}^T u_b, stored back as [d, d_e] by the reduction
+    wi.left_t = static_cast<const T *>(a.dz_t); wi.right = static_cast<const T *>(a.u);
+    if ((err = bwd_gemm(wi, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 0, st, a.partial, static_cast<uint16_t *>(a.d_a_in), a.d_e,
+                       a.d, a.splits, 1);
+    return hipGetLastError();
 }
 
 }  // namespace uoe

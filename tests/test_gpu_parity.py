@@ -263,6 +263,8 @@ BWD_CONFIGS = {
     # ragged row tiles (l = 96, 160), an expert nobody selects (n = 6, b = 2, k = 2), d_e != d
     "bwd_small": small(b=2, l=96, d=64, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=6, d_e=32, k_m=2, dtype=synth.BF16),
     "bwd_ragged": small(b=5, l=160, d=96, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=4, d_e=160, k_m=3, dtype=synth.BF16),
+    # long token axis, few experts: the weight-gradient launch cuts the token axis into 4 ranges
+    "bwd_split4": small(b=8, l=1024, d=32, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
     "bwd_k1": small(b=3, l=32, d=32, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=3, d_e=32, k_m=1, dtype=synth.BF16),
 }
 
