@@ -333,6 +333,91 @@ def uome_backward(u, a_in, a_out, expert_id, expert_gate, d_out, flags: int = RE
 
 
 @dataclass
+class SmhaGrads:
+    d_x: np.ndarray           # [b,l,d]
+    d_wq: np.ndarray          # [n,d,d_h]
+    d_wk: np.ndarray
+    d_wv: np.ndarray
+    d_wo: np.ndarray          # [n,d_h,d]
+    d_expert_gate: np.ndarray  # [b,n]    zero for inactive experts and without GATE_EXPERT
+    d_patch_gate: np.ndarray   # [b,n,m]  zero for patches the expert did not select and without GATE_PATCH
+
+
+def _rope(a, rope_dim: int, sign: float):
+    """Eq. 32 on the rows of a [rows, d_h] (row r at position r); sign = -1 applies the transposed
+    (inverse) rotation, which is what the chain rule needs."""
+    if rope_dim == 0:
+        return a
+    rows, d_h = a.shape
+    first = d_h - rope_dim
+    out = a.copy()
+    pos = np.arange(rows, dtype=np.float64)[:, None]
+    theta = 10000.0 ** (-2.0 * np.arange(rope_dim // 2, dtype=np.float64) / rope_dim)[None, :]
+    cs, sn = np.cos(pos * theta), sign * np.sin(pos * theta)
+    ev, od = a[:, first::2], a[:, first + 1::2]
+    out[:, first::2] = ev * cs - od * sn
+    out[:, first + 1::2] = ev * sn + od * cs
+    return out
+
+
+def smha_backward(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: int, d_out,
+                  flags: int = RESIDUAL, rope_dim: int = 0) -> SmhaGrads:
+    """Gradients of the SMHA block (Eq. 27-36, with the partial RoPE of Eq. 32 and the shared causal
+    mask of Sec. III-C.3) for an upstream gradient d_out = dL/du [b,l,d].
+
+    Chain rule, per sample b and active expert i with gathered token positions T (Eq. 12, 18):
+    u[T] += w_t * (softmax(q k^T / sqrt(d_h)) v) W^O_i with q, k, v = x[T] W^{q,k,v}_i (q, k rotated).
+    The selections (expert_id, patch_id) are constants; the gates enter as values and their
+    gradients are returned for the caller to chain into the routers."""
+    x, wq, wk, wv, wo, d_out = _f64(x), _f64(wq), _f64(wk), _f64(wv), _f64(wo), _f64(d_out)
+    b, l, d = x.shape
+    n, _, d_h = wq.shape
+    expert_id, patch_id = _i32(expert_id), _i32(patch_id)
+    c = patch_id.shape[2]
+    g_e, g_d = _f64(expert_gate), _f64(patch_gate_)
+    l_p = l // m
+    l_a = c * l_p
+    scale = 1.0 / np.sqrt(float(d_h))
+    gr = SmhaGrads(d_out.copy() if flags & RESIDUAL else np.zeros_like(x), np.zeros_like(wq), np.zeros_like(wk),
+                   np.zeros_like(wv), np.zeros_like(wo), np.zeros((b, n)), np.zeros((b, n, m)))
+    allowed = np.tril(np.ones((l_a, l_a), bool)) if flags & CAUSAL else np.ones((l_a, l_a), bool)
+    for bb in range(b):
+        for i in expert_id[bb]:
+            pid = patch_id[bb, i]
+            T = (pid[:, None] * l_p + np.arange(l_p)[None, :]).reshape(-1)
+            ge = g_e[bb, i] if flags & GATE_EXPERT else 1.0
+            gp = np.repeat(g_d[bb, i, pid], l_p) if flags & GATE_PATCH else np.ones(l_a)
+            # forward, kept
+            h = x[bb, T]
+            q, kk, v = _rope(h @ wq[i], rope_dim, 1.0), _rope(h @ wk[i], rope_dim, 1.0), h @ wv[i]
+            sc = np.where(allowed, (q @ kk.T) * scale, -np.inf)
+            p = np.exp(sc - sc.max(axis=1, keepdims=True))
+            p /= p.sum(axis=1, keepdims=True)
+            o = p @ v
+            y = o @ wo[i]                                   # [l_a,d] before the gates
+            # backward
+            d_y_raw = d_out[bb, T]                          # dL/d(w_t * y_t) = d_out at the row's token
+            row_dot = np.sum(d_y_raw * y, axis=1)           # dL/dw_t
+            if flags & GATE_EXPERT:
+                gr.d_expert_gate[bb, i] = np.sum(row_dot * gp)
+            if flags & GATE_PATCH:
+                gr.d_patch_gate[bb, i, pid] = ge * row_dot.reshape(c, l_p).sum(axis=1)
+            d_y = d_y_raw * (ge * gp)[:, None]
+            gr.d_wo[i] += o.T @ d_y
+            d_o = d_y @ wo[i].T
+            gr_v = p.T @ d_o
+            d_p = d_o @ v.T
+            d_s = p * (d_p - np.sum(d_p * p, axis=1, keepdims=True))   # softmax backward, masked entries have p = 0
+            d_q = _rope((d_s @ kk) * scale, rope_dim, -1.0)
+            d_k = _rope((d_s.T @ q) * scale, rope_dim, -1.0)
+            gr.d_wq[i] += h.T @ d_q
+            gr.d_wk[i] += h.T @ d_k
+            gr.d_wv[i] += h.T @ gr_v
+            np.add.at(gr.d_x[bb], T, d_q @ wq[i].T + d_k @ wk[i].T + gr_v @ wv[i].T)
+    return gr
+
+
+@dataclass
 class LayerResult:
     routing_a: Routing
     u: np.ndarray
