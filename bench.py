@@ -62,6 +62,11 @@ def run_stage(args, cfg, dev, B, torch) -> int:
         from paper_2503_02495_amd.harness import to_device
         d_out = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
         calls["uome_bwd"] = lambda: dev.uome_backward(d_out)
+    if args.stage == "smha_bwd":   # backward of the SMHA block on a synthetic upstream gradient
+        from paper_2503_02495_amd import synth
+        from paper_2503_02495_amd.harness import to_device
+        d_out_a = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
+        calls["smha_bwd"] = lambda: dev.smha_backward(d_out_a)
     if args.stage == "copy":   # a plain copy of known size (1 GiB read + 1 GiB written): counter calibration
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).normal_()
         dst = torch.empty_like(src)
@@ -102,7 +107,7 @@ def main() -> int:
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
                     choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather", "copy",
-                             "uome_bwd"],
+                             "uome_bwd", "smha_bwd"],
                     help="profiling aid: loop one C-ABI call of the path instead of the whole layer "
                          "and print its time (no JSON contract line)")
     args = ap.parse_args()

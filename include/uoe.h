@@ -216,6 +216,34 @@ typedef struct {
     const void *w_expert, *w_b, *w_a, *wq, *wk, *wv, *wo;
 } uoe_smha_weights;
 
+/* Gradients of the four SMHA weight tensors, shaped like the weights. */
+typedef struct {
+    void *d_wq, *d_wk, *d_wv, *d_wo;
+} uoe_smha_weight_grads;
+
+/*
+ * Backward pass of uoe_smha_forward (the derivatives of Eq. 27-36, with the shared causal mask of
+ * Sec. III-C.3 when UOE_FLAG_CAUSAL is set; the selections of Eq. 17 and 22 are piecewise constant
+ * and pass no gradient).  Given d_out = dL/d(out) [b,l,d] and the forward inputs (w->wq/wk/wv/wo;
+ * the router members of w are ignored), writes, all in full:
+ *   d_x [b,l,d]            (d_out, with UOE_FLAG_RESIDUAL) + the gradients scattered back from every
+ *                          active expert that selected the token's patch; must not alias x or d_out
+ *   dw->d_wq/d_wk/d_wv [n,d,d_h], dw->d_wo [n,d_h,d]   zero for an expert no sample selected
+ *   d_expert_gate [b,n] fp32, d_patch_gate [b,n,m] fp32   dL/d(gate) for the active experts and
+ *                          their selected patches, zero elsewhere and when the matching flag is
+ *                          off; either may be NULL
+ * The forward intermediates are recomputed.  This build: bf16 storage, d_h in {32, 64, 128},
+ * d % 32 == 0, l_p % 32 == 0, b <= 128, rope_dim == 0, no padding mask; otherwise
+ * UOE_ERR_UNSUPPORTED.  Deterministic: fixed summation order, no atomics.  ws: at least
+ * uoe_smha_backward_workspace_bytes(blk) bytes (0 = descriptor invalid or unsupported).
+ */
+size_t uoe_smha_backward_workspace_bytes(const uoe_block_desc *blk);
+int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_weights *w,
+                      const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
+                      const float *patch_gate, const void *d_out, void *d_x,
+                      const uoe_smha_weight_grads *dw, float *d_expert_gate, float *d_patch_gate,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
 /* w_b [d,n] / w_a [l,m]: the UoME block's data-selection router (Eq. 13), both NULL for
  * expert selection only */
 typedef struct {

@@ -20,7 +20,8 @@ FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward",
            "uoe_smha_forward_masked",
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward",
-           "uoe_uome_backward_workspace_bytes", "uoe_uome_backward")
+           "uoe_uome_backward_workspace_bytes", "uoe_uome_backward",
+           "uoe_smha_backward_workspace_bytes", "uoe_smha_backward")
 
 
 class UoeError(RuntimeError):
@@ -43,6 +44,10 @@ class SmhaWeights(ctypes.Structure):
 
 class UomeWeights(ctypes.Structure):
     _fields_ = [(f, ctypes.c_void_p) for f in ("w_expert", "w_b", "w_a", "a_in", "a_out")]
+
+
+class SmhaWeightGrads(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_void_p) for f in ("d_wq", "d_wk", "d_wv", "d_wo")]
 
 
 class RoutingOut(ctypes.Structure):
@@ -75,13 +80,17 @@ def lib():
         L.uoe_uome_backward_workspace_bytes.argtypes = [D]
         L.uoe_uome_backward_workspace_bytes.restype = S
         L.uoe_uome_backward.argtypes = [D] + [P] * 10 + [P, S, P]
+        L.uoe_smha_backward_workspace_bytes.argtypes = [D]
+        L.uoe_smha_backward_workspace_bytes.restype = S
+        L.uoe_smha_backward.argtypes = [D, P, ctypes.POINTER(SmhaWeights), P, P, P, P, P, P,
+                                        ctypes.POINTER(SmhaWeightGrads), P, P, P, S, P]
         L.uoe_uome_up.argtypes = [D, P, P, P, P, P, P]
         L.uoe_uome_down.argtypes = [D, P, P, P, P, P, P]
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
         for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
-                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward"):
+                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -187,6 +196,23 @@ def uome_backward(blk, u, a_in, a_out, expert_idx, expert_gate, d_out, d_u, d_a_
                                  _ptr(d_out), _ptr(d_u), _ptr(d_a_in), _ptr(d_a_out), _ptr(d_gate), _ptr(ws),
                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_uome_backward", check)
+
+
+def smha_backward_workspace_bytes(blk) -> int:
+    return int(lib().uoe_smha_backward_workspace_bytes(_ref(blk)))
+
+
+def smha_weight_grads(d_wq, d_wk, d_wv, d_wo) -> SmhaWeightGrads:
+    return SmhaWeightGrads(*(_ptr(t) for t in (d_wq, d_wk, d_wv, d_wo)))
+
+
+def smha_backward(blk, x, w: SmhaWeights, expert_idx, expert_gate, patch_idx, patch_gate, d_out, d_x,
+                  dw: SmhaWeightGrads, d_expert_gate, d_patch_gate, ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_smha_backward(_ref(blk), _ptr(x), ctypes.byref(w), _ptr(expert_idx), _ptr(expert_gate),
+                                 _ptr(patch_idx), _ptr(patch_gate), _ptr(d_out), _ptr(d_x), ctypes.byref(dw),
+                                 _ptr(d_expert_gate), _ptr(d_patch_gate), _ptr(ws),
+                                 _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_smha_backward", check)
 
 
 def uome_up(blk, u, a_in, expert_idx, expert_gate, hidden, stream=None, check=True) -> int:

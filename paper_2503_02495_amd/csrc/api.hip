@@ -129,6 +129,44 @@ int check_uome_bwd(const uoe_block_desc *blk)
     return UOE_OK;
 }
 
+// backward pass of the SMHA block: the forward's scratch, then the backward's own
+struct SmhaBwdWs {
+    SmhaWs fwd;
+    size_t lse, rt, dd, wo_t, wqkv_t, do_raw, d_o, o_t, dqkv, dqkv_t, partial, total;
+};
+SmhaBwdWs smha_bwd_ws(const uoe_block_desc *d)
+{
+    SmhaBwdWs w;
+    w.fwd = smha_ws(d);
+    const size_t es = elem_size(d->dtype);
+    const size_t l_a = (size_t)d->c * (d->l / d->m), units = (size_t)d->b * d->k;
+    const size_t rows = up(units * l_a * sizeof(float)), one = up(units * l_a * d->width * es);
+    size_t off = w.fwd.total;
+    w.lse = off; off += rows;
+    w.rt = off; off += rows;
+    w.dd = off; off += rows;
+    w.wo_t = off; off += up((size_t)d->n * d->d * d->width * es);
+    w.wqkv_t = off; off += up(3 * (size_t)d->n * d->d * d->width * es);
+    w.do_raw = off; off += up(units * l_a * d->width * sizeof(float));
+    w.d_o = off; off += one;
+    w.o_t = off; off += one;
+    w.dqkv = off; off += 3 * one;
+    w.dqkv_t = off; off += 3 * one;
+    w.partial = off;
+    off += up((size_t)d->n * smha_backward_splits(d->b, d->n, d->k, d->c) * 3 * d->width * d->d * sizeof(float));
+    w.total = off;
+    return w;
+}
+int check_smha_bwd(const uoe_block_desc *blk)
+{
+    const int rc = check_desc(blk, DESC_SMHA);
+    if (rc != UOE_OK) return rc;
+    if (blk->dtype != UOE_BF16 || blk->rope_dim != 0) return UOE_ERR_UNSUPPORTED;
+    if (blk->width != 32 && blk->width != 64 && blk->width != 128) return UOE_ERR_UNSUPPORTED;
+    if (blk->d % 32 || (blk->l / blk->m) % 32 || blk->b > 128) return UOE_ERR_UNSUPPORTED;
+    return UOE_OK;
+}
+
 struct RoutingBuf {
     size_t expert_idx, expert_gate, patch_idx, patch_gate, total;
 };
@@ -390,6 +428,48 @@ int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in
     a.gchunks = uome_backward_gate_chunks(blk->l, blk->width);
     a.splits = uome_backward_splits(blk->b, blk->l, blk->d, blk->n, blk->k, blk->width);
     return launch_uome_backward(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+size_t uoe_smha_backward_workspace_bytes(const uoe_block_desc *blk)
+{
+    return check_smha_bwd(blk) == UOE_OK ? smha_bwd_ws(blk).total : 0;
+}
+
+int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_weights *w, const int32_t *expert_idx,
+                      const float *expert_gate, const int32_t *patch_idx, const float *patch_gate, const void *d_out,
+                      void *d_x, const uoe_smha_weight_grads *dw, float *d_expert_gate, float *d_patch_gate, void *ws,
+                      size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_smha_bwd(blk);
+    if (rc != UOE_OK) return rc;
+    if (!x || !w || !dw || !expert_idx || !patch_idx || !d_out || !d_x) return UOE_ERR_INVALID_ARG;
+    if (!w->wq || !w->wk || !w->wv || !w->wo || !dw->d_wq || !dw->d_wk || !dw->d_wv || !dw->d_wo) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_EXPERT) && !expert_gate) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_PATCH) && !patch_gate) return UOE_ERR_INVALID_ARG;
+    const void *ptrs[] = {x, w->wq, w->wk, w->wv, w->wo, d_out, d_x, dw->d_wq, dw->d_wk, dw->d_wv, dw->d_wo};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return UOE_ERR_INVALID_ARG;
+    if (d_x == x || d_x == d_out) return UOE_ERR_INVALID_ARG;
+    const SmhaBwdWs s = smha_bwd_ws(blk);
+    if (!ws || ws_bytes < s.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+
+    SmhaBwdArgs a{};
+    SmhaArgs &f = a.f;
+    f.x = x; f.wq = w->wq; f.wk = w->wk; f.wv = w->wv; f.wo = w->wo;
+    f.expert_idx = expert_idx; f.patch_idx = patch_idx;
+    f.b = blk->b; f.l = blk->l; f.d = blk->d; f.n = blk->n; f.k = blk->k; f.m = blk->m; f.c = blk->c;
+    f.d_h = blk->width; f.flags = blk->flags & UOE_FLAG_CAUSAL;  // the recomputed o carries no gate
+    f.q = at(ws, s.fwd.q); f.kk = at(ws, s.fwd.k); f.v = at(ws, s.fwd.v); f.o = at(ws, s.fwd.o); f.o_lo = at(ws, s.fwd.o_lo);
+    f.lse = reinterpret_cast<float *>(at(ws, s.lse));
+    a.d_out = d_out; a.expert_gate = expert_gate; a.patch_gate = patch_gate; a.flags = blk->flags;
+    a.d_x = d_x; a.d_wq = dw->d_wq; a.d_wk = dw->d_wk; a.d_wv = dw->d_wv; a.d_wo = dw->d_wo;
+    a.d_expert_gate = d_expert_gate; a.d_patch_gate = d_patch_gate;
+    a.wo_t = at(ws, s.wo_t); a.wqkv_t = at(ws, s.wqkv_t); a.do_raw = reinterpret_cast<float *>(at(ws, s.do_raw)); a.d_o = at(ws, s.d_o);
+    a.o_t = at(ws, s.o_t); a.dqkv = at(ws, s.dqkv); a.dqkv_t = at(ws, s.dqkv_t);
+    a.rt = reinterpret_cast<float *>(at(ws, s.rt)); a.dd = reinterpret_cast<float *>(at(ws, s.dd));
+    a.partial = reinterpret_cast<float *>(at(ws, s.partial));
+    a.splits = smha_backward_splits(blk->b, blk->n, blk->k, blk->c);
+    return launch_smha_backward(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
 }
 
 int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, const int32_t *expert_idx,

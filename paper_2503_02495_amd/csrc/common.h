@@ -99,6 +99,8 @@ struct SmhaArgs {
     // workspace
     void *q, *kk, *v, *o, *o_lo;              // [b*k, l_a, d_h] each, storage dtype (o_lo: low part of o, MFMA path)
     int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k]: which (slot s, pick t) chose patch p
+    float *lse;                               // [b*k, l_a] or NULL: base-2 log-sum-exp of each query's scaled logits
+                                              // (MFMA attention only; kept for the backward pass)
 };
 
 struct UomeArgs {
@@ -141,6 +143,25 @@ struct UomeBwdArgs {
     int gchunks, splits;
 };
 
+// Backward pass of the SMHA block (bf16 storage, MFMA shapes only)
+struct SmhaBwdArgs {
+    SmhaArgs f;                               // the forward call that is recomputed: no gates in f.flags, f.lse set
+    const void *d_out;                        // [b,l,d]
+    const float *expert_gate, *patch_gate;    // as in the forward call (NULL when the flag is off)
+    uint32_t flags;                           // the block's flags
+    void *d_x, *d_wq, *d_wk, *d_wv, *d_wo;    // [b,l,d], 3 x [n,d,d_h], [n,d_h,d], storage dtype
+    float *d_expert_gate, *d_patch_gate;      // [b,n], [b,n,m], or NULL
+    // workspace, storage dtype unless noted
+    void *wo_t, *wqkv_t;                      // [n, d, d_h], [n, 3*d_h, d]
+    float *do_raw;                            // [units, l_a, d_h] fp32
+    void *d_o;                                // [units, l_a, d_h]
+    void *o_t;                                // [units, d_h, l_a]
+    void *dqkv, *dqkv_t;                      // [units, l_a, 3*d_h], [units, 3*d_h, l_a]
+    float *rt, *dd;                           // [units, l_a] each: dL/dw_t and the softmax row term
+    float *partial;                           // [n*splits, 3*d_h, d] split tiles of a weight gradient
+    int splits;
+};
+
 struct GatherArgs {
     const void *x;
     const int32_t *expert_idx, *patch_idx;
@@ -152,11 +173,16 @@ struct GatherArgs {
 hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_gather(const GatherArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st);
+// Eq. 28-34 of the MFMA path only (projections, rotary embedding, attention into a.o / a.o_lo / a.lse);
+// the caller has checked bf16 storage, d % 32 == 0 and d_h in {32, 64, 128}
+hipError_t launch_smha_qkv_attention(const SmhaArgs &a, hipStream_t st);
 hipError_t launch_uome(const UomeArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome_up(const UomeArgs &a, bool bf16, hipStream_t st);    // Eq. 38 only
 hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // Eq. 39-40 only
 hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st);
+hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st);
+int smha_backward_splits(int b, int n, int k, int c);
 int uome_backward_gate_chunks(int l, int d_e);
 int uome_backward_splits(int b, int l, int d, int n, int k, int d_e);
 

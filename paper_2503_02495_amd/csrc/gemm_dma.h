@@ -303,4 +303,18 @@ static hipError_t launch_gemm_dma(const P &p, int groups, int max_rows, int ncol
     return hipGetLastError();
 }
 
+// Tile choice for contractions without a tuned rule of their own (the backward passes): the large
+// tile when it still gives 512 workgroups, short tiles when the launch would not fill the chip.
+template <typename P> static hipError_t launch_gemm_dma_auto(const P &p, int groups, int rows, int ncols, int kseg, hipStream_t st)
+{
+    const long tiles128 = (long)groups * ((rows + 127) / 128) * ((ncols + 127) / 128);
+    if (rows > 128 && (long)groups * ((rows + 255) / 256) * ((ncols + 127) / 128) >= 512)
+        return launch_gemm_dma<P, 256, 128, 32, 2, 2, 3, 2>(p, groups, rows, ncols, st);
+    if (tiles128 < 256 || rows <= 64)
+        return kseg % 64 == 0 ? launch_gemm_dma<P, 64, 128, 64, 2, 2, 3, 2>(p, groups, rows, ncols, st)
+                              : launch_gemm_dma<P, 64, 128, 32, 2, 2, 4, 2>(p, groups, rows, ncols, st);
+    return kseg % 64 == 0 ? launch_gemm_dma<P, 128, 128, 64, 2, 2, 2, 2>(p, groups, rows, ncols, st)
+                          : launch_gemm_dma<P, 128, 128, 32, 2, 2, 4, 2>(p, groups, rows, ncols, st);
+}
+
 }  // namespace uoe

@@ -47,16 +47,24 @@ __device__ __forceinline__ uint4 add8_bf16(uint4 v, uint4 r)
 // ---------------------------------------------------------------------------------------------
 // SMHA Eq. 28-30 with the index selection of Eq. 18 folded into the A-row lookup.
 // group = active unit (b, slot s); M = l_a; K = d; N = 3*d_h laid out [q | k | v].
-template <typename T> struct QkvProblem {
+// F32: the single-projection form (nout = 1) stores fp32 rows into q32 instead.
+template <typename T, bool F32 = false> struct QkvProblem {
     const T *x, *wq, *wk, *wv;
     const int32_t *expert_idx, *patch_idx;
     T *q, *k, *v;  // [units, l_a, d_h]
+    float *q32;    // [units, l_a, d_h] (F32 only)
+    static constexpr bool kF32Out = F32;
+    __device__ void put4_f32(int g, int r, int nn, float4 val) const
+    {
+        *reinterpret_cast<float4 *>(q32 + ((size_t)g * l_a + r) * d_h + nn) = val;
+    }
     int l, d, n, kact, m, c, l_p, l_a, d_h;
     float q_scale;  // folded into q on the way out (1 for the plain layout)
+    int nout;       // 3: q, k and v; 1: the first projection only (N = d_h)
 
     __device__ int rows(int) const { return l_a; }
     __device__ int kdim(int) const { return d; }
-    __device__ int ncols() const { return 3 * d_h; }
+    __device__ int ncols() const { return nout * d_h; }
     __device__ int expert(int g) const { return clampi(expert_idx[g], n); }
     __device__ int token(int g, int r) const
     {
@@ -404,22 +412,28 @@ template <typename T> struct WgradProblem {
     __device__ long b_stride() const { return right_stride; }
     __device__ int kdim(int) const { return 0; }  // prepare() supplies K
     static constexpr bool kPrepare = true;
+    // thread bb looks up which slot of sample bb (if any) holds the expert; the samples that do are
+    // listed in sample order (b <= 128 = the engine's segment table)
     __device__ int prepare(int g, uint32_t *segtab, int tid, int) const
     {
-        __shared__ int cnt_sh;
-        if (tid == 0) {  // b*k small integers, L2 resident: one thread lists the pairs in order
-            const int expert = g / splits;
-            int cnt = 0;
-            for (int bb = 0; bb < b && cnt < 128; ++bb)
-                for (int s = 0; s < kact; ++s)
-                    if (expert_idx[bb * kact + s] == expert) {
-                        segtab[cnt++] = ((uint32_t)bb << 8) | (uint32_t)s;
-                        break;  // an expert appears at most once in a sample's list
-                    }
-            cnt_sh = cnt;
+        __shared__ int slot_of[128];
+        const int expert = g / splits;
+        if (tid < b) {
+            int slot = -1;
+            for (int s = 0; s < kact; ++s)
+                if (expert_idx[tid * kact + s] == expert) slot = slot < 0 ? s : slot;
+            slot_of[tid] = slot;
         }
         __syncthreads();
-        return cnt_sh * (l / splits);
+        int before = 0, cnt = 0;
+        for (int bb = 0; bb < b; ++bb) {  // every thread counts: cnt is uniform
+            const bool has = slot_of[bb] >= 0;
+            before += (has && bb < tid) ? 1 : 0;
+            cnt += has ? 1 : 0;
+        }
+        if (tid < b && slot_of[tid] >= 0) segtab[before] = ((uint32_t)tid << 8) | (uint32_t)slot_of[tid];
+        __syncthreads();
+        return cnt * (l / splits);
     }
     __device__ uint32_t seg_ctx(int, int) const { return 0; }
     __device__ const T *a_ptr_ctx(int g, int r, int, uint32_t ctx) const
@@ -442,6 +456,85 @@ template <typename T> struct WgradProblem {
     __device__ void put4_f32(int g, int r, int nn, float4 v) const
     {
         *reinterpret_cast<float4 *>(partial + ((size_t)g * M + r) * N + nn) = v;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Weight gradients of the SMHA block: for expert i,
+//   dW[M, d] = sum over the units (b, slot s) of expert i and their c picks t of
+//              L^T[unit][M rows][tokens of pick t]  x  R[b][tokens of the picked patch][d]
+// i.e. the left factor is a per-unit tensor in token-minor layout [unit][M][l_a] and the right
+// factor is a [b, l, d] tensor (x or the upstream gradient) whose rows are gathered patch by patch
+// (Eq. 18), never copied.  K segments = (unit, pick) of l_p tokens, in (sample, pick) order; the
+// list is cut into `splits` consecutive parts, group = expert * splits + j stores the fp32 partial
+// tile [group][M][d] of part j.
+//   dW^O_i           [d_h, d]:   left = (gated o)^T [unit][d_h][l_a],        right = d_out
+//   [dWq|dWk|dWv]_i^T [3d_h, d]: left = [dq|dk|dv]^T [unit][3d_h][l_a],     right = x
+template <typename T> struct SmhaWgradProblem {
+    const T *left_t, *right;
+    const int32_t *expert_idx, *patch_idx;
+    float *partial;
+    int b, l, d, n, kact, m, c, l_p, l_a, splits;
+    int M;
+
+    static constexpr bool kF32Out = true;
+    __device__ int rows(int) const { return M; }
+    __device__ int ncols() const { return d; }
+    __device__ int kseg() const { return l_p; }
+    __device__ long b_stride() const { return d; }
+    __device__ int kdim(int) const { return 0; }
+    static constexpr bool kPrepare = true;
+    // context of a segment: sample in bits 0-6, slot in bits 7-11, pick in bits 12-21, patch in bits 22-31
+    __device__ int prepare(int g, uint32_t *segtab, int tid, int nthreads) const
+    {
+        __shared__ int slot_of[128];
+        const int expert = g / splits, part = g - expert * splits;
+        if (tid < b) {
+            int slot = -1;
+            for (int s = 0; s < kact; ++s)
+                if (expert_idx[tid * kact + s] == expert) slot = slot < 0 ? s : slot;
+            slot_of[tid] = slot;
+        }
+        __syncthreads();
+        int units = 0;
+        for (int bb = 0; bb < b; ++bb) units += slot_of[bb] >= 0 ? 1 : 0;
+        const int total = units * c, per = (total + splits - 1) / splits;
+        const int first = part * per, last = min(total, first + per);  // this part's segments
+        // thread (sample bb, pick t): its position in the full list is (units before bb) * c + t
+        for (int idx = tid; idx < b * c; idx += nthreads) {
+            const int bb = idx / c, t = idx - bb * c;
+            if (slot_of[bb] < 0) continue;
+            int before = 0;
+            for (int q = 0; q < bb; ++q) before += slot_of[q] >= 0 ? 1 : 0;
+            const int pos = before * c + t;
+            if (pos < first || pos >= last || pos - first >= 128) continue;
+            const int p = clampi(patch_idx[((size_t)bb * n + expert) * c + t], m);
+            segtab[pos - first] = (uint32_t)bb | ((uint32_t)slot_of[bb] << 7) | ((uint32_t)t << 12) | ((uint32_t)p << 22);
+        }
+        __syncthreads();
+        return max(0, min(last - first, 128)) * l_p;
+    }
+    __device__ uint32_t seg_ctx(int, int) const { return 0; }
+    __device__ const T *a_ptr_ctx(int, int r, int, uint32_t ctx) const
+    {
+        const int bb = (int)(ctx & 0x7Fu), s = (int)((ctx >> 7) & 0x1Fu), t = (int)((ctx >> 12) & 0x3FFu);
+        return left_t + (((size_t)bb * kact + s) * M + r) * l_a + (size_t)t * l_p;
+    }
+    __device__ const T *b_ptr_ctx(int, int, int nn, uint32_t ctx) const
+    {
+        const int bb = (int)(ctx & 0x7Fu), p = (int)(ctx >> 22);
+        return right + ((size_t)bb * l + (size_t)p * l_p) * d + nn;
+    }
+    static constexpr bool kRowScale = false;
+    static constexpr bool kColScale = false;
+    __device__ float col_scale(int, int) const { return 1.0f; }
+    __device__ float epi(float val, float) const { return val; }
+    __device__ bool has_residual() const { return false; }
+    __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
+    __device__ void put8(int, int, int, uint4) const {}
+    __device__ void put4_f32(int g, int r, int nn, float4 v) const
+    {
+        *reinterpret_cast<float4 *>(partial + ((size_t)g * M + r) * d + nn) = v;
     }
 };
 

@@ -363,6 +363,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
     if (qrow >= l_a) return;
     lsum += __shfl_xor(lsum, 32, 64);
     const float inv = lsum > 0.f ? w / lsum : 0.f;  // a row with no admissible key contributes nothing
+    if (a.lse && lh == 0) a.lse[(size_t)g * l_a + qrow] = lsum > 0.f ? mrun + log2f(lsum) : 0.f;
     bf16_t *o = static_cast<bf16_t *>(a.o) + ((size_t)g * l_a + qrow) * DH;
     bf16_t *o_lo = static_cast<bf16_t *>(a.o_lo) + ((size_t)g * l_a + qrow) * DH;
     // accumulator register q of tile td is head-dim index td*32 + (q/4)*8 + lh*4 + q%4.
@@ -419,6 +420,7 @@ template <typename T> static QkvProblem<T> make_qkv(const SmhaArgs &a)
     qp.l = a.l; qp.d = a.d; qp.n = a.n; qp.kact = a.k; qp.m = a.m; qp.c = a.c;
     qp.l_p = a.l / a.m; qp.l_a = a.c * qp.l_p; qp.d_h = a.d_h;
     qp.q_scale = 1.0f;
+    qp.nout = 3;
     return qp;
 }
 
@@ -462,18 +464,12 @@ template <typename OP> static hipError_t launch_outproj_dma(const OP &op, int gr
     return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, groups, l_p, d, st);
 }
 
-// MFMA path: bf16 storage, d and d_h multiples of 32 (the K segments of the two projections)
-static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
+// projections, rotary embedding and attention of the MFMA path
+static hipError_t smha_mfma_qkv_attention(const SmhaArgs &a, hipStream_t st)
 {
     typedef QkvProblem<bf16_t> QP;
-    typedef OutProjProblem<bf16_t> OP;
     const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
     hipError_t err;
-    // the pipelined out-projection finds each patch's segments itself; the other engines read the
-    // inverse map
-    const bool out_dma = (long)a.k * a.c < (1L << 20);
-    if (!out_dma && (err = launch_inverse_map(a, st)) != hipSuccess) return err;
-
     QP qp = make_qkv<bf16_t>(a);
     const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
     if (mfma_attn) qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);  // base-2 softmax in the MFMA kernel
@@ -497,8 +493,23 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     if (err != hipSuccess) return err;
     if ((err = launch_rope<bf16_t>(a, st)) != hipSuccess) return err;
 
-    err = mfma_attn ? launch_attention_mfma(a, st) : launch_attention_generic<bf16_t>(a, st);
-    if (err != hipSuccess) return err;
+    return mfma_attn ? launch_attention_mfma(a, st) : launch_attention_generic<bf16_t>(a, st);
+}
+
+hipError_t launch_smha_qkv_attention(const SmhaArgs &a, hipStream_t st) { return smha_mfma_qkv_attention(a, st); }
+
+// MFMA path: bf16 storage, d and d_h multiples of 32 (the K segments of the two projections)
+static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
+{
+    typedef OutProjProblem<bf16_t> OP;
+    const int l_p = a.l / a.m;
+    hipError_t err;
+    // the pipelined out-projection finds each patch's segments itself; the other engines read the
+    // inverse map
+    const bool out_dma = (long)a.k * a.c < (1L << 20);
+    if (!out_dma && (err = launch_inverse_map(a, st)) != hipSuccess) return err;
+    if ((err = smha_mfma_qkv_attention(a, st)) != hipSuccess) return err;
+    const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
 
     OP op = make_outproj<bf16_t>(a);
     if (mfma_attn) {  // the MFMA attention kernel writes o as a (hi, lo) bf16 pair

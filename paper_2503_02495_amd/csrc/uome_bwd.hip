@@ -20,6 +20,7 @@
 #include "problems.h"
 #include "gemm_mfma.h"
 #include "gemm_dma.h"
+#include "wgrad_reduce.h"
 
 namespace uoe {
 
@@ -120,30 +121,6 @@ __global__ __launch_bounds__(256) void uome_bwd_mid_kernel(UomeBwdArgs a)
     if (tid == 0) a.gpart[((size_t)bb * a.k + s) * a.gchunks + chunk * per_slot + (cb - s * per_slot)] = red[0];
 }
 
-// Adds the split-K partial tiles of a weight gradient in range order and stores the storage dtype,
-// as [n][M][N] or transposed as [n][N][M].  32x32 tiles through LDS.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *partial, uint16_t *dst, int M, int N, int splits,
-                                                           int transposed)
-{
-    __shared__ float tile[32][33];
-    const int e = blockIdx.z, r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    for (int i = ty; i < 32; i += 8) {
-        float v = 0.f;
-        if (r0 + i < M && c0 + tx < N)
-            for (int j = 0; j < splits; ++j) v += partial[(((size_t)e * splits + j) * M + r0 + i) * N + c0 + tx];
-        tile[i][tx] = v;
-    }
-    __syncthreads();
-    for (int i = ty; i < 32; i += 8) {
-        if (transposed) {
-            if (c0 + i < N && r0 + tx < M)
-                dst[((size_t)e * N + c0 + i) * M + r0 + tx] = (uint16_t)(pack2_bf16(tile[tx][i], 0.f) & 0xFFFFu);
-        } else if (r0 + i < M && c0 + tx < N)
-            dst[((size_t)e * M + r0 + i) * N + c0 + tx] = (uint16_t)(pack2_bf16(tile[i][tx], 0.f) & 0xFFFFu);
-    }
-}
-
 // d_gate [b,n]: block (slot s, sample b) adds the slot's partial sums (each thread a strided
 // subset in index order, then a fixed tree) into the entry of the slot's expert; the block of slot 0
 // also writes the zeros of the experts the sample did not select (all of them without the gate flag).
@@ -170,16 +147,6 @@ __global__ __launch_bounds__(256) void uome_bwd_gate_kernel(UomeBwdArgs a)
     if (tid == 0) a.d_gate[(size_t)bb * a.n + clampi(a.expert_idx[bb * a.k + s], a.n)] = red[0];
 }
 
-template <typename P> static hipError_t bwd_gemm(const P &p, int groups, int rows, int ncols, int kseg, hipStream_t st)
-{
-    const long tiles128 = (long)groups * ((rows + 127) / 128) * ((ncols + 127) / 128);
-    if (rows > 128 && (long)groups * ((rows + 255) / 256) * ((ncols + 127) / 128) >= 512)
-        return launch_gemm_dma<P, 256, 128, 32, 2, 2, 3, 2>(p, groups, rows, ncols, st);
-    if (kseg % 64 == 0 && tiles128 < 256) return launch_gemm_dma<P, 64, 128, 64, 2, 2, 3, 2>(p, groups, rows, ncols, st);
-    return kseg % 64 == 0 ? launch_gemm_dma<P, 128, 128, 64, 2, 2, 2, 2>(p, groups, rows, ncols, st)
-                          : launch_gemm_dma<P, 128, 128, 32, 2, 2, 4, 2>(p, groups, rows, ncols, st);
-}
-
 hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
 {
     typedef bf16_t T;
@@ -198,10 +165,10 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     zp.u = static_cast<const T *>(a.u); zp.a_in = static_cast<const T *>(a.a_in);
     zp.expert_idx = a.expert_idx; zp.expert_gate = nullptr; zp.hidden = static_cast<T *>(a.z);
     zp.l = a.l; zp.d = a.d; zp.n = a.n; zp.kact = a.k; zp.d_e = a.d_e; zp.raw = 1;
-    if ((err = bwd_gemm(zp, a.b, a.l, width, a.d, st)) != hipSuccess) return err;
+    if ((err = launch_gemm_dma_auto(zp, a.b, a.l, width, a.d, st)) != hipSuccess) return err;
     UomeUpProblem<T> hp = zp;  // dH = d_out W2_b^T: the same contraction with (A^O_i)^T [d, d_e] as the weight
     hp.u = static_cast<const T *>(a.d_out); hp.a_in = static_cast<const T *>(a.a_out_t); hp.hidden = static_cast<T *>(a.dh);
-    if ((err = bwd_gemm(hp, a.b, a.l, width, a.d, st)) != hipSuccess) return err;
+    if ((err = launch_gemm_dma_auto(hp, a.b, a.l, width, a.d, st)) != hipSuccess) return err;
 
     hipLaunchKernelGGL(uome_bwd_mid_kernel, dim3((a.l + 63) / 64, width / 32, a.b), dim3(256), 0, st, a);
     if ((err = hipGetLastError()) != hipSuccess) return err;
@@ -214,25 +181,24 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     up.hidden = static_cast<const T *>(a.dz); up.a_out = static_cast<const T *>(a.a_in_t);
     up.u = static_cast<const T *>(a.d_out); up.expert_idx = a.expert_idx; up.out = static_cast<T *>(a.d_u);
     up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e; up.flags = a.flags;
-    if ((err = bwd_gemm(up, a.b, a.l, a.d, a.d_e, st)) != hipSuccess) return err;
+    if ((err = launch_gemm_dma_auto(up, a.b, a.l, a.d, a.d_e, st)) != hipSuccess) return err;
 
     // weight gradients: [d_e, d] tiles per expert, token axis cut into a.splits ranges
-    const dim3 rgrid((a.d + 31) / 32, (a.d_e + 31) / 32, a.n);
+    WgradReduceArgs ra{};
+    ra.partial = a.partial; ra.M = a.d_e; ra.N = a.d; ra.splits = a.splits; ra.parts = 1;
     WgradProblem<T> wo;  // dA^O_i = sum H_{b,s}^T d_out_b
     wo.left_t = static_cast<const T *>(a.h_t); wo.right = static_cast<const T *>(a.d_out);
     wo.expert_idx = a.expert_idx; wo.partial = a.partial;
     wo.b = a.b; wo.l = a.l; wo.n = a.n; wo.kact = a.k; wo.splits = a.splits;
     wo.M = a.d_e; wo.N = a.d; wo.left_rows = width; wo.left_slot_rows = a.d_e; wo.right_stride = a.d;
-    if ((err = bwd_gemm(wo, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 0, st, a.partial, static_cast<uint16_t *>(a.d_a_out), a.d_e,
-                       a.d, a.splits, 0);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
+    if ((err = launch_gemm_dma_auto(wo, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
+    ra.dst[0] = static_cast<uint16_t *>(a.d_a_out); ra.transposed = 0;
+    if ((err = launch_wgrad_reduce(ra, a.n, st)) != hipSuccess) return err;
     WgradProblem<T> wi = wo;  // (dA^I_i)^T = sum dZ_{b,s}^T u_b, stored back as [d, d_e] by the reduction
     wi.left_t = static_cast<const T *>(a.dz_t); wi.right = static_cast<const T *>(a.u);
-    if ((err = bwd_gemm(wi, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 0, st, a.partial, static_cast<uint16_t *>(a.d_a_in), a.d_e,
-                       a.d, a.splits, 1);
-    return hipGetLastError();
+    if ((err = launch_gemm_dma_auto(wi, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
+    ra.dst[0] = static_cast<uint16_t *>(a.d_a_in); ra.transposed = 1;
+    return launch_wgrad_reduce(ra, a.n, st);
 }
 
 }  // namespace uoe

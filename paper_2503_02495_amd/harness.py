@@ -119,6 +119,28 @@ class DeviceLayer:
                         self.d_u, self.d_a_in, self.d_a_out, self.d_gate, self.bwd_ws)
         return self.d_u, self.d_a_in, self.d_a_out, self.d_gate
 
+    def smha_backward(self, d_out, expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None):
+        """Gradients of the SMHA block; returns (d_x, d_wq, d_wk, d_wv, d_wo, d_expert_gate, d_patch_gate)."""
+        if not hasattr(self, "smha_bwd_ws"):
+            nbytes = B.smha_backward_workspace_bytes(self.smha)
+            if nbytes == 0:
+                raise B.UoeError(B.ERR_UNSUPPORTED, "uoe_smha_backward_workspace_bytes")
+            self.smha_bwd_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self.d_x = torch.empty_like(self.x)
+            self.d_wq, self.d_wk, self.d_wv = (torch.empty_like(t) for t in (self.wq, self.wk, self.wv))
+            self.d_wo = torch.empty_like(self.wo)
+            cfg = self.cfg
+            self.d_a_expert_gate = torch.empty(cfg.b, cfg.n_a, dtype=torch.float32, device=self.device)
+            self.d_a_patch_gate = torch.empty(cfg.b, cfg.n_a, cfg.m, dtype=torch.float32, device=self.device)
+            self.smha_dw = B.smha_weight_grads(self.d_wq, self.d_wk, self.d_wv, self.d_wo)
+        B.smha_backward(self.smha, self.x, self.wa,
+                        self.a_expert_idx if expert_idx is None else expert_idx,
+                        self.a_expert_gate if expert_gate is None else expert_gate,
+                        self.a_patch_idx if patch_idx is None else patch_idx,
+                        self.a_patch_gate if patch_gate is None else patch_gate, d_out, self.d_x, self.smha_dw,
+                        self.d_a_expert_gate, self.d_a_patch_gate, self.smha_bwd_ws)
+        return self.d_x, self.d_wq, self.d_wk, self.d_wv, self.d_wo, self.d_a_expert_gate, self.d_a_patch_gate
+
     def layer_forward(self):
         B.layer_forward(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
                         self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws)

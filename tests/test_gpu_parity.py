@@ -280,6 +280,14 @@ def grad_err(y, r):
     return float(np.max(np.abs(y - r) / np.maximum(np.abs(r), rms)))
 
 
+def fro_err(y, r):
+    """||y - r|| / ||r||: the average error, which a wrong factor or a dropped term cannot hide in."""
+    r = np.asarray(r, np.float64)
+    y = np.asarray(y, np.float64)
+    nr = np.sqrt(np.sum(r * r))
+    return float(np.sqrt(np.sum((y - r) ** 2)) / nr) if nr > 0 else float(np.any(y))
+
+
 @pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["lm", "vit_bwd"])
 @pytest.mark.parametrize("flags", [0, R | GE])
 def test_uome_backward_parity(name, flags):
@@ -309,6 +317,9 @@ def test_uome_backward_parity(name, flags):
     assert not np.any(got_in[unused]) and not np.any(got_out[unused])
     errs = {"d_u": grad_err(to_host(d_u), want.d_u), "d_a_in": grad_err(got_in, want.d_a_in),
             "d_a_out": grad_err(got_out, want.d_a_out), "d_gate": grad_err(to_host(d_gate), want.d_gate)}
+    fro = max(fro_err(to_host(d_u), want.d_u), fro_err(got_in, want.d_a_in), fro_err(got_out, want.d_a_out),
+              fro_err(to_host(d_gate), want.d_gate))
+    assert fro <= 6e-3, fro
     print(f"[uome backward {name} flags={flags}] unused experts {unused.tolist()} " +
           " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {TOL[cfg.dtype]:.0e})", flush=True)
     assert max(errs.values()) <= TOL[cfg.dtype]
@@ -320,6 +331,65 @@ def test_uome_backward_rejects_unsupported():
     assert B.uome_backward_workspace_bytes(blk) == 0       # l % 32 != 0
     blk = B.block_desc(2, 64, 64, 2, 1, 1, 1, 32, B.F32, R)
     assert B.uome_backward_workspace_bytes(blk) == 0       # fp32 storage
+
+
+# --------------------------------------------------------------------------- SMHA backward
+SMHA_BWD_CONFIGS = {
+    # l_p = 32, l_a = 64: one key tile; an expert nobody selects (n = 5, b = 2, k = 2)
+    "sb_small": small(b=2, l=128, d=64, n_a=5, d_h=32, m=4, c=2, k_a=2, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
+    # l_p = 64, l_a = 128, d_h = 64, d not a multiple of 64
+    "sb_dh64": small(b=3, l=192, d=96, n_a=4, d_h=64, m=3, c=2, k_a=2, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
+    # l_a = 96: a ragged last key/query tile; d_h = 128; every patch selected by the one active expert or not at all
+    "sb_dh128_tail": small(b=2, l=160, d=64, n_a=2, d_h=128, m=5, c=3, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
+    # l_a = 320: several query blocks and key tiles per unit
+    "sb_long": small(b=2, l=512, d=64, n_a=3, d_h=32, m=8, c=5, k_a=2, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
+}
+CA = B.FLAG_CAUSAL
+# A gradient of the SMHA block passes through about eight bf16 roundings (q/k, v, the probabilities'
+# operands, dO, dS's operands, dq/dk/dv, the transposed copies, the output), each 2^-9/sqrt(3) = 1.1e-3
+# relative rms: 3.2e-3 in quadrature, which is what the Frobenius-relative error measures (2.8-3.7e-3
+# on every output, so no term is wrong by a factor: that would read 1e-2 or more).  The maximum over
+# 10^5-10^6 elements of such noise is 5-8 sigma (softmax turns absolute logit errors into relative
+# ones, which fattens the tail): 1.3-2.8e-2 measured, hence a bound of 4e-2 on the worst element
+# and of 6e-3 on the average.
+SMHA_BWD_TOL = 4e-2
+BWD_FRO_TOL = 6e-3
+
+
+@pytest.mark.parametrize("name", list(SMHA_BWD_CONFIGS) + ["lm"])
+@pytest.mark.parametrize("flags", [0, R | GE | GP, R | GE | GP | CA])
+def test_smha_backward_parity(name, flags):
+    """uoe_smha_backward against the oracle's chain rule (itself pinned by finite differences of
+    the forward oracle) on the same routing, inputs and upstream gradient; every gradient in full."""
+    cfg = SMHA_BWD_CONFIGS[name] if name in SMHA_BWD_CONFIGS else synth.CONFIGS[name]
+    w_std = 0.02 if name in synth.CONFIGS else 0.06
+    print(f"smha backward {name} flags={flags}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std)
+    d_out = synth.make_upstream_grad(cfg)
+    dev = DeviceLayer(inp, flags, R)
+    ref = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                       inp.noise_a_expert, inp.noise_a_patch)
+    ge, gp = ref.expert_gate.astype(np.float32), ref.patch_gate.astype(np.float32)
+    got = dev.smha_backward(to_device(d_out, cfg.dtype, dev.device),
+                            expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
+                            expert_gate=to_device(ge, synth.F32, dev.device),
+                            patch_idx=torch.from_numpy(ref.patch_id).to(dev.device),
+                            patch_gate=to_device(gp, synth.F32, dev.device))
+    torch.cuda.synchronize()
+    want = oracle.smha_backward(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ref.expert_id, ge, ref.patch_id, gp, cfg.m,
+                                d_out, flags)
+    names = ("d_x", "d_wq", "d_wk", "d_wv", "d_wo", "d_expert_gate", "d_patch_gate")
+    refs = (want.d_x, want.d_wq, want.d_wk, want.d_wv, want.d_wo, want.d_expert_gate, want.d_patch_gate)
+    errs = {nm: grad_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
+    fro = {nm: fro_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
+    print(f"[smha backward {name} flags={flags}] fro " + " ".join(f"{k} {v:.2e}" for k, v in fro.items()), flush=True)
+    unused = np.setdiff1d(np.arange(cfg.n_a), ref.expert_id.ravel())
+    for g in got[1:5]:
+        assert not np.any(to_host(g)[unused])
+    print(f"[smha backward {name} flags={flags}] unused experts {unused.tolist()} " +
+          " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {SMHA_BWD_TOL:.0e})", flush=True)
+    assert max(errs.values()) <= SMHA_BWD_TOL
+    assert max(fro.values()) <= BWD_FRO_TOL
 
 
 # --------------------------------------------------------------------------- single-mode SMHA blocks
