@@ -21,34 +21,42 @@
 
 namespace uoe {
 
-// [batch][rows][cols] -> [batch][cols][rows] with separate batch strides, 2-byte elements
-__global__ __launch_bounds__(256) void transpose_batched_kernel(const uint16_t *src, uint16_t *dst, int rows, int cols,
-                                                                long src_bs, long dst_bs)
+// Set-up in one launch.  Blocks z < 4n transpose one 32x32 tile of a weight (2-byte elements):
+// job 0 turns W^O_i [d_h, d] into [d, d_h]; jobs 1-3 turn W^q_i, W^k_i, W^v_i [d, d_h] into row
+// blocks of [3*d_h, d].  Blocks z == 4n clear the two gate-gradient outputs.
+struct SmhaBwdPrepArgs {
+    const uint16_t *w[4];  // wo, wq, wk, wv
+    uint16_t *wo_t, *wqkv_t;
+    float *zero[2];
+    long zero_count[2];
+    int n, d, d_h;
+};
+
+__global__ __launch_bounds__(256) void smha_bwd_prep_kernel(SmhaBwdPrepArgs a)
 {
     __shared__ uint16_t tile[32][33];
-    src += (size_t)blockIdx.z * src_bs;
-    dst += (size_t)blockIdx.z * dst_bs;
-    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int z = blockIdx.z;
+    if (z == 4 * a.n) {
+        const long at = ((long)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x, step = (long)gridDim.x * gridDim.y * 256;
+        for (int q = 0; q < 2; ++q)
+            if (a.zero[q])
+                for (long i = at; i < a.zero_count[q]; i += step) a.zero[q][i] = 0.f;
+        return;
+    }
+    const int job = z / a.n, e = z - job * a.n;
+    const int rows = job == 0 ? a.d_h : a.d, cols = job == 0 ? a.d : a.d_h;
+    // the grid covers the larger of the two tile counts in each direction
+    const int r0 = (job == 0 ? blockIdx.x : blockIdx.y) * 32, c0 = (job == 0 ? blockIdx.y : blockIdx.x) * 32;
+    if (r0 >= rows || c0 >= cols) return;
+    const uint16_t *src = a.w[job] + (size_t)e * a.d * a.d_h;
+    uint16_t *dst = job == 0 ? a.wo_t + (size_t)e * a.d * a.d_h
+                             : a.wqkv_t + (size_t)e * 3 * a.d * a.d_h + (size_t)(job - 1) * a.d * a.d_h;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int i = ty; i < 32; i += 8)
         if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[(size_t)(r0 + i) * cols + c0 + tx];
     __syncthreads();
     for (int i = ty; i < 32; i += 8)
         if (c0 + i < cols && r0 + tx < rows) dst[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
-}
-
-static hipError_t launch_transpose(const void *src, void *dst, int batch, int rows, int cols, long src_bs, long dst_bs,
-                                   hipStream_t st)
-{
-    hipLaunchKernelGGL(transpose_batched_kernel, dim3((cols + 31) / 32, (rows + 31) / 32, batch), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(src), static_cast<uint16_t *>(dst), rows, cols, src_bs, dst_bs);
-    return hipGetLastError();
-}
-
-__global__ __launch_bounds__(256) void fill_zero_kernel(float *p, long count)
-{
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i < count) p[i] = 0.f;
 }
 
 // Row pass between the out-projection gradient and the attention gradient.  Block = 32 rows of one
@@ -420,20 +428,15 @@ hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st)
     const int l_p = f.l / f.m, l_a = f.c * l_p, units = f.b * f.k, dh = f.d_h;
     hipError_t err;
 
-    // weights with K contiguous: W^O_i^T [d, d_h]; [W^q_i | W^k_i | W^v_i]^T [3*d_h, d]
-    if ((err = launch_transpose(f.wo, a.wo_t, f.n, dh, f.d, (long)dh * f.d, (long)dh * f.d, st)) != hipSuccess) return err;
-    const void *w3[3] = {f.wq, f.wk, f.wv};
-    for (int j = 0; j < 3; ++j)
-        if ((err = launch_transpose(w3[j], static_cast<T *>(a.wqkv_t) + (size_t)j * dh * f.d, f.n, f.d, dh, (long)dh * f.d,
-                                    3L * dh * f.d, st)) != hipSuccess)
-            return err;
-    if (a.d_expert_gate) {
-        hipLaunchKernelGGL(fill_zero_kernel, dim3((f.b * f.n + 255) / 256), dim3(256), 0, st, a.d_expert_gate, (long)f.b * f.n);
-        if ((err = hipGetLastError()) != hipSuccess) return err;
-    }
-    if (a.d_patch_gate) {
-        const long cnt = (long)f.b * f.n * f.m;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.d_patch_gate, cnt);
+    {   // weights with K contiguous, cleared gate outputs
+        SmhaBwdPrepArgs pa;
+        pa.w[0] = static_cast<const uint16_t *>(f.wo); pa.w[1] = static_cast<const uint16_t *>(f.wq);
+        pa.w[2] = static_cast<const uint16_t *>(f.wk); pa.w[3] = static_cast<const uint16_t *>(f.wv);
+        pa.wo_t = static_cast<uint16_t *>(a.wo_t); pa.wqkv_t = static_cast<uint16_t *>(a.wqkv_t);
+        pa.zero[0] = a.d_expert_gate; pa.zero_count[0] = (long)f.b * f.n;
+        pa.zero[1] = a.d_patch_gate; pa.zero_count[1] = (long)f.b * f.n * f.m;
+        pa.n = f.n; pa.d = f.d; pa.d_h = dh;
+        hipLaunchKernelGGL(smha_bwd_prep_kernel, dim3((dh + 31) / 32, (f.d + 31) / 32, 4 * f.n + 1), dim3(256), 0, st, pa);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
 

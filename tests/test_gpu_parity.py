@@ -270,14 +270,22 @@ BWD_CONFIGS = {
 
 
 def grad_err(y, r):
-    """max |y - r| / max(|r|, rms of r): a gradient tensor judged against its own magnitude."""
+    """max |y - r| / max(|r|, rms of r's slice): a gradient judged against the magnitude of the slice
+    of its leading index (one expert's weight gradient, one sample's rows): experts differ several
+    times in gradient magnitude (it scales with their gates and with how many samples chose them),
+    and an error belongs to the expert it was computed for.  All-zero slices must match exactly.
+    The floor never goes below 1e-30: with peaked gates (the noisy router of `large` gives experts
+    gates of 1e-19 ... 1e-40) a slice can sit at the bottom of bf16's exponent range, where the
+    format, not the kernel, decides its digits."""
     r = np.asarray(r, np.float64)
     y = np.asarray(y, np.float64)
-    rms = np.sqrt(np.mean(r * r))
-    if rms == 0.0:
-        assert not np.any(y)
+    r2, y2 = r.reshape(r.shape[0], -1), y.reshape(r.shape[0], -1)
+    rms = np.sqrt(np.mean(r2 * r2, axis=1, keepdims=True))
+    live = rms[:, 0] > 0
+    assert not np.any(y2[~live])
+    if not live.any():
         return 0.0
-    return float(np.max(np.abs(y - r) / np.maximum(np.abs(r), rms)))
+    return float(np.max(np.abs(y2[live] - r2[live]) / np.maximum(np.maximum(np.abs(r2[live]), rms[live]), 1e-30)))
 
 
 def fro_err(y, r):
@@ -347,17 +355,17 @@ SMHA_BWD_CONFIGS = {
 CA = B.FLAG_CAUSAL
 # A gradient of the SMHA block passes through about eight bf16 roundings (q/k, v, the probabilities'
 # operands, dO, dS's operands, dq/dk/dv, the transposed copies, the output), each 2^-9/sqrt(3) = 1.1e-3
-# relative rms: 3.2e-3 in quadrature, which is what the Frobenius-relative error measures (2.8-3.7e-3
+# relative rms: 3.2e-3 in quadrature, which is what the Frobenius-relative error measures (2.8-3.9e-3
 # on every output, so no term is wrong by a factor: that would read 1e-2 or more).  The maximum over
-# 10^5-10^6 elements of such noise is 5-8 sigma (softmax turns absolute logit errors into relative
-# ones, which fattens the tail): 1.3-2.8e-2 measured, hence a bound of 4e-2 on the worst element
-# and of 6e-3 on the average.
-SMHA_BWD_TOL = 4e-2
+# 10^5-10^6 elements of such noise is 5-7 sigma (softmax turns absolute logit errors into relative
+# ones, which fattens the tail): 1.0-2.1e-2 measured on the tensors and up to 2.6e-2 on the patch
+# gates, hence a bound of 3e-2 on the worst element and of 6e-3 on the average.
+SMHA_BWD_TOL = 3e-2
 BWD_FRO_TOL = 6e-3
 
 
-@pytest.mark.parametrize("name", list(SMHA_BWD_CONFIGS) + ["lm"])
-@pytest.mark.parametrize("flags", [0, R | GE | GP, R | GE | GP | CA])
+@pytest.mark.parametrize("name,flags", [(nm, fl) for nm in list(SMHA_BWD_CONFIGS) + ["lm"] for fl in (0, R | GE | GP, R | GE | GP | CA)]
+                         + [("longrange", R | GE | GP), ("large", R | GE | GP | CA)])
 def test_smha_backward_parity(name, flags):
     """uoe_smha_backward against the oracle's chain rule (itself pinned by finite differences of
     the forward oracle) on the same routing, inputs and upstream gradient; every gradient in full."""
