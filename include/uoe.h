@@ -223,7 +223,7 @@ typedef struct {
 
 /*
  * Backward pass of uoe_smha_forward (the derivatives of Eq. 27-36, with the shared causal mask of
- * Sec. III-C.3 when UOE_FLAG_CAUSAL is set; the selections of Eq. 17 and 22 are piecewise constant
+ * Sec. III-C.3 when UOE_FLAG_CAUSAL is set and the partial RoPE of Eq. 32 when rope_dim > 0; the selections of Eq. 17 and 22 are piecewise constant
  * and pass no gradient).  Given d_out = dL/d(out) [b,l,d] and the forward inputs (w->wq/wk/wv/wo;
  * the router members of w are ignored), writes, all in full:
  *   d_x [b,l,d]            (d_out, with UOE_FLAG_RESIDUAL) + the gradients scattered back from every
@@ -233,7 +233,7 @@ typedef struct {
  *                          their selected patches, zero elsewhere and when the matching flag is
  *                          off; either may be NULL
  * The forward intermediates are recomputed.  This build: bf16 storage, d_h in {32, 64, 128},
- * d % 32 == 0, l_p % 32 == 0, b <= 128, rope_dim == 0, no padding mask; otherwise
+ * d % 32 == 0, l_p % 32 == 0, b <= 128, no padding mask; otherwise
  * UOE_ERR_UNSUPPORTED.  Deterministic: fixed summation order, no atomics.  ws: at least
  * uoe_smha_backward_workspace_bytes(blk) bytes (0 = descriptor invalid or unsupported).
  */

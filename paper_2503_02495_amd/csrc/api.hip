@@ -161,7 +161,7 @@ int check_smha_bwd(const uoe_block_desc *blk)
 {
     const int rc = check_desc(blk, DESC_SMHA);
     if (rc != UOE_OK) return rc;
-    if (blk->dtype != UOE_BF16 || blk->rope_dim != 0) return UOE_ERR_UNSUPPORTED;
+    if (blk->dtype != UOE_BF16) return UOE_ERR_UNSUPPORTED;
     if (blk->width != 32 && blk->width != 64 && blk->width != 128) return UOE_ERR_UNSUPPORTED;
     if (blk->d % 32 || (blk->l / blk->m) % 32 || blk->b > 128) return UOE_ERR_UNSUPPORTED;
     return UOE_OK;
@@ -459,6 +459,7 @@ int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_w
     f.expert_idx = expert_idx; f.patch_idx = patch_idx;
     f.b = blk->b; f.l = blk->l; f.d = blk->d; f.n = blk->n; f.k = blk->k; f.m = blk->m; f.c = blk->c;
     f.d_h = blk->width; f.flags = blk->flags & UOE_FLAG_CAUSAL;  // the recomputed o carries no gate
+    f.rope_dim = blk->rope_dim;
     f.q = at(ws, s.fwd.q); f.kk = at(ws, s.fwd.k); f.v = at(ws, s.fwd.v); f.o = at(ws, s.fwd.o); f.o_lo = at(ws, s.fwd.o_lo);
     f.lse = reinterpret_cast<float *>(at(ws, s.lse));
     a.d_out = d_out; a.expert_gate = expert_gate; a.patch_gate = patch_gate; a.flags = blk->flags;

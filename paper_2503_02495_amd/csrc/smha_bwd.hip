@@ -153,6 +153,7 @@ struct AttnBwdArgs {
     float *dd;              // [units, l_a]: written by the query-owning kernel, read by the key-owning one
     bf16_t *dqkv, *dqkv_t;  // [units, l_a, 3*d_h], [units, 3*d_h, l_a]
     int l_a, causal;
+    int rope_dim;           // Eq. 32: dq and dk are rotated back (the transposed rotation) on the way out
 };
 
 template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void attention_bwd_kernel(AttnBwdArgs a)
@@ -367,14 +368,34 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
     const float scale_a = KV ? 0.6931471805599453f : rsqrtf((float)DH);
     bf16_t *row_out = a.dqkv + ((size_t)g * l_a + orow) * (3 * DH);
     bf16_t *col_out = a.dqkv_t + (size_t)g * (3 * DH) * l_a + orow;
+    // q and k were rotated in adjacent pairs (2i, 2i+1) of the last rope_dim dims, row r by r * theta_i;
+    // the gradient of the unrotated projection is the gradient rotated by -r * theta_i.  A lane's four
+    // consecutive head dims hold two whole pairs (rope_dim and d_h are even).
+    const int rope_first = DH - a.rope_dim;
     auto put = [&](const f32x16_t (&acc)[DH / 32], int block, float scale) {
 #pragma unroll
         for (int td = 0; td < DH / 32; ++td)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const int dh0 = td * 32 + i4 * 8 + lh * 4;
-                const uint32_t w0 = pack2_bf16(acc[td][i4 * 4 + 0] * scale, acc[td][i4 * 4 + 1] * scale);
-                const uint32_t w1 = pack2_bf16(acc[td][i4 * 4 + 2] * scale, acc[td][i4 * 4 + 3] * scale);
+                float v[4] = {acc[td][i4 * 4 + 0] * scale, acc[td][i4 * 4 + 1] * scale, acc[td][i4 * 4 + 2] * scale,
+                              acc[td][i4 * 4 + 3] * scale};
+                if (block < 2 && a.rope_dim > 0) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int dh = dh0 + 2 * h;
+                        if (dh >= rope_first) {
+                            const float theta = exp2f(-((float)(dh - rope_first) / (float)a.rope_dim) * 13.287712379549449f);
+                            float sn, cs;
+                            sincosf((float)orow * theta, &sn, &cs);
+                            const float ga = v[2 * h], gb = v[2 * h + 1];
+                            v[2 * h] = ga * cs + gb * sn;
+                            v[2 * h + 1] = gb * cs - ga * sn;
+                        }
+                    }
+                }
+                const uint32_t w0 = pack2_bf16(v[0], v[1]);
+                const uint32_t w1 = pack2_bf16(v[2], v[3]);
                 *reinterpret_cast<uint2 *>(row_out + block * DH + dh0) = make_uint2(w0, w1);
                 uint16_t *ct = reinterpret_cast<uint16_t *>(col_out) + (size_t)(block * DH + dh0) * l_a;
                 ct[0] = (uint16_t)(w0 & 0xFFFFu);
@@ -468,7 +489,7 @@ hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st)
     ab.q = static_cast<const T *>(f.q); ab.k = static_cast<const T *>(f.kk); ab.v = static_cast<const T *>(f.v);
     ab.d_o = static_cast<const T *>(a.d_o); ab.lse = f.lse; ab.dd = a.dd;
     ab.dqkv = static_cast<T *>(a.dqkv); ab.dqkv_t = static_cast<T *>(a.dqkv_t);
-    ab.l_a = l_a; ab.causal = (f.flags & F_CAUSAL) ? 1 : 0;
+    ab.l_a = l_a; ab.causal = (f.flags & F_CAUSAL) ? 1 : 0; ab.rope_dim = f.rope_dim;
     err = dh == 32 ? launch_attention_bwd_dh<32>(ab, units, st)
                    : (dh == 64 ? launch_attention_bwd_dh<64>(ab, units, st) : launch_attention_bwd_dh<128>(ab, units, st));
     if (err != hipSuccess) return err;

@@ -280,7 +280,9 @@ def grad_err(y, r):
     r = np.asarray(r, np.float64)
     y = np.asarray(y, np.float64)
     r2, y2 = r.reshape(r.shape[0], -1), y.reshape(r.shape[0], -1)
-    rms = np.sqrt(np.mean(r2 * r2, axis=1, keepdims=True))
+    # rms over the entries that are not structurally zero (gate gradients of unselected experts and
+    # patches, rows of unselected patches without the residual)
+    rms = np.sqrt(np.sum(r2 * r2, axis=1, keepdims=True) / np.maximum(np.count_nonzero(r2, axis=1)[:, None], 1))
     live = rms[:, 0] > 0
     assert not np.any(y2[~live])
     if not live.any():
@@ -367,14 +369,24 @@ BWD_FRO_TOL = 6e-3
 @pytest.mark.parametrize("name,flags", [(nm, fl) for nm in list(SMHA_BWD_CONFIGS) + ["lm"] for fl in (0, R | GE | GP, R | GE | GP | CA)]
                          + [("longrange", R | GE | GP), ("large", R | GE | GP | CA)])
 def test_smha_backward_parity(name, flags):
+    run_smha_backward(name, flags, 0)
+
+
+@pytest.mark.parametrize("name,rope_dim", [("sb_small", 32), ("sb_dh64", 16), ("sb_dh128_tail", 64), ("lm", 32)])
+def test_smha_backward_parity_rope_causal(name, rope_dim):
+    """The LM setting: shared causal mask and partial RoPE (the rotation is undone on dq and dk)."""
+    run_smha_backward(name, R | GE | GP | CA, rope_dim)
+
+
+def run_smha_backward(name, flags, rope_dim):
     """uoe_smha_backward against the oracle's chain rule (itself pinned by finite differences of
     the forward oracle) on the same routing, inputs and upstream gradient; every gradient in full."""
     cfg = SMHA_BWD_CONFIGS[name] if name in SMHA_BWD_CONFIGS else synth.CONFIGS[name]
     w_std = 0.02 if name in synth.CONFIGS else 0.06
-    print(f"smha backward {name} flags={flags}", flush=True)
+    print(f"smha backward {name} flags={flags} rope_dim={rope_dim}", flush=True)
     inp = synth.make_inputs(cfg, w_std=w_std)
     d_out = synth.make_upstream_grad(cfg)
-    dev = DeviceLayer(inp, flags, R)
+    dev = DeviceLayer(inp, flags, R, rope_dim=rope_dim)
     ref = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
                        inp.noise_a_expert, inp.noise_a_patch)
     ge, gp = ref.expert_gate.astype(np.float32), ref.patch_gate.astype(np.float32)
@@ -385,7 +397,7 @@ def test_smha_backward_parity(name, flags):
                             patch_gate=to_device(gp, synth.F32, dev.device))
     torch.cuda.synchronize()
     want = oracle.smha_backward(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ref.expert_id, ge, ref.patch_id, gp, cfg.m,
-                                d_out, flags)
+                                d_out, flags, rope_dim)
     names = ("d_x", "d_wq", "d_wk", "d_wv", "d_wo", "d_expert_gate", "d_patch_gate")
     refs = (want.d_x, want.d_wq, want.d_wk, want.d_wv, want.d_wo, want.d_expert_gate, want.d_patch_gate)
     errs = {nm: grad_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
