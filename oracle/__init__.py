@@ -203,6 +203,46 @@ def route(x, n: int, k: int, m: int, c: int, w_expert=None, w_b=None, w_a=None,
 
 
 @dataclass
+class RouteGrads:
+    d_x: np.ndarray            # [b,l,d]   the routers' contribution only
+    d_w_expert: Optional[np.ndarray]   # [n, l*d]
+    d_w_b: Optional[np.ndarray]        # [d,n]
+    d_w_a: Optional[np.ndarray]        # [l,m]
+
+
+def route_backward(x, w_expert, w_b, w_a, expert_gate, patch_gate_, d_expert_gate, d_patch_gate) -> RouteGrads:
+    """Gradients of the two routers (Eq. 21 and Eq. 13-14) for given gradients of their gates.
+
+    Expert router: z = W_E vec(x) (+ noise), g = softmax over the n experts; data router:
+    g'[i,j] = sum_t (x W_B)[t,i] W_A[t,j] (+ noise), gate = softmax over the experts for each patch.
+    The noise is additive and the top-k / top-c selections are piecewise constant, so neither
+    appears here; the gates are passed in as the forward computed them.  A router that is absent
+    (weights None) contributes nothing."""
+    x = _f64(x)
+    b, l, d = x.shape
+    d_x = np.zeros_like(x)
+    d_we = d_wb = d_wa = None
+    if w_expert is not None:
+        w_e, g, d_g = _f64(w_expert), _f64(expert_gate), _f64(d_expert_gate)
+        d_z = g * (d_g - np.sum(g * d_g, axis=1, keepdims=True))        # softmax over experts
+        xf = x.reshape(b, l * d)
+        d_we = d_z.T @ xf
+        d_x += (d_z @ w_e).reshape(b, l, d)
+    if w_b is not None:
+        w_b, w_a = _f64(w_b), _f64(w_a)
+        pg, d_pg = _f64(patch_gate_), _f64(d_patch_gate)                # [b,n,m]
+        d_l = pg * (d_pg - np.sum(pg * d_pg, axis=1, keepdims=True))    # softmax over experts, per patch
+        d_wb, d_wa = np.zeros_like(w_b), np.zeros_like(w_a)
+        for bb in range(b):
+            t1 = x[bb] @ w_b                                            # FFN_B(x): [l,n]
+            d_wa += t1 @ d_l[bb]                                        # [l,n] [n,m]
+            d_t1 = w_a @ d_l[bb].T                                      # [l,m] [m,n]
+            d_wb += x[bb].T @ d_t1
+            d_x[bb] += d_t1 @ w_b.T
+    return RouteGrads(d_x, d_we, d_wb, d_wa)
+
+
+@dataclass
 class Capacity:
     capacity: np.ndarray      # [b] int32, Eq. 16
     count: np.ndarray         # [b,n] int32: patches that put expert i among their top-k (Eq. 15)
