@@ -216,6 +216,27 @@ typedef struct {
     const void *w_expert, *w_b, *w_a, *wq, *wk, *wv, *wo;
 } uoe_smha_weights;
 
+/*
+ * Backward pass of uoe_route (the derivatives of the expert router, Eq. 21, and of the data
+ * router, Eq. 13-14; the additive noise and the top-k / top-c selections pass no gradient).
+ * Given the gates the forward call returned and their gradients (as the block backward calls
+ * return them), writes the router weight gradients in full and ADDS the routers' share of the
+ * input gradient to d_x, which is read, updated and written in place:
+ *   d_w_expert [n, l*d] = dz^T vec(x),  dz = g * (dg - sum_i g_i dg_i);   d_x += dz W_E
+ *   d_w_a [l,m] = sum_b (x W_B) dL,  d_w_b [d,n] = sum_b x^T (W_A dL^T),  d_x += W_A dL^T W_B^T,
+ *   dL = gate * (dgate - sum over experts of gate * dgate) per patch
+ * A router whose weights are NULL is skipped (its gate and gradient pointers are ignored); at
+ * least one must be present; w_b and w_a come together.  Storage dtype fp32 or bf16, fp32
+ * arithmetic.  Limits of this build: b <= 128, d <= 2048, (n*m + 64*n) * 4 + d*n*elem <= 64 KiB.
+ * ws: at least uoe_route_backward_workspace_bytes(blk) bytes (0 = invalid or unsupported).
+ */
+size_t uoe_route_backward_workspace_bytes(const uoe_block_desc *blk);
+int uoe_route_backward(const uoe_block_desc *blk, const void *x, const void *w_expert,
+                       const void *w_b, const void *w_a, const float *expert_gate,
+                       const float *patch_gate, const float *d_expert_gate,
+                       const float *d_patch_gate, void *d_x, void *d_w_expert, void *d_w_b,
+                       void *d_w_a, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Gradients of the four SMHA weight tensors, shaped like the weights. */
 typedef struct {
     void *d_wq, *d_wk, *d_wv, *d_wo;

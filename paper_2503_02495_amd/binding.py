@@ -21,7 +21,8 @@ EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_c
            "uoe_smha_forward_masked",
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward",
            "uoe_uome_backward_workspace_bytes", "uoe_uome_backward",
-           "uoe_smha_backward_workspace_bytes", "uoe_smha_backward")
+           "uoe_smha_backward_workspace_bytes", "uoe_smha_backward",
+           "uoe_route_backward_workspace_bytes", "uoe_route_backward")
 
 
 class UoeError(RuntimeError):
@@ -84,13 +85,16 @@ def lib():
         L.uoe_smha_backward_workspace_bytes.restype = S
         L.uoe_smha_backward.argtypes = [D, P, ctypes.POINTER(SmhaWeights), P, P, P, P, P, P,
                                         ctypes.POINTER(SmhaWeightGrads), P, P, P, S, P]
+        L.uoe_route_backward_workspace_bytes.argtypes = [D]
+        L.uoe_route_backward_workspace_bytes.restype = S
+        L.uoe_route_backward.argtypes = [D] + [P] * 12 + [P, S, P]
         L.uoe_uome_up.argtypes = [D, P, P, P, P, P, P]
         L.uoe_uome_down.argtypes = [D, P, P, P, P, P, P]
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
         for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
-                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward"):
+                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward", "uoe_route_backward"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -213,6 +217,19 @@ def smha_backward(blk, x, w: SmhaWeights, expert_idx, expert_gate, patch_idx, pa
                                  _ptr(d_expert_gate), _ptr(d_patch_gate), _ptr(ws),
                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_smha_backward", check)
+
+
+def route_backward_workspace_bytes(blk) -> int:
+    return int(lib().uoe_route_backward_workspace_bytes(_ref(blk)))
+
+
+def route_backward(blk, x, w_expert, w_b, w_a, expert_gate, patch_gate, d_expert_gate, d_patch_gate, d_x,
+                   d_w_expert, d_w_b, d_w_a, ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_route_backward(_ref(blk), _ptr(x), _ptr(w_expert), _ptr(w_b), _ptr(w_a), _ptr(expert_gate),
+                                  _ptr(patch_gate), _ptr(d_expert_gate), _ptr(d_patch_gate), _ptr(d_x),
+                                  _ptr(d_w_expert), _ptr(d_w_b), _ptr(d_w_a), _ptr(ws),
+                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_route_backward", check)
 
 
 def uome_up(blk, u, a_in, expert_idx, expert_gate, hidden, stream=None, check=True) -> int:

@@ -167,6 +167,36 @@ int check_smha_bwd(const uoe_block_desc *blk)
     return UOE_OK;
 }
 
+// backward pass of the routers
+struct RouteBwdWs {
+    size_t dz, dl, t1, u, wb_part, total;
+    int wb_tokens, wb_chunks;
+};
+RouteBwdWs route_bwd_ws(const uoe_block_desc *d)
+{
+    RouteBwdWs w;
+    w.wb_tokens = 256;
+    w.wb_chunks = (int)(((size_t)d->b * d->l + w.wb_tokens - 1) / w.wb_tokens);
+    size_t off = 0;
+    w.dz = off; off += up((size_t)d->b * d->n * sizeof(float));
+    w.dl = off; off += up((size_t)d->b * d->n * d->m * sizeof(float));
+    w.t1 = off; off += up((size_t)d->b * d->l * d->n * sizeof(float));
+    w.u = off; off += up((size_t)d->b * d->l * d->n * sizeof(float));
+    w.wb_part = off; off += up((size_t)w.wb_chunks * (256 / (d->d / 8)) * d->d * d->n * sizeof(float));
+    w.total = off;
+    return w;
+}
+int check_route_bwd(const uoe_block_desc *blk)
+{
+    const int rc = check_desc(blk, DESC_ROUTE);
+    if (rc != UOE_OK) return rc;
+    if (blk->b > 128 || blk->d > 2048) return UOE_ERR_UNSUPPORTED;
+    // the data router's per-token kernel stages dL [n,m], U [64,n] and W_B [d,n] in LDS
+    const size_t lds = ((size_t)blk->n * blk->m + 64 * (size_t)blk->n) * sizeof(float) + (size_t)blk->d * blk->n * elem_size(blk->dtype);
+    if (lds > 64 * 1024) return UOE_ERR_UNSUPPORTED;
+    return UOE_OK;
+}
+
 struct RoutingBuf {
     size_t expert_idx, expert_gate, patch_idx, patch_gate, total;
 };
@@ -471,6 +501,40 @@ int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_w
     a.partial = reinterpret_cast<float *>(at(ws, s.partial));
     a.splits = smha_backward_splits(blk->b, blk->n, blk->k, blk->c);
     return launch_smha_backward(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+size_t uoe_route_backward_workspace_bytes(const uoe_block_desc *blk)
+{
+    return check_route_bwd(blk) == UOE_OK ? route_bwd_ws(blk).total : 0;
+}
+
+int uoe_route_backward(const uoe_block_desc *blk, const void *x, const void *w_expert, const void *w_b, const void *w_a,
+                       const float *expert_gate, const float *patch_gate, const float *d_expert_gate,
+                       const float *d_patch_gate, void *d_x, void *d_w_expert, void *d_w_b, void *d_w_a, void *ws,
+                       size_t ws_bytes, void *hip_stream)
+{
+    const int rc = check_route_bwd(blk);
+    if (rc != UOE_OK) return rc;
+    if (!x || !d_x || d_x == x || (!w_expert && !w_b)) return UOE_ERR_INVALID_ARG;
+    if ((w_b == nullptr) != (w_a == nullptr)) return UOE_ERR_INVALID_ARG;
+    if (w_expert && (!expert_gate || !d_expert_gate || !d_w_expert)) return UOE_ERR_INVALID_ARG;
+    if (w_b && (!patch_gate || !d_patch_gate || !d_w_b || !d_w_a)) return UOE_ERR_INVALID_ARG;
+    const void *ptrs[] = {x, d_x, w_expert, w_b, w_a, d_w_expert, d_w_b, d_w_a};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return UOE_ERR_INVALID_ARG;
+    const RouteBwdWs w = route_bwd_ws(blk);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+    RouteBwdArgs a{};
+    a.x = x; a.w_e = w_expert; a.w_b = w_b; a.w_a = w_a;
+    a.g_e = expert_gate; a.g_p = patch_gate; a.d_g_e = d_expert_gate; a.d_g_p = d_patch_gate;
+    a.d_x = d_x; a.d_w_e = d_w_expert; a.d_w_b = d_w_b; a.d_w_a = d_w_a;
+    a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.m = blk->m;
+    a.dz = reinterpret_cast<float *>(at(ws, w.dz)); a.dl = reinterpret_cast<float *>(at(ws, w.dl));
+    a.t1 = reinterpret_cast<float *>(at(ws, w.t1)); a.u = reinterpret_cast<float *>(at(ws, w.u));
+    a.wb_part = reinterpret_cast<float *>(at(ws, w.wb_part));
+    a.wb_tokens = w.wb_tokens; a.wb_chunks = w.wb_chunks;
+    return launch_route_backward(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? UOE_OK : UOE_ERR_DEVICE;
 }
 
 int uoe_uome_up(const uoe_block_desc *blk, const void *u, const void *a_in, const int32_t *expert_idx,

@@ -162,6 +162,21 @@ struct SmhaBwdArgs {
     int splits;
 };
 
+// Backward pass of the routers of one block
+struct RouteBwdArgs {
+    const void *x, *w_e, *w_b, *w_a;          // w_e NULL: no expert router; w_b NULL: no data router
+    const float *g_e, *g_p;                   // gates of the forward pass [b,n], [b,n,m]
+    const float *d_g_e, *d_g_p;               // their gradients
+    void *d_x;                                // [b,l,d] in/out: the routers' contribution is added
+    void *d_w_e, *d_w_b, *d_w_a;              // [n,l*d], [d,n], [l,m], storage dtype
+    int b, l, d, n, m;
+    // workspace (fp32)
+    float *dz, *dl;                           // [b,n], [b,n,m]: gradients of the router logits
+    float *t1, *u;                            // [b,l,n] each: x W_B and W_A dL^T
+    float *wb_part;                           // [wb_chunks * (256 / (d/8)), d, n] partial sums of dW_B
+    int wb_tokens, wb_chunks;                 // tokens per chunk, chunks over the b*l tokens
+};
+
 struct GatherArgs {
     const void *x;
     const int32_t *expert_idx, *patch_idx;
@@ -182,6 +197,7 @@ hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // E
 hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st);
 hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st);
+hipError_t launch_route_backward(const RouteBwdArgs &a, bool bf16, hipStream_t st);
 int smha_backward_splits(int b, int n, int k, int c);
 int uome_backward_gate_chunks(int l, int d_e);
 int uome_backward_splits(int b, int l, int d, int n, int k, int d_e);

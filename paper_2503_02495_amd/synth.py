@@ -174,6 +174,14 @@ def make_upstream_grad(cfg: LayerConfig, seed: Optional[int] = None) -> np.ndarr
     return _draw(rng, (cfg.b, cfg.l, cfg.d), 1.0, cfg.dtype)
 
 
+def make_gate_grads(cfg: LayerConfig, n: int, m: int, seed: Optional[int] = None):
+    """Synthetic gradients of a block's gates, (d_expert_gate [b,n], d_patch_gate [b,n,m]) float32,
+    for the router backward tests: unit normal, from a stream of their own."""
+    rng = np.random.default_rng((cfg.seed if seed is None else seed) + 104729)
+    return (rng.standard_normal(size=(cfg.b, n), dtype=np.float32),
+            rng.standard_normal(size=(cfg.b, n, m), dtype=np.float32))
+
+
 def small_config(name: str = "small", **kw) -> LayerConfig:
     """A config with every size overridable, for randomly drawn tiny shapes in tests."""
     base = dict(b=2, l=24, d=16, n_a=3, d_h=8, m=4, c=2, k_a=2, n_m=3, d_e=8, k_m=2,

@@ -412,6 +412,45 @@ def run_smha_backward(name, flags, rope_dim):
     assert max(fro.values()) <= BWD_FRO_TOL
 
 
+# --------------------------------------------------------------------------- router backward
+@pytest.mark.parametrize("name", ["tiny", "ragged_lp14", "bf16_noise", "bf16_n32", "bf16_b40", "lm", "longrange", "vit", "large"])
+def test_route_backward_parity(name):
+    """uoe_route_backward on the SMHA block's routers against the oracle (pinned by finite
+    differences of the forward routers): weight gradients in full, and the in-place update of d_x."""
+    cfg = get_cfg(name)
+    print(f"route backward {name}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    # The synthetic W_E (std 0.02 over l*d inputs) gives logits of std 0.02*sqrt(l*d), up to 20: gates
+    # that are one-hot to 1e-10, where a softmax passes no gradient and what is left of it is
+    # decided by the last bit of the fp32 gates (relative error 6e-8 / (1 - g_max) whatever the
+    # kernel does).  The backward test scales W_E by a power of two (exact in bf16) to logits of
+    # std <= 1, the regime in which a router trains.
+    ld_std = w_std_for(name) * np.sqrt(cfg.l * cfg.d)
+    if ld_std > 1.0:
+        inp.a_w_expert = inp.a_w_expert * np.float32(2.0 ** -np.ceil(np.log2(ld_std)))
+    ref = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                       inp.noise_a_expert, inp.noise_a_patch)
+    ge, gp = ref.expert_gate.astype(np.float32), ref.patch_gate.astype(np.float32)
+    d_ge, d_gp = synth.make_gate_grads(cfg, cfg.n_a, cfg.m)
+    d_x0 = synth.make_upstream_grad(cfg)
+    dev = DeviceLayer(inp, R, R)
+    f32 = lambda a: to_device(a, synth.F32, dev.device)
+    d_x = to_device(d_x0, cfg.dtype, dev.device)
+    d_we, d_wb, d_wa = (torch.empty_like(t) for t in (dev.a_w_expert, dev.a_w_b, dev.a_w_a))
+    ws = torch.empty(B.route_backward_workspace_bytes(dev.smha), dtype=torch.uint8, device=dev.device)
+    B.route_backward(dev.smha, dev.x, dev.a_w_expert, dev.a_w_b, dev.a_w_a, f32(ge), f32(gp), f32(d_ge), f32(d_gp),
+                     d_x, d_we, d_wb, d_wa, ws)
+    torch.cuda.synchronize()
+    want = oracle.route_backward(inp.x, inp.a_w_expert, inp.a_w_b, inp.a_w_a, ge, gp, d_ge, d_gp)
+    errs = {"d_x": scaled_err(to_host(d_x), d_x0.astype(np.float64) + want.d_x),
+            "d_w_expert": grad_err(to_host(d_we), want.d_w_expert),
+            "d_w_b": grad_err(to_host(d_wb).T, want.d_w_b.T),      # slices = experts
+            "d_w_a": grad_err(to_host(d_wa).T, want.d_w_a.T)}      # slices = patches
+    print(f"[route backward {name}] " + " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {TOL[cfg.dtype]:.0e})",
+          flush=True)
+    assert max(errs.values()) <= TOL[cfg.dtype]
+
+
 # --------------------------------------------------------------------------- single-mode SMHA blocks
 @pytest.mark.parametrize("mode", ["expert_only", "data_only"])
 @pytest.mark.parametrize("name", ["bf16_ragged", "lm"])
