@@ -67,6 +67,23 @@ def run_stage(args, cfg, dev, B, torch) -> int:
         from paper_2503_02495_amd.harness import to_device
         d_out_a = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
         calls["smha_bwd"] = lambda: dev.smha_backward(d_out_a)
+    if args.stage in ("layer_bwd", "layer_fwd_bwd", "route_bwd"):
+        from paper_2503_02495_amd import synth
+        from paper_2503_02495_amd.harness import to_device
+        d_out_l = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
+        calls["layer_bwd"] = lambda: dev.layer_backward(d_out_l, u=dev.u)      # u kept from the forward pass
+
+        def fwd_bwd():
+            dev.layer_forward()
+            dev.layer_backward(d_out_l)                                         # u recomputed (the layer call keeps it private)
+        calls["layer_fwd_bwd"] = fwd_bwd
+        if args.stage == "route_bwd":
+            d_ge, d_gp = (to_device(t, synth.F32, dev.device) for t in synth.make_gate_grads(cfg, cfg.n_a, cfg.m))
+            d_x = torch.empty_like(dev.x).copy_(d_out_l)
+            grads = [torch.empty_like(t) for t in (dev.a_w_expert, dev.a_w_b, dev.a_w_a)]
+            ws = torch.empty(B.route_backward_workspace_bytes(dev.smha), dtype=torch.uint8, device=dev.device)
+            calls["route_bwd"] = lambda: B.route_backward(dev.smha, dev.x, dev.a_w_expert, dev.a_w_b, dev.a_w_a,
+                                                          dev.a_expert_gate, dev.a_patch_gate, d_ge, d_gp, d_x, *grads, ws)
     if args.stage == "copy":   # a plain copy of known size (1 GiB read + 1 GiB written): counter calibration
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).normal_()
         dst = torch.empty_like(src)
@@ -107,7 +124,7 @@ def main() -> int:
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
                     choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather", "copy",
-                             "uome_bwd", "smha_bwd"],
+                             "uome_bwd", "smha_bwd", "route_bwd", "layer_bwd", "layer_fwd_bwd"],
                     help="profiling aid: loop one C-ABI call of the path instead of the whole layer "
                          "and print its time (no JSON contract line)")
     args = ap.parse_args()

@@ -294,6 +294,36 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
                       const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, void *ws,
                       size_t ws_bytes, void *hip_stream);
 
+/* Gradients of a block's router weights, shaped like the weights; a member may be NULL when the
+ * block has no such router. */
+typedef struct {
+    void *d_w_expert, *d_w_b, *d_w_a;
+} uoe_router_grads;
+
+/*
+ * Backward pass of uoe_layer_forward (Sec. III-C): the four backward calls above chained on one
+ * stream.  d_out = dL/d(out) [b,l,d]  ->  uoe_uome_backward and the UoME router's
+ * uoe_route_backward (on u) give dL/du  ->  uoe_smha_backward and the SMHA routers'
+ * uoe_route_backward (on x) give d_x = dL/dx [b,l,d].
+ *   routing_a / routing_m: the routing results of the forward call (its uoe_routing_out copies),
+ *       read only; expert_idx and, for SMHA, patch_idx are required, a gate is required when its
+ *       flag is set.
+ *   u: the SMHA output of the forward pass, or NULL to have it recomputed from x.
+ *   dwa, d_a_in, d_a_out: gradients of the block weights; dra / drm: gradients of the routers'
+ *       weights (required when the block has a router; a router's gate flag must then be set,
+ *       otherwise its weights have no influence on the output: UOE_ERR_INVALID_ARG).
+ * Limits: those of the four calls; the UoME block in expert-selection mode.  ws: at least
+ * uoe_layer_backward_workspace_bytes(smha, uome) bytes (0 = invalid or unsupported).
+ */
+size_t uoe_layer_backward_workspace_bytes(const uoe_block_desc *smha, const uoe_block_desc *uome);
+int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
+                       const uoe_block_desc *uome, const uoe_uome_weights *wm, const void *x,
+                       const void *u, const uoe_routing_out *routing_a,
+                       const uoe_routing_out *routing_m, const void *d_out, void *d_x,
+                       const uoe_smha_weight_grads *dwa, const uoe_router_grads *dra, void *d_a_in,
+                       void *d_a_out, const uoe_router_grads *drm, void *ws, size_t ws_bytes,
+                       void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -484,3 +484,36 @@ def layer_forward(inp, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
         rm = route(u, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
         out = uome(u, inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, flags_m)
     return LayerResult(ra, u, rm, out)
+
+
+@dataclass
+class LayerGrads:
+    d_x: np.ndarray
+    smha: SmhaGrads            # block weights (d_x, gate members: the block's own share)
+    route_a: RouteGrads        # SMHA routers
+    uome: UomeGrads            # d_u member: dL/du before the UoME router's share is added
+    route_m: RouteGrads        # UoME router
+
+
+def layer_backward(inp, fwd: LayerResult, d_out, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
+                   flags_m: int = RESIDUAL | GATE_EXPERT, rope_dim: int = 0, gates_a=None, gate_m=None) -> LayerGrads:
+    """Gradients of layer_forward (expert-selection UoME) for d_out = dL/d(out): the chain rule through
+    out = UoME(u; routers on u), u = SMHA(x; routers on x), the selections held constant.
+
+    `fwd` is the forward result whose routing is differentiated through; gates_a = (expert, patch)
+    and gate_m override the gate VALUES used (a test passes the fp32-rounded gates the device gets)."""
+    cfg = inp.cfg
+    ra, rm = fwd.routing_a, fwd.routing_m
+    ge_a, gp_a = (ra.expert_gate, ra.patch_gate) if gates_a is None else gates_a
+    ge_m = rm.expert_gate if gate_m is None else gate_m
+    gm = uome_backward(fwd.u, inp.a_in, inp.a_out, rm.expert_id, ge_m, d_out, flags_m)
+    d_u = gm.d_u.copy()
+    if inp.m_w_expert is not None:
+        rgm = route_backward(fwd.u, inp.m_w_expert, None, None, ge_m, None, gm.d_gate, None)
+        d_u += rgm.d_x
+    else:
+        rgm = RouteGrads(np.zeros_like(d_u), None, None, None)
+    ga = smha_backward(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ge_a, ra.patch_id, gp_a, cfg.m, d_u,
+                       flags_a, rope_dim)
+    rga = route_backward(inp.x, inp.a_w_expert, inp.a_w_b, inp.a_w_a, ge_a, gp_a, ga.d_expert_gate, ga.d_patch_gate)
+    return LayerGrads(ga.d_x + rga.d_x, ga, rga, gm, rgm)

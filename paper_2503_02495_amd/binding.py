@@ -22,7 +22,8 @@ EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_c
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward",
            "uoe_uome_backward_workspace_bytes", "uoe_uome_backward",
            "uoe_smha_backward_workspace_bytes", "uoe_smha_backward",
-           "uoe_route_backward_workspace_bytes", "uoe_route_backward")
+           "uoe_route_backward_workspace_bytes", "uoe_route_backward",
+           "uoe_layer_backward_workspace_bytes", "uoe_layer_backward")
 
 
 class UoeError(RuntimeError):
@@ -49,6 +50,10 @@ class UomeWeights(ctypes.Structure):
 
 class SmhaWeightGrads(ctypes.Structure):
     _fields_ = [(f, ctypes.c_void_p) for f in ("d_wq", "d_wk", "d_wv", "d_wo")]
+
+
+class RouterGrads(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_void_p) for f in ("d_w_expert", "d_w_b", "d_w_a")]
 
 
 class RoutingOut(ctypes.Structure):
@@ -88,13 +93,19 @@ def lib():
         L.uoe_route_backward_workspace_bytes.argtypes = [D]
         L.uoe_route_backward_workspace_bytes.restype = S
         L.uoe_route_backward.argtypes = [D] + [P] * 12 + [P, S, P]
+        L.uoe_layer_backward_workspace_bytes.argtypes = [D, D]
+        L.uoe_layer_backward_workspace_bytes.restype = S
+        L.uoe_layer_backward.argtypes = [D, ctypes.POINTER(SmhaWeights), D, ctypes.POINTER(UomeWeights), P, P,
+                                         ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut), P, P,
+                                         ctypes.POINTER(SmhaWeightGrads), ctypes.POINTER(RouterGrads), P, P,
+                                         ctypes.POINTER(RouterGrads), P, S, P]
         L.uoe_uome_up.argtypes = [D, P, P, P, P, P, P]
         L.uoe_uome_down.argtypes = [D, P, P, P, P, P, P]
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
         for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
-                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward", "uoe_route_backward"):
+                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward", "uoe_route_backward", "uoe_layer_backward"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -230,6 +241,25 @@ def route_backward(blk, x, w_expert, w_b, w_a, expert_gate, patch_gate, d_expert
                                   _ptr(d_w_expert), _ptr(d_w_b), _ptr(d_w_a), _ptr(ws),
                                   _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_route_backward", check)
+
+
+def router_grads(d_w_expert=None, d_w_b=None, d_w_a=None) -> RouterGrads:
+    return RouterGrads(*(_ptr(t) for t in (d_w_expert, d_w_b, d_w_a)))
+
+
+def layer_backward_workspace_bytes(smha, uome) -> int:
+    return int(lib().uoe_layer_backward_workspace_bytes(_ref(smha), _ref(uome)))
+
+
+def layer_backward(smha, wa: SmhaWeights, uome, wm: UomeWeights, x, u, routing_a: RoutingOut, routing_m: RoutingOut,
+                   d_out, d_x, dwa: SmhaWeightGrads, dra: Optional[RouterGrads], d_a_in, d_a_out,
+                   drm: Optional[RouterGrads], ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_layer_backward(_ref(smha), ctypes.byref(wa), _ref(uome), ctypes.byref(wm), _ptr(x), _ptr(u),
+                                  ctypes.byref(routing_a), ctypes.byref(routing_m), _ptr(d_out), _ptr(d_x),
+                                  ctypes.byref(dwa), None if dra is None else ctypes.byref(dra), _ptr(d_a_in),
+                                  _ptr(d_a_out), None if drm is None else ctypes.byref(drm), _ptr(ws),
+                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_layer_backward", check)
 
 
 def uome_up(blk, u, a_in, expert_idx, expert_gate, hidden, stream=None, check=True) -> int:

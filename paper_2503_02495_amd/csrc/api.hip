@@ -655,4 +655,103 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
     return do_uome(uome, u, wm->a_in, wm->a_out, m_eidx, m_egate, nullptr, nullptr, out, uome_scratch, uome_bytes, st);
 }
 
+// workspace of the layer backward: [u][d_u][gate gradients][the largest of the stages' own scratch]
+struct LayerBwdWs {
+    size_t u, d_u, d_gate_m, d_gate_a, d_pgate_a, stage, stage_bytes, total;
+};
+static LayerBwdWs layer_bwd_ws(const uoe_block_desc *smha, const uoe_block_desc *uome)
+{
+    LayerBwdWs w;
+    const size_t act = up((size_t)smha->b * smha->l * smha->d * elem_size(smha->dtype));
+    uoe_block_desc um = *uome;
+    um.m = um.c = 1;
+    size_t off = 0;
+    w.u = off; off += act;
+    w.d_u = off; off += act;
+    w.d_gate_m = off; off += up((size_t)uome->b * uome->n * sizeof(float));
+    w.d_gate_a = off; off += up((size_t)smha->b * smha->n * sizeof(float));
+    w.d_pgate_a = off; off += up((size_t)smha->b * smha->n * smha->m * sizeof(float));
+    size_t stage = smha_ws(smha).total;
+    const size_t others[] = {uoe_uome_backward_workspace_bytes(uome), uoe_smha_backward_workspace_bytes(smha),
+                             uoe_route_backward_workspace_bytes(smha), uoe_route_backward_workspace_bytes(&um)};
+    for (size_t v : others) stage = v > stage ? v : stage;
+    w.stage = off; w.stage_bytes = stage; off += up(stage);
+    w.total = off;
+    return w;
+}
+static int check_layer_bwd(const uoe_block_desc *smha, const uoe_block_desc *uome)
+{
+    int rc = check_smha_bwd(smha);
+    if (rc != UOE_OK) return rc;
+    rc = check_uome_bwd(uome);  // expert-selection UoME only
+    if (rc != UOE_OK) return rc;
+    if (smha->b != uome->b || smha->l != uome->l || smha->d != uome->d || smha->dtype != uome->dtype) return UOE_ERR_INVALID_ARG;
+    uoe_block_desc um = *uome;
+    um.m = um.c = 1;
+    if ((rc = check_route_bwd(smha)) != UOE_OK) return rc;
+    return check_route_bwd(&um);
+}
+
+size_t uoe_layer_backward_workspace_bytes(const uoe_block_desc *smha, const uoe_block_desc *uome)
+{
+    if (!smha || !uome || check_layer_bwd(smha, uome) != UOE_OK) return 0;
+    return layer_bwd_ws(smha, uome).total;
+}
+
+int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa, const uoe_block_desc *uome,
+                       const uoe_uome_weights *wm, const void *x, const void *u, const uoe_routing_out *routing_a,
+                       const uoe_routing_out *routing_m, const void *d_out, void *d_x, const uoe_smha_weight_grads *dwa,
+                       const uoe_router_grads *dra, void *d_a_in, void *d_a_out, const uoe_router_grads *drm, void *ws,
+                       size_t ws_bytes, void *hip_stream)
+{
+    if (!smha || !uome) return UOE_ERR_INVALID_ARG;
+    int rc = check_layer_bwd(smha, uome);
+    if (rc != UOE_OK) return rc;
+    if (!wa || !wm || !x || !routing_a || !routing_m || !d_out || !d_x || !dwa || !d_a_in || !d_a_out) return UOE_ERR_INVALID_ARG;
+    if (!routing_a->expert_idx || !routing_a->patch_idx || !routing_m->expert_idx) return UOE_ERR_INVALID_ARG;
+    const bool route_a = wa->w_expert || wa->w_b, route_m = wm->w_expert != nullptr;
+    if (route_a && !dra) return UOE_ERR_INVALID_ARG;
+    if (route_m && !drm) return UOE_ERR_INVALID_ARG;
+    // a router's gate must be an input of its block for its gradient to exist
+    if (wa->w_expert && (!(smha->flags & UOE_FLAG_GATE_EXPERT) || !routing_a->expert_gate)) return UOE_ERR_INVALID_ARG;
+    if (wa->w_b && (!(smha->flags & UOE_FLAG_GATE_PATCH) || !routing_a->patch_gate)) return UOE_ERR_INVALID_ARG;
+    if (route_m && (!(uome->flags & UOE_FLAG_GATE_EXPERT) || !routing_m->expert_gate)) return UOE_ERR_INVALID_ARG;
+    const LayerBwdWs w = layer_bwd_ws(smha, uome);
+    if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    void *stage = at(ws, w.stage);
+    void *d_u = at(ws, w.d_u);
+    float *d_gate_m = reinterpret_cast<float *>(at(ws, w.d_gate_m));
+    float *d_gate_a = reinterpret_cast<float *>(at(ws, w.d_gate_a));
+    float *d_pgate_a = reinterpret_cast<float *>(at(ws, w.d_pgate_a));
+
+    if (!u) {  // u = SMHA(x) with the given routing
+        void *u_ws = at(ws, w.u);
+        rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, routing_a->expert_idx, routing_a->expert_gate,
+                     routing_a->patch_idx, routing_a->patch_gate, nullptr, u_ws, stage, w.stage_bytes, st);
+        if (rc != UOE_OK) return rc;
+        u = u_ws;
+    }
+    // UoME block and its router: d_out -> d_u
+    rc = uoe_uome_backward(uome, u, wm->a_in, wm->a_out, routing_m->expert_idx, routing_m->expert_gate, d_out, d_u, d_a_in,
+                           d_a_out, d_gate_m, stage, w.stage_bytes, hip_stream);
+    if (rc != UOE_OK) return rc;
+    if (route_m) {
+        uoe_block_desc um = *uome;
+        um.m = um.c = 1;
+        rc = uoe_route_backward(&um, u, wm->w_expert, nullptr, nullptr, routing_m->expert_gate, nullptr, d_gate_m, nullptr,
+                                d_u, drm->d_w_expert, nullptr, nullptr, stage, w.stage_bytes, hip_stream);
+        if (rc != UOE_OK) return rc;
+    }
+    // SMHA block and its routers: d_u -> d_x
+    rc = uoe_smha_backward(smha, x, wa, routing_a->expert_idx, routing_a->expert_gate, routing_a->patch_idx,
+                           routing_a->patch_gate, d_u, d_x, dwa, d_gate_a, d_pgate_a, stage, w.stage_bytes, hip_stream);
+    if (rc != UOE_OK) return rc;
+    if (route_a)
+        rc = uoe_route_backward(smha, x, wa->w_expert, wa->w_b, wa->w_a, routing_a->expert_gate, routing_a->patch_gate,
+                                d_gate_a, d_pgate_a, d_x, dra->d_w_expert, dra->d_w_b, dra->d_w_a, stage, w.stage_bytes,
+                                hip_stream);
+    return rc;
+}
+
 }  // extern "C"

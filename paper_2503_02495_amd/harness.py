@@ -141,6 +141,28 @@ class DeviceLayer:
                         self.d_a_expert_gate, self.d_a_patch_gate, self.smha_bwd_ws)
         return self.d_x, self.d_wq, self.d_wk, self.d_wv, self.d_wo, self.d_a_expert_gate, self.d_a_patch_gate
 
+    def layer_backward(self, d_out, routing_a=None, routing_m=None, u=None):
+        """Gradients of the whole layer for d_out = dL/d(out).  routing_a / routing_m default to the
+        results the last layer_forward wrote; u = None has it recomputed.  Returns a dict of tensors."""
+        if not hasattr(self, "layer_bwd_ws"):
+            nbytes = B.layer_backward_workspace_bytes(self.smha, self.uome)
+            if nbytes == 0:
+                raise B.UoeError(B.ERR_UNSUPPORTED, "uoe_layer_backward_workspace_bytes")
+            self.layer_bwd_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            like = lambda t: None if t is None else torch.empty_like(t)
+            self.g = {"d_x": like(self.x), "d_wq": like(self.wq), "d_wk": like(self.wk), "d_wv": like(self.wv),
+                      "d_wo": like(self.wo), "d_a_w_expert": like(self.a_w_expert), "d_a_w_b": like(self.a_w_b),
+                      "d_a_w_a": like(self.a_w_a), "d_a_in": like(self.a_in), "d_a_out": like(self.a_out),
+                      "d_m_w_expert": like(self.m_w_expert)}
+            g = self.g
+            self.layer_dwa = B.smha_weight_grads(g["d_wq"], g["d_wk"], g["d_wv"], g["d_wo"])
+            self.layer_dra = B.router_grads(g["d_a_w_expert"], g["d_a_w_b"], g["d_a_w_a"])
+            self.layer_drm = B.router_grads(g["d_m_w_expert"])
+        B.layer_backward(self.smha, self.wa, self.uome, self.wm, self.x, u, self.ra if routing_a is None else routing_a,
+                         self.rm if routing_m is None else routing_m, d_out, self.g["d_x"], self.layer_dwa,
+                         self.layer_dra, self.g["d_a_in"], self.g["d_a_out"], self.layer_drm, self.layer_bwd_ws)
+        return self.g
+
     def layer_forward(self):
         B.layer_forward(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
                         self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws)

@@ -364,6 +364,10 @@ CA = B.FLAG_CAUSAL
 # gates, hence a bound of 3e-2 on the worst element and of 6e-3 on the average.
 SMHA_BWD_TOL = 3e-2
 BWD_FRO_TOL = 6e-3
+# The chained layer backward adds the UoME backward's roundings and the bf16 hand-over of dL/du in
+# front of the SMHA backward's, and the router gradients inherit the gate gradients' error.
+LAYER_BWD_TOL = 4e-2
+LAYER_BWD_FRO_TOL = 1e-2
 
 
 @pytest.mark.parametrize("name,flags", [(nm, fl) for nm in list(SMHA_BWD_CONFIGS) + ["lm"] for fl in (0, R | GE | GP, R | GE | GP | CA)]
@@ -449,6 +453,46 @@ def test_route_backward_parity(name):
     print(f"[route backward {name}] " + " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {TOL[cfg.dtype]:.0e})",
           flush=True)
     assert max(errs.values()) <= TOL[cfg.dtype]
+
+
+# --------------------------------------------------------------------------- layer backward
+@pytest.mark.parametrize("name,fa,rope_dim", [("sb_dh64", R | GE | GP, 0), ("sb_long", R | GE | GP | CA, 16),
+                                              ("lm", R | GE | GP, 0), ("lm", R | GE | GP | CA, 32)])
+def test_layer_backward_parity(name, fa, rope_dim):
+    """uoe_layer_backward (UoME backward, its router, SMHA backward, its routers, chained on the
+    device) against the oracle's chain, on the oracle's routing and the fp32-rounded gates."""
+    cfg = SMHA_BWD_CONFIGS[name] if name in SMHA_BWD_CONFIGS else synth.CONFIGS[name]
+    w_std = 0.02 if name in synth.CONFIGS else 0.06
+    fm = R | GE
+    print(f"layer backward {name} fa={fa} rope_dim={rope_dim}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=w_std)
+    for attr in ("a_w_expert", "m_w_expert"):      # unsaturated expert routers, as in the router backward test
+        ld_std = w_std * np.sqrt(cfg.l * cfg.d)
+        if ld_std > 1.0:
+            setattr(inp, attr, getattr(inp, attr) * np.float32(2.0 ** -np.ceil(np.log2(ld_std))))
+    d_out = synth.make_upstream_grad(cfg)
+    fwd = oracle.layer_forward(inp, fa, fm, rope_dim)
+    ra, rm = fwd.routing_a, fwd.routing_m
+    ge_a, gp_a, ge_m = (g.astype(np.float32) for g in (ra.expert_gate, ra.patch_gate, rm.expert_gate))
+    dev = DeviceLayer(inp, fa, fm, rope_dim=rope_dim)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev.device)
+    f32 = lambda a: to_device(a, synth.F32, dev.device)
+    keep = [i32(ra.expert_id), f32(ge_a), i32(ra.patch_id), f32(gp_a), i32(rm.expert_id), f32(ge_m)]
+    g = dev.layer_backward(to_device(d_out, cfg.dtype, dev.device), routing_a=B.routing_out(*keep[:4]),
+                           routing_m=B.routing_out(keep[4], keep[5]))
+    torch.cuda.synchronize()
+    want = oracle.layer_backward(inp, fwd, d_out, fa, fm, rope_dim, gates_a=(ge_a, gp_a), gate_m=ge_m)
+    refs = {"d_x": want.d_x, "d_wq": want.smha.d_wq, "d_wk": want.smha.d_wk, "d_wv": want.smha.d_wv, "d_wo": want.smha.d_wo,
+            "d_a_w_expert": want.route_a.d_w_expert, "d_a_w_b": want.route_a.d_w_b.T, "d_a_w_a": want.route_a.d_w_a.T,
+            "d_a_in": want.uome.d_a_in, "d_a_out": want.uome.d_a_out, "d_m_w_expert": want.route_m.d_w_expert}
+    errs, fro = {}, {}
+    for nm, r in refs.items():
+        y = to_host(g[nm])
+        y = y.T if nm in ("d_a_w_b", "d_a_w_a") else y          # slices = experts / patches
+        errs[nm], fro[nm] = grad_err(y, r), fro_err(y, r)
+    print(f"[layer backward {name} fa={fa}] " + " ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
+    print(f"[layer backward {name} fa={fa}] fro " + " ".join(f"{k} {v:.2e}" for k, v in fro.items()), flush=True)
+    assert max(errs.values()) <= LAYER_BWD_TOL and max(fro.values()) <= LAYER_BWD_FRO_TOL
 
 
 # --------------------------------------------------------------------------- single-mode SMHA blocks
