@@ -175,14 +175,17 @@ struct RouteBwdWs {
 RouteBwdWs route_bwd_ws(const uoe_block_desc *d)
 {
     RouteBwdWs w;
-    w.wb_tokens = 256;
-    w.wb_chunks = (int)(((size_t)d->b * d->l + w.wb_tokens - 1) / w.wb_tokens);
+    // chunks of the token axis for dW_B: about 512 of them, never shorter than 64 tokens
+    const size_t tokens = (size_t)d->b * d->l;
+    w.wb_tokens = (int)((tokens + 511) / 512);
+    if (w.wb_tokens < 64) w.wb_tokens = 64;
+    w.wb_chunks = (int)((tokens + w.wb_tokens - 1) / w.wb_tokens);
     size_t off = 0;
     w.dz = off; off += up((size_t)d->b * d->n * sizeof(float));
     w.dl = off; off += up((size_t)d->b * d->n * d->m * sizeof(float));
     w.t1 = off; off += up((size_t)d->b * d->l * d->n * sizeof(float));
     w.u = off; off += up((size_t)d->b * d->l * d->n * sizeof(float));
-    w.wb_part = off; off += up((size_t)w.wb_chunks * (256 / (d->d / 8)) * d->d * d->n * sizeof(float));
+    w.wb_part = off; off += up((size_t)w.wb_chunks * d->d * d->n * sizeof(float));
     w.total = off;
     return w;
 }
@@ -192,7 +195,7 @@ int check_route_bwd(const uoe_block_desc *blk)
     if (rc != UOE_OK) return rc;
     if (blk->b > 128 || blk->d > 2048) return UOE_ERR_UNSUPPORTED;
     // the data router's per-token kernel stages dL [n,m], U [64,n] and W_B [d,n] in LDS
-    const size_t lds = ((size_t)blk->n * blk->m + 64 * (size_t)blk->n) * sizeof(float) + (size_t)blk->d * blk->n * elem_size(blk->dtype);
+    const size_t lds = ((size_t)blk->n * blk->m + 64 * (size_t)blk->n) * sizeof(float) + 16 + (size_t)blk->d * blk->n * elem_size(blk->dtype);
     if (lds > 64 * 1024) return UOE_ERR_UNSUPPORTED;
     return UOE_OK;
 }

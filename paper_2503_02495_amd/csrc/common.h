@@ -173,7 +173,7 @@ struct RouteBwdArgs {
     // workspace (fp32)
     float *dz, *dl;                           // [b,n], [b,n,m]: gradients of the router logits
     float *t1, *u;                            // [b,l,n] each: x W_B and W_A dL^T
-    float *wb_part;                           // [wb_chunks * (256 / (d/8)), d, n] partial sums of dW_B
+    float *wb_part;                           // [wb_chunks, d, n] partial sums of dW_B
     int wb_tokens, wb_chunks;                 // tokens per chunk, chunks over the b*l tokens
 };
 

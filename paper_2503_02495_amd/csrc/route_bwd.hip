@@ -129,17 +129,21 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_xexpert_k
 
 // Data router, per token: U[t,:] = W_A[t,:] dL^T, then one pass over the token's row of x that
 // forms (x W_B)[t,:] and adds U[t,:] W_B^T to d_x.  Block = 64 tokens of one sample, 4 lanes per
-// token; W_B and the sample's dL are staged in LDS.
+// token; the sample's dL and W_B^T ([n][d], so that the 8 weights a piece of x meets are one
+// 16-byte read) are staged in LDS.
 template <typename T> __global__ __launch_bounds__(256) void route_bwd_data_token_kernel(RouteBwdArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     float *dls = reinterpret_cast<float *>(smem);                       // [n][m]
     float *us = dls + (size_t)a.n * a.m;                                // [64][n]
-    T *wbs = reinterpret_cast<T *>(us + 64 * a.n);                      // [d][n]
+    T *wbt = reinterpret_cast<T *>(smem + ((((size_t)a.n * a.m + 64 * (size_t)a.n) * sizeof(float) + 15) & ~(size_t)15));  // [n][d]
     const int bb = blockIdx.y, tid = threadIdx.x, tl = tid >> 2, part = tid & 3;
     const int t = blockIdx.x * 64 + tl;
     for (int idx = tid; idx < a.n * a.m; idx += 256) dls[idx] = a.dl[(size_t)bb * a.n * a.m + idx];
-    for (int idx = tid; idx < a.d * a.n; idx += 256) wbs[idx] = static_cast<const T *>(a.w_b)[idx];
+    for (int idx = tid; idx < a.d * a.n; idx += 256) {
+        const int e = idx / a.n, i = idx - e * a.n;
+        wbt[(size_t)i * a.d + e] = static_cast<const T *>(a.w_b)[idx];
+    }
     __syncthreads();
     if (t < a.l) {
         const T *wa = static_cast<const T *>(a.w_a) + (size_t)t * a.m;
@@ -165,11 +169,12 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_data_toke
             for (int i = 0; i < 32; ++i) {
                 if (i < a.n) {
                     const float ui = us[tl * a.n + i];
+                    float wv[8];
+                    load8(wbt + (size_t)i * a.d + pc * 8, wv);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const float w = to_f32(wbs[(pc * 8 + e) * a.n + i]);
-                        t1[i] = fmaf(xv[e], w, t1[i]);
-                        dv[e] = fmaf(ui, w, dv[e]);
+                        t1[i] = fmaf(xv[e], wv[e], t1[i]);
+                        dv[e] = fmaf(ui, wv[e], dv[e]);
                     }
                 }
             }
@@ -200,15 +205,17 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_wa_kernel
 }
 
 // dW_B[e,i] = sum over all b*l tokens of x[token,e] U[token,i].  Block = a chunk of tokens; thread =
-// (8 consecutive e, row lane); each row lane's sums go to its own partial [d][n] (no block
-// reduction: the final kernel adds all partials in order).  block.y = a group of 16 experts.
+// (8 consecutive e, row lane).  The row lanes' sums are added in lane order through LDS, one
+// expert at a time, so that a block leaves one partial [d][n]; the final kernel adds the chunks
+// in order.  block.y = a group of 16 experts.
 template <typename T> __global__ __launch_bounds__(256) void route_bwd_wb_partial_kernel(RouteBwdArgs a)
 {
     constexpr int IG = 16;
+    __shared__ float red[256][9];
     const int P = a.d / 8, R = 256 / P, tid = threadIdx.x;
     const int pc = tid % P, rl = tid / P;
     const int i0 = blockIdx.y * IG, ni = min(IG, a.n - i0);
-    if (rl >= R) return;
+    const bool live = rl < R;
     float acc[IG][8];
 #pragma unroll
     for (int i = 0; i < IG; ++i)
@@ -217,33 +224,56 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_wb_partia
     const long tokens = (long)a.b * a.l, tok0 = (long)blockIdx.x * a.wb_tokens;
     const long tok1 = min(tokens, tok0 + a.wb_tokens);
     const T *x = static_cast<const T *>(a.x);
-    for (long tok = tok0 + rl; tok < tok1; tok += R) {
-        float xv[8];
-        load8(x + tok * a.d + pc * 8, xv);
-        const float *u = a.u + tok * a.n + i0;
+    if (live)
+        for (long tok = tok0 + rl; tok < tok1; tok += R) {
+            float xv[8];
+            load8(x + tok * a.d + pc * 8, xv);
+            const float *u = a.u + tok * a.n + i0;
 #pragma unroll
-        for (int i = 0; i < IG; ++i) {
-            const float ui = i < ni ? u[i] : 0.f;
+            for (int i = 0; i < IG; ++i) {
+                const float ui = i < ni ? u[i] : 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(xv[e], ui, acc[i][e]);
+                for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(xv[e], ui, acc[i][e]);
+            }
         }
+    float *dst = a.wb_part + (size_t)blockIdx.x * a.d * a.n;
+#pragma unroll
+    for (int i = 0; i < IG; ++i) {
+        if (i >= ni) break;  // uniform
+        if (live)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[tid][e] = acc[i][e];
+        __syncthreads();
+        if (rl == 0) {
+            float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int q = 0; q < R; ++q)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] += red[q * P + pc][e];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[(size_t)(pc * 8 + e) * a.n + i0 + i] = s[e];
+        }
+        __syncthreads();
     }
-    float *dst = a.wb_part + ((size_t)blockIdx.x * R + rl) * a.d * a.n;
-#pragma unroll
-    for (int i = 0; i < IG; ++i)
-        if (i < ni)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dst[(size_t)(pc * 8 + e) * a.n + i0 + i] = acc[i][e];
 }
 
+// adds the chunks' partials in chunk order: block = 32 outputs x 8 part lanes (lane q takes chunks
+// q, q+8, ...), then the 8 lanes in lane order
 template <typename T> __global__ __launch_bounds__(256) void route_bwd_wb_reduce_kernel(RouteBwdArgs a)
 {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= a.d * a.n) return;
-    const int parts = a.wb_chunks * (256 / (a.d / 8));
+    __shared__ float red[8][33];
+    const int ol = threadIdx.x & 31, ql = threadIdx.x >> 5;
+    const int idx = blockIdx.x * 32 + ol, total = a.d * a.n;
     float s = 0.f;
-    for (int p = 0; p < parts; ++p) s += a.wb_part[(size_t)p * a.d * a.n + idx];
-    static_cast<T *>(a.d_w_b)[idx] = from_f32<T>(s);
+    if (idx < total)
+        for (int p = ql; p < a.wb_chunks; p += 8) s += a.wb_part[(size_t)p * total + idx];
+    red[ql][ol] = s;
+    __syncthreads();
+    if (ql == 0 && idx < total) {
+        float v = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v += red[q][ol];
+        static_cast<T *>(a.d_w_b)[idx] = from_f32<T>(v);
+    }
 }
 
 template <typename T> static hipError_t route_backward(const RouteBwdArgs &a, hipStream_t st)
@@ -260,14 +290,14 @@ template <typename T> static hipError_t route_backward(const RouteBwdArgs &a, hi
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (a.w_b) {
-        const size_t smem = ((size_t)a.n * a.m + 64 * a.n) * sizeof(float) + (size_t)a.d * a.n * sizeof(T);
+        const size_t smem = ((((size_t)a.n * a.m + 64 * (size_t)a.n) * sizeof(float) + 15) & ~(size_t)15) + (size_t)a.d * a.n * sizeof(T);
         hipLaunchKernelGGL((route_bwd_data_token_kernel<T>), dim3((a.l + 63) / 64, a.b), dim3(256), smem, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
         hipLaunchKernelGGL((route_bwd_wa_kernel<T>), dim3((unsigned)(((long)a.l * a.m + 255) / 256)), dim3(256), 0, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
         hipLaunchKernelGGL((route_bwd_wb_partial_kernel<T>), dim3(a.wb_chunks, (a.n + 15) / 16), dim3(256), 0, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
-        hipLaunchKernelGGL((route_bwd_wb_reduce_kernel<T>), dim3((a.d * a.n + 255) / 256), dim3(256), 0, st, a);
+        hipLaunchKernelGGL((route_bwd_wb_reduce_kernel<T>), dim3((a.d * a.n + 31) / 32), dim3(256), 0, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     return hipSuccess;
