@@ -29,10 +29,10 @@ template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *p, const floa
 // Softmax backward of both routers: block = sample.  dz_i = g_i (dg_i - sum_j g_j dg_j) is
 // evaluated as g_i * sum_j g_j (dg_i - dg_j) (the gates sum to one): with one gate close to 1 the
 // first form subtracts two nearly equal numbers, the second adds small terms of mixed sign only.
-__global__ __launch_bounds__(256) void route_bwd_softmax_kernel(RouteBwdArgs a)
+__global__ __launch_bounds__(64) void route_bwd_softmax_kernel(RouteBwdArgs a)
 {
     const int bb = blockIdx.x, tid = threadIdx.x;
-    if (a.w_e && tid < a.n) {
+    if (a.w_e && blockIdx.y == 0 && tid < a.n) {
         const float *g = a.g_e + (size_t)bb * a.n, *dg = a.d_g_e + (size_t)bb * a.n;
         const float mine = dg[tid];
         float s = 0.f;
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void route_bwd_softmax_kernel(RouteBwdArgs a)
         a.dz[(size_t)bb * a.n + tid] = g[tid] * s;
     }
     if (a.w_b)
-        for (int j = tid; j < a.m; j += 256) {
+        for (int j = blockIdx.y * 64 + tid; j < a.m; j += 64 * gridDim.y) {
             const float *g = a.g_p + (size_t)bb * a.n * a.m + j, *dg = a.d_g_p + (size_t)bb * a.n * a.m + j;
             for (int i = 0; i < a.n; ++i) {
                 const float mine = dg[(size_t)i * a.m];
@@ -212,6 +212,7 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_wb_partia
 {
     constexpr int IG = 16;
     __shared__ float red[256][9];
+    __shared__ float us[128 * IG];  // the chunk's rows of U (at most 128 tokens per chunk)
     const int P = a.d / 8, R = 256 / P, tid = threadIdx.x;
     const int pc = tid % P, rl = tid / P;
     const int i0 = blockIdx.y * IG, ni = min(IG, a.n - i0);
@@ -224,22 +225,28 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_wb_partia
     const long tokens = (long)a.b * a.l, tok0 = (long)blockIdx.x * a.wb_tokens;
     const long tok1 = min(tokens, tok0 + a.wb_tokens);
     const T *x = static_cast<const T *>(a.x);
-    if (live)
-        for (long tok = tok0 + rl; tok < tok1; tok += R) {
+    const int ntok = (int)(tok1 - tok0);
+    for (int idx = tid; idx < ntok * IG; idx += 256) {
+        const int tk = idx / IG, i = idx - tk * IG;
+        us[idx] = i < ni ? a.u[(tok0 + tk) * a.n + i0 + i] : 0.f;
+    }
+    __syncthreads();
+    if (live) {
+        for (int tk = rl; tk < ntok; tk += R) {
             float xv[8];
-            load8(x + tok * a.d + pc * 8, xv);
-            const float *u = a.u + tok * a.n + i0;
+            load8(x + (tok0 + tk) * a.d + pc * 8, xv);
 #pragma unroll
             for (int i = 0; i < IG; ++i) {
-                const float ui = i < ni ? u[i] : 0.f;
+                const float ui = us[tk * IG + i];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(xv[e], ui, acc[i][e]);
             }
         }
+    }
     float *dst = a.wb_part + (size_t)blockIdx.x * a.d * a.n;
 #pragma unroll
-    for (int i = 0; i < IG; ++i) {
-        if (i >= ni) break;  // uniform
+    for (int i = 0; i < IG; ++i) {  // fully unrolled: acc stays in registers; the skip is uniform
+        if (i < ni) {
         if (live)
 #pragma unroll
             for (int e = 0; e < 8; ++e) red[tid][e] = acc[i][e];
@@ -253,6 +260,7 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_wb_partia
             for (int e = 0; e < 8; ++e) dst[(size_t)(pc * 8 + e) * a.n + i0 + i] = s[e];
         }
         __syncthreads();
+        }
     }
 }
 
@@ -279,7 +287,7 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_wb_reduce
 template <typename T> static hipError_t route_backward(const RouteBwdArgs &a, hipStream_t st)
 {
     hipError_t err;
-    hipLaunchKernelGGL(route_bwd_softmax_kernel, dim3(a.b), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(route_bwd_softmax_kernel, dim3(a.b, a.w_b ? (a.m + 63) / 64 : 1), dim3(64), 0, st, a);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     const long pieces = (long)a.l * a.d / 8;
     const unsigned pblocks = (unsigned)((pieces + 255) / 256);
