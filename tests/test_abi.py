@@ -160,3 +160,53 @@ def test_smha_uome_layer_argument_validation():
     assert ly(d, u, FAKE, FAKE + 16, ws_bytes=64) == B.ERR_WORKSPACE
     assert B.gather(d, FAKE, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG   # h aliases x
     assert B.gather(d, None, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG
+
+
+def test_backward_argument_validation():
+    """The backward entry points: unsupported shapes give a zero workspace size and
+    UOE_ERR_UNSUPPORTED, bad pointer combinations UOE_ERR_INVALID_ARG, all before any launch."""
+    assert ctypes.sizeof(B.SmhaWeightGrads) == 4 * 8 and ctypes.sizeof(B.RouterGrads) == 3 * 8
+    big = 1 << 40
+    fl = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT
+    # UoME backward: bf16, l, d, d_e multiples of 32, expert-selection mode
+    u = B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.BF16, fl)
+    assert B.uome_backward_workspace_bytes(u) > 0
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.F32, fl)) == 0
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 48, 64, 4, 2, 1, 1, 64, B.BF16, fl)) == 0
+    ub = lambda *a, **k: B.uome_backward(u, *a, stream=0, check=False, **k)
+    ok = [FAKE, FAKE + 16, FAKE + 32, FAKE, FAKE, FAKE + 48, FAKE + 64, FAKE + 80, FAKE + 96, FAKE, FAKE]
+    assert ub(*ok, ws_bytes=8) == B.ERR_WORKSPACE
+    bad = list(ok); bad[4] = None                       # gate flag without gates
+    assert ub(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
+    bad = list(ok); bad[6] = ok[0]                      # d_u aliases u
+    assert ub(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
+    # SMHA backward: d_h in {32, 64, 128}, l_p a multiple of 32
+    a = B.block_desc(2, 128, 64, 4, 2, 4, 2, 32, B.BF16, fl | B.FLAG_GATE_PATCH)
+    assert B.smha_backward_workspace_bytes(a) > 0
+    assert B.smha_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 8, 2, 32, B.BF16, fl)) == 0    # l_p = 16
+    assert B.smha_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 4, 2, 16, B.BF16, fl)) == 0    # d_h = 16
+    wa = B.smha_weights(*([FAKE] * 7))
+    dw = B.smha_weight_grads(FAKE + 16, FAKE + 32, FAKE + 48, FAKE + 64)
+    sb = lambda *args, **k: B.smha_backward(a, *args, stream=0, check=False, **k)
+    assert sb(FAKE, wa, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE + 32, dw, None, None, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
+    assert sb(FAKE, wa, FAKE, FAKE, FAKE, None, FAKE + 16, FAKE + 32, dw, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG
+    assert sb(FAKE, wa, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, dw, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # d_x aliases x
+    # router backward: at least one router, w_b and w_a together, gates with their routers
+    rb = lambda *args, **k: B.route_backward(a, *args, stream=0, check=False, **k)
+    assert B.route_backward_workspace_bytes(a) > 0
+    assert rb(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, FAKE, FAKE, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
+    assert rb(FAKE, None, None, None, None, None, None, None, FAKE + 16, None, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG
+    assert rb(FAKE, None, FAKE, None, None, FAKE, None, FAKE, FAKE + 16, None, FAKE, FAKE, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG
+    assert rb(FAKE, FAKE, None, None, None, None, FAKE, None, FAKE + 16, FAKE, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG
+    # layer backward: the sizes of its parts, the same shape rules
+    assert B.layer_backward_workspace_bytes(a, u) == 0              # l differs (128 vs 64)
+    u2 = B.block_desc(2, 128, 64, 4, 2, 1, 1, 64, B.BF16, fl)
+    need = B.layer_backward_workspace_bytes(a, u2)
+    assert need >= max(B.smha_backward_workspace_bytes(a), B.uome_backward_workspace_bytes(u2))
+    wm = B.uome_weights(FAKE, FAKE, FAKE)
+    ra = B.routing_out(FAKE, FAKE, FAKE, FAKE)
+    rm = B.routing_out(FAKE, FAKE)
+    lb = lambda dra, drm, **k: B.layer_backward(a, wa, u2, wm, FAKE, None, ra, rm, FAKE + 16, FAKE + 32, dw, dra,
+                                                FAKE + 48, FAKE + 64, drm, FAKE, stream=0, check=False, **k)
+    assert lb(B.router_grads(FAKE, FAKE, FAKE), B.router_grads(FAKE), ws_bytes=8) == B.ERR_WORKSPACE
+    assert lb(None, B.router_grads(FAKE), ws_bytes=big) == B.ERR_INVALID_ARG      # SMHA has routers, no place for their gradients
