@@ -340,14 +340,18 @@ class UomeGrads:
     d_a_in: np.ndarray     # [n,d,d_e]
     d_a_out: np.ndarray    # [n,d_e,d]
     d_gate: np.ndarray     # [b,n]  (zero for experts a sample did not select, and without GATE_EXPERT)
+    d_patch_gate: Optional[np.ndarray] = None   # [b,n,m] in data-selection mode (zero off the selected patches)
 
 
-def uome_backward(u, a_in, a_out, expert_id, expert_gate, d_out, flags: int = RESIDUAL) -> UomeGrads:
-    """Gradients of the expert-selection UoME block (Eq. 38-40 with Eq. 24-26) for a given upstream
-    gradient d_out = dL/dh [b,l,d]: chain rule through h[b] = (u[b]) + sum_s w * SiLU(u[b] A^I_i) A^O_i.
+def uome_backward(u, a_in, a_out, expert_id, expert_gate, d_out, flags: int = RESIDUAL, patch_id=None,
+                  patch_gate_=None, m: int = 1) -> UomeGrads:
+    """Gradients of the UoME block (Eq. 37-40) for a given upstream gradient d_out = dL/dh [b,l,d].
+    Expert-selection mode (Eq. 24-26): h[b] = (u[b]) + sum_s w * SiLU(u[b] A^I_i) A^O_i.  Data-selection
+    mode (patch_id [b,n,c] given): expert i sees only the tokens T of its c selected patches and
+    h[b][T_t] += w_t * (SiLU(u[b][T] A^I_i) A^O_i)_t with w_t the expert and/or patch gate of row t.
 
-    The selection (expert_id) is a constant of the backward pass; the gate enters as a value
-    (d_gate is dL/dg, to be chained into the router by the caller)."""
+    The selections are constants of the backward pass; the gates enter as values (d_gate and
+    d_patch_gate are dL/dg, to be chained into the routers by the caller)."""
     u, a_in, a_out, d_out = _f64(u), _f64(a_in), _f64(a_out), _f64(d_out)
     b, l, d = u.shape
     n, _, d_e = a_in.shape
@@ -355,6 +359,32 @@ def uome_backward(u, a_in, a_out, expert_id, expert_gate, d_out, flags: int = RE
     g = _f64(expert_gate)
     d_u = d_out.copy() if flags & RESIDUAL else np.zeros_like(u)
     d_a_in, d_a_out, d_gate = np.zeros_like(a_in), np.zeros_like(a_out), np.zeros((b, n))
+    if patch_id is not None:
+        patch_id, g_d = _i32(patch_id), _f64(patch_gate_)
+        c, l_p = patch_id.shape[2], l // m
+        d_pg = np.zeros((b, n, m))
+        for bb in range(b):
+            for i in expert_id[bb]:
+                pid = patch_id[bb, i]
+                T = (pid[:, None] * l_p + np.arange(l_p)[None, :]).reshape(-1)
+                ge = g[bb, i] if flags & GATE_EXPERT else 1.0
+                gp = np.repeat(g_d[bb, i, pid], l_p) if flags & GATE_PATCH else np.ones(c * l_p)
+                up = u[bb, T]
+                z = up @ a_in[i]
+                sig = 1.0 / (1.0 + np.exp(-z))
+                v = z * sig
+                d_y_raw = d_out[bb, T]                       # dL/d(w_t * y_t), y = v A^O
+                row_dot = np.sum((d_y_raw @ a_out[i].T) * v, axis=1)   # dL/dw_t
+                if flags & GATE_EXPERT:
+                    d_gate[bb, i] = np.sum(row_dot * gp)
+                if flags & GATE_PATCH:
+                    d_pg[bb, i, pid] = ge * row_dot.reshape(c, l_p).sum(axis=1)
+                d_y = d_y_raw * (ge * gp)[:, None]
+                d_a_out[i] += v.T @ d_y
+                d_z = (d_y @ a_out[i].T) * (sig * (1.0 + z * (1.0 - sig)))
+                d_a_in[i] += up.T @ d_z
+                np.add.at(d_u[bb], T, d_z @ a_in[i].T)
+        return UomeGrads(d_u, d_a_in, d_a_out, d_gate, d_pg)
     for bb in range(b):
         for i in expert_id[bb]:
             w = g[bb, i] if flags & GATE_EXPERT else 1.0

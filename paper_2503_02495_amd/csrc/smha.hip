@@ -421,6 +421,7 @@ template <typename T> static QkvProblem<T> make_qkv(const SmhaArgs &a)
     qp.l_p = a.l / a.m; qp.l_a = a.c * qp.l_p; qp.d_h = a.d_h;
     qp.q_scale = 1.0f;
     qp.nout = 3;
+    qp.q32 = nullptr;
     return qp;
 }
 

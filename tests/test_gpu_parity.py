@@ -495,6 +495,23 @@ def test_layer_backward_parity(name, fa, rope_dim):
     assert max(errs.values()) <= LAYER_BWD_TOL and max(fro.values()) <= LAYER_BWD_FRO_TOL
 
 
+def test_layer_backward_is_deterministic_and_reusable():
+    """Two calls on the same buffers give the same bits (fixed summation orders, no atomics), also
+    after the scratch has been used by a forward call in between."""
+    cfg = synth.CONFIGS["lm"]
+    inp = synth.make_inputs(cfg)
+    dev = DeviceLayer(inp, R | GE | GP, R | GE)
+    d_out = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
+    dev.layer_forward()
+    first = {k: v.clone() for k, v in dev.layer_backward(d_out).items()}
+    dev.layer_forward()
+    second = dev.layer_backward(d_out)
+    torch.cuda.synchronize()
+    for k in first:
+        assert torch.equal(first[k].view(torch.int16), second[k].view(torch.int16)), k
+        assert torch.isfinite(first[k].float()).all(), k
+
+
 # --------------------------------------------------------------------------- single-mode SMHA blocks
 @pytest.mark.parametrize("mode", ["expert_only", "data_only"])
 @pytest.mark.parametrize("name", ["bf16_ragged", "lm"])

@@ -55,3 +55,39 @@ def test_unselected_experts_get_no_gradient():
             assert gr.d_gate[bb, i] == 0.0
     # without the gate flag the gate has no influence
     assert not oracle.uome_backward(u, a_in, a_out, eid, gate, d_out, R).d_gate.any()
+
+
+GP = oracle.GATE_PATCH
+
+
+@pytest.mark.parametrize("flags", [0, R | GE, R | GP, R | GE | GP])
+def test_data_selection_backward_matches_finite_differences(flags):
+    """Data-selection mode: each expert sees its own patches (two experts of a sample may share one)."""
+    r = np.random.default_rng(21)
+    b, l, d, n, k, d_e, m, c = 2, 12, 5, 4, 2, 4, 4, 2
+    u = r.standard_normal((b, l, d))
+    a_in = r.standard_normal((n, d, d_e)) * 0.5
+    a_out = r.standard_normal((n, d_e, d)) * 0.5
+    eid = np.stack([np.sort(r.choice(n, k, replace=False)) for _ in range(b)]).astype(np.int32)
+    pid = np.stack([[np.sort(r.choice(m, c, replace=False)) for _ in range(n)] for _ in range(b)]).astype(np.int32)
+    pid[0, eid[0, 0]] = pid[0, eid[0, 1]]                      # a collision: both experts pick the same patches
+    ge, gp = r.uniform(0.2, 1.0, (b, n)), r.uniform(0.2, 1.0, (b, n, m))
+    d_out = r.standard_normal((b, l, d))
+    arrs = dict(u=u, a_in=a_in, a_out=a_out, ge=ge, gp=gp)
+
+    def loss():
+        return float(np.sum(oracle.uome(u, a_in, a_out, eid, ge, flags, pid, gp, m) * d_out))
+
+    gr = oracle.uome_backward(u, a_in, a_out, eid, ge, d_out, flags, pid, gp, m)
+    eps = 1e-6
+    for name, grad in (("u", gr.d_u), ("a_in", gr.d_a_in), ("a_out", gr.d_a_out), ("ge", gr.d_gate), ("gp", gr.d_patch_gate)):
+        flat = arrs[name].reshape(-1)
+        for idx in r.choice(flat.size, min(flat.size, 30), replace=False):
+            keep = flat[idx]
+            flat[idx] = keep + eps
+            lp = loss()
+            flat[idx] = keep - eps
+            lm = loss()
+            flat[idx] = keep
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - grad.reshape(-1)[idx]) <= 2e-6 * max(1.0, abs(fd)), (name, idx, fd, grad.reshape(-1)[idx])
