@@ -191,26 +191,31 @@ int uoe_uome_down(const uoe_block_desc *blk, const void *hidden, const void *a_o
                   const int32_t *expert_idx, void *out, void *hip_stream);
 
 /*
- * Backward pass of uoe_uome_forward in expert-selection mode (the derivatives of Eq. 38-40 with
- * Eq. 24-26; the selection of Eq. 22 is piecewise constant and passes no gradient).  Given
- * d_out = dL/d(out) [b,l,d] and the forward inputs, writes
- *   d_u     [b,l,d]     = (d_out, with UOE_FLAG_RESIDUAL) + sum_s (d_out A^O_i^T * gate * SiLU'(u A^I_i)) A^I_i^T
- *   d_a_in  [n,d,d_e]   gradient of A^I, summed over the samples that selected the expert; zero
- *                       for an expert no sample selected
- *   d_a_out [n,d_e,d]   the same for A^O
+ * Backward pass of uoe_uome_forward (the derivatives of Eq. 37-40; the selections of Eq. 17 and
+ * Eq. 22 are piecewise constant and pass no gradient).  The mode follows the forward call:
+ * patch_idx NULL (needs blk->c == blk->m, no UOE_FLAG_GATE_PATCH) = expert selection, patch_idx
+ * [b,n,c] = data selection (needs blk->c < blk->m).  Given d_out = dL/d(out) [b,l,d] and the forward
+ * inputs, writes, all in full and in the storage dtype unless noted:
+ *   d_u     [b,l,d]     = (d_out, with UOE_FLAG_RESIDUAL) + the gradient through every active expert
+ *                         (data selection: scattered back onto the tokens of its patches)
+ *   d_a_in  [n,d,d_e], d_a_out [n,d_e,d]   summed over the samples that selected the expert; zero
+ *                         for an expert no sample selected
  *   d_gate  [b,n] fp32  dL/d(expert_gate[b,i]) for the sample's active experts, zero elsewhere and
  *                       everywhere without UOE_FLAG_GATE_EXPERT; may be NULL
- * all in full, in the storage dtype unless noted.  Intermediates (u A^I, d_out A^O^T) are kept in
- * the storage dtype between the kernels.  This build: bf16 storage only, l, d and d_e multiples
- * of 32, b <= 128; otherwise UOE_ERR_UNSUPPORTED.  Outputs must not alias inputs.  Deterministic:
- * fixed summation order, no atomics.  ws: at least uoe_uome_backward_workspace_bytes(blk) bytes
- * (0 = descriptor invalid or unsupported).
+ *   d_patch_gate [b,n,m] fp32 (data selection) dL/d(patch_gate) on the selected patches of the
+ *                       active experts, zero elsewhere and without UOE_FLAG_GATE_PATCH; may be NULL
+ * Intermediates (u A^I, d_out A^O^T) are kept in the storage dtype between the kernels.  This
+ * build: bf16 storage only, l, d and d_e multiples of 32, b <= 128, and l_p a multiple of 32 in
+ * data-selection mode; otherwise UOE_ERR_UNSUPPORTED.  Outputs must not alias inputs.
+ * Deterministic: fixed summation order, no atomics.  ws: at least
+ * uoe_uome_backward_workspace_bytes(blk) bytes (0 = descriptor invalid or unsupported).
  */
 size_t uoe_uome_backward_workspace_bytes(const uoe_block_desc *blk);
 int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
-                      const int32_t *expert_idx, const float *expert_gate, const void *d_out,
-                      void *d_u, void *d_a_in, void *d_a_out, float *d_gate, void *ws,
-                      size_t ws_bytes, void *hip_stream);
+                      const int32_t *expert_idx, const float *expert_gate,
+                      const int32_t *patch_idx, const float *patch_gate, const void *d_out,
+                      void *d_u, void *d_a_in, void *d_a_out, float *d_gate, float *d_patch_gate,
+                      void *ws, size_t ws_bytes, void *hip_stream);
 
 typedef struct {
     const void *w_expert, *w_b, *w_a, *wq, *wk, *wv, *wo;
@@ -312,7 +317,8 @@ typedef struct {
  *   dwa, d_a_in, d_a_out: gradients of the block weights; dra / drm: gradients of the routers'
  *       weights (required when the block has a router; a router's gate flag must then be set,
  *       otherwise its weights have no influence on the output: UOE_ERR_INVALID_ARG).
- * Limits: those of the four calls; the UoME block in expert-selection mode.  ws: at least
+ * Limits: those of the four calls.  A UoME block with c < m runs in data-selection mode as in the
+ * forward call (wm->w_b / wm->w_a and routing_m->patch_idx required).  ws: at least
  * uoe_layer_backward_workspace_bytes(smha, uome) bytes (0 = invalid or unsupported).
  */
 size_t uoe_layer_backward_workspace_bytes(const uoe_block_desc *smha, const uoe_block_desc *uome);

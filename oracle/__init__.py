@@ -526,8 +526,9 @@ class LayerGrads:
 
 
 def layer_backward(inp, fwd: LayerResult, d_out, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
-                   flags_m: int = RESIDUAL | GATE_EXPERT, rope_dim: int = 0, gates_a=None, gate_m=None) -> LayerGrads:
-    """Gradients of layer_forward (expert-selection UoME) for d_out = dL/d(out): the chain rule through
+                   flags_m: int = RESIDUAL | GATE_EXPERT, rope_dim: int = 0, gates_a=None, gate_m=None,
+                   patch_gate_m=None) -> LayerGrads:
+    """Gradients of layer_forward for d_out = dL/d(out): the chain rule through
     out = UoME(u; routers on u), u = SMHA(x; routers on x), the selections held constant.
 
     `fwd` is the forward result whose routing is differentiated through; gates_a = (expert, patch)
@@ -536,13 +537,17 @@ def layer_backward(inp, fwd: LayerResult, d_out, flags_a: int = RESIDUAL | GATE_
     ra, rm = fwd.routing_a, fwd.routing_m
     ge_a, gp_a = (ra.expert_gate, ra.patch_gate) if gates_a is None else gates_a
     ge_m = rm.expert_gate if gate_m is None else gate_m
-    gm = uome_backward(fwd.u, inp.a_in, inp.a_out, rm.expert_id, ge_m, d_out, flags_m)
-    d_u = gm.d_u.copy()
-    if inp.m_w_expert is not None:
-        rgm = route_backward(fwd.u, inp.m_w_expert, None, None, ge_m, None, gm.d_gate, None)
-        d_u += rgm.d_x
+    if getattr(cfg, "m_m", 1) > 1:   # UoME with patch-wise data selection: its data router is live too
+        gp_m = rm.patch_gate if patch_gate_m is None else patch_gate_m
+        gm = uome_backward(fwd.u, inp.a_in, inp.a_out, rm.expert_id, ge_m, d_out, flags_m, rm.patch_id, gp_m, cfg.m_m)
+        rgm = route_backward(fwd.u, inp.m_w_expert, inp.m_w_b, inp.m_w_a, ge_m, gp_m, gm.d_gate, gm.d_patch_gate)
     else:
-        rgm = RouteGrads(np.zeros_like(d_u), None, None, None)
+        gm = uome_backward(fwd.u, inp.a_in, inp.a_out, rm.expert_id, ge_m, d_out, flags_m)
+        if inp.m_w_expert is not None:
+            rgm = route_backward(fwd.u, inp.m_w_expert, None, None, ge_m, None, gm.d_gate, None)
+        else:
+            rgm = RouteGrads(np.zeros_like(gm.d_u), None, None, None)
+    d_u = gm.d_u + rgm.d_x
     ga = smha_backward(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ge_a, ra.patch_id, gp_a, cfg.m, d_u,
                        flags_a, rope_dim)
     rga = route_backward(inp.x, inp.a_w_expert, inp.a_w_b, inp.a_w_a, ge_a, gp_a, ga.d_expert_gate, ga.d_patch_gate)

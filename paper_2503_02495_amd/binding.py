@@ -85,7 +85,7 @@ def lib():
         L.uoe_uome_forward.argtypes = [D] + [P] * 8 + [P, S, P]
         L.uoe_uome_backward_workspace_bytes.argtypes = [D]
         L.uoe_uome_backward_workspace_bytes.restype = S
-        L.uoe_uome_backward.argtypes = [D] + [P] * 10 + [P, S, P]
+        L.uoe_uome_backward.argtypes = [D] + [P] * 13 + [P, S, P]
         L.uoe_smha_backward_workspace_bytes.argtypes = [D]
         L.uoe_smha_backward_workspace_bytes.restype = S
         L.uoe_smha_backward.argtypes = [D, P, ctypes.POINTER(SmhaWeights), P, P, P, P, P, P,
@@ -205,10 +205,11 @@ def uome_backward_workspace_bytes(blk) -> int:
     return int(lib().uoe_uome_backward_workspace_bytes(_ref(blk)))
 
 
-def uome_backward(blk, u, a_in, a_out, expert_idx, expert_gate, d_out, d_u, d_a_in, d_a_out, d_gate, ws,
-                  stream=None, check=True, ws_bytes=None) -> int:
+def uome_backward(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_gate, d_out, d_u, d_a_in, d_a_out,
+                  d_gate, d_patch_gate, ws, stream=None, check=True, ws_bytes=None) -> int:
     st = lib().uoe_uome_backward(_ref(blk), _ptr(u), _ptr(a_in), _ptr(a_out), _ptr(expert_idx), _ptr(expert_gate),
-                                 _ptr(d_out), _ptr(d_u), _ptr(d_a_in), _ptr(d_a_out), _ptr(d_gate), _ptr(ws),
+                                 _ptr(patch_idx), _ptr(patch_gate), _ptr(d_out), _ptr(d_u), _ptr(d_a_in),
+                                 _ptr(d_a_out), _ptr(d_gate), _ptr(d_patch_gate), _ptr(ws),
                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_uome_backward", check)
 

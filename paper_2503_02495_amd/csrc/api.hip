@@ -97,7 +97,8 @@ size_t uome_ws(const uoe_block_desc *d) { return uome_ws_layout(d).total; }
 // backward pass of the UoME block: Z, dH, dZ [b,l,k*d_e]; dZ^T, H^T [b,k*d_e,l]; the two transposed
 // weight tensors; split-K tiles of one weight gradient; partial sums of the gate gradient
 struct UomeBwdWs {
-    size_t z, dh, dz, dz_t, h_t, a_in_t, a_out_t, partial, gpart, total;
+    size_t z, dh, dz, dz_t, h_t, a_in_t, a_out_t, partial, gpart, rt, total;
+    int splits;
 };
 UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
 {
@@ -113,9 +114,14 @@ UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
     w.h_t = off; off += act;
     w.a_in_t = off; off += wt;
     w.a_out_t = off; off += wt;
+    // data-selection mode (c < m) works on at most as many rows (units * l_a <= b * k * l) in the same
+    // buffers; its weight gradients are cut by (unit, pick) segments instead of token ranges
+    w.splits = d->c < d->m ? smha_backward_splits(d->b, d->n, d->k, d->c)
+                           : uome_backward_splits(d->b, d->l, d->d, d->n, d->k, d->width);
     w.partial = off;
-    off += up((size_t)d->n * uome_backward_splits(d->b, d->l, d->d, d->n, d->k, d->width) * d->d * d->width * sizeof(float));
+    off += up((size_t)d->n * w.splits * d->d * d->width * sizeof(float));
     w.gpart = off; off += up((size_t)d->b * d->k * uome_backward_gate_chunks(d->l, d->width) * sizeof(float));
+    w.rt = off; off += up((size_t)d->b * d->k * d->l * sizeof(float));
     w.total = off;
     return w;
 }
@@ -123,9 +129,9 @@ int check_uome_bwd(const uoe_block_desc *blk)
 {
     const int rc = check_desc(blk, DESC_UOME);
     if (rc != UOE_OK) return rc;
-    if (blk->c != blk->m || (blk->flags & UOE_FLAG_GATE_PATCH)) return UOE_ERR_UNSUPPORTED;
     if (blk->dtype != UOE_BF16) return UOE_ERR_UNSUPPORTED;
     if (blk->l % 32 || blk->d % 32 || blk->width % 32 || blk->b > 128) return UOE_ERR_UNSUPPORTED;
+    if (blk->c < blk->m && (blk->l / blk->m) % 32) return UOE_ERR_UNSUPPORTED;
     return UOE_OK;
 }
 
@@ -438,13 +444,18 @@ size_t uoe_uome_backward_workspace_bytes(const uoe_block_desc *blk)
 }
 
 int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
-                      const int32_t *expert_idx, const float *expert_gate, const void *d_out, void *d_u,
-                      void *d_a_in, void *d_a_out, float *d_gate, void *ws, size_t ws_bytes, void *hip_stream)
+                      const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
+                      const float *patch_gate, const void *d_out, void *d_u, void *d_a_in, void *d_a_out, float *d_gate,
+                      float *d_patch_gate, void *ws, size_t ws_bytes, void *hip_stream)
 {
     const int rc = check_uome_bwd(blk);
     if (rc != UOE_OK) return rc;
     if (!u || !a_in || !a_out || !expert_idx || !d_out || !d_u || !d_a_in || !d_a_out) return UOE_ERR_INVALID_ARG;
     if ((blk->flags & UOE_FLAG_GATE_EXPERT) && !expert_gate) return UOE_ERR_INVALID_ARG;
+    // mode as in uoe_uome_forward: patch_idx given = data selection, else c == m and no patch gate
+    if ((patch_idx == nullptr) != (blk->c == blk->m)) return UOE_ERR_INVALID_ARG;
+    if (!patch_idx && (blk->flags & UOE_FLAG_GATE_PATCH)) return UOE_ERR_INVALID_ARG;
+    if ((blk->flags & UOE_FLAG_GATE_PATCH) && !patch_gate) return UOE_ERR_INVALID_ARG;
     if (!aligned16(u) || !aligned16(a_in) || !aligned16(a_out) || !aligned16(d_out) || !aligned16(d_u) ||
         !aligned16(d_a_in) || !aligned16(d_a_out))
         return UOE_ERR_INVALID_ARG;
@@ -460,7 +471,9 @@ int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in
     a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
     a.partial = reinterpret_cast<float *>(at(ws, w.partial));
     a.gchunks = uome_backward_gate_chunks(blk->l, blk->width);
-    a.splits = uome_backward_splits(blk->b, blk->l, blk->d, blk->n, blk->k, blk->width);
+    a.splits = w.splits;
+    a.patch_idx = patch_idx; a.patch_gate = patch_gate; a.d_patch_gate = d_patch_gate;
+    a.rt = reinterpret_cast<float *>(at(ws, w.rt)); a.m = blk->m; a.c = blk->c;
     return launch_uome_backward(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
 }
 
@@ -661,18 +674,25 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
 
 // workspace of the layer backward: [u][d_u][gate gradients][the largest of the stages' own scratch]
 struct LayerBwdWs {
-    size_t u, d_u, d_gate_m, d_gate_a, d_pgate_a, stage, stage_bytes, total;
+    size_t u, d_u, d_gate_m, d_pgate_m, d_gate_a, d_pgate_a, stage, stage_bytes, total;
 };
+// the descriptor the UoME routers ran with: one patch = the sample in expert-selection mode
+static uoe_block_desc uome_route_desc(const uoe_block_desc *uome)
+{
+    uoe_block_desc um = *uome;
+    if (um.c == um.m) um.m = um.c = 1;
+    return um;
+}
 static LayerBwdWs layer_bwd_ws(const uoe_block_desc *smha, const uoe_block_desc *uome)
 {
     LayerBwdWs w;
     const size_t act = up((size_t)smha->b * smha->l * smha->d * elem_size(smha->dtype));
-    uoe_block_desc um = *uome;
-    um.m = um.c = 1;
+    const uoe_block_desc um = uome_route_desc(uome);
     size_t off = 0;
     w.u = off; off += act;
     w.d_u = off; off += act;
     w.d_gate_m = off; off += up((size_t)uome->b * uome->n * sizeof(float));
+    w.d_pgate_m = off; off += up((size_t)uome->b * uome->n * uome->m * sizeof(float));
     w.d_gate_a = off; off += up((size_t)smha->b * smha->n * sizeof(float));
     w.d_pgate_a = off; off += up((size_t)smha->b * smha->n * smha->m * sizeof(float));
     size_t stage = smha_ws(smha).total;
@@ -687,11 +707,10 @@ static int check_layer_bwd(const uoe_block_desc *smha, const uoe_block_desc *uom
 {
     int rc = check_smha_bwd(smha);
     if (rc != UOE_OK) return rc;
-    rc = check_uome_bwd(uome);  // expert-selection UoME only
+    rc = check_uome_bwd(uome);
     if (rc != UOE_OK) return rc;
     if (smha->b != uome->b || smha->l != uome->l || smha->d != uome->d || smha->dtype != uome->dtype) return UOE_ERR_INVALID_ARG;
-    uoe_block_desc um = *uome;
-    um.m = um.c = 1;
+    const uoe_block_desc um = uome_route_desc(uome);
     if ((rc = check_route_bwd(smha)) != UOE_OK) return rc;
     return check_route_bwd(&um);
 }
@@ -713,19 +732,24 @@ int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa, c
     if (rc != UOE_OK) return rc;
     if (!wa || !wm || !x || !routing_a || !routing_m || !d_out || !d_x || !dwa || !d_a_in || !d_a_out) return UOE_ERR_INVALID_ARG;
     if (!routing_a->expert_idx || !routing_a->patch_idx || !routing_m->expert_idx) return UOE_ERR_INVALID_ARG;
-    const bool route_a = wa->w_expert || wa->w_b, route_m = wm->w_expert != nullptr;
+    const bool uome_ds = uome->c < uome->m;
+    if (uome_ds && (!wm->w_b || !wm->w_a || !routing_m->patch_idx)) return UOE_ERR_INVALID_ARG;
+    if (!uome_ds && (wm->w_b || wm->w_a)) return UOE_ERR_INVALID_ARG;
+    const bool route_a = wa->w_expert || wa->w_b, route_m = wm->w_expert || wm->w_b;
     if (route_a && !dra) return UOE_ERR_INVALID_ARG;
     if (route_m && !drm) return UOE_ERR_INVALID_ARG;
     // a router's gate must be an input of its block for its gradient to exist
     if (wa->w_expert && (!(smha->flags & UOE_FLAG_GATE_EXPERT) || !routing_a->expert_gate)) return UOE_ERR_INVALID_ARG;
     if (wa->w_b && (!(smha->flags & UOE_FLAG_GATE_PATCH) || !routing_a->patch_gate)) return UOE_ERR_INVALID_ARG;
-    if (route_m && (!(uome->flags & UOE_FLAG_GATE_EXPERT) || !routing_m->expert_gate)) return UOE_ERR_INVALID_ARG;
+    if (wm->w_expert && (!(uome->flags & UOE_FLAG_GATE_EXPERT) || !routing_m->expert_gate)) return UOE_ERR_INVALID_ARG;
+    if (wm->w_b && (!(uome->flags & UOE_FLAG_GATE_PATCH) || !routing_m->patch_gate)) return UOE_ERR_INVALID_ARG;
     const LayerBwdWs w = layer_bwd_ws(smha, uome);
     if (!ws || ws_bytes < w.total || !aligned16(ws)) return UOE_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     void *stage = at(ws, w.stage);
     void *d_u = at(ws, w.d_u);
     float *d_gate_m = reinterpret_cast<float *>(at(ws, w.d_gate_m));
+    float *d_pgate_m = reinterpret_cast<float *>(at(ws, w.d_pgate_m));
     float *d_gate_a = reinterpret_cast<float *>(at(ws, w.d_gate_a));
     float *d_pgate_a = reinterpret_cast<float *>(at(ws, w.d_pgate_a));
 
@@ -737,14 +761,15 @@ int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa, c
         u = u_ws;
     }
     // UoME block and its router: d_out -> d_u
-    rc = uoe_uome_backward(uome, u, wm->a_in, wm->a_out, routing_m->expert_idx, routing_m->expert_gate, d_out, d_u, d_a_in,
-                           d_a_out, d_gate_m, stage, w.stage_bytes, hip_stream);
+    rc = uoe_uome_backward(uome, u, wm->a_in, wm->a_out, routing_m->expert_idx, routing_m->expert_gate,
+                           uome_ds ? routing_m->patch_idx : nullptr, uome_ds ? routing_m->patch_gate : nullptr, d_out, d_u,
+                           d_a_in, d_a_out, d_gate_m, uome_ds ? d_pgate_m : nullptr, stage, w.stage_bytes, hip_stream);
     if (rc != UOE_OK) return rc;
     if (route_m) {
-        uoe_block_desc um = *uome;
-        um.m = um.c = 1;
-        rc = uoe_route_backward(&um, u, wm->w_expert, nullptr, nullptr, routing_m->expert_gate, nullptr, d_gate_m, nullptr,
-                                d_u, drm->d_w_expert, nullptr, nullptr, stage, w.stage_bytes, hip_stream);
+        const uoe_block_desc um = uome_route_desc(uome);
+        rc = uoe_route_backward(&um, u, wm->w_expert, wm->w_b, wm->w_a, routing_m->expert_gate, routing_m->patch_gate,
+                                d_gate_m, d_pgate_m, d_u, drm->d_w_expert, drm->d_w_b, drm->d_w_a, stage, w.stage_bytes,
+                                hip_stream);
         if (rc != UOE_OK) return rc;
     }
     // SMHA block and its routers: d_u -> d_x

@@ -141,6 +141,13 @@ struct UomeBwdArgs {
     float *gpart;                             // [b, k, gchunks] partial sums of d_gate
     float *partial;                           // [n*splits, d_e, d] split-K tiles of a weight gradient
     int gchunks, splits;
+    // data-selection mode (patch_idx != NULL): units = (sample, slot) with l_a = c*l/m gathered rows;
+    // z, dh, dz are [units, l_a, d_e], dz_t and h_t [units, d_e, l_a]
+    const int32_t *patch_idx;
+    const float *patch_gate;                  // NULL when GATE_PATCH is off
+    float *d_patch_gate;                      // [b,n,m] or NULL
+    float *rt;                                // [units, l_a]: dL/d(weight of row t)
+    int m, c;
 };
 
 // Backward pass of the SMHA block (bf16 storage, MFMA shapes only)
@@ -197,6 +204,9 @@ hipError_t launch_uome_down(const UomeArgs &a, bool bf16, hipStream_t st);  // E
 hipError_t launch_uome_ds(const UomeDsArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st);
 hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st);
+// gate gradients of the units of a data-selected block from the row terms a.rt (uses the routing
+// fields of a.f, a.flags, the gates and the two outputs, which it clears first)
+hipError_t launch_unit_gate_grads(const SmhaBwdArgs &a, hipStream_t st);
 hipError_t launch_route_backward(const RouteBwdArgs &a, bool bf16, hipStream_t st);
 int smha_backward_splits(int b, int n, int k, int c);
 int uome_backward_gate_chunks(int l, int d_e);

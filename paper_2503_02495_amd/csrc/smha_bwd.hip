@@ -431,6 +431,23 @@ template <int DH> static hipError_t launch_attention_bwd_dh(const AttnBwdArgs &a
     return hipGetLastError();
 }
 
+hipError_t launch_unit_gate_grads(const SmhaBwdArgs &a, hipStream_t st)
+{
+    const SmhaArgs &f = a.f;
+    SmhaBwdPrepArgs pa{};  // only its clearing blocks run: n = 0 puts them at z = 0
+    pa.zero[0] = a.d_expert_gate; pa.zero_count[0] = (long)f.b * f.n;
+    pa.zero[1] = a.d_patch_gate; pa.zero_count[1] = (long)f.b * f.n * f.m;
+    pa.n = 0; pa.d = f.d; pa.d_h = 32;
+    hipLaunchKernelGGL(smha_bwd_prep_kernel, dim3(8, 8, 1), dim3(256), 0, st, pa);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    if (a.flags & (F_GATE_EXPERT | F_GATE_PATCH)) {
+        hipLaunchKernelGGL(smha_bwd_gate_kernel, dim3(f.b * f.k), dim3(256), 0, st, a);
+        err = hipGetLastError();
+    }
+    return err;
+}
+
 int smha_backward_splits(int b, int n, int k, int c)
 {
     // parts of an expert's (unit, pick) list: about 8 segments each, at most 8 parts, and never more

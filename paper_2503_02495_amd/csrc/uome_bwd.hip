@@ -147,9 +147,12 @@ __global__ __launch_bounds__(256) void uome_bwd_gate_kernel(UomeBwdArgs a)
     if (tid == 0) a.d_gate[(size_t)bb * a.n + clampi(a.expert_idx[bb * a.k + s], a.n)] = red[0];
 }
 
+hipError_t launch_uome_ds_backward(const UomeBwdArgs &a, hipStream_t st);
+
 hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
 {
     typedef bf16_t T;
+    if (a.patch_idx) return launch_uome_ds_backward(a, st);
     hipError_t err;
     const int width = a.k * a.d_e;
     // weights with K contiguous for the two data-gradient GEMMs
@@ -197,6 +200,139 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     WgradProblem<T> wi = wo;  // (dA^I_i)^T = sum dZ_{b,s}^T u_b, stored back as [d, d_e] by the reduction
     wi.left_t = static_cast<const T *>(a.dz_t); wi.right = static_cast<const T *>(a.u);
     if ((err = launch_gemm_dma_auto(wi, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
+    ra.dst[0] = static_cast<uint16_t *>(a.d_a_in); ra.transposed = 1;
+    return launch_wgrad_reduce(ra, a.n, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Data-selection mode (Eq. 37-40 with Eq. 12-18): expert i of an active unit sees only the l_a
+// gathered rows of its c patches.  Same chain as above per unit, with the gathers folded into
+// operand addressing (the forward's gathered projection for Z and dH, the output-stationary
+// per-patch contraction for d_u, patch-gathered right operands for the weight gradients) and the
+// row weight w_t = expert gate and/or the gate of the row's patch.
+
+// Elementwise middle, data-selection mode.  Block = 32 rows of one unit; it walks the d_e columns in
+// tiles of 64 (one 8-element piece per thread and tile), writes dZ token-major, dZ^T and H^T
+// token-minor through LDS tiles, and the rows' dL/dw_t = sum_j dH_raw * SiLU(Z).
+__global__ __launch_bounds__(256) void uome_ds_bwd_mid_kernel(UomeBwdArgs a)
+{
+    __shared__ __align__(16) uint16_t tz[64][40], th[64][40];
+    const int g = blockIdx.y, tid = threadIdx.x, r = tid >> 3, pc = tid & 7;
+    const int l_p = a.l / a.m, l_a = a.c * l_p, row = blockIdx.x * 32 + r;
+    const int bb = g / a.k, i = clampi(a.expert_idx[g], a.n);
+    float w = 1.0f;
+    if ((a.flags & F_GATE_EXPERT) && a.expert_gate) w *= a.expert_gate[(size_t)bb * a.n + i];
+    if ((a.flags & F_GATE_PATCH) && a.patch_gate) {
+        const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + row / l_p], a.m);
+        w *= a.patch_gate[((size_t)bb * a.n + i) * a.m + p];
+    }
+    const bf16_t *z = static_cast<const bf16_t *>(a.z), *dh = static_cast<const bf16_t *>(a.dh);
+    bf16_t *dz = static_cast<bf16_t *>(a.dz);
+    float part = 0.f;
+    for (int c0 = 0; c0 < a.d_e; c0 += 64) {
+        const int col = c0 + pc * 8;
+        float zv[8] = {0, 0, 0, 0, 0, 0, 0, 0}, dv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        const size_t at = ((size_t)g * l_a + row) * a.d_e + col;
+        if (col < a.d_e) {
+            load8(z + at, zv);
+            load8(dh + at, dv);
+        }
+        uint32_t oz[4];
+#pragma unroll
+        for (int q = 0; q < 8; q += 2) {
+            float dzv[2], hv[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float sig = 1.0f / (1.0f + __expf(-zv[q + e]));
+                const float v = zv[q + e] * sig;
+                part = fmaf(dv[q + e], v, part);
+                hv[e] = v * w;
+                dzv[e] = dv[q + e] * w * (sig * (1.0f + zv[q + e] * (1.0f - sig)));
+            }
+            oz[q / 2] = pack2_bf16(dzv[0], dzv[1]);
+            const uint32_t oh = pack2_bf16(hv[0], hv[1]);
+            tz[pc * 8 + q][r] = (uint16_t)(oz[q / 2] & 0xFFFFu);
+            tz[pc * 8 + q + 1][r] = (uint16_t)(oz[q / 2] >> 16);
+            th[pc * 8 + q][r] = (uint16_t)(oh & 0xFFFFu);
+            th[pc * 8 + q + 1][r] = (uint16_t)(oh >> 16);
+        }
+        if (col < a.d_e) *reinterpret_cast<uint4 *>(dz + at) = make_uint4(oz[0], oz[1], oz[2], oz[3]);
+        __syncthreads();
+        const int tc = tid >> 2, tp = tid & 3;  // column of the tile, 8 consecutive rows
+        if (c0 + tc < a.d_e) {
+            const size_t to = ((size_t)g * a.d_e + c0 + tc) * l_a + blockIdx.x * 32 + tp * 8;
+            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.dz_t) + to) = *reinterpret_cast<const uint4 *>(&tz[tc][tp * 8]);
+            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(a.h_t) + to) = *reinterpret_cast<const uint4 *>(&th[tc][tp * 8]);
+        }
+        __syncthreads();
+    }
+    part += __shfl_xor(part, 1, 64);
+    part += __shfl_xor(part, 2, 64);
+    part += __shfl_xor(part, 4, 64);
+    if (pc == 0) a.rt[(size_t)g * l_a + row] = part;
+}
+
+hipError_t launch_uome_ds_backward(const UomeBwdArgs &a, hipStream_t st)
+{
+    typedef bf16_t T;
+    hipError_t err;
+    const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
+    {
+        const int tiles = ((a.d + 31) / 32) * ((a.d_e + 31) / 32);
+        hipLaunchKernelGGL(transpose_weights_kernel, dim3(tiles, 1, 2 * a.n), dim3(256), 0, st,
+                           static_cast<const uint16_t *>(a.a_out), static_cast<uint16_t *>(a.a_out_t),
+                           static_cast<const uint16_t *>(a.a_in), static_cast<uint16_t *>(a.a_in_t), a.n, a.d, a.d_e);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    // Z = u[T] A^I_i and dH_raw = d_out[T] A^O_i^T: the gathered projection with one output block
+    QkvProblem<T> zp;
+    zp.x = static_cast<const T *>(a.u);
+    zp.wq = zp.wk = zp.wv = static_cast<const T *>(a.a_in);
+    zp.expert_idx = a.expert_idx; zp.patch_idx = a.patch_idx;
+    zp.q = zp.k = zp.v = static_cast<T *>(a.z); zp.q32 = nullptr;
+    zp.l = a.l; zp.d = a.d; zp.n = a.n; zp.kact = a.k; zp.m = a.m; zp.c = a.c;
+    zp.l_p = l_p; zp.l_a = l_a; zp.d_h = a.d_e; zp.q_scale = 1.0f; zp.nout = 1;
+    if ((err = launch_gemm_dma_auto(zp, units, l_a, a.d_e, a.d, st)) != hipSuccess) return err;
+    QkvProblem<T> hp = zp;
+    hp.x = static_cast<const T *>(a.d_out);
+    hp.wq = hp.wk = hp.wv = static_cast<const T *>(a.a_out_t);
+    hp.q = hp.k = hp.v = static_cast<T *>(a.dh);
+    if ((err = launch_gemm_dma_auto(hp, units, l_a, a.d_e, a.d, st)) != hipSuccess) return err;
+
+    hipLaunchKernelGGL(uome_ds_bwd_mid_kernel, dim3(l_a / 32, units), dim3(256), 0, st, a);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+
+    SmhaBwdArgs ga{};  // the unit gate kernel reads its routing fields, the row terms and the gates
+    ga.f.expert_idx = a.expert_idx; ga.f.patch_idx = a.patch_idx;
+    ga.f.b = a.b; ga.f.l = a.l; ga.f.d = a.d; ga.f.n = a.n; ga.f.k = a.k; ga.f.m = a.m; ga.f.c = a.c;
+    ga.expert_gate = a.expert_gate; ga.patch_gate = a.patch_gate; ga.flags = a.flags;
+    ga.d_expert_gate = a.d_gate; ga.d_patch_gate = a.d_patch_gate; ga.rt = a.rt;
+    if ((err = launch_unit_gate_grads(ga, st)) != hipSuccess) return err;
+
+    // d_u = (d_out) + scatter-add of dZ A^I_i^T: the output-stationary per-patch contraction
+    OutProjProblem<T> xp;
+    xp.o = static_cast<const T *>(a.dz); xp.o_lo = nullptr; xp.parts = 1;
+    xp.wo = static_cast<const T *>(a.a_in_t); xp.x = static_cast<const T *>(a.d_out);
+    xp.expert_idx = a.expert_idx; xp.patch_idx = a.patch_idx; xp.inv_cnt = nullptr; xp.inv_ent = nullptr;
+    xp.out = static_cast<T *>(a.d_u);
+    xp.l = a.l; xp.d = a.d; xp.n = a.n; xp.kact = a.k; xp.m = a.m; xp.c = a.c;
+    xp.l_p = l_p; xp.l_a = l_a; xp.d_h = a.d_e; xp.flags = a.flags & F_RESIDUAL;
+    if (l_p <= 32) err = launch_gemm_dma<OutProjProblem<T>, 32, 128, 32, 1, 4, 4, 2>(xp, a.b * a.m, l_p, a.d, st);
+    else err = launch_gemm_dma<OutProjProblem<T>, 64, 128, 32, 2, 2, 4, 2>(xp, a.b * a.m, l_p, a.d, st);
+    if (err != hipSuccess) return err;
+
+    SmhaWgradProblem<T> wp;
+    wp.expert_idx = a.expert_idx; wp.patch_idx = a.patch_idx; wp.partial = a.partial;
+    wp.b = a.b; wp.l = a.l; wp.d = a.d; wp.n = a.n; wp.kact = a.k; wp.m = a.m; wp.c = a.c;
+    wp.l_p = l_p; wp.l_a = l_a; wp.splits = a.splits; wp.M = a.d_e;
+    WgradReduceArgs ra{};
+    ra.partial = a.partial; ra.M = a.d_e; ra.N = a.d; ra.splits = a.splits; ra.parts = 1;
+    wp.left_t = static_cast<const T *>(a.h_t); wp.right = static_cast<const T *>(a.d_out);  // dA^O_i
+    if ((err = launch_gemm_dma_auto(wp, a.n * a.splits, a.d_e, a.d, l_p, st)) != hipSuccess) return err;
+    ra.dst[0] = static_cast<uint16_t *>(a.d_a_out); ra.transposed = 0;
+    if ((err = launch_wgrad_reduce(ra, a.n, st)) != hipSuccess) return err;
+    wp.left_t = static_cast<const T *>(a.dz_t); wp.right = static_cast<const T *>(a.u);     // (dA^I_i)^T
+    if ((err = launch_gemm_dma_auto(wp, a.n * a.splits, a.d_e, a.d, l_p, st)) != hipSuccess) return err;
     ra.dst[0] = static_cast<uint16_t *>(a.d_a_in); ra.transposed = 1;
     return launch_wgrad_reduce(ra, a.n, st);
 }

@@ -103,8 +103,11 @@ class DeviceLayer:
                        self.m_expert_gate if expert_gate is None else expert_gate, patch_idx, patch_gate,
                        self.out if out is None else out, self.ws)
 
-    def uome_backward(self, d_out, expert_idx=None, expert_gate=None, u=None):
-        """Gradients of the expert-selection UoME block; returns (d_u, d_a_in, d_a_out, d_gate)."""
+    def uome_backward(self, d_out, expert_idx=None, expert_gate=None, u=None, patch_idx=None, patch_gate=None):
+        """Gradients of the UoME block; returns (d_u, d_a_in, d_a_out, d_gate) and, for a data-selection
+        block, d_patch_gate as a fifth member."""
+        if self.uome_ds and patch_idx is None:
+            patch_idx, patch_gate = self.m_patch_idx, self.m_patch_gate
         if not hasattr(self, "bwd_ws"):
             nbytes = B.uome_backward_workspace_bytes(self.uome)
             if nbytes == 0:
@@ -113,10 +116,14 @@ class DeviceLayer:
             self.d_u = torch.empty_like(self.x)
             self.d_a_in, self.d_a_out = torch.empty_like(self.a_in), torch.empty_like(self.a_out)
             self.d_gate = torch.empty(self.cfg.b, self.cfg.n_m, dtype=torch.float32, device=self.device)
+            self.d_m_patch_gate = (torch.empty(self.cfg.b, self.cfg.n_m, self.cfg.m_m, dtype=torch.float32, device=self.device)
+                                   if self.uome_ds else None)
         B.uome_backward(self.uome, self.u if u is None else u, self.a_in, self.a_out,
                         self.m_expert_idx if expert_idx is None else expert_idx,
-                        self.m_expert_gate if expert_gate is None else expert_gate, d_out,
-                        self.d_u, self.d_a_in, self.d_a_out, self.d_gate, self.bwd_ws)
+                        self.m_expert_gate if expert_gate is None else expert_gate, patch_idx, patch_gate, d_out,
+                        self.d_u, self.d_a_in, self.d_a_out, self.d_gate, self.d_m_patch_gate, self.bwd_ws)
+        if self.uome_ds:
+            return self.d_u, self.d_a_in, self.d_a_out, self.d_gate, self.d_m_patch_gate
         return self.d_u, self.d_a_in, self.d_a_out, self.d_gate
 
     def smha_backward(self, d_out, expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None):
@@ -153,11 +160,11 @@ class DeviceLayer:
             self.g = {"d_x": like(self.x), "d_wq": like(self.wq), "d_wk": like(self.wk), "d_wv": like(self.wv),
                       "d_wo": like(self.wo), "d_a_w_expert": like(self.a_w_expert), "d_a_w_b": like(self.a_w_b),
                       "d_a_w_a": like(self.a_w_a), "d_a_in": like(self.a_in), "d_a_out": like(self.a_out),
-                      "d_m_w_expert": like(self.m_w_expert)}
+                      "d_m_w_expert": like(self.m_w_expert), "d_m_w_b": like(self.m_w_b), "d_m_w_a": like(self.m_w_a)}
             g = self.g
             self.layer_dwa = B.smha_weight_grads(g["d_wq"], g["d_wk"], g["d_wv"], g["d_wo"])
             self.layer_dra = B.router_grads(g["d_a_w_expert"], g["d_a_w_b"], g["d_a_w_a"])
-            self.layer_drm = B.router_grads(g["d_m_w_expert"])
+            self.layer_drm = B.router_grads(g["d_m_w_expert"], g["d_m_w_b"], g["d_m_w_a"])
         B.layer_backward(self.smha, self.wa, self.uome, self.wm, self.x, u, self.ra if routing_a is None else routing_a,
                          self.rm if routing_m is None else routing_m, d_out, self.g["d_x"], self.layer_dwa,
                          self.layer_dra, self.g["d_a_in"], self.g["d_a_out"], self.layer_drm, self.layer_bwd_ws)

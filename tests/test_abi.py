@@ -174,12 +174,24 @@ def test_backward_argument_validation():
     assert B.uome_backward_workspace_bytes(B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.F32, fl)) == 0
     assert B.uome_backward_workspace_bytes(B.block_desc(2, 48, 64, 4, 2, 1, 1, 64, B.BF16, fl)) == 0
     ub = lambda *a, **k: B.uome_backward(u, *a, stream=0, check=False, **k)
-    ok = [FAKE, FAKE + 16, FAKE + 32, FAKE, FAKE, FAKE + 48, FAKE + 64, FAKE + 80, FAKE + 96, FAKE, FAKE]
+    ok = [FAKE, FAKE + 16, FAKE + 32, FAKE, FAKE, None, None, FAKE + 48, FAKE + 64, FAKE + 80, FAKE + 96, FAKE, None, FAKE]
     assert ub(*ok, ws_bytes=8) == B.ERR_WORKSPACE
     bad = list(ok); bad[4] = None                       # gate flag without gates
     assert ub(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
-    bad = list(ok); bad[6] = ok[0]                      # d_u aliases u
+    bad = list(ok); bad[8] = ok[0]                      # d_u aliases u
     assert ub(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
+    bad = list(ok); bad[5] = FAKE                       # patch indices on an expert-selection descriptor
+    assert ub(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
+    uds = B.block_desc(2, 128, 64, 4, 2, 4, 2, 64, B.BF16, fl | B.FLAG_GATE_PATCH)     # data selection, l_p = 32
+    assert B.uome_backward_workspace_bytes(uds) > 0
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 8, 2, 64, B.BF16, fl)) == 0    # l_p = 16
+    dsb = lambda *a, **k: B.uome_backward(uds, *a, stream=0, check=False, **k)
+    okd = list(ok); okd[5] = FAKE; okd[6] = FAKE; okd[12] = FAKE
+    assert dsb(*okd, ws_bytes=8) == B.ERR_WORKSPACE
+    bad = list(okd); bad[5] = None                      # c < m needs patch indices
+    assert dsb(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
+    bad = list(okd); bad[6] = None                      # patch gate flag without patch gates
+    assert dsb(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
     # SMHA backward: d_h in {32, 64, 128}, l_p a multiple of 32
     a = B.block_desc(2, 128, 64, 4, 2, 4, 2, 32, B.BF16, fl | B.FLAG_GATE_PATCH)
     assert B.smha_backward_workspace_bytes(a) > 0

@@ -457,13 +457,16 @@ def test_route_backward_parity(name):
 
 # --------------------------------------------------------------------------- layer backward
 @pytest.mark.parametrize("name,fa,rope_dim", [("sb_dh64", R | GE | GP, 0), ("sb_long", R | GE | GP | CA, 16),
-                                              ("lm", R | GE | GP, 0), ("lm", R | GE | GP | CA, 32)])
+                                              ("lm", R | GE | GP, 0), ("lm", R | GE | GP | CA, 32),
+                                              ("ds_bf16_lp32", R | GE | GP, 0), ("ds_lm", R | GE | GP | CA, 32)])
 def test_layer_backward_parity(name, fa, rope_dim):
-    """uoe_layer_backward (UoME backward, its router, SMHA backward, its routers, chained on the
-    device) against the oracle's chain, on the oracle's routing and the fp32-rounded gates."""
-    cfg = SMHA_BWD_CONFIGS[name] if name in SMHA_BWD_CONFIGS else synth.CONFIGS[name]
-    w_std = 0.02 if name in synth.CONFIGS else 0.06
-    fm = R | GE
+    """uoe_layer_backward (UoME backward, its router(s), SMHA backward, its routers, chained on the
+    device) against the oracle's chain, on the oracle's routing and the fp32-rounded gates; the
+    ds_* shapes run the UoME block with patch-wise data selection."""
+    cfg = (SMHA_BWD_CONFIGS.get(name) or DS_BWD_CONFIGS.get(name) or synth.CONFIGS[name])
+    w_std = 0.02 if name in synth.CONFIGS or name == "ds_lm" else 0.06
+    ds = cfg.m_m > 1
+    fm = R | GE | (GP if ds else 0)
     print(f"layer backward {name} fa={fa} rope_dim={rope_dim}", flush=True)
     inp = synth.make_inputs(cfg, w_std=w_std)
     for attr in ("a_w_expert", "m_w_expert"):      # unsaturated expert routers, as in the router backward test
@@ -473,22 +476,29 @@ def test_layer_backward_parity(name, fa, rope_dim):
     d_out = synth.make_upstream_grad(cfg)
     fwd = oracle.layer_forward(inp, fa, fm, rope_dim)
     ra, rm = fwd.routing_a, fwd.routing_m
-    ge_a, gp_a, ge_m = (g.astype(np.float32) for g in (ra.expert_gate, ra.patch_gate, rm.expert_gate))
+    ge_a, gp_a, ge_m, gp_m = (g.astype(np.float32) for g in (ra.expert_gate, ra.patch_gate, rm.expert_gate, rm.patch_gate))
     dev = DeviceLayer(inp, fa, fm, rope_dim=rope_dim)
     i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev.device)
     f32 = lambda a: to_device(a, synth.F32, dev.device)
     keep = [i32(ra.expert_id), f32(ge_a), i32(ra.patch_id), f32(gp_a), i32(rm.expert_id), f32(ge_m)]
+    if ds:
+        keep += [i32(rm.patch_id), f32(gp_m)]
     g = dev.layer_backward(to_device(d_out, cfg.dtype, dev.device), routing_a=B.routing_out(*keep[:4]),
-                           routing_m=B.routing_out(keep[4], keep[5]))
+                           routing_m=B.routing_out(*keep[4:]))
     torch.cuda.synchronize()
-    want = oracle.layer_backward(inp, fwd, d_out, fa, fm, rope_dim, gates_a=(ge_a, gp_a), gate_m=ge_m)
+    want = oracle.layer_backward(inp, fwd, d_out, fa, fm, rope_dim, gates_a=(ge_a, gp_a), gate_m=ge_m, patch_gate_m=gp_m)
     refs = {"d_x": want.d_x, "d_wq": want.smha.d_wq, "d_wk": want.smha.d_wk, "d_wv": want.smha.d_wv, "d_wo": want.smha.d_wo,
-            "d_a_w_expert": want.route_a.d_w_expert, "d_a_w_b": want.route_a.d_w_b.T, "d_a_w_a": want.route_a.d_w_a.T,
+            "d_a_w_expert": want.route_a.d_w_expert, "d_a_w_b": want.route_a.d_w_b, "d_a_w_a": want.route_a.d_w_a,
             "d_a_in": want.uome.d_a_in, "d_a_out": want.uome.d_a_out, "d_m_w_expert": want.route_m.d_w_expert}
+    if ds:
+        refs.update({"d_m_w_b": want.route_m.d_w_b, "d_m_w_a": want.route_m.d_w_a})
     errs, fro = {}, {}
     for nm, r in refs.items():
         y = to_host(g[nm])
-        y = y.T if nm in ("d_a_w_b", "d_a_w_a") else y          # slices = experts / patches
+        if "_w_expert" in nm or "_w_b" in nm or "_w_a" in nm:
+            # a router's weight gradient is driven by the gate gradients, whose error is relative to
+            # the whole gate-gradient tensor, not to one expert's or one patch's share of it
+            y, r = y.reshape(1, -1), r.reshape(1, -1)
         errs[nm], fro[nm] = grad_err(y, r), fro_err(y, r)
     print(f"[layer backward {name} fa={fa}] " + " ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
     print(f"[layer backward {name} fa={fa}] fro " + " ".join(f"{k} {v:.2e}" for k, v in fro.items()), flush=True)
@@ -503,7 +513,7 @@ def test_layer_backward_is_deterministic_and_reusable():
     dev = DeviceLayer(inp, R | GE | GP, R | GE)
     d_out = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
     dev.layer_forward()
-    first = {k: v.clone() for k, v in dev.layer_backward(d_out).items()}
+    first = {k: v.clone() for k, v in dev.layer_backward(d_out).items() if v is not None}
     dev.layer_forward()
     second = dev.layer_backward(d_out)
     torch.cuda.synchronize()
@@ -619,6 +629,45 @@ def ds_w_std(name):
     if name in ("ds_lm", "ds_large"):
         return 0.02
     return 0.2 if cfg.dtype == synth.F32 else 0.06
+
+
+DS_BWD_CONFIGS = {
+    "ds_bf16_lp32": DS_CONFIGS["ds_bf16_lp32"],
+    # l_p = 64, l_a = 192, d_e = 96 (a ragged column tile), experts nobody selects
+    "ds_bwd_tail": small(b=2, l=256, d=96, n_a=2, d_h=32, m=4, c=2, k_a=1, n_m=5, d_e=96, k_m=2, m_m=4, c_m=3,
+                         dtype=synth.BF16),
+    "ds_lm": DS_CONFIGS["ds_lm"],
+}
+
+
+@pytest.mark.parametrize("name", list(DS_BWD_CONFIGS))
+@pytest.mark.parametrize("flags", [0, R | GE | GP])
+def test_uome_data_selection_backward_parity(name, flags):
+    """uoe_uome_backward in data-selection mode against the oracle (pinned by finite differences),
+    on the oracle's routing of the block input x; every gradient in full."""
+    cfg = DS_BWD_CONFIGS[name]
+    print(f"uome data selection backward {name} flags={flags}", flush=True)
+    inp = synth.make_inputs(cfg, w_std=0.02 if name == "ds_lm" else 0.06)
+    d_out = synth.make_upstream_grad(cfg)
+    dev = DeviceLayer(inp, R, flags)
+    ref = oracle.route(inp.x, cfg.n_m, cfg.k_m, cfg.m_m, cfg.c_m, inp.m_w_expert, inp.m_w_b, inp.m_w_a,
+                       inp.noise_m_expert, inp.noise_m_patch)
+    ge, gp = ref.expert_gate.astype(np.float32), ref.patch_gate.astype(np.float32)
+    got = dev.uome_backward(to_device(d_out, cfg.dtype, dev.device), expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
+                            expert_gate=to_device(ge, synth.F32, dev.device), u=dev.x,
+                            patch_idx=torch.from_numpy(ref.patch_id).to(dev.device),
+                            patch_gate=to_device(gp, synth.F32, dev.device))
+    torch.cuda.synchronize()
+    want = oracle.uome_backward(inp.x, inp.a_in, inp.a_out, ref.expert_id, ge, d_out, flags, ref.patch_id, gp, cfg.m_m)
+    refs = (want.d_u, want.d_a_in, want.d_a_out, want.d_gate, want.d_patch_gate)
+    names = ("d_u", "d_a_in", "d_a_out", "d_gate", "d_patch_gate")
+    errs = {nm: grad_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
+    fro = max(fro_err(to_host(g), r) for g, r in zip(got, refs))
+    unused = np.setdiff1d(np.arange(cfg.n_m), ref.expert_id.ravel())
+    assert not np.any(to_host(got[1])[unused]) and not np.any(to_host(got[2])[unused])
+    print(f"[uome ds backward {name} flags={flags}] unused experts {unused.tolist()} " +
+          " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" fro {fro:.2e} (tol {TOL[cfg.dtype]:.0e})", flush=True)
+    assert max(errs.values()) <= TOL[cfg.dtype] and fro <= BWD_FRO_TOL
 
 
 @pytest.mark.parametrize("name", list(DS_CONFIGS))

@@ -12,14 +12,18 @@ R, GE, GP, CA = oracle.RESIDUAL, oracle.GATE_EXPERT, oracle.GATE_PATCH, oracle.C
 
 
 def as_f64(inp):
-    for name in ("x", "a_w_expert", "a_w_b", "a_w_a", "wq", "wk", "wv", "wo", "m_w_expert", "a_in", "a_out"):
-        setattr(inp, name, np.ascontiguousarray(getattr(inp, name), np.float64))
+    for name in ("x", "a_w_expert", "a_w_b", "a_w_a", "wq", "wk", "wv", "wo", "m_w_expert", "a_in", "a_out", "m_w_b", "m_w_a"):
+        if getattr(inp, name, None) is not None:
+            setattr(inp, name, np.ascontiguousarray(getattr(inp, name), np.float64))
     return inp
 
 
-@pytest.mark.parametrize("fa,fm,rope_dim,noise", [(R | GE | GP, R | GE, 0, False), (R | GE | GP | CA, R | GE, 2, True)])
-def test_layer_backward_matches_finite_differences(fa, fm, rope_dim, noise):
-    cfg = synth.small_config(b=2, l=12, d=8, n_a=3, d_h=4, m=4, c=2, k_a=2, n_m=3, d_e=6, k_m=2, router_noise=noise)
+@pytest.mark.parametrize("fa,fm,rope_dim,noise,ds", [(R | GE | GP, R | GE, 0, False, False),
+                                                     (R | GE | GP | CA, R | GE, 2, True, False),
+                                                     (R | GE | GP, R | GE | GP, 0, False, True)])
+def test_layer_backward_matches_finite_differences(fa, fm, rope_dim, noise, ds):
+    extra = dict(m_m=3, c_m=2) if ds else {}         # data-selected UoME: five routers' worth of gates live
+    cfg = synth.small_config(b=2, l=12, d=8, n_a=3, d_h=4, m=4, c=2, k_a=2, n_m=3, d_e=6, k_m=2, router_noise=noise, **extra)
     inp = as_f64(synth.make_inputs(cfg, w_std=0.3))
     fwd = oracle.layer_forward(inp, fa, fm, rope_dim)
     r = np.random.default_rng(7).standard_normal(fwd.out.shape)
@@ -27,6 +31,8 @@ def test_layer_backward_matches_finite_differences(fa, fm, rope_dim, noise):
     pairs = (("x", gr.d_x), ("wq", gr.smha.d_wq), ("wk", gr.smha.d_wk), ("wv", gr.smha.d_wv), ("wo", gr.smha.d_wo),
              ("a_w_expert", gr.route_a.d_w_expert), ("a_w_b", gr.route_a.d_w_b), ("a_w_a", gr.route_a.d_w_a),
              ("a_in", gr.uome.d_a_in), ("a_out", gr.uome.d_a_out), ("m_w_expert", gr.route_m.d_w_expert))
+    if ds:
+        pairs += (("m_w_b", gr.route_m.d_w_b), ("m_w_a", gr.route_m.d_w_a))
     eps, checked = 1e-6, 0
     rr = np.random.default_rng(11)
 
@@ -34,7 +40,8 @@ def test_layer_backward_matches_finite_differences(fa, fm, rope_dim, noise):
         f = oracle.layer_forward(inp, fa, fm, rope_dim)
         same = (np.array_equal(f.routing_a.expert_id, fwd.routing_a.expert_id) and
                 np.array_equal(f.routing_a.patch_id, fwd.routing_a.patch_id) and
-                np.array_equal(f.routing_m.expert_id, fwd.routing_m.expert_id))
+                np.array_equal(f.routing_m.expert_id, fwd.routing_m.expert_id) and
+                np.array_equal(f.routing_m.patch_id, fwd.routing_m.patch_id))
         return float(np.sum(f.out * r)), same
 
     for name, grad in pairs:
