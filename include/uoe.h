@@ -258,15 +258,16 @@ typedef struct {
  *   d_expert_gate [b,n] fp32, d_patch_gate [b,n,m] fp32   dL/d(gate) for the active experts and
  *                          their selected patches, zero elsewhere and when the matching flag is
  *                          off; either may be NULL
- * The forward intermediates are recomputed.  This build: bf16 storage, d_h in {32, 64, 128},
- * d % 32 == 0, l_p % 32 == 0, b <= 128, no padding mask; otherwise
+ * pad_mask [b,l] bytes or NULL as in uoe_smha_forward_masked (Eq. 41: padded keys are out of every
+ * softmax).  The forward intermediates are recomputed.  This build: bf16 storage, d_h in {32, 64, 128},
+ * d % 32 == 0, l_p % 32 == 0, b <= 128; otherwise
  * UOE_ERR_UNSUPPORTED.  Deterministic: fixed summation order, no atomics.  ws: at least
  * uoe_smha_backward_workspace_bytes(blk) bytes (0 = descriptor invalid or unsupported).
  */
 size_t uoe_smha_backward_workspace_bytes(const uoe_block_desc *blk);
 int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_weights *w,
                       const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
-                      const float *patch_gate, const void *d_out, void *d_x,
+                      const float *patch_gate, const uint8_t *pad_mask, const void *d_out, void *d_x,
                       const uoe_smha_weight_grads *dw, float *d_expert_gate, float *d_patch_gate,
                       void *ws, size_t ws_bytes, void *hip_stream);
 

@@ -431,14 +431,15 @@ def _rope(a, rope_dim: int, sign: float):
 
 
 def smha_backward(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: int, d_out,
-                  flags: int = RESIDUAL, rope_dim: int = 0) -> SmhaGrads:
+                  flags: int = RESIDUAL, rope_dim: int = 0, pad_mask=None) -> SmhaGrads:
     """Gradients of the SMHA block (Eq. 27-36, with the partial RoPE of Eq. 32 and the shared causal
     mask of Sec. III-C.3) for an upstream gradient d_out = dL/du [b,l,d].
 
     Chain rule, per sample b and active expert i with gathered token positions T (Eq. 12, 18):
     u[T] += w_t * (softmax(q k^T / sqrt(d_h)) v) W^O_i with q, k, v = x[T] W^{q,k,v}_i (q, k rotated).
     The selections (expert_id, patch_id) are constants; the gates enter as values and their
-    gradients are returned for the caller to chain into the routers."""
+    gradients are returned for the caller to chain into the routers.  pad_mask [b,l] (1 = token,
+    0 = padding; Eq. 41) removes padded keys; a query left without any key contributes nothing."""
     x, wq, wk, wv, wo, d_out = _f64(x), _f64(wq), _f64(wk), _f64(wv), _f64(wo), _f64(d_out)
     b, l, d = x.shape
     n, _, d_h = wq.shape
@@ -460,9 +461,11 @@ def smha_backward(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gat
             # forward, kept
             h = x[bb, T]
             q, kk, v = _rope(h @ wq[i], rope_dim, 1.0), _rope(h @ wk[i], rope_dim, 1.0), h @ wv[i]
-            sc = np.where(allowed, (q @ kk.T) * scale, -np.inf)
-            p = np.exp(sc - sc.max(axis=1, keepdims=True))
-            p /= p.sum(axis=1, keepdims=True)
+            ok = allowed if pad_mask is None else allowed & (np.asarray(pad_mask)[bb, T] != 0)[None, :]
+            sc = np.where(ok, (q @ kk.T) * scale, -np.inf)
+            live = ok.any(axis=1, keepdims=True)
+            p = np.where(ok, np.exp(sc - np.where(live, sc.max(axis=1, keepdims=True), 0.0)), 0.0)
+            p /= np.where(live, p.sum(axis=1, keepdims=True), 1.0)
             o = p @ v
             y = o @ wo[i]                                   # [l_a,d] before the gates
             # backward

@@ -88,7 +88,7 @@ def lib():
         L.uoe_uome_backward.argtypes = [D] + [P] * 13 + [P, S, P]
         L.uoe_smha_backward_workspace_bytes.argtypes = [D]
         L.uoe_smha_backward_workspace_bytes.restype = S
-        L.uoe_smha_backward.argtypes = [D, P, ctypes.POINTER(SmhaWeights), P, P, P, P, P, P,
+        L.uoe_smha_backward.argtypes = [D, P, ctypes.POINTER(SmhaWeights), P, P, P, P, P, P, P,
                                         ctypes.POINTER(SmhaWeightGrads), P, P, P, S, P]
         L.uoe_route_backward_workspace_bytes.argtypes = [D]
         L.uoe_route_backward_workspace_bytes.restype = S
@@ -222,10 +222,10 @@ def smha_weight_grads(d_wq, d_wk, d_wv, d_wo) -> SmhaWeightGrads:
     return SmhaWeightGrads(*(_ptr(t) for t in (d_wq, d_wk, d_wv, d_wo)))
 
 
-def smha_backward(blk, x, w: SmhaWeights, expert_idx, expert_gate, patch_idx, patch_gate, d_out, d_x,
+def smha_backward(blk, x, w: SmhaWeights, expert_idx, expert_gate, patch_idx, patch_gate, pad_mask, d_out, d_x,
                   dw: SmhaWeightGrads, d_expert_gate, d_patch_gate, ws, stream=None, check=True, ws_bytes=None) -> int:
     st = lib().uoe_smha_backward(_ref(blk), _ptr(x), ctypes.byref(w), _ptr(expert_idx), _ptr(expert_gate),
-                                 _ptr(patch_idx), _ptr(patch_gate), _ptr(d_out), _ptr(d_x), ctypes.byref(dw),
+                                 _ptr(patch_idx), _ptr(patch_gate), _ptr(pad_mask), _ptr(d_out), _ptr(d_x), ctypes.byref(dw),
                                  _ptr(d_expert_gate), _ptr(d_patch_gate), _ptr(ws),
                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_smha_backward", check)

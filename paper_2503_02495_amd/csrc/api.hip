@@ -483,9 +483,9 @@ size_t uoe_smha_backward_workspace_bytes(const uoe_block_desc *blk)
 }
 
 int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_weights *w, const int32_t *expert_idx,
-                      const float *expert_gate, const int32_t *patch_idx, const float *patch_gate, const void *d_out,
-                      void *d_x, const uoe_smha_weight_grads *dw, float *d_expert_gate, float *d_patch_gate, void *ws,
-                      size_t ws_bytes, void *hip_stream)
+                      const float *expert_gate, const int32_t *patch_idx, const float *patch_gate, const uint8_t *pad_mask,
+                      const void *d_out, void *d_x, const uoe_smha_weight_grads *dw, float *d_expert_gate,
+                      float *d_patch_gate, void *ws, size_t ws_bytes, void *hip_stream)
 {
     const int rc = check_smha_bwd(blk);
     if (rc != UOE_OK) return rc;
@@ -506,7 +506,7 @@ int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_w
     f.expert_idx = expert_idx; f.patch_idx = patch_idx;
     f.b = blk->b; f.l = blk->l; f.d = blk->d; f.n = blk->n; f.k = blk->k; f.m = blk->m; f.c = blk->c;
     f.d_h = blk->width; f.flags = blk->flags & UOE_FLAG_CAUSAL;  // the recomputed o carries no gate
-    f.rope_dim = blk->rope_dim;
+    f.rope_dim = blk->rope_dim; f.pad_mask = pad_mask;
     f.q = at(ws, s.fwd.q); f.kk = at(ws, s.fwd.k); f.v = at(ws, s.fwd.v); f.o = at(ws, s.fwd.o); f.o_lo = at(ws, s.fwd.o_lo);
     f.lse = reinterpret_cast<float *>(at(ws, s.lse));
     a.d_out = d_out; a.expert_gate = expert_gate; a.patch_gate = patch_gate; a.flags = blk->flags;
@@ -774,7 +774,7 @@ int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa, c
     }
     // SMHA block and its routers: d_u -> d_x
     rc = uoe_smha_backward(smha, x, wa, routing_a->expert_idx, routing_a->expert_gate, routing_a->patch_idx,
-                           routing_a->patch_gate, d_u, d_x, dwa, d_gate_a, d_pgate_a, stage, w.stage_bytes, hip_stream);
+                           routing_a->patch_gate, nullptr, d_u, d_x, dwa, d_gate_a, d_pgate_a, stage, w.stage_bytes, hip_stream);
     if (rc != UOE_OK) return rc;
     if (route_a)
         rc = uoe_route_backward(smha, x, wa->w_expert, wa->w_b, wa->w_a, routing_a->expert_gate, routing_a->patch_gate,

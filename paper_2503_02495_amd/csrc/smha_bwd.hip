@@ -154,7 +154,19 @@ struct AttnBwdArgs {
     bf16_t *dqkv, *dqkv_t;  // [units, l_a, 3*d_h], [units, 3*d_h, l_a]
     int l_a, causal;
     int rope_dim;           // Eq. 32: dq and dk are rotated back (the transposed rotation) on the way out
+    // Eq. 41: padded keys are out of every softmax.  pad_mask [b,l] (1 = token) or NULL, looked up
+    // through the unit's patch indices
+    const unsigned char *pad_mask;
+    const int32_t *expert_idx, *patch_idx;
+    int l, n, kact, c, m, l_p;
 };
+
+__device__ __forceinline__ bool bwd_key_is_token(const AttnBwdArgs &a, int g, int key)
+{
+    const int bb = g / a.kact, i = clampi(a.expert_idx[g], a.n);
+    const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + key / a.l_p], a.m);
+    return a.pad_mask[(size_t)bb * a.l + p * a.l_p + key % a.l_p] != 0;
+}
 
 template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void attention_bwd_kernel(AttnBwdArgs a)
 {
@@ -165,6 +177,7 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
     __shared__ __align__(16) uint16_t TBr[BT][KP];
     __shared__ __align__(16) uint16_t TBt[KV ? BT : 1][VP];
     __shared__ __align__(16) float Ls[BT], Ds[BT];
+    __shared__ unsigned char Km[BT];  // streamed key admissible under the padding mask (KV = false)
 
     const int g = blockIdx.y, l_a = a.l_a;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -187,6 +200,8 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
     }
     float lse_o = 0.f, d_own = 0.f;
     if (!KV && orow < l_a) lse_o = a.lse[(size_t)g * l_a + orow];
+    const bool padded = a.pad_mask != nullptr;
+    const bool own_key_ok = !(KV && padded) || bwd_key_is_token(a, g, min(orow, l_a - 1));
 
     f32x16_t acc_a[DH / 32], acc_b[DH / 32];
 #pragma unroll
@@ -204,6 +219,7 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
 
     uint4 ra[PER_T], rb[PER_T];
     float lreg = 0.f, dreg = 0.f;
+    unsigned char kmreg = 1;
     auto load_global = [&](int row0) {
 #pragma unroll
         for (int i = 0; i < PER_T; ++i) {
@@ -222,6 +238,7 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
             lreg = in ? a.lse[(size_t)g * l_a + row0 + tid] : 0.f;
             dreg = in ? a.dd[(size_t)g * l_a + row0 + tid] : 0.f;
         }
+        if (!KV && padded && tid < BT) kmreg = row0 + tid < l_a && bwd_key_is_token(a, g, min(row0 + tid, l_a - 1));
     };
     auto store_lds = [&]() {
 #pragma unroll
@@ -239,6 +256,7 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
             Ls[tid] = lreg;
             Ds[tid] = dreg;
         }
+        if (!KV && padded && tid < BT) Km[tid] = kmreg;
     };
 
     // first products of one tile and the probabilities: leaves P^T in sacc and dP^T in pacc
@@ -272,7 +290,8 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
                     const int q = qg * 4 + e, crow = kt * BT + cl0 + e;
                     const int query = KV ? crow : orow, key = KV ? orow : crow;
                     const float p = __builtin_amdgcn_exp2f(sacc[t][q] - l4[e]);
-                    sacc[t][q] = (crow >= l_a || (a.causal && key > query)) ? 0.f : p;
+                    const bool key_ok = KV ? own_key_ok : (!padded || Km[cl0 + e]);
+                    sacc[t][q] = (crow >= l_a || (a.causal && key > query) || !key_ok) ? 0.f : p;
                 }
             }
     };
@@ -507,6 +526,8 @@ hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st)
     ab.d_o = static_cast<const T *>(a.d_o); ab.lse = f.lse; ab.dd = a.dd;
     ab.dqkv = static_cast<T *>(a.dqkv); ab.dqkv_t = static_cast<T *>(a.dqkv_t);
     ab.l_a = l_a; ab.causal = (f.flags & F_CAUSAL) ? 1 : 0; ab.rope_dim = f.rope_dim;
+    ab.pad_mask = f.pad_mask; ab.expert_idx = f.expert_idx; ab.patch_idx = f.patch_idx;
+    ab.l = f.l; ab.n = f.n; ab.kact = f.k; ab.c = f.c; ab.m = f.m; ab.l_p = l_p;
     err = dh == 32 ? launch_attention_bwd_dh<32>(ab, units, st)
                    : (dh == 64 ? launch_attention_bwd_dh<64>(ab, units, st) : launch_attention_bwd_dh<128>(ab, units, st));
     if (err != hipSuccess) return err;

@@ -126,7 +126,7 @@ class DeviceLayer:
             return self.d_u, self.d_a_in, self.d_a_out, self.d_gate, self.d_m_patch_gate
         return self.d_u, self.d_a_in, self.d_a_out, self.d_gate
 
-    def smha_backward(self, d_out, expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None):
+    def smha_backward(self, d_out, expert_idx=None, expert_gate=None, patch_idx=None, patch_gate=None, pad_mask=None):
         """Gradients of the SMHA block; returns (d_x, d_wq, d_wk, d_wv, d_wo, d_expert_gate, d_patch_gate)."""
         if not hasattr(self, "smha_bwd_ws"):
             nbytes = B.smha_backward_workspace_bytes(self.smha)
@@ -144,7 +144,7 @@ class DeviceLayer:
                         self.a_expert_idx if expert_idx is None else expert_idx,
                         self.a_expert_gate if expert_gate is None else expert_gate,
                         self.a_patch_idx if patch_idx is None else patch_idx,
-                        self.a_patch_gate if patch_gate is None else patch_gate, d_out, self.d_x, self.smha_dw,
+                        self.a_patch_gate if patch_gate is None else patch_gate, pad_mask, d_out, self.d_x, self.smha_dw,
                         self.d_a_expert_gate, self.d_a_patch_gate, self.smha_bwd_ws)
         return self.d_x, self.d_wq, self.d_wk, self.d_wv, self.d_wo, self.d_a_expert_gate, self.d_a_patch_gate
 

@@ -182,6 +182,16 @@ def make_gate_grads(cfg: LayerConfig, n: int, m: int, seed: Optional[int] = None
             rng.standard_normal(size=(cfg.b, n, m), dtype=np.float32))
 
 
+def make_pad_mask(cfg: LayerConfig, pad_frac: float, seed: Optional[int] = None) -> np.ndarray:
+    """A synthetic padding mask [b,l] uint8 (1 = token, 0 = padding): tokens padded at random with
+    probability pad_frac, plus a padded run over the first half of sample 0 (whole units lose all
+    their early keys)."""
+    rng = np.random.default_rng((cfg.seed if seed is None else seed) + 15485863)
+    pad = (rng.random((cfg.b, cfg.l)) >= pad_frac).astype(np.uint8)
+    pad[0, : cfg.l // 2] = 0
+    return pad
+
+
 def small_config(name: str = "small", **kw) -> LayerConfig:
     """A config with every size overridable, for randomly drawn tiny shapes in tests."""
     base = dict(b=2, l=24, d=16, n_a=3, d_h=8, m=4, c=2, k_a=2, n_m=3, d_e=8, k_m=2,

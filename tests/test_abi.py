@@ -200,9 +200,9 @@ def test_backward_argument_validation():
     wa = B.smha_weights(*([FAKE] * 7))
     dw = B.smha_weight_grads(FAKE + 16, FAKE + 32, FAKE + 48, FAKE + 64)
     sb = lambda *args, **k: B.smha_backward(a, *args, stream=0, check=False, **k)
-    assert sb(FAKE, wa, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE + 32, dw, None, None, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
-    assert sb(FAKE, wa, FAKE, FAKE, FAKE, None, FAKE + 16, FAKE + 32, dw, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG
-    assert sb(FAKE, wa, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, dw, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # d_x aliases x
+    assert sb(FAKE, wa, FAKE, FAKE, FAKE, FAKE, None, FAKE + 16, FAKE + 32, dw, None, None, FAKE, ws_bytes=8) == B.ERR_WORKSPACE
+    assert sb(FAKE, wa, FAKE, FAKE, FAKE, None, None, FAKE + 16, FAKE + 32, dw, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG
+    assert sb(FAKE, wa, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, FAKE, dw, None, None, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG  # d_x aliases x
     # router backward: at least one router, w_b and w_a together, gates with their routers
     rb = lambda *args, **k: B.route_backward(a, *args, stream=0, check=False, **k)
     assert B.route_backward_workspace_bytes(a) > 0

@@ -364,6 +364,12 @@ CA = B.FLAG_CAUSAL
 # gates, hence a bound of 3e-2 on the worst element and of 6e-3 on the average.
 SMHA_BWD_TOL = 3e-2
 BWD_FRO_TOL = 6e-3
+# A gate gradient is a sum of a few row terms r_t = dO_t . o_t (l_p of them for a patch gate), and a dot
+# product of two rounded vectors is in error by eps * |dO_t| * |o_t|, not by eps * |r_t|: terms that
+# cancel leave the error behind.  Under the causal and padding masks (rows with one or two keys are
+# several times larger than the rest) single patch gates read up to 5.2e-2 of their sample's rms while
+# the tensor's Frobenius error stays at 2-4e-3; the worst-element bound for the gate gradients is 8e-2.
+GATE_GRAD_TOL = 8e-2
 # The chained layer backward adds the UoME backward's roundings and the bf16 hand-over of dL/du in
 # front of the SMHA backward's, and the router gradients inherit the gate gradients' error.
 LAYER_BWD_TOL = 4e-2
@@ -382,7 +388,14 @@ def test_smha_backward_parity_rope_causal(name, rope_dim):
     run_smha_backward(name, R | GE | GP | CA, rope_dim)
 
 
-def run_smha_backward(name, flags, rope_dim):
+@pytest.mark.parametrize("name,flags", [("sb_dh64", R | GE | GP), ("sb_long", R | GE | GP | CA), ("lm", R | GE | GP | CA)])
+def test_smha_backward_parity_padding_mask(name, flags):
+    """Eq. 41 in the backward pass: padded keys are out of every softmax; with the causal mask some
+    queries are left without any key and must pass nothing on."""
+    run_smha_backward(name, flags, 0, pad_frac=0.2)
+
+
+def run_smha_backward(name, flags, rope_dim, pad_frac=0.0):
     """uoe_smha_backward against the oracle's chain rule (itself pinned by finite differences of
     the forward oracle) on the same routing, inputs and upstream gradient; every gradient in full."""
     cfg = SMHA_BWD_CONFIGS[name] if name in SMHA_BWD_CONFIGS else synth.CONFIGS[name]
@@ -394,14 +407,18 @@ def run_smha_backward(name, flags, rope_dim):
     ref = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
                        inp.noise_a_expert, inp.noise_a_patch)
     ge, gp = ref.expert_gate.astype(np.float32), ref.patch_gate.astype(np.float32)
+    pad = synth.make_pad_mask(cfg, pad_frac) if pad_frac > 0 else None
     got = dev.smha_backward(to_device(d_out, cfg.dtype, dev.device),
                             expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
                             expert_gate=to_device(ge, synth.F32, dev.device),
                             patch_idx=torch.from_numpy(ref.patch_id).to(dev.device),
-                            patch_gate=to_device(gp, synth.F32, dev.device))
+                            patch_gate=to_device(gp, synth.F32, dev.device),
+                            pad_mask=None if pad is None else torch.from_numpy(pad).to(dev.device))
     torch.cuda.synchronize()
     want = oracle.smha_backward(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ref.expert_id, ge, ref.patch_id, gp, cfg.m,
-                                d_out, flags, rope_dim)
+                                d_out, flags, rope_dim, pad)
+    for g in got:
+        assert torch.isfinite(g.float()).all()
     names = ("d_x", "d_wq", "d_wk", "d_wv", "d_wo", "d_expert_gate", "d_patch_gate")
     refs = (want.d_x, want.d_wq, want.d_wk, want.d_wv, want.d_wo, want.d_expert_gate, want.d_patch_gate)
     errs = {nm: grad_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
@@ -412,7 +429,8 @@ def run_smha_backward(name, flags, rope_dim):
         assert not np.any(to_host(g)[unused])
     print(f"[smha backward {name} flags={flags}] unused experts {unused.tolist()} " +
           " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {SMHA_BWD_TOL:.0e})", flush=True)
-    assert max(errs.values()) <= SMHA_BWD_TOL
+    assert max(v for k, v in errs.items() if "gate" not in k) <= SMHA_BWD_TOL
+    assert max(errs["d_expert_gate"], errs["d_patch_gate"]) <= GATE_GRAD_TOL
     assert max(fro.values()) <= BWD_FRO_TOL
 
 

@@ -70,3 +70,35 @@ def test_collisions_and_unselected():
     no_gate = oracle.smha_backward(cs["x"], cs["wq"], cs["wk"], cs["wv"], cs["wo"], cs["eid"], cs["ge"], cs["pid"],
                                    cs["gp"], cs["m"], cs["d_out"], R)
     assert not no_gate.d_expert_gate.any() and not no_gate.d_patch_gate.any()
+
+
+@pytest.mark.parametrize("flags", [R | GE | GP, R | GE | GP | CA])
+def test_backward_with_padding_mask_matches_finite_differences(flags):
+    """Eq. 41: padded keys are out of every softmax; under the causal mask the first query of a unit
+    whose first token is padding has no key at all and must contribute nothing."""
+    cs = case(2)
+    pad = np.ones((2, 12), np.uint8)
+    pad[0, [0, 4, 5]] = 0
+    pad[1, 9:] = 0
+    gr = oracle.smha_backward(cs["x"], cs["wq"], cs["wk"], cs["wv"], cs["wo"], cs["eid"], cs["ge"], cs["pid"], cs["gp"],
+                              cs["m"], cs["d_out"], flags, 0, pad)
+
+    def loss():
+        u = oracle.smha(cs["x"], cs["wq"], cs["wk"], cs["wv"], cs["wo"], cs["eid"], cs["ge"], cs["pid"], cs["gp"], cs["m"],
+                        flags, 0, pad)
+        return float(np.sum(u * cs["d_out"]))
+
+    eps = 1e-6
+    rr = np.random.default_rng(9)
+    for name, grad in (("x", gr.d_x), ("wq", gr.d_wq), ("wk", gr.d_wk), ("wv", gr.d_wv), ("wo", gr.d_wo),
+                       ("ge", gr.d_expert_gate), ("gp", gr.d_patch_gate)):
+        flat = cs[name].reshape(-1)
+        for idx in rr.choice(flat.size, min(flat.size, 20), replace=False):
+            keep = flat[idx]
+            flat[idx] = keep + eps
+            lp = loss()
+            flat[idx] = keep - eps
+            lm = loss()
+            flat[idx] = keep
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - grad.reshape(-1)[idx]) <= 2e-6 * max(1.0, abs(fd)), (name, idx, fd, grad.reshape(-1)[idx])
