@@ -168,7 +168,7 @@ __device__ __forceinline__ bool bwd_key_is_token(const AttnBwdArgs &a, int g, in
     return a.pad_mask[(size_t)bb * a.l + p * a.l_p + key % a.l_p] != 0;
 }
 
-template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void attention_bwd_kernel(AttnBwdArgs a)
+template <int DH, int NW, bool KV, bool PAD> __global__ __launch_bounds__(NW * 64) void attention_bwd_kernel(AttnBwdArgs a)
 {
     constexpr int BT = 64, KP = DH + 8, VP = 2 * b_pitch_dwords(DH), NT = NW * 64;
     constexpr int CHUNKS = BT * DH / 8, PER_T = (CHUNKS + NT - 1) / NT;
@@ -177,7 +177,7 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
     __shared__ __align__(16) uint16_t TBr[BT][KP];
     __shared__ __align__(16) uint16_t TBt[KV ? BT : 1][VP];
     __shared__ __align__(16) float Ls[BT], Ds[BT];
-    __shared__ unsigned char Km[BT];  // streamed key admissible under the padding mask (KV = false)
+    __shared__ unsigned char Km[PAD ? BT : 1];  // streamed key admissible under the padding mask (KV = false)
 
     const int g = blockIdx.y, l_a = a.l_a;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -200,7 +200,7 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
     }
     float lse_o = 0.f, d_own = 0.f;
     if (!KV && orow < l_a) lse_o = a.lse[(size_t)g * l_a + orow];
-    const bool padded = a.pad_mask != nullptr;
+    constexpr bool padded = PAD;  // compile-time: the unmasked kernels keep two waves per SIMD
     const bool own_key_ok = !(KV && padded) || bwd_key_is_token(a, g, min(orow, l_a - 1));
 
     f32x16_t acc_a[DH / 32], acc_b[DH / 32];
@@ -290,7 +290,8 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
                     const int q = qg * 4 + e, crow = kt * BT + cl0 + e;
                     const int query = KV ? crow : orow, key = KV ? orow : crow;
                     const float p = __builtin_amdgcn_exp2f(sacc[t][q] - l4[e]);
-                    const bool key_ok = KV ? own_key_ok : (!padded || Km[cl0 + e]);
+                    bool key_ok = true;
+                    if constexpr (PAD) key_ok = KV ? own_key_ok : Km[cl0 + e] != 0;
                     sacc[t][q] = (crow >= l_a || (a.causal && key > query) || !key_ok) ? 0.f : p;
                 }
             }
@@ -431,23 +432,30 @@ template <int DH, int NW, bool KV> __global__ __launch_bounds__(NW * 64) void at
     }
 }
 
-template <int DH> static hipError_t launch_attention_bwd_dh(const AttnBwdArgs &a, int units, hipStream_t st)
+template <int DH, bool PAD> static hipError_t launch_attention_bwd_dh(const AttnBwdArgs &a, int units, hipStream_t st)
 {
     const int l_a = a.l_a;
     if ((long)((l_a + 127) / 128) * units >= 128) {
         const dim3 grid((l_a + 127) / 128, units);
-        hipLaunchKernelGGL((attention_bwd_kernel<DH, 4, false>), grid, dim3(256), 0, st, a);
-        hipLaunchKernelGGL((attention_bwd_kernel<DH, 4, true>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attention_bwd_kernel<DH, 4, false, PAD>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attention_bwd_kernel<DH, 4, true, PAD>), grid, dim3(256), 0, st, a);
     } else if ((long)((l_a + 63) / 64) * units >= 64) {
         const dim3 grid((l_a + 63) / 64, units);
-        hipLaunchKernelGGL((attention_bwd_kernel<DH, 2, false>), grid, dim3(128), 0, st, a);
-        hipLaunchKernelGGL((attention_bwd_kernel<DH, 2, true>), grid, dim3(128), 0, st, a);
+        hipLaunchKernelGGL((attention_bwd_kernel<DH, 2, false, PAD>), grid, dim3(128), 0, st, a);
+        hipLaunchKernelGGL((attention_bwd_kernel<DH, 2, true, PAD>), grid, dim3(128), 0, st, a);
     } else {
         const dim3 grid((l_a + 31) / 32, units);
-        hipLaunchKernelGGL((attention_bwd_kernel<DH, 1, false>), grid, dim3(64), 0, st, a);
-        hipLaunchKernelGGL((attention_bwd_kernel<DH, 1, true>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((attention_bwd_kernel<DH, 1, false, PAD>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((attention_bwd_kernel<DH, 1, true, PAD>), grid, dim3(64), 0, st, a);
     }
     return hipGetLastError();
+}
+
+template <bool PAD> static hipError_t launch_attention_bwd(const AttnBwdArgs &a, int dh, int units, hipStream_t st)
+{
+    if (dh == 32) return launch_attention_bwd_dh<32, PAD>(a, units, st);
+    if (dh == 64) return launch_attention_bwd_dh<64, PAD>(a, units, st);
+    return launch_attention_bwd_dh<128, PAD>(a, units, st);
 }
 
 hipError_t launch_unit_gate_grads(const SmhaBwdArgs &a, hipStream_t st)
@@ -528,8 +536,7 @@ hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st)
     ab.l_a = l_a; ab.causal = (f.flags & F_CAUSAL) ? 1 : 0; ab.rope_dim = f.rope_dim;
     ab.pad_mask = f.pad_mask; ab.expert_idx = f.expert_idx; ab.patch_idx = f.patch_idx;
     ab.l = f.l; ab.n = f.n; ab.kact = f.k; ab.c = f.c; ab.m = f.m; ab.l_p = l_p;
-    err = dh == 32 ? launch_attention_bwd_dh<32>(ab, units, st)
-                   : (dh == 64 ? launch_attention_bwd_dh<64>(ab, units, st) : launch_attention_bwd_dh<128>(ab, units, st));
+    err = ab.pad_mask ? launch_attention_bwd<true>(ab, dh, units, st) : launch_attention_bwd<false>(ab, dh, units, st);
     if (err != hipSuccess) return err;
 
     // d_x = (G) + scatter-add of [dq|dk|dv] [W^q|W^k|W^v]^T: the out-projection's output-stationary
