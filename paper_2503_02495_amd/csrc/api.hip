@@ -181,11 +181,11 @@ struct RouteBwdWs {
 RouteBwdWs route_bwd_ws(const uoe_block_desc *d)
 {
     RouteBwdWs w;
-    // chunks of the token axis for dW_B: about 512 of them, 64 to 128 tokens each (the kernel stages a
+    // chunks of the token axis for dW_B: about 512 of them, 32 to 128 tokens each (the kernel stages a
     // chunk's rows of U in LDS)
     const size_t tokens = (size_t)d->b * d->l;
     w.wb_tokens = (int)((tokens + 511) / 512);
-    w.wb_tokens = w.wb_tokens < 64 ? 64 : (w.wb_tokens > 128 ? 128 : w.wb_tokens);
+    w.wb_tokens = w.wb_tokens < 32 ? 32 : (w.wb_tokens > 128 ? 128 : w.wb_tokens);
     w.wb_chunks = (int)((tokens + w.wb_tokens - 1) / w.wb_tokens);
     size_t off = 0;
     w.dz = off; off += up((size_t)d->b * d->n * sizeof(float));

@@ -128,17 +128,18 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_xexpert_k
 }
 
 // Data router, per token: U[t,:] = W_A[t,:] dL^T, then one pass over the token's row of x that
-// forms (x W_B)[t,:] and adds U[t,:] W_B^T to d_x.  Block = 64 tokens of one sample, 4 lanes per
-// token; the sample's dL and W_B^T ([n][d], so that the 8 weights a piece of x meets are one
-// 16-byte read) are staged in LDS.
-template <typename T> __global__ __launch_bounds__(256) void route_bwd_data_token_kernel(RouteBwdArgs a)
+// forms (x W_B)[t,:] and adds U[t,:] W_B^T to d_x.  Block = 256/LPT tokens of one sample, LPT lanes
+// per token (16 when 4 would leave compute units without a block); the sample's dL and W_B^T
+// ([n][d], so that the 8 weights a piece of x meets are one 16-byte read) are staged in LDS.
+template <typename T, int LPT> __global__ __launch_bounds__(256) void route_bwd_data_token_kernel(RouteBwdArgs a)
 {
+    constexpr int TPB = 256 / LPT;  // tokens per block
     extern __shared__ __align__(16) unsigned char smem[];
     float *dls = reinterpret_cast<float *>(smem);                       // [n][m]
-    float *us = dls + (size_t)a.n * a.m;                                // [64][n]
+    float *us = dls + (size_t)a.n * a.m;                                // [64][n] (TPB <= 64 rows used)
     T *wbt = reinterpret_cast<T *>(smem + ((((size_t)a.n * a.m + 64 * (size_t)a.n) * sizeof(float) + 15) & ~(size_t)15));  // [n][d]
-    const int bb = blockIdx.y, tid = threadIdx.x, tl = tid >> 2, part = tid & 3;
-    const int t = blockIdx.x * 64 + tl;
+    const int bb = blockIdx.y, tid = threadIdx.x, tl = tid / LPT, part = tid % LPT;
+    const int t = blockIdx.x * TPB + tl;
     for (int idx = tid; idx < a.n * a.m; idx += 256) dls[idx] = a.dl[(size_t)bb * a.n * a.m + idx];
     for (int idx = tid; idx < a.d * a.n; idx += 256) {
         const int e = idx / a.n, i = idx - e * a.n;
@@ -147,7 +148,7 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_data_toke
     __syncthreads();
     if (t < a.l) {
         const T *wa = static_cast<const T *>(a.w_a) + (size_t)t * a.m;
-        for (int i = part; i < a.n; i += 4) {
+        for (int i = part; i < a.n; i += LPT) {
             float s = 0.f;
             for (int j = 0; j < a.m; ++j) s = fmaf(to_f32(wa[j]), dls[i * a.m + j], s);
             us[tl * a.n + i] = s;
@@ -161,7 +162,7 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_data_toke
     if (t < a.l) {
         const T *xr = static_cast<const T *>(a.x) + ((size_t)bb * a.l + t) * a.d;
         T *dxr = static_cast<T *>(a.d_x) + ((size_t)bb * a.l + t) * a.d;
-        for (int pc = part; pc < a.d / 8; pc += 4) {
+        for (int pc = part; pc < a.d / 8; pc += LPT) {
             float xv[8], dv[8];
             load8(xr + pc * 8, xv);
             load8(dxr + pc * 8, dv);
@@ -182,10 +183,9 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_data_toke
         }
     }
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-        t1[i] += __shfl_xor(t1[i], 1, 64);
-        t1[i] += __shfl_xor(t1[i], 2, 64);
-    }
+    for (int i = 0; i < 32; ++i)
+#pragma unroll
+        for (int off = 1; off < LPT; off <<= 1) t1[i] += __shfl_xor(t1[i], off, 64);
     if (t < a.l && part == 0)
         for (int i = 0; i < a.n; ++i) a.t1[((size_t)bb * a.l + t) * a.n + i] = t1[i];
 }
@@ -299,7 +299,10 @@ template <typename T> static hipError_t route_backward(const RouteBwdArgs &a, hi
     }
     if (a.w_b) {
         const size_t smem = ((((size_t)a.n * a.m + 64 * (size_t)a.n) * sizeof(float) + 15) & ~(size_t)15) + (size_t)a.d * a.n * sizeof(T);
-        hipLaunchKernelGGL((route_bwd_data_token_kernel<T>), dim3((a.l + 63) / 64, a.b), dim3(256), smem, st, a);
+        if ((long)((a.l + 63) / 64) * a.b >= 256)
+            hipLaunchKernelGGL((route_bwd_data_token_kernel<T, 4>), dim3((a.l + 63) / 64, a.b), dim3(256), smem, st, a);
+        else
+            hipLaunchKernelGGL((route_bwd_data_token_kernel<T, 16>), dim3((a.l + 15) / 16, a.b), dim3(256), smem, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
         hipLaunchKernelGGL((route_bwd_wa_kernel<T>), dim3((unsigned)(((long)a.l * a.m + 255) / 256)), dim3(256), 0, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
