@@ -1,12 +1,12 @@
-// Backward pass of the SMHA block (Eq. 27-36 with the shared causal mask of Sec. III-C.3), bf16
-// storage, MFMA shapes.  For an upstream gradient G = dL/du [b,l,d], per active unit (sample b,
+// Backward pass of the SMHA block (Eq. 27-36 with the partial RoPE of Eq. 32 and the masks of
+// Sec. III-C.3), bf16 storage, MFMA shapes.  For an upstream gradient G = dL/du [b,l,d], per active unit (sample b,
 // slot s, expert i) with gathered token positions T, gate weight w_t of row t (Eq. 36 with the
 // gate flags), o = softmax(q k^T / sqrt(d_h)) v and y = o W^O_i (u[T_t] += w_t y_t):
-//   dO_raw = G[T] W^O_i^T,   r_t = dO_raw_t . o_t  (= dL/dw_t),   dO = w * dO_raw,   D_t = w_t r_t
+//   dO_raw = G[T] W^O_i^T,   r_t = dO_raw_t . o_t  (= dL/dw_t),   dO = w * dO_raw
 //   dW^O_i += (w * o)^T G[T]
 //   d_expert_gate[b,i] = sum_t g_patch(t) r_t,  d_patch_gate[b,i,p] = g_expert * sum_{t in p} r_t
-//   P = softmax(...), dV = P^T dO, dP = dO V^T, dS = P * (dP - D), dQ = dS K / sqrt(d_h),
-//   dK = dS^T Q / sqrt(d_h)
+//   P = softmax(...), dV = P^T dO, dP = dO V^T, dS = P * (dP - D) with D_i = sum_j P_ij dP_ij,
+//   dQ = dS K / sqrt(d_h), dK = dS^T Q / sqrt(d_h)  (both rotated back when q, k were rotated)
 //   dW^{q,k,v}_i += x[T]^T d{Q,K,V},   d_x[T] += dQ W^q_i^T + dK W^k_i^T + dV W^v_i^T  (+ G: residual)
 // The forward intermediates are recomputed with the forward's own kernels (projections and
 // attention, which also keeps each query's log-sum-exp); the contractions with the weights run on

@@ -1,4 +1,5 @@
-// Backward pass of the expert-selection UoME block (Eq. 38-40 with Eq. 24-26), bf16 storage.
+// Backward pass of the UoME block, bf16 storage.  Expert-selection mode first (Eq. 38-40 with
+// Eq. 24-26); the data-selection mode (Eq. 37 with Eq. 12-18) follows at the end of the file.
 // Forward, per sample b with active experts i(s), s < k, gate w_s (1 without the gate flag):
 //   Z = u W1_b           W1_b = [A^I_i(0) | ... | A^I_i(k-1)]            [l, k*d_e]
 //   H = SiLU(Z) * w      (column block s scaled by w_s)
