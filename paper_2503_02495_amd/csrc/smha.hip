@@ -486,6 +486,11 @@ static hipError_t smha_mfma_qkv_attention(const SmhaArgs &a, hipStream_t st)
                             : launch_gemm_dma<QP, 128, 192, 32, 2, 2, 4>(qp, units, l_a, 192, st);
         else if (k64 && l_a > 32 && (long)units * ((l_a + 63) / 64) >= 256)
             err = launch_gemm_dma<QP, 64, 192, 64, 2, 2, 3>(qp, units, l_a, 192, st);
+        // fewer row tiles than compute units: one workgroup per projection (64 columns), three
+        // times the workgroups for three reads of the gathered rows out of L2 (the LM shape: 128 row
+        // tiles, the stage 26 -> 22.4 us)
+        else if (k64 && (long)units * ((l_a + 31) / 32) < 256)
+            err = launch_gemm_dma<QP, 32, 64, 64, 1, 2, 4>(qp, units, l_a, 192, st);
         else if (k64) err = launch_gemm_dma<QP, 32, 192, 64, 1, 2, 4>(qp, units, l_a, 192, st);
         else err = launch_gemm_dma<QP, 32, 192, 32, 1, 2, 4>(qp, units, l_a, 192, st);
     } else {
