@@ -874,6 +874,35 @@ def test_layer_under_hip_graph_replay():
         assert torch.equal(dev.a_patch_idx, want_idx), f"replay {rep}"
 
 
+def test_layer_backward_under_hip_graph_replay():
+    """The chained backward is capturable too (kernel launches only, no clears by the runtime);
+    every replay reproduces the eager gradients with the scratch overwritten between replays."""
+    cfg = get_cfg("lm")
+    inp = synth.make_inputs(cfg)
+    dev = DeviceLayer(inp, R | GE | GP, R | GE)
+    d_out = to_device(synth.make_upstream_grad(cfg), cfg.dtype, dev.device)
+    dev.layer_forward()
+    want = {k: v.clone() for k, v in dev.layer_backward(d_out).items() if v is not None}
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dev.layer_backward(d_out)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dev.layer_backward(d_out)
+    for rep in range(3):
+        for k in want:
+            dev.g[k].fill_(7.0)                  # eager work between replays
+        dev.layer_bwd_ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in want:
+            assert torch.equal(dev.g[k].view(torch.int16), want[k].view(torch.int16)), f"replay {rep}: {k}"
+
+
 # --------------------------------------------------------------------------- masks and RoPE
 CA = B.FLAG_CAUSAL
 assert CA == oracle.CAUSAL
