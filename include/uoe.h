@@ -1,6 +1,6 @@
 /*
  * uoe.h -- C ABI of the MI355X (gfx950) forward pass of one Union-of-Experts layer
- * (arXiv 2503.02495, Sec. III).
+ * (arXiv 2503.02495, Sec. III), and of its backward pass.
  *
  * Notation is the paper's: b batch, l sequence length, d model dim, n experts,
  * k experts kept per sample, m patches per sample, l_p = l/m tokens per patch,
@@ -11,7 +11,8 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller, row-major,
  *     contiguous, 16-byte aligned.  The library allocates no device memory,
  *     keeps no state between calls and never retains a pointer.  Scratch space
- *     is the caller's `ws` buffer of at least uoe_workspace_bytes() bytes.
+ *     is the caller's `ws` buffer of at least uoe_workspace_bytes() bytes (the
+ *     backward calls have sizing functions of their own).
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and return without waiting.  Calls on distinct
  *     streams with distinct workspaces may run concurrently.
