@@ -119,7 +119,7 @@ UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
     w.splits = d->c < d->m ? smha_backward_splits(d->b, d->n, d->k, d->c)
                            : uome_backward_splits(d->b, d->l, d->d, d->n, d->k, d->width);
     w.partial = off;
-    off += up((size_t)d->n * w.splits * d->d * d->width * sizeof(float));
+    off += up(2 * (size_t)d->n * w.splits * d->d * d->width * sizeof(float));  // both weight gradients
     w.gpart = off; off += up((size_t)d->b * d->k * uome_backward_gate_chunks(d->l, d->width) * sizeof(float));
     w.rt = off; off += up((size_t)d->b * d->k * d->l * sizeof(float));
     w.total = off;
@@ -159,7 +159,7 @@ SmhaBwdWs smha_bwd_ws(const uoe_block_desc *d)
     w.dqkv = off; off += 3 * one;
     w.dqkv_t = off; off += 3 * one;
     w.partial = off;
-    off += up((size_t)d->n * smha_backward_splits(d->b, d->n, d->k, d->c) * 3 * d->width * d->d * sizeof(float));
+    off += up((size_t)d->n * smha_backward_splits(d->b, d->n, d->k, d->c) * 4 * d->width * d->d * sizeof(float));
     w.total = off;
     return w;
 }

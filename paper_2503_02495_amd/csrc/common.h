@@ -139,7 +139,7 @@ struct UomeBwdArgs {
     void *dz_t, *h_t;                         // [b, k*d_e, l] each
     void *a_in_t, *a_out_t;                   // [n, d_e, d], [n, d, d_e]
     float *gpart;                             // [b, k, gchunks] partial sums of d_gate
-    float *partial;                           // [n*splits, d_e, d] split-K tiles of a weight gradient
+    float *partial;                           // [2*n*splits, d_e, d] split-K tiles of the two weight gradients
     int gchunks, splits;
     // data-selection mode (patch_idx != NULL): units = (sample, slot) with l_a = c*l/m gathered rows;
     // z, dh, dz are [units, l_a, d_e], dz_t and h_t [units, d_e, l_a]
@@ -165,7 +165,7 @@ struct SmhaBwdArgs {
     void *o_t;                                // [units, d_h, l_a]
     void *dqkv, *dqkv_t;                      // [units, l_a, 3*d_h], [units, 3*d_h, l_a]
     float *rt, *dd;                           // [units, l_a] each: dL/dw_t and the softmax row term
-    float *partial;                           // [n*splits, 3*d_h, d] split tiles of a weight gradient
+    float *partial;                           // [4*n*splits, d_h, d] split tiles of the four weight gradients
     int splits;
 };
 

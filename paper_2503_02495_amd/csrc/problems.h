@@ -385,20 +385,23 @@ template <typename T> struct UomeDownProblem {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Weight gradients of the expert-selection UoME block: for expert i,
-//   dW[M, N] = sum over the (sample b, slot s) pairs with expert_idx[b,s] == i of  L_{b,s}^T R_{b,s}
-// contracted over the l tokens of the sample.  The left factor is given TRANSPOSED
-// ([sample][rows][l], so that its rows are K-contiguous like every A operand), the right factor in
-// its natural token-major layout.  K segments = the pairs, found by the workgroup itself (prepare),
-// in sample order, which fixes the summation order.  The token axis is cut into `splits` equal
-// ranges for parallelism: group = expert * splits + j contracts range j of every pair and stores
-// its fp32 partial tile [group][M][N]; a reduction kernel adds the ranges in order.
-//   dA^O_i   [d_e, d]:  left = H^T  [b][k*d_e][l] (rows s*d_e + e of the pair), right = d_out [b][l][d]
-//   dA^I_i^T [d_e, d]:  left = dZ^T [b][k*d_e][l] (the same rows),              right = u     [b][l][d]
+// Weight gradients of the backward passes, as split contractions over the tokens with fp32 partial
+// tiles.  A launch covers up to four gradient tensors ("sets") of the same shape [n][M][N] at once:
+// group = (set * n + expert) * splits + part, partial tile [group][M][N]; a reduction kernel adds
+// the parts in order.  The left factor of a set is given TRANSPOSED, token-minor (rows are
+// K-contiguous like every A operand); the right factor in its natural token-major layout.
+//
+// Expert-selection UoME: for expert i,
+//   dW[M, N] = sum over the (sample b, slot s) pairs with expert_idx[b,s] == i of  L_{b,s}^T R_b
+// contracted over the l tokens of the sample.  K segments = the pairs, found by the workgroup itself
+// (prepare), in sample order, which fixes the summation order; the token axis is cut into `splits`
+// equal ranges, part j contracts range j of every pair.
+//   set 0: dA^O_i   [d_e, d]:  left = H^T  [b][k*d_e][l] (rows s*d_e + e of the pair), right = d_out [b][l][d]
+//   set 1: dA^I_i^T [d_e, d]:  left = dZ^T [b][k*d_e][l] (the same rows),              right = u     [b][l][d]
 template <typename T> struct WgradProblem {
-    const T *left_t, *right;
+    const T *left_t[2], *right[2];
     const int32_t *expert_idx;
-    float *partial;        // [n*splits, M, N]
+    float *partial;        // [sets*n*splits, M, N]
     int b, l, n, kact, splits;
     int M, N;              // rows and columns of one expert's gradient
     int left_rows;         // rows of one sample in left_t (k*d_e)
@@ -417,7 +420,7 @@ template <typename T> struct WgradProblem {
     __device__ int prepare(int g, uint32_t *segtab, int tid, int) const
     {
         __shared__ int slot_of[128];
-        const int expert = g / splits;
+        const int expert = (g % (n * splits)) / splits;
         if (tid < b) {
             int slot = -1;
             for (int s = 0; s < kact; ++s)
@@ -439,12 +442,14 @@ template <typename T> struct WgradProblem {
     __device__ const T *a_ptr_ctx(int g, int r, int, uint32_t ctx) const
     {
         const int bb = (int)(ctx >> 8), s = (int)(ctx & 0xFFu);
-        return left_t + ((size_t)bb * left_rows + (size_t)s * left_slot_rows + r) * l + (g % splits) * (l / splits);
+        const T *base = g < n * splits ? left_t[0] : left_t[1];
+        return base + ((size_t)bb * left_rows + (size_t)s * left_slot_rows + r) * l + (g % splits) * (l / splits);
     }
     __device__ const T *b_ptr_ctx(int g, int, int nn, uint32_t ctx) const
     {
         const int bb = (int)(ctx >> 8);
-        return right + ((size_t)bb * l + (size_t)(g % splits) * (l / splits)) * right_stride + nn;
+        const T *base = g < n * splits ? right[0] : right[1];
+        return base + ((size_t)bb * l + (size_t)(g % splits) * (l / splits)) * right_stride + nn;
     }
     static constexpr bool kRowScale = false;
     static constexpr bool kColScale = false;
@@ -459,21 +464,22 @@ template <typename T> struct WgradProblem {
     }
 };
 
-// ---------------------------------------------------------------------------------------------
-// Weight gradients of the SMHA block: for expert i,
+// Blocks with patch-wise data selection (SMHA; the data-selected UoME): for expert i,
 //   dW[M, d] = sum over the units (b, slot s) of expert i and their c picks t of
 //              L^T[unit][M rows][tokens of pick t]  x  R[b][tokens of the picked patch][d]
-// i.e. the left factor is a per-unit tensor in token-minor layout [unit][M][l_a] and the right
-// factor is a [b, l, d] tensor (x or the upstream gradient) whose rows are gathered patch by patch
-// (Eq. 18), never copied.  K segments = (unit, pick) of l_p tokens, in (sample, pick) order; the
-// list is cut into `splits` consecutive parts, group = expert * splits + j stores the fp32 partial
-// tile [group][M][d] of part j.
-//   dW^O_i           [d_h, d]:   left = (gated o)^T [unit][d_h][l_a],        right = d_out
-//   [dWq|dWk|dWv]_i^T [3d_h, d]: left = [dq|dk|dv]^T [unit][3d_h][l_a],     right = x
+// i.e. the left factor is a per-unit tensor in token-minor layout [unit][rows][l_a] (the set's M
+// rows start at row0 of the unit's rows) and the right factor is a [b, l, d] tensor (x, u or the
+// upstream gradient) whose rows are gathered patch by patch (Eq. 18), never copied.  K segments =
+// (unit, pick) of l_p tokens, in (sample, pick) order; the list is cut into `splits` consecutive
+// parts.
+//   SMHA, M = d_h:  sets 0-2: dW^{q,k,v}_i^T, left = [dq|dk|dv]^T [unit][3d_h][l_a] rows set*d_h.., right = x
+//                   set 3:    dW^O_i,         left = (gated o)^T  [unit][d_h][l_a],                  right = d_out
+//   UoME, M = d_e:  set 0: dA^O_i, left = H^T [unit][d_e][l_a], right = d_out;  set 1: dA^I_i^T, left = dZ^T, right = u
 template <typename T> struct SmhaWgradProblem {
-    const T *left_t, *right;
+    const T *left_t[4], *right[4];
+    int unit_rows[4], row0[4];  // rows of one unit in left_t[set]; first row of the set's M rows
     const int32_t *expert_idx, *patch_idx;
-    float *partial;
+    float *partial;             // [sets*n*splits, M, d]
     int b, l, d, n, kact, m, c, l_p, l_a, splits;
     int M;
 
@@ -488,7 +494,7 @@ template <typename T> struct SmhaWgradProblem {
     __device__ int prepare(int g, uint32_t *segtab, int tid, int nthreads) const
     {
         __shared__ int slot_of[128];
-        const int expert = g / splits, part = g - expert * splits;
+        const int ge = g % (n * splits), expert = ge / splits, part = ge - expert * splits;
         if (tid < b) {
             int slot = -1;
             for (int s = 0; s < kact; ++s)
@@ -515,15 +521,16 @@ template <typename T> struct SmhaWgradProblem {
         return max(0, min(last - first, 128)) * l_p;
     }
     __device__ uint32_t seg_ctx(int, int) const { return 0; }
-    __device__ const T *a_ptr_ctx(int, int r, int, uint32_t ctx) const
+    __device__ const T *a_ptr_ctx(int g, int r, int, uint32_t ctx) const
     {
         const int bb = (int)(ctx & 0x7Fu), s = (int)((ctx >> 7) & 0x1Fu), t = (int)((ctx >> 12) & 0x3FFu);
-        return left_t + (((size_t)bb * kact + s) * M + r) * l_a + (size_t)t * l_p;
+        const int set = g / (n * splits);
+        return left_t[set] + (((size_t)bb * kact + s) * unit_rows[set] + row0[set] + r) * l_a + (size_t)t * l_p;
     }
-    __device__ const T *b_ptr_ctx(int, int, int nn, uint32_t ctx) const
+    __device__ const T *b_ptr_ctx(int g, int, int nn, uint32_t ctx) const
     {
         const int bb = (int)(ctx & 0x7Fu), p = (int)(ctx >> 22);
-        return right + ((size_t)bb * l + (size_t)p * l_p) * d + nn;
+        return right[g / (n * splits)] + ((size_t)bb * l + (size_t)p * l_p) * d + nn;
     }
     static constexpr bool kRowScale = false;
     static constexpr bool kColScale = false;

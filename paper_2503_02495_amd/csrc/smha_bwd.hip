@@ -552,24 +552,25 @@ hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st)
     else err = launch_gemm_dma<OutProjProblem<T>, 64, 128, 32, 2, 2, 4, 2>(xp, f.b * f.m, l_p, f.d, st);
     if (err != hipSuccess) return err;
 
-    // weight gradients
+    // weight gradients, all four in one launch (M = d_h each): sets 0-2 = (dW^q, dW^k, dW^v)^T from
+    // the rows of [dq|dk|dv]^T against gathered x, set 3 = dW^O from (w*o)^T against gathered d_out
     SmhaWgradProblem<T> wp;
+    for (int q = 0; q < 3; ++q) {
+        wp.left_t[q] = static_cast<const T *>(a.dqkv_t); wp.right[q] = static_cast<const T *>(f.x);
+        wp.unit_rows[q] = 3 * dh; wp.row0[q] = q * dh;
+    }
+    wp.left_t[3] = static_cast<const T *>(a.o_t); wp.right[3] = static_cast<const T *>(a.d_out);
+    wp.unit_rows[3] = dh; wp.row0[3] = 0;
     wp.expert_idx = f.expert_idx; wp.patch_idx = f.patch_idx; wp.partial = a.partial;
     wp.b = f.b; wp.l = f.l; wp.d = f.d; wp.n = f.n; wp.kact = f.k; wp.m = f.m; wp.c = f.c;
-    wp.l_p = l_p; wp.l_a = l_a; wp.splits = a.splits;
+    wp.l_p = l_p; wp.l_a = l_a; wp.splits = a.splits; wp.M = dh;
+    if ((err = launch_gemm_dma_auto(wp, 4 * f.n * a.splits, dh, f.d, l_p, st)) != hipSuccess) return err;
     WgradReduceArgs ra{};
-    ra.partial = a.partial; ra.N = f.d; ra.splits = a.splits;
-
-    wp.left_t = static_cast<const T *>(a.o_t); wp.right = static_cast<const T *>(a.d_out); wp.M = dh;
-    if ((err = launch_gemm_dma_auto(wp, f.n * a.splits, dh, f.d, l_p, st)) != hipSuccess) return err;
-    ra.M = dh; ra.parts = 1; ra.transposed = 0; ra.dst[0] = static_cast<uint16_t *>(a.d_wo);
-    if ((err = launch_wgrad_reduce(ra, f.n, st)) != hipSuccess) return err;
-
-    wp.left_t = static_cast<const T *>(a.dqkv_t); wp.right = static_cast<const T *>(f.x); wp.M = 3 * dh;
-    if ((err = launch_gemm_dma_auto(wp, f.n * a.splits, 3 * dh, f.d, l_p, st)) != hipSuccess) return err;
-    ra.M = 3 * dh; ra.parts = 3; ra.transposed = 1;
-    ra.dst[0] = static_cast<uint16_t *>(a.d_wq); ra.dst[1] = static_cast<uint16_t *>(a.d_wk); ra.dst[2] = static_cast<uint16_t *>(a.d_wv);
-    return launch_wgrad_reduce(ra, f.n, st);
+    ra.partial = a.partial; ra.n = f.n; ra.M = dh; ra.N = f.d; ra.splits = a.splits;
+    ra.dst[0] = static_cast<uint16_t *>(a.d_wq); ra.dst[1] = static_cast<uint16_t *>(a.d_wk);
+    ra.dst[2] = static_cast<uint16_t *>(a.d_wv); ra.dst[3] = static_cast<uint16_t *>(a.d_wo);
+    ra.transposed[0] = ra.transposed[1] = ra.transposed[2] = 1; ra.transposed[3] = 0;
+    return launch_wgrad_reduce(ra, 4, st);
 }
 
 }  // namespace uoe

@@ -187,22 +187,20 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e; up.flags = a.flags;
     if ((err = launch_gemm_dma_auto(up, a.b, a.l, a.d, a.d_e, st)) != hipSuccess) return err;
 
-    // weight gradients: [d_e, d] tiles per expert, token axis cut into a.splits ranges
+    // weight gradients, both in one launch: [d_e, d] tiles per expert, token axis cut into a.splits
+    // ranges; (dA^I_i)^T = sum dZ_{b,s}^T u_b is stored back as [d, d_e] by the reduction
+    WgradProblem<T> wp;
+    wp.left_t[0] = static_cast<const T *>(a.h_t); wp.right[0] = static_cast<const T *>(a.d_out);  // dA^O_i
+    wp.left_t[1] = static_cast<const T *>(a.dz_t); wp.right[1] = static_cast<const T *>(a.u);     // (dA^I_i)^T
+    wp.expert_idx = a.expert_idx; wp.partial = a.partial;
+    wp.b = a.b; wp.l = a.l; wp.n = a.n; wp.kact = a.k; wp.splits = a.splits;
+    wp.M = a.d_e; wp.N = a.d; wp.left_rows = width; wp.left_slot_rows = a.d_e; wp.right_stride = a.d;
+    if ((err = launch_gemm_dma_auto(wp, 2 * a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
     WgradReduceArgs ra{};
-    ra.partial = a.partial; ra.M = a.d_e; ra.N = a.d; ra.splits = a.splits; ra.parts = 1;
-    WgradProblem<T> wo;  // dA^O_i = sum H_{b,s}^T d_out_b
-    wo.left_t = static_cast<const T *>(a.h_t); wo.right = static_cast<const T *>(a.d_out);
-    wo.expert_idx = a.expert_idx; wo.partial = a.partial;
-    wo.b = a.b; wo.l = a.l; wo.n = a.n; wo.kact = a.k; wo.splits = a.splits;
-    wo.M = a.d_e; wo.N = a.d; wo.left_rows = width; wo.left_slot_rows = a.d_e; wo.right_stride = a.d;
-    if ((err = launch_gemm_dma_auto(wo, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
-    ra.dst[0] = static_cast<uint16_t *>(a.d_a_out); ra.transposed = 0;
-    if ((err = launch_wgrad_reduce(ra, a.n, st)) != hipSuccess) return err;
-    WgradProblem<T> wi = wo;  // (dA^I_i)^T = sum dZ_{b,s}^T u_b, stored back as [d, d_e] by the reduction
-    wi.left_t = static_cast<const T *>(a.dz_t); wi.right = static_cast<const T *>(a.u);
-    if ((err = launch_gemm_dma_auto(wi, a.n * a.splits, a.d_e, a.d, a.l / a.splits, st)) != hipSuccess) return err;
-    ra.dst[0] = static_cast<uint16_t *>(a.d_a_in); ra.transposed = 1;
-    return launch_wgrad_reduce(ra, a.n, st);
+    ra.partial = a.partial; ra.n = a.n; ra.M = a.d_e; ra.N = a.d; ra.splits = a.splits;
+    ra.dst[0] = static_cast<uint16_t *>(a.d_a_out); ra.transposed[0] = 0;
+    ra.dst[1] = static_cast<uint16_t *>(a.d_a_in); ra.transposed[1] = 1;
+    return launch_wgrad_reduce(ra, 2, st);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -322,20 +320,20 @@ hipError_t launch_uome_ds_backward(const UomeBwdArgs &a, hipStream_t st)
     else err = launch_gemm_dma<OutProjProblem<T>, 64, 128, 32, 2, 2, 4, 2>(xp, a.b * a.m, l_p, a.d, st);
     if (err != hipSuccess) return err;
 
-    SmhaWgradProblem<T> wp;
+    SmhaWgradProblem<T> wp;  // both weight gradients in one launch
+    wp.left_t[0] = static_cast<const T *>(a.h_t); wp.right[0] = static_cast<const T *>(a.d_out);  // dA^O_i
+    wp.left_t[1] = static_cast<const T *>(a.dz_t); wp.right[1] = static_cast<const T *>(a.u);     // (dA^I_i)^T
+    wp.left_t[2] = wp.left_t[3] = wp.right[2] = wp.right[3] = nullptr;
+    for (int q = 0; q < 4; ++q) { wp.unit_rows[q] = a.d_e; wp.row0[q] = 0; }
     wp.expert_idx = a.expert_idx; wp.patch_idx = a.patch_idx; wp.partial = a.partial;
     wp.b = a.b; wp.l = a.l; wp.d = a.d; wp.n = a.n; wp.kact = a.k; wp.m = a.m; wp.c = a.c;
     wp.l_p = l_p; wp.l_a = l_a; wp.splits = a.splits; wp.M = a.d_e;
+    if ((err = launch_gemm_dma_auto(wp, 2 * a.n * a.splits, a.d_e, a.d, l_p, st)) != hipSuccess) return err;
     WgradReduceArgs ra{};
-    ra.partial = a.partial; ra.M = a.d_e; ra.N = a.d; ra.splits = a.splits; ra.parts = 1;
-    wp.left_t = static_cast<const T *>(a.h_t); wp.right = static_cast<const T *>(a.d_out);  // dA^O_i
-    if ((err = launch_gemm_dma_auto(wp, a.n * a.splits, a.d_e, a.d, l_p, st)) != hipSuccess) return err;
-    ra.dst[0] = static_cast<uint16_t *>(a.d_a_out); ra.transposed = 0;
-    if ((err = launch_wgrad_reduce(ra, a.n, st)) != hipSuccess) return err;
-    wp.left_t = static_cast<const T *>(a.dz_t); wp.right = static_cast<const T *>(a.u);     // (dA^I_i)^T
-    if ((err = launch_gemm_dma_auto(wp, a.n * a.splits, a.d_e, a.d, l_p, st)) != hipSuccess) return err;
-    ra.dst[0] = static_cast<uint16_t *>(a.d_a_in); ra.transposed = 1;
-    return launch_wgrad_reduce(ra, a.n, st);
+    ra.partial = a.partial; ra.n = a.n; ra.M = a.d_e; ra.N = a.d; ra.splits = a.splits;
+    ra.dst[0] = static_cast<uint16_t *>(a.d_a_out); ra.transposed[0] = 0;
+    ra.dst[1] = static_cast<uint16_t *>(a.d_a_in); ra.transposed[1] = 1;
+    return launch_wgrad_reduce(ra, 2, st);
 }
 
 }  // namespace uoe
