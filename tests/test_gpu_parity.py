@@ -351,6 +351,8 @@ SMHA_BWD_CONFIGS = {
     "sb_dh64": small(b=3, l=192, d=96, n_a=4, d_h=64, m=3, c=2, k_a=2, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
     # l_a = 96: a ragged last key/query tile; d_h = 128; every patch selected by the one active expert or not at all
     "sb_dh128_tail": small(b=2, l=160, d=64, n_a=2, d_h=128, m=5, c=3, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
+    # l_a = 32: one 32-row group per unit, half-empty key tile; d = 32 (K segments of 32)
+    "sb_la32": small(b=2, l=64, d=32, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
     # l_a = 320: several query blocks and key tiles per unit
     "sb_long": small(b=2, l=512, d=64, n_a=3, d_h=32, m=8, c=5, k_a=2, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
 }
@@ -520,6 +522,50 @@ def test_layer_backward_parity(name, fa, rope_dim):
         errs[nm], fro[nm] = grad_err(y, r), fro_err(y, r)
     print(f"[layer backward {name} fa={fa}] " + " ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
     print(f"[layer backward {name} fa={fa}] fro " + " ".join(f"{k} {v:.2e}" for k, v in fro.items()), flush=True)
+    assert max(errs.values()) <= LAYER_BWD_TOL and max(fro.values()) <= LAYER_BWD_FRO_TOL
+
+
+@pytest.mark.parametrize("mode", ["expert_only", "data_only"])
+def test_layer_backward_with_single_mode_smha(mode):
+    """The paper's default of one selection mode per block (Sec. III-B) in the backward pass: an SMHA
+    block without data router (every active expert sees the whole sample) or without expert router
+    (every expert active on its own patches); the absent router gets no gradient call."""
+    import dataclasses
+    base = synth.CONFIGS["lm"]
+    cfg = dataclasses.replace(base, c=base.m) if mode == "expert_only" else dataclasses.replace(base, k_a=base.n_a)
+    print(f"layer backward, {mode} SMHA", flush=True)
+    inp = synth.make_inputs(cfg)
+    for attr in ("a_w_expert", "m_w_expert"):
+        setattr(inp, attr, getattr(inp, attr) * np.float32(2.0 ** -np.ceil(np.log2(0.02 * np.sqrt(cfg.l * cfg.d)))))
+    if mode == "expert_only":
+        inp.a_w_b = inp.a_w_a = inp.noise_a_patch = None
+        fa = R | GE
+    else:
+        inp.a_w_expert = inp.noise_a_expert = None
+        fa = R | GP
+    fm = R | GE
+    d_out = synth.make_upstream_grad(cfg)
+    fwd = oracle.layer_forward(inp, fa, fm)
+    ra, rm = fwd.routing_a, fwd.routing_m
+    ge_a, gp_a, ge_m = (g.astype(np.float32) for g in (ra.expert_gate, ra.patch_gate, rm.expert_gate))
+    dev = DeviceLayer(inp, fa, fm)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev.device)
+    f32 = lambda a: to_device(a, synth.F32, dev.device)
+    keep = [i32(ra.expert_id), f32(ge_a), i32(ra.patch_id), f32(gp_a), i32(rm.expert_id), f32(ge_m)]
+    g = dev.layer_backward(to_device(d_out, cfg.dtype, dev.device), routing_a=B.routing_out(*keep[:4]),
+                           routing_m=B.routing_out(*keep[4:]))
+    torch.cuda.synchronize()
+    want = oracle.layer_backward(inp, fwd, d_out, fa, fm, 0, gates_a=(ge_a, gp_a), gate_m=ge_m)
+    refs = {"d_x": want.d_x, "d_wq": want.smha.d_wq, "d_wo": want.smha.d_wo, "d_a_in": want.uome.d_a_in,
+            "d_m_w_expert": want.route_m.d_w_expert.reshape(1, -1)}
+    if mode == "expert_only":
+        refs["d_a_w_expert"] = want.route_a.d_w_expert.reshape(1, -1)
+    else:
+        refs["d_a_w_b"] = want.route_a.d_w_b.reshape(1, -1)
+        refs["d_a_w_a"] = want.route_a.d_w_a.reshape(1, -1)
+    errs = {nm: grad_err(to_host(g[nm]).reshape(r.shape), r) for nm, r in refs.items()}
+    fro = {nm: fro_err(to_host(g[nm]).reshape(r.shape), r) for nm, r in refs.items()}
+    print(f"[layer backward {mode}] " + " ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
     assert max(errs.values()) <= LAYER_BWD_TOL and max(fro.values()) <= LAYER_BWD_FRO_TOL
 
 
