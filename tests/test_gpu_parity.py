@@ -478,7 +478,8 @@ def test_route_backward_parity(name):
 # --------------------------------------------------------------------------- layer backward
 @pytest.mark.parametrize("name,fa,rope_dim", [("sb_dh64", R | GE | GP, 0), ("sb_long", R | GE | GP | CA, 16),
                                               ("lm", R | GE | GP, 0), ("lm", R | GE | GP | CA, 32),
-                                              ("ds_bf16_lp32", R | GE | GP, 0), ("ds_lm", R | GE | GP | CA, 32)])
+                                              ("ds_bf16_lp32", R | GE | GP, 0), ("ds_lm", R | GE | GP | CA, 32),
+                                              ("longrange", R | GE | GP, 0)])
 def test_layer_backward_parity(name, fa, rope_dim):
     """uoe_layer_backward (UoME backward, its router(s), SMHA backward, its routers, chained on the
     device) against the oracle's chain, on the oracle's routing and the fp32-rounded gates; the
