@@ -265,11 +265,11 @@ def main() -> int:
         oracle.layer_forward(sub, fa, fm, args.rope_dim) if fl["total"] * nb / cfg.b < 2e10 else None   # warm the pages
         passes = 0
         c0 = time.perf_counter()
-        while True:   # whole passes until about 5 s of CPU work have been timed
+        while True:   # whole passes until about 10 s of CPU work have been timed
             oracle.layer_forward(sub, fa, fm, args.rope_dim)
             passes += 1
             c1 = time.perf_counter()
-            if c1 - c0 >= 5.0 or passes >= 200:
+            if c1 - c0 >= 10.0 or passes >= 400:
                 break
         cpu = {"value": round(passes * nb * cfg.l / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.get_threads(),
                "kind": "oracle", "sample": f"{nb} of {cfg.b} samples of the {cfg.name} workload, {passes} fp64 "
