@@ -265,6 +265,9 @@ BWD_CONFIGS = {
     "bwd_ragged": small(b=5, l=160, d=96, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=4, d_e=160, k_m=3, dtype=synth.BF16),
     # long token axis, few experts: the weight-gradient launch cuts the token axis into 4 ranges
     "bwd_split4": small(b=8, l=1024, d=32, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
+    # the largest batch the backward accepts, one expert that every sample selects: 128 K segments,
+    # the whole segment table of a weight-gradient workgroup
+    "bwd_b128": small(b=128, l=32, d=32, n_a=2, d_h=32, m=1, c=1, k_a=1, n_m=1, d_e=32, k_m=1, dtype=synth.BF16),
     "bwd_k1": small(b=3, l=32, d=32, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=3, d_e=32, k_m=1, dtype=synth.BF16),
 }
 
@@ -288,6 +291,12 @@ def grad_err(y, r):
     if not live.any():
         return 0.0
     return float(np.max(np.abs(y2[live] - r2[live]) / np.maximum(np.maximum(np.abs(r2[live]), rms[live]), 1e-30)))
+
+
+def gate_err(y, r):
+    """grad_err with the whole tensor as one slice: a gate gradient is a sum of signed row terms, and
+    a sample whose terms cancel has nothing of its own to be judged against."""
+    return grad_err(np.asarray(y).reshape(1, -1), np.asarray(r).reshape(1, -1))
 
 
 def fro_err(y, r):
@@ -326,7 +335,7 @@ def test_uome_backward_parity(name, flags):
     got_in, got_out = to_host(d_a_in), to_host(d_a_out)
     assert not np.any(got_in[unused]) and not np.any(got_out[unused])
     errs = {"d_u": grad_err(to_host(d_u), want.d_u), "d_a_in": grad_err(got_in, want.d_a_in),
-            "d_a_out": grad_err(got_out, want.d_a_out), "d_gate": grad_err(to_host(d_gate), want.d_gate)}
+            "d_a_out": grad_err(got_out, want.d_a_out), "d_gate": gate_err(to_host(d_gate), want.d_gate)}
     fro = max(fro_err(to_host(d_u), want.d_u), fro_err(got_in, want.d_a_in), fro_err(got_out, want.d_a_out),
               fro_err(to_host(d_gate), want.d_gate))
     assert fro <= 6e-3, fro
@@ -353,6 +362,8 @@ SMHA_BWD_CONFIGS = {
     "sb_dh128_tail": small(b=2, l=160, d=64, n_a=2, d_h=128, m=5, c=3, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
     # l_a = 32: one 32-row group per unit, half-empty key tile; d = 32 (K segments of 32)
     "sb_la32": small(b=2, l=64, d=32, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
+    # the largest batch, one expert, one pick each: 128 (unit, pick) segments in one part
+    "sb_b128": small(b=128, l=64, d=32, n_a=1, d_h=32, m=2, c=1, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
     # l_a = 320: several query blocks and key tiles per unit
     "sb_long": small(b=2, l=512, d=64, n_a=3, d_h=32, m=8, c=5, k_a=2, n_m=2, d_e=32, k_m=1, dtype=synth.BF16),
 }
@@ -368,10 +379,11 @@ SMHA_BWD_TOL = 3e-2
 BWD_FRO_TOL = 6e-3
 # A gate gradient is a sum of a few row terms r_t = dO_t . o_t (l_p of them for a patch gate), and a dot
 # product of two rounded vectors is in error by eps * |dO_t| * |o_t|, not by eps * |r_t|: terms that
-# cancel leave the error behind.  Under the causal and padding masks (rows with one or two keys are
-# several times larger than the rest) single patch gates read up to 5.2e-2 of their sample's rms while
-# the tensor's Frobenius error stays at 2-4e-3; the worst-element bound for the gate gradients is 8e-2.
-GATE_GRAD_TOL = 8e-2
+# cancel leave the error behind, so a gate gradient is judged against the rms of the whole tensor (a
+# sample with one expert has a single entry and no rms of its own).  Under the causal and padding
+# masks (rows with one or two keys are several times larger than the rest) single patch gates read up
+# to 2.9e-2 of that rms while the tensor's Frobenius error stays at 2-4e-3; the bound is 4e-2.
+GATE_GRAD_TOL = 4e-2
 # The chained layer backward adds the UoME backward's roundings and the bf16 hand-over of dL/du in
 # front of the SMHA backward's, and the router gradients inherit the gate gradients' error.
 LAYER_BWD_TOL = 4e-2
@@ -423,7 +435,7 @@ def run_smha_backward(name, flags, rope_dim, pad_frac=0.0):
         assert torch.isfinite(g.float()).all()
     names = ("d_x", "d_wq", "d_wk", "d_wv", "d_wo", "d_expert_gate", "d_patch_gate")
     refs = (want.d_x, want.d_wq, want.d_wk, want.d_wv, want.d_wo, want.d_expert_gate, want.d_patch_gate)
-    errs = {nm: grad_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
+    errs = {nm: (gate_err if "gate" in nm else grad_err)(to_host(g), r) for nm, g, r in zip(names, got, refs)}
     fro = {nm: fro_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
     print(f"[smha backward {name} flags={flags}] fro " + " ".join(f"{k} {v:.2e}" for k, v in fro.items()), flush=True)
     unused = np.setdiff1d(np.arange(cfg.n_a), ref.expert_id.ravel())
@@ -726,7 +738,7 @@ def test_uome_data_selection_backward_parity(name, flags):
     want = oracle.uome_backward(inp.x, inp.a_in, inp.a_out, ref.expert_id, ge, d_out, flags, ref.patch_id, gp, cfg.m_m)
     refs = (want.d_u, want.d_a_in, want.d_a_out, want.d_gate, want.d_patch_gate)
     names = ("d_u", "d_a_in", "d_a_out", "d_gate", "d_patch_gate")
-    errs = {nm: grad_err(to_host(g), r) for nm, g, r in zip(names, got, refs)}
+    errs = {nm: (gate_err if "gate" in nm else grad_err)(to_host(g), r) for nm, g, r in zip(names, got, refs)}
     fro = max(fro_err(to_host(g), r) for g, r in zip(got, refs))
     unused = np.setdiff1d(np.arange(cfg.n_m), ref.expert_id.ravel())
     assert not np.any(to_host(got[1])[unused]) and not np.any(to_host(got[2])[unused])
