@@ -88,6 +88,29 @@ def run_stage(args, cfg, dev, B, torch) -> int:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).normal_()
         dst = torch.empty_like(src)
         calls["copy"] = lambda: dst.copy_(src)
+    if args.stage == "lib_gemm":   # context only: the vendor library's plain batched GEMM (no expert lookup, no SiLU,
+        # no gate, no residual) on the shapes of the two UoME GEMMs; nothing in the path calls it
+        ncol = cfg.k_m * cfg.d_e
+        ga = torch.empty((cfg.b, cfg.l, cfg.d), dtype=dev.tdtype, device=dev.device).normal_()
+        gw1 = torch.empty((cfg.b, cfg.d, ncol), dtype=dev.tdtype, device=dev.device).normal_()
+        gh = torch.empty((cfg.b, cfg.l, ncol), dtype=dev.tdtype, device=dev.device)
+        gw2 = torch.empty((cfg.b, ncol, cfg.d), dtype=dev.tdtype, device=dev.device).normal_()
+        go = torch.empty((cfg.b, cfg.l, cfg.d), dtype=dev.tdtype, device=dev.device)
+        res = {}
+        for nm, f in (("up_shape", lambda: torch.bmm(ga, gw1, out=gh)), ("down_shape", lambda: torch.bmm(gh, gw2, out=go))):
+            for _ in range(args.warmup):
+                f()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.steps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / args.steps
+            res[nm] = {"us_per_call": round(us, 3), "tflops": round(2.0 * cfg.b * cfg.l * cfg.d * ncol / us * 1e-6, 1)}
+        print(json.dumps({"stage": "lib_gemm", "workload": cfg.name, "steps": args.steps, **res}))
+        return 0
     fn = calls[args.stage]
     for _ in range(args.warmup):
         fn()
@@ -124,7 +147,7 @@ def main() -> int:
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
                     choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather", "copy",
-                             "uome_bwd", "smha_bwd", "route_bwd", "layer_bwd", "layer_fwd_bwd"],
+                             "uome_bwd", "smha_bwd", "route_bwd", "layer_bwd", "layer_fwd_bwd", "lib_gemm"],
                     help="profiling aid: loop one C-ABI call of the path instead of the whole layer "
                          "and print its time (no JSON contract line)")
     args = ap.parse_args()
