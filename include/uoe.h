@@ -301,6 +301,20 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
                       const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, void *ws,
                       size_t ws_bytes, void *hip_stream);
 
+/*
+ * uoe_layer_forward with a padding mask on the SMHA block (Eq. 41, Sec. III-C.3): pad_mask [b,l]
+ * bytes on the device, 1 = token, 0 = padding, as in uoe_smha_forward_masked (padded keys are out
+ * of every attention softmax; routing and UoME see every row).  pad_mask == NULL is
+ * uoe_layer_forward.  Same workspace.
+ */
+int uoe_layer_forward_masked(const uoe_block_desc *smha, const uoe_smha_weights *wa,
+                             const float *noise_a_expert, const float *noise_a_patch,
+                             const uoe_block_desc *uome, const uoe_uome_weights *wm,
+                             const float *noise_m_expert, const void *x, const uint8_t *pad_mask,
+                             void *out, const uoe_routing_out *routing_a,
+                             const uoe_routing_out *routing_m, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+
 /* Gradients of a block's router weights, shaped like the weights; a member may be NULL when the
  * block has no such router. */
 typedef struct {
@@ -331,6 +345,20 @@ int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
                        const uoe_smha_weight_grads *dwa, const uoe_router_grads *dra, void *d_a_in,
                        void *d_a_out, const uoe_router_grads *drm, void *ws, size_t ws_bytes,
                        void *hip_stream);
+
+/*
+ * Backward pass of uoe_layer_forward_masked: uoe_layer_backward with the forward call's padding
+ * mask (Eq. 41) handed to the SMHA block's backward pass and to the recomputation of u.
+ * pad_mask == NULL is uoe_layer_backward.  Same workspace.
+ */
+int uoe_layer_backward_masked(const uoe_block_desc *smha, const uoe_smha_weights *wa,
+                              const uoe_block_desc *uome, const uoe_uome_weights *wm,
+                              const void *x, const uint8_t *pad_mask, const void *u,
+                              const uoe_routing_out *routing_a, const uoe_routing_out *routing_m,
+                              const void *d_out, void *d_x, const uoe_smha_weight_grads *dwa,
+                              const uoe_router_grads *dra, void *d_a_in, void *d_a_out,
+                              const uoe_router_grads *drm, void *ws, size_t ws_bytes,
+                              void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -499,16 +499,17 @@ class LayerResult:
 
 
 def layer_forward(inp, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
-                  flags_m: int = RESIDUAL | GATE_EXPERT, rope_dim: int = 0) -> LayerResult:
+                  flags_m: int = RESIDUAL | GATE_EXPERT, rope_dim: int = 0, pad_mask=None) -> LayerResult:
     """One UoE layer (Sec. III-C): out = UoME(SMHA(x)); `inp` is a LayerInputs-like object.
 
-    The UoME router reads u, the finished SMHA output.
+    The UoME router reads u, the finished SMHA output.  pad_mask [b,l] (Eq. 41) acts inside the
+    attention of the SMHA block only.
     """
     cfg = inp.cfg
     ra = route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
                inp.noise_a_expert, inp.noise_a_patch)
     u = smha(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ra.expert_gate, ra.patch_id,
-             ra.patch_gate, cfg.m, flags_a, rope_dim)
+             ra.patch_gate, cfg.m, flags_a, rope_dim, pad_mask)
     if getattr(cfg, "m_m", 1) > 1:  # UoME with patch-wise data selection (Eq. 37)
         rm = route(u, cfg.n_m, cfg.k_m, cfg.m_m, cfg.c_m, inp.m_w_expert, inp.m_w_b, inp.m_w_a,
                    inp.noise_m_expert, inp.noise_m_patch)
@@ -530,12 +531,13 @@ class LayerGrads:
 
 def layer_backward(inp, fwd: LayerResult, d_out, flags_a: int = RESIDUAL | GATE_EXPERT | GATE_PATCH,
                    flags_m: int = RESIDUAL | GATE_EXPERT, rope_dim: int = 0, gates_a=None, gate_m=None,
-                   patch_gate_m=None) -> LayerGrads:
+                   patch_gate_m=None, pad_mask=None) -> LayerGrads:
     """Gradients of layer_forward for d_out = dL/d(out): the chain rule through
     out = UoME(u; routers on u), u = SMHA(x; routers on x), the selections held constant.
 
     `fwd` is the forward result whose routing is differentiated through; gates_a = (expert, patch)
-    and gate_m override the gate VALUES used (a test passes the fp32-rounded gates the device gets)."""
+    and gate_m override the gate VALUES used (a test passes the fp32-rounded gates the device gets);
+    pad_mask is the forward call's (Eq. 41)."""
     cfg = inp.cfg
     ra, rm = fwd.routing_a, fwd.routing_m
     ge_a, gp_a = (ra.expert_gate, ra.patch_gate) if gates_a is None else gates_a
@@ -552,6 +554,6 @@ def layer_backward(inp, fwd: LayerResult, d_out, flags_a: int = RESIDUAL | GATE_
             rgm = RouteGrads(np.zeros_like(gm.d_u), None, None, None)
     d_u = gm.d_u + rgm.d_x
     ga = smha_backward(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ge_a, ra.patch_id, gp_a, cfg.m, d_u,
-                       flags_a, rope_dim)
+                       flags_a, rope_dim, pad_mask)
     rga = route_backward(inp.x, inp.a_w_expert, inp.a_w_b, inp.a_w_a, ge_a, gp_a, ga.d_expert_gate, ga.d_patch_gate)
     return LayerGrads(ga.d_x + rga.d_x, ga, rga, gm, rgm)

@@ -19,11 +19,11 @@ FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
 EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward",
            "uoe_smha_forward_masked",
-           "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward",
+           "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward", "uoe_layer_forward_masked",
            "uoe_uome_backward_workspace_bytes", "uoe_uome_backward",
            "uoe_smha_backward_workspace_bytes", "uoe_smha_backward",
            "uoe_route_backward_workspace_bytes", "uoe_route_backward",
-           "uoe_layer_backward_workspace_bytes", "uoe_layer_backward")
+           "uoe_layer_backward_workspace_bytes", "uoe_layer_backward", "uoe_layer_backward_masked")
 
 
 class UoeError(RuntimeError):
@@ -99,13 +99,21 @@ def lib():
                                          ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut), P, P,
                                          ctypes.POINTER(SmhaWeightGrads), ctypes.POINTER(RouterGrads), P, P,
                                          ctypes.POINTER(RouterGrads), P, S, P]
+        L.uoe_layer_backward_masked.argtypes = [D, ctypes.POINTER(SmhaWeights), D, ctypes.POINTER(UomeWeights), P, P, P,
+                                                ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut), P, P,
+                                                ctypes.POINTER(SmhaWeightGrads), ctypes.POINTER(RouterGrads), P, P,
+                                                ctypes.POINTER(RouterGrads), P, S, P]
         L.uoe_uome_up.argtypes = [D, P, P, P, P, P, P]
         L.uoe_uome_down.argtypes = [D, P, P, P, P, P, P]
         L.uoe_layer_forward.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
                                         P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
                                         P, S, P]
+        L.uoe_layer_forward_masked.argtypes = [D, ctypes.POINTER(SmhaWeights), P, P, D, ctypes.POINTER(UomeWeights),
+                                               P, P, P, P, ctypes.POINTER(RoutingOut), ctypes.POINTER(RoutingOut),
+                                               P, S, P]
         for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
-                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward", "uoe_route_backward", "uoe_layer_backward"):
+                  "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward", "uoe_route_backward", "uoe_layer_backward",
+                  "uoe_layer_forward_masked", "uoe_layer_backward_masked"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -263,6 +271,18 @@ def layer_backward(smha, wa: SmhaWeights, uome, wm: UomeWeights, x, u, routing_a
     return _done(st, "uoe_layer_backward", check)
 
 
+def layer_backward_masked(smha, wa: SmhaWeights, uome, wm: UomeWeights, x, pad_mask, u, routing_a: RoutingOut,
+                          routing_m: RoutingOut, d_out, d_x, dwa: SmhaWeightGrads, dra: Optional[RouterGrads], d_a_in,
+                          d_a_out, drm: Optional[RouterGrads], ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_layer_backward_masked(_ref(smha), ctypes.byref(wa), _ref(uome), ctypes.byref(wm), _ptr(x),
+                                         _ptr(pad_mask), _ptr(u), ctypes.byref(routing_a), ctypes.byref(routing_m),
+                                         _ptr(d_out), _ptr(d_x), ctypes.byref(dwa),
+                                         None if dra is None else ctypes.byref(dra), _ptr(d_a_in), _ptr(d_a_out),
+                                         None if drm is None else ctypes.byref(drm), _ptr(ws),
+                                         _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_layer_backward_masked", check)
+
+
 def uome_up(blk, u, a_in, expert_idx, expert_gate, hidden, stream=None, check=True) -> int:
     st = lib().uoe_uome_up(_ref(blk), _ptr(u), _ptr(a_in), _ptr(expert_idx), _ptr(expert_gate), _ptr(hidden),
                            _stream(stream))
@@ -297,3 +317,15 @@ def layer_forward(smha, wa: SmhaWeights, noise_a_expert, noise_a_patch, uome, wm
                                  ctypes.byref(routing_m) if routing_m is not None else None, _ptr(ws),
                                  _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_layer_forward", check)
+
+
+def layer_forward_masked(smha, wa: SmhaWeights, noise_a_expert, noise_a_patch, uome, wm: UomeWeights,
+                         noise_m_expert, x, pad_mask, out, routing_a: Optional[RoutingOut],
+                         routing_m: Optional[RoutingOut], ws, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_layer_forward_masked(_ref(smha), ctypes.byref(wa) if wa is not None else None, _ptr(noise_a_expert),
+                                        _ptr(noise_a_patch), _ref(uome), ctypes.byref(wm) if wm is not None else None,
+                                        _ptr(noise_m_expert), _ptr(x), _ptr(pad_mask), _ptr(out),
+                                        ctypes.byref(routing_a) if routing_a is not None else None,
+                                        ctypes.byref(routing_m) if routing_m is not None else None, _ptr(ws),
+                                        _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    return _done(st, "uoe_layer_forward_masked", check)

@@ -595,6 +595,17 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
                       const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, void *ws,
                       size_t ws_bytes, void *hip_stream)
 {
+    return uoe_layer_forward_masked(smha, wa, noise_a_expert, noise_a_patch, uome, wm, noise_m_expert, x, nullptr, out,
+                                    routing_a, routing_m, ws, ws_bytes, hip_stream);
+}
+
+int uoe_layer_forward_masked(const uoe_block_desc *smha, const uoe_smha_weights *wa,
+                             const float *noise_a_expert, const float *noise_a_patch,
+                             const uoe_block_desc *uome, const uoe_uome_weights *wm,
+                             const float *noise_m_expert, const void *x, const uint8_t *pad_mask, void *out,
+                             const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, void *ws,
+                             size_t ws_bytes, void *hip_stream)
+{
     int rc = check_desc(smha, DESC_SMHA);
     if (rc != UOE_OK) return rc;
     rc = check_desc(uome, DESC_UOME);
@@ -655,7 +666,7 @@ int uoe_layer_forward(const uoe_block_desc *smha, const uoe_smha_weights *wa,
     rc = do_route(smha, smha->m, smha->c, x, wa->w_expert, wa->w_b, wa->w_a, noise_a_expert, noise_a_patch,
                   a_eidx, a_egate, a_pidx, a_pgate, route_a_ws, route_a_bytes, st);
     if (rc != UOE_OK) return rc;
-    rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, a_eidx, a_egate, a_pidx, a_pgate, nullptr, u, smha_scratch,
+    rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, a_eidx, a_egate, a_pidx, a_pgate, pad_mask, u, smha_scratch,
                  smha_bytes, st);
     if (rc != UOE_OK) return rc;
     // the UoME routers read u, the finished SMHA output
@@ -727,6 +738,16 @@ int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa, c
                        const uoe_router_grads *dra, void *d_a_in, void *d_a_out, const uoe_router_grads *drm, void *ws,
                        size_t ws_bytes, void *hip_stream)
 {
+    return uoe_layer_backward_masked(smha, wa, uome, wm, x, nullptr, u, routing_a, routing_m, d_out, d_x, dwa, dra, d_a_in,
+                                     d_a_out, drm, ws, ws_bytes, hip_stream);
+}
+
+int uoe_layer_backward_masked(const uoe_block_desc *smha, const uoe_smha_weights *wa, const uoe_block_desc *uome,
+                              const uoe_uome_weights *wm, const void *x, const uint8_t *pad_mask, const void *u,
+                              const uoe_routing_out *routing_a, const uoe_routing_out *routing_m, const void *d_out,
+                              void *d_x, const uoe_smha_weight_grads *dwa, const uoe_router_grads *dra, void *d_a_in,
+                              void *d_a_out, const uoe_router_grads *drm, void *ws, size_t ws_bytes, void *hip_stream)
+{
     if (!smha || !uome) return UOE_ERR_INVALID_ARG;
     int rc = check_layer_bwd(smha, uome);
     if (rc != UOE_OK) return rc;
@@ -756,7 +777,7 @@ int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa, c
     if (!u) {  // u = SMHA(x) with the given routing
         void *u_ws = at(ws, w.u);
         rc = do_smha(smha, x, wa->wq, wa->wk, wa->wv, wa->wo, routing_a->expert_idx, routing_a->expert_gate,
-                     routing_a->patch_idx, routing_a->patch_gate, nullptr, u_ws, stage, w.stage_bytes, st);
+                     routing_a->patch_idx, routing_a->patch_gate, pad_mask, u_ws, stage, w.stage_bytes, st);
         if (rc != UOE_OK) return rc;
         u = u_ws;
     }
@@ -774,7 +795,7 @@ int uoe_layer_backward(const uoe_block_desc *smha, const uoe_smha_weights *wa, c
     }
     // SMHA block and its routers: d_u -> d_x
     rc = uoe_smha_backward(smha, x, wa, routing_a->expert_idx, routing_a->expert_gate, routing_a->patch_idx,
-                           routing_a->patch_gate, nullptr, d_u, d_x, dwa, d_gate_a, d_pgate_a, stage, w.stage_bytes, hip_stream);
+                           routing_a->patch_gate, pad_mask, d_u, d_x, dwa, d_gate_a, d_pgate_a, stage, w.stage_bytes, hip_stream);
     if (rc != UOE_OK) return rc;
     if (route_a)
         rc = uoe_route_backward(smha, x, wa->w_expert, wa->w_b, wa->w_a, routing_a->expert_gate, routing_a->patch_gate,

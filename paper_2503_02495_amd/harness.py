@@ -148,9 +148,10 @@ class DeviceLayer:
                         self.d_a_expert_gate, self.d_a_patch_gate, self.smha_bwd_ws)
         return self.d_x, self.d_wq, self.d_wk, self.d_wv, self.d_wo, self.d_a_expert_gate, self.d_a_patch_gate
 
-    def layer_backward(self, d_out, routing_a=None, routing_m=None, u=None):
+    def layer_backward(self, d_out, routing_a=None, routing_m=None, u=None, pad_mask=None):
         """Gradients of the whole layer for d_out = dL/d(out).  routing_a / routing_m default to the
-        results the last layer_forward wrote; u = None has it recomputed.  Returns a dict of tensors."""
+        results the last layer_forward wrote; u = None has it recomputed; pad_mask as in the forward
+        call.  Returns a dict of tensors."""
         if not hasattr(self, "layer_bwd_ws"):
             nbytes = B.layer_backward_workspace_bytes(self.smha, self.uome)
             if nbytes == 0:
@@ -165,11 +166,19 @@ class DeviceLayer:
             self.layer_dwa = B.smha_weight_grads(g["d_wq"], g["d_wk"], g["d_wv"], g["d_wo"])
             self.layer_dra = B.router_grads(g["d_a_w_expert"], g["d_a_w_b"], g["d_a_w_a"])
             self.layer_drm = B.router_grads(g["d_m_w_expert"], g["d_m_w_b"], g["d_m_w_a"])
-        B.layer_backward(self.smha, self.wa, self.uome, self.wm, self.x, u, self.ra if routing_a is None else routing_a,
-                         self.rm if routing_m is None else routing_m, d_out, self.g["d_x"], self.layer_dwa,
-                         self.layer_dra, self.g["d_a_in"], self.g["d_a_out"], self.layer_drm, self.layer_bwd_ws)
+        tail = (self.ra if routing_a is None else routing_a, self.rm if routing_m is None else routing_m, d_out,
+                self.g["d_x"], self.layer_dwa, self.layer_dra, self.g["d_a_in"], self.g["d_a_out"], self.layer_drm,
+                self.layer_bwd_ws)
+        if pad_mask is None:
+            B.layer_backward(self.smha, self.wa, self.uome, self.wm, self.x, u, *tail)
+        else:
+            B.layer_backward_masked(self.smha, self.wa, self.uome, self.wm, self.x, pad_mask, u, *tail)
         return self.g
 
-    def layer_forward(self):
-        B.layer_forward(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
-                        self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws)
+    def layer_forward(self, pad_mask=None):
+        if pad_mask is None:
+            B.layer_forward(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
+                            self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws)
+        else:
+            B.layer_forward_masked(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
+                                   self.noise_m_expert, self.x, pad_mask, self.out, self.ra, self.rm, self.ws)

@@ -158,6 +158,10 @@ def test_smha_uome_layer_argument_validation():
     assert ly(d, u, FAKE, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG                      # out aliases x
     assert ly(d, good(b=3, m=1, c=1, width=64), FAKE, FAKE + 16, ws_bytes=big) == B.ERR_INVALID_ARG  # b mismatch
     assert ly(d, u, FAKE, FAKE + 16, ws_bytes=64) == B.ERR_WORKSPACE
+    lym = lambda a, m_, x, out, **k: B.layer_forward_masked(a, wa, None, None, m_, wm, None, x, FAKE + 32, out, None, None,
+                                                            FAKE, stream=0, check=False, **k)
+    assert lym(d, u, FAKE, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG                     # the same rules with a padding mask
+    assert lym(d, u, FAKE, FAKE + 16, ws_bytes=64) == B.ERR_WORKSPACE
     assert B.gather(d, FAKE, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG   # h aliases x
     assert B.gather(d, None, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG
 
@@ -222,3 +226,7 @@ def test_backward_argument_validation():
                                                 FAKE + 48, FAKE + 64, drm, FAKE, stream=0, check=False, **k)
     assert lb(B.router_grads(FAKE, FAKE, FAKE), B.router_grads(FAKE), ws_bytes=8) == B.ERR_WORKSPACE
     assert lb(None, B.router_grads(FAKE), ws_bytes=big) == B.ERR_INVALID_ARG      # SMHA has routers, no place for their gradients
+    lbm = lambda dra, drm, **k: B.layer_backward_masked(a, wa, u2, wm, FAKE, FAKE + 80, None, ra, rm, FAKE + 16, FAKE + 32,
+                                                        dw, dra, FAKE + 48, FAKE + 64, drm, FAKE, stream=0, check=False, **k)
+    assert lbm(B.router_grads(FAKE, FAKE, FAKE), B.router_grads(FAKE), ws_bytes=8) == B.ERR_WORKSPACE
+    assert lbm(None, B.router_grads(FAKE), ws_bytes=big) == B.ERR_INVALID_ARG

@@ -493,6 +493,17 @@ def test_route_backward_parity(name):
                                               ("ds_bf16_lp32", R | GE | GP, 0), ("ds_lm", R | GE | GP | CA, 32),
                                               ("longrange", R | GE | GP, 0)])
 def test_layer_backward_parity(name, fa, rope_dim):
+    run_layer_backward(name, fa, rope_dim)
+
+
+@pytest.mark.parametrize("name,fa,rope_dim", [("sb_long", R | GE | GP | CA, 16), ("lm", R | GE | GP | CA, 32)])
+def test_layer_backward_parity_padding_mask(name, fa, rope_dim):
+    """uoe_layer_backward_masked: the forward call's padding mask (Eq. 41) in the SMHA block's
+    backward pass and in the recomputation of u."""
+    run_layer_backward(name, fa, rope_dim, pad_frac=0.2)
+
+
+def run_layer_backward(name, fa, rope_dim, pad_frac=0.0):
     """uoe_layer_backward (UoME backward, its router(s), SMHA backward, its routers, chained on the
     device) against the oracle's chain, on the oracle's routing and the fp32-rounded gates; the
     ds_* shapes run the UoME block with patch-wise data selection."""
@@ -507,7 +518,8 @@ def test_layer_backward_parity(name, fa, rope_dim):
         if ld_std > 1.0:
             setattr(inp, attr, getattr(inp, attr) * np.float32(2.0 ** -np.ceil(np.log2(ld_std))))
     d_out = synth.make_upstream_grad(cfg)
-    fwd = oracle.layer_forward(inp, fa, fm, rope_dim)
+    pad = synth.make_pad_mask(cfg, pad_frac) if pad_frac > 0 else None
+    fwd = oracle.layer_forward(inp, fa, fm, rope_dim, pad)
     ra, rm = fwd.routing_a, fwd.routing_m
     ge_a, gp_a, ge_m, gp_m = (g.astype(np.float32) for g in (ra.expert_gate, ra.patch_gate, rm.expert_gate, rm.patch_gate))
     dev = DeviceLayer(inp, fa, fm, rope_dim=rope_dim)
@@ -517,9 +529,11 @@ def test_layer_backward_parity(name, fa, rope_dim):
     if ds:
         keep += [i32(rm.patch_id), f32(gp_m)]
     g = dev.layer_backward(to_device(d_out, cfg.dtype, dev.device), routing_a=B.routing_out(*keep[:4]),
-                           routing_m=B.routing_out(*keep[4:]))
+                           routing_m=B.routing_out(*keep[4:]),
+                           pad_mask=None if pad is None else torch.from_numpy(pad).to(dev.device))
     torch.cuda.synchronize()
-    want = oracle.layer_backward(inp, fwd, d_out, fa, fm, rope_dim, gates_a=(ge_a, gp_a), gate_m=ge_m, patch_gate_m=gp_m)
+    want = oracle.layer_backward(inp, fwd, d_out, fa, fm, rope_dim, gates_a=(ge_a, gp_a), gate_m=ge_m, patch_gate_m=gp_m,
+                                 pad_mask=pad)
     refs = {"d_x": want.d_x, "d_wq": want.smha.d_wq, "d_wk": want.smha.d_wk, "d_wv": want.smha.d_wv, "d_wo": want.smha.d_wo,
             "d_a_w_expert": want.route_a.d_w_expert, "d_a_w_b": want.route_a.d_w_b, "d_a_w_a": want.route_a.d_w_a,
             "d_a_in": want.uome.d_a_in, "d_a_out": want.uome.d_a_out, "d_m_w_expert": want.route_m.d_w_expert}
@@ -1018,17 +1032,22 @@ def test_smha_masks_and_rope_parity_large_sampled():
     run_smha_variant("large", CA, 32, 0.1, samples=slice(2, 3))
 
 
-def test_layer_with_causal_mask_and_rope():
-    cfg = get_cfg("lm")
+@pytest.mark.parametrize("name,pad_frac", [("lm", 0.0), ("lm", 0.2), ("bf16_ragged", 0.3), ("tiny", 0.3)])
+def test_layer_with_causal_mask_and_rope(name, pad_frac):
+    """The LM setting at the layer call: shared causal mask, partial RoPE and (pad_frac > 0,
+    uoe_layer_forward_masked) the padding mask of Eq. 41 inside the SMHA block."""
+    cfg = get_cfg(name)
+    rope_dim = cfg.d_h // 2
     inp = synth.make_inputs(cfg)
     fa, fm = R | GE | GP | CA, R | GE
-    dev = DeviceLayer(inp, fa, fm, rope_dim=32)
-    dev.layer_forward()
+    pad = synth.make_pad_mask(cfg, pad_frac) if pad_frac > 0 else None
+    dev = DeviceLayer(inp, fa, fm, rope_dim=rope_dim)
+    dev.layer_forward(pad_mask=None if pad is None else torch.from_numpy(pad).to(dev.device))
     torch.cuda.synchronize()
-    ref = oracle.layer_forward(inp, fa, fm, rope_dim=32)
-    check_indices("lm-causal:smha-patch", to_host(dev.a_patch_idx), ref.routing_a.patch_id, ref.routing_a.patch_margin)
+    ref = oracle.layer_forward(inp, fa, fm, rope_dim, pad)
+    check_indices(f"{name}-causal:smha-patch", to_host(dev.a_patch_idx), ref.routing_a.patch_id, ref.routing_a.patch_margin)
     same = np.all(to_host(dev.m_expert_idx) == ref.routing_m.expert_id, axis=-1)
     assert same.any()
     err = scaled_err(to_host(dev.out)[same], ref.out[same])
-    print(f"[layer lm causal+rope] out scaled err {err:.3e}", flush=True)
+    print(f"[layer {name} causal+rope pad {pad_frac}] out scaled err {err:.3e}", flush=True)
     assert err <= TOL[cfg.dtype]

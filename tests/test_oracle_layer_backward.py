@@ -18,16 +18,18 @@ def as_f64(inp):
     return inp
 
 
-@pytest.mark.parametrize("fa,fm,rope_dim,noise,ds", [(R | GE | GP, R | GE, 0, False, False),
-                                                     (R | GE | GP | CA, R | GE, 2, True, False),
-                                                     (R | GE | GP, R | GE | GP, 0, False, True)])
-def test_layer_backward_matches_finite_differences(fa, fm, rope_dim, noise, ds):
+@pytest.mark.parametrize("fa,fm,rope_dim,noise,ds,pad", [(R | GE | GP, R | GE, 0, False, False, False),
+                                                         (R | GE | GP | CA, R | GE, 2, True, False, False),
+                                                         (R | GE | GP, R | GE | GP, 0, False, True, False),
+                                                         (R | GE | GP | CA, R | GE, 0, False, False, True)])
+def test_layer_backward_matches_finite_differences(fa, fm, rope_dim, noise, ds, pad):
     extra = dict(m_m=3, c_m=2) if ds else {}         # data-selected UoME: five routers' worth of gates live
     cfg = synth.small_config(b=2, l=12, d=8, n_a=3, d_h=4, m=4, c=2, k_a=2, n_m=3, d_e=6, k_m=2, router_noise=noise, **extra)
     inp = as_f64(synth.make_inputs(cfg, w_std=0.3))
-    fwd = oracle.layer_forward(inp, fa, fm, rope_dim)
+    pm = synth.make_pad_mask(cfg, 0.25) if pad else None   # Eq. 41 inside the SMHA block of the layer
+    fwd = oracle.layer_forward(inp, fa, fm, rope_dim, pm)
     r = np.random.default_rng(7).standard_normal(fwd.out.shape)
-    gr = oracle.layer_backward(inp, fwd, r, fa, fm, rope_dim)
+    gr = oracle.layer_backward(inp, fwd, r, fa, fm, rope_dim, pad_mask=pm)
     pairs = (("x", gr.d_x), ("wq", gr.smha.d_wq), ("wk", gr.smha.d_wk), ("wv", gr.smha.d_wv), ("wo", gr.smha.d_wo),
              ("a_w_expert", gr.route_a.d_w_expert), ("a_w_b", gr.route_a.d_w_b), ("a_w_a", gr.route_a.d_w_a),
              ("a_in", gr.uome.d_a_in), ("a_out", gr.uome.d_a_out), ("m_w_expert", gr.route_m.d_w_expert))
@@ -37,7 +39,7 @@ def test_layer_backward_matches_finite_differences(fa, fm, rope_dim, noise, ds):
     rr = np.random.default_rng(11)
 
     def loss():
-        f = oracle.layer_forward(inp, fa, fm, rope_dim)
+        f = oracle.layer_forward(inp, fa, fm, rope_dim, pm)
         same = (np.array_equal(f.routing_a.expert_id, fwd.routing_a.expert_id) and
                 np.array_equal(f.routing_a.patch_id, fwd.routing_a.patch_id) and
                 np.array_equal(f.routing_m.expert_id, fwd.routing_m.expert_id) and
