@@ -455,12 +455,15 @@ template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStrea
 }
 
 // Tile choice of the pipelined output-stationary contraction (out-projection of SMHA, second layer
-// of the data-selected UoME).  With many short (sample, patch) groups and d = 384 one workgroup takes
-// the whole row width: the group's segment list is built once and its A rows are fetched once
-// (measured 10 % faster on the ViT shape; for d = 256 with 64-row patches the narrower tiles win).
+// of the data-selected UoME).  A (sample, patch) group is a short chain of dependent steps (find the
+// experts that picked the patch, fetch their rows, a few K-steps, add the residual), so with many
+// short groups what counts is how many of them a CU holds at once: two-wave workgroups with two
+// stage buffers (five per CU) beat four-wave ones on the ViT shape (out-projection 30 -> 22 us; one
+// workgroup over the whole row width, one-wave workgroups and 64-column tiles were all slower),
+// while the LM shape's 128 groups are better off with four waves and every K-step in flight.
 template <typename OP> static hipError_t launch_outproj_dma(const OP &op, int groups, int l_p, int d, hipStream_t st)
 {
-    if (groups >= 512 && d == 384 && l_p <= 32) return launch_gemm_dma<OP, 32, 384, 32, 1, 4, 2, 2>(op, groups, l_p, d, st);
+    if (groups >= 512 && l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 2, 2, 4>(op, groups, l_p, d, st);
     if (l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 4, 4, 2>(op, groups, l_p, d, st);
     return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, groups, l_p, d, st);
 }
