@@ -115,6 +115,19 @@ int uoe_route_capacity(const uoe_block_desc *blk, const void *x, const void *w_b
                        float *load_p, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The auxiliary load-balancing loss (Eq. 42) from the statistics uoe_route_capacity returns, and
+ * its gradient with respect to the patch gates:
+ *   loss[b] = alpha * sum_i load_f[b,i] * load_p[b,i]                       (one value per sequence)
+ *   d_patch_gate[b,i,j] += alpha * load_f[b,i] / m                          (every patch j)
+ * load_f counts selections and is piecewise constant, so only load_p = mean_j gate[b,i,j] (Eq. 44)
+ * passes a gradient.  d_patch_gate [b,n,m] fp32 is UPDATED in place (it holds the block's own gate
+ * gradient, as uoe_smha_backward returns it, and goes on to uoe_route_backward); NULL = loss only.
+ * loss [b] fp32 may be NULL when only the gradient is wanted.  fp32 arithmetic; blk gives b, n, m.
+ */
+int uoe_balance_loss(const uoe_block_desc *blk, const float *load_f, const float *load_p,
+                     float alpha, float *loss, float *d_patch_gate, void *hip_stream);
+
+/*
  * Index selection of Eq. 18 / 24 as a standalone copy: for every active unit
  * (sample b, slot s < k, expert i = expert_idx[b,s]) the l_a selected token rows
  * of x, in ascending position, into h[b,s,:,:].

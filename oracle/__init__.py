@@ -278,6 +278,18 @@ def capacity(gprime, k: int) -> Capacity:
     return Capacity(cap, cnt, n * cnt / float(k * m), g.mean(axis=2), margin)
 
 
+def balance_loss(load_f, load_p, alpha: float) -> np.ndarray:
+    """Eq. 42 per sequence: L_b = alpha * sum_i f_{b,i} P_{b,i} (f, P of Eq. 43-44, [b,n] each)."""
+    return float(alpha) * np.sum(_f64(load_f) * _f64(load_p), axis=1)
+
+
+def balance_loss_grad(load_f, alpha: float, m: int) -> np.ndarray:
+    """dL_b / d g_{b,i,j} [b,n,m] of Eq. 42: f_i (Eq. 43) is a count and passes nothing, P_i (Eq. 44)
+    is the mean of the expert's m patch gates, so every patch of expert i gets alpha * f_i / m."""
+    f = _f64(load_f)
+    return np.repeat((float(alpha) * f / m)[:, :, None], m, axis=2)
+
+
 # --------------------------------------------------------------------------- blocks
 def smha(x, wq, wk, wv, wo, expert_id, expert_gate, patch_id, patch_gate_, m: int,
          flags: int = RESIDUAL, rope_dim: int = 0, pad_mask=None) -> np.ndarray:

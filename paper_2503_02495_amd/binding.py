@@ -17,7 +17,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
-EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward",
+EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_balance_loss", "uoe_gather",
+           "uoe_smha_forward",
            "uoe_smha_forward_masked",
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward", "uoe_layer_forward_masked",
            "uoe_uome_backward_workspace_bytes", "uoe_uome_backward",
@@ -79,6 +80,7 @@ def lib():
         L.uoe_status_string.restype = ctypes.c_char_p
         L.uoe_route.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_route_capacity.argtypes = [D, P, P, P, P, ctypes.c_int32, P, P, P, P, S, P]
+        L.uoe_balance_loss.argtypes = [D, P, P, ctypes.c_float, P, P, P]
         L.uoe_gather.argtypes = [D, P, P, P, P, P]
         L.uoe_smha_forward.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_smha_forward_masked.argtypes = [D] + [P] * 11 + [P, S, P]
@@ -113,7 +115,7 @@ def lib():
                                                P, S, P]
         for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
                   "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward", "uoe_route_backward", "uoe_layer_backward",
-                  "uoe_layer_forward_masked", "uoe_layer_backward_masked"):
+                  "uoe_layer_forward_masked", "uoe_layer_backward_masked", "uoe_balance_loss"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -177,6 +179,12 @@ def route_capacity(blk, x, w_b, w_a, noise_patch, patch_k, capacity, load_f, loa
                                   _ptr(capacity), _ptr(load_f), _ptr(load_p), _ptr(ws),
                                   _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_route_capacity", check)
+
+
+def balance_loss(blk, load_f, load_p, alpha, loss, d_patch_gate, stream=None, check=True) -> int:
+    st = lib().uoe_balance_loss(_ref(blk), _ptr(load_f), _ptr(load_p), float(alpha), _ptr(loss), _ptr(d_patch_gate),
+                                _stream(stream))
+    return _done(st, "uoe_balance_loss", check)
 
 
 def gather(blk, x, expert_idx, patch_idx, h, stream=None, check=True) -> int:

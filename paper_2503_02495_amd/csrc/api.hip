@@ -406,6 +406,17 @@ int uoe_route_capacity(const uoe_block_desc *blk, const void *x, const void *w_b
                                                                                                          : UOE_ERR_DEVICE;
 }
 
+int uoe_balance_loss(const uoe_block_desc *blk, const float *load_f, const float *load_p, float alpha, float *loss,
+                     float *d_patch_gate, void *hip_stream)
+{
+    const int rc = check_desc(blk, DESC_ROUTE);
+    if (rc != UOE_OK) return rc;
+    if (!load_f || (loss && !load_p) || (!loss && !d_patch_gate)) return UOE_ERR_INVALID_ARG;
+    if (!(alpha == alpha)) return UOE_ERR_INVALID_ARG;  // NaN
+    return launch_balance_loss(load_f, load_p, alpha, loss, d_patch_gate, blk->b, blk->n, blk->m,
+                               static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
 int uoe_smha_forward(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
                      const void *wv, const void *wo, const int32_t *expert_idx,
                      const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,

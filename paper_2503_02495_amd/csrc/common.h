@@ -193,6 +193,8 @@ struct GatherArgs {
 
 // Launchers: enqueue on `st`, return the runtime's launch status.
 hipError_t launch_route(const RouteArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_balance_loss(const float *load_f, const float *load_p, float alpha, float *loss, float *d_patch_gate,
+                               int b, int n, int m, hipStream_t st);
 hipError_t launch_gather(const GatherArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_smha(const SmhaArgs &a, bool bf16, hipStream_t st);
 // Eq. 28-34 of the MFMA path only (projections, rotary embedding, attention into a.o / a.o_lo / a.lse);

@@ -669,6 +669,33 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(RouteArgs 
     }
 }
 
+// Eq. 42 per sample and its gradient through P_i = mean_j g_{i,j} (Eq. 44); f_i (Eq. 43) is a count.
+// One workgroup per sample; the n products are added in expert order.
+__global__ __launch_bounds__(256) void balance_loss_kernel(const float *load_f, const float *load_p, float alpha, float *loss,
+                                                           float *d_patch_gate, int n, int m)
+{
+    const int bb = blockIdx.x, tid = threadIdx.x;
+    const float *f = load_f + (size_t)bb * n;
+    if (loss && tid == 0) {
+        const float *pr = load_p + (size_t)bb * n;
+        float s = 0.f;
+        for (int i = 0; i < n; ++i) s += f[i] * pr[i];
+        loss[bb] = alpha * s;
+    }
+    if (d_patch_gate) {
+        float *dg = d_patch_gate + (size_t)bb * n * m;
+        const float scale = alpha / (float)m;
+        for (int idx = tid; idx < n * m; idx += 256) dg[idx] += scale * f[idx / m];
+    }
+}
+
+hipError_t launch_balance_loss(const float *load_f, const float *load_p, float alpha, float *loss, float *d_patch_gate,
+                               int b, int n, int m, hipStream_t st)
+{
+    hipLaunchKernelGGL(balance_loss_kernel, dim3(b), dim3(256), 0, st, load_f, load_p, alpha, loss, d_patch_gate, n, m);
+    return hipGetLastError();
+}
+
 template <typename T, int NMAX>
 static hipError_t launch_partial(const RouteArgs &a, bool has_e, bool has_d, hipStream_t st)
 {

@@ -162,6 +162,10 @@ def test_smha_uome_layer_argument_validation():
                                                             FAKE, stream=0, check=False, **k)
     assert lym(d, u, FAKE, FAKE, ws_bytes=big) == B.ERR_INVALID_ARG                     # the same rules with a padding mask
     assert lym(d, u, FAKE, FAKE + 16, ws_bytes=64) == B.ERR_WORKSPACE
+    assert B.balance_loss(d, None, FAKE, 0.01, FAKE, None, stream=0, check=False) == B.ERR_INVALID_ARG   # no statistics
+    assert B.balance_loss(d, FAKE, FAKE, 0.01, None, None, stream=0, check=False) == B.ERR_INVALID_ARG   # nothing to write
+    assert B.balance_loss(d, FAKE, None, 0.01, FAKE, None, stream=0, check=False) == B.ERR_INVALID_ARG   # the loss needs P
+    assert B.balance_loss(d, FAKE, FAKE, float("nan"), FAKE, None, stream=0, check=False) == B.ERR_INVALID_ARG
     assert B.gather(d, FAKE, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG   # h aliases x
     assert B.gather(d, None, FAKE, FAKE, FAKE, stream=0, check=False) == B.ERR_INVALID_ARG
 

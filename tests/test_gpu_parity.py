@@ -692,6 +692,35 @@ def test_route_capacity_parity(name, patch_k):
     check_indices(name + ":patch(c dynamic)", to_host(pidx), r2.patch_id, r2.patch_margin)
 
 
+@pytest.mark.parametrize("name", ["bf16_ragged", "lm", "vit", "large"])
+def test_balance_loss_parity(name):
+    """Eq. 42 from the device's own Eq. 43-44 statistics, and its gradient added onto a gate gradient."""
+    cfg = get_cfg(name)
+    alpha = 0.01
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+    dev = DeviceLayer(inp, R | GE | GP, R | GE)
+    cap = torch.zeros((cfg.b,), dtype=torch.int32, device=dev.device)
+    lf = torch.zeros((cfg.b, cfg.n_a), dtype=torch.float32, device=dev.device)
+    lp = torch.zeros((cfg.b, cfg.n_a), dtype=torch.float32, device=dev.device)
+    B.route_capacity(dev.smha, dev.x, dev.a_w_b, dev.a_w_a, dev.noise_a_patch, 1, cap, lf, lp, dev.ws)
+    base = np.random.default_rng(5).standard_normal((cfg.b, cfg.n_a, cfg.m)).astype(np.float32)
+    dg = to_device(base, synth.F32, dev.device)
+    loss = torch.full((cfg.b,), -1.0, dtype=torch.float32, device=dev.device)
+    B.balance_loss(dev.smha, lf, lp, alpha, loss, dg)
+    torch.cuda.synchronize()
+    f, pm = to_host(lf).astype(np.float64), to_host(lp).astype(np.float64)
+    np.testing.assert_allclose(to_host(loss), oracle.balance_loss(f, pm, alpha), rtol=1e-5)
+    np.testing.assert_allclose(to_host(dg), base + oracle.balance_loss_grad(f, alpha, cfg.m), rtol=1e-6, atol=1e-7)
+    B.balance_loss(dev.smha, lf, None, alpha, None, dg)           # gradient only: added a second time
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_host(dg), base + 2 * oracle.balance_loss_grad(f, alpha, cfg.m), rtol=1e-6, atol=1e-7)
+    # against the oracle's own statistics (rows without near-ties only differ by the fp32 gates)
+    ref = oracle.capacity(oracle.data_router_logits(inp.x, inp.a_w_b, inp.a_w_a, inp.noise_a_patch), 1)
+    clean = ~np.any(ref.margin < oracle.NEAR_TIE_REL, axis=1)
+    np.testing.assert_allclose(to_host(loss)[clean], oracle.balance_loss(ref.load_f, ref.load_p, alpha)[clean], rtol=GATE_RTOL)
+    print(f"[balance loss {name}] L per sample {to_host(loss)[:4].tolist()}", flush=True)
+
+
 # --------------------------------------------------------------------------- UoME, data selection
 import dataclasses
 

@@ -78,3 +78,45 @@ def test_capacity_bounds_the_fixed_c_selection():
     gp = np.random.default_rng(11).standard_normal((2, 5, 10))
     res = oracle.capacity(gp, 2)
     assert np.all(res.count.max(axis=1) == res.capacity)
+
+
+# --------------------------------------------------------------------------- balance loss (Eq. 42)
+def test_balance_loss_known_values():
+    n, m, alpha = 4, 8, 0.01
+    # perfectly even routing: all logits equal -> P_i = 1/n; a rotation of preferences (patch j prefers
+    # expert j % n by a hair) -> with k = 1 every expert is named m/n times, f_i = 1: L = alpha * n * (1/n)
+    gp = np.zeros((1, n, m))
+    for j in range(m):
+        gp[0, j % n, j] = 1e-9
+    st = oracle.capacity(gp, 1)
+    np.testing.assert_allclose(st.load_f[0], 1.0)
+    np.testing.assert_allclose(oracle.balance_loss(st.load_f, st.load_p, alpha), [alpha], rtol=1e-8)
+    # collapse: every patch is certain of expert 0 -> f_0 = n, P_0 -> 1: L -> alpha * n, the maximum
+    gp = np.full((1, n, m), -50.0)
+    gp[0, 0, :] = 50.0
+    st = oracle.capacity(gp, 1)
+    np.testing.assert_allclose(oracle.balance_loss(st.load_f, st.load_p, alpha), [alpha * n], rtol=1e-12)
+    # in between, the loss lies between the two (sum_i f_i = n, sum_i P_i = 1, f_i <= n)
+    gp = np.random.default_rng(3).standard_normal((5, n, m)) * 3
+    st = oracle.capacity(gp, 2)
+    lb = oracle.balance_loss(st.load_f, st.load_p, alpha)
+    assert np.all(lb > 0) and np.all(lb <= alpha * n / 2 + 1e-12)   # k = 2: f_i <= n/2
+
+
+def test_balance_loss_gradient_matches_finite_differences():
+    """The loss as a function of the gate values g (Eq. 44 inside Eq. 42) with the counts of Eq. 43
+    held fixed: perturb single gates, recompute P and the loss from their definitions."""
+    b, n, m, k, alpha = 2, 5, 6, 2, 0.3
+    gp = np.random.default_rng(11).standard_normal((b, n, m))
+    st = oracle.capacity(gp, k)
+    g = oracle.patch_gate(gp)
+    grad = oracle.balance_loss_grad(st.load_f, alpha, m)
+    assert grad.shape == (b, n, m)
+    eps = 1e-6
+    for bb, i, j in [(0, 0, 0), (1, 3, 5), (0, 4, 2), (1, 1, 1)]:
+        def loss(delta):
+            gg = g.copy()
+            gg[bb, i, j] += delta
+            return alpha * np.sum(st.load_f[bb] * gg[bb].mean(axis=1))     # Eq. 42 with Eq. 44 written out
+        fd = (loss(eps) - loss(-eps)) / (2 * eps)
+        assert abs(fd - grad[bb, i, j]) <= 1e-9
