@@ -487,8 +487,11 @@ static hipError_t smha_mfma_qkv_attention(const SmhaArgs &a, hipStream_t st)
     } else if (a.d_h == 64) {
         if (tall) err = k64 ? launch_gemm_dma<QP, 128, 192, 64, 2, 2, 3>(qp, units, l_a, 192, st)
                             : launch_gemm_dma<QP, 128, 192, 32, 2, 2, 4>(qp, units, l_a, 192, st);
+        // 64-row tiles for mid-sized units (the ViT shape: 384 units of 56 rows): three 16 KB stage
+        // buffers, so that two workgroups share a CU and the 384 of them run in one round (with
+        // 64-deep K-steps and one workgroup per CU the second round ran half empty: SMHA stage 50 -> 46 us)
         else if (k64 && l_a > 32 && (long)units * ((l_a + 63) / 64) >= 256)
-            err = launch_gemm_dma<QP, 64, 192, 64, 2, 2, 3>(qp, units, l_a, 192, st);
+            err = launch_gemm_dma<QP, 64, 192, 32, 2, 2, 3, 2>(qp, units, l_a, 192, st);
         // fewer row tiles than compute units: one workgroup per projection (64 columns), three
         // times the workgroups for three reads of the gathered rows out of L2 (the LM shape: 128 row
         // tiles, the stage 26 -> 22.4 us)
