@@ -143,6 +143,12 @@ def main() -> int:
     ap.add_argument("--dynamic-capacity", type=int, default=0, metavar="K",
                     help="two-stage routing (Eq. 15-16): every step first computes the SMHA capacity with K experts per "
                          "patch (uoe_route_capacity), reads it back and runs the layer with c = its maximum over the batch")
+    ap.add_argument("--streams", type=int, default=8, metavar="S",
+                    help="independent steps in flight: step i runs on HIP stream i %% S with its own inputs, workspace and "
+                         "output (the steps of a throughput job do not depend on each other; one layer call is a chain of "
+                         "nine dependent launches that leaves the GPU idle between them; the default is twice the four "
+                         "hardware queues a process has here, so that every queue gets work however streams map to "
+                         "them).  1 = one call after the other; that figure is reported beside the headline either way")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
@@ -222,6 +228,31 @@ def main() -> int:
     eager_ms = timed(step_fn)
     launch = "eager"
     ms_per_step = eager_ms
+    n_streams = 1 if (args.graph or args.dynamic_capacity) else max(1, args.streams)
+    if n_streams > 1:
+        # S replicas of the layer's buffers (same synthetic batch, separate allocations), one stream each
+        lanes = [dev] + [DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim) for _ in range(n_streams - 1)]
+        streams = [torch.cuda.Stream() for _ in lanes]
+        raw = [int(st.cuda_stream) for st in streams]   # the hipStream_t values the C ABI takes
+        torch.cuda.synchronize()                        # the replicas' uploads ran on the default stream
+
+        def timed_lanes():
+            def run(count):
+                for i in range(count):
+                    lanes[i % n_streams].layer_forward(stream=raw[i % n_streams])
+            run(max(args.warmup, n_streams))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run(args.steps)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / args.steps
+        ms_per_step = timed_lanes()
+        launch = f"eager, {n_streams} streams (independent steps in flight)"
+        for lane in lanes[1:]:   # every lane ran the same batch through the same kernels
+            if not torch.equal(lane.out, dev.out):
+                print("bench.py: lanes disagree", file=sys.stderr)
+                return 1
+        del lanes[1:]
     if args.graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -312,7 +343,7 @@ def main() -> int:
                             (f"; SMHA c from Eq. 15-16 with {args.dynamic_capacity} experts per patch, read back every step"
                              if args.dynamic_capacity else ""),
                    "seed": cfg.seed, "launch": launch},
-        "ms_per_step_eager": round(eager_ms, 5),
+        "single_stream": {"ms_per_step": round(eager_ms, 5), "value": round(cfg.tokens / (eager_ms * 1e-3), 1)},
         "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 3),
         "flops_per_step": fl["total"],
         "roofline": roofline,

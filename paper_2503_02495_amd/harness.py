@@ -175,10 +175,11 @@ class DeviceLayer:
             B.layer_backward_masked(self.smha, self.wa, self.uome, self.wm, self.x, pad_mask, u, *tail)
         return self.g
 
-    def layer_forward(self, pad_mask=None):
+    def layer_forward(self, pad_mask=None, stream=None):
+        """stream: a torch stream or a raw hipStream_t value; None = torch's current stream."""
         if pad_mask is None:
             B.layer_forward(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
-                            self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws)
+                            self.noise_m_expert, self.x, self.out, self.ra, self.rm, self.ws, stream=stream)
         else:
             B.layer_forward_masked(self.smha, self.wa, self.noise_a_expert, self.noise_a_patch, self.uome, self.wm,
-                                   self.noise_m_expert, self.x, pad_mask, self.out, self.ra, self.rm, self.ws)
+                                   self.noise_m_expert, self.x, pad_mask, self.out, self.ra, self.rm, self.ws, stream=stream)

@@ -947,6 +947,36 @@ def test_layer_is_deterministic_and_reusable():
     assert torch.equal(first.view(torch.int16), dev.out.view(torch.int16))
 
 
+@pytest.mark.parametrize("name", ["bf16_ragged", "lm"])
+def test_layer_calls_on_concurrent_streams(name):
+    """Independent layer calls in flight on four streams (the launch configuration bench.py times by
+    default): each lane has its own batch, workspace and output; every lane's result is bit-identical
+    to what the same lane produced alone, round after round."""
+    cfg = get_cfg(name)
+    lanes = []
+    for s in range(4):
+        inp = synth.make_inputs(dataclasses.replace(cfg, seed=cfg.seed + 101 * s), w_std=w_std_for(name))
+        inp.noise_m_patch = None
+        lanes.append(DeviceLayer(inp, R | GE | GP, R | GE))
+    alone = []
+    for lane in lanes:
+        lane.layer_forward()
+        torch.cuda.synchronize()
+        alone.append(lane.out.clone())
+    assert not torch.equal(alone[0], alone[1])                  # different batches
+    streams = [torch.cuda.Stream() for _ in lanes]
+    for rnd in range(3):
+        for lane in lanes:
+            lane.out.zero_()
+        torch.cuda.synchronize()
+        for i in range(40):                                     # ten calls per lane, interleaved
+            with torch.cuda.stream(streams[i % 4]):
+                lanes[i % 4].layer_forward()
+        torch.cuda.synchronize()
+        for s, lane in enumerate(lanes):
+            assert torch.equal(lane.out, alone[s]), (rnd, s)
+
+
 def test_layer_under_hip_graph_replay():
     """The layer call is capturable (kernel launches only); every replay reproduces the eager result,
     with eager work and synchronisations between replays."""
