@@ -965,13 +965,17 @@ def test_layer_calls_on_concurrent_streams(name):
         alone.append(lane.out.clone())
     assert not torch.equal(alone[0], alone[1])                  # different batches
     streams = [torch.cuda.Stream() for _ in lanes]
+    raw = [int(st.cuda_stream) for st in streams]               # hipStream_t values, as bench.py passes them
     for rnd in range(3):
         for lane in lanes:
             lane.out.zero_()
         torch.cuda.synchronize()
         for i in range(40):                                     # ten calls per lane, interleaved
-            with torch.cuda.stream(streams[i % 4]):
-                lanes[i % 4].layer_forward()
+            if rnd == 2:                                        # the same through torch's current-stream route
+                with torch.cuda.stream(streams[i % 4]):
+                    lanes[i % 4].layer_forward()
+            else:
+                lanes[i % 4].layer_forward(stream=raw[i % 4])
         torch.cuda.synchronize()
         for s, lane in enumerate(lanes):
             assert torch.equal(lane.out, alone[s]), (rnd, s)
