@@ -143,12 +143,12 @@ def main() -> int:
     ap.add_argument("--dynamic-capacity", type=int, default=0, metavar="K",
                     help="two-stage routing (Eq. 15-16): every step first computes the SMHA capacity with K experts per "
                          "patch (uoe_route_capacity), reads it back and runs the layer with c = its maximum over the batch")
-    ap.add_argument("--streams", type=int, default=8, metavar="S",
+    ap.add_argument("--streams", type=int, default=4, metavar="S",
                     help="independent steps in flight: step i runs on HIP stream i %% S with its own inputs, workspace and "
                          "output (the steps of a throughput job do not depend on each other; one layer call is a chain of "
-                         "nine dependent launches that leaves the GPU idle between them; the default is twice the four "
-                         "hardware queues a process has here, so that every queue gets work however streams map to "
-                         "them).  1 = one call after the other; that figure is reported beside the headline either way")
+                         "nine dependent launches that leaves the GPU idle between them; the default is one lane per "
+                         "hardware queue of the process: the stream the rest of the program uses and three more).  "
+                         "1 = one call after the other; that figure is reported beside the headline either way")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
@@ -232,7 +232,8 @@ def main() -> int:
     if n_streams > 1:
         # S replicas of the layer's buffers (same synthetic batch, separate allocations), one stream each
         lanes = [dev] + [DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim) for _ in range(n_streams - 1)]
-        streams = [torch.cuda.Stream() for _ in lanes]
+        # lane 0 stays on the stream everything so far ran on (it already owns a hardware queue)
+        streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in lanes[1:]]
         raw = [int(st.cuda_stream) for st in streams]   # the hipStream_t values the C ABI takes
         torch.cuda.synchronize()                        # the replicas' uploads ran on the default stream
 
