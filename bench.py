@@ -42,7 +42,7 @@ def describe(c) -> str:
             f"UoME n{c.n_m} d_e{c.d_e} k{c.k_m}{ds}; {c.dtype}")
 
 
-def run_stage(args, cfg, dev, B, torch) -> int:
+def run_stage(args, cfg, dev, B, torch, make_lane) -> int:
     """Loop one stage (its inputs produced once by the stages before it) and print its mean time."""
     dev.layer_forward()      # fills routing results and u
     dev.smha_forward()
@@ -111,6 +111,31 @@ def run_stage(args, cfg, dev, B, torch) -> int:
             res[nm] = {"us_per_call": round(us, 3), "tflops": round(2.0 * cfg.b * cfg.l * cfg.d * ncol / us * 1e-6, 1)}
         print(json.dumps({"stage": "lib_gemm", "workload": cfg.name, "steps": args.steps, **res}))
         return 0
+    if args.stage == "layer_fwd_bwd" and args.stage_streams > 1:
+        # a training step per batch, several independent batches in flight (one lane per stream, lane 0 on the
+        # program's own stream), as the forward benchmark does by default
+        n_lanes = args.stage_streams
+        lanes = [dev] + [make_lane() for _ in range(n_lanes - 1)]
+        raw = [int(torch.cuda.current_stream().cuda_stream)] + [int(torch.cuda.Stream().cuda_stream) for _ in lanes[1:]]
+        for lane in lanes:
+            lane.layer_forward()
+            lane.layer_backward(d_out_l)           # allocates the lane's gradient buffers
+        torch.cuda.synchronize()
+
+        def run(count):
+            for i in range(count):
+                lane, st = lanes[i % n_lanes], raw[i % n_lanes]
+                lane.layer_forward(stream=st)
+                lane.layer_backward(d_out_l, stream=st)
+        run(max(args.warmup, n_lanes))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / args.steps
+        print(json.dumps({"stage": args.stage, "workload": cfg.name, "steps": args.steps, "streams": n_lanes,
+                          "us_per_call": round(us, 3)}))
+        return 0
     fn = calls[args.stage]
     for _ in range(args.warmup):
         fn()
@@ -149,6 +174,8 @@ def main() -> int:
                          "nine dependent launches that leaves the GPU idle between them; the default is one lane per "
                          "hardware queue of the process: the stream the rest of the program uses and three more).  "
                          "1 = one call after the other; that figure is reported beside the headline either way")
+    ap.add_argument("--stage-streams", type=int, default=1, metavar="S",
+                    help="with --stage layer_fwd_bwd: S independent training steps in flight, one lane per stream")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
@@ -193,7 +220,8 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     if args.stage:
-        return run_stage(args, cfg, dev, B, torch)
+        return run_stage(args, cfg, dev, B, torch,
+                         lambda: DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim))
 
     # ---- whole-path throughput.  The layer call only enqueues kernels (no allocation, no memset, no
     # synchronisation), so it can also be captured into a HIP graph (--graph: a step is one replay).

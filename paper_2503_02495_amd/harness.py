@@ -148,7 +148,7 @@ class DeviceLayer:
                         self.d_a_expert_gate, self.d_a_patch_gate, self.smha_bwd_ws)
         return self.d_x, self.d_wq, self.d_wk, self.d_wv, self.d_wo, self.d_a_expert_gate, self.d_a_patch_gate
 
-    def layer_backward(self, d_out, routing_a=None, routing_m=None, u=None, pad_mask=None):
+    def layer_backward(self, d_out, routing_a=None, routing_m=None, u=None, pad_mask=None, stream=None):
         """Gradients of the whole layer for d_out = dL/d(out).  routing_a / routing_m default to the
         results the last layer_forward wrote; u = None has it recomputed; pad_mask as in the forward
         call.  Returns a dict of tensors."""
@@ -170,9 +170,9 @@ class DeviceLayer:
                 self.g["d_x"], self.layer_dwa, self.layer_dra, self.g["d_a_in"], self.g["d_a_out"], self.layer_drm,
                 self.layer_bwd_ws)
         if pad_mask is None:
-            B.layer_backward(self.smha, self.wa, self.uome, self.wm, self.x, u, *tail)
+            B.layer_backward(self.smha, self.wa, self.uome, self.wm, self.x, u, *tail, stream=stream)
         else:
-            B.layer_backward_masked(self.smha, self.wa, self.uome, self.wm, self.x, pad_mask, u, *tail)
+            B.layer_backward_masked(self.smha, self.wa, self.uome, self.wm, self.x, pad_mask, u, *tail, stream=stream)
         return self.g
 
     def layer_forward(self, pad_mask=None, stream=None):
