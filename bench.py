@@ -328,6 +328,26 @@ def main() -> int:
                 "frac": round(achieved / peak, 5), "traffic": traffic,
                 "flops_per_launch": up_flops, "ms_per_launch": round(up_ms, 5)}
 
+    # ---- what a dependent launch costs here whatever the kernel does: the smallest kernel of the library
+    # (the gather of the 128-token fp32 shape) launched back to back on one stream, timed the same way.
+    # Context for the figures above: a layer call is nine such launches in a row.
+    tiny_inp = synth.make_inputs(synth.CONFIGS["tiny"])
+    tiny_inp.noise_m_patch = None
+    tiny = DeviceLayer(tiny_inp, B.FLAG_RESIDUAL, B.FLAG_RESIDUAL, device="cuda:0")
+    tiny.layer_forward()
+    tcfg = tiny.cfg
+    th = torch.empty((tcfg.b, tcfg.k_a, tcfg.l_a, tcfg.d), dtype=tiny.tdtype, device=tiny.device)
+    small = lambda: B.gather(tiny.smha, tiny.x, tiny.a_expert_idx, tiny.a_patch_idx, th)
+    for _ in range(20):
+        small()
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(200):
+        small()
+    ev1.record()
+    torch.cuda.synchronize()
+    roofline["dependent_launch_floor_us"] = round(ev0.elapsed_time(ev1) * 1e3 / 200, 2)
+
     # ---- CPU oracle on this machine's host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
