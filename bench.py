@@ -307,13 +307,25 @@ def main() -> int:
     for _ in range(max(3, args.warmup)):
         up()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    ev0.record()
-    for _ in range(args.steps):
-        up()
-    ev1.record()
-    torch.cuda.synchronize()
-    up_ms = ev0.elapsed_time(ev1) / args.steps
+    src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).zero_()
+    dst = torch.empty_like(src)
+
+    def gpu_paced(fn, count):
+        """Mean time of `count` launches of fn on the current stream, by events, with the launches queued
+        while the GPU is still busy with large copies: what is timed is the GPU working through its queue,
+        not the host filling it.  Second value: whether the host really stayed ahead."""
+        torch.cuda.synchronize()
+        for _ in range(8):
+            dst.copy_(src)
+        ev0.record()
+        for _ in range(count):
+            fn()
+        ev1.record()
+        ahead = not ev0.query()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / count, ahead
+    up_launches = min(args.steps, 200)
+    up_ms, up_ahead = gpu_paced(up, up_launches)
     up_flops = float(fl["uome"]) if uome_ds else 2.0 * cfg.b * cfg.l * cfg.d * cfg.k_m * cfg.d_e
     is_bf16 = cfg.dtype == synth.BF16
     peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
@@ -326,11 +338,15 @@ def main() -> int:
                 else "uome_up (Eq. 38 grouped GEMM + SiLU + gate)", "bound": "mfma",
                 "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 5), "traffic": traffic,
-                "flops_per_launch": up_flops, "ms_per_launch": round(up_ms, 5)}
+                "flops_per_launch": up_flops, "ms_per_launch": round(up_ms, 5), "launches_timed": up_launches,
+                "host_stayed_ahead": up_ahead}
 
-    # ---- what a dependent launch costs here whatever the kernel does: the smallest kernel of the library
-    # (the gather of the 128-token fp32 shape) launched back to back on one stream, timed the same way.
-    # Context for the figures above: a layer call is nine such launches in a row.
+    # ---- what a dependent launch costs on the GPU's side whatever the kernel does: the smallest kernel of
+    # the library (the gather of the 128-token fp32 shape) 100 times on one stream, queued while the GPU is
+    # still busy (gpu_paced above; the figure is dropped if the GPU caught up with the host before
+    # everything was queued).  Context for the small shapes: their
+    # kernels take several times this, they are chains of dependent memory round trips in a single round
+    # of workgroups, which is why independent steps in flight fill the GPU.
     tiny_inp = synth.make_inputs(synth.CONFIGS["tiny"])
     tiny_inp.noise_m_patch = None
     tiny = DeviceLayer(tiny_inp, B.FLAG_RESIDUAL, B.FLAG_RESIDUAL, device="cuda:0")
@@ -338,15 +354,11 @@ def main() -> int:
     tcfg = tiny.cfg
     th = torch.empty((tcfg.b, tcfg.k_a, tcfg.l_a, tcfg.d), dtype=tiny.tdtype, device=tiny.device)
     small = lambda: B.gather(tiny.smha, tiny.x, tiny.a_expert_idx, tiny.a_patch_idx, th)
-    for _ in range(20):
+    for _ in range(10):
         small()
-    torch.cuda.synchronize()
-    ev0.record()
-    for _ in range(200):
-        small()
-    ev1.record()
-    torch.cuda.synchronize()
-    roofline["dependent_launch_floor_us"] = round(ev0.elapsed_time(ev1) * 1e3 / 200, 2)
+    floor_ms, floor_ahead = gpu_paced(small, 100)
+    roofline["dependent_launch_floor_us"] = round(floor_ms * 1e3, 2) if floor_ahead else None
+    del src, dst
 
     # ---- CPU oracle on this machine's host cores, on a bounded sample of the same workload
     cpu = None
