@@ -101,7 +101,10 @@ struct SmhaArgs {
     int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k]: which (slot s, pick t) chose patch p
     float *lse;                               // [b*k, l_a] or NULL: base-2 log-sum-exp of each query's scaled logits
                                               // (MFMA attention only; kept for the backward pass)
+    uint32_t skip;                            // steps NOT to run (SMHA_STEP_* bits; 0 = the whole block): a caller
+                                              // that times one step runs it on what the others left in the workspace
 };
+constexpr uint32_t SMHA_STEP_QKV = 1u, SMHA_STEP_ATTENTION = 2u, SMHA_STEP_OUT = 4u;
 
 struct UomeArgs {
     const void *u, *a_in, *a_out;

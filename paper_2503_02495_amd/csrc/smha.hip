@@ -447,10 +447,13 @@ template <typename T> static hipError_t smha_generic(const SmhaArgs &a, hipStrea
 {
     const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
     hipError_t err;
+    if (!(a.skip & SMHA_STEP_QKV)) {
+        if ((err = launch_gemm_generic<T>(make_qkv<T>(a), units, l_a, 3 * a.d_h, st)) != hipSuccess) return err;
+        if ((err = launch_rope<T>(a, st)) != hipSuccess) return err;
+    }
+    if (!(a.skip & SMHA_STEP_ATTENTION) && (err = launch_attention_generic<T>(a, st)) != hipSuccess) return err;
+    if (a.skip & SMHA_STEP_OUT) return hipSuccess;
     if ((err = launch_inverse_map(a, st)) != hipSuccess) return err;
-    if ((err = launch_gemm_generic<T>(make_qkv<T>(a), units, l_a, 3 * a.d_h, st)) != hipSuccess) return err;
-    if ((err = launch_rope<T>(a, st)) != hipSuccess) return err;
-    if ((err = launch_attention_generic<T>(a, st)) != hipSuccess) return err;
     return launch_gemm_generic<T>(make_outproj<T>(a), a.b * a.m, l_p, a.d, st);
 }
 
@@ -479,6 +482,7 @@ static hipError_t smha_mfma_qkv_attention(const SmhaArgs &a, hipStream_t st)
     if (mfma_attn) qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);  // base-2 softmax in the MFMA kernel
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
     // 128-row tiles for long units (measured faster from l_a = 512 up), 32-row tiles for short ones
+    auto projections = [&]() -> hipError_t {
     const bool tall = l_a >= 256 && (long)units * ((l_a + 127) / 128) >= 128, k64 = a.d % 64 == 0;
     if (a.d_h == 32) {  // N = 96: 128-column tiles with the tail columns clamped
         if (tall) err = launch_gemm_dma<QP, 128, 128, 32, 2, 2, 4, 2>(qp, units, l_a, 96, st);
@@ -503,8 +507,10 @@ static hipError_t smha_mfma_qkv_attention(const SmhaArgs &a, hipStream_t st)
         err = launch_gemm_dma<QP, 128, 128, 32, 2, 2, 4, 2>(qp, units, l_a, 3 * a.d_h, st);
     }
     if (err != hipSuccess) return err;
-    if ((err = launch_rope<bf16_t>(a, st)) != hipSuccess) return err;
-
+    return launch_rope<bf16_t>(a, st);
+    };
+    if (!(a.skip & SMHA_STEP_QKV) && (err = projections()) != hipSuccess) return err;
+    if (a.skip & SMHA_STEP_ATTENTION) return hipSuccess;
     return mfma_attn ? launch_attention_mfma(a, st) : launch_attention_generic<bf16_t>(a, st);
 }
 
@@ -519,8 +525,9 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     // the pipelined out-projection finds each patch's segments itself; the other engines read the
     // inverse map
     const bool out_dma = (long)a.k * a.c < (1L << 20);
-    if (!out_dma && (err = launch_inverse_map(a, st)) != hipSuccess) return err;
     if ((err = smha_mfma_qkv_attention(a, st)) != hipSuccess) return err;
+    if (a.skip & SMHA_STEP_OUT) return hipSuccess;
+    if (!out_dma && (err = launch_inverse_map(a, st)) != hipSuccess) return err;
     const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
 
     OP op = make_outproj<bf16_t>(a);

@@ -1,7 +1,7 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the same
 seeded inputs.  Selection indices must be bit-exact (rows the oracle flags as near-ties, kept vs
 dropped gate within 1e-5 relative, are counted and reported, not failed); outputs must be within
-max |y-r| / max(|r|, rms of r's row) <= 1e-4 for fp32 storage and 2e-2 for bf16 storage with fp32
+max |y-r| / max(|r|, rms(r)) <= 1e-4 for fp32 storage and 2e-2 for bf16 storage with fp32
 accumulation.  Stage tests feed each GPU stage the exact tensors the oracle stage sees, and are
 run without the residual and without gates so every expert's contribution is checked at full
 size; the layer test runs the benchmark's own call (uoe_layer_forward, all flags on).
@@ -20,29 +20,41 @@ pytestmark = pytest.mark.gpu
 R, GE, GP = B.FLAG_RESIDUAL, B.FLAG_GATE_EXPERT, B.FLAG_GATE_PATCH
 assert (R, GE, GP) == (oracle.RESIDUAL, oracle.GATE_EXPERT, oracle.GATE_PATCH)
 TOL = {synth.F32: 1e-4, synth.BF16: 2e-2}
-GATE_RTOL = 1e-3      # fp32 router arithmetic against fp64, relative, on the gate values
+# fp32 router arithmetic against fp64, relative, on the gate values; by storage dtype as the output bounds are
+GATE_RTOL = {synth.F32: 1e-4, synth.BF16: 1e-3}
 
 
-def scaled_err(y, r):
-    """max |y - r| / max(|r|, rms(r[token])): relative error with the token's own output magnitude
-    (the rms of its d output values) as the floor.
-
-    The floor is per output row because rows can differ a lot in magnitude (under the causal mask the
-    first tokens of an expert attend to one or two keys and their outputs are several times larger
-    than those of tokens that average over hundreds), and an error is judged against the vector it
-    belongs to.  Rows the block does not write (without the residual: patches nobody selected) are
-    exactly zero on both sides and must match exactly.
-    """
+def _err_parts(y, r):
     r = np.asarray(r, np.float64)
     y = np.asarray(y, np.float64)
     written = np.any(r != 0.0, axis=-1)
+    # rows the block does not write (without the residual: patches nobody selected) are exactly zero
+    # on both sides and must match exactly
     assert np.array_equal(y[~written], r[~written])
+    return y, r, written
+
+
+def scaled_err(y, r):
+    """max |y - r| / max(|r|, rms(r)) with rms(r) taken over the whole reference tensor: the metric
+    every base-path test (no causal mask) asserts."""
+    y, r, written = _err_parts(y, r)
+    if not written.any():
+        return 0.0
+    rms = np.sqrt(np.mean(r * r))
+    return float(np.max(np.abs(y - r) / np.maximum(np.abs(r), rms)))
+
+
+def scaled_err_rows(y, r):
+    """The same with the floor taken per output token (rms of its d values).  Only the tests that run
+    the shared causal mask assert this one: there the first tokens of an expert attend to one or two
+    keys and their rows are several times larger than rows that average over hundreds of keys, so the
+    bf16 rounding of v on those rows alone exceeds the bound when measured against the tensor-wide rms."""
+    y, r, written = _err_parts(y, r)
     if not written.any():
         return 0.0
     rw = r[written]
     rms = np.sqrt(np.mean(rw * rw, axis=-1, keepdims=True))
-    den = np.maximum(np.abs(rw), rms)
-    return float(np.max(np.abs(y[written] - rw) / den))
+    return float(np.max(np.abs(y[written] - rw) / np.maximum(np.abs(rw), rms)))
 
 
 def check_indices(name, got, want, margin):
@@ -125,14 +137,14 @@ def test_route_parity(name):
     check_valid_selection(p_idx, cfg.m)
     check_indices(name + ":expert", e_idx, ref.expert_id, ref.expert_margin)
     check_indices(name + ":patch", p_idx, ref.patch_id, ref.patch_margin)
-    np.testing.assert_allclose(to_host(dev.a_expert_gate), ref.expert_gate, rtol=GATE_RTOL, atol=1e-30)
-    np.testing.assert_allclose(to_host(dev.a_patch_gate), ref.patch_gate, rtol=GATE_RTOL, atol=1e-30)
+    np.testing.assert_allclose(to_host(dev.a_expert_gate), ref.expert_gate, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
+    np.testing.assert_allclose(to_host(dev.a_patch_gate), ref.patch_gate, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
     # the UoME-style call: expert selection only, one patch
     dev.route_m(u=dev.x)
     torch.cuda.synchronize()
     refm = oracle.route(inp.x, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
     check_indices(name + ":uome-expert", to_host(dev.m_expert_idx), refm.expert_id, refm.expert_margin)
-    np.testing.assert_allclose(to_host(dev.m_expert_gate), refm.expert_gate, rtol=GATE_RTOL, atol=1e-30)
+    np.testing.assert_allclose(to_host(dev.m_expert_gate), refm.expert_gate, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
 
 
 def test_route_degenerate_modes_and_ties():
@@ -161,7 +173,7 @@ def test_route_degenerate_modes_and_ties():
 
 
 # --------------------------------------------------------------------------- gather
-@pytest.mark.parametrize("name", ["ragged_lp14", "bf16_ragged", "tiny", "lm", "vit"])
+@pytest.mark.parametrize("name", ["ragged_lp14", "bf16_ragged"] + synth.CONFIG_ORDER)
 def test_gather_bit_exact(name):
     cfg = get_cfg(name)
     inp = synth.make_inputs(cfg, w_std=w_std_for(name))
@@ -307,7 +319,7 @@ def fro_err(y, r):
     return float(np.sqrt(np.sum((y - r) ** 2)) / nr) if nr > 0 else float(np.any(y))
 
 
-@pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["lm", "vit_bwd"])
+@pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["lm", "vit_bwd", "longrange", "large"])
 @pytest.mark.parametrize("flags", [0, R | GE])
 def test_uome_backward_parity(name, flags):
     """uoe_uome_backward against the oracle's chain rule (itself pinned by finite differences of
@@ -388,6 +400,13 @@ GATE_GRAD_TOL = 4e-2
 # front of the SMHA backward's, and the router gradients inherit the gate gradients' error.
 LAYER_BWD_TOL = 4e-2
 LAYER_BWD_FRO_TOL = 1e-2
+# A router's weight gradient is an outer product of the (few) logit gradients with the block input:
+# d_w_expert[i, :] = sum_b dz[b,i] * x[b, :].  An error delta in dz[b,i] shows up on every element of row i
+# as delta * x, and the worst of N such elements carries the largest |x| of N unit normals, sqrt(2 ln N):
+# 5.4 for the 2M elements of `lm`, 6.1 for the 134M elements of `large`.  With gate gradients good to
+# 6-8e-3 of their tensor's rms (the Frobenius bound below holds at every size) the worst element reads
+# 3-4e-2 on `lm` and 4.4-4.8e-2 on `large`: the element-wise bound on the router gradients is 5e-2.
+ROUTER_GRAD_TOL = 5e-2
 
 
 @pytest.mark.parametrize("name,flags", [(nm, fl) for nm in list(SMHA_BWD_CONFIGS) + ["lm"] for fl in (0, R | GE | GP, R | GE | GP | CA)]
@@ -491,7 +510,7 @@ def test_route_backward_parity(name):
 @pytest.mark.parametrize("name,fa,rope_dim", [("sb_dh64", R | GE | GP, 0), ("sb_long", R | GE | GP | CA, 16),
                                               ("lm", R | GE | GP, 0), ("lm", R | GE | GP | CA, 32),
                                               ("ds_bf16_lp32", R | GE | GP, 0), ("ds_lm", R | GE | GP | CA, 32),
-                                              ("longrange", R | GE | GP, 0)])
+                                              ("longrange", R | GE | GP, 0), ("large", R | GE | GP | CA, 32)])
 def test_layer_backward_parity(name, fa, rope_dim):
     run_layer_backward(name, fa, rope_dim)
 
@@ -519,7 +538,15 @@ def run_layer_backward(name, fa, rope_dim, pad_frac=0.0):
             setattr(inp, attr, getattr(inp, attr) * np.float32(2.0 ** -np.ceil(np.log2(ld_std))))
     d_out = synth.make_upstream_grad(cfg)
     pad = synth.make_pad_mask(cfg, pad_frac) if pad_frac > 0 else None
-    fwd = oracle.layer_forward(inp, fa, fm, rope_dim, pad)
+    if name == "large":   # the backward chain needs the routing and u, not the layer output: skip the oracle's MLP forward
+        ra = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                          inp.noise_a_expert, inp.noise_a_patch)
+        u = oracle.smha(inp.x, inp.wq, inp.wk, inp.wv, inp.wo, ra.expert_id, ra.expert_gate, ra.patch_id,
+                        ra.patch_gate, cfg.m, fa, rope_dim, pad)
+        fwd = oracle.LayerResult(ra, u, oracle.route(u, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None,
+                                                     inp.noise_m_expert, None), None)
+    else:
+        fwd = oracle.layer_forward(inp, fa, fm, rope_dim, pad)
     ra, rm = fwd.routing_a, fwd.routing_m
     ge_a, gp_a, ge_m, gp_m = (g.astype(np.float32) for g in (ra.expert_gate, ra.patch_gate, rm.expert_gate, rm.patch_gate))
     dev = DeviceLayer(inp, fa, fm, rope_dim=rope_dim)
@@ -549,7 +576,10 @@ def run_layer_backward(name, fa, rope_dim, pad_frac=0.0):
         errs[nm], fro[nm] = grad_err(y, r), fro_err(y, r)
     print(f"[layer backward {name} fa={fa}] " + " ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
     print(f"[layer backward {name} fa={fa}] fro " + " ".join(f"{k} {v:.2e}" for k, v in fro.items()), flush=True)
-    assert max(errs.values()) <= LAYER_BWD_TOL and max(fro.values()) <= LAYER_BWD_FRO_TOL
+    is_router = lambda nm: "_w_expert" in nm or "_w_b" in nm or "_w_a" in nm
+    assert max(v for k, v in errs.items() if not is_router(k)) <= LAYER_BWD_TOL
+    assert max(v for k, v in errs.items() if is_router(k)) <= ROUTER_GRAD_TOL
+    assert max(fro.values()) <= LAYER_BWD_FRO_TOL
 
 
 @pytest.mark.parametrize("mode", ["expert_only", "data_only"])
@@ -613,6 +643,51 @@ def test_layer_backward_is_deterministic_and_reusable():
         assert torch.isfinite(first[k].float()).all(), k
 
 
+def check_u_against_oracle(dev, inp, ra, u_ref, fa, tag):
+    """The SMHA output against the all-fp64 chain.  Where the device's own selection equals the
+    oracle's (always, except on rows the oracle flags as near-ties) this is the u the layer call
+    produced; otherwise the oracle's routing results are fed to the compute call, so that the
+    contraction is still judged on the reference's selection."""
+    cfg = dev.cfg
+    own = (np.array_equal(to_host(dev.a_expert_idx), ra.expert_id) and np.array_equal(to_host(dev.a_patch_idx), ra.patch_id))
+    if own:
+        dev.smha_forward()
+    else:
+        dev.smha_forward(expert_idx=torch.from_numpy(ra.expert_id).to(dev.device),
+                         expert_gate=to_device(ra.expert_gate.astype(np.float32), synth.F32, dev.device),
+                         patch_idx=torch.from_numpy(ra.patch_id).to(dev.device),
+                         patch_gate=to_device(ra.patch_gate.astype(np.float32), synth.F32, dev.device))
+    torch.cuda.synchronize()
+    got = to_host(dev.u)
+    err, err_rows = scaled_err(got, u_ref), scaled_err_rows(got, u_ref)
+    print(f"[{tag}] u scaled err {err:.3e} (per-row floor {err_rows:.3e}), "
+          f"{'own' if own else 'oracle-fed'} routing", flush=True)
+    return err
+
+
+def check_layer_out(dev, inp, out_layer, m_idx, rm, want, pick, fm, tag, err_fn=None):
+    """End-to-end output against the all-fp64 chain on the token rows `pick`.  Samples whose UoME
+    top-k equals the chain's are judged on the layer call's own output.  Every sample is judged a
+    second time with the chain's UoME selection and gates fed to uoe_uome_forward on the device's
+    u, so a selection flipped by the rounding of u never leaves a sample unchecked."""
+    cfg = dev.cfg
+    err_fn = err_fn or scaled_err
+    same = np.all(m_idx == rm.expert_id, axis=-1)
+    print(f"[{tag}] UoME top-k equal to the all-fp64 chain on {int(same.sum())}/{cfg.b} samples", flush=True)
+    if same.any():
+        err = err_fn(out_layer[same][:, pick], want[same])
+        print(f"[{tag}] out scaled err {err:.3e} on the layer's own routing (tol {TOL[cfg.dtype]:.0e})", flush=True)
+        assert err <= TOL[cfg.dtype]
+    fed = torch.empty_like(dev.out)
+    dev.uome_forward(expert_idx=torch.from_numpy(rm.expert_id).to(dev.device),
+                     expert_gate=to_device(rm.expert_gate.astype(np.float32), synth.F32, dev.device), out=fed)
+    torch.cuda.synchronize()
+    err = err_fn(to_host(fed)[:, pick], want)
+    print(f"[{tag}] out scaled err {err:.3e} with the chain's UoME routing fed, all {cfg.b} samples", flush=True)
+    assert err <= TOL[cfg.dtype]
+    return same
+
+
 # --------------------------------------------------------------------------- single-mode SMHA blocks
 @pytest.mark.parametrize("mode", ["expert_only", "data_only"])
 @pytest.mark.parametrize("name", ["bf16_ragged", "lm"])
@@ -640,16 +715,9 @@ def test_layer_with_single_mode_smha(name, mode):
     check_indices(name + ":smha-patch", to_host(dev.a_patch_idx), ref.routing_a.patch_id, ref.routing_a.patch_margin)
     out_layer = to_host(dev.out)
     m_idx = to_host(dev.m_expert_idx)
-    dev.smha_forward()
-    torch.cuda.synchronize()
-    err_u = scaled_err(to_host(dev.u), ref.u)
-    print(f"[layer {mode} {name}] u scaled err {err_u:.3e}", flush=True)
+    err_u = check_u_against_oracle(dev, inp, ref.routing_a, ref.u, fa, f"layer {mode} {name}")
     assert err_u <= TOL[cfg.dtype]
-    same = np.all(m_idx == ref.routing_m.expert_id, axis=-1)
-    if same.any():
-        err = scaled_err(out_layer[same], ref.out[same])
-        print(f"[layer {mode} {name}] out scaled err {err:.3e} on {int(same.sum())}/{cfg.b} samples", flush=True)
-        assert err <= TOL[cfg.dtype]
+    check_layer_out(dev, inp, out_layer, m_idx, ref.routing_m, ref.out, np.arange(cfg.l), fm, f"layer {mode} {name}")
 
 
 # --------------------------------------------------------------------------- dynamic capacity
@@ -676,7 +744,7 @@ def test_route_capacity_parity(name, patch_k):
         assert abs(int(got_cap[bb]) - int(ref.capacity[bb])) <= slack, (bb, got_cap[bb], ref.capacity[bb], slack)
         if slack == 0:
             np.testing.assert_array_equal(got_f[bb], (cfg.n_a * ref.count[bb] / (patch_k * cfg.m)).astype(np.float32))
-    np.testing.assert_allclose(got_p, ref.load_p, rtol=GATE_RTOL, atol=1e-30)
+    np.testing.assert_allclose(got_p, ref.load_p, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
     print(f"[capacity {name} k={patch_k}] c per sample {got_cap.tolist()[:8]} near-tie patches {int(near.sum())}", flush=True)
     # the protocol: one c for the call, routing with it
     c_dyn = int(got_cap.max())
@@ -717,7 +785,7 @@ def test_balance_loss_parity(name):
     # against the oracle's own statistics (rows without near-ties only differ by the fp32 gates)
     ref = oracle.capacity(oracle.data_router_logits(inp.x, inp.a_w_b, inp.a_w_a, inp.noise_a_patch), 1)
     clean = ~np.any(ref.margin < oracle.NEAR_TIE_REL, axis=1)
-    np.testing.assert_allclose(to_host(loss)[clean], oracle.balance_loss(ref.load_f, ref.load_p, alpha)[clean], rtol=GATE_RTOL)
+    np.testing.assert_allclose(to_host(loss)[clean], oracle.balance_loss(ref.load_f, ref.load_p, alpha)[clean], rtol=GATE_RTOL[cfg.dtype])
     print(f"[balance loss {name}] L per sample {to_host(loss)[:4].tolist()}", flush=True)
 
 
@@ -807,7 +875,7 @@ def test_uome_data_selection_stage_parity(name, flags):
     check_valid_selection(p_idx, cfg.m_m)
     check_indices(name + ":expert", e_idx, ref.expert_id, ref.expert_margin)
     check_indices(name + ":patch", p_idx, ref.patch_id, ref.patch_margin)
-    np.testing.assert_allclose(to_host(dev.m_patch_gate), ref.patch_gate, rtol=GATE_RTOL, atol=1e-30)
+    np.testing.assert_allclose(to_host(dev.m_patch_gate), ref.patch_gate, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
     # the block on the oracle's routing results
     dev.uome_forward(expert_idx=torch.from_numpy(ref.expert_id).to(dev.device),
                      expert_gate=to_device(ref.expert_gate.astype(np.float32), synth.F32, dev.device),
@@ -865,7 +933,7 @@ def test_layer_with_data_selected_uome(name):
                       inp.noise_m_expert, None)
     check_indices(name + ":uome-expert", m_idx, rm.expert_id, rm.expert_margin)
     check_indices(name + ":uome-patch", m_pidx, rm.patch_id, rm.patch_margin)
-    np.testing.assert_allclose(m_pgate, rm.patch_gate, rtol=GATE_RTOL, atol=1e-30)
+    np.testing.assert_allclose(m_pgate, rm.patch_gate, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
     want = oracle.uome(u_gpu, inp.a_in, inp.a_out, m_idx, m_gate.astype(np.float32), fm, m_pidx,
                        m_pgate.astype(np.float32), cfg.m_m)
     err = scaled_err(out_layer, want)
@@ -902,32 +970,23 @@ def test_layer_parity(name):
     # call keeps u in its workspace; the path is deterministic, so the SMHA call on the layer's own
     # routing results reproduces it bit for bit.
     m_idx, m_gate = to_host(dev.m_expert_idx), to_host(dev.m_expert_gate)
-    out_layer = dev.out.clone()
+    out_layer = to_host(dev.out)
     dev.smha_forward()
     torch.cuda.synchronize()
     u_gpu = to_host(dev.u)
-    err_u = scaled_err(u_gpu, u)
-    print(f"[layer {name}] u scaled err {err_u:.3e}", flush=True)
-    assert err_u <= TOL[cfg.dtype]
     rm_on_gpu_u = oracle.route(u_gpu, cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None,
                                inp.noise_m_expert, None)
     check_indices(name + ":uome-expert(on GPU u)", m_idx, rm_on_gpu_u.expert_id, rm_on_gpu_u.expert_margin)
-    np.testing.assert_allclose(m_gate, rm_on_gpu_u.expert_gate, rtol=GATE_RTOL, atol=1e-30)
+    np.testing.assert_allclose(m_gate, rm_on_gpu_u.expert_gate, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
+    err_u = check_u_against_oracle(dev, inp, ra, u, fa, f"layer {name}")
+    assert err_u <= TOL[cfg.dtype]
 
-    # end to end: only meaningful where rounding of u did not flip the UoME top-k
-    same = np.all(m_idx == rm.expert_id, axis=-1)
-    print(f"[layer {name}] UoME top-k equal to the all-fp64 chain on {int(same.sum())}/{cfg.b} samples", flush=True)
-    got = to_host(out_layer)
     if ref is not None:
-        want = ref.out
-        pick = np.arange(cfg.l)
+        want, pick = ref.out, np.arange(cfg.l)
     else:
         pick = np.sort(np.random.default_rng(6).choice(cfg.l, 128, replace=False))
         want = oracle.uome(u[:, pick], inp.a_in, inp.a_out, rm.expert_id, rm.expert_gate, fm)
-    if same.any():
-        err = scaled_err(got[same][:, pick], want[same])
-        print(f"[layer {name}] out scaled err {err:.3e} (tol {TOL[cfg.dtype]:.0e})", flush=True)
-        assert err <= TOL[cfg.dtype]
+    same = check_layer_out(dev, inp, out_layer, m_idx, rm, want, pick, fm, f"layer {name}")
     if cfg.dtype == synth.F32:
         assert same.all()
 
@@ -1105,9 +1164,11 @@ def run_smha_variant(name, flags, rope_dim=0, pad_frac=0.0, samples=None):
                        ref.patch_gate.astype(np.float32)[sel], cfg.m, flags, rope_dim,
                        None if pad is None else pad[sel])
     assert np.all(np.isfinite(got))
-    err = scaled_err(got[sel], want)
-    print(f"[smha {name} flags={flags} rope={rope_dim} pad={pad_frac}] scaled err {err:.3e} (tol {TOL[cfg.dtype]:.0e})",
-          flush=True)
+    # the tensor-wide floor is asserted unless the causal mask is on (see scaled_err_rows)
+    err_g, err_r = scaled_err(got[sel], want), scaled_err_rows(got[sel], want)
+    err = err_r if flags & CA else err_g
+    print(f"[smha {name} flags={flags} rope={rope_dim} pad={pad_frac}] scaled err {err_g:.3e}, per-row floor {err_r:.3e} "
+          f"(asserted: {'per-row' if flags & CA else 'tensor-wide'}, tol {TOL[cfg.dtype]:.0e})", flush=True)
     assert err <= TOL[cfg.dtype]
 
 
@@ -1143,8 +1204,10 @@ def test_layer_with_causal_mask_and_rope(name, pad_frac):
     torch.cuda.synchronize()
     ref = oracle.layer_forward(inp, fa, fm, rope_dim, pad)
     check_indices(f"{name}-causal:smha-patch", to_host(dev.a_patch_idx), ref.routing_a.patch_id, ref.routing_a.patch_margin)
-    same = np.all(to_host(dev.m_expert_idx) == ref.routing_m.expert_id, axis=-1)
-    assert same.any()
-    err = scaled_err(to_host(dev.out)[same], ref.out[same])
-    print(f"[layer {name} causal+rope pad {pad_frac}] out scaled err {err:.3e}", flush=True)
-    assert err <= TOL[cfg.dtype]
+    out_layer, m_idx = to_host(dev.out), to_host(dev.m_expert_idx)
+    # u of the layer call, reproduced by the SMHA call on the layer's own routing (deterministic path)
+    dev.smha_forward(pad_mask=None if pad is None else torch.from_numpy(pad).to(dev.device))
+    torch.cuda.synchronize()
+    # causal mask: judged with the per-row floor (see scaled_err_rows)
+    check_layer_out(dev, inp, out_layer, m_idx, ref.routing_m, ref.out, np.arange(cfg.l), fm,
+                    f"layer {name} causal+rope pad {pad_frac}", err_fn=scaled_err_rows)
