@@ -1,18 +1,24 @@
 #!/usr/bin/env python3
 """Throughput of one Union-of-Experts layer forward (uoe_layer_forward) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lm|longrange|vit|large|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|lm|longrange|vit|tiny]
 
 A step is one pass of the whole hot path (route -> SMHA -> route -> UoME) over one batch of seeded
-synthetic input that is already resident in HBM.  Prints ONE JSON line with the whole-job
-tokens/s, a roofline entry for the dominant kernel (timed live with events on the launch stream)
-and the CPU oracle timed on this machine's host cores as a reported baseline.
+synthetic input that is already resident in HBM; steps run one after the other on one stream.
+After W warm-up steps, K steps are timed between two synchronisations with events on the launch
+stream; that region is repeated (--regions) and the median region is reported.  Prints ONE JSON
+line: whole-job tokens/s, a roofline entry for the dominant kernel and one per kernel of the layer
+(each timed live with events on the launch stream against its algorithmic FLOPs or bytes), what
+the device delivers for a plain copy / read-only stream / MFMA loop, the realised expert loads,
+and the CPU oracle timed on this machine's host cores as a reported baseline (with the selection
+parity and near-tie counts of the timed batch).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -36,27 +42,118 @@ def layer_flops(c) -> dict:
                 total=routers + qkv + attn + outp + uome)
 
 
+def kernel_work(c, es: int) -> dict:
+    """Algorithmic work of each kernel of the layer call: FLOPs and the HBM bytes the method itself
+    has to move (every operand once, active units only), per launch.  es = bytes per stored element."""
+    bld = c.b * c.l * c.d
+    units_a = c.b * c.k_a
+    hidden = c.b * c.l * c.k_m * c.d_e
+    return {
+        # Eq. 21: x and W_E once each
+        "route_expert_a": dict(eq="Eq. 21-22", flops=2 * bld * c.n_a, bytes=(bld + c.n_a * c.l * c.d) * es),
+        # Eq. 13-14, 17: x once, W_B, W_A
+        "route_data_a": dict(eq="Eq. 13-14, 17", flops=2 * bld * c.n_a + 2 * c.b * c.n_a * c.l * c.m,
+                             bytes=(bld + c.d * c.n_a + c.l * c.m) * es),
+        # both SMHA routers read the same x: once
+        "route_a": dict(eq="Eq. 13-14, 17, 21-22", flops=4 * bld * c.n_a + 2 * c.b * c.n_a * c.l * c.m,
+                        bytes=(bld + c.n_a * c.l * c.d + c.d * c.n_a + c.l * c.m) * es),
+        "gather": dict(eq="Eq. 18", flops=0, bytes=2 * units_a * c.l_a * c.d * es),
+        # gathered rows in, q/k/v out, the active experts' projection weights
+        "smha_qkv": dict(eq="Eq. 18, 28-30", flops=6 * units_a * c.l_a * c.d * c.d_h,
+                         bytes=(units_a * c.l_a * c.d + 3 * units_a * c.l_a * c.d_h + 3 * c.n_a * c.d * c.d_h) * es),
+        "smha_attention": dict(eq="Eq. 33-34", flops=4 * units_a * c.l_a * c.l_a * c.d_h,
+                               bytes=4 * units_a * c.l_a * c.d_h * es),
+        # attention output in, residual in, u out, W^o
+        "smha_out": dict(eq="Eq. 35-36", flops=2 * units_a * c.l_a * c.d_h * c.d,
+                         bytes=(units_a * c.l_a * c.d_h + 2 * bld + c.n_a * c.d_h * c.d) * es),
+        "route_m": dict(eq="Eq. 21-22 on u", flops=2 * bld * c.n_m, bytes=(bld + c.n_m * c.l * c.d) * es),
+        "uome_up": dict(eq="Eq. 38", flops=2 * bld * c.k_m * c.d_e, bytes=(bld + c.n_m * c.d * c.d_e + hidden) * es),
+        "uome_down": dict(eq="Eq. 39-40", flops=2 * bld * c.k_m * c.d_e,
+                          bytes=(hidden + c.n_m * c.d_e * c.d + 2 * bld) * es),
+    }
+
+
 def describe(c) -> str:
     ds = f" m{c.m_m} c{c.c_m}" if c.m_m > 1 else ""
     return (f"{c.name}: b{c.b} l{c.l} d{c.d}; SMHA n{c.n_a} d_h{c.d_h} m{c.m} c{c.c} k{c.k_a}; "
             f"UoME n{c.n_m} d_e{c.d_e} k{c.k_m}{ds}; {c.dtype}")
 
 
-def run_stage(args, cfg, dev, B, torch, make_lane) -> int:
-    """Loop one stage (its inputs produced once by the stages before it) and print its mean time."""
-    dev.layer_forward()      # fills routing results and u
-    dev.smha_forward()
+class Pacer:
+    """Times launches by events with the host out of the picture: the launches are queued while the
+    GPU is still busy with a few large copies (the library's own copy probe), so what is timed is the
+    GPU working through its queue, not the host filling it."""
+
+    def __init__(self, torch, B, device):
+        self.torch, self.B = torch, B
+        self.src = torch.zeros(1 << 28, dtype=torch.uint8, device=device)
+        self.dst = torch.empty_like(self.src)
+        self.ev0, self.ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def __call__(self, fn, count):
+        """(mean ms per launch, whether the host stayed ahead of the GPU)."""
+        torch = self.torch
+        torch.cuda.synchronize()
+        for _ in range(6):
+            self.B.probe_copy(self.src, self.dst, self.src.numel())
+        self.ev0.record()
+        for _ in range(count):
+            fn()
+        self.ev1.record()
+        ahead = not self.ev0.query()
+        torch.cuda.synchronize()
+        return self.ev0.elapsed_time(self.ev1) / count, ahead
+
+
+def stage_calls(cfg, dev, B, torch):
+    """One C-ABI call per kernel (or kernel group) of the layer, on the tensors a layer call left."""
+    dev.layer_forward()      # fills routing results
+    dev.smha_forward()       # u and the SMHA workspace (q, k, v, o)
     dev.route_m()
     hidden = torch.empty((cfg.b, cfg.l, cfg.k_m * cfg.d_e), dtype=dev.tdtype, device=dev.device)
     h = torch.empty((cfg.b, cfg.k_a, cfg.l_a, cfg.d), dtype=dev.tdtype, device=dev.device)
     if cfg.m_m == 1:
         B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden)
+    dev.smha_forward()       # again: the routing call above used the head of the workspace as its scratch
+    code = dev.smha.dtype
+    # single-router descriptors of the SMHA block: expert router alone (one patch), data router alone (k = n)
+    blk_e = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_a, cfg.k_a, 1, 1, cfg.d_h, code, 0)
+    blk_d = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_a, cfg.n_a, cfg.m, cfg.c, cfg.d_h, code, 0)
+    i32 = dict(dtype=torch.int32, device=dev.device)
+    e_idx_all = torch.empty((cfg.b, cfg.n_a), **i32)
+    e_idx, e_gate = torch.empty_like(dev.a_expert_idx), torch.empty_like(dev.a_expert_gate)
+    p_idx, p_gate = torch.empty_like(dev.a_patch_idx), torch.empty_like(dev.a_patch_gate)
+
+    def smha_step(steps):
+        return lambda: B.smha_forward_steps(dev.smha, dev.x, dev.wq, dev.wk, dev.wv, dev.wo, dev.a_expert_idx,
+                                            dev.a_expert_gate, dev.a_patch_idx, dev.a_patch_gate, None, dev.u, dev.ws,
+                                            steps)
     calls = {
         "route_a": dev.route_a, "smha": dev.smha_forward, "route_m": dev.route_m, "uome": dev.uome_forward,
-        "uome_up": lambda: B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden),
-        "uome_down": lambda: B.uome_down(dev.uome, hidden, dev.a_out, dev.u, dev.m_expert_idx, dev.out),
+        "route_expert_a": (lambda: B.route(blk_e, dev.x, dev.a_w_expert, None, None, dev.noise_a_expert, None, e_idx, e_gate,
+                                           None, None, dev.ws)) if dev.a_w_expert is not None else None,
+        "route_data_a": (lambda: B.route(blk_d, dev.x, None, dev.a_w_b, dev.a_w_a, None, dev.noise_a_patch, e_idx_all, None,
+                                         p_idx, p_gate, dev.ws)) if dev.a_w_b is not None else None,
+        "smha_qkv": smha_step(B.SMHA_STEP_QKV), "smha_attention": smha_step(B.SMHA_STEP_ATTENTION),
+        "smha_out": smha_step(B.SMHA_STEP_OUT),
+        "uome_up": (lambda: B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden))
+        if cfg.m_m == 1 else None,
+        "uome_down": (lambda: B.uome_down(dev.uome, hidden, dev.a_out, dev.u, dev.m_expert_idx, dev.out))
+        if cfg.m_m == 1 else None,
         "gather": lambda: B.gather(dev.smha, dev.x, dev.a_expert_idx, dev.a_patch_idx, h),
     }
+    return {k: v for k, v in calls.items() if v is not None}
+
+
+def run_stage(args, cfg, dev, B, torch, make_lane) -> int:
+    """Loop one stage (its inputs produced once by the stages before it) and print its mean time."""
+    calls = stage_calls(cfg, dev, B, torch)
+    if args.stage in ("probe_copy", "probe_read"):   # transfers of known size (1 GiB): counter calibration
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev.device).random_(0, 255)
+        dst = torch.empty_like(src)
+        sink = torch.empty(4096, dtype=torch.int32, device=dev.device)
+        calls["probe_copy"] = lambda: B.probe_copy(src, dst, src.numel())
+        calls["probe_read"] = lambda: B.probe_read(src, src.numel(), sink)
     if args.stage == "uome_bwd":   # backward of the expert-selection UoME block on a synthetic upstream gradient
         from paper_2503_02495_amd import synth
         from paper_2503_02495_amd.harness import to_device
@@ -84,36 +181,9 @@ def run_stage(args, cfg, dev, B, torch, make_lane) -> int:
             ws = torch.empty(B.route_backward_workspace_bytes(dev.smha), dtype=torch.uint8, device=dev.device)
             calls["route_bwd"] = lambda: B.route_backward(dev.smha, dev.x, dev.a_w_expert, dev.a_w_b, dev.a_w_a,
                                                           dev.a_expert_gate, dev.a_patch_gate, d_ge, d_gp, d_x, *grads, ws)
-    if args.stage == "copy":   # a plain copy of known size (1 GiB read + 1 GiB written): counter calibration
-        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).normal_()
-        dst = torch.empty_like(src)
-        calls["copy"] = lambda: dst.copy_(src)
-    if args.stage == "lib_gemm":   # context only: the vendor library's plain batched GEMM (no expert lookup, no SiLU,
-        # no gate, no residual) on the shapes of the two UoME GEMMs; nothing in the path calls it
-        ncol = cfg.k_m * cfg.d_e
-        ga = torch.empty((cfg.b, cfg.l, cfg.d), dtype=dev.tdtype, device=dev.device).normal_()
-        gw1 = torch.empty((cfg.b, cfg.d, ncol), dtype=dev.tdtype, device=dev.device).normal_()
-        gh = torch.empty((cfg.b, cfg.l, ncol), dtype=dev.tdtype, device=dev.device)
-        gw2 = torch.empty((cfg.b, ncol, cfg.d), dtype=dev.tdtype, device=dev.device).normal_()
-        go = torch.empty((cfg.b, cfg.l, cfg.d), dtype=dev.tdtype, device=dev.device)
-        res = {}
-        for nm, f in (("up_shape", lambda: torch.bmm(ga, gw1, out=gh)), ("down_shape", lambda: torch.bmm(gh, gw2, out=go))):
-            for _ in range(args.warmup):
-                f()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(args.steps):
-                f()
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / args.steps
-            res[nm] = {"us_per_call": round(us, 3), "tflops": round(2.0 * cfg.b * cfg.l * cfg.d * ncol / us * 1e-6, 1)}
-        print(json.dumps({"stage": "lib_gemm", "workload": cfg.name, "steps": args.steps, **res}))
-        return 0
     if args.stage == "layer_fwd_bwd" and args.stage_streams > 1:
         # a training step per batch, several independent batches in flight (one lane per stream, lane 0 on the
-        # program's own stream), as the forward benchmark does by default
+        # program's own stream)
         n_lanes = args.stage_streams
         lanes = [dev] + [make_lane() for _ in range(n_lanes - 1)]
         raw = [int(torch.cuda.current_stream().cuda_stream)] + [int(torch.cuda.Stream().cuda_stream) for _ in lanes[1:]]
@@ -136,6 +206,9 @@ def run_stage(args, cfg, dev, B, torch, make_lane) -> int:
         print(json.dumps({"stage": args.stage, "workload": cfg.name, "steps": args.steps, "streams": n_lanes,
                           "us_per_call": round(us, 3)}))
         return 0
+    if args.stage not in calls:
+        print(f"bench.py: stage {args.stage} does not apply to this configuration", file=sys.stderr)
+        return 2
     fn = calls[args.stage]
     for _ in range(args.warmup):
         fn()
@@ -151,13 +224,52 @@ def run_stage(args, cfg, dev, B, torch, make_lane) -> int:
     return 0
 
 
+def measured_ceilings(B, torch, device, pace) -> dict:
+    """What this device delivers for a plain copy, a read-only stream and a register-resident bf16 MFMA
+    loop (the library's probe kernels): the scale next to the published peaks."""
+    import numpy as np
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=device).random_(0, 255)
+    dst = torch.empty_like(src)
+    sink = torch.empty(4096, dtype=torch.int32, device=device)
+    out = {}
+    for _ in range(2):
+        B.probe_copy(src, dst, n)
+        B.probe_read(src, n, sink)
+    ms, _ = pace(lambda: B.probe_copy(src, dst, n), 10)
+    out["copy_GBs"] = round(2.0 * n / (ms * 1e-3) / 1e9, 1)          # bytes read + bytes written
+    ms, _ = pace(lambda: B.probe_read(src, n, sink), 10)
+    out["read_GBs"] = round(n / (ms * 1e-3) / 1e9, 1)
+    del src, dst
+    msink = torch.empty(131072, dtype=torch.float32, device=device)
+    rng = np.random.default_rng(0)
+    vals = rng.standard_normal(6 * 64 * 8).astype(np.float32)
+    for tag, host in (("zeros", np.zeros_like(vals)), ("random", vals)):
+        ops = torch.from_numpy(host).to(device).to(torch.bfloat16).contiguous()
+        iters = 20000
+        B.probe_mfma(ops, iters, msink)
+        flops = [0.0]
+
+        def run():
+            flops[0] = B.probe_mfma(ops, iters, msink)
+        ms, _ = pace(run, 5)
+        out[f"mfma_bf16_TFLOPs_{tag}_operands"] = round(flops[0] / (ms * 1e-3) / 1e12, 1)
+    out["note"] = ("library probe kernels on this device: 1 GiB copy (read + write bytes counted), 1 GiB read-only "
+                   "stream, MFMA 32x32x16 bf16 loop without memory traffic")
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="lm")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="large",
+                    help="large (default: the largest single-GPU shape), lm, longrange, vit or tiny")
+    ap.add_argument("--regions", type=int, default=5,
+                    help="how many times the timed region of --steps steps is repeated; the median region is reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-rooflines", action="store_true", help="skip the per-kernel timings and the probes")
     ap.add_argument("--causal", action="store_true", help="SMHA with the shared causal mask (Sec. III-C.3)")
     ap.add_argument("--rope-dim", type=int, default=0, help="SMHA with partial RoPE on the last N dims (Eq. 32)")
     ap.add_argument("--uome-data-selection", default=None, metavar="M,C",
@@ -168,19 +280,16 @@ def main() -> int:
     ap.add_argument("--dynamic-capacity", type=int, default=0, metavar="K",
                     help="two-stage routing (Eq. 15-16): every step first computes the SMHA capacity with K experts per "
                          "patch (uoe_route_capacity), reads it back and runs the layer with c = its maximum over the batch")
-    ap.add_argument("--streams", type=int, default=4, metavar="S",
-                    help="independent steps in flight: step i runs on HIP stream i %% S with its own inputs, workspace and "
-                         "output (the steps of a throughput job do not depend on each other; one layer call is a chain of "
-                         "nine dependent launches that leaves the GPU idle between them; the default is one lane per "
-                         "hardware queue of the process: the stream the rest of the program uses and three more).  "
-                         "1 = one call after the other; that figure is reported beside the headline either way")
+    ap.add_argument("--streams", type=int, default=1, metavar="S",
+                    help="S > 1: additionally report (extra key steps_in_flight) the rate with S independent steps in "
+                         "flight, step i on HIP stream i %% S with its own inputs, workspace and output.  The headline "
+                         "value is always one call after the other on one stream")
     ap.add_argument("--stage-streams", type=int, default=1, metavar="S",
                     help="with --stage layer_fwd_bwd: S independent training steps in flight, one lane per stream")
-    ap.add_argument("--graph", action="store_true",
-                    help="replay one captured HIP graph per step instead of launching call by call")
     ap.add_argument("--stage", default=None,
-                    choices=["route_a", "smha", "route_m", "uome", "uome_up", "uome_down", "gather", "copy",
-                             "uome_bwd", "smha_bwd", "route_bwd", "layer_bwd", "layer_fwd_bwd", "lib_gemm"],
+                    choices=["route_a", "route_expert_a", "route_data_a", "smha", "smha_qkv", "smha_attention", "smha_out",
+                             "route_m", "uome", "uome_up", "uome_down", "gather", "probe_copy", "probe_read",
+                             "uome_bwd", "smha_bwd", "route_bwd", "layer_bwd", "layer_fwd_bwd"],
                     help="profiling aid: loop one C-ABI call of the path instead of the whole layer "
                          "and print its time (no JSON contract line)")
     args = ap.parse_args()
@@ -192,7 +301,7 @@ def main() -> int:
     import torch
     from paper_2503_02495_amd import binding as B
     from paper_2503_02495_amd import synth
-    from paper_2503_02495_amd.harness import DeviceLayer
+    from paper_2503_02495_amd.harness import DeviceLayer, to_host
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -223,19 +332,8 @@ def main() -> int:
         return run_stage(args, cfg, dev, B, torch,
                          lambda: DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim))
 
-    # ---- whole-path throughput.  The layer call only enqueues kernels (no allocation, no memset, no
-    # synchronisation), so it can also be captured into a HIP graph (--graph: a step is one replay).
-    # Either way every kernel of the path runs in every step.
-    def timed(step):
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / args.steps
-
+    # ---- whole-path throughput: one layer call after the other on one stream.  The call only enqueues
+    # kernels (no allocation, no memset, no synchronisation); every kernel of the path runs in every step.
     step_fn = dev.layer_forward
     if args.dynamic_capacity:
         import dataclasses
@@ -253,115 +351,117 @@ def main() -> int:
         dynamic_step()
         cfg = next(iter(by_c.values())).cfg        # report the shape that actually ran
         step_fn = dynamic_step
-    eager_ms = timed(step_fn)
-    launch = "eager"
-    ms_per_step = eager_ms
-    n_streams = 1 if (args.graph or args.dynamic_capacity) else max(1, args.streams)
-    if n_streams > 1:
-        # S replicas of the layer's buffers (same synthetic batch, separate allocations), one stream each
+
+    for _ in range(args.warmup):
+        step_fn()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    region_ms, region_wall_ms = [], []
+    for _ in range(max(1, args.regions)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(args.steps):
+            step_fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        region_wall_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
+        region_ms.append(ev0.elapsed_time(ev1) / args.steps)
+    ms_per_step = statistics.median(region_ms)
+    tokens_per_s = cfg.tokens / (ms_per_step * 1e-3)
+    fl = layer_flops(cfg)
+    is_bf16 = cfg.dtype == synth.BF16
+    es = 2 if is_bf16 else 4
+    peak_tf = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
+
+    # ---- independent steps in flight (extra key only)
+    in_flight = None
+    if args.streams > 1 and not args.dynamic_capacity:
+        n_streams = args.streams
         lanes = [dev] + [DeviceLayer(inp, fa, fm, device="cuda:0", rope_dim=args.rope_dim) for _ in range(n_streams - 1)]
-        # lane 0 stays on the stream everything so far ran on (it already owns a hardware queue)
         streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in lanes[1:]]
         raw = [int(st.cuda_stream) for st in streams]   # the hipStream_t values the C ABI takes
         torch.cuda.synchronize()                        # the replicas' uploads ran on the default stream
 
-        def timed_lanes():
-            def run(count):
-                for i in range(count):
-                    lanes[i % n_streams].layer_forward(stream=raw[i % n_streams])
-            run(max(args.warmup, n_streams))
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            run(args.steps)
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) * 1e3 / args.steps
-        ms_per_step = timed_lanes()
-        launch = f"eager, {n_streams} streams (independent steps in flight)"
+        def run(count):
+            for i in range(count):
+                lanes[i % n_streams].layer_forward(stream=raw[i % n_streams])
+        run(max(args.warmup, n_streams))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps)
+        torch.cuda.synchronize()
+        lanes_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         for lane in lanes[1:]:   # every lane ran the same batch through the same kernels
             if not torch.equal(lane.out, dev.out):
                 print("bench.py: lanes disagree", file=sys.stderr)
                 return 1
         del lanes[1:]
-    if args.graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            dev.layer_forward()
-        torch.cuda.current_stream().wait_stream(side)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            dev.layer_forward()
-        ms_per_step = timed(graph.replay)
-        launch = "hip graph replay"
-    tokens_per_s = cfg.tokens / (ms_per_step * 1e-3)
-    fl = layer_flops(cfg)
+        in_flight = {"streams": n_streams, "ms_per_step": round(lanes_ms, 5),
+                     "value": round(cfg.tokens / (lanes_ms * 1e-3), 1), "clock": "host wall clock"}
 
-    # ---- dominant kernel: the UoME up-projection grouped GEMM (half of the UoME FLOPs, which are
-    # 84-90% of the layer).  Timed alone with events on the stream it is launched on.
-    hidden = torch.empty((cfg.b, cfg.l, cfg.k_m * cfg.d_e), dtype=dev.tdtype, device=dev.device)
-    up = lambda: B.uome_up(dev.uome, dev.u, dev.a_in, dev.m_expert_idx, dev.m_expert_gate, hidden)
-    dev.smha_forward()          # u, then the UoME routing the GEMM reads
-    dev.route_m()
-    if uome_ds:                 # no separate entry point for the first layer: time the block's two GEMMs together
-        up = dev.uome_forward
-    for _ in range(max(3, args.warmup)):
-        up()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev.device).zero_()
-    dst = torch.empty_like(src)
+    # ---- realised expert loads of the timed batch (Eq. 23: how many samples each expert serves)
+    dev.layer_forward()
+    torch.cuda.synchronize()
+    loads = {"smha_samples_per_expert": np.bincount(to_host(dev.a_expert_idx).ravel(), minlength=cfg.n_a).tolist(),
+             "uome_samples_per_expert": np.bincount(to_host(dev.m_expert_idx).ravel(), minlength=cfg.n_m).tolist()}
+    pidx = to_host(dev.a_patch_idx)
+    eidx = to_host(dev.a_expert_idx)
+    picks = np.zeros((cfg.b, cfg.m), np.int64)       # how many active experts picked each patch
+    for bb in range(cfg.b):
+        for i in eidx[bb]:
+            picks[bb, pidx[bb, i]] += 1
+    loads["smha_patches_by_pick_count"] = np.bincount(picks.ravel(), minlength=cfg.k_a + 1).tolist()
 
-    def gpu_paced(fn, count):
-        """Mean time of `count` launches of fn on the current stream, by events, with the launches queued
-        while the GPU is still busy with large copies: what is timed is the GPU working through its queue,
-        not the host filling it.  Second value: whether the host really stayed ahead."""
-        torch.cuda.synchronize()
-        for _ in range(8):
-            dst.copy_(src)
-        ev0.record()
-        for _ in range(count):
-            fn()
-        ev1.record()
-        ahead = not ev0.query()
-        torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) / count, ahead
-    up_launches = min(args.steps, 200)
-    up_ms, up_ahead = gpu_paced(up, up_launches)
-    up_flops = float(fl["uome"]) if uome_ds else 2.0 * cfg.b * cfg.l * cfg.d * cfg.k_m * cfg.d_e
-    is_bf16 = cfg.dtype == synth.BF16
-    peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
-    achieved = up_flops / (up_ms * 1e-3) / 1e12
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath) and not uome_ds:
-        traffic = json.load(open(tpath)).get(f"uome_up:{cfg.name}")
-    roofline = {"kernel": "uome_forward, data selection (Eq. 37-40: both grouped GEMMs)" if uome_ds
-                else "uome_up (Eq. 38 grouped GEMM + SiLU + gate)", "bound": "mfma",
-                "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 5), "traffic": traffic,
-                "flops_per_launch": up_flops, "ms_per_launch": round(up_ms, 5), "launches_timed": up_launches,
-                "host_stayed_ahead": up_ahead}
+    # ---- per-kernel rooflines: every kernel of the layer call through its own C-ABI entry point, on the
+    # tensors the layer call left, timed with events on the launch stream while the host stays ahead
+    kernels, ceilings, roofline = [], None, None
+    if not args.no_kernel_rooflines and not uome_ds and not args.dynamic_capacity:
+        pace = Pacer(torch, B, dev.device)
+        calls = stage_calls(cfg, dev, B, torch)
+        work = kernel_work(cfg, es)
+        launches = max(5, min(args.steps, 50))
+        ridge = peak_tf * 1e12 / (PEAK_HBM_GBS * 1e9)
+        for name in ("route_expert_a", "route_data_a", "route_a", "gather", "smha_qkv", "smha_attention", "smha_out",
+                     "route_m", "uome_up", "uome_down"):
+            if name not in calls:
+                continue
+            fn, w = calls[name], work[name]
+            for _ in range(3):
+                fn()
+            ms, ahead = pace(fn, launches)
+            gbs, tfs = w["bytes"] / (ms * 1e-3) / 1e9, w["flops"] / (ms * 1e-3) / 1e12
+            bound = "mfma" if is_bf16 and w["bytes"] and w["flops"] / w["bytes"] >= ridge else "hbm"
+            if not is_bf16 and w["flops"] / max(w["bytes"], 1) >= PEAK_FP32_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+                bound = "alu"
+            ach, peak, unit = (gbs, PEAK_HBM_GBS, "GB/s") if bound == "hbm" else (tfs, peak_tf, "TFLOP/s")
+            kernels.append({"kernel": name, "eq": w["eq"], "bound": bound, "achieved": round(ach, 2), "peak": peak,
+                            "unit": unit, "frac": round(ach / peak, 4), "us_per_launch": round(ms * 1e3, 2),
+                            "flops": w["flops"], "bytes": w["bytes"], "GBs": round(gbs, 1), "TFLOPs": round(tfs, 2),
+                            "launches_timed": launches, "host_stayed_ahead": ahead,
+                            "note": {"route_expert_a": "expert router + its selection kernel",
+                                     "route_data_a": "data router + reduction + selection kernels",
+                                     "route_a": "the whole SMHA routing call (both routers, selection)",
+                                     "route_m": "UoME expert router + its selection kernel",
+                                     "gather": "standalone Eq. 18 copy; the layer call folds it into smha_qkv"}.get(name)})
+        # the dominant kernel: the single-kernel stage that takes the most time
+        single = [k for k in kernels if k["kernel"] not in ("route_a", "gather")]
+        dom = max(single, key=lambda k: k["us_per_launch"])
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(f"{dom['kernel']}:{cfg.name}")
+        roofline = {"kernel": f"{dom['kernel']} ({dom['eq']})", "bound": dom["bound"], "achieved": dom["achieved"],
+                    "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic,
+                    "algorithmic_flops_per_launch": dom["flops"], "algorithmic_bytes_per_launch": dom["bytes"],
+                    "ms_per_launch": round(dom["us_per_launch"] * 1e-3, 5), "launches_timed": launches,
+                    "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/ (bytes per launch)"
+                    if traffic is not None else None}
+        ceilings = measured_ceilings(B, torch, dev.device, pace)
+        del pace
 
-    # ---- what a dependent launch costs on the GPU's side whatever the kernel does: the smallest kernel of
-    # the library (the gather of the 128-token fp32 shape) 100 times on one stream, queued while the GPU is
-    # still busy (gpu_paced above; the figure is dropped if the GPU caught up with the host before
-    # everything was queued).  Context for the small shapes: their
-    # kernels take several times this, they are chains of dependent memory round trips in a single round
-    # of workgroups, which is why independent steps in flight fill the GPU.
-    tiny_inp = synth.make_inputs(synth.CONFIGS["tiny"])
-    tiny_inp.noise_m_patch = None
-    tiny = DeviceLayer(tiny_inp, B.FLAG_RESIDUAL, B.FLAG_RESIDUAL, device="cuda:0")
-    tiny.layer_forward()
-    tcfg = tiny.cfg
-    th = torch.empty((tcfg.b, tcfg.k_a, tcfg.l_a, tcfg.d), dtype=tiny.tdtype, device=tiny.device)
-    small = lambda: B.gather(tiny.smha, tiny.x, tiny.a_expert_idx, tiny.a_patch_idx, th)
-    for _ in range(10):
-        small()
-    floor_ms, floor_ahead = gpu_paced(small, 100)
-    roofline["dependent_launch_floor_us"] = round(floor_ms * 1e3, 2) if floor_ahead else None
-    del src, dst
-
-    # ---- CPU oracle on this box's host cores, on a bounded sample of the same workload
-    cpu = None
+    # ---- CPU oracle on this machine's host cores, on a bounded sample of the same workload; with it, the
+    # selection parity of the timed batch (indices bit-exact except on rows the oracle flags as near-ties)
+    cpu, selection = None, None
     if not args.no_cpu_baseline:
         import oracle
         nb = cfg.b
@@ -389,6 +489,23 @@ def main() -> int:
         cpu = {"value": round(passes * nb * cfg.l / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.get_threads(),
                "kind": "oracle", "sample": f"{nb} of {cfg.b} samples of the {cfg.name} workload, {passes} fp64 "
                                            f"pass(es) in {c1 - c0:.2f} s"}
+        if args.smha_mode == "both" and not uome_ds and not args.dynamic_capacity:
+            # routing of the whole timed batch by the oracle (routers only: a few GFLOP)
+            ra = oracle.route(inp.x, cfg.n_a, cfg.k_a, cfg.m, cfg.c, inp.a_w_expert, inp.a_w_b, inp.a_w_a,
+                              inp.noise_a_expert, inp.noise_a_patch)
+            dev.smha_forward()
+            torch.cuda.synchronize()
+            rm = oracle.route(to_host(dev.u), cfg.n_m, cfg.k_m, 1, 1, inp.m_w_expert, None, None, inp.noise_m_expert, None)
+
+            def rows(got, want, margin):
+                differ = np.any(np.asarray(got) != np.asarray(want), axis=-1)
+                flagged = (margin >= 0) & (margin <= oracle.NEAR_TIE_REL)
+                return {"rows": int(differ.size), "near_ties": int(flagged.sum()), "mismatching_rows": int(differ.sum()),
+                        "mismatching_rows_not_near_ties": int((differ & ~flagged).sum())}
+            selection = {"near_tie_rel": oracle.NEAR_TIE_REL,
+                         "smha_expert": rows(eidx, ra.expert_id, ra.expert_margin),
+                         "smha_patch": rows(pidx, ra.patch_id, ra.patch_margin),
+                         "uome_expert_on_device_u": rows(to_host(dev.m_expert_idx), rm.expert_id, rm.expert_margin)}
 
     line = {
         "metric": "UoE layer fwd tokens/sec (SMHA+UoME) at 1 GPU",
@@ -403,11 +520,19 @@ def main() -> int:
                             ("; UoME data selection, +patch gate" if uome_ds else "") +
                             (f"; SMHA c from Eq. 15-16 with {args.dynamic_capacity} experts per patch, read back every step"
                              if args.dynamic_capacity else ""),
-                   "seed": cfg.seed, "launch": launch},
-        "single_stream": {"ms_per_step": round(eager_ms, 5), "value": round(cfg.tokens / (eager_ms * 1e-3), 1)},
+                   "seed": cfg.seed, "launch": "eager, one stream, one call after the other"},
+        "timing": {"clock": "events on the launch stream around each region of `steps` calls, median region",
+                   "regions": len(region_ms), "ms_per_step_by_region": [round(v, 5) for v in region_ms],
+                   "host_wall_ms_per_step_by_region": [round(v, 5) for v in region_wall_ms]},
         "tflops": round(fl["total"] / (ms_per_step * 1e-3) / 1e12, 3),
+        "frac_of_bf16_mfma_peak": round(fl["total"] / (ms_per_step * 1e-3) / 1e12 / peak_tf, 4),
         "flops_per_step": fl["total"],
         "roofline": roofline,
+        "kernels": kernels,
+        "measured_ceilings": ceilings,
+        "expert_load": loads,
+        "selection_parity": selection,
+        "steps_in_flight": in_flight,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -173,6 +173,21 @@ int uoe_smha_forward_masked(const uoe_block_desc *blk, const void *x, const void
                             void *hip_stream);
 
 /*
+ * The steps of uoe_smha_forward_masked one at a time, for callers that time or inspect them
+ * (Eq. 28-30 + Eq. 32; Eq. 33-34; Eq. 35-36).  `steps` is a non-empty set of UOE_SMHA_STEP_* bits;
+ * the selected steps run in their natural order on the same workspace, and a step reads what the
+ * steps before it left there (q, k, v; the attention output), by this call or by an earlier one
+ * with the same descriptor, routing and ws.  `out` is only written by UOE_SMHA_STEP_OUT.  All bits
+ * set is uoe_smha_forward_masked.  Same arguments, limits and errors otherwise.
+ */
+enum { UOE_SMHA_STEP_QKV = 1u, UOE_SMHA_STEP_ATTENTION = 2u, UOE_SMHA_STEP_OUT = 4u };
+int uoe_smha_forward_steps(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
+                           const void *wv, const void *wo, const int32_t *expert_idx,
+                           const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
+                           const uint8_t *pad_mask, void *out, void *ws, size_t ws_bytes, uint32_t steps,
+                           void *hip_stream);
+
+/*
  * Union-of-MLP-Experts on given routing results (Eq. 37-40).  The second layer is linear.
  *   a_in [n,d,d_e]; a_out [n,d_e,d]; expert_idx [b,k]; expert_gate [b,n] or NULL
  * Expert-selection mode (patch_idx NULL; needs blk->c == blk->m and no UOE_FLAG_GATE_PATCH, with
@@ -372,6 +387,24 @@ int uoe_layer_backward_masked(const uoe_block_desc *smha, const uoe_smha_weights
                               const uoe_router_grads *dra, void *d_a_in, void *d_a_out,
                               const uoe_router_grads *drm, void *ws, size_t ws_bytes,
                               void *hip_stream);
+
+/*
+ * Measurement probes (not steps of the layer; Sec. IV-D measures run time, these give the scale to
+ * read such measurements against on this GPU): what the device delivers for a plain copy, a
+ * read-only stream and a register-resident bf16 MFMA loop.  A benchmark prices a kernel against the
+ * published peaks and reports these beside them; the copy also calibrates hardware byte counters
+ * on a transfer of known size.  All pointers are device pointers, 16-byte aligned; bytes % 16 == 0.
+ *   uoe_probe_copy   dst[0..bytes) = src[0..bytes)  (reads `bytes`, writes `bytes`; no overlap)
+ *   uoe_probe_read   reads src[0..bytes) and folds it into sink[0..4096) (uint32, device)
+ *   uoe_probe_mfma   512 workgroups of 4 waves, each wave `iters` rounds of 8 independent
+ *                    v_mfma_f32_32x32x16_bf16 on operand fragments read once from `operands`
+ *                    (6 KiB, device: zeros and random values clock differently); the accumulator
+ *                    sums go to sink[0..131072) (fp32, device); *flops (host, may be NULL) receives
+ *                    the FLOP count of the launch
+ */
+int uoe_probe_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+int uoe_probe_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
+int uoe_probe_mfma(const void *operands, int32_t iters, float *sink, double *flops, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,7 @@ FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
 EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_balance_loss", "uoe_gather",
            "uoe_smha_forward",
-           "uoe_smha_forward_masked",
+           "uoe_smha_forward_masked", "uoe_smha_forward_steps", "uoe_probe_copy", "uoe_probe_read", "uoe_probe_mfma",
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward", "uoe_layer_forward_masked",
            "uoe_uome_backward_workspace_bytes", "uoe_uome_backward",
            "uoe_smha_backward_workspace_bytes", "uoe_smha_backward",
@@ -84,6 +84,10 @@ def lib():
         L.uoe_gather.argtypes = [D, P, P, P, P, P]
         L.uoe_smha_forward.argtypes = [D] + [P] * 10 + [P, S, P]
         L.uoe_smha_forward_masked.argtypes = [D] + [P] * 11 + [P, S, P]
+        L.uoe_smha_forward_steps.argtypes = [D] + [P] * 11 + [P, S, ctypes.c_uint32, P]
+        L.uoe_probe_copy.argtypes = [P, P, S, P]
+        L.uoe_probe_read.argtypes = [P, S, P, P]
+        L.uoe_probe_mfma.argtypes = [P, ctypes.c_int32, P, ctypes.POINTER(ctypes.c_double), P]
         L.uoe_uome_forward.argtypes = [D] + [P] * 8 + [P, S, P]
         L.uoe_uome_backward_workspace_bytes.argtypes = [D]
         L.uoe_uome_backward_workspace_bytes.restype = S
@@ -115,7 +119,8 @@ def lib():
                                                P, S, P]
         for f in ("uoe_route", "uoe_route_capacity", "uoe_gather", "uoe_smha_forward", "uoe_smha_forward_masked", "uoe_uome_forward", "uoe_uome_up",
                   "uoe_uome_down", "uoe_layer_forward", "uoe_uome_backward", "uoe_smha_backward", "uoe_route_backward", "uoe_layer_backward",
-                  "uoe_layer_forward_masked", "uoe_layer_backward_masked", "uoe_balance_loss"):
+                  "uoe_layer_forward_masked", "uoe_layer_backward_masked", "uoe_balance_loss", "uoe_smha_forward_steps",
+                  "uoe_probe_copy", "uoe_probe_read", "uoe_probe_mfma"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -207,6 +212,34 @@ def smha_forward_masked(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_i
                                        _ptr(pad_mask), _ptr(out), _ptr(ws),
                                        _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     return _done(st, "uoe_smha_forward_masked", check)
+
+
+SMHA_STEP_QKV, SMHA_STEP_ATTENTION, SMHA_STEP_OUT = 1, 2, 4
+
+
+def smha_forward_steps(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, pad_mask, out,
+                       ws, steps, stream=None, check=True, ws_bytes=None) -> int:
+    st = lib().uoe_smha_forward_steps(_ref(blk), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+                                      _ptr(expert_idx), _ptr(expert_gate), _ptr(patch_idx), _ptr(patch_gate),
+                                      _ptr(pad_mask), _ptr(out), _ptr(ws),
+                                      _nbytes(ws) if ws_bytes is None else ws_bytes, int(steps), _stream(stream))
+    return _done(st, "uoe_smha_forward_steps", check)
+
+
+def probe_copy(src, dst, nbytes, stream=None, check=True) -> int:
+    return _done(lib().uoe_probe_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)), "uoe_probe_copy", check)
+
+
+def probe_read(src, nbytes, sink, stream=None, check=True) -> int:
+    return _done(lib().uoe_probe_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)), "uoe_probe_read", check)
+
+
+def probe_mfma(operands, iters, sink, stream=None, check=True) -> float:
+    """Returns the FLOP count of the launch."""
+    flops = ctypes.c_double(0.0)
+    _done(lib().uoe_probe_mfma(_ptr(operands), int(iters), _ptr(sink), ctypes.byref(flops), _stream(stream)),
+          "uoe_probe_mfma", check)
+    return float(flops.value)
 
 
 def uome_forward(blk, u, a_in, a_out, expert_idx, expert_gate, patch_idx, patch_gate, out, ws,

@@ -256,7 +256,8 @@ int do_route(const uoe_block_desc *blk, int m, int c, const void *x, const void 
 
 int do_smha(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk, const void *wv,
             const void *wo, const int32_t *expert_idx, const float *expert_gate, const int32_t *patch_idx,
-            const float *patch_gate, const uint8_t *pad_mask, void *out, void *ws, size_t ws_bytes, hipStream_t st)
+            const float *patch_gate, const uint8_t *pad_mask, void *out, void *ws, size_t ws_bytes, hipStream_t st,
+            uint32_t skip = 0)
 {
     if (!x || !wq || !wk || !wv || !wo || !expert_idx || !patch_idx || !out) return UOE_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(wo) || !aligned16(out))
@@ -274,7 +275,7 @@ int do_smha(const uoe_block_desc *blk, const void *x, const void *wq, const void
     a.out = out;
     a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.m = blk->m; a.c = blk->c;
     a.d_h = blk->width; a.flags = blk->flags;
-    a.rope_dim = blk->rope_dim; a.pad_mask = pad_mask;
+    a.rope_dim = blk->rope_dim; a.pad_mask = pad_mask; a.skip = skip;
     a.q = at(ws, w.q); a.kk = at(ws, w.k); a.v = at(ws, w.v); a.o = at(ws, w.o); a.o_lo = at(ws, w.o_lo);
     a.inv_cnt = reinterpret_cast<int32_t *>(at(ws, w.inv_cnt));
     a.inv_ent = reinterpret_cast<int32_t *>(at(ws, w.inv_ent));
@@ -437,6 +438,20 @@ int uoe_smha_forward_masked(const uoe_block_desc *blk, const void *x, const void
     if (rc != UOE_OK) return rc;
     return do_smha(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, pad_mask, out, ws,
                    ws_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int uoe_smha_forward_steps(const uoe_block_desc *blk, const void *x, const void *wq, const void *wk,
+                           const void *wv, const void *wo, const int32_t *expert_idx,
+                           const float *expert_gate, const int32_t *patch_idx, const float *patch_gate,
+                           const uint8_t *pad_mask, void *out, void *ws, size_t ws_bytes, uint32_t steps,
+                           void *hip_stream)
+{
+    const int rc = check_desc(blk, DESC_SMHA);
+    if (rc != UOE_OK) return rc;
+    const uint32_t all = UOE_SMHA_STEP_QKV | UOE_SMHA_STEP_ATTENTION | UOE_SMHA_STEP_OUT;
+    if (steps == 0 || (steps & ~all)) return UOE_ERR_INVALID_ARG;
+    return do_smha(blk, x, wq, wk, wv, wo, expert_idx, expert_gate, patch_idx, patch_gate, pad_mask, out, ws,
+                   ws_bytes, static_cast<hipStream_t>(hip_stream), all & ~steps);
 }
 
 int uoe_uome_forward(const uoe_block_desc *blk, const void *u, const void *a_in, const void *a_out,
@@ -813,6 +828,26 @@ int uoe_layer_backward_masked(const uoe_block_desc *smha, const uoe_smha_weights
                                 d_gate_a, d_pgate_a, d_x, dra->d_w_expert, dra->d_w_b, dra->d_w_a, stage, w.stage_bytes,
                                 hip_stream);
     return rc;
+}
+
+int uoe_probe_copy(const void *src, void *dst, size_t bytes, void *hip_stream)
+{
+    if (!src || !dst || src == dst || !aligned16(src) || !aligned16(dst) || (bytes & 15)) return UOE_ERR_INVALID_ARG;
+    return launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+int uoe_probe_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream)
+{
+    if (!src || !sink || !aligned16(src) || (bytes & 15)) return UOE_ERR_INVALID_ARG;
+    return launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
+}
+
+int uoe_probe_mfma(const void *operands, int32_t iters, float *sink, double *flops, void *hip_stream)
+{
+    if (!operands || !sink || !aligned16(operands) || iters < 1) return UOE_ERR_INVALID_ARG;
+    // blocks x 4 waves x iters x 8 MFMAs of 32x32x16 (2*32*32*16 FLOP each)
+    if (flops) *flops = (double)PROBE_MFMA_BLOCKS * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+    return launch_probe_mfma(operands, iters, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;
 }
 
 }  // extern "C"

@@ -217,6 +217,12 @@ int smha_backward_splits(int b, int n, int k, int c);
 int uome_backward_gate_chunks(int l, int d_e);
 int uome_backward_splits(int b, int l, int d, int n, int k, int d_e);
 
+// measurement probes (probe.hip)
+constexpr unsigned PROBE_READ_BLOCKS = 256 * 16, PROBE_MFMA_BLOCKS = 256 * 2;
+hipError_t launch_probe_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+hipError_t launch_probe_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t st);
+hipError_t launch_probe_mfma(const void *operands, int iters, float *sink, hipStream_t st);
+
 // host-side sizing shared by api.cpp and the launchers
 int route_tokens_per_chunk(int b, int l);
 int route_expert_mfma_tokens_per_chunk(int b, int l, int d, int n);
