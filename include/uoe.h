@@ -42,7 +42,8 @@ typedef enum {
     UOE_ERR_INVALID_ARG = 1, /* NULL where not allowed, bad sizes, misaligned pointer, aliasing   */
     UOE_ERR_UNSUPPORTED = 2, /* a valid request outside this build (see shape limits, flags)      */
     UOE_ERR_WORKSPACE = 3,   /* ws is NULL or ws_bytes is below uoe_workspace_bytes()             */
-    UOE_ERR_DEVICE = 4       /* a kernel launch was refused by the runtime                        */
+    UOE_ERR_DEVICE = 4,      /* a kernel launch was refused by the runtime                        */
+    UOE_ERR_SCRATCH_LIMIT = 5 /* uoe_route_static: the request needs more than its fixed scratch  */
 } uoe_status;
 
 enum { UOE_F32 = 0, UOE_BF16 = 1 }; /* storage dtype of activations, weights and outputs */
@@ -95,6 +96,28 @@ int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, co
               const void *w_a, const float *noise_expert, const float *noise_patch,
               int32_t *expert_idx, float *expert_gate, int32_t *patch_idx, float *patch_gate,
               void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * uoe_route for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, outputs, kernels
+ * and results as uoe_route, without ws / ws_bytes: the per-chunk partial sums of the routers live
+ * in a fixed array of UOE_ROUTE_STATIC_SCRATCH_BYTES in device memory that is part of the library
+ * image (one copy per GPU, held until the process ends; its address is looked up on the first
+ * call on each device).  The call allocates nothing, on the host or on the device.
+ *   - A descriptor whose partial sums need more than that (what uoe_workspace_bytes counts for
+ *     routing: about 4*(chunks*b*n*(m+1) + b*n*m) bytes with up to 512 chunks) is rejected with
+ *     UOE_ERR_SCRATCH_LIMIT and nothing is launched.  The five workload shapes need at most 4.3 MiB.
+ *   - The device of hip_stream must be the current device.
+ *   - All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ *     streams or threads) race and give wrong results; calls on one stream are safe back to back.
+ *     Every value the kernels read from the array was written earlier by the same call, so nothing
+ *     needs to be cleared between calls.
+ */
+enum { UOE_ROUTE_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024 };
+int uoe_route_static(const uoe_block_desc *blk, const void *x, const void *w_expert, const void *w_b,
+                     const void *w_a, const float *noise_expert, const float *noise_patch,
+                     int32_t *expert_idx, float *expert_gate, int32_t *patch_idx, float *patch_gate,
+                     void *hip_stream);
 
 /*
  * Dynamic capacity of the two-stage routing (Eq. 15-16) and the statistics of the balance loss

@@ -13,11 +13,12 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libuoe.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, 1, 2, 3, 4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_SCRATCH_LIMIT = 0, 1, 2, 3, 4, 5
+ROUTE_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024
 F32, BF16 = 0, 1
 FLAG_RESIDUAL, FLAG_GATE_EXPERT, FLAG_GATE_PATCH, FLAG_CAUSAL = 1, 2, 4, 8
 
-EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_capacity", "uoe_balance_loss", "uoe_gather",
+EXPORTS = ("uoe_workspace_bytes", "uoe_status_string", "uoe_route", "uoe_route_static", "uoe_route_capacity", "uoe_balance_loss", "uoe_gather",
            "uoe_smha_forward",
            "uoe_smha_forward_masked", "uoe_smha_forward_steps", "uoe_probe_copy", "uoe_probe_read", "uoe_probe_mfma",
            "uoe_uome_forward", "uoe_uome_up", "uoe_uome_down", "uoe_layer_forward", "uoe_layer_forward_masked",
@@ -79,6 +80,8 @@ def lib():
         L.uoe_status_string.argtypes = [ctypes.c_int]
         L.uoe_status_string.restype = ctypes.c_char_p
         L.uoe_route.argtypes = [D] + [P] * 10 + [P, S, P]
+        L.uoe_route_static.argtypes = [D] + [P] * 10 + [P]
+        L.uoe_route_static.restype = ctypes.c_int
         L.uoe_route_capacity.argtypes = [D, P, P, P, P, ctypes.c_int32, P, P, P, P, S, P]
         L.uoe_balance_loss.argtypes = [D, P, P, ctypes.c_float, P, P, P]
         L.uoe_gather.argtypes = [D, P, P, P, P, P]
@@ -176,6 +179,14 @@ def route(blk, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx, exp
                          _ptr(patch_gate), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
                          _stream(stream))
     return _done(st, "uoe_route", check)
+
+
+def route_static(blk, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx, expert_gate, patch_idx,
+                 patch_gate, stream=None, check=True) -> int:
+    st = lib().uoe_route_static(_ref(blk), _ptr(x), _ptr(w_expert), _ptr(w_b), _ptr(w_a), _ptr(noise_expert),
+                                _ptr(noise_patch), _ptr(expert_idx), _ptr(expert_gate), _ptr(patch_idx),
+                                _ptr(patch_gate), _stream(stream))
+    return _done(st, "uoe_route_static", check)
 
 
 def route_capacity(blk, x, w_b, w_a, noise_patch, patch_k, capacity, load_f, load_p, ws, stream=None, check=True,

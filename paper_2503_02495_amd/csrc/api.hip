@@ -2,8 +2,14 @@
 // Nothing here allocates or synchronises; every entry point validates, then enqueues.
 #include "../../include/uoe.h"
 #include "common.h"
+#include <mutex>
 
 using namespace uoe;
+
+// Scratch of uoe_route_static, the entry point that allocates nothing: a fixed array in device
+// memory, one copy per GPU the library runs on, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[UOE_ROUTE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -224,6 +230,24 @@ RoutingBuf routing_buf(const uoe_block_desc *d, int m, int c)
 
 inline char *at(void *ws, size_t off) { return static_cast<char *>(ws) + off; }
 
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[MAX_DEVICES] = {};
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return UOE_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return UOE_ERR_DEVICE;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return UOE_OK;
+}
+
 // validated routing launch; `m`/`c` are passed separately so a UoME block routes with m = c = 1
 int do_route(const uoe_block_desc *blk, int m, int c, const void *x, const void *w_expert, const void *w_b,
              const void *w_a, const float *noise_expert, const float *noise_patch, int32_t *expert_idx,
@@ -333,6 +357,7 @@ const char *uoe_status_string(int status)
         case UOE_ERR_UNSUPPORTED: return "valid request not supported by this build";
         case UOE_ERR_WORKSPACE: return "workspace missing or too small";
         case UOE_ERR_DEVICE: return "kernel launch failed";
+        case UOE_ERR_SCRATCH_LIMIT: return "request needs more than the fixed scratch of the entry point that allocates nothing";
         default: return "unknown status";
     }
 }
@@ -363,6 +388,23 @@ int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, co
     if (rc != UOE_OK) return rc;
     return do_route(blk, blk->m, blk->c, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx,
                     expert_gate, patch_idx, patch_gate, ws, ws_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int uoe_route_static(const uoe_block_desc *blk, const void *x, const void *w_expert, const void *w_b,
+                     const void *w_a, const float *noise_expert, const float *noise_patch,
+                     int32_t *expert_idx, float *expert_gate, int32_t *patch_idx, float *patch_gate,
+                     void *hip_stream)
+{
+    const int rc = check_desc(blk, DESC_ROUTE);
+    if (rc != UOE_OK) return rc;
+    const RouteWs w = route_ws(blk->b, blk->l, blk->d, blk->n, blk->m, blk->dtype == UOE_BF16);
+    if (w.total > (size_t)UOE_ROUTE_STATIC_SCRATCH_BYTES) return UOE_ERR_SCRATCH_LIMIT;
+    void *ws = nullptr;
+    const int sc = static_scratch(&ws);
+    if (sc != UOE_OK) return sc;
+    // every partial the kernels read from the scratch was written by this same call: nothing to clear
+    return do_route(blk, blk->m, blk->c, x, w_expert, w_b, w_a, noise_expert, noise_patch, expert_idx,
+                    expert_gate, patch_idx, patch_gate, ws, UOE_ROUTE_STATIC_SCRATCH_BYTES, static_cast<hipStream_t>(hip_stream));
 }
 
 int uoe_gather(const uoe_block_desc *blk, const void *x, const int32_t *expert_idx,
