@@ -22,6 +22,10 @@
  *   - Storage dtype (x, weights, outputs) is fp32 or bf16; all accumulation is
  *     fp32; gates are fp32; indices are int32.
  *   - Inputs must be finite; behaviour on NaN/Inf is unspecified.
+ *   - Environment: UOE_ROUTE_STREAM_MIN_BYTES (read at every routing call) moves the input size, in
+ *     bytes of x plus the expert router's weights, from which the routers run as one streaming
+ *     pass over x (default 100e6; 0 = whenever that kernel applies).  Results do not depend on it
+ *     beyond the summation order of the router logits.
  *   - Shape limits: d % 8 == 0, width % 8 == 0, l % m == 0, 1 <= n <= 32,
  *     1 <= k <= n, 1 <= c <= m, m <= 1024, width <= 128 for SMHA.  Valid but
  *     unsupported requests return UOE_ERR_UNSUPPORTED (also: UOE_FLAG_CAUSAL or rope_dim on a

@@ -46,7 +46,7 @@ int check_desc(const uoe_block_desc *d, DescKind kind)
 
 struct RouteWs {
     int tc, nchunks, tc_d, nchunks_d;
-    size_t zpart, gpart, gred, total;
+    size_t zpart, gpart, gred, t1, total;
 };
 RouteWs route_ws(int b, int l, int d, int n, int m, bool bf16)
 {
@@ -59,6 +59,7 @@ RouteWs route_ws(int b, int l, int d, int n, int m, bool bf16)
     w.zpart = off; off += up((size_t)w.nchunks * b * n * sizeof(float));
     w.gpart = off; off += up((size_t)w.nchunks_d * b * n * m * sizeof(float));
     w.gred = off;  off += up((size_t)b * n * m * sizeof(float));
+    w.t1 = off;    off += route_stream_plan(b, l, d, n, bf16, true).ok ? up((size_t)b * l * n * sizeof(float)) : 0;
     w.total = off;
     return w;
 }
@@ -273,6 +274,7 @@ int do_route(const uoe_block_desc *blk, int m, int c, const void *x, const void 
     a.zpart = reinterpret_cast<float *>(at(ws, w.zpart));
     a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
     a.gred = reinterpret_cast<float *>(at(ws, w.gred));
+    a.t1 = reinterpret_cast<float *>(at(ws, w.t1));
     a.expert_idx = expert_idx; a.patch_idx = patch_idx;
     a.expert_gate = expert_gate; a.patch_gate = patch_gate;
     return launch_route(a, blk->dtype == UOE_BF16, st) == hipSuccess ? UOE_OK : UOE_ERR_DEVICE;

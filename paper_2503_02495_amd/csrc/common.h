@@ -79,6 +79,7 @@ struct RouteArgs {
     int tc_d, nchunks_d;                      // data router: the same
     float *zpart, *gpart;                     // [nchunks, b, n], [nchunks_d, b, n*m]
     float *gred;                              // [b, n*m]
+    float *t1;                                // [b, l, n]: per-token expert scores x W_B of the one-pass kernel
     int32_t *expert_idx, *patch_idx;          // outputs (any may be NULL)
     float *expert_gate, *patch_gate;
     // dynamic capacity (Eq. 15-16) and balance statistics (Eq. 43-44): capacity NULL = not asked for
@@ -227,5 +228,19 @@ hipError_t launch_probe_mfma(const void *operands, int iters, float *sink, hipSt
 int route_tokens_per_chunk(int b, int l);
 int route_expert_mfma_tokens_per_chunk(int b, int l, int d, int n);
 int route_data_tokens_per_chunk(int b, int l, int d, int n, bool bf16);
+// streaming router kernel: applicability and launch shape (host side)
+constexpr int ROUTE_STREAM_CHUNKS = 256;      // one workgroup per compute unit
+struct RouteStreamPlan {
+    bool ok;             // the kernel applies to this shape
+    int rt, ct, rb;      // 16-sample tiles per workgroup, 16-expert tiles, bytes per row per stage
+    int tpc, nchunks;    // tokens per chunk, chunks
+    int ipw;             // load instructions per wave per stage
+    size_t lds;          // dynamic LDS bytes
+};
+RouteStreamPlan route_stream_plan(int b, int l, int d, int n, bool bf16, bool has_d);
+struct RouteFoldPlan {
+    int tr, ranges;      // tokens per range, ranges per sample
+};
+RouteFoldPlan route_fold_plan(int b, int l);
 
 }  // namespace uoe

@@ -147,6 +147,29 @@ def test_route_parity(name):
     np.testing.assert_allclose(to_host(dev.m_expert_gate), refm.expert_gate, rtol=GATE_RTOL[cfg.dtype], atol=1e-30)
 
 
+STREAM_NAMES = ["bf16_noise", "bf16_dh128", "lm", "longrange", "vit", "large", "stream_n24_b40", "stream_b70_m20"]
+STREAM_CONFIGS = {
+    # two expert tiles, three 16-sample tiles (half-KiB stage rows), chunks of one token, m % 8 != 0
+    "stream_n24_b40": small(b=40, l=70, d=128, n_a=24, d_h=32, m=10, c=3, k_a=5, n_m=20, d_e=32, k_m=3, dtype=synth.BF16),
+    # 64 + 6 samples: two workgroup rows, the second one almost empty; ragged last chunk (l = 300: 2 tokens per chunk)
+    "stream_b70_m20": small(b=70, l=300, d=256, n_a=6, d_h=32, m=20, c=4, k_a=2, n_m=4, d_e=32, k_m=2, dtype=synth.BF16,
+                            router_noise=True),
+}
+
+
+@pytest.mark.parametrize("name", STREAM_NAMES)
+def test_route_parity_streaming_kernel(name, monkeypatch):
+    """The one-pass streaming routers (route_stream + route_fold_mfma), which the size rule reserves for
+    inputs of 100 MB and more, forced on for every shape they apply to (bf16, d % 128 == 0)."""
+    monkeypatch.setenv("UOE_ROUTE_STREAM_MIN_BYTES", "0")
+    if name in STREAM_CONFIGS:
+        EDGE_CONFIGS[name] = STREAM_CONFIGS[name]
+    try:
+        test_route_parity(name)
+    finally:
+        EDGE_CONFIGS.pop(name, None) if name in STREAM_CONFIGS else None
+
+
 def test_route_degenerate_modes_and_ties():
     """No routers: everything selected, gates 1.  Exact ties (x = 0): lowest indices win."""
     cfg = small(b=2, l=32, d=16, n_a=4, d_h=8, m=4, c=4, k_a=4, n_m=4, d_e=8, k_m=4)
