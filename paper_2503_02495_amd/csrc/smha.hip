@@ -179,31 +179,60 @@ template <typename T> static hipError_t launch_attention_generic(const SmhaArgs 
 }
 
 // ---------------------------------------------------------------------------------------------
-// MFMA attention (bf16, d_h in {32, 64, 128}).  One wave owns 32 query rows of one unit and walks
-// the unit's keys in tiles of 64, online softmax in fp32 (base 2: q arrives pre-scaled by
-// log2(e)/sqrt(d_h)).  The scores are computed TRANSPOSED, S^T = K Q^T, so that an accumulator
-// lane holds one query column: the row max / row sum of the softmax are then in-lane reductions
-// plus one exchange with the partner lane (lane ^ 32), and the probabilities, converted to bf16
+// MFMA attention (bf16, d_h in {32, 64, 128}), Eq. 33-34.  One wave owns 32 query rows of one unit and
+// walks key tiles of 64, online softmax in fp32 (base 2: q arrives pre-scaled by log2(e)/sqrt(d_h)).
+//
+// Layout.  The scores are computed TRANSPOSED, S^T = K Q^T (v_mfma_f32_32x32x16_bf16), so that an
+// accumulator lane holds one query column: the row max / row sum of the softmax are in-lane
+// reductions plus one exchange with the partner lane (lane ^ 32), and the probabilities, converted
 // in place, already ARE the B operand of the second product O^T = V^T P^T (the k-slots of an MFMA
 // operand may hold any permutation of K as long as both operands agree, so V^T is read with the
 // accumulator's key order: keys 16s+4h..+4 and 16s+8+4h..+4 for k-step s, half-wave h).
-// K and V tiles [key][d_h] are staged through double-buffered LDS as plain 16-byte row copies;
-// the V^T fragments come out of the [key][d_h] tile through the transposing LDS read.
-template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
+//
+// What the kernel is bound by is the vector ALU work of the softmax, not the matrix pipe, so that work
+// is kept to a max, an exp2, an add and half a convert per score:
+//  * P V runs in fp16 (v_mfma_f32_32x32x16_f16): probabilities carry 11 significant bits, enough for
+//    the 2e-2 bound with one MFMA pass (a bf16 P needs a (hi, lo) pair: twice the MFMAs plus the split
+//    arithmetic).  V is converted bf16 -> fp16 while its tile is staged into LDS (exact for
+//    |v| in [6.1e-5, 65504]; larger magnitudes saturate, smaller ones lose low bits).
+//  * The running maximum is subtracted by the matrix pipe: the score accumulators are initialised
+//    with -m instead of 0.  As long as no score of a tile exceeds the running maximum by more than
+//    2^8 the tile needs no rescaling at all (p = exp2(s - m) <= 256 fits fp16 and fp32 sums); only
+//    when one does (always on the first tile) the maximum moves and O and the row sum are rescaled.
+//  * KSPLIT waves share a query block and take key tiles KSPLIT apart, so that a compute unit holds
+//    two waves per SIMD also when the grid has only one wave of queries per SIMD: one wave's softmax
+//    then runs under another's MFMAs.  Their (max, sum, O) triples are merged through LDS at the end.
+// K and V tiles [key][d_h] are staged through double-buffered LDS as 16-byte row copies; the V^T
+// fragments come out of the [key][d_h] tile through the transposing LDS read.
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ uint32_t pack2_f16(float a, float b)
 {
-    constexpr int BKV = 64, KP = DH + 8, VP = 2 * b_pitch_dwords(DH), NT = NW * 64;
-    constexpr int K_CHUNKS = BKV * DH / 8, V_CHUNKS = DH * BKV / 8;
-    constexpr int K_PER_T = (K_CHUNKS + NT - 1) / NT, V_PER_T = (V_CHUNKS + NT - 1) / NT;
-    __shared__ __align__(16) uint16_t Ks[2][BKV][KP];
-    __shared__ __align__(16) uint16_t Vs[2][BKV][VP];  // [key][d_h], read with the transposing LDS read
-    __shared__ unsigned char Km[2][BKV];                // key admissible under the padding mask
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));  // toward zero: never rounds up to inf
+}
+
+template <int DH, int NQ, int KSPLIT>
+__global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArgs a)
+{
+    constexpr int BKV = 64, KP = DH + 8, VP = 2 * b_pitch_dwords(DH), NTH = NQ * 64;  // NTH: threads that stage one split's tiles
+    constexpr int CHUNKS = BKV * DH / 8, PER_T = (CHUNKS + NTH - 1) / NTH;
+    constexpr float TAU = 8.0f;
+    constexpr int PD = 3;   // register sets of the K/V prefetch
+    constexpr int K_BYTES = 2 * BKV * KP * 2, V_BYTES = 2 * BKV * VP * 2, SPLIT_BYTES = K_BYTES + V_BYTES + 2 * BKV;
+    constexpr int MERGE_BYTES = (KSPLIT - 1) * NQ * 64 * (DH / 2 + 2) * 4;
+    constexpr int LDS_BYTES = KSPLIT * SPLIT_BYTES > MERGE_BYTES ? KSPLIT * SPLIT_BYTES : MERGE_BYTES;
+    __shared__ __align__(16) unsigned char lds_raw[LDS_BYTES];
 
     const int g = blockIdx.y;
     const int l_p = a.l / a.m, l_a = a.c * l_p;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int split = wave / NQ, qg = wave - split * NQ, stid = tid - split * NTH;  // key split, query group, thread within the split
     const int lr = lane & 31, lh = lane >> 5;
-    const int qrow = blockIdx.x * (32 * NW) + wave * 32 + lr;
+    const int qrow = blockIdx.x * (32 * NQ) + qg * 32 + lr;
+    unsigned char *sbase = lds_raw + (size_t)split * SPLIT_BYTES;
+    uint16_t(*Ks)[BKV][KP] = reinterpret_cast<uint16_t(*)[BKV][KP]>(sbase);
+    uint16_t(*Vs)[BKV][VP] = reinterpret_cast<uint16_t(*)[BKV][VP]>(sbase + K_BYTES);   // fp16, [key][d_h]
+    unsigned char(*Km)[BKV] = reinterpret_cast<unsigned char(*)[BKV]>(sbase + K_BYTES + V_BYTES);
     const bf16_t *Q = static_cast<const bf16_t *>(a.q) + (size_t)g * l_a * DH;
     const bf16_t *Kg = static_cast<const bf16_t *>(a.kk) + (size_t)g * l_a * DH;
     const bf16_t *Vg = static_cast<const bf16_t *>(a.v) + (size_t)g * l_a * DH;
@@ -211,7 +240,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
     // gate weight of this row (Eq. 36 with the optional gate flags): two dependent lookups, started
     // here so that they complete under the key loop instead of in front of the output stores
     float w = 1.0f;
-    {
+    if (split == 0) {
         const int bb = g / a.k, i = clampi(a.expert_idx[g], a.n);
         if ((a.flags & F_GATE_EXPERT) && a.expert_gate) w *= a.expert_gate[(size_t)bb * a.n + i];
         if ((a.flags & F_GATE_PATCH) && a.patch_gate) {
@@ -233,131 +262,198 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
     for (int t = 0; t < DH / 32; ++t)
 #pragma unroll
         for (int q = 0; q < 16; ++q) oacc[t][q] = 0.f;
-    float mrun = -INFINITY, lsum = 0.f;
+    float mrun = -INFINITY, lsum = 0.f;   // running maximum of this query (both half-waves agree), this lane's part of the row sum
 
     const bool causal = (a.flags & F_CAUSAL) != 0, masked = a.pad_mask != nullptr;
-    uint4 kreg[K_PER_T], vreg[V_PER_T];
-    unsigned char kmreg = 1;
-    auto load_global = [&](int key0) {
-        if (masked && tid < BKV) kmreg = (key0 + tid < l_a) && key_is_token(a, g, min(key0 + tid, l_a - 1), l_p);
+    // K/V tiles travel global -> registers -> LDS.  A tile's loads are issued PD - 1 iterations before the
+    // tile is used (PD register sets): one iteration of a key split is shorter than a memory round trip.
+    struct Staged {   // plain words, moved one by one: whole-vector copies of a local array would be a memcpy, which
+        uint32_t k[PER_T][4], v[PER_T][4];   // keeps the array out of the register file
+        unsigned char km;
+    };
+    Staged set0, set1, set2;   // separate objects: each one small enough to live in registers
+    // Loads are issued for every iteration, also past the last tile (the last tile again, never stored),
+    // with clamped addresses instead of guards: straight-line code whose outstanding loads the
+    // compiler can count, so a wait for one tile leaves the younger tiles in flight.
+    static_assert(CHUNKS % NTH == 0, "every staging thread moves the same number of pieces");
+    auto load_global = [&](Staged &sr, int tile) {
+        const int key0 = min(tile, (l_a - 1) / BKV) * BKV;
+        if (masked && stid < BKV) sr.km = (key0 + stid < l_a) && key_is_token(a, g, min(key0 + stid, l_a - 1), l_p);
 #pragma unroll
-        for (int i = 0; i < K_PER_T; ++i) {
-            const int c = tid + i * NT;
+        for (int i = 0; i < PER_T; ++i) {
+            const int c = stid + i * NTH;
             const int row = c / (DH / 8), kc = c % (DH / 8);
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (c < K_CHUNKS && key0 + row < l_a)
-                v = *reinterpret_cast<const uint4 *>(Kg + (size_t)(key0 + row) * DH + kc * 8);
-            kreg[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < V_PER_T; ++i) {
-            const int c = tid + i * NT;
-            const int row = c / (DH / 8), kc = c % (DH / 8);
-            uint4 v = make_uint4(0, 0, 0, 0);  // keys past l_a are zero rows: their probability is 0 as well
-            if (c < V_CHUNKS && key0 + row < l_a)
-                v = *reinterpret_cast<const uint4 *>(Vg + (size_t)(key0 + row) * DH + kc * 8);
-            vreg[i] = v;
+            // keys past l_a repeat the last key: their scores are masked to -inf below, so they get
+            // probability 0 against finite V rows (zeroing the registers here would make every load wait)
+            const size_t at = (size_t)min(key0 + row, l_a - 1) * DH + kc * 8;
+            const uint4 kq = *reinterpret_cast<const uint4 *>(Kg + at), vq = *reinterpret_cast<const uint4 *>(Vg + at);
+            sr.k[i][0] = kq.x; sr.k[i][1] = kq.y; sr.k[i][2] = kq.z; sr.k[i][3] = kq.w;
+            sr.v[i][0] = vq.x; sr.v[i][1] = vq.y; sr.v[i][2] = vq.z; sr.v[i][3] = vq.w;
         }
     };
-    auto store_lds = [&](int buf) {
-        if (masked && tid < BKV) Km[buf][tid] = kmreg;
+    auto store_lds = [&](const Staged &sr, int buf) {
+        if (masked && stid < BKV) Km[buf][stid] = sr.km;
 #pragma unroll
-        for (int i = 0; i < K_PER_T; ++i) {
-            const int c = tid + i * NT;
-            if (c < K_CHUNKS) *reinterpret_cast<uint4 *>(&Ks[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = kreg[i];
-        }
+        for (int i = 0; i < PER_T; ++i) {
+            const int c = stid + i * NTH;
+            {
+                *reinterpret_cast<uint4 *>(&Ks[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = make_uint4(sr.k[i][0], sr.k[i][1], sr.k[i][2], sr.k[i][3]);
+                // bf16 -> fp16: widen to fp32 (a shift), then narrow; exact whenever fp16 can hold the value
+                const uint32_t u[4] = {sr.v[i][0], sr.v[i][1], sr.v[i][2], sr.v[i][3]};
+                uint32_t h[4];
 #pragma unroll
-        for (int i = 0; i < V_PER_T; ++i) {
-            const int c = tid + i * NT;
-            if (c < V_CHUNKS) *reinterpret_cast<uint4 *>(&Vs[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = vreg[i];
+                for (int e = 0; e < 4; ++e) h[e] = pack2_f16(__uint_as_float(u[e] << 16), __uint_as_float(u[e] & 0xFFFF0000u));
+                *reinterpret_cast<uint4 *>(&Vs[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = make_uint4(h[0], h[1], h[2], h[3]);
+            }
         }
     };
 
     // under the causal mask no query of this workgroup sees keys past the workgroup's last row
-    const int key_end = causal ? min(l_a, (int)(blockIdx.x + 1) * 32 * NW) : l_a;
+    const int key_end = causal ? min(l_a, (int)(blockIdx.x + 1) * 32 * NQ) : l_a;
     const int nkt = (key_end + BKV - 1) / BKV;
-    load_global(0);
-    store_lds(0);
+    const int nit = (nkt + KSPLIT - 1) / KSPLIT;   // iterations: split s takes tiles s, s + KSPLIT, ...
+    auto tile_of = [&](int it) { return it * KSPLIT + split; };   // this split's it-th tile (exists if < nkt)
+    set0.km = set1.km = set2.km = 1;
+    load_global(set0, tile_of(0));
+    load_global(set1, tile_of(1));
+    store_lds(set0, 0);
     __syncthreads();
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nkt) load_global((kt + 1) * BKV);
-
-        // S^T tile: [64 keys x 32 queries] as two 32x32 accumulators
-        f32x16_t sacc[2];
+    // one iteration; J = it % PD picks the register sets at compile time (arrays indexed by a run-time
+    // value would leave the register file)
+    auto iteration = [&](auto jc, int it) {
+        constexpr int J = decltype(jc)::value;
+        const int kt = tile_of(it), buf = it & 1;
+        Staged &fill = J == 0 ? set2 : (J == 1 ? set0 : set1), &drain = J == 0 ? set1 : (J == 1 ? set2 : set0);
+        load_global(fill, tile_of(it + PD - 1));
+        if (kt < nkt) {
+            // S^T tile: [64 keys x 32 queries] as two 32x32 accumulators, started at -m
+            const float moff = mrun == -INFINITY ? 0.f : mrun;
+            f32x16_t sacc[2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) sacc[t][q] = 0.f;
+                for (int q = 0; q < 16; ++q) sacc[t][q] = -moff;
 #pragma unroll
-        for (int ks = 0; ks < DH / 16; ++ks)
+            for (int ks = 0; ks < DH / 16; ++ks)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(&Ks[buf][t * 32 + lr][ks * 16 + lh * 8]);
-                sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
+                for (int t = 0; t < 2; ++t) {
+                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(&Ks[buf][t * 32 + lr][ks * 16 + lh * 8]);
+                    sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
+                }
+            // accumulator register q of tile t is key kt*64 + t*32 + (q/4)*8 + lh*4 + q%4.  Masks: a wave-uniform
+            // test whether the tile can hold an inadmissible key for any query of the wave, then straight-line
+            // selects (accumulators must not cross divergent branches).
+            const int qrow_first = blockIdx.x * (32 * NQ) + qg * 32;
+            if ((kt + 1) * BKV > l_a || masked || (causal && (kt + 1) * BKV > qrow_first + 1)) {
+                uint32_t kmw[2][4];   // the padding flags of this lane's keys, four consecutive keys per word
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq)
+                        kmw[t][gq] = masked ? *reinterpret_cast<const uint32_t *>(&Km[buf][t * 32 + gq * 8 + lh * 4]) : 0x01010101u;
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const int key = kt * BKV + t * 32 + (q >> 2) * 8 + lh * 4 + (q & 3);
+                        const bool ok = key < l_a && (!causal || key <= qrow) && ((kmw[t][q >> 2] >> ((q & 3) * 8)) & 0xFFu) != 0;
+                        sacc[t][q] = ok ? sacc[t][q] : -INFINITY;
+                    }
             }
-        // accumulator register q of tile t is key kt*64 + t*32 + (q/4)*8 + lh*4 + q%4
-        if ((kt + 1) * BKV > l_a || masked || (causal && (kt + 1) * BKV > qrow)) {
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, sacc[t][q]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));   // largest score of the tile, relative to the running maximum
+            // the maximum moves only when a score exceeds it by more than 2^TAU, or when there is none yet
+            const bool move = tmax > TAU || (mrun == -INFINITY && tmax > -INFINITY);
+            if (__builtin_amdgcn_ballot_w64(move) != 0) {   // wave-uniform: rare after the first tile
+                if (move) {
+                    const float corr = mrun == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(-tmax);
+                    mrun = moff + tmax;
+                    lsum *= corr;
+#pragma unroll
+                    for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) oacc[t][q] *= corr;
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) sacc[t][q] -= tmax;
+                }
+            }
+            float psum = 0.f;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
-                    const int kl = t * 32 + (q >> 2) * 8 + lh * 4 + (q & 3), key = kt * BKV + kl;
-                    if (key >= l_a || (causal && key > qrow) || (masked && !Km[buf][kl])) sacc[t][q] = -INFINITY;
+                    const float pv = __builtin_amdgcn_exp2f(sacc[t][q]);   // exp2(-inf) = 0 for masked keys
+                    sacc[t][q] = pv;
+                    psum += pv;
                 }
-        }
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, sacc[t][q]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float mnew = fmaxf(mrun, tmax);
-        const float msafe = mnew == -INFINITY ? 0.f : mnew;      // every key so far masked: all p = 0
-        const float corr = __builtin_amdgcn_exp2f(mrun - msafe);  // 0 on the first tile
-        mrun = mnew;
-        float psum = 0.f;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const float pv = __builtin_amdgcn_exp2f(sacc[t][q] - msafe);
-                sacc[t][q] = pv;
-                psum += pv;
-            }
-        lsum = lsum * corr + psum;
-#pragma unroll
-        for (int t = 0; t < DH / 32; ++t)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) oacc[t][q] *= corr;
+            lsum += psum;
 
-        // O^T += V^T P^T over the 64 keys of the tile: four k-steps of 16 keys
+            // O^T += V^T P^T over the 64 keys of the tile: four k-steps of 16 keys
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-            const int t = s4 >> 1, r0 = (s4 & 1) * 8;
-            // probabilities as a (hi, lo) bf16 pair: P V = P_hi V + P_lo V keeps ~16 bits of P
-            uint32_t hi[4], lo[4];  // two values per word
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const int t = s4 >> 1, r0 = (s4 & 1) * 8;
+                uint32_t ph[4];  // two probabilities per word, fp16
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float p0 = sacc[t][r0 + 2 * e], p1 = sacc[t][r0 + 2 * e + 1];
-                hi[e] = pack2_bf16(p0, p1);
-                lo[e] = pack2_bf16(p0 - __uint_as_float(hi[e] << 16), p1 - __uint_as_float(hi[e] & 0xFFFF0000u));
-            }
-            const bf16x8_t pf_hi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
-            const bf16x8_t pf_lo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+                for (int e = 0; e < 4; ++e) ph[e] = pack2_f16(sacc[t][r0 + 2 * e], sacc[t][r0 + 2 * e + 1]);
+                const f16x8_t pf = __builtin_bit_cast(f16x8_t, make_uint4(ph[0], ph[1], ph[2], ph[3]));
 #pragma unroll
-            for (int td = 0; td < DH / 32; ++td) {
-                // V^T fragment for head-dim column td*32 + lr: keys 16*s4 + 4*lh + 0..3, then + 8
-                const uint16_t *vsrc = &Vs[buf][s4 * 16 + lh * 4 + ((lane & 15) >> 2)][td * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4];
-                const uint2 v0 = lds_read_tr4(vsrc);
-                const uint2 v1 = lds_read_tr4(vsrc + 8 * VP);
-                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, make_uint4(v0.x, v0.y, v1.x, v1.y));
-                oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_hi, oacc[td], 0, 0, 0);
-                oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, oacc[td], 0, 0, 0);
+                for (int td = 0; td < DH / 32; ++td) {
+                    // V^T fragment for head-dim column td*32 + lr: keys 16*s4 + 4*lh + 0..3, then + 8
+                    const uint16_t *vsrc = &Vs[buf][s4 * 16 + lh * 4 + ((lane & 15) >> 2)][td * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4];
+                    const uint2 v0 = lds_read_tr4(vsrc);
+                    const uint2 v1 = lds_read_tr4(vsrc + 8 * VP);
+                    const f16x8_t vf = __builtin_bit_cast(f16x8_t, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                    oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, oacc[td], 0, 0, 0);
+                }
             }
         }
-        if (kt + 1 < nkt) store_lds(buf ^ 1);
+        if (tile_of(it + 1) < nkt) store_lds(drain, buf ^ 1);
         __syncthreads();
+    };
+    static_assert(PD == 3, "the loop below names the register sets");
+    for (int it0 = 0; it0 < nit; it0 += PD) {   // nit is uniform over the workgroup
+        iteration(std::integral_constant<int, 0>{}, it0);
+        if (it0 + 1 < nit) iteration(std::integral_constant<int, 1>{}, it0 + 1);
+        if (it0 + 2 < nit) iteration(std::integral_constant<int, 2>{}, it0 + 2);
+    }
+
+    // merge the key splits: splits 1.. park (max, row-sum part, O^T) in LDS (the tile buffers are free:
+    // the loop ended on a barrier), split 0 folds them in, in split order
+    if constexpr (KSPLIT > 1) {
+        float *mg = reinterpret_cast<float *>(lds_raw);
+        constexpr int SLOT = DH / 2 + 2;   // floats per lane
+        if (split > 0) {
+            float *dst = mg + ((size_t)((split - 1) * NQ + qg) * 64 + lane) * SLOT;
+            dst[0] = mrun;
+            dst[1] = lsum;
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) dst[2 + t * 16 + q] = oacc[t][q];
+        }
+        __syncthreads();
+        if (split > 0) return;
+#pragma unroll
+        for (int s = 1; s < KSPLIT; ++s) {
+            const float *src = mg + ((size_t)((s - 1) * NQ + qg) * 64 + lane) * SLOT;
+            const float m1 = src[0], l1 = src[1];
+            const float mf = fmaxf(mrun, m1);
+            // a side that has seen no admissible key (max = -inf) contributes nothing
+            const float c0 = mrun == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun - mf);
+            const float c1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - mf);
+            lsum = lsum * c0 + l1 * c1;
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) oacc[t][q] = oacc[t][q] * c0 + src[2 + t * 16 + q] * c1;
+            mrun = mf;
+        }
     }
 
     if (qrow >= l_a) return;
@@ -384,17 +480,39 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(SmhaArgs a)
         }
 }
 
+// Launch shape: NQ waves of 32 queries per workgroup (more share K/V tiles, fewer give more workgroups:
+// at least one workgroup per compute unit if possible), KSPLIT key splits so that the grid holds two
+// waves per SIMD (2048 waves) where the key tiles allow it.
+template <int DH, int NQ, int KSPLIT> static void launch_attention_shape(const SmhaArgs &a, hipStream_t st)
+{
+    const int l_a = a.c * (a.l / a.m), units = a.b * a.k;
+    hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT>), dim3((l_a + 32 * NQ - 1) / (32 * NQ), units), dim3(NQ * KSPLIT * 64), 0,
+                       st, a);
+}
+
 template <int DH> static hipError_t launch_attention_mfma_dh(const SmhaArgs &a, hipStream_t st)
 {
     const int l_a = a.c * (a.l / a.m), units = a.b * a.k;
-    // more waves per workgroup share K/V tiles; fewer give more workgroups: keep >= 512 if possible
-    if ((long)((l_a + 127) / 128) * units >= 128) {
-        hipLaunchKernelGGL((attention_mfma_kernel<DH, 4>), dim3((l_a + 127) / 128, units), dim3(256), 0, st, a);
-    } else if ((long)((l_a + 63) / 64) * units >= 64) {
-        hipLaunchKernelGGL((attention_mfma_kernel<DH, 2>), dim3((l_a + 63) / 64, units), dim3(128), 0, st, a);
+    const long waves = (long)units * ((l_a + 31) / 32);
+    const int nkt = (l_a + 63) / 64;
+    int ks = 1;
+    while (ks < 4 && waves * ks < 2048 && 2 * ks <= nkt) ks *= 2;
+    if (DH > 32 && ks > 2) ks = 2;     // LDS: four splits fit a compute unit only with d_h = 32 tiles
+    int nq = 4;
+    while (nq > 1 && ((l_a + 32 * nq - 1) / (32 * nq)) * (long)units < 256) nq >>= 1;
+    if (nq == 4 && ks == 4) ks = 2;    // at most 8 waves per workgroup
+#define UOE_ATT(NQ, KS) launch_attention_shape<DH, NQ, KS>(a, st)
+    if (nq == 4) { if (ks == 1) UOE_ATT(4, 1); else UOE_ATT(4, 2); }
+    else if (nq == 2) {
+        if (ks == 1) UOE_ATT(2, 1);
+        else if (ks == 2) UOE_ATT(2, 2);
+        else if constexpr (DH == 32) UOE_ATT(2, 4);
     } else {
-        hipLaunchKernelGGL((attention_mfma_kernel<DH, 1>), dim3((l_a + 31) / 32, units), dim3(64), 0, st, a);
+        if (ks == 1) UOE_ATT(1, 1);
+        else if (ks == 2) UOE_ATT(1, 2);
+        else if constexpr (DH == 32) UOE_ATT(1, 4);
     }
+#undef UOE_ATT
     return hipGetLastError();
 }
 
