@@ -225,7 +225,7 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
 
     const int g = blockIdx.y;
     const int l_p = a.l / a.m, l_a = a.c * l_p;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile tests stay scalar
     const int split = wave / NQ, qg = wave - split * NQ, stid = tid - split * NTH;  // key split, query group, thread within the split
     const int lr = lane & 31, lh = lane >> 5;
     const int qrow = blockIdx.x * (32 * NQ) + qg * 32 + lr;
@@ -265,6 +265,7 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
     float mrun = -INFINITY, lsum = 0.f;   // running maximum of this query (both half-waves agree), this lane's part of the row sum
 
     const bool causal = (a.flags & F_CAUSAL) != 0, masked = a.pad_mask != nullptr;
+    const int nkt_all = (l_a + BKV - 1) / BKV;
     // K/V tiles travel global -> registers -> LDS.  A tile's loads are issued PD - 1 iterations before the
     // tile is used (PD register sets): one iteration of a key split is shorter than a memory round trip.
     struct Staged {   // plain words, moved one by one: whole-vector copies of a local array would be a memcpy, which
@@ -276,16 +277,25 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
     // with clamped addresses instead of guards: straight-line code whose outstanding loads the
     // compiler can count, so a wait for one tile leaves the younger tiles in flight.
     static_assert(CHUNKS % NTH == 0, "every staging thread moves the same number of pieces");
+    // Element offset of piece i in tile t: ((t * BKV + row_i) * DH + kc_i * 8), clamped to the same piece of
+    // the last key (keys past l_a repeat the last key: their scores are masked to -inf below, so they get
+    // probability 0 against finite V rows; zeroing the registers instead would make every load wait).
+    uint32_t piece[PER_T], piece_last[PER_T];
+#pragma unroll
+    for (int i = 0; i < PER_T; ++i) {
+        const int c = stid + i * NTH;
+        piece[i] = (uint32_t)(c / (DH / 8)) * DH + (c % (DH / 8)) * 8;
+        piece_last[i] = (uint32_t)(l_a - 1) * DH + (c % (DH / 8)) * 8;
+    }
     auto load_global = [&](Staged &sr, int tile) {
-        const int key0 = min(tile, (l_a - 1) / BKV) * BKV;
-        if (masked && stid < BKV) sr.km = (key0 + stid < l_a) && key_is_token(a, g, min(key0 + stid, l_a - 1), l_p);
+        if (masked && stid < BKV) {
+            const int key = tile * BKV + stid;
+            sr.km = key < l_a && key_is_token(a, g, min(key, l_a - 1), l_p);
+        }
+        const uint32_t t0 = (uint32_t)min(tile, nkt_all) * (BKV * DH);   // a tile past the end: clamped below, never stored
 #pragma unroll
         for (int i = 0; i < PER_T; ++i) {
-            const int c = stid + i * NTH;
-            const int row = c / (DH / 8), kc = c % (DH / 8);
-            // keys past l_a repeat the last key: their scores are masked to -inf below, so they get
-            // probability 0 against finite V rows (zeroing the registers here would make every load wait)
-            const size_t at = (size_t)min(key0 + row, l_a - 1) * DH + kc * 8;
+            const uint32_t at = min(t0 + piece[i], piece_last[i]);
             const uint4 kq = *reinterpret_cast<const uint4 *>(Kg + at), vq = *reinterpret_cast<const uint4 *>(Vg + at);
             sr.k[i][0] = kq.x; sr.k[i][1] = kq.y; sr.k[i][2] = kq.z; sr.k[i][3] = kq.w;
             sr.v[i][0] = vq.x; sr.v[i][1] = vq.y; sr.v[i][2] = vq.z; sr.v[i][3] = vq.w;
@@ -596,7 +606,8 @@ static hipError_t smha_mfma_qkv_attention(const SmhaArgs &a, hipStream_t st)
     const int l_p = a.l / a.m, l_a = a.c * l_p, units = a.b * a.k;
     hipError_t err;
     QP qp = make_qkv<bf16_t>(a);
-    const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
+    // the MFMA kernel addresses one unit's keys with 32-bit element offsets
+    const bool mfma_attn = (a.d_h == 32 || a.d_h == 64 || a.d_h == 128) && (long)l_a * a.d_h < (1L << 31);
     if (mfma_attn) qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);  // base-2 softmax in the MFMA kernel
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
     // 128-row tiles for long units (measured faster from l_a = 512 up), 32-row tiles for short ones
@@ -646,7 +657,8 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     if ((err = smha_mfma_qkv_attention(a, st)) != hipSuccess) return err;
     if (a.skip & SMHA_STEP_OUT) return hipSuccess;
     if (!out_dma && (err = launch_inverse_map(a, st)) != hipSuccess) return err;
-    const bool mfma_attn = a.d_h == 32 || a.d_h == 64 || a.d_h == 128;
+    // the MFMA kernel addresses one unit's keys with 32-bit element offsets
+    const bool mfma_attn = (a.d_h == 32 || a.d_h == 64 || a.d_h == 128) && (long)a.c * l_p * a.d_h < (1L << 31);
 
     OP op = make_outproj<bf16_t>(a);
     if (mfma_attn) {  // the MFMA attention kernel writes o as a (hi, lo) bf16 pair
