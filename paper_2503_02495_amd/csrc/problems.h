@@ -235,13 +235,13 @@ template <typename T> struct OutProjProblem {
 // ---------------------------------------------------------------------------------------------
 // UoME Eq. 38: group = sample b; M = l; K = d; N = k*d_e (the sample's active experts side by
 // side); epilogue SiLU and the expert's gate.
-template <typename T> struct UomeUpProblem {
+template <typename T, bool RAW = false> struct UomeUpProblem {
     const T *u, *a_in;
     const int32_t *expert_idx;
     const float *expert_gate;  // NULL: weight 1
     T *hidden;                 // [b, l, k*d_e]
     int l, d, n, kact, d_e;
-    int raw;                   // 1: store the plain product (backward pass), no SiLU, no gate
+    static constexpr bool raw = RAW;   // true: store the plain product (backward pass), no SiLU, no gate
 
     __device__ int rows(int) const { return l; }
     __device__ int kdim(int) const { return d; }

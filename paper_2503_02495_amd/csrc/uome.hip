@@ -19,7 +19,7 @@ template <typename T> static hipError_t uome_up_generic(const UomeArgs &a, hipSt
     up.expert_idx = a.expert_idx;
     up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
     up.hidden = static_cast<T *>(a.hidden);
-    up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e; up.raw = 0;
+    up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
     return launch_gemm_generic<T>(up, a.b, a.l, a.k * a.d_e, st);
 }
 
@@ -65,7 +65,7 @@ static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
     up.expert_idx = a.expert_idx;
     up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
     up.hidden = static_cast<bf16_t *>(a.hidden);
-    up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e; up.raw = 0;
+    up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
     return uome_gemm(up, a.b, a.l, a.k * a.d_e, a.d, st);  // K segment = d
 }
 
