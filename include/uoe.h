@@ -26,10 +26,15 @@
  *     bytes of x plus the expert router's weights, from which the routers run as one streaming
  *     pass over x (default 100e6; 0 = whenever that kernel applies).  Results do not depend on it
  *     beyond the summation order of the router logits.
- *   - Shape limits: d % 8 == 0, width % 8 == 0, l % m == 0, 1 <= n <= 32,
- *     1 <= k <= n, 1 <= c <= m, m <= 1024, width <= 128 for SMHA.  Valid but
- *     unsupported requests return UOE_ERR_UNSUPPORTED (also: UOE_FLAG_CAUSAL or rope_dim on a
- *     UoME call; uoe_route and uoe_gather ignore them).
+ *   - Shape limits, all checked on the host before anything is launched (a valid request outside
+ *     them returns UOE_ERR_UNSUPPORTED): d % 8 == 0, width % 8 == 0, l % m == 0, 1 <= n <= 32,
+ *     1 <= k <= n, 1 <= c <= m, m <= 1024, n*m <= 8192, width <= 128 for SMHA, b*m <= 65535 and
+ *     b*k <= 65535 (grid dimensions), b*l*max(d, k*width) <= 1e12 (index arithmetic), and with a
+ *     data router n*d*sizeof(element) <= 48 KiB (W_B is staged in LDS).  Also UNSUPPORTED:
+ *     UOE_FLAG_CAUSAL or rope_dim on a UoME call (uoe_route and uoe_gather ignore them).
+ *   - Routing indices (expert_idx, patch_idx) handed to a compute call are caller data: an index
+ *     outside [0, n) or [0, m) is clamped into range (the call then works on the wrong row, but never
+ *     outside a tensor); it is not reported.
  */
 #ifndef UOE_H
 #define UOE_H
@@ -87,7 +92,8 @@ const char *uoe_status_string(int status);
  *   w_b, w_a     [d,n], [l,m]  data router: per-token map d->n, then map l->m over the
  *                          transposed result (Eq. 13); both NULL iff c == m and gate 1
  *   noise_expert [b,n] fp32, noise_patch [b,n,m] fp32: optional additive logit noise, or NULL
- * Outputs (device, caller-owned):
+ * Outputs (device, caller-owned; each may be NULL, and what it would hold is then not written: a
+ * call with every output NULL computes nothing useful but is valid):
  *   expert_idx   [b,k] int32   the k experts with the largest gate, ascending index;
  *                              ties go to the lower index
  *   expert_gate  [b,n] fp32    softmax over experts of the Eq. 21 logits
@@ -110,7 +116,8 @@ int uoe_route(const uoe_block_desc *blk, const void *x, const void *w_expert, co
  * call on each device).  The call allocates nothing, on the host or on the device.
  *   - A descriptor whose partial sums need more than that (what uoe_workspace_bytes counts for
  *     routing: about 4*(chunks*b*n*(m+1) + b*n*m) bytes with up to 512 chunks) is rejected with
- *     UOE_ERR_SCRATCH_LIMIT and nothing is launched.  The five workload shapes need at most 4.3 MiB.
+ *     UOE_ERR_SCRATCH_LIMIT and nothing is launched.  The five workload shapes need at most 6.3 MiB
+ *     (the largest one, whose routers run as one streaming pass, keeps a [b,l,n] fp32 array there).
  *   - The device of hip_stream must be the current device.
  *   - All calls on one GPU share the array: calls that overlap in time on one GPU (different
  *     streams or threads) race and give wrong results; calls on one stream are safe back to back.
@@ -260,9 +267,11 @@ int uoe_uome_down(const uoe_block_desc *blk, const void *hidden, const void *a_o
  *                       everywhere without UOE_FLAG_GATE_EXPERT; may be NULL
  *   d_patch_gate [b,n,m] fp32 (data selection) dL/d(patch_gate) on the selected patches of the
  *                       active experts, zero elsewhere and without UOE_FLAG_GATE_PATCH; may be NULL
- * Intermediates (u A^I, d_out A^O^T) are kept in the storage dtype between the kernels.  This
- * build: bf16 storage only, l, d and d_e multiples of 32, b <= 128, and l_p a multiple of 32 in
- * data-selection mode; otherwise UOE_ERR_UNSUPPORTED.  Outputs must not alias inputs.
+ * Two paths.  bf16 storage with l, d and d_e multiples of 32, b <= 128 (and l_p a multiple of 32 in
+ * data-selection mode) runs on the matrix cores, intermediates (u A^I, d_out A^O^T) kept in bf16
+ * between the kernels.  Every other expert-selection request (fp32 storage, any l, d, d_e) runs on
+ * the vector ALU with fp32 intermediates: general, not fast.  Data selection outside the first path
+ * is UOE_ERR_UNSUPPORTED.  Outputs must not alias inputs.
  * Deterministic: fixed summation order, no atomics.  ws: at least
  * uoe_uome_backward_workspace_bytes(blk) bytes (0 = descriptor invalid or unsupported).
  */
@@ -315,9 +324,12 @@ typedef struct {
  *                          their selected patches, zero elsewhere and when the matching flag is
  *                          off; either may be NULL
  * pad_mask [b,l] bytes or NULL as in uoe_smha_forward_masked (Eq. 41: padded keys are out of every
- * softmax).  The forward intermediates are recomputed.  This build: bf16 storage, d_h in {32, 64, 128},
- * d % 32 == 0, l_p % 32 == 0, b <= 128; otherwise
- * UOE_ERR_UNSUPPORTED.  Deterministic: fixed summation order, no atomics.  ws: at least
+ * softmax).  The forward intermediates are recomputed.  Two paths: bf16 storage with d_h in
+ * {32, 64, 128}, d % 32 == 0, l_p % 32 == 0 and b <= 128 runs on the matrix cores; every other
+ * request (fp32 storage, a 14-token patch, d_h = 16) runs on the vector ALU with fp32 intermediates
+ * and the attention probabilities of every unit materialised ([b*k, l_a, l_a] fp32 twice in ws):
+ * general, not fast, and UOE_ERR_UNSUPPORTED beyond b*k*l_a*l_a = 2^31 or c > 1024.
+ * Deterministic: fixed summation order, no atomics.  ws: at least
  * uoe_smha_backward_workspace_bytes(blk) bytes (0 = descriptor invalid or unsupported).
  */
 size_t uoe_smha_backward_workspace_bytes(const uoe_block_desc *blk);

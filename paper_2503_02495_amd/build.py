@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libuoe.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["api.hip", "route.hip", "gather.hip", "smha.hip", "uome.hip", "uome_bwd.hip", "smha_bwd.hip", "route_bwd.hip", "probe.hip"]
+SOURCES = ["api.hip", "route.hip", "gather.hip", "smha.hip", "uome.hip", "uome_bwd.hip", "smha_bwd.hip", "route_bwd.hip", "bwd_generic.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept off for every device TU
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -107,9 +107,16 @@ struct UomeBwdWs {
     size_t z, dh, dz, dz_t, h_t, a_in_t, a_out_t, partial, gpart, rt, total;
     int splits;
 };
+static bool uome_bwd_mfma(const uoe_block_desc *blk);
 UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
 {
-    UomeBwdWs w;
+    UomeBwdWs w{};
+    if (!uome_bwd_mfma(d)) {  // vector-ALU path: Z/H and dH/dZ in fp32
+        const size_t act32 = up((size_t)d->b * d->l * d->k * d->width * sizeof(float));
+        w.z = 0; w.dh = act32; w.total = 2 * act32;
+        w.splits = 1;
+        return w;
+    }
     const size_t es = elem_size(d->dtype);
     const size_t act = up((size_t)d->b * d->l * d->k * d->width * es);
     const size_t wt = up((size_t)d->n * d->d * d->width * es);
@@ -132,13 +139,20 @@ UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
     w.total = off;
     return w;
 }
+// the matrix-core backward takes bf16 storage and 32-multiples; everything else goes to the vector-ALU path
+static bool uome_bwd_mfma(const uoe_block_desc *blk)
+{
+    if (blk->dtype != UOE_BF16) return false;
+    if (blk->l % 32 || blk->d % 32 || blk->width % 32 || blk->b > 128) return false;
+    if (blk->c < blk->m && (blk->l / blk->m) % 32) return false;
+    return true;
+}
 int check_uome_bwd(const uoe_block_desc *blk)
 {
     const int rc = check_desc(blk, DESC_UOME);
     if (rc != UOE_OK) return rc;
-    if (blk->dtype != UOE_BF16) return UOE_ERR_UNSUPPORTED;
-    if (blk->l % 32 || blk->d % 32 || blk->width % 32 || blk->b > 128) return UOE_ERR_UNSUPPORTED;
-    if (blk->c < blk->m && (blk->l / blk->m) % 32) return UOE_ERR_UNSUPPORTED;
+    // the vector-ALU path covers the expert-selection mode only
+    if (!uome_bwd_mfma(blk) && blk->c < blk->m) return UOE_ERR_UNSUPPORTED;
     return UOE_OK;
 }
 
@@ -146,10 +160,34 @@ int check_uome_bwd(const uoe_block_desc *blk)
 struct SmhaBwdWs {
     SmhaWs fwd;
     size_t lse, rt, dd, wo_t, wqkv_t, do_raw, d_o, o_t, dqkv, dqkv_t, partial, total;
+    size_t g_q, g_k, g_v, g_o, g_probs, g_dscores;  // vector-ALU path (fp32 arrays)
 };
+static bool smha_bwd_mfma(const uoe_block_desc *blk)
+{
+    if (blk->dtype != UOE_BF16) return false;
+    if (blk->width != 32 && blk->width != 64 && blk->width != 128) return false;
+    return !(blk->d % 32 || (blk->l / blk->m) % 32 || blk->b > 128);
+}
 SmhaBwdWs smha_bwd_ws(const uoe_block_desc *d)
 {
-    SmhaBwdWs w;
+    SmhaBwdWs w{};
+    if (!smha_bwd_mfma(d)) {
+        const size_t l_a = (size_t)d->c * (d->l / d->m), units = (size_t)d->b * d->k;
+        const size_t rows = up(units * l_a * sizeof(float)), one = up(units * l_a * d->width * sizeof(float));
+        const size_t sq = up(units * l_a * l_a * sizeof(float));
+        size_t off = 0;
+        w.g_q = off; off += one;
+        w.g_k = off; off += one;
+        w.g_v = off; off += one;
+        w.g_o = off; off += one;
+        w.do_raw = off; off += one;
+        w.dqkv = off; off += 3 * one;
+        w.rt = off; off += rows;
+        w.g_probs = off; off += sq;
+        w.g_dscores = off; off += sq;
+        w.total = off;
+        return w;
+    }
     w.fwd = smha_ws(d);
     const size_t es = elem_size(d->dtype);
     const size_t l_a = (size_t)d->c * (d->l / d->m), units = (size_t)d->b * d->k;
@@ -174,9 +212,11 @@ int check_smha_bwd(const uoe_block_desc *blk)
 {
     const int rc = check_desc(blk, DESC_SMHA);
     if (rc != UOE_OK) return rc;
-    if (blk->dtype != UOE_BF16) return UOE_ERR_UNSUPPORTED;
-    if (blk->width != 32 && blk->width != 64 && blk->width != 128) return UOE_ERR_UNSUPPORTED;
-    if (blk->d % 32 || (blk->l / blk->m) % 32 || blk->b > 128) return UOE_ERR_UNSUPPORTED;
+    if (!smha_bwd_mfma(blk)) {
+        // vector-ALU path: the materialised [units, l_a, l_a] arrays bound the size; the gate kernel holds c sums
+        const size_t l_a = (size_t)blk->c * (blk->l / blk->m);
+        if (blk->c > 1024 || (size_t)blk->b * blk->k * l_a * l_a > ((size_t)1 << 31)) return UOE_ERR_UNSUPPORTED;
+    }
     return UOE_OK;
 }
 
@@ -536,6 +576,11 @@ int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in
     a.u = u; a.a_in = a_in; a.a_out = a_out; a.d_out = d_out; a.expert_idx = expert_idx; a.expert_gate = expert_gate;
     a.d_u = d_u; a.d_a_in = d_a_in; a.d_a_out = d_a_out; a.d_gate = d_gate;
     a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.d_e = blk->width; a.flags = blk->flags;
+    if (!uome_bwd_mfma(blk)) {
+        a.z = at(ws, w.z); a.dh = at(ws, w.dh);
+        return launch_uome_backward_generic(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+                   ? UOE_OK : UOE_ERR_DEVICE;
+    }
     a.z = at(ws, w.z); a.dh = at(ws, w.dh); a.dz = at(ws, w.dz);
     a.dz_t = at(ws, w.dz_t); a.h_t = at(ws, w.h_t); a.a_in_t = at(ws, w.a_in_t); a.a_out_t = at(ws, w.a_out_t);
     a.gpart = reinterpret_cast<float *>(at(ws, w.gpart));
@@ -577,6 +622,17 @@ int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_w
     f.b = blk->b; f.l = blk->l; f.d = blk->d; f.n = blk->n; f.k = blk->k; f.m = blk->m; f.c = blk->c;
     f.d_h = blk->width; f.flags = blk->flags & UOE_FLAG_CAUSAL;  // the recomputed o carries no gate
     f.rope_dim = blk->rope_dim; f.pad_mask = pad_mask;
+    if (!smha_bwd_mfma(blk)) {
+        f.q = at(ws, s.g_q); f.kk = at(ws, s.g_k); f.v = at(ws, s.g_v); f.o = at(ws, s.g_o);
+        a.d_out = d_out; a.expert_gate = expert_gate; a.patch_gate = patch_gate; a.flags = blk->flags;
+        a.d_x = d_x; a.d_wq = dw->d_wq; a.d_wk = dw->d_wk; a.d_wv = dw->d_wv; a.d_wo = dw->d_wo;
+        a.d_expert_gate = d_expert_gate; a.d_patch_gate = d_patch_gate;
+        a.do_raw = reinterpret_cast<float *>(at(ws, s.do_raw)); a.dqkv = at(ws, s.dqkv);
+        a.rt = reinterpret_cast<float *>(at(ws, s.rt));
+        a.probs = reinterpret_cast<float *>(at(ws, s.g_probs)); a.dscores = reinterpret_cast<float *>(at(ws, s.g_dscores));
+        return launch_smha_backward_generic(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+                   ? UOE_OK : UOE_ERR_DEVICE;
+    }
     f.q = at(ws, s.fwd.q); f.kk = at(ws, s.fwd.k); f.v = at(ws, s.fwd.v); f.o = at(ws, s.fwd.o); f.o_lo = at(ws, s.fwd.o_lo);
     f.lse = reinterpret_cast<float *>(at(ws, s.lse));
     a.d_out = d_out; a.expert_gate = expert_gate; a.patch_gate = patch_gate; a.flags = blk->flags;

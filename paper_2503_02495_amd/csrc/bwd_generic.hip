@@ -1,0 +1,487 @@
+// Backward passes of the SMHA block (Eq. 27-36, Eq. 32 RoPE, the masks of Sec. III-C.3) and of the UoME block
+// in expert-selection mode (Eq. 38-40 with Eq. 24-26) for every shape and storage type the matrix-core
+// kernels do not take: fp32 storage, head or expert widths and token counts that are not multiples of 32
+// (a 14-token patch, a 196-token sequence).  Same formulas as smha_bwd.hip / uome_bwd.hip, written as plain
+// vector-ALU kernels, one thread per output element with its contraction as a loop in fixed order (no
+// atomics: results do not depend on scheduling).  Every intermediate lives in fp32 in the workspace,
+// whatever the storage type; the softmax probabilities and their gradients are materialised
+// ([units, l_a, l_a]), which is what bounds the sizes this path is meant for.  It favours generality over
+// speed.
+#include "common.h"
+
+namespace uoe {
+
+namespace {
+
+constexpr int GT = 256;  // threads per block of every kernel here
+
+inline dim3 blocks_for(long total) { return dim3((unsigned)((total + GT - 1) / GT)); }
+
+// ------------------------------------------------------------------------------------------ UoME
+// a.z and a.dh are fp32 [b, l, k*d_e] here: Z then H, dH_raw then dZ.
+
+// Z = u W1_b and dH = d_out W2_b^T: thread = (token row, hidden column)
+template <typename T> __global__ __launch_bounds__(GT) void gen_uome_z_dh(UomeBwdArgs a)
+{
+    const long W = (long)a.k * a.d_e, total = (long)a.b * a.l * W;
+    const long idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const long row = idx / W;
+    const int col = (int)(idx - row * W), bb = (int)(row / a.l);
+    const int s = col / a.d_e, e = col - s * a.d_e;
+    const int i = clampi(a.expert_idx[bb * a.k + s], a.n);
+    const T *ur = static_cast<const T *>(a.u) + row * a.d, *gr = static_cast<const T *>(a.d_out) + row * a.d;
+    const T *wi = static_cast<const T *>(a.a_in) + (size_t)i * a.d * a.d_e + e;          // column e of A^I_i
+    const T *wo = static_cast<const T *>(a.a_out) + ((size_t)i * a.d_e + e) * a.d;       // row e of A^O_i
+    float z = 0.f, dh = 0.f;
+    for (int j = 0; j < a.d; ++j) {
+        z = fmaf(to_f32(ur[j]), to_f32(wi[(size_t)j * a.d_e]), z);
+        dh = fmaf(to_f32(gr[j]), to_f32(wo[j]), dh);
+    }
+    static_cast<float *>(a.z)[idx] = z;
+    static_cast<float *>(a.dh)[idx] = dh;
+}
+
+// H = SiLU(Z) w, dZ = dH w SiLU'(Z) in place, and d_gate[b, i(s)] = sum dH SiLU(Z): block = (slot, sample),
+// each thread a strided subset of the slot's l*d_e elements in index order, then a fixed tree
+__global__ __launch_bounds__(GT) void gen_uome_mid(UomeBwdArgs a)
+{
+    __shared__ float red[GT];
+    const int s = blockIdx.x, bb = blockIdx.y, tid = threadIdx.x;
+    const bool gated = (a.flags & F_GATE_EXPERT) && a.expert_gate;
+    const int i = clampi(a.expert_idx[bb * a.k + s], a.n);
+    const float w = gated ? a.expert_gate[(size_t)bb * a.n + i] : 1.0f;
+    const long W = (long)a.k * a.d_e, count = (long)a.l * a.d_e;
+    float *zb = static_cast<float *>(a.z), *hb = static_cast<float *>(a.dh);
+    float part = 0.f;
+    for (long q = tid; q < count; q += GT) {
+        const long t = q / a.d_e;
+        const long at = ((long)bb * a.l + t) * W + (long)s * a.d_e + (q - t * a.d_e);
+        const float z = zb[at], dh = hb[at];
+        const float sig = 1.0f / (1.0f + expf(-z)), v = z * sig;
+        part = fmaf(dh, v, part);
+        zb[at] = v * w;
+        hb[at] = dh * w * (sig * (1.0f + z * (1.0f - sig)));
+    }
+    if (!a.d_gate) return;
+    red[tid] = part;
+    __syncthreads();
+    for (int st = GT / 2; st > 0; st >>= 1) {
+        if (tid < st) red[tid] += red[tid + st];
+        __syncthreads();
+    }
+    if (s == 0 && tid < a.n) {  // the experts the sample did not select (all of them without the gate flag)
+        bool chosen = false;
+        for (int q = 0; q < a.k; ++q) chosen |= clampi(a.expert_idx[bb * a.k + q], a.n) == tid;
+        if (!chosen || !(a.flags & F_GATE_EXPERT)) a.d_gate[(size_t)bb * a.n + tid] = 0.f;
+    }
+    if ((a.flags & F_GATE_EXPERT) && tid == 0) a.d_gate[(size_t)bb * a.n + i] = red[0];
+}
+
+// d_u = (d_out) + dZ W1_b^T: thread = (token row, model column j)
+template <typename T> __global__ __launch_bounds__(GT) void gen_uome_du(UomeBwdArgs a)
+{
+    const long total = (long)a.b * a.l * a.d, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const long row = idx / a.d;
+    const int j = (int)(idx - row * a.d), bb = (int)(row / a.l);
+    const long W = (long)a.k * a.d_e;
+    float acc = (a.flags & F_RESIDUAL) ? to_f32(static_cast<const T *>(a.d_out)[idx]) : 0.f;
+    for (int s = 0; s < a.k; ++s) {
+        const int i = clampi(a.expert_idx[bb * a.k + s], a.n);
+        const T *wi = static_cast<const T *>(a.a_in) + ((size_t)i * a.d + j) * a.d_e;  // row j of A^I_i
+        const float *dz = static_cast<const float *>(a.dh) + row * W + (long)s * a.d_e;
+        for (int e = 0; e < a.d_e; ++e) acc = fmaf(dz[e], to_f32(wi[e]), acc);
+    }
+    static_cast<T *>(a.d_u)[idx] = from_f32<T>(acc);
+}
+
+// dA^O_i [d_e, d] = sum H_{b,s}^T d_out_b and dA^I_i [d, d_e] = sum u_b^T dZ_{b,s} over the (sample, slot)
+// pairs that selected expert i, samples then slots then tokens in order: thread = one weight element
+template <typename T> __global__ __launch_bounds__(GT) void gen_uome_dw(UomeBwdArgs a)
+{
+    const long per = (long)a.n * a.d * a.d_e, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= 2 * per) return;
+    const bool second = idx >= per;   // false: dA^O, true: dA^I
+    const long q = second ? idx - per : idx;
+    const int i = (int)(q / ((long)a.d * a.d_e));
+    const long rem = q - (long)i * a.d * a.d_e;
+    const int e = second ? (int)(rem % a.d_e) : (int)(rem / a.d), j = second ? (int)(rem / a.d_e) : (int)(rem % a.d);
+    const long W = (long)a.k * a.d_e;
+    const float *hb = static_cast<const float *>(a.z), *dzb = static_cast<const float *>(a.dh);
+    const T *left = static_cast<const T *>(second ? a.u : a.d_out);
+    float acc = 0.f;
+    for (int bb = 0; bb < a.b; ++bb)
+        for (int s = 0; s < a.k; ++s) {
+            if (clampi(a.expert_idx[bb * a.k + s], a.n) != i) continue;
+            const float *act = (second ? dzb : hb) + (long)bb * a.l * W + (long)s * a.d_e + e;
+            const T *tok = left + (long)bb * a.l * a.d + j;
+            for (int t = 0; t < a.l; ++t) acc = fmaf(act[(long)t * W], to_f32(tok[(long)t * a.d]), acc);
+        }
+    static_cast<T *>(second ? a.d_a_in : a.d_a_out)[q] = from_f32<T>(acc);
+}
+
+// ------------------------------------------------------------------------------------------ SMHA
+// fp32 workspace: f.q, f.kk, f.v, f.o and do_raw [units, l_a, d_h]; dqkv [units, l_a, 3*d_h] as [dq | dk | dv];
+// probs and dscores [units, l_a, l_a]; rt, dd [units, l_a].
+
+struct UnitRow {
+    int bb, i, tok;
+};
+__device__ __forceinline__ UnitRow unit_row(const SmhaArgs &f, int g, int r, int l_p)
+{
+    UnitRow u;
+    u.bb = g / f.k;
+    u.i = clampi(f.expert_idx[g], f.n);
+    const int p = clampi(f.patch_idx[((size_t)u.bb * f.n + u.i) * f.c + r / l_p], f.m);
+    u.tok = p * l_p + r % l_p;
+    return u;
+}
+
+// weight of row r of unit g in the block's output (Eq. 36 with the gate flags)
+__device__ __forceinline__ float row_weight(const SmhaBwdArgs &a, int g, int r, int l_p)
+{
+    const SmhaArgs &f = a.f;
+    const int bb = g / f.k, i = clampi(f.expert_idx[g], f.n);
+    float w = 1.0f;
+    if (a.flags & F_GATE_EXPERT) w *= a.expert_gate[(size_t)bb * f.n + i];
+    if (a.flags & F_GATE_PATCH) {
+        const int p = clampi(f.patch_idx[((size_t)bb * f.n + i) * f.c + r / l_p], f.m);
+        w *= a.patch_gate[((size_t)bb * f.n + i) * f.m + p];
+    }
+    return w;
+}
+
+// q, k, v of the gathered rows (Eq. 18, 28-30): thread = (unit, row, head column)
+template <typename T> __global__ __launch_bounds__(GT) void gen_smha_qkv(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_p = f.l / f.m, l_a = f.c * l_p;
+    const long total = (long)f.b * f.k * l_a * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const int e = (int)(idx % f.d_h);
+    const long ur = idx / f.d_h;
+    const int g = (int)(ur / l_a), r = (int)(ur - (long)g * l_a);
+    const UnitRow u = unit_row(f, g, r, l_p);
+    const T *xr = static_cast<const T *>(f.x) + ((size_t)u.bb * f.l + u.tok) * f.d;
+    const size_t wat = (size_t)u.i * f.d * f.d_h + e;
+    const T *wq = static_cast<const T *>(f.wq) + wat, *wk = static_cast<const T *>(f.wk) + wat, *wv = static_cast<const T *>(f.wv) + wat;
+    float q = 0.f, k = 0.f, v = 0.f;
+    for (int j = 0; j < f.d; ++j) {
+        const float xv = to_f32(xr[j]);
+        q = fmaf(xv, to_f32(wq[(size_t)j * f.d_h]), q);
+        k = fmaf(xv, to_f32(wk[(size_t)j * f.d_h]), k);
+        v = fmaf(xv, to_f32(wv[(size_t)j * f.d_h]), v);
+    }
+    static_cast<float *>(f.q)[idx] = q;
+    static_cast<float *>(f.kk)[idx] = k;
+    static_cast<float *>(f.v)[idx] = v;
+}
+
+// Partial RoPE of Eq. 32 on two [units, l_a, stride] fp32 arrays (columns col0.. of each row hold a head), in
+// place: pairs (2i, 2i+1) of the last rope_dim dims rotated by row position * 10000^(-2i/rope_dim);
+// inverse = the transposed rotation (the gradient's way back).  Thread = (unit row, pair).
+__global__ __launch_bounds__(GT) void gen_smha_rope(SmhaArgs f, float *pa, float *pb, int stride, int inverse)
+{
+    const int l_a = f.c * (f.l / f.m), half = f.rope_dim >> 1;
+    const long total = (long)f.b * f.k * l_a * half, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx % half);
+    const long row = idx / half;
+    const int r = (int)(row % l_a);
+    const float theta = exp2f(-(2.0f * (float)i / (float)f.rope_dim) * 13.287712379549449f);  // log2(10000)
+    float sn, cs;
+    sincosf((float)r * theta, &sn, &cs);
+    if (inverse) sn = -sn;
+    const size_t at = (size_t)row * stride + (f.d_h - f.rope_dim) + 2 * i;
+    const float a0 = pa[at], a1 = pa[at + 1], b0 = pb[at], b1 = pb[at + 1];
+    pa[at] = a0 * cs - a1 * sn;
+    pa[at + 1] = a0 * sn + a1 * cs;
+    pb[at] = b0 * cs - b1 * sn;
+    pb[at + 1] = b0 * sn + b1 * cs;
+}
+
+__device__ __forceinline__ bool gen_key_ok(const SmhaArgs &f, int g, int r, int key, int l_p)
+{
+    if ((f.flags & F_CAUSAL) && key > r) return false;
+    if (!f.pad_mask) return true;
+    const UnitRow u = unit_row(f, g, key, l_p);
+    return f.pad_mask[(size_t)u.bb * f.l + u.tok] != 0;   // Eq. 41: padded keys are out of every softmax
+}
+
+// scaled scores of the admissible (query, key) pairs, -inf elsewhere: thread = (unit, query, key)
+__global__ __launch_bounds__(GT) void gen_smha_scores(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_p = f.l / f.m, l_a = f.c * l_p;
+    const long total = (long)f.b * f.k * l_a * l_a, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const int key = (int)(idx % l_a);
+    const long ur = idx / l_a;
+    const int g = (int)(ur / l_a), r = (int)(ur - (long)g * l_a);
+    float s = -INFINITY;
+    if (gen_key_ok(f, g, r, key, l_p)) {
+        const float *q = static_cast<const float *>(f.q) + ur * f.d_h;
+        const float *k = static_cast<const float *>(f.kk) + ((long)g * l_a + key) * f.d_h;
+        s = 0.f;
+        for (int e = 0; e < f.d_h; ++e) s = fmaf(q[e], k[e], s);
+        s *= rsqrtf((float)f.d_h);
+    }
+    a.probs[idx] = s;
+}
+
+// softmax of every query row in place (Eq. 33); a row with no admissible key becomes all zeros
+__global__ __launch_bounds__(GT) void gen_smha_softmax(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_a = f.c * (f.l / f.m);
+    const long total = (long)f.b * f.k * l_a, ur = (long)blockIdx.x * GT + threadIdx.x;
+    if (ur >= total) return;
+    float *p = a.probs + ur * l_a;
+    float mx = -INFINITY;
+    for (int j = 0; j < l_a; ++j) mx = fmaxf(mx, p[j]);
+    if (mx == -INFINITY) {
+        for (int j = 0; j < l_a; ++j) p[j] = 0.f;
+        return;
+    }
+    float den = 0.f;
+    for (int j = 0; j < l_a; ++j) den += expf(p[j] - mx);
+    const float inv = 1.0f / den;
+    for (int j = 0; j < l_a; ++j) p[j] = expf(p[j] - mx) * inv;
+}
+
+// o = P v (Eq. 34, no gate): thread = (unit, row, head column)
+__global__ __launch_bounds__(GT) void gen_smha_o(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_a = f.c * (f.l / f.m);
+    const long total = (long)f.b * f.k * l_a * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const int e = (int)(idx % f.d_h);
+    const long ur = idx / f.d_h;
+    const int g = (int)(ur / l_a);
+    const float *p = a.probs + ur * l_a, *v = static_cast<const float *>(f.v) + (long)g * l_a * f.d_h + e;
+    float o = 0.f;
+    for (int j = 0; j < l_a; ++j) o = fmaf(p[j], v[(long)j * f.d_h], o);
+    static_cast<float *>(f.o)[idx] = o;
+}
+
+// dO_raw = G[T] W^O_i^T: thread = (unit, row, head column)
+template <typename T> __global__ __launch_bounds__(GT) void gen_smha_do(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_p = f.l / f.m, l_a = f.c * l_p;
+    const long total = (long)f.b * f.k * l_a * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const int e = (int)(idx % f.d_h);
+    const long ur = idx / f.d_h;
+    const int g = (int)(ur / l_a), r = (int)(ur - (long)g * l_a);
+    const UnitRow u = unit_row(f, g, r, l_p);
+    const T *gr = static_cast<const T *>(a.d_out) + ((size_t)u.bb * f.l + u.tok) * f.d;
+    const T *wo = static_cast<const T *>(f.wo) + ((size_t)u.i * f.d_h + e) * f.d;   // row e of W^O_i
+    float acc = 0.f;
+    for (int j = 0; j < f.d; ++j) acc = fmaf(to_f32(gr[j]), to_f32(wo[j]), acc);
+    a.do_raw[idx] = acc;
+}
+
+// r_t = dO_raw_t . o_t (the gradient of the row's weight), then dO = w dO_raw in place: thread = (unit, row)
+__global__ __launch_bounds__(GT) void gen_smha_row(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_p = f.l / f.m, l_a = f.c * l_p;
+    const long total = (long)f.b * f.k * l_a, ur = (long)blockIdx.x * GT + threadIdx.x;
+    if (ur >= total) return;
+    const int g = (int)(ur / l_a), r = (int)(ur - (long)g * l_a);
+    const float w = row_weight(a, g, r, l_p);
+    float *dr = a.do_raw + ur * f.d_h;
+    const float *o = static_cast<const float *>(f.o) + ur * f.d_h;
+    float dot = 0.f;
+    for (int e = 0; e < f.d_h; ++e) {
+        dot = fmaf(dr[e], o[e], dot);
+        dr[e] *= w;
+    }
+    a.rt[ur] = dot;
+}
+
+// dP = dO V^T: thread = (unit, query, key)
+__global__ __launch_bounds__(GT) void gen_smha_dp(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_a = f.c * (f.l / f.m);
+    const long total = (long)f.b * f.k * l_a * l_a, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const int key = (int)(idx % l_a);
+    const long ur = idx / l_a;
+    const int g = (int)(ur / l_a);
+    const float *d_o = a.do_raw + ur * f.d_h, *v = static_cast<const float *>(f.v) + ((long)g * l_a + key) * f.d_h;
+    float s = 0.f;
+    for (int e = 0; e < f.d_h; ++e) s = fmaf(d_o[e], v[e], s);
+    a.dscores[idx] = s;
+}
+
+// dS = P * (dP - D), D = sum_j P_j dP_j, in place: thread = (unit, query)
+__global__ __launch_bounds__(GT) void gen_smha_ds(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_a = f.c * (f.l / f.m);
+    const long total = (long)f.b * f.k * l_a, ur = (long)blockIdx.x * GT + threadIdx.x;
+    if (ur >= total) return;
+    const float *p = a.probs + ur * l_a;
+    float *ds = a.dscores + ur * l_a;
+    float dsum = 0.f;
+    for (int j = 0; j < l_a; ++j) dsum = fmaf(p[j], ds[j], dsum);
+    for (int j = 0; j < l_a; ++j) ds[j] = p[j] * (ds[j] - dsum);
+}
+
+// dQ = dS K / sqrt(d_h), dK = dS^T Q / sqrt(d_h), dV = P^T dO: thread = (unit, row, head column)
+__global__ __launch_bounds__(GT) void gen_smha_dqkv(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_a = f.c * (f.l / f.m);
+    const long total = (long)f.b * f.k * l_a * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const int e = (int)(idx % f.d_h);
+    const long ur = idx / f.d_h;
+    const int g = (int)(ur / l_a), r = (int)(ur - (long)g * l_a);
+    const long ubase = (long)g * l_a;
+    const float *q = static_cast<const float *>(f.q) + ubase * f.d_h + e, *k = static_cast<const float *>(f.kk) + ubase * f.d_h + e;
+    const float *d_o = a.do_raw + ubase * f.d_h + e;
+    const float *ds_row = a.dscores + ur * l_a;            // dS[r, :]
+    const float *ds_col = a.dscores + ubase * l_a + r;     // dS[:, r]
+    const float *p_col = a.probs + ubase * l_a + r;        // P[:, r]
+    float dq = 0.f, dk = 0.f, dv = 0.f;
+    for (int j = 0; j < l_a; ++j) {
+        dq = fmaf(ds_row[j], k[(long)j * f.d_h], dq);
+        dk = fmaf(ds_col[(long)j * l_a], q[(long)j * f.d_h], dk);
+        dv = fmaf(p_col[(long)j * l_a], d_o[(long)j * f.d_h], dv);
+    }
+    const float scale = rsqrtf((float)f.d_h);
+    float *out = static_cast<float *>(a.dqkv) + ur * 3 * f.d_h + e;
+    out[0] = dq * scale;
+    out[f.d_h] = dk * scale;
+    out[2 * f.d_h] = dv;
+}
+
+// d_x = (G) + sum over the units that picked the token's patch of [dq|dk|dv] [W^q|W^k|W^v]_i^T, slots then
+// picks in order: thread = (token, model column j)
+template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dx(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_p = f.l / f.m, l_a = f.c * l_p;
+    const long total = (long)f.b * f.l * f.d, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const long trow = idx / f.d;
+    const int j = (int)(idx - trow * f.d), bb = (int)(trow / f.l), tok = (int)(trow - (long)bb * f.l);
+    const int patch = tok / l_p, within = tok - patch * l_p;
+    float acc = (a.flags & F_RESIDUAL) ? to_f32(static_cast<const T *>(a.d_out)[idx]) : 0.f;
+    for (int s = 0; s < f.k; ++s) {
+        const int g = bb * f.k + s, i = clampi(f.expert_idx[g], f.n);
+        const int32_t *picks = f.patch_idx + ((size_t)bb * f.n + i) * f.c;
+        const size_t wat = ((size_t)i * f.d + j) * f.d_h;   // row j of the expert's [d, d_h] weights
+        const T *wq = static_cast<const T *>(f.wq) + wat, *wk = static_cast<const T *>(f.wk) + wat, *wv = static_cast<const T *>(f.wv) + wat;
+        for (int t = 0; t < f.c; ++t) {
+            if (clampi(picks[t], f.m) != patch) continue;
+            const float *row = static_cast<const float *>(a.dqkv) + ((long)g * l_a + t * l_p + within) * 3 * f.d_h;
+            for (int e = 0; e < f.d_h; ++e) {
+                acc = fmaf(row[e], to_f32(wq[e]), acc);
+                acc = fmaf(row[f.d_h + e], to_f32(wk[e]), acc);
+                acc = fmaf(row[2 * f.d_h + e], to_f32(wv[e]), acc);
+            }
+        }
+    }
+    static_cast<T *>(a.d_x)[idx] = from_f32<T>(acc);
+}
+
+// dW^{q,k,v}_i [d, d_h] = sum x[T]^T d{Q,K,V} and dW^O_i [d_h, d] = sum (w o)^T G[T] over the units of
+// expert i, units then rows in order: thread = one weight element
+template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const int l_p = f.l / f.m, l_a = f.c * l_p, units = f.b * f.k;
+    const long per = (long)f.n * f.d * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= 4 * per) return;
+    const int which = (int)(idx / per);   // 0..2: dW^q, dW^k, dW^v; 3: dW^O
+    const long q = idx - (long)which * per;
+    const int i = (int)(q / ((long)f.d * f.d_h));
+    const long rem = q - (long)i * f.d * f.d_h;
+    const int e = which < 3 ? (int)(rem % f.d_h) : (int)(rem / f.d), j = which < 3 ? (int)(rem / f.d_h) : (int)(rem % f.d);
+    const T *tokens = static_cast<const T *>(which < 3 ? f.x : a.d_out);
+    float acc = 0.f;
+    for (int g = 0; g < units; ++g) {
+        if (clampi(f.expert_idx[g], f.n) != i) continue;
+        const int bb = g / f.k;
+        const int32_t *picks = f.patch_idx + ((size_t)bb * f.n + i) * f.c;
+        for (int t = 0; t < f.c; ++t) {
+            const int p = clampi(picks[t], f.m);
+            const T *tk = tokens + ((size_t)bb * f.l + (size_t)p * l_p) * f.d + j;
+            const long r0 = (long)g * l_a + t * l_p;
+            for (int rr = 0; rr < l_p; ++rr) {
+                float left;
+                if (which < 3) left = static_cast<const float *>(a.dqkv)[(r0 + rr) * 3 * f.d_h + which * f.d_h + e];
+                else left = static_cast<const float *>(f.o)[(r0 + rr) * f.d_h + e] * row_weight(a, g, t * l_p + rr, l_p);
+                acc = fmaf(left, to_f32(tk[(size_t)rr * f.d]), acc);
+            }
+        }
+    }
+    T *dst = static_cast<T *>(which == 0 ? a.d_wq : which == 1 ? a.d_wk : which == 2 ? a.d_wv : a.d_wo);
+    dst[q] = from_f32<T>(acc);
+}
+
+template <typename T> hipError_t uome_backward_generic(const UomeBwdArgs &a, hipStream_t st)
+{
+    const long W = (long)a.k * a.d_e;
+    hipError_t err;
+    hipLaunchKernelGGL((gen_uome_z_dh<T>), blocks_for((long)a.b * a.l * W), dim3(GT), 0, st, a);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    hipLaunchKernelGGL(gen_uome_mid, dim3(a.k, a.b), dim3(GT), 0, st, a);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    hipLaunchKernelGGL((gen_uome_du<T>), blocks_for((long)a.b * a.l * a.d), dim3(GT), 0, st, a);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    hipLaunchKernelGGL((gen_uome_dw<T>), blocks_for(2L * a.n * a.d * a.d_e), dim3(GT), 0, st, a);
+    return hipGetLastError();
+}
+
+template <typename T> hipError_t smha_backward_generic(const SmhaBwdArgs &a, hipStream_t st)
+{
+    const SmhaArgs &f = a.f;
+    const int l_p = f.l / f.m, l_a = f.c * l_p;
+    const long rows = (long)f.b * f.k * l_a, elems = rows * f.d_h, pairs = rows * l_a;
+    const long rope_pairs = rows * (f.rope_dim >> 1);
+    hipError_t err;
+#define UOE_GEN(kernel, total, ...)                                                       \
+    hipLaunchKernelGGL(kernel, blocks_for(total), dim3(GT), 0, st, __VA_ARGS__);          \
+    if ((err = hipGetLastError()) != hipSuccess) return err
+    UOE_GEN((gen_smha_qkv<T>), elems, a);
+    if (f.rope_dim > 0) { UOE_GEN(gen_smha_rope, rope_pairs, f, static_cast<float *>(f.q), static_cast<float *>(f.kk), f.d_h, 0); }
+    UOE_GEN(gen_smha_scores, pairs, a);
+    UOE_GEN(gen_smha_softmax, rows, a);
+    UOE_GEN(gen_smha_o, elems, a);
+    UOE_GEN((gen_smha_do<T>), elems, a);
+    UOE_GEN(gen_smha_row, rows, a);
+    if ((err = launch_unit_gate_grads(a, st)) != hipSuccess) return err;
+    UOE_GEN(gen_smha_dp, pairs, a);
+    UOE_GEN(gen_smha_ds, rows, a);
+    UOE_GEN(gen_smha_dqkv, elems, a);
+    if (f.rope_dim > 0) {
+        float *dq = static_cast<float *>(a.dqkv);
+        UOE_GEN(gen_smha_rope, rope_pairs, f, dq, dq + f.d_h, 3 * f.d_h, 1);
+    }
+    UOE_GEN((gen_smha_dx<T>), (long)f.b * f.l * f.d, a);
+    UOE_GEN((gen_smha_dw<T>), 4L * f.n * f.d * f.d_h, a);
+#undef UOE_GEN
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_uome_backward_generic(const UomeBwdArgs &a, bool bf16, hipStream_t st)
+{
+    return bf16 ? uome_backward_generic<bf16_t>(a, st) : uome_backward_generic<float>(a, st);
+}
+
+hipError_t launch_smha_backward_generic(const SmhaBwdArgs &a, bool bf16, hipStream_t st)
+{
+    return bf16 ? smha_backward_generic<bf16_t>(a, st) : smha_backward_generic<float>(a, st);
+}
+
+}  // namespace uoe

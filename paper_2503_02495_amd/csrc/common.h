@@ -154,7 +154,7 @@ struct UomeBwdArgs {
     int m, c;
 };
 
-// Backward pass of the SMHA block (bf16 storage, MFMA shapes only)
+// Backward pass of the SMHA block
 struct SmhaBwdArgs {
     SmhaArgs f;                               // the forward call that is recomputed: no gates in f.flags, f.lse set
     const void *d_out;                        // [b,l,d]
@@ -171,6 +171,8 @@ struct SmhaBwdArgs {
     float *rt, *dd;                           // [units, l_a] each: dL/dw_t and the softmax row term
     float *partial;                           // [4*n*splits, d_h, d] split tiles of the four weight gradients
     int splits;
+    // vector-ALU path only (any shape, any storage type): every workspace array above that it uses is fp32
+    float *probs, *dscores;                   // [units, l_a, l_a] each: softmax probabilities and score gradients
 };
 
 // Backward pass of the routers of one block
@@ -213,6 +215,9 @@ hipError_t launch_smha_backward(const SmhaBwdArgs &a, hipStream_t st);
 // gate gradients of the units of a data-selected block from the row terms a.rt (uses the routing
 // fields of a.f, a.flags, the gates and the two outputs, which it clears first)
 hipError_t launch_unit_gate_grads(const SmhaBwdArgs &a, hipStream_t st);
+// vector-ALU backward passes for the shapes and storage types the matrix-core kernels do not take
+hipError_t launch_uome_backward_generic(const UomeBwdArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_smha_backward_generic(const SmhaBwdArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_route_backward(const RouteBwdArgs &a, bool bf16, hipStream_t st);
 int smha_backward_splits(int b, int n, int k, int c);
 int uome_backward_gate_chunks(int l, int d_e);

@@ -172,15 +172,17 @@ def test_smha_uome_layer_argument_validation():
 
 def test_backward_argument_validation():
     """The backward entry points: unsupported shapes give a zero workspace size and
-    UOE_ERR_UNSUPPORTED, bad pointer combinations UOE_ERR_INVALID_ARG, all before any launch."""
+    UOE_ERR_UNSUPPORTED, bad pointer combinations UOE_ERR_INVALID_ARG, all before any launch.  Shapes
+    off the matrix-core grid and fp32 storage are taken by the vector-ALU path, except the UoME block
+    with patch-wise data selection."""
     assert ctypes.sizeof(B.SmhaWeightGrads) == 4 * 8 and ctypes.sizeof(B.RouterGrads) == 3 * 8
     big = 1 << 40
     fl = B.FLAG_RESIDUAL | B.FLAG_GATE_EXPERT
-    # UoME backward: bf16, l, d, d_e multiples of 32, expert-selection mode
+    # UoME backward, expert-selection mode: every shape and both storage types
     u = B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.BF16, fl)
     assert B.uome_backward_workspace_bytes(u) > 0
-    assert B.uome_backward_workspace_bytes(B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.F32, fl)) == 0
-    assert B.uome_backward_workspace_bytes(B.block_desc(2, 48, 64, 4, 2, 1, 1, 64, B.BF16, fl)) == 0
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.F32, fl)) == 2 * 2 * 64 * 2 * 64 * 4
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 48, 64, 4, 2, 1, 1, 64, B.BF16, fl)) == 2 * 2 * 48 * 2 * 64 * 4
     ub = lambda *a, **k: B.uome_backward(u, *a, stream=0, check=False, **k)
     ok = [FAKE, FAKE + 16, FAKE + 32, FAKE, FAKE, None, None, FAKE + 48, FAKE + 64, FAKE + 80, FAKE + 96, FAKE, None, FAKE]
     assert ub(*ok, ws_bytes=8) == B.ERR_WORKSPACE
@@ -193,6 +195,7 @@ def test_backward_argument_validation():
     uds = B.block_desc(2, 128, 64, 4, 2, 4, 2, 64, B.BF16, fl | B.FLAG_GATE_PATCH)     # data selection, l_p = 32
     assert B.uome_backward_workspace_bytes(uds) > 0
     assert B.uome_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 8, 2, 64, B.BF16, fl)) == 0    # l_p = 16
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 4, 2, 64, B.F32, fl)) == 0     # fp32 storage
     dsb = lambda *a, **k: B.uome_backward(uds, *a, stream=0, check=False, **k)
     okd = list(ok); okd[5] = FAKE; okd[6] = FAKE; okd[12] = FAKE
     assert dsb(*okd, ws_bytes=8) == B.ERR_WORKSPACE
@@ -200,11 +203,13 @@ def test_backward_argument_validation():
     assert dsb(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
     bad = list(okd); bad[6] = None                      # patch gate flag without patch gates
     assert dsb(*bad, ws_bytes=big) == B.ERR_INVALID_ARG
-    # SMHA backward: d_h in {32, 64, 128}, l_p a multiple of 32
+    # SMHA backward: every shape and both storage types (d_h in {32, 64, 128} with l_p a multiple of 32 on the
+    # matrix cores, the rest on the vector ALU, whose [units, l_a, l_a] arrays bound the size)
     a = B.block_desc(2, 128, 64, 4, 2, 4, 2, 32, B.BF16, fl | B.FLAG_GATE_PATCH)
     assert B.smha_backward_workspace_bytes(a) > 0
-    assert B.smha_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 8, 2, 32, B.BF16, fl)) == 0    # l_p = 16
-    assert B.smha_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 4, 2, 16, B.BF16, fl)) == 0    # d_h = 16
+    assert B.smha_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 8, 2, 32, B.BF16, fl)) > 0    # l_p = 16
+    assert B.smha_backward_workspace_bytes(B.block_desc(2, 128, 64, 4, 2, 4, 2, 16, B.F32, fl)) > 0     # d_h = 16, fp32
+    assert B.smha_backward_workspace_bytes(B.block_desc(64, 8192, 64, 4, 4, 8, 8, 16, B.F32, fl)) == 0  # 256 units of 8192 rows
     wa = B.smha_weights(*([FAKE] * 7))
     dw = B.smha_weight_grads(FAKE + 16, FAKE + 32, FAKE + 48, FAKE + 64)
     sb = lambda *args, **k: B.smha_backward(a, *args, stream=0, check=False, **k)

@@ -342,7 +342,7 @@ def fro_err(y, r):
     return float(np.sqrt(np.sum((y - r) ** 2)) / nr) if nr > 0 else float(np.any(y))
 
 
-@pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["lm", "vit_bwd", "longrange", "large"])
+@pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["tiny", "ragged_lp14", "lm", "vit", "vit_bwd", "longrange", "large"])
 @pytest.mark.parametrize("flags", [0, R | GE])
 def test_uome_backward_parity(name, flags):
     """uoe_uome_backward against the oracle's chain rule (itself pinned by finite differences of
@@ -353,7 +353,7 @@ def test_uome_backward_parity(name, flags):
         cfg = dataclasses.replace(synth.CONFIGS["vit"], l=224, b=16)
         w_std = 0.02
     else:
-        cfg = BWD_CONFIGS[name] if name in BWD_CONFIGS else synth.CONFIGS[name]
+        cfg = BWD_CONFIGS[name] if name in BWD_CONFIGS else get_cfg(name)
         w_std = 0.02 if name in synth.CONFIGS else 0.06
     print(f"uome backward {name} flags={flags}", flush=True)
     inp = synth.make_inputs(cfg, w_std=w_std)
@@ -373,18 +373,23 @@ def test_uome_backward_parity(name, flags):
             "d_a_out": grad_err(got_out, want.d_a_out), "d_gate": gate_err(to_host(d_gate), want.d_gate)}
     fro = max(fro_err(to_host(d_u), want.d_u), fro_err(got_in, want.d_a_in), fro_err(got_out, want.d_a_out),
               fro_err(to_host(d_gate), want.d_gate))
-    assert fro <= 6e-3, fro
+    assert fro <= BWD_FRO[cfg.dtype], fro
     print(f"[uome backward {name} flags={flags}] unused experts {unused.tolist()} " +
           " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {TOL[cfg.dtype]:.0e})", flush=True)
     assert max(errs.values()) <= TOL[cfg.dtype]
 
 
 def test_uome_backward_rejects_unsupported():
-    cfg = small(b=2, l=40, d=64, n_a=2, d_h=32, m=2, c=1, k_a=1, n_m=2, d_e=32, k_m=1, dtype=synth.BF16)
-    blk = B.block_desc(cfg.b, cfg.l, cfg.d, cfg.n_m, cfg.k_m, 1, 1, cfg.d_e, B.BF16, R)
-    assert B.uome_backward_workspace_bytes(blk) == 0       # l % 32 != 0
+    """Shapes off the matrix-core grid and fp32 storage run on the vector-ALU path in expert-selection
+    mode; with patch-wise data selection they are refused (no workspace size, UNSUPPORTED)."""
+    blk = B.block_desc(2, 40, 64, 2, 1, 1, 1, 32, B.BF16, R)
+    assert B.uome_backward_workspace_bytes(blk) > 0        # l % 32 != 0, expert selection: vector-ALU path
     blk = B.block_desc(2, 64, 64, 2, 1, 1, 1, 32, B.F32, R)
-    assert B.uome_backward_workspace_bytes(blk) == 0       # fp32 storage
+    assert B.uome_backward_workspace_bytes(blk) > 0        # fp32 storage, expert selection: vector-ALU path
+    blk = B.block_desc(2, 64, 64, 2, 1, 4, 2, 32, B.F32, R)
+    assert B.uome_backward_workspace_bytes(blk) == 0       # fp32 storage with data selection
+    blk = B.block_desc(2, 56, 64, 2, 1, 4, 2, 32, B.BF16, R)
+    assert B.uome_backward_workspace_bytes(blk) == 0       # 14-token patches with data selection
 
 
 # --------------------------------------------------------------------------- SMHA backward
@@ -412,6 +417,12 @@ CA = B.FLAG_CAUSAL
 # gates, hence a bound of 3e-2 on the worst element and of 6e-3 on the average.
 SMHA_BWD_TOL = 3e-2
 BWD_FRO_TOL = 6e-3
+# fp32 storage (the vector-ALU backward: fp32 arithmetic and fp32 intermediates): each of the ~6 chained
+# contractions of up to d terms adds sqrt(d) * 2^-24 = 1e-6 relative rms, the worst of 10^5 elements sits
+# 5 sigma out: 1e-5 expected, bound 1e-4 on the worst element (the forward's fp32 bound) and 1e-5 on the
+# average.  bf16 storage on that path rounds only the outputs, so the bf16 bounds hold with room to spare.
+SMHA_BWD_TOLS = {synth.BF16: (SMHA_BWD_TOL, 4e-2, BWD_FRO_TOL), synth.F32: (1e-4, 1e-4, 1e-5)}   # tensors, gates, average
+BWD_FRO = {synth.BF16: 6e-3, synth.F32: 1e-5}
 # A gate gradient is a sum of a few row terms r_t = dO_t . o_t (l_p of them for a patch gate), and a dot
 # product of two rounded vectors is in error by eps * |dO_t| * |o_t|, not by eps * |r_t|: terms that
 # cancel leave the error behind, so a gate gradient is judged against the rms of the whole tensor (a
@@ -432,19 +443,23 @@ LAYER_BWD_FRO_TOL = 1e-2
 ROUTER_GRAD_TOL = 5e-2
 
 
-@pytest.mark.parametrize("name,flags", [(nm, fl) for nm in list(SMHA_BWD_CONFIGS) + ["lm"] for fl in (0, R | GE | GP, R | GE | GP | CA)]
-                         + [("longrange", R | GE | GP), ("large", R | GE | GP | CA)])
+@pytest.mark.parametrize("name,flags", [(nm, fl) for nm in list(SMHA_BWD_CONFIGS) + ["lm", "tiny", "ragged_lp14"]
+                                        for fl in (0, R | GE | GP, R | GE | GP | CA)]
+                         + [("vit", R | GE | GP), ("bf16_ragged", R | GE | GP | CA), ("longrange", R | GE | GP),
+                            ("large", R | GE | GP | CA)])
 def test_smha_backward_parity(name, flags):
     run_smha_backward(name, flags, 0)
 
 
-@pytest.mark.parametrize("name,rope_dim", [("sb_small", 32), ("sb_dh64", 16), ("sb_dh128_tail", 64), ("lm", 32)])
+@pytest.mark.parametrize("name,rope_dim", [("sb_small", 32), ("sb_dh64", 16), ("sb_dh128_tail", 64), ("lm", 32), ("tiny", 8),
+                                           ("vit", 32)])
 def test_smha_backward_parity_rope_causal(name, rope_dim):
     """The LM setting: shared causal mask and partial RoPE (the rotation is undone on dq and dk)."""
     run_smha_backward(name, R | GE | GP | CA, rope_dim)
 
 
-@pytest.mark.parametrize("name,flags", [("sb_dh64", R | GE | GP), ("sb_long", R | GE | GP | CA), ("lm", R | GE | GP | CA)])
+@pytest.mark.parametrize("name,flags", [("sb_dh64", R | GE | GP), ("sb_long", R | GE | GP | CA), ("lm", R | GE | GP | CA),
+                                        ("tiny", R | GE | GP | CA), ("ragged_lp14", R | GE | GP)])
 def test_smha_backward_parity_padding_mask(name, flags):
     """Eq. 41 in the backward pass: padded keys are out of every softmax; with the causal mask some
     queries are left without any key and must pass nothing on."""
@@ -454,8 +469,9 @@ def test_smha_backward_parity_padding_mask(name, flags):
 def run_smha_backward(name, flags, rope_dim, pad_frac=0.0):
     """uoe_smha_backward against the oracle's chain rule (itself pinned by finite differences of
     the forward oracle) on the same routing, inputs and upstream gradient; every gradient in full."""
-    cfg = SMHA_BWD_CONFIGS[name] if name in SMHA_BWD_CONFIGS else synth.CONFIGS[name]
+    cfg = SMHA_BWD_CONFIGS[name] if name in SMHA_BWD_CONFIGS else get_cfg(name)
     w_std = 0.02 if name in synth.CONFIGS else 0.06
+    tol, gate_tol, fro_tol = SMHA_BWD_TOLS[cfg.dtype]
     print(f"smha backward {name} flags={flags} rope_dim={rope_dim}", flush=True)
     inp = synth.make_inputs(cfg, w_std=w_std)
     d_out = synth.make_upstream_grad(cfg)
@@ -484,10 +500,10 @@ def run_smha_backward(name, flags, rope_dim, pad_frac=0.0):
     for g in got[1:5]:
         assert not np.any(to_host(g)[unused])
     print(f"[smha backward {name} flags={flags}] unused experts {unused.tolist()} " +
-          " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {SMHA_BWD_TOL:.0e})", flush=True)
-    assert max(v for k, v in errs.items() if "gate" not in k) <= SMHA_BWD_TOL
-    assert max(errs["d_expert_gate"], errs["d_patch_gate"]) <= GATE_GRAD_TOL
-    assert max(fro.values()) <= BWD_FRO_TOL
+          " ".join(f"{k} {v:.3e}" for k, v in errs.items()) + f" (tol {tol:.0e})", flush=True)
+    assert max(v for k, v in errs.items() if "gate" not in k) <= tol
+    assert max(errs["d_expert_gate"], errs["d_patch_gate"]) <= gate_tol
+    assert max(fro.values()) <= fro_tol
 
 
 # --------------------------------------------------------------------------- router backward
@@ -533,7 +549,8 @@ def test_route_backward_parity(name):
 @pytest.mark.parametrize("name,fa,rope_dim", [("sb_dh64", R | GE | GP, 0), ("sb_long", R | GE | GP | CA, 16),
                                               ("lm", R | GE | GP, 0), ("lm", R | GE | GP | CA, 32),
                                               ("ds_bf16_lp32", R | GE | GP, 0), ("ds_lm", R | GE | GP | CA, 32),
-                                              ("longrange", R | GE | GP, 0), ("large", R | GE | GP | CA, 32)])
+                                              ("longrange", R | GE | GP, 0), ("large", R | GE | GP | CA, 32),
+                                              ("tiny", R | GE | GP | CA, 8), ("vit", R | GE | GP, 0)])
 def test_layer_backward_parity(name, fa, rope_dim):
     run_layer_backward(name, fa, rope_dim)
 
@@ -600,9 +617,10 @@ def run_layer_backward(name, fa, rope_dim, pad_frac=0.0):
     print(f"[layer backward {name} fa={fa}] " + " ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
     print(f"[layer backward {name} fa={fa}] fro " + " ".join(f"{k} {v:.2e}" for k, v in fro.items()), flush=True)
     is_router = lambda nm: "_w_expert" in nm or "_w_b" in nm or "_w_a" in nm
-    assert max(v for k, v in errs.items() if not is_router(k)) <= LAYER_BWD_TOL
-    assert max(v for k, v in errs.items() if is_router(k)) <= ROUTER_GRAD_TOL
-    assert max(fro.values()) <= LAYER_BWD_FRO_TOL
+    f32 = cfg.dtype == synth.F32   # fp32 storage: the bounds of the fp32 block tests, the chain twice as long
+    assert max(v for k, v in errs.items() if not is_router(k)) <= (2e-4 if f32 else LAYER_BWD_TOL)
+    assert max(v for k, v in errs.items() if is_router(k)) <= (2e-4 if f32 else ROUTER_GRAD_TOL)
+    assert max(fro.values()) <= (2e-5 if f32 else LAYER_BWD_FRO_TOL)
 
 
 @pytest.mark.parametrize("mode", ["expert_only", "data_only"])
