@@ -152,7 +152,7 @@ static void top_select(const double *v, int count, int keep, int32_t *out, doubl
         } else
             *margin = -1.0;
     }
-    /* sort the kept indices ascending ("restore their original relative position") */
+    /* the kept indices are reported in ascending order (Sec. III-B, the text after Eq. 17) */
     for (int a = 0; a < keep; ++a) {
         int p = a;
         int val = ord[a];
