@@ -622,6 +622,7 @@ int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_w
     f.b = blk->b; f.l = blk->l; f.d = blk->d; f.n = blk->n; f.k = blk->k; f.m = blk->m; f.c = blk->c;
     f.d_h = blk->width; f.flags = blk->flags & UOE_FLAG_CAUSAL;  // the recomputed o carries no gate
     f.rope_dim = blk->rope_dim; f.pad_mask = pad_mask;
+    f.keep_v_bf16 = 1;   // the attention gradient kernels take v in bf16
     if (!smha_bwd_mfma(blk)) {
         f.q = at(ws, s.g_q); f.kk = at(ws, s.g_k); f.v = at(ws, s.g_v); f.o = at(ws, s.g_o);
         a.d_out = d_out; a.expert_gate = expert_gate; a.patch_gate = patch_gate; a.flags = blk->flags;

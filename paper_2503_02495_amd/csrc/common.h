@@ -102,6 +102,8 @@ struct SmhaArgs {
     int32_t *inv_cnt, *inv_ent;               // [b,m], [b,m,k]: which (slot s, pick t) chose patch p
     float *lse;                               // [b*k, l_a] or NULL: base-2 log-sum-exp of each query's scaled logits
                                               // (MFMA attention only; kept for the backward pass)
+    int keep_v_bf16;                          // 1: the MFMA path leaves v in bf16 (the backward pass reads it); 0: it
+                                              // writes v as fp16, the operand format of the attention kernel's P V
     uint32_t skip;                            // steps NOT to run (SMHA_STEP_* bits; 0 = the whole block): a caller
                                               // that times one step runs it on what the others left in the workspace
 };

@@ -104,6 +104,20 @@ template <typename P> struct writes_f32<P, std::void_t<decltype(P::kF32Out)>> {
     static constexpr bool value = P::kF32Out;
 };
 
+// problems that store some column blocks as fp16 instead of bf16 declare f16_col(column)
+template <typename P, typename = void> struct has_f16_cols {
+    static constexpr bool value = false;
+};
+template <typename P> struct has_f16_cols<P, std::void_t<decltype(&P::f16_col)>> {
+    static constexpr bool value = true;
+};
+// two fp32 -> packed fp16, round to nearest even
+__device__ __forceinline__ uint32_t pack2_f16_rn(float a, float b)
+{
+    const _Float16 ha = (_Float16)a, hb = (_Float16)b;
+    return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
+}
+
 template <typename P, int TM, int TN, int SPITCH>
 __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN], uint16_t (*stage)[SPITCH], const float *coltab,
                                               const float (&rs)[TM], int g, int grow0, int gcol0, int wcol0, int M, int N,
@@ -136,11 +150,15 @@ __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN
             const int cl = j * 32 + qg * 8 + lh * 4;  // first of 4 consecutive columns, wave-local
             float sc = 1.0f;
             if constexpr (P::kColScale) sc = coltab[(wcol0 + cl) >> 3];
+            bool half = false;   // uniform over the wave: a column block's format
+            if constexpr (has_f16_cols<P>::value) half = p.f16_col(gcol0 + j * 32 + qg * 8);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const float s2 = P::kRowScale ? sc * rs[i] : sc;
-                const uint32_t w0 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 0], s2), p.epi(acc[i][j][qg * 4 + 1], s2));
-                const uint32_t w1 = pack2_bf16(p.epi(acc[i][j][qg * 4 + 2], s2), p.epi(acc[i][j][qg * 4 + 3], s2));
+                const float e0 = p.epi(acc[i][j][qg * 4 + 0], s2), e1 = p.epi(acc[i][j][qg * 4 + 1], s2);
+                const float e2 = p.epi(acc[i][j][qg * 4 + 2], s2), e3 = p.epi(acc[i][j][qg * 4 + 3], s2);
+                const uint32_t w0 = half ? pack2_f16_rn(e0, e1) : pack2_bf16(e0, e1);
+                const uint32_t w1 = half ? pack2_f16_rn(e2, e3) : pack2_bf16(e2, e3);
                 *reinterpret_cast<uint2 *>(&stage[i * 32 + lr][cl]) = make_uint2(w0, w1);
             }
         }

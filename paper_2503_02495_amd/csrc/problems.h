@@ -61,6 +61,8 @@ template <typename T, bool F32 = false> struct QkvProblem {
     int l, d, n, kact, m, c, l_p, l_a, d_h;
     float q_scale;  // folded into q on the way out (1 for the plain layout)
     int nout;       // 3: q, k and v; 1: the first projection only (N = d_h)
+    int v_f16 = 0;  // MFMA engines, bf16 storage: v is written as fp16 (what the attention kernel's P V product takes)
+    __device__ bool f16_col(int nn) const { return v_f16 && nn >= 2 * d_h; }
 
     __device__ int rows(int) const { return l_a; }
     __device__ int kdim(int) const { return d; }

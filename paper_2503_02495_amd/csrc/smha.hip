@@ -193,8 +193,10 @@ template <typename T> static hipError_t launch_attention_generic(const SmhaArgs 
 // is kept to a max, an exp2, an add and half a convert per score:
 //  * P V runs in fp16 (v_mfma_f32_32x32x16_f16): probabilities carry 11 significant bits, enough for
 //    the 2e-2 bound with one MFMA pass (a bf16 P needs a (hi, lo) pair: twice the MFMAs plus the split
-//    arithmetic).  V is converted bf16 -> fp16 while its tile is staged into LDS (exact for
-//    |v| in [6.1e-5, 65504]; larger magnitudes saturate, smaller ones lose low bits).
+//    arithmetic).  The projection kernel writes V as fp16 straight from its fp32 accumulators (VF16;
+//    11 significant bits instead of bf16's 8, |v| up to 65504).  When the caller needs V in bf16 (the
+//    backward pass) the kernel converts bf16 -> fp16 while it stages the tile instead (exact for
+//    |v| in [6.1e-5, 65504]).
 //  * The running maximum is subtracted by the matrix pipe: the score accumulators are initialised
 //    with -m instead of 0.  As long as no score of a tile exceeds the running maximum by more than
 //    2^8 the tile needs no rescaling at all (p = exp2(s - m) <= 256 fits fp16 and fp32 sums); only
@@ -211,7 +213,7 @@ __device__ __forceinline__ uint32_t pack2_f16(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));  // toward zero: never rounds up to inf
 }
 
-template <int DH, int NQ, int KSPLIT>
+template <int DH, int NQ, int KSPLIT, bool VF16>
 __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArgs a)
 {
     constexpr int BKV = 64, KP = DH + 8, VP = 2 * b_pitch_dwords(DH), NTH = NQ * 64;  // NTH: threads that stage one split's tiles
@@ -223,12 +225,28 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
     constexpr int LDS_BYTES = KSPLIT * SPLIT_BYTES > MERGE_BYTES ? KSPLIT * SPLIT_BYTES : MERGE_BYTES;
     __shared__ __align__(16) unsigned char lds_raw[LDS_BYTES];
 
-    const int g = blockIdx.y;
     const int l_p = a.l / a.m, l_a = a.c * l_p;
+    // Workgroup -> (unit, query block).  Hardware deals consecutive workgroup ids round-robin over the 8
+    // XCDs, each with its own L2: the query blocks of one unit are given ids 8 apart, so that a unit's K and
+    // V are fetched into one L2 only (units in groups of 8; a ragged last group keeps the plain order).
+    int g, qblk;
+    {
+        const int nqb = (l_a + 32 * NQ - 1) / (32 * NQ), units = a.b * a.k, id = blockIdx.x;
+        const int full = (units / 8) * 8 * nqb;   // ids that belong to whole groups of 8 units
+        if (id < full) {
+            const int grp = id / (8 * nqb), rem = id - grp * 8 * nqb;
+            g = grp * 8 + (rem & 7);
+            qblk = rem >> 3;
+        } else {
+            const int rem = id - full;
+            g = (units / 8) * 8 + rem / nqb;
+            qblk = rem % nqb;
+        }
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile tests stay scalar
     const int split = wave / NQ, qg = wave - split * NQ, stid = tid - split * NTH;  // key split, query group, thread within the split
     const int lr = lane & 31, lh = lane >> 5;
-    const int qrow = blockIdx.x * (32 * NQ) + qg * 32 + lr;
+    const int qrow = qblk * (32 * NQ) + qg * 32 + lr;
     unsigned char *sbase = lds_raw + (size_t)split * SPLIT_BYTES;
     uint16_t(*Ks)[BKV][KP] = reinterpret_cast<uint16_t(*)[BKV][KP]>(sbase);
     uint16_t(*Vs)[BKV][VP] = reinterpret_cast<uint16_t(*)[BKV][VP]>(sbase + K_BYTES);   // fp16, [key][d_h]
@@ -308,18 +326,21 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
             const int c = stid + i * NTH;
             {
                 *reinterpret_cast<uint4 *>(&Ks[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = make_uint4(sr.k[i][0], sr.k[i][1], sr.k[i][2], sr.k[i][3]);
-                // bf16 -> fp16: widen to fp32 (a shift), then narrow; exact whenever fp16 can hold the value
                 const uint32_t u[4] = {sr.v[i][0], sr.v[i][1], sr.v[i][2], sr.v[i][3]};
                 uint32_t h[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = pack2_f16(__uint_as_float(u[e] << 16), __uint_as_float(u[e] & 0xFFFF0000u));
+                for (int e = 0; e < 4; ++e) {
+                    // a bf16 v: widen to fp32 (a shift), then narrow; exact whenever fp16 can hold the value
+                    if constexpr (VF16) h[e] = u[e];
+                    else h[e] = pack2_f16(__uint_as_float(u[e] << 16), __uint_as_float(u[e] & 0xFFFF0000u));
+                }
                 *reinterpret_cast<uint4 *>(&Vs[buf][c / (DH / 8)][(c % (DH / 8)) * 8]) = make_uint4(h[0], h[1], h[2], h[3]);
             }
         }
     };
 
     // under the causal mask no query of this workgroup sees keys past the workgroup's last row
-    const int key_end = causal ? min(l_a, (int)(blockIdx.x + 1) * 32 * NQ) : l_a;
+    const int key_end = causal ? min(l_a, (qblk + 1) * 32 * NQ) : l_a;
     const int nkt = (key_end + BKV - 1) / BKV;
     const int nit = (nkt + KSPLIT - 1) / KSPLIT;   // iterations: split s takes tiles s, s + KSPLIT, ...
     auto tile_of = [&](int it) { return it * KSPLIT + split; };   // this split's it-th tile (exists if < nkt)
@@ -353,7 +374,7 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
             // accumulator register q of tile t is key kt*64 + t*32 + (q/4)*8 + lh*4 + q%4.  Masks: a wave-uniform
             // test whether the tile can hold an inadmissible key for any query of the wave, then straight-line
             // selects (accumulators must not cross divergent branches).
-            const int qrow_first = blockIdx.x * (32 * NQ) + qg * 32;
+            const int qrow_first = qblk * (32 * NQ) + qg * 32;
             if ((kt + 1) * BKV > l_a || masked || (causal && (kt + 1) * BKV > qrow_first + 1)) {
                 uint32_t kmw[2][4];   // the padding flags of this lane's keys, four consecutive keys per word
 #pragma unroll
@@ -496,8 +517,9 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
 template <int DH, int NQ, int KSPLIT> static void launch_attention_shape(const SmhaArgs &a, hipStream_t st)
 {
     const int l_a = a.c * (a.l / a.m), units = a.b * a.k;
-    hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT>), dim3((l_a + 32 * NQ - 1) / (32 * NQ), units), dim3(NQ * KSPLIT * 64), 0,
-                       st, a);
+    const dim3 grid(((l_a + 32 * NQ - 1) / (32 * NQ)) * units), block(NQ * KSPLIT * 64);
+    if (a.keep_v_bf16) hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT, false>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT, true>), grid, block, 0, st, a);
 }
 
 template <int DH> static hipError_t launch_attention_mfma_dh(const SmhaArgs &a, hipStream_t st)
@@ -609,6 +631,7 @@ static hipError_t smha_mfma_qkv_attention(const SmhaArgs &a, hipStream_t st)
     // the MFMA kernel addresses one unit's keys with 32-bit element offsets
     const bool mfma_attn = (a.d_h == 32 || a.d_h == 64 || a.d_h == 128) && (long)l_a * a.d_h < (1L << 31);
     if (mfma_attn) qp.q_scale = 1.4426950408889634f / sqrtf((float)a.d_h);  // base-2 softmax in the MFMA kernel
+    qp.v_f16 = mfma_attn && !a.keep_v_bf16;
     // one workgroup row-tile computes q, k and v together so the gathered rows are read once
     // 128-row tiles for long units (measured faster from l_a = 512 up), 32-row tiles for short ones
     auto projections = [&]() -> hipError_t {
