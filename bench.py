@@ -421,6 +421,10 @@ def main() -> int:
         work = kernel_work(cfg, es)
         launches = max(5, min(args.steps, 50))
         ridge = peak_tf * 1e12 / (PEAK_HBM_GBS * 1e9)
+        # HBM-side bytes per launch measured with hardware counters (profiles/traffic.json, written from the
+        # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries beside it), where a summary covers the kernel
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        measured_traffic = json.load(open(tpath)) if os.path.exists(tpath) else {}
         for name in ("route_expert_a", "route_data_a", "route_a", "gather", "smha_qkv", "smha_attention", "smha_out",
                      "route_m", "uome_up", "uome_down"):
             if name not in calls:
@@ -438,6 +442,7 @@ def main() -> int:
                             "unit": unit, "frac": round(ach / peak, 4), "us_per_launch": round(ms * 1e3, 2),
                             "flops": w["flops"], "bytes": w["bytes"], "GBs": round(gbs, 1), "TFLOPs": round(tfs, 2),
                             "launches_timed": launches, "host_stayed_ahead": ahead,
+                            "traffic": measured_traffic.get(f"{name}:{cfg.name}"),
                             "note": {"route_expert_a": "expert router + its selection kernel",
                                      "route_data_a": "data router + reduction + selection kernels",
                                      "route_a": "the whole SMHA routing call (both routers, selection)",
@@ -446,10 +451,7 @@ def main() -> int:
         # the dominant kernel: the single-kernel stage that takes the most time
         single = [k for k in kernels if k["kernel"] not in ("route_a", "gather")]
         dom = max(single, key=lambda k: k["us_per_launch"])
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "traffic.json")
-        if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get(f"{dom['kernel']}:{cfg.name}")
+        traffic = measured_traffic.get(f"{dom['kernel']}:{cfg.name}")
         roofline = {"kernel": f"{dom['kernel']} ({dom['eq']})", "bound": dom["bound"], "achieved": dom["achieved"],
                     "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic,
                     "algorithmic_flops_per_launch": dom["flops"], "algorithmic_bytes_per_launch": dom["bytes"],
