@@ -1,12 +1,14 @@
 // Backward passes of the SMHA block (Eq. 27-36, Eq. 32 RoPE, the masks of Sec. III-C.3) and of the UoME block
 // in expert-selection mode (Eq. 38-40 with Eq. 24-26) for every shape and storage type the matrix-core
 // kernels do not take: fp32 storage, head or expert widths and token counts that are not multiples of 32
-// (a 14-token patch, a 196-token sequence).  Same formulas as smha_bwd.hip / uome_bwd.hip, written as plain
-// vector-ALU kernels, one thread per output element with its contraction as a loop in fixed order (no
-// atomics: results do not depend on scheduling).  Every intermediate lives in fp32 in the workspace,
-// whatever the storage type; the softmax probabilities and their gradients are materialised
-// ([units, l_a, l_a]), which is what bounds the sizes this path is meant for.  It favours generality over
-// speed.
+// (a 14-token patch, a 196-token sequence).  Same formulas as smha_bwd.hip / uome_bwd.hip on the vector ALU.
+// The UoME block's contractions run through one small tiled engine (gen_gemm: 64x64 output tile, 16-deep K
+// steps through LDS, 4x4 outputs per thread, operands fetched element by element through a functor that does
+// the routing lookups); the SMHA block's kernels are one thread per output element with the contraction
+// as a loop.  Every sum has a fixed order (no atomics: results do not depend on scheduling).
+// Every intermediate lives in fp32 in the workspace, whatever the storage type; the softmax probabilities
+// and their gradients are materialised ([units, l_a, l_a]), which is what bounds the sizes this path is
+// meant for.  It favours generality over speed.
 #include "common.h"
 
 namespace uoe {
@@ -17,30 +19,99 @@ constexpr int GT = 256;  // threads per block of every kernel here
 
 inline dim3 blocks_for(long total) { return dim3((unsigned)((total + GT - 1) / GT)); }
 
+// ------------------------------------------------------------------------------------------ tiled engine
+// C[m][n] = sum over segments, sum over k of A(m,k) B(k,n) for one group g = blockIdx.z.  A functor F gives
+//   rows(g), cols(g), nseg(g); seg(g, s, ctx) -> false to skip a segment; klen(ctx);
+//   lhs(ctx, g, m, k), rhs(ctx, g, k, n) as fp32; store(g, m, n, sum)
+// and says which index is contiguous in memory for each operand (A_K_FAST / B_K_FAST) so that adjacent
+// threads fetch adjacent elements.  Segments and K steps are walked in order: fixed summation order.
+template <typename F> __global__ __launch_bounds__(GT) void gen_gemm(F f)
+{
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float As[BK][BM + 4], Bs[BK][BN + 4];
+    const int g = blockIdx.z, M = f.rows(g), N = f.cols(g);
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    if (m0 >= M || n0 >= N) return;   // uniform over the workgroup
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    const int nseg = f.nseg(g);
+    for (int sg = 0; sg < nseg; ++sg) {
+        typename F::Ctx ctx;
+        if (!f.seg(g, sg, ctx)) continue;   // uniform
+        const int K = f.klen(ctx);
+        for (int k0 = 0; k0 < K; k0 += BK) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = tid + i * GT;
+                const int ak = F::A_K_FAST ? e % BK : e / BM, am = F::A_K_FAST ? e / BK : e % BM;
+                As[ak][am] = (m0 + am < M && k0 + ak < K) ? f.lhs(ctx, g, m0 + am, k0 + ak) : 0.f;
+                const int bk = F::B_K_FAST ? e % BK : e / BN, bn = F::B_K_FAST ? e / BK : e % BN;
+                Bs[bk][bn] = (n0 + bn < N && k0 + bk < K) ? f.rhs(ctx, g, k0 + bk, n0 + bn) : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < BK; ++kk) {
+                float av[4], bv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) av[i] = As[kk][ty * 4 + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+            }
+            __syncthreads();
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (m < M && n < N) f.store(g, m, n, acc[i][j]);
+        }
+}
+
+template <typename F> hipError_t launch_gen_gemm(const F &f, int groups, int max_rows, int max_cols, hipStream_t st)
+{
+    if (groups <= 0 || max_rows <= 0 || max_cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL((gen_gemm<F>), dim3((max_cols + 63) / 64, (max_rows + 63) / 64, groups), dim3(GT), 0, st, f);
+    return hipGetLastError();
+}
+
+struct NoCtx {};
+
 // ------------------------------------------------------------------------------------------ UoME
 // a.z and a.dh are fp32 [b, l, k*d_e] here: Z then H, dH_raw then dZ.
 
-// Z = u W1_b and dH = d_out W2_b^T: thread = (token row, hidden column)
-template <typename T> __global__ __launch_bounds__(GT) void gen_uome_z_dh(UomeBwdArgs a)
-{
-    const long W = (long)a.k * a.d_e, total = (long)a.b * a.l * W;
-    const long idx = (long)blockIdx.x * GT + threadIdx.x;
-    if (idx >= total) return;
-    const long row = idx / W;
-    const int col = (int)(idx - row * W), bb = (int)(row / a.l);
-    const int s = col / a.d_e, e = col - s * a.d_e;
-    const int i = clampi(a.expert_idx[bb * a.k + s], a.n);
-    const T *ur = static_cast<const T *>(a.u) + row * a.d, *gr = static_cast<const T *>(a.d_out) + row * a.d;
-    const T *wi = static_cast<const T *>(a.a_in) + (size_t)i * a.d * a.d_e + e;          // column e of A^I_i
-    const T *wo = static_cast<const T *>(a.a_out) + ((size_t)i * a.d_e + e) * a.d;       // row e of A^O_i
-    float z = 0.f, dh = 0.f;
-    for (int j = 0; j < a.d; ++j) {
-        z = fmaf(to_f32(ur[j]), to_f32(wi[(size_t)j * a.d_e]), z);
-        dh = fmaf(to_f32(gr[j]), to_f32(wo[j]), dh);
+// Z = u W1_b (second = false) and dH = d_out W2_b^T (second = true): group = sample, [l] x [k*d_e], K = d
+template <typename T, bool second> struct GenUomeProj {
+    UomeBwdArgs a;
+    typedef NoCtx Ctx;
+    static constexpr bool A_K_FAST = true, B_K_FAST = second;   // A^I [d][d_e] runs along the columns, A^O [d_e][d] along K
+    __device__ int rows(int) const { return a.l; }
+    __device__ int cols(int) const { return a.k * a.d_e; }
+    __device__ int nseg(int) const { return 1; }
+    __device__ bool seg(int, int, Ctx &) const { return true; }
+    __device__ int klen(const Ctx &) const { return a.d; }
+    __device__ float a_(const T *base, int g, int m, int k) const { return to_f32(base[((size_t)g * a.l + m) * a.d + k]); }
+    __device__ float lhs(const Ctx &, int g, int m, int k) const { return a_(static_cast<const T *>(second ? a.d_out : a.u), g, m, k); }
+    __device__ float rhs(const Ctx &, int g, int k, int n) const
+    {
+        const int s = n / a.d_e, e = n - s * a.d_e, i = clampi(a.expert_idx[g * a.k + s], a.n);
+        return second ? to_f32(static_cast<const T *>(a.a_out)[((size_t)i * a.d_e + e) * a.d + k])
+                      : to_f32(static_cast<const T *>(a.a_in)[((size_t)i * a.d + k) * a.d_e + e]);
     }
-    static_cast<float *>(a.z)[idx] = z;
-    static_cast<float *>(a.dh)[idx] = dh;
-}
+    __device__ void store(int g, int m, int n, float v) const
+    {
+        static_cast<float *>(second ? a.dh : a.z)[((size_t)g * a.l + m) * ((size_t)a.k * a.d_e) + n] = v;
+    }
+};
 
 // H = SiLU(Z) w, dZ = dH w SiLU'(Z) in place, and d_gate[b, i(s)] = sum dH SiLU(Z): block = (slot, sample),
 // each thread a strided subset of the slot's l*d_e elements in index order, then a fixed tree
@@ -78,48 +149,75 @@ __global__ __launch_bounds__(GT) void gen_uome_mid(UomeBwdArgs a)
     if ((a.flags & F_GATE_EXPERT) && tid == 0) a.d_gate[(size_t)bb * a.n + i] = red[0];
 }
 
-// d_u = (d_out) + dZ W1_b^T: thread = (token row, model column j)
-template <typename T> __global__ __launch_bounds__(GT) void gen_uome_du(UomeBwdArgs a)
-{
-    const long total = (long)a.b * a.l * a.d, idx = (long)blockIdx.x * GT + threadIdx.x;
-    if (idx >= total) return;
-    const long row = idx / a.d;
-    const int j = (int)(idx - row * a.d), bb = (int)(row / a.l);
-    const long W = (long)a.k * a.d_e;
-    float acc = (a.flags & F_RESIDUAL) ? to_f32(static_cast<const T *>(a.d_out)[idx]) : 0.f;
-    for (int s = 0; s < a.k; ++s) {
-        const int i = clampi(a.expert_idx[bb * a.k + s], a.n);
-        const T *wi = static_cast<const T *>(a.a_in) + ((size_t)i * a.d + j) * a.d_e;  // row j of A^I_i
-        const float *dz = static_cast<const float *>(a.dh) + row * W + (long)s * a.d_e;
-        for (int e = 0; e < a.d_e; ++e) acc = fmaf(dz[e], to_f32(wi[e]), acc);
+// d_u = (d_out) + dZ W1_b^T: group = sample, [l] x [d], K = k*d_e (slot s, hidden column e)
+template <typename T> struct GenUomeDu {
+    UomeBwdArgs a;
+    typedef NoCtx Ctx;
+    static constexpr bool A_K_FAST = true, B_K_FAST = true;
+    __device__ int rows(int) const { return a.l; }
+    __device__ int cols(int) const { return a.d; }
+    __device__ int nseg(int) const { return 1; }
+    __device__ bool seg(int, int, Ctx &) const { return true; }
+    __device__ int klen(const Ctx &) const { return a.k * a.d_e; }
+    __device__ float lhs(const Ctx &, int g, int m, int kk) const
+    {
+        return static_cast<const float *>(a.dh)[((size_t)g * a.l + m) * ((size_t)a.k * a.d_e) + kk];
     }
-    static_cast<T *>(a.d_u)[idx] = from_f32<T>(acc);
-}
+    __device__ float rhs(const Ctx &, int g, int kk, int j) const
+    {
+        const int s = kk / a.d_e, e = kk - s * a.d_e, i = clampi(a.expert_idx[g * a.k + s], a.n);
+        return to_f32(static_cast<const T *>(a.a_in)[((size_t)i * a.d + j) * a.d_e + e]);
+    }
+    __device__ void store(int g, int m, int j, float v) const
+    {
+        const size_t at = ((size_t)g * a.l + m) * a.d + j;
+        if (a.flags & F_RESIDUAL) v += to_f32(static_cast<const T *>(a.d_out)[at]);
+        static_cast<T *>(a.d_u)[at] = from_f32<T>(v);
+    }
+};
 
-// dA^O_i [d_e, d] = sum H_{b,s}^T d_out_b and dA^I_i [d, d_e] = sum u_b^T dZ_{b,s} over the (sample, slot)
-// pairs that selected expert i, samples then slots then tokens in order: thread = one weight element
-template <typename T> __global__ __launch_bounds__(GT) void gen_uome_dw(UomeBwdArgs a)
-{
-    const long per = (long)a.n * a.d * a.d_e, idx = (long)blockIdx.x * GT + threadIdx.x;
-    if (idx >= 2 * per) return;
-    const bool second = idx >= per;   // false: dA^O, true: dA^I
-    const long q = second ? idx - per : idx;
-    const int i = (int)(q / ((long)a.d * a.d_e));
-    const long rem = q - (long)i * a.d * a.d_e;
-    const int e = second ? (int)(rem % a.d_e) : (int)(rem / a.d), j = second ? (int)(rem / a.d_e) : (int)(rem % a.d);
-    const long W = (long)a.k * a.d_e;
-    const float *hb = static_cast<const float *>(a.z), *dzb = static_cast<const float *>(a.dh);
-    const T *left = static_cast<const T *>(second ? a.u : a.d_out);
-    float acc = 0.f;
-    for (int bb = 0; bb < a.b; ++bb)
-        for (int s = 0; s < a.k; ++s) {
-            if (clampi(a.expert_idx[bb * a.k + s], a.n) != i) continue;
-            const float *act = (second ? dzb : hb) + (long)bb * a.l * W + (long)s * a.d_e + e;
-            const T *tok = left + (long)bb * a.l * a.d + j;
-            for (int t = 0; t < a.l; ++t) acc = fmaf(act[(long)t * W], to_f32(tok[(long)t * a.d]), acc);
-        }
-    static_cast<T *>(second ? a.d_a_in : a.d_a_out)[q] = from_f32<T>(acc);
-}
+// dA^O_i [d_e, d] = sum H_{b,s}^T d_out_b (groups 0..n-1) and dA^I_i [d, d_e] = sum u_b^T dZ_{b,s} (groups
+// n..2n-1): segments = the (sample, slot) pairs in order, those of other experts skipped; K = the l tokens
+template <typename T> struct GenUomeDw {
+    UomeBwdArgs a;
+    struct Ctx {
+        int bb, s;
+    };
+    static constexpr bool A_K_FAST = false, B_K_FAST = false;
+    __device__ bool second(int g) const { return g >= a.n; }
+    __device__ int rows(int g) const { return second(g) ? a.d : a.d_e; }
+    __device__ int cols(int g) const { return second(g) ? a.d_e : a.d; }
+    __device__ int nseg(int) const { return a.b * a.k; }
+    __device__ bool seg(int g, int sg, Ctx &c) const
+    {
+        c.bb = sg / a.k;
+        c.s = sg - c.bb * a.k;
+        return clampi(a.expert_idx[sg], a.n) == (second(g) ? g - a.n : g);
+    }
+    __device__ int klen(const Ctx &) const { return a.l; }
+    __device__ float act(const float *buf, const Ctx &c, int t, int e) const
+    {
+        return buf[((size_t)c.bb * a.l + t) * ((size_t)a.k * a.d_e) + (size_t)c.s * a.d_e + e];
+    }
+    __device__ float tok(const void *p, const Ctx &c, int t, int j) const
+    {
+        return to_f32(static_cast<const T *>(p)[((size_t)c.bb * a.l + t) * a.d + j]);
+    }
+    __device__ float a_(const Ctx &c, int g, int m, int t) const
+    {
+        return second(g) ? tok(a.u, c, t, m) : act(static_cast<const float *>(a.z), c, t, m);
+    }
+    __device__ float lhs(const Ctx &c, int g, int m, int t) const { return a_(c, g, m, t); }
+    __device__ float rhs(const Ctx &c, int g, int t, int n) const
+    {
+        return second(g) ? act(static_cast<const float *>(a.dh), c, t, n) : tok(a.d_out, c, t, n);
+    }
+    __device__ void store(int g, int m, int n, float v) const
+    {
+        if (second(g)) static_cast<T *>(a.d_a_in)[((size_t)(g - a.n) * a.d + m) * a.d_e + n] = from_f32<T>(v);
+        else static_cast<T *>(a.d_a_out)[((size_t)g * a.d_e + m) * a.d + n] = from_f32<T>(v);
+    }
+};
 
 // ------------------------------------------------------------------------------------------ SMHA
 // fp32 workspace: f.q, f.kk, f.v, f.o and do_raw [units, l_a, d_h]; dqkv [units, l_a, 3*d_h] as [dq | dk | dv];
@@ -429,16 +527,14 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw(SmhaBwdA
 
 template <typename T> hipError_t uome_backward_generic(const UomeBwdArgs &a, hipStream_t st)
 {
-    const long W = (long)a.k * a.d_e;
+    const int W = a.k * a.d_e;
     hipError_t err;
-    hipLaunchKernelGGL((gen_uome_z_dh<T>), blocks_for((long)a.b * a.l * W), dim3(GT), 0, st, a);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
+    if ((err = launch_gen_gemm(GenUomeProj<T, false>{a}, a.b, a.l, W, st)) != hipSuccess) return err;
+    if ((err = launch_gen_gemm(GenUomeProj<T, true>{a}, a.b, a.l, W, st)) != hipSuccess) return err;
     hipLaunchKernelGGL(gen_uome_mid, dim3(a.k, a.b), dim3(GT), 0, st, a);
     if ((err = hipGetLastError()) != hipSuccess) return err;
-    hipLaunchKernelGGL((gen_uome_du<T>), blocks_for((long)a.b * a.l * a.d), dim3(GT), 0, st, a);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
-    hipLaunchKernelGGL((gen_uome_dw<T>), blocks_for(2L * a.n * a.d * a.d_e), dim3(GT), 0, st, a);
-    return hipGetLastError();
+    if ((err = launch_gen_gemm(GenUomeDu<T>{a}, a.b, a.l, a.d, st)) != hipSuccess) return err;
+    return launch_gen_gemm(GenUomeDw<T>{a}, 2 * a.n, a.d > a.d_e ? a.d : a.d_e, a.d > a.d_e ? a.d : a.d_e, st);
 }
 
 template <typename T> hipError_t smha_backward_generic(const SmhaBwdArgs &a, hipStream_t st)
