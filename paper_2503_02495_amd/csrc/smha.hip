@@ -618,6 +618,9 @@ template <typename OP> static hipError_t launch_outproj_dma(const OP &op, int gr
 {
     if (groups >= 512 && l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 2, 2, 4>(op, groups, l_p, d, st);
     if (l_p <= 32) return launch_gemm_dma<OP, 32, 128, 32, 1, 4, 4, 2>(op, groups, l_p, d, st);
+    // many 64-row groups: four workgroups per CU with two stage buffers each (more of the short dependent
+    // chains in flight: out-projection of the large shape 40.5 -> 35.9 us)
+    if ((long)groups * ((d + 127) / 128) >= 2048) return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 2, 4>(op, groups, l_p, d, st);
     return launch_gemm_dma<OP, 64, 128, 32, 2, 2, 4, 2>(op, groups, l_p, d, st);
 }
 
