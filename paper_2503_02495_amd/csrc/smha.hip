@@ -396,7 +396,12 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, sacc[t][q]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));   // largest score of the tile, relative to the running maximum
+            {   // largest score of the tile, relative to the running maximum: the other half-wave's value through
+                // v_permlane32_swap (lanes 32-63 of the first result and lanes 0-31 of the second hold the partner's)
+                const uint32_t tb = __float_as_uint(tmax);
+                const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
+                tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
             // the maximum moves only when a score exceeds it by more than 2^TAU, or when there is none yet
             const bool move = tmax > TAU || (mrun == -INFINITY && tmax > -INFINITY);
             if (__builtin_amdgcn_ballot_w64(move) != 0) {   // wave-uniform: rare after the first tile
