@@ -213,12 +213,112 @@ __device__ __forceinline__ uint32_t pack2_f16(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));  // toward zero: never rounds up to inf
 }
 
+// One key tile of 64 keys for the 32 queries of a wave: scores, masks, the lazy running maximum, probabilities and
+// O^T += V^T P^T.  kfrag(t, ks) gives the K fragment of accumulator tile t (keys t*32 + lane%32) for k-step ks,
+// vfrag(s4, td) the V^T fragment of key step s4 for head-dim block td; km points at the tile's padding flags
+// (one byte per key) or is NULL.  The staging of K and V is the caller's.
+template <int DH, typename KF, typename VF>
+__device__ __forceinline__ void attention_tile(const bf16x8_t (&qf)[DH / 16], f32x16_t (&oacc)[DH / 32], float &mrun, float &lsum, int kt,
+                                               int l_a, int qrow, int qrow_first, bool causal, const unsigned char *km, int lane,
+                                               KF kfrag, VF vfrag)
+{
+    constexpr int BKV = 64;
+    constexpr float TAU = 8.0f;
+    const int lh = lane >> 5;
+    const bool masked = km != nullptr;
+    // S^T tile: [64 keys x 32 queries] as two 32x32 accumulators, started at -m
+    const float moff = mrun == -INFINITY ? 0.f : mrun;
+    f32x16_t sacc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) sacc[t][q] = -moff;
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const bf16x8_t kf = kfrag(t, ks);
+            sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
+        }
+    // accumulator register q of tile t is key kt*64 + t*32 + (q/4)*8 + lh*4 + q%4.  Masks: a wave-uniform
+    // test whether the tile can hold an inadmissible key for any query of the wave, then straight-line
+    // selects (accumulators must not cross divergent branches).
+    if ((kt + 1) * BKV > l_a || masked || (causal && (kt + 1) * BKV > qrow_first + 1)) {
+        uint32_t kmw[2][4];   // the padding flags of this lane's keys, four consecutive keys per word
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq)
+                kmw[t][gq] = masked ? *reinterpret_cast<const uint32_t *>(km + t * 32 + gq * 8 + lh * 4) : 0x01010101u;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int key = kt * BKV + t * 32 + (q >> 2) * 8 + lh * 4 + (q & 3);
+                const bool ok = key < l_a && (!causal || key <= qrow) && ((kmw[t][q >> 2] >> ((q & 3) * 8)) & 0xFFu) != 0;
+                sacc[t][q] = ok ? sacc[t][q] : -INFINITY;
+            }
+    }
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, sacc[t][q]);
+    {   // largest score of the tile, relative to the running maximum: the other half-wave's value through
+        // v_permlane32_swap (lanes 32-63 of the first result and lanes 0-31 of the second hold the partner's)
+        const uint32_t tb = __float_as_uint(tmax);
+        const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
+        tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
+    // the maximum moves only when a score exceeds it by more than 2^TAU, or when there is none yet
+    const bool move = tmax > TAU || (mrun == -INFINITY && tmax > -INFINITY);
+    if (__builtin_amdgcn_ballot_w64(move) != 0) {   // wave-uniform: rare after the first tile
+        if (move) {
+            const float corr = mrun == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(-tmax);
+            mrun = moff + tmax;
+            lsum *= corr;
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) oacc[t][q] *= corr;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) sacc[t][q] -= tmax;
+        }
+    }
+    float psum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const float pv = __builtin_amdgcn_exp2f(sacc[t][q]);   // exp2(-inf) = 0 for masked keys
+            sacc[t][q] = pv;
+            psum += pv;
+        }
+    lsum += psum;
+
+    // O^T += V^T P^T over the 64 keys of the tile: four k-steps of 16 keys
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int t = s4 >> 1, r0 = (s4 & 1) * 8;
+        uint32_t ph[4];  // two probabilities per word, fp16
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ph[e] = pack2_f16(sacc[t][r0 + 2 * e], sacc[t][r0 + 2 * e + 1]);
+        const f16x8_t pf = __builtin_bit_cast(f16x8_t, make_uint4(ph[0], ph[1], ph[2], ph[3]));
+#pragma unroll
+        for (int td = 0; td < DH / 32; ++td) {
+            const f16x8_t vf = vfrag(s4, td);
+            oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, oacc[td], 0, 0, 0);
+        }
+    }
+}
+
 template <int DH, int NQ, int KSPLIT, bool VF16>
 __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArgs a)
 {
     constexpr int BKV = 64, KP = DH + 8, VP = 2 * b_pitch_dwords(DH), NTH = NQ * 64;  // NTH: threads that stage one split's tiles
     constexpr int CHUNKS = BKV * DH / 8, PER_T = (CHUNKS + NTH - 1) / NTH;
-    constexpr float TAU = 8.0f;
     constexpr int PD = 3;   // register sets of the K/V prefetch
     constexpr int K_BYTES = 2 * BKV * KP * 2, V_BYTES = 2 * BKV * VP * 2, SPLIT_BYTES = K_BYTES + V_BYTES + 2 * BKV;
     constexpr int MERGE_BYTES = (KSPLIT - 1) * NQ * 64 * (DH / 2 + 2) * 4;
@@ -357,97 +457,15 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
         Staged &fill = J == 0 ? set2 : (J == 1 ? set0 : set1), &drain = J == 0 ? set1 : (J == 1 ? set2 : set0);
         load_global(fill, tile_of(it + PD - 1));
         if (kt < nkt) {
-            // S^T tile: [64 keys x 32 queries] as two 32x32 accumulators, started at -m
-            const float moff = mrun == -INFINITY ? 0.f : mrun;
-            f32x16_t sacc[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) sacc[t][q] = -moff;
-#pragma unroll
-            for (int ks = 0; ks < DH / 16; ++ks)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(&Ks[buf][t * 32 + lr][ks * 16 + lh * 8]);
-                    sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
-                }
-            // accumulator register q of tile t is key kt*64 + t*32 + (q/4)*8 + lh*4 + q%4.  Masks: a wave-uniform
-            // test whether the tile can hold an inadmissible key for any query of the wave, then straight-line
-            // selects (accumulators must not cross divergent branches).
-            const int qrow_first = qblk * (32 * NQ) + qg * 32;
-            if ((kt + 1) * BKV > l_a || masked || (causal && (kt + 1) * BKV > qrow_first + 1)) {
-                uint32_t kmw[2][4];   // the padding flags of this lane's keys, four consecutive keys per word
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq)
-                        kmw[t][gq] = masked ? *reinterpret_cast<const uint32_t *>(&Km[buf][t * 32 + gq * 8 + lh * 4]) : 0x01010101u;
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int q = 0; q < 16; ++q) {
-                        const int key = kt * BKV + t * 32 + (q >> 2) * 8 + lh * 4 + (q & 3);
-                        const bool ok = key < l_a && (!causal || key <= qrow) && ((kmw[t][q >> 2] >> ((q & 3) * 8)) & 0xFFu) != 0;
-                        sacc[t][q] = ok ? sacc[t][q] : -INFINITY;
-                    }
-            }
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, sacc[t][q]);
-            {   // largest score of the tile, relative to the running maximum: the other half-wave's value through
-                // v_permlane32_swap (lanes 32-63 of the first result and lanes 0-31 of the second hold the partner's)
-                const uint32_t tb = __float_as_uint(tmax);
-                const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);
-                tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            }
-            // the maximum moves only when a score exceeds it by more than 2^TAU, or when there is none yet
-            const bool move = tmax > TAU || (mrun == -INFINITY && tmax > -INFINITY);
-            if (__builtin_amdgcn_ballot_w64(move) != 0) {   // wave-uniform: rare after the first tile
-                if (move) {
-                    const float corr = mrun == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(-tmax);
-                    mrun = moff + tmax;
-                    lsum *= corr;
-#pragma unroll
-                    for (int t = 0; t < DH / 32; ++t)
-#pragma unroll
-                        for (int q = 0; q < 16; ++q) oacc[t][q] *= corr;
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-#pragma unroll
-                        for (int q = 0; q < 16; ++q) sacc[t][q] -= tmax;
-                }
-            }
-            float psum = 0.f;
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const float pv = __builtin_amdgcn_exp2f(sacc[t][q]);   // exp2(-inf) = 0 for masked keys
-                    sacc[t][q] = pv;
-                    psum += pv;
-                }
-            lsum += psum;
-
-            // O^T += V^T P^T over the 64 keys of the tile: four k-steps of 16 keys
-#pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) {
-                const int t = s4 >> 1, r0 = (s4 & 1) * 8;
-                uint32_t ph[4];  // two probabilities per word, fp16
-#pragma unroll
-                for (int e = 0; e < 4; ++e) ph[e] = pack2_f16(sacc[t][r0 + 2 * e], sacc[t][r0 + 2 * e + 1]);
-                const f16x8_t pf = __builtin_bit_cast(f16x8_t, make_uint4(ph[0], ph[1], ph[2], ph[3]));
-#pragma unroll
-                for (int td = 0; td < DH / 32; ++td) {
-                    // V^T fragment for head-dim column td*32 + lr: keys 16*s4 + 4*lh + 0..3, then + 8
-                    const uint16_t *vsrc = &Vs[buf][s4 * 16 + lh * 4 + ((lane & 15) >> 2)][td * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4];
-                    const uint2 v0 = lds_read_tr4(vsrc);
-                    const uint2 v1 = lds_read_tr4(vsrc + 8 * VP);
-                    const f16x8_t vf = __builtin_bit_cast(f16x8_t, make_uint4(v0.x, v0.y, v1.x, v1.y));
-                    oacc[td] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, oacc[td], 0, 0, 0);
-                }
-            }
+            attention_tile<DH>(qf, oacc, mrun, lsum, kt, l_a, qrow, qblk * (32 * NQ) + qg * 32, causal, masked ? &Km[buf][0] : nullptr, lane,
+                               [&](int t, int ks) { return *reinterpret_cast<const bf16x8_t *>(&Ks[buf][t * 32 + lr][ks * 16 + lh * 8]); },
+                               [&](int s4, int td) {
+                                   // V^T fragment for head-dim column td*32 + lr: keys 16*s4 + 4*lh + 0..3, then + 8
+                                   const uint16_t *vsrc = &Vs[buf][s4 * 16 + lh * 4 + ((lane & 15) >> 2)][td * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4];
+                                   const uint2 v0 = lds_read_tr4(vsrc);
+                                   const uint2 v1 = lds_read_tr4(vsrc + 8 * VP);
+                                   return __builtin_bit_cast(f16x8_t, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                               });
         }
         if (tile_of(it + 1) < nkt) store_lds(drain, buf ^ 1);
         __syncthreads();
