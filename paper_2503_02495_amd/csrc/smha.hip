@@ -10,6 +10,7 @@
 //                      contributions of every expert that picked the patch along K and writes
 //                      each output row once, residual included (Eq. 35-36).
 #include "common.h"
+#include <cstdlib>
 #include "problems.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
@@ -314,6 +315,70 @@ __device__ __forceinline__ void attention_tile(const bf16x8_t (&qf)[DH / 16], f3
     }
 }
 
+// End of an attention workgroup: the key splits are merged (splits 1.. park their (max, row sum, O^T) in LDS, whose
+// tile buffers are free once the key loop has ended on a barrier; split 0 folds them in, in split order), then
+// split 0 normalises, applies the row's gate weight and writes o as a (hi, lo) bf16 pair and, if asked, the
+// base-2 log-sum-exp of the row.
+template <int DH, int NQ, int KSPLIT>
+__device__ __forceinline__ void attention_finish(const SmhaArgs &a, unsigned char *lds_raw, int split, int qg, int lane, int g, int qrow,
+                                                 int l_a, float w, f32x16_t (&oacc)[DH / 32], float mrun, float lsum)
+{
+    const int lh = lane >> 5;
+    if constexpr (KSPLIT > 1) {
+        float *mg = reinterpret_cast<float *>(lds_raw);
+        constexpr int SLOT = DH / 2 + 2;   // floats per lane
+        if (split > 0) {
+            float *dst = mg + ((size_t)((split - 1) * NQ + qg) * 64 + lane) * SLOT;
+            dst[0] = mrun;
+            dst[1] = lsum;
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) dst[2 + t * 16 + q] = oacc[t][q];
+        }
+        __syncthreads();
+        if (split > 0) return;
+#pragma unroll
+        for (int s = 1; s < KSPLIT; ++s) {
+            const float *src = mg + ((size_t)((s - 1) * NQ + qg) * 64 + lane) * SLOT;
+            const float m1 = src[0], l1 = src[1];
+            const float mf = fmaxf(mrun, m1);
+            // a side that has seen no admissible key (max = -inf) contributes nothing
+            const float c0 = mrun == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun - mf);
+            const float c1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - mf);
+            lsum = lsum * c0 + l1 * c1;
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) oacc[t][q] = oacc[t][q] * c0 + src[2 + t * 16 + q] * c1;
+            mrun = mf;
+        }
+    }
+
+    if (qrow >= l_a) return;
+    lsum += __shfl_xor(lsum, 32, 64);
+    const float inv = lsum > 0.f ? w / lsum : 0.f;  // a row with no admissible key contributes nothing
+    if (a.lse && lh == 0) a.lse[(size_t)g * l_a + qrow] = lsum > 0.f ? mrun + log2f(lsum) : 0.f;
+    bf16_t *o = static_cast<bf16_t *>(a.o) + ((size_t)g * l_a + qrow) * DH;
+    bf16_t *o_lo = static_cast<bf16_t *>(a.o_lo) + ((size_t)g * l_a + qrow) * DH;
+    // accumulator register q of tile td is head-dim index td*32 + (q/4)*8 + lh*4 + q%4.
+    // o is written as hi = bf16(o) and lo = bf16(o - hi): the out-projection contracts both.
+#pragma unroll
+    for (int td = 0; td < DH / 32; ++td)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            uint32_t hi[2], lo[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float v0 = oacc[td][i4 * 4 + 2 * e] * inv, v1 = oacc[td][i4 * 4 + 2 * e + 1] * inv;
+                hi[e] = pack2_bf16(v0, v1);
+                lo[e] = pack2_bf16(v0 - __uint_as_float(hi[e] << 16), v1 - __uint_as_float(hi[e] & 0xFFFF0000u));
+            }
+            *reinterpret_cast<uint2 *>(o + td * 32 + i4 * 8 + lh * 4) = make_uint2(hi[0], hi[1]);
+            *reinterpret_cast<uint2 *>(o_lo + td * 32 + i4 * 8 + lh * 4) = make_uint2(lo[0], lo[1]);
+        }
+}
+
 template <int DH, int NQ, int KSPLIT, bool VF16>
 __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArgs a)
 {
@@ -477,61 +542,151 @@ __global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_mfma_kernel(SmhaArg
         if (it0 + 2 < nit) iteration(std::integral_constant<int, 2>{}, it0 + 2);
     }
 
-    // merge the key splits: splits 1.. park (max, row-sum part, O^T) in LDS (the tile buffers are free:
-    // the loop ended on a barrier), split 0 folds them in, in split order
-    if constexpr (KSPLIT > 1) {
-        float *mg = reinterpret_cast<float *>(lds_raw);
-        constexpr int SLOT = DH / 2 + 2;   // floats per lane
-        if (split > 0) {
-            float *dst = mg + ((size_t)((split - 1) * NQ + qg) * 64 + lane) * SLOT;
-            dst[0] = mrun;
-            dst[1] = lsum;
-#pragma unroll
-            for (int t = 0; t < DH / 32; ++t)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) dst[2 + t * 16 + q] = oacc[t][q];
-        }
-        __syncthreads();
-        if (split > 0) return;
-#pragma unroll
-        for (int s = 1; s < KSPLIT; ++s) {
-            const float *src = mg + ((size_t)((s - 1) * NQ + qg) * 64 + lane) * SLOT;
-            const float m1 = src[0], l1 = src[1];
-            const float mf = fmaxf(mrun, m1);
-            // a side that has seen no admissible key (max = -inf) contributes nothing
-            const float c0 = mrun == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun - mf);
-            const float c1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - mf);
-            lsum = lsum * c0 + l1 * c1;
-#pragma unroll
-            for (int t = 0; t < DH / 32; ++t)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) oacc[t][q] = oacc[t][q] * c0 + src[2 + t * 16 + q] * c1;
-            mrun = mf;
+    attention_finish<DH, NQ, KSPLIT>(a, lds_raw, split, qg, lane, g, qrow, l_a, w, oacc, mrun, lsum);
+}
+
+// The same kernel with K and V tiles copied from global memory straight into LDS (global_load_lds_dwordx4:
+// 16 bytes per lane, the 64 lanes of an instruction fill 1 KiB of consecutive LDS), three tiles deep: no
+// staging registers, no LDS store instructions and no converts in the loop, and a wave waits for a tile only
+// when it needs it.  What that takes: V already in fp16 in memory (the projection kernel writes it so), no
+// padding mask (its per-key lookups are ordinary loads, whose compiler-placed waits would drain the copies in
+// flight: masked calls take the register-staged kernel), and unpadded tiles, so bank conflicts are avoided
+// by permuting which 16-byte piece of a row an LDS slot receives (every lane supplies its own global
+// address): K slot (r, pos) <- piece pos ^ ((r / (16/CK)) % CK), the rule for tiles read as row fragments; V
+// slot (r, pos) <- piece pos ^ ((r & 3) << 2) for 256-byte rows (d_h = 128) and pos ^ (((r >> 1) & 1) << 2) for
+// 128-byte rows (d_h = 64), the rule for tiles read with the transposing LDS read.  The copies are inline
+// assembly that the compiler cannot count, so their completion is waited for by hand (they complete in
+// issue order): at the top of an iteration at most the copies of the STAGES-2 younger tiles may be
+// outstanding, then one barrier publishes every wave's part of the tile and frees the buffer of the tile
+// before for the copies issued right after it.
+template <int DH, int NQ, int KSPLIT>
+__global__ __launch_bounds__(NQ *KSPLIT * 64) void attention_dma_kernel(SmhaArgs a)
+{
+    static_assert(DH == 64 || DH == 128, "piece permutations are written for 128- and 256-byte rows");
+    constexpr int BKV = 64, STAGES = 4;
+    constexpr int CK = DH / 8;                        // 16-byte pieces per row
+    constexpr int RPI = 64 / CK;                      // rows one copy instruction covers
+    constexpr int TILE_BYTES = BKV * DH * 2, INSTR = TILE_BYTES / 1024;
+    constexpr int PER_W = INSTR / NQ;                 // copy instructions per wave, tile and operand
+    static_assert(INSTR % NQ == 0, "every wave of a split issues the same number of copies");
+    constexpr int SPLIT_BYTES = STAGES * 2 * TILE_BYTES;
+    constexpr int MERGE_BYTES = (KSPLIT - 1) * NQ * 64 * (DH / 2 + 2) * 4;
+    constexpr int LDS_BYTES = KSPLIT * SPLIT_BYTES > MERGE_BYTES ? KSPLIT * SPLIT_BYTES : MERGE_BYTES;
+    __shared__ __align__(1024) unsigned char lds_raw[LDS_BYTES];
+
+    const int l_p = a.l / a.m, l_a = a.c * l_p;
+    int g, qblk;   // workgroup -> (unit, query block): the query blocks of a unit share an XCD (see attention_mfma_kernel)
+    {
+        const int nqb = (l_a + 32 * NQ - 1) / (32 * NQ), units = a.b * a.k, id = blockIdx.x;
+        const int full = (units / 8) * 8 * nqb;
+        if (id < full) {
+            const int grp = id / (8 * nqb), rem = id - grp * 8 * nqb;
+            g = grp * 8 + (rem & 7);
+            qblk = rem >> 3;
+        } else {
+            const int rem = id - full;
+            g = (units / 8) * 8 + rem / nqb;
+            qblk = rem % nqb;
         }
     }
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int split = wave / NQ, qg = wave - split * NQ;
+    const int lr = lane & 31, lh = lane >> 5;
+    const int qrow = qblk * (32 * NQ) + qg * 32 + lr;
+    unsigned char *sbase = lds_raw + (size_t)split * SPLIT_BYTES;   // stage s: K tile at s * 2 * TILE_BYTES, V tile after it
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)sbase;
+    const bf16_t *Q = static_cast<const bf16_t *>(a.q) + (size_t)g * l_a * DH;
+    const uint16_t *Kg = static_cast<const uint16_t *>(a.kk) + (size_t)g * l_a * DH;
+    const uint16_t *Vg = static_cast<const uint16_t *>(a.v) + (size_t)g * l_a * DH;
 
-    if (qrow >= l_a) return;
-    lsum += __shfl_xor(lsum, 32, 64);
-    const float inv = lsum > 0.f ? w / lsum : 0.f;  // a row with no admissible key contributes nothing
-    if (a.lse && lh == 0) a.lse[(size_t)g * l_a + qrow] = lsum > 0.f ? mrun + log2f(lsum) : 0.f;
-    bf16_t *o = static_cast<bf16_t *>(a.o) + ((size_t)g * l_a + qrow) * DH;
-    bf16_t *o_lo = static_cast<bf16_t *>(a.o_lo) + ((size_t)g * l_a + qrow) * DH;
-    // accumulator register q of tile td is head-dim index td*32 + (q/4)*8 + lh*4 + q%4.
-    // o is written as hi = bf16(o) and lo = bf16(o - hi): the out-projection contracts both.
-#pragma unroll
-    for (int td = 0; td < DH / 32; ++td)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            uint32_t hi[2], lo[2];
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const float v0 = oacc[td][i4 * 4 + 2 * e] * inv, v1 = oacc[td][i4 * 4 + 2 * e + 1] * inv;
-                hi[e] = pack2_bf16(v0, v1);
-                lo[e] = pack2_bf16(v0 - __uint_as_float(hi[e] << 16), v1 - __uint_as_float(hi[e] & 0xFFFF0000u));
-            }
-            *reinterpret_cast<uint2 *>(o + td * 32 + i4 * 8 + lh * 4) = make_uint2(hi[0], hi[1]);
-            *reinterpret_cast<uint2 *>(o_lo + td * 32 + i4 * 8 + lh * 4) = make_uint2(lo[0], lo[1]);
+    float w = 1.0f;   // gate weight of this row (Eq. 36), looked up early
+    if (split == 0) {
+        const int bb = g / a.k, i = clampi(a.expert_idx[g], a.n);
+        if ((a.flags & F_GATE_EXPERT) && a.expert_gate) w *= a.expert_gate[(size_t)bb * a.n + i];
+        if ((a.flags & F_GATE_PATCH) && a.patch_gate) {
+            const int p = clampi(a.patch_idx[((size_t)bb * a.n + i) * a.c + min(qrow, l_a - 1) / l_p], a.m);
+            w *= a.patch_gate[((size_t)bb * a.n + i) * a.m + p];
         }
+    }
+    bf16x8_t qf[DH / 16];
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (qrow < l_a) v = *reinterpret_cast<const uint4 *>(Q + (size_t)qrow * DH + ks * 16 + lh * 8);
+        qf[ks] = __builtin_bit_cast(bf16x8_t, v);
+    }
+    f32x16_t oacc[DH / 32];
+#pragma unroll
+    for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) oacc[t][q] = 0.f;
+    float mrun = -INFINITY, lsum = 0.f;
+
+    auto v_swz = [](int r) { return (DH == 128 ? (r & 3) : ((r >> 1) & 1)) << 2; };
+    // Copy roles.  Instruction j of this wave fills 1 KiB block qg * PER_W + j of a tile: lane -> slot (row, pos).
+    // Element offsets inside the unit's K (V) array, for tile 0; a tile adds BKV * DH.  Keys past l_a repeat
+    // the last key (their scores are masked, so they get probability 0 against finite V rows).
+    uint32_t k_off[PER_W], v_off[PER_W], k_last[PER_W], v_last[PER_W];
+#pragma unroll
+    for (int j = 0; j < PER_W; ++j) {
+        const int r = (qg * PER_W + j) * RPI + lane / CK, pos = lane % CK;
+        const int kp = pos ^ ((r / (16 / CK)) % CK), vp = pos ^ v_swz(r);
+        k_off[j] = (uint32_t)r * DH + kp * 8;
+        v_off[j] = (uint32_t)r * DH + vp * 8;
+        k_last[j] = (uint32_t)(l_a - 1) * DH + kp * 8;
+        v_last[j] = (uint32_t)(l_a - 1) * DH + vp * 8;
+    }
+    const bool causal = (a.flags & F_CAUSAL) != 0;
+    const int nkt_all = (l_a + BKV - 1) / BKV;
+    const int key_end = causal ? min(l_a, (qblk + 1) * 32 * NQ) : l_a;   // no query of this workgroup sees later keys
+    const int nkt = (key_end + BKV - 1) / BKV;
+    const int nit = (nkt + KSPLIT - 1) / KSPLIT;   // iterations: split s takes tiles s, s + KSPLIT, ...
+    auto tile_of = [&](int it) { return it * KSPLIT + split; };
+    // copies are issued for every iteration, also past the last tile (clamped to the end, never read): the
+    // number outstanding is then the same in every iteration
+    auto issue = [&](int it, int stage) {
+        const uint32_t t0 = (uint32_t)min(tile_of(it), nkt_all) * (BKV * DH);
+        const uint32_t dst = lds_base + stage * (2 * TILE_BYTES) + qg * PER_W * 1024;
+#pragma unroll
+        for (int j = 0; j < PER_W; ++j) {
+            dma_load16(Kg + min(t0 + k_off[j], k_last[j]), dst + j * 1024);
+            dma_load16(Vg + min(t0 + v_off[j], v_last[j]), dst + TILE_BYTES + j * 1024);
+        }
+    };
+#pragma unroll
+    for (int q = 0; q < STAGES - 1; ++q) issue(q, q);
+    // fragment offsets (bytes inside a stage): K row fragments, V^T through the transposing read
+    const int vx = (lane & 15) >> 2;   // row of the 4-row group this lane points at
+    int stage = 0, fill = STAGES - 1;
+    for (int it = 0; it < nit; ++it) {   // nit is uniform over the workgroup
+        dma_wait<(STAGES - 2) * 2 * PER_W>();
+        __syncthreads();
+        issue(it + STAGES - 1, fill);
+        const int kt = tile_of(it);
+        if (kt < nkt) {
+            const unsigned char *kb = sbase + stage * (2 * TILE_BYTES), *vb = kb + TILE_BYTES;
+            attention_tile<DH>(qf, oacc, mrun, lsum, kt, l_a, qrow, qblk * (32 * NQ) + qg * 32, causal, nullptr, lane,
+                               [&](int t, int ks) {
+                                   const int r = t * 32 + lr;
+                                   return *reinterpret_cast<const bf16x8_t *>(kb + r * (DH * 2) + (((ks * 2 + lh) ^ ((r / (16 / CK)) % CK)) * 16));
+                               },
+                               [&](int s4, int td) {
+                                   // keys 16*s4 + 4*lh + vx, then + 8 (the same permutation of both rows), head-dim columns
+                                   // td*32 + ((lane>>4)&1)*16 + (lane&3)*4 .. +3
+                                   const int r = s4 * 16 + lh * 4 + vx;
+                                   const int piece = (td * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1)) ^ v_swz(r);
+                                   const uint16_t *vsrc = reinterpret_cast<const uint16_t *>(vb + r * (DH * 2) + piece * 16 + (lane & 1) * 8);
+                                   const uint2 v0 = lds_read_tr4(vsrc);
+                                   const uint2 v1 = lds_read_tr4(vsrc + 8 * DH);
+                                   return __builtin_bit_cast(f16x8_t, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                               });
+        }
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
+        fill = fill + 1 == STAGES ? 0 : fill + 1;
+    }
+    dma_wait<0>();     // the copies past the last tile
+    __syncthreads();   // every wave is done with the tiles: LDS is free for the merge
+    attention_finish<DH, NQ, KSPLIT>(a, lds_raw, split, qg, lane, g, qrow, l_a, w, oacc, mrun, lsum);
 }
 
 // Launch shape: NQ waves of 32 queries per workgroup (more share K/V tiles, fewer give more workgroups:
@@ -541,8 +696,20 @@ template <int DH, int NQ, int KSPLIT> static void launch_attention_shape(const S
 {
     const int l_a = a.c * (a.l / a.m), units = a.b * a.k;
     const dim3 grid(((l_a + 32 * NQ - 1) / (32 * NQ)) * units), block(NQ * KSPLIT * 64);
-    if (a.keep_v_bf16) hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT, false>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT, true>), grid, block, 0, st, a);
+    if (a.keep_v_bf16) {
+        hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT, false>), grid, block, 0, st, a);
+        return;
+    }
+    // (LDS: stages x (K + V tile) per split; every wave the same number of copies; the wait count fits its field)
+    if constexpr ((DH == 64 || DH == 128) && KSPLIT * 4 * 2 * 64 * DH * 2 <= 160 * 1024 && (64 * DH * 2 / 1024) % NQ == 0 &&
+                  2 * 2 * (64 * DH * 2 / 1024 / NQ) <= 63) {
+        static const char *nodma = getenv("UOE_ATT_NO_DMA");   // EXPERIMENT
+        if (!a.pad_mask && !nodma) {   // V in fp16, no padding mask: tiles copied straight into LDS
+            hipLaunchKernelGGL((attention_dma_kernel<DH, NQ, KSPLIT>), grid, block, 0, st, a);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((attention_mfma_kernel<DH, NQ, KSPLIT, true>), grid, block, 0, st, a);
 }
 
 template <int DH> static hipError_t launch_attention_mfma_dh(const SmhaArgs &a, hipStream_t st)
