@@ -10,7 +10,6 @@
 //                      contributions of every expert that picked the patch along K and writes
 //                      each output row once, residual included (Eq. 35-36).
 #include "common.h"
-#include <cstdlib>
 #include "problems.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
@@ -703,8 +702,7 @@ template <int DH, int NQ, int KSPLIT> static void launch_attention_shape(const S
     // (LDS: stages x (K + V tile) per split; every wave the same number of copies; the wait count fits its field)
     if constexpr ((DH == 64 || DH == 128) && KSPLIT * 4 * 2 * 64 * DH * 2 <= 160 * 1024 && (64 * DH * 2 / 1024) % NQ == 0 &&
                   2 * 2 * (64 * DH * 2 / 1024 / NQ) <= 63) {
-        static const char *nodma = getenv("UOE_ATT_NO_DMA");   // EXPERIMENT
-        if (!a.pad_mask && !nodma) {   // V in fp16, no padding mask: tiles copied straight into LDS
+        if (!a.pad_mask) {   // V in fp16, no padding mask: tiles copied straight into LDS
             hipLaunchKernelGGL((attention_dma_kernel<DH, NQ, KSPLIT>), grid, block, 0, st, a);
             return;
         }
