@@ -160,7 +160,7 @@ int check_uome_bwd(const uoe_block_desc *blk)
 struct SmhaBwdWs {
     SmhaWs fwd;
     size_t lse, rt, dd, wo_t, wqkv_t, do_raw, d_o, o_t, dqkv, dqkv_t, partial, total;
-    size_t g_q, g_k, g_v, g_o, g_probs, g_dscores;  // vector-ALU path (fp32 arrays)
+    size_t g_q, g_k, g_v, g_o, g_probs, g_dscores, g_wt;  // vector-ALU path (fp32 arrays)
 };
 static bool smha_bwd_mfma(const uoe_block_desc *blk)
 {
@@ -185,6 +185,7 @@ SmhaBwdWs smha_bwd_ws(const uoe_block_desc *d)
         w.rt = off; off += rows;
         w.g_probs = off; off += sq;
         w.g_dscores = off; off += sq;
+        w.g_wt = off; off += up((size_t)4 * d->n * d->d * d->width * sizeof(float));
         w.total = off;
         return w;
     }
@@ -631,6 +632,7 @@ int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_w
         a.do_raw = reinterpret_cast<float *>(at(ws, s.do_raw)); a.dqkv = at(ws, s.dqkv);
         a.rt = reinterpret_cast<float *>(at(ws, s.rt));
         a.probs = reinterpret_cast<float *>(at(ws, s.g_probs)); a.dscores = reinterpret_cast<float *>(at(ws, s.g_dscores));
+        a.wt = reinterpret_cast<float *>(at(ws, s.g_wt));
         return launch_smha_backward_generic(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
                    ? UOE_OK : UOE_ERR_DEVICE;
     }

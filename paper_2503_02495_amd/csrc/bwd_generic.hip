@@ -221,7 +221,7 @@ template <typename T> struct GenUomeDw {
 
 // ------------------------------------------------------------------------------------------ SMHA
 // fp32 workspace: f.q, f.kk, f.v, f.o and do_raw [units, l_a, d_h]; dqkv [units, l_a, 3*d_h] as [dq | dk | dv];
-// probs and dscores [units, l_a, l_a]; rt, dd [units, l_a].
+// probs and dscores [units, l_a, l_a]; rt [units, l_a]; wt [4, n, d*d_h] (transposed weights, see gen_smha_wt).
 
 struct UnitRow {
     int bb, i, tok;
@@ -248,6 +248,30 @@ __device__ __forceinline__ float row_weight(const SmhaBwdArgs &a, int g, int r, 
         w *= a.patch_gate[((size_t)bb * f.n + i) * f.m + p];
     }
     return w;
+}
+
+// Transposed fp32 copies of the block's weights, so that the kernels whose threads run along the model
+// dimension (d_x) or along the head dimension (dO) read them with consecutive lanes on consecutive
+// addresses: wt[which][i][e][j] = W^{q,k,v}_i[j][e] for which = 0..2, then wt[3][i][j][e] = W^O_i[e][j].
+// Thread = one source element (reads in storage order).
+template <typename T> __global__ __launch_bounds__(GT) void gen_smha_wt(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const long per = (long)f.n * f.d * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= 4 * per) return;
+    const int which = (int)(idx / per);
+    const long q = idx - (long)which * per;
+    const int i = (int)(q / ((long)f.d * f.d_h));
+    const long rem = q - (long)i * f.d * f.d_h;
+    const T *src = static_cast<const T *>(which == 0 ? f.wq : which == 1 ? f.wk : which == 2 ? f.wv : f.wo);
+    float *dst = a.wt + (long)which * per + (long)i * f.d * f.d_h;
+    if (which < 3) {
+        const int j = (int)(rem / f.d_h), e = (int)(rem - (long)j * f.d_h);
+        dst[(long)e * f.d + j] = to_f32(src[q]);
+    } else {
+        const int e = (int)(rem / f.d), j = (int)(rem - (long)e * f.d);
+        dst[(long)j * f.d_h + e] = to_f32(src[q]);
+    }
 }
 
 // q, k, v of the gathered rows (Eq. 18, 28-30): thread = (unit, row, head column)
@@ -376,9 +400,9 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_do(SmhaBwdA
     const int g = (int)(ur / l_a), r = (int)(ur - (long)g * l_a);
     const UnitRow u = unit_row(f, g, r, l_p);
     const T *gr = static_cast<const T *>(a.d_out) + ((size_t)u.bb * f.l + u.tok) * f.d;
-    const T *wo = static_cast<const T *>(f.wo) + ((size_t)u.i * f.d_h + e) * f.d;   // row e of W^O_i
+    const float *wo = a.wt + ((size_t)3 * f.n + u.i) * f.d * f.d_h + e;   // column e of the transposed W^O_i [d][d_h]
     float acc = 0.f;
-    for (int j = 0; j < f.d; ++j) acc = fmaf(to_f32(gr[j]), to_f32(wo[j]), acc);
+    for (int j = 0; j < f.d; ++j) acc = fmaf(to_f32(gr[j]), wo[(size_t)j * f.d_h], acc);
     a.do_raw[idx] = acc;
 }
 
@@ -475,15 +499,15 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dx(SmhaBwdA
     for (int s = 0; s < f.k; ++s) {
         const int g = bb * f.k + s, i = clampi(f.expert_idx[g], f.n);
         const int32_t *picks = f.patch_idx + ((size_t)bb * f.n + i) * f.c;
-        const size_t wat = ((size_t)i * f.d + j) * f.d_h;   // row j of the expert's [d, d_h] weights
-        const T *wq = static_cast<const T *>(f.wq) + wat, *wk = static_cast<const T *>(f.wk) + wat, *wv = static_cast<const T *>(f.wv) + wat;
+        const size_t per = (size_t)f.n * f.d * f.d_h;
+        const float *wq = a.wt + (size_t)i * f.d_h * f.d + j, *wk = wq + per, *wv = wk + per;   // column j of the transposed [d_h, d] weights
         for (int t = 0; t < f.c; ++t) {
             if (clampi(picks[t], f.m) != patch) continue;
             const float *row = static_cast<const float *>(a.dqkv) + ((long)g * l_a + t * l_p + within) * 3 * f.d_h;
             for (int e = 0; e < f.d_h; ++e) {
-                acc = fmaf(row[e], to_f32(wq[e]), acc);
-                acc = fmaf(row[f.d_h + e], to_f32(wk[e]), acc);
-                acc = fmaf(row[2 * f.d_h + e], to_f32(wv[e]), acc);
+                acc = fmaf(row[e], wq[(size_t)e * f.d], acc);
+                acc = fmaf(row[f.d_h + e], wk[(size_t)e * f.d], acc);
+                acc = fmaf(row[2 * f.d_h + e], wv[(size_t)e * f.d], acc);
             }
         }
     }
@@ -491,20 +515,23 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dx(SmhaBwdA
 }
 
 // dW^{q,k,v}_i [d, d_h] = sum x[T]^T d{Q,K,V} and dW^O_i [d_h, d] = sum (w o)^T G[T] over the units of
-// expert i, units then rows in order: thread = one weight element
+// expert i, units then rows in order: thread = four consecutive weight elements (four head columns of one
+// row of dW^{q,k,v}, four model columns of one row of dW^O), so that the operand every lane shares is
+// loaded once for four products
 template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw(SmhaBwdArgs a)
 {
     const SmhaArgs &f = a.f;
     const int l_p = f.l / f.m, l_a = f.c * l_p, units = f.b * f.k;
-    const long per = (long)f.n * f.d * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
-    if (idx >= 4 * per) return;
-    const int which = (int)(idx / per);   // 0..2: dW^q, dW^k, dW^v; 3: dW^O
-    const long q = idx - (long)which * per;
+    const long per = (long)f.n * f.d * f.d_h, quads = per / 4, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= 4 * quads) return;
+    const int which = (int)(idx / quads);   // 0..2: dW^q, dW^k, dW^v; 3: dW^O
+    const long q = (idx - (long)which * quads) * 4;   // first of the four elements (d_h and d are multiples of 8)
     const int i = (int)(q / ((long)f.d * f.d_h));
     const long rem = q - (long)i * f.d * f.d_h;
+    // which < 3: row j, columns e..e+3 of [d][d_h]; which == 3: row e, columns j..j+3 of [d_h][d]
     const int e = which < 3 ? (int)(rem % f.d_h) : (int)(rem / f.d), j = which < 3 ? (int)(rem / f.d_h) : (int)(rem % f.d);
     const T *tokens = static_cast<const T *>(which < 3 ? f.x : a.d_out);
-    float acc = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int g = 0; g < units; ++g) {
         if (clampi(f.expert_idx[g], f.n) != i) continue;
         const int bb = g / f.k;
@@ -513,16 +540,28 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw(SmhaBwdA
             const int p = clampi(picks[t], f.m);
             const T *tk = tokens + ((size_t)bb * f.l + (size_t)p * l_p) * f.d + j;
             const long r0 = (long)g * l_a + t * l_p;
-            for (int rr = 0; rr < l_p; ++rr) {
-                float left;
-                if (which < 3) left = static_cast<const float *>(a.dqkv)[(r0 + rr) * 3 * f.d_h + which * f.d_h + e];
-                else left = static_cast<const float *>(f.o)[(r0 + rr) * f.d_h + e] * row_weight(a, g, t * l_p + rr, l_p);
-                acc = fmaf(left, to_f32(tk[(size_t)rr * f.d]), acc);
+            if (which < 3) {
+                for (int rr = 0; rr < l_p; ++rr) {
+                    const float4 left = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.dqkv) + (r0 + rr) * 3 * f.d_h + which * f.d_h + e);
+                    const float right = to_f32(tk[(size_t)rr * f.d]);
+                    acc[0] = fmaf(left.x, right, acc[0]);
+                    acc[1] = fmaf(left.y, right, acc[1]);
+                    acc[2] = fmaf(left.z, right, acc[2]);
+                    acc[3] = fmaf(left.w, right, acc[3]);
+                }
+            } else {
+                const float w = row_weight(a, g, t * l_p, l_p);   // one weight per (unit, pick)
+                for (int rr = 0; rr < l_p; ++rr) {
+                    const float left = static_cast<const float *>(f.o)[(r0 + rr) * f.d_h + e] * w;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc[u] = fmaf(left, to_f32(tk[(size_t)rr * f.d + u]), acc[u]);
+                }
             }
         }
     }
     T *dst = static_cast<T *>(which == 0 ? a.d_wq : which == 1 ? a.d_wk : which == 2 ? a.d_wv : a.d_wo);
-    dst[q] = from_f32<T>(acc);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) dst[q + u] = from_f32<T>(acc[u]);
 }
 
 template <typename T> hipError_t uome_backward_generic(const UomeBwdArgs &a, hipStream_t st)
@@ -547,6 +586,7 @@ template <typename T> hipError_t smha_backward_generic(const SmhaBwdArgs &a, hip
 #define UOE_GEN(kernel, total, ...)                                                       \
     hipLaunchKernelGGL(kernel, blocks_for(total), dim3(GT), 0, st, __VA_ARGS__);          \
     if ((err = hipGetLastError()) != hipSuccess) return err
+    UOE_GEN((gen_smha_wt<T>), 4L * f.n * f.d * f.d_h, a);
     UOE_GEN((gen_smha_qkv<T>), elems, a);
     if (f.rope_dim > 0) { UOE_GEN(gen_smha_rope, rope_pairs, f, static_cast<float *>(f.q), static_cast<float *>(f.kk), f.d_h, 0); }
     UOE_GEN(gen_smha_scores, pairs, a);
@@ -563,7 +603,7 @@ template <typename T> hipError_t smha_backward_generic(const SmhaBwdArgs &a, hip
         UOE_GEN(gen_smha_rope, rope_pairs, f, dq, dq + f.d_h, 3 * f.d_h, 1);
     }
     UOE_GEN((gen_smha_dx<T>), (long)f.b * f.l * f.d, a);
-    UOE_GEN((gen_smha_dw<T>), 4L * f.n * f.d * f.d_h, a);
+    UOE_GEN((gen_smha_dw<T>), (long)f.n * f.d * f.d_h, a);
 #undef UOE_GEN
     return hipSuccess;
 }

@@ -175,6 +175,7 @@ struct SmhaBwdArgs {
     int splits;
     // vector-ALU path only (any shape, any storage type): every workspace array above that it uses is fp32
     float *probs, *dscores;                   // [units, l_a, l_a] each: softmax probabilities and score gradients
+    float *wt;                                // transposed fp32 copies of the weights: W^{q,k,v} as [3][n][d_h][d], then W^O as [n][d][d_h]
 };
 
 // Backward pass of the routers of one block
