@@ -114,7 +114,17 @@ UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
     if (!uome_bwd_mfma(d)) {  // vector-ALU path: Z/H and dH/dZ in fp32
         const size_t act32 = up((size_t)d->b * d->l * d->k * d->width * sizeof(float));
         w.z = 0; w.dh = act32; w.total = 2 * act32;
-        w.splits = 1;
+        // weight gradients: the (sample, slot) pairs cut into ranges until about 1024 tiles of 64x64 are
+        // in flight, partial tiles in fp32, added in range order
+        const long tiles = 2L * d->n * ((d->d + 63) / 64) * ((d->width + 63) / 64);
+        long s = 1024 / tiles;
+        s = s < 1 ? 1 : (s > 8 ? 8 : s);
+        if (s > (long)d->b * d->k) s = (long)d->b * d->k;
+        w.splits = (int)s;
+        if (w.splits > 1) {
+            w.partial = w.total;
+            w.total += up((size_t)2 * d->n * w.splits * d->d * d->width * sizeof(float));
+        }
         return w;
     }
     const size_t es = elem_size(d->dtype);
@@ -579,6 +589,8 @@ int uoe_uome_backward(const uoe_block_desc *blk, const void *u, const void *a_in
     a.b = blk->b; a.l = blk->l; a.d = blk->d; a.n = blk->n; a.k = blk->k; a.d_e = blk->width; a.flags = blk->flags;
     if (!uome_bwd_mfma(blk)) {
         a.z = at(ws, w.z); a.dh = at(ws, w.dh);
+        a.splits = w.splits;
+        a.partial = w.splits > 1 ? reinterpret_cast<float *>(at(ws, w.partial)) : nullptr;
         return launch_uome_backward_generic(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
                    ? UOE_OK : UOE_ERR_DEVICE;
     }

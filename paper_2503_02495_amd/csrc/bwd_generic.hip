@@ -176,23 +176,32 @@ template <typename T> struct GenUomeDu {
     }
 };
 
-// dA^O_i [d_e, d] = sum H_{b,s}^T d_out_b (groups 0..n-1) and dA^I_i [d, d_e] = sum u_b^T dZ_{b,s} (groups
-// n..2n-1): segments = the (sample, slot) pairs in order, those of other experts skipped; K = the l tokens
+// dA^O_i [d_e, d] = sum H_{b,s}^T d_out_b (weight gradients 0..n-1) and dA^I_i [d, d_e] = sum u_b^T dZ_{b,s}
+// (n..2n-1): segments = the (sample, slot) pairs in order, those of other experts skipped; K = the l tokens.
+// With a.splits > 1 the pairs are cut into that many contiguous ranges, group = gradient * splits + range,
+// each range's tile goes to a.partial in fp32 and gen_uome_dw_reduce adds the ranges in order.
 template <typename T> struct GenUomeDw {
     UomeBwdArgs a;
     struct Ctx {
         int bb, s;
     };
     static constexpr bool A_K_FAST = false, B_K_FAST = false;
-    __device__ bool second(int g) const { return g >= a.n; }
+    __device__ int grad(int g) const { return g / a.splits; }
+    __device__ int per_range() const { return (a.b * a.k + a.splits - 1) / a.splits; }
+    __device__ bool second(int g) const { return grad(g) >= a.n; }
     __device__ int rows(int g) const { return second(g) ? a.d : a.d_e; }
     __device__ int cols(int g) const { return second(g) ? a.d_e : a.d; }
-    __device__ int nseg(int) const { return a.b * a.k; }
-    __device__ bool seg(int g, int sg, Ctx &c) const
+    __device__ int nseg(int g) const
     {
+        const int first = (g - grad(g) * a.splits) * per_range(), left = a.b * a.k - first;
+        return left < per_range() ? (left > 0 ? left : 0) : per_range();
+    }
+    __device__ bool seg(int g, int sgi, Ctx &c) const
+    {
+        const int sg = (g - grad(g) * a.splits) * per_range() + sgi;
         c.bb = sg / a.k;
         c.s = sg - c.bb * a.k;
-        return clampi(a.expert_idx[sg], a.n) == (second(g) ? g - a.n : g);
+        return clampi(a.expert_idx[sg], a.n) == (second(g) ? grad(g) - a.n : grad(g));
     }
     __device__ int klen(const Ctx &) const { return a.l; }
     __device__ float act(const float *buf, const Ctx &c, int t, int e) const
@@ -214,10 +223,26 @@ template <typename T> struct GenUomeDw {
     }
     __device__ void store(int g, int m, int n, float v) const
     {
+        if (a.splits > 1) {   // [2n][splits][d * d_e]: both gradients have d * d_e elements, in their own layouts
+            a.partial[(size_t)g * a.d * a.d_e + (size_t)m * cols(g) + n] = v;
+            return;
+        }
         if (second(g)) static_cast<T *>(a.d_a_in)[((size_t)(g - a.n) * a.d + m) * a.d_e + n] = from_f32<T>(v);
         else static_cast<T *>(a.d_a_out)[((size_t)g * a.d_e + m) * a.d + n] = from_f32<T>(v);
     }
 };
+
+// the ranges of gen_gemm<GenUomeDw> added in order: thread = one weight-gradient element
+template <typename T> __global__ __launch_bounds__(GT) void gen_uome_dw_reduce(UomeBwdArgs a)
+{
+    const long per = (long)a.d * a.d_e, total = 2L * a.n * per, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= total) return;
+    const long gi = idx / per, at = idx - gi * per;   // gradient 0..2n-1, element in its layout
+    float sum = 0.f;
+    for (int sp = 0; sp < a.splits; ++sp) sum += a.partial[((size_t)gi * a.splits + sp) * per + at];
+    if (gi >= a.n) static_cast<T *>(a.d_a_in)[(size_t)(gi - a.n) * per + at] = from_f32<T>(sum);
+    else static_cast<T *>(a.d_a_out)[(size_t)gi * per + at] = from_f32<T>(sum);
+}
 
 // ------------------------------------------------------------------------------------------ SMHA
 // fp32 workspace: f.q, f.kk, f.v, f.o and do_raw [units, l_a, d_h]; dqkv [units, l_a, 3*d_h] as [dq | dk | dv];
@@ -573,7 +598,13 @@ template <typename T> hipError_t uome_backward_generic(const UomeBwdArgs &a, hip
     hipLaunchKernelGGL(gen_uome_mid, dim3(a.k, a.b), dim3(GT), 0, st, a);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     if ((err = launch_gen_gemm(GenUomeDu<T>{a}, a.b, a.l, a.d, st)) != hipSuccess) return err;
-    return launch_gen_gemm(GenUomeDw<T>{a}, 2 * a.n, a.d > a.d_e ? a.d : a.d_e, a.d > a.d_e ? a.d : a.d_e, st);
+    if ((err = launch_gen_gemm(GenUomeDw<T>{a}, 2 * a.n * a.splits, a.d > a.d_e ? a.d : a.d_e, a.d > a.d_e ? a.d : a.d_e, st)) != hipSuccess)
+        return err;
+    if (a.splits > 1) {
+        hipLaunchKernelGGL((gen_uome_dw_reduce<T>), blocks_for(2L * a.n * a.d * a.d_e), dim3(GT), 0, st, a);
+        err = hipGetLastError();
+    }
+    return err;
 }
 
 template <typename T> hipError_t smha_backward_generic(const SmhaBwdArgs &a, hipStream_t st)

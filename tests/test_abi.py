@@ -181,8 +181,12 @@ def test_backward_argument_validation():
     # UoME backward, expert-selection mode: every shape and both storage types
     u = B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.BF16, fl)
     assert B.uome_backward_workspace_bytes(u) > 0
-    assert B.uome_backward_workspace_bytes(B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.F32, fl)) == 2 * 2 * 64 * 2 * 64 * 4
-    assert B.uome_backward_workspace_bytes(B.block_desc(2, 48, 64, 4, 2, 1, 1, 64, B.BF16, fl)) == 2 * 2 * 48 * 2 * 64 * 4
+    # vector-ALU path (fp32 storage): Z/H and dH/dZ in fp32, plus the weight gradients' partial tiles, here
+    # 4 ranges of (sample, slot) pairs (b * k = 4 caps the 8 that so few tiles would ask for)
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 64, 64, 4, 2, 1, 1, 64, B.F32, fl)) == \
+        2 * (2 * 64 * 2 * 64 * 4) + 2 * 4 * 4 * 64 * 64 * 4
+    assert B.uome_backward_workspace_bytes(B.block_desc(2, 48, 64, 4, 2, 1, 1, 64, B.BF16, fl)) == \
+        2 * (2 * 48 * 2 * 64 * 4) + 2 * 4 * 4 * 64 * 64 * 4
     ub = lambda *a, **k: B.uome_backward(u, *a, stream=0, check=False, **k)
     ok = [FAKE, FAKE + 16, FAKE + 32, FAKE, FAKE, None, None, FAKE + 48, FAKE + 64, FAKE + 80, FAKE + 96, FAKE, None, FAKE]
     assert ub(*ok, ws_bytes=8) == B.ERR_WORKSPACE
