@@ -226,7 +226,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_dma_kernel(P 
         const unsigned char *st = lds_raw + cbuf * STAGE_BYTES;
         // Fragments are double-buffered in registers: the LDS reads of sub-step ks+1 are issued
         // before the MFMAs of sub-step ks, so their latency is covered by 32*TM*TN cycles of matrix
-        // work of this same wave (one wave per SIMD at the large tile: nobody else would cover it).
+        // work of this same wave (at one or two waves per SIMD there is little else to cover it).
         // The scheduling fences keep the compiler from sinking the reads back down to their uses.
         bf16x8_t af[2][TM], wf[2][TN];
         auto load_frags = [&](int ks, int slot) {

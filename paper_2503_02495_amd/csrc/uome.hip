@@ -38,9 +38,10 @@ template <typename T> static hipError_t uome_down_generic(const UomeArgs &a, hip
 // MFMA path: bf16 storage, and every K segment (d for GEMM-1, d_e for GEMM-2) a multiple of 32
 static bool uome_mfma_ok(const UomeArgs &a, bool bf16) { return bf16 && a.d % 32 == 0 && a.d_e % 32 == 0; }
 
-// Tile choice for the pipelined engine.  256x128 tiles (wave tile 128x64, two workgroups per CU so
-// that one's SiLU/store epilogue runs under the other's MFMAs) once they fill the chip's 512
-// workgroup slots; 128x128 tiles with a 64-deep K-step otherwise.
+// Tile choice for the pipelined engine.  256x128 tiles (wave tile 128x64, register budget held to two
+// workgroups per CU: twice the operand bytes in flight, and a CU is not idle while one of them is
+// between tiles) once they fill the chip's 512 workgroup slots; 128x128 tiles with a 64-deep K-step
+// otherwise.
 static bool uome_big(int b, int l, int ncols)
 {
     return l > 128 && (long)b * ((l + 255) / 256) * ((ncols + 127) / 128) >= 512;
