@@ -171,6 +171,7 @@ struct SmhaBwdWs {
     SmhaWs fwd;
     size_t lse, rt, dd, wo_t, wqkv_t, do_raw, d_o, o_t, dqkv, dqkv_t, partial, total;
     size_t g_q, g_k, g_v, g_o, g_probs, g_dscores, g_wt;  // vector-ALU path (fp32 arrays)
+    int g_splits;                                           // vector-ALU path: unit ranges of the weight gradients
 };
 static bool smha_bwd_mfma(const uoe_block_desc *blk)
 {
@@ -196,6 +197,15 @@ SmhaBwdWs smha_bwd_ws(const uoe_block_desc *d)
         w.g_probs = off; off += sq;
         w.g_dscores = off; off += sq;
         w.g_wt = off; off += up((size_t)4 * d->n * d->d * d->width * sizeof(float));
+        // weight gradients: the units cut into ranges until about 16 waves per SIMD are in flight, partial
+        // sums in fp32, added in range order
+        const size_t per = (size_t)d->n * d->d * d->width;
+        size_t sp = (16384 * 64 + per - 1) / per;
+        sp = sp < 1 ? 1 : (sp > 8 ? 8 : sp);
+        if (sp > units) sp = units;
+        w.g_splits = (int)sp;
+        w.partial = off;
+        if (sp > 1) off += up(sp * 4 * per * sizeof(float));
         w.total = off;
         return w;
     }
@@ -645,6 +655,8 @@ int uoe_smha_backward(const uoe_block_desc *blk, const void *x, const uoe_smha_w
         a.rt = reinterpret_cast<float *>(at(ws, s.rt));
         a.probs = reinterpret_cast<float *>(at(ws, s.g_probs)); a.dscores = reinterpret_cast<float *>(at(ws, s.g_dscores));
         a.wt = reinterpret_cast<float *>(at(ws, s.g_wt));
+        a.splits = s.g_splits;
+        a.partial = s.g_splits > 1 ? reinterpret_cast<float *>(at(ws, s.partial)) : nullptr;
         return launch_smha_backward_generic(a, blk->dtype == UOE_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess
                    ? UOE_OK : UOE_ERR_DEVICE;
     }

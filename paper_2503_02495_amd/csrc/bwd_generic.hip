@@ -547,8 +547,14 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw(SmhaBwdA
 {
     const SmhaArgs &f = a.f;
     const int l_p = f.l / f.m, l_a = f.c * l_p, units = f.b * f.k;
-    const long per = (long)f.n * f.d * f.d_h, quads = per / 4, idx = (long)blockIdx.x * GT + threadIdx.x;
-    if (idx >= 4 * quads) return;
+    const long per = (long)f.n * f.d * f.d_h, quads = per / 4, tid = (long)blockIdx.x * GT + threadIdx.x;
+    if (tid >= 4 * quads * a.splits) return;
+    // a.splits > 1: the units are cut into that many contiguous ranges, one thread per (range, four elements),
+    // partial sums to a.partial [splits][4][per], added in range order by gen_smha_dw_reduce
+    const int sp = (int)(tid / (4 * quads));
+    const long idx = tid - (long)sp * 4 * quads;
+    const int per_range = (units + a.splits - 1) / a.splits;
+    const int g_first = sp * per_range, g_end = g_first + per_range < units ? g_first + per_range : units;
     const int which = (int)(idx / quads);   // 0..2: dW^q, dW^k, dW^v; 3: dW^O
     const long q = (idx - (long)which * quads) * 4;   // first of the four elements (d_h and d are multiples of 8)
     const int i = (int)(q / ((long)f.d * f.d_h));
@@ -557,7 +563,7 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw(SmhaBwdA
     const int e = which < 3 ? (int)(rem % f.d_h) : (int)(rem / f.d), j = which < 3 ? (int)(rem / f.d_h) : (int)(rem % f.d);
     const T *tokens = static_cast<const T *>(which < 3 ? f.x : a.d_out);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int g = 0; g < units; ++g) {
+    for (int g = g_first; g < g_end; ++g) {
         if (clampi(f.expert_idx[g], f.n) != i) continue;
         const int bb = g / f.k;
         const int32_t *picks = f.patch_idx + ((size_t)bb * f.n + i) * f.c;
@@ -584,9 +590,29 @@ template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw(SmhaBwdA
             }
         }
     }
+    if (a.splits > 1) {
+        float *part = a.partial + ((size_t)sp * 4 + which) * per + q;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) part[u] = acc[u];
+        return;
+    }
     T *dst = static_cast<T *>(which == 0 ? a.d_wq : which == 1 ? a.d_wk : which == 2 ? a.d_wv : a.d_wo);
 #pragma unroll
     for (int u = 0; u < 4; ++u) dst[q + u] = from_f32<T>(acc[u]);
+}
+
+// the unit ranges of gen_smha_dw added in order: thread = one weight-gradient element
+template <typename T> __global__ __launch_bounds__(GT) void gen_smha_dw_reduce(SmhaBwdArgs a)
+{
+    const SmhaArgs &f = a.f;
+    const long per = (long)f.n * f.d * f.d_h, idx = (long)blockIdx.x * GT + threadIdx.x;
+    if (idx >= 4 * per) return;
+    const int which = (int)(idx / per);
+    const long q = idx - (long)which * per;
+    float sum = 0.f;
+    for (int sp = 0; sp < a.splits; ++sp) sum += a.partial[((size_t)sp * 4 + which) * per + q];
+    T *dst = static_cast<T *>(which == 0 ? a.d_wq : which == 1 ? a.d_wk : which == 2 ? a.d_wv : a.d_wo);
+    dst[q] = from_f32<T>(sum);
 }
 
 template <typename T> hipError_t uome_backward_generic(const UomeBwdArgs &a, hipStream_t st)
@@ -634,7 +660,8 @@ template <typename T> hipError_t smha_backward_generic(const SmhaBwdArgs &a, hip
         UOE_GEN(gen_smha_rope, rope_pairs, f, dq, dq + f.d_h, 3 * f.d_h, 1);
     }
     UOE_GEN((gen_smha_dx<T>), (long)f.b * f.l * f.d, a);
-    UOE_GEN((gen_smha_dw<T>), (long)f.n * f.d * f.d_h, a);
+    UOE_GEN((gen_smha_dw<T>), (long)f.n * f.d * f.d_h * a.splits, a);
+    if (a.splits > 1) { UOE_GEN((gen_smha_dw_reduce<T>), 4L * f.n * f.d * f.d_h, a); }
 #undef UOE_GEN
     return hipSuccess;
 }
