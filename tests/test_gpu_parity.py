@@ -342,7 +342,7 @@ def fro_err(y, r):
     return float(np.sqrt(np.sum((y - r) ** 2)) / nr) if nr > 0 else float(np.any(y))
 
 
-@pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["tiny", "ragged_lp14", "lm", "vit", "vit_bwd", "longrange", "large"])
+@pytest.mark.parametrize("name", list(BWD_CONFIGS) + ["tiny", "ragged_lp14", "b1_n1", "lm", "vit", "vit_bwd", "longrange", "large"])
 @pytest.mark.parametrize("flags", [0, R | GE])
 def test_uome_backward_parity(name, flags):
     """uoe_uome_backward against the oracle's chain rule (itself pinned by finite differences of
@@ -446,7 +446,8 @@ ROUTER_GRAD_TOL = 5e-2
 @pytest.mark.parametrize("name,flags", [(nm, fl) for nm in list(SMHA_BWD_CONFIGS) + ["lm", "tiny", "ragged_lp14"]
                                         for fl in (0, R | GE | GP, R | GE | GP | CA)]
                          + [("vit", R | GE | GP), ("bf16_ragged", R | GE | GP | CA), ("longrange", R | GE | GP),
-                            ("large", R | GE | GP | CA)])
+                            ("large", R | GE | GP | CA),
+                            ("b1_n1", R | GE | GP)])   # one unit: the weight gradients of the vector-ALU path in one range
 def test_smha_backward_parity(name, flags):
     run_smha_backward(name, flags, 0)
 
