@@ -114,10 +114,10 @@ UomeBwdWs uome_bwd_ws(const uoe_block_desc *d)
     if (!uome_bwd_mfma(d)) {  // vector-ALU path: Z/H and dH/dZ in fp32
         const size_t act32 = up((size_t)d->b * d->l * d->k * d->width * sizeof(float));
         w.z = 0; w.dh = act32; w.total = 2 * act32;
-        // weight gradients: the (sample, slot) pairs cut into ranges until about 1024 tiles of 64x64 are
-        // in flight, partial tiles in fp32, added in range order
+        // weight gradients: the (sample, slot) pairs cut into ranges (at most 8) until about 4096 tiles of
+        // 64x64 exist, a few rounds of them per CU; partial tiles in fp32, added in range order
         const long tiles = 2L * d->n * ((d->d + 63) / 64) * ((d->width + 63) / 64);
-        long s = 1024 / tiles;
+        long s = 4096 / tiles;
         s = s < 1 ? 1 : (s > 8 ? 8 : s);
         if (s > (long)d->b * d->k) s = (long)d->b * d->k;
         w.splits = (int)s;
