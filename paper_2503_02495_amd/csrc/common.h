@@ -11,6 +11,29 @@ struct bf16_t {
     uint16_t v;
 };
 
+// 16-byte accesses with the non-temporal hint, for bytes a call touches once: an output nobody reads
+// again before the call ends, a residual at its last use.  Without the hint such streams displace, in L2
+// and in the memory-side cache, the tensors that later kernels of the same call do read again
+// (x, u, the hidden activations).  Operands that several workgroups share must NOT take it.
+// `once` is decided on the host (stream_once): tensors that fit the caches keep the plain accesses, which
+// let the next kernel find them there.
+typedef unsigned int once_u32x4 __attribute__((ext_vector_type(4)));
+template <bool ONCE> __device__ __forceinline__ void store16(void *p, uint4 v)
+{
+    const once_u32x4 w = {v.x, v.y, v.z, v.w};
+    if constexpr (ONCE) __builtin_nontemporal_store(w, reinterpret_cast<once_u32x4 *>(p));
+    else *reinterpret_cast<once_u32x4 *>(p) = w;
+}
+template <bool ONCE> __device__ __forceinline__ uint4 load16(const void *p)
+{
+    once_u32x4 w;
+    if constexpr (ONCE) w = __builtin_nontemporal_load(reinterpret_cast<const once_u32x4 *>(p));
+    else w = *reinterpret_cast<const once_u32x4 *>(p);
+    return make_uint4(w.x, w.y, w.z, w.w);
+}
+// a tensor of this many bytes is streamed past the caches (measured: 67 MB and up gain, 34 MB and down lose)
+inline bool stream_once(size_t bytes) { return bytes >= ((size_t)48 << 20); }
+
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.v) << 16); }
 

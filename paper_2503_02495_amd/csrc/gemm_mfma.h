@@ -28,6 +28,8 @@
 // tails are masked.
 #pragma once
 #include <type_traits>
+#include <utility>
+#include <type_traits>
 #include "common.h"
 
 namespace uoe {
@@ -118,6 +120,47 @@ __device__ __forceinline__ uint32_t pack2_f16_rn(float a, float b)
     return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
 }
 
+template <typename P, typename = void> struct streams_once : std::false_type {};
+template <typename P> struct streams_once<P, std::void_t<decltype(std::declval<P>().once)>> : std::true_type {};
+
+// second half of the epilogue: the staged wave tile back out of LDS in 16-byte pieces, the residual
+// added, the pieces stored (ONCE: through the problem's non-temporal accessors)
+template <typename P, int TM, int TN, int SPITCH, bool ONCE>
+__device__ __forceinline__ void wave_write_out(const P &p, uint16_t (*stage)[SPITCH], int g, int grow0, int gcol0, int M, int N, int lane)
+{
+    constexpr int WM = TM * 32, WN = TN * 32;
+    constexpr int WC = WN / 8;           // 16-byte pieces per staged row
+    constexpr int NPIECE = (WM * WC) / 64;
+    constexpr int BATCH = largest_divisor_upto(NPIECE, 8);
+    const bool res = p.has_residual();
+#pragma unroll
+    for (int t0 = 0; t0 < NPIECE; t0 += BATCH) {
+        uint4 r[BATCH];
+        if (res) {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int c = lane + (t0 + u) * 64;
+                const int grow = grow0 + c / WC, gcol = gcol0 + (c % WC) * 8;
+                if constexpr (streams_once<P>::value)
+                    r[u] = (grow < M && gcol < N) ? p.template res8_as<ONCE>(g, grow, gcol) : make_uint4(0, 0, 0, 0);
+                else r[u] = (grow < M && gcol < N) ? p.res8(g, grow, gcol) : make_uint4(0, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int c = lane + (t0 + u) * 64;
+            const int row = c / WC, pc = c % WC;
+            const int grow = grow0 + row, gcol = gcol0 + pc * 8;
+            uint4 piece = *reinterpret_cast<const uint4 *>(&stage[row][pc * 8]);
+            if (res) piece = add8_bf16(piece, r[u]);
+            if (grow < M && gcol < N) {
+                if constexpr (streams_once<P>::value) p.template put8_as<ONCE>(g, grow, gcol, piece);
+                else p.put8(g, grow, gcol, piece);
+            }
+        }
+    }
+}
+
 template <typename P, int TM, int TN, int SPITCH>
 __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN], uint16_t (*stage)[SPITCH], const float *coltab,
                                               const float (&rs)[TM], int g, int grow0, int gcol0, int wcol0, int M, int N,
@@ -165,30 +208,14 @@ __device__ __forceinline__ void wave_epilogue(const P &p, f32x16_t (&acc)[TM][TN
     // no workgroup barrier: a wave reads back only what it staged itself, and the LDS executes one
     // wave's instructions in order
     __builtin_amdgcn_wave_barrier();
-    constexpr int WC = WN / 8;           // 16-byte pieces per staged row
-    constexpr int NPIECE = (WM * WC) / 64;
-    constexpr int BATCH = largest_divisor_upto(NPIECE, 8);
-    const bool res = p.has_residual();
-#pragma unroll
-    for (int t0 = 0; t0 < NPIECE; t0 += BATCH) {
-        uint4 r[BATCH];
-        if (res) {
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int c = lane + (t0 + u) * 64;
-                const int grow = grow0 + c / WC, gcol = gcol0 + (c % WC) * 8;
-                r[u] = (grow < M && gcol < N) ? p.res8(g, grow, gcol) : make_uint4(0, 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int c = lane + (t0 + u) * 64;
-            const int row = c / WC, pc = c % WC;
-            const int grow = grow0 + row, gcol = gcol0 + pc * 8;
-            uint4 piece = *reinterpret_cast<const uint4 *>(&stage[row][pc * 8]);
-            if (res) piece = add8_bf16(piece, r[u]);
-            if (grow < M && gcol < N) p.put8(g, grow, gcol, piece);
-        }
+    // Problems with a `once` member choose per launch whether the residual read and the output store carry
+    // the non-temporal hint; the choice is made here, once per wave, so that each version keeps its
+    // batch of residual loads in flight (a test per access would put a branch between them).
+    if constexpr (streams_once<P>::value) {
+        if (p.once) wave_write_out<P, TM, TN, SPITCH, true>(p, stage, g, grow0, gcol0, M, N, lane);
+        else wave_write_out<P, TM, TN, SPITCH, false>(p, stage, g, grow0, gcol0, M, N, lane);
+    } else {
+        wave_write_out<P, TM, TN, SPITCH, false>(p, stage, g, grow0, gcol0, M, N, lane);
     }
 }
 

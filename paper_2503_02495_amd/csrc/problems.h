@@ -134,6 +134,7 @@ template <typename T, bool F32 = false> struct QkvProblem {
 // buffers, o = hi + lo, so that the attention output enters this contraction with ~16 significant
 // bits instead of 8 (the rows of W^o are simply visited twice).
 template <typename T> struct OutProjProblem {
+    bool once = false;   // this launch streams its output (and residual) past the caches: see store16, wave_write_out
     const T *o, *o_lo, *wo, *x;
     const int32_t *expert_idx, *patch_idx, *inv_cnt, *inv_ent;  // inv_*: engines without prepare()
     T *out;
@@ -230,14 +231,18 @@ template <typename T> struct OutProjProblem {
         return ((size_t)bb * l + p * l_p + r) * d + nn;
     }
     __device__ bool has_residual() const { return flags & F_RESIDUAL; }
-    __device__ uint4 res8(int g, int r, int nn) const { return *reinterpret_cast<const uint4 *>(x + at8(g, r, nn)); }
-    __device__ void put8(int g, int r, int nn, uint4 piece) const { *reinterpret_cast<uint4 *>(out + at8(g, r, nn)) = piece; }
+    __device__ uint4 res8(int g, int r, int nn) const { return res8_as<false>(g, r, nn); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const { put8_as<false>(g, r, nn, piece); }
+    // ONCE: the residual is this tensor's last use in the call and every output piece is written once
+    template <bool ONCE> __device__ uint4 res8_as(int g, int r, int nn) const { return load16<ONCE>(x + at8(g, r, nn)); }
+    template <bool ONCE> __device__ void put8_as(int g, int r, int nn, uint4 piece) const { store16<ONCE>(out + at8(g, r, nn), piece); }
 };
 
 // ---------------------------------------------------------------------------------------------
 // UoME Eq. 38: group = sample b; M = l; K = d; N = k*d_e (the sample's active experts side by
 // side); epilogue SiLU and the expert's gate.
 template <typename T, bool RAW = false> struct UomeUpProblem {
+    bool once = false;   // this launch streams its output (and residual) past the caches: see store16, wave_write_out
     const T *u, *a_in;
     const int32_t *expert_idx;
     const float *expert_gate;  // NULL: weight 1
@@ -279,9 +284,11 @@ template <typename T, bool RAW = false> struct UomeUpProblem {
     __device__ float epi(float val, float gate) const { return raw ? val : silu_fast(val) * gate; }
     __device__ bool has_residual() const { return false; }
     __device__ uint4 res8(int, int, int) const { return make_uint4(0, 0, 0, 0); }
-    __device__ void put8(int g, int r, int nn, uint4 piece) const
+    __device__ void put8(int g, int r, int nn, uint4 piece) const { put8_as<false>(g, r, nn, piece); }
+    template <bool ONCE> __device__ uint4 res8_as(int, int, int) const { return make_uint4(0, 0, 0, 0); }
+    template <bool ONCE> __device__ void put8_as(int g, int r, int nn, uint4 piece) const   // ONCE: 134 MB on the largest shape, streamed past L2
     {
-        *reinterpret_cast<uint4 *>(hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + nn) = piece;
+        store16<ONCE>(hidden + ((size_t)g * l + r) * ((size_t)kact * d_e) + nn, piece);
     }
 };
 
@@ -344,6 +351,7 @@ template <typename T> struct UomeDsUpProblem {
 // UoME Eq. 39 + Eq. 40: group = sample b; M = l; K = k*d_e (row slices of A^O of the active
 // experts stacked); N = d; epilogue adds the residual.  One write per output element.
 template <typename T> struct UomeDownProblem {
+    bool once = false;   // this launch streams its output (and residual) past the caches: see store16, wave_write_out
     const T *hidden, *a_out, *u;
     const int32_t *expert_idx;
     T *out;
@@ -382,8 +390,11 @@ template <typename T> struct UomeDownProblem {
     __device__ float col_scale(int, int) const { return 1.0f; }
     __device__ float epi(float val, float) const { return val; }
     __device__ bool has_residual() const { return flags & F_RESIDUAL; }
-    __device__ uint4 res8(int g, int r, int nn) const { return *reinterpret_cast<const uint4 *>(u + ((size_t)g * l + r) * d + nn); }
-    __device__ void put8(int g, int r, int nn, uint4 piece) const { *reinterpret_cast<uint4 *>(out + ((size_t)g * l + r) * d + nn) = piece; }
+    __device__ uint4 res8(int g, int r, int nn) const { return res8_as<false>(g, r, nn); }
+    __device__ void put8(int g, int r, int nn, uint4 piece) const { put8_as<false>(g, r, nn, piece); }
+    // ONCE: u's last use and the block's output
+    template <bool ONCE> __device__ uint4 res8_as(int g, int r, int nn) const { return load16<ONCE>(u + ((size_t)g * l + r) * d + nn); }
+    template <bool ONCE> __device__ void put8_as(int g, int r, int nn, uint4 piece) const { store16<ONCE>(out + ((size_t)g * l + r) * d + nn, piece); }
 };
 
 // ---------------------------------------------------------------------------------------------

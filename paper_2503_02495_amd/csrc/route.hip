@@ -564,6 +564,13 @@ __device__ __forceinline__ void rs_dma16(const void *gptr, uint32_t lds_byte)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte), "v"(gptr) : "memory", "m0");
 }
+// The same with the non-temporal hint, for the rows of W_E: they are read once per call and are larger
+// than the memory-side cache, where they would push out x, u and the hidden activations that the
+// kernels after the router read again.
+__device__ __forceinline__ void rs_dma16_once(const void *gptr, uint32_t lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_byte), "v"(gptr) : "memory", "m0");
+}
 #pragma clang diagnostic pop
 // wait until at most n (0..16) of this wave's vector-memory operations are outstanding
 __device__ __forceinline__ void rs_wait(int n)
@@ -612,7 +619,8 @@ __global__ __launch_bounds__(256) void route_stream_kernel(RouteArgs a, int ipw)
                                            : static_cast<const uint16_t *>(a.w_e) + (size_t)(rc - bg) * ld;
             long e = c0 + (long)st * SE + (((lane % LPR) ^ (row & 15)) * 8);
             e = e < ld - 8 ? e : ld - 8;           // past the end of the row: any valid address (never used)
-            rs_dma16(base + e, lds_base + buf * SB + ins * 1024);
+            if (ins * RPI >= bg) rs_dma16_once(base + e, lds_base + buf * SB + ins * 1024);   // all rows of the instruction are W_E's (wave-uniform)
+            else rs_dma16(base + e, lds_base + buf * SB + ins * 1024);
         }
     };
 #pragma unroll

@@ -875,6 +875,7 @@ static hipError_t smha_mfma(const SmhaArgs &a, hipStream_t st)
     const bool mfma_attn = (a.d_h == 32 || a.d_h == 64 || a.d_h == 128) && (long)a.c * l_p * a.d_h < (1L << 31);
 
     OP op = make_outproj<bf16_t>(a);
+    op.once = stream_once((size_t)a.b * a.l * a.d * sizeof(bf16_t));
     if (mfma_attn) {  // the MFMA attention kernel writes o as a (hi, lo) bf16 pair
         op.o_lo = static_cast<const bf16_t *>(a.o_lo);
         op.parts = 2;

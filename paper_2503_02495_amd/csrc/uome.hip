@@ -67,6 +67,7 @@ static hipError_t uome_up_mfma(const UomeArgs &a, hipStream_t st)
     up.expert_gate = (a.flags & F_GATE_EXPERT) ? a.expert_gate : nullptr;
     up.hidden = static_cast<bf16_t *>(a.hidden);
     up.l = a.l; up.d = a.d; up.n = a.n; up.kact = a.k; up.d_e = a.d_e;
+    up.once = stream_once((size_t)a.b * a.l * a.k * a.d_e * sizeof(bf16_t));
     return uome_gemm(up, a.b, a.l, a.k * a.d_e, a.d, st);  // K segment = d
 }
 
@@ -79,6 +80,7 @@ static hipError_t uome_down_mfma(const UomeArgs &a, hipStream_t st)
     dn.expert_idx = a.expert_idx;
     dn.out = static_cast<bf16_t *>(a.out);
     dn.l = a.l; dn.d = a.d; dn.n = a.n; dn.kact = a.k; dn.d_e = a.d_e; dn.flags = a.flags;
+    dn.once = stream_once((size_t)a.b * a.l * a.d * sizeof(bf16_t));
     return uome_gemm(dn, a.b, a.l, a.d, a.d_e, st);  // K segments = the active experts' d_e rows
 }
 
