@@ -26,6 +26,27 @@ template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *p, const floa
     *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// W_E and its gradient are read or written once per call and are larger than the memory-side cache on the
+// big shapes: with ONCE (chosen per launch, stream_once) their 16-byte accesses carry the non-temporal hint,
+// so that they do not push x and d_x out of the caches.  fp32 storage keeps the plain accesses.
+template <bool ONCE> __device__ __forceinline__ void load8_w(const float *p, float (&o)[8]) { load8(p, o); }
+template <bool ONCE> __device__ __forceinline__ void load8_w(const bf16_t *p, float (&o)[8])
+{
+    const uint4 a = load16<ONCE>(p);
+    o[0] = __uint_as_float(a.x << 16); o[1] = __uint_as_float(a.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(a.y << 16); o[3] = __uint_as_float(a.y & 0xFFFF0000u);
+    o[4] = __uint_as_float(a.z << 16); o[5] = __uint_as_float(a.z & 0xFFFF0000u);
+    o[6] = __uint_as_float(a.w << 16); o[7] = __uint_as_float(a.w & 0xFFFF0000u);
+}
+template <bool ONCE> __device__ __forceinline__ void store8_w(float *p, const float (&v)[8]) { store8<float>(p, v); }
+template <bool ONCE> __device__ __forceinline__ void store8_w(bf16_t *p, const float (&v)[8])
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)f32_to_bf16_bits(v[2 * e]) | ((uint32_t)f32_to_bf16_bits(v[2 * e + 1]) << 16);
+    store16<ONCE>(p, make_uint4(w[0], w[1], w[2], w[3]));
+}
+
 // Softmax backward of both routers: block = sample.  dz_i = g_i (dg_i - sum_j g_j dg_j) is
 // evaluated as g_i * sum_j g_j (dg_i - dg_j) (the gates sum to one): with one gate close to 1 the
 // first form subtracts two nearly equal numbers, the second adds small terms of mixed sign only.
@@ -52,7 +73,7 @@ __global__ __launch_bounds__(64) void route_bwd_softmax_kernel(RouteBwdArgs a)
 }
 
 // dW_E[i, q] = sum_b dz[b,i] x[b,q]: thread = 8 consecutive q, block.y = a group of 8 experts
-template <typename T> __global__ __launch_bounds__(256) void route_bwd_wexpert_kernel(RouteBwdArgs a)
+template <typename T, bool ONCE> __global__ __launch_bounds__(256) void route_bwd_wexpert_kernel(RouteBwdArgs a)
 {
     constexpr int EG = 8;
     __shared__ float dzs[128 * EG];
@@ -83,11 +104,11 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_wexpert_k
     T *dw = static_cast<T *>(a.d_w_e) + q;
 #pragma unroll
     for (int e = 0; e < EG; ++e)
-        if (e < ne) store8<T>(dw + (size_t)(e0 + e) * ld, acc[e]);
+        if (e < ne) store8_w<ONCE>(dw + (size_t)(e0 + e) * ld, acc[e]);
 }
 
 // d_x[b, q] += sum_i dz[b,i] W_E[i,q]: thread = 8 consecutive q, block.y = a group of 8 samples
-template <typename T> __global__ __launch_bounds__(256) void route_bwd_xexpert_kernel(RouteBwdArgs a)
+template <typename T, bool ONCE> __global__ __launch_bounds__(256) void route_bwd_xexpert_kernel(RouteBwdArgs a)
 {
     constexpr int BG = 8;
     __shared__ float dzs[BG * 32];
@@ -107,7 +128,7 @@ template <typename T> __global__ __launch_bounds__(256) void route_bwd_xexpert_k
     const T *w = static_cast<const T *>(a.w_e) + q;
     for (int i = 0; i < a.n; ++i) {
         float wv[8];
-        load8(w + (size_t)i * ld, wv);
+        load8_w<ONCE>(w + (size_t)i * ld, wv);
 #pragma unroll
         for (int s = 0; s < BG; ++s) {
             const float z = dzs[s * 32 + i];
@@ -292,9 +313,12 @@ template <typename T> static hipError_t route_backward(const RouteBwdArgs &a, hi
     const long pieces = (long)a.l * a.d / 8;
     const unsigned pblocks = (unsigned)((pieces + 255) / 256);
     if (a.w_e) {
-        hipLaunchKernelGGL((route_bwd_wexpert_kernel<T>), dim3(pblocks, (a.n + 7) / 8), dim3(256), 0, st, a);
+        const bool once = stream_once((size_t)a.n * a.l * a.d * sizeof(T));
+        if (once) hipLaunchKernelGGL((route_bwd_wexpert_kernel<T, true>), dim3(pblocks, (a.n + 7) / 8), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((route_bwd_wexpert_kernel<T, false>), dim3(pblocks, (a.n + 7) / 8), dim3(256), 0, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
-        hipLaunchKernelGGL((route_bwd_xexpert_kernel<T>), dim3(pblocks, (a.b + 7) / 8), dim3(256), 0, st, a);
+        if (once) hipLaunchKernelGGL((route_bwd_xexpert_kernel<T, true>), dim3(pblocks, (a.b + 7) / 8), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((route_bwd_xexpert_kernel<T, false>), dim3(pblocks, (a.b + 7) / 8), dim3(256), 0, st, a);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (a.w_b) {

@@ -169,6 +169,7 @@ hipError_t launch_uome_backward(const UomeBwdArgs &a, hipStream_t st)
     zp.u = static_cast<const T *>(a.u); zp.a_in = static_cast<const T *>(a.a_in);
     zp.expert_idx = a.expert_idx; zp.expert_gate = nullptr; zp.hidden = static_cast<T *>(a.z);
     zp.l = a.l; zp.d = a.d; zp.n = a.n; zp.kact = a.k; zp.d_e = a.d_e;
+    zp.once = stream_once((size_t)a.b * a.l * width * sizeof(T));   // Z and dH: written here, read once by the next kernel
     if ((err = launch_gemm_dma_auto(zp, a.b, a.l, width, a.d, st)) != hipSuccess) return err;
     UomeUpProblem<T, true> hp = zp;  // dH = d_out W2_b^T: the same contraction with (A^O_i)^T [d, d_e] as the weight
     hp.u = static_cast<const T *>(a.d_out); hp.a_in = static_cast<const T *>(a.a_out_t); hp.hidden = static_cast<T *>(a.dh);
