@@ -17,6 +17,10 @@
 //                                 epilogue passes col_scale * row_scale to epi
 //   has_residual() / res8(g, m, nn)  the 16-byte piece of the residual row, loaded in batches
 //   put8(g, m, nn, piece)         plain store of a finished piece
+//   once, res8_as<ONCE> / put8_as<ONCE>  (optional) a problem with a `once` member lets the launch choose the
+//                                 non-temporal versions of the two accesses above, for outputs and
+//                                 residuals that this call touches exactly once and that are too large
+//                                 for the caches
 // and, for the pipelined engine (which may not touch global memory through the compiler inside
 // its K loop),
 //   seg_ctx(g, seg)               32 bits of routing context of a K segment, looked up once per tile
