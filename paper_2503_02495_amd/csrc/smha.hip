@@ -960,7 +960,8 @@ static hipError_t uome_ds_mfma(const UomeDsArgs &a, hipStream_t st)
                                            : launch_gemm_dma<UP, 128, 128, 32, 2, 2, 4, 2>(up, units, l_a, a.d_e, st);
     else err = launch_gemm_mfma<UP, 64, 64, 32, 2, 2>(up, units, l_a, a.d_e, st);
     if (err != hipSuccess) return err;
-    const OP op = make_ds_down<bf16_t>(a);
+    OP op = make_ds_down<bf16_t>(a);
+    op.once = stream_once((size_t)a.b * a.l * a.d * sizeof(bf16_t));   // u's last use, the block's output
     if (!out_dma) {
         if (l_p <= 32) return launch_gemm_mfma<OP, 32, 128, 32, 1, 4>(op, a.b * a.m, l_p, a.d, st);
         return launch_gemm_mfma<OP, 64, 128, 32, 2, 2>(op, a.b * a.m, l_p, a.d, st);
