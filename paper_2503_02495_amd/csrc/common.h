@@ -1,5 +1,6 @@
 // Shared device helpers and the internal launcher interface of libuoe (gfx950 only).
 #pragma once
+#include <cstdlib>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -31,8 +32,14 @@ template <bool ONCE> __device__ __forceinline__ uint4 load16(const void *p)
     else w = *reinterpret_cast<const once_u32x4 *>(p);
     return make_uint4(w.x, w.y, w.z, w.w);
 }
-// a tensor of this many bytes is streamed past the caches (measured: 67 MB and up gain, 34 MB and down lose)
-inline bool stream_once(size_t bytes) { return bytes >= ((size_t)48 << 20); }
+// a tensor of this many bytes is streamed past the caches (measured: 67 MB and up gain, 34 MB and down lose);
+// UOE_STREAM_ONCE_MIN_BYTES in the environment overrides the threshold (0: always, for tests of the hinted paths)
+inline bool stream_once(size_t bytes)
+{
+    const char *env = getenv("UOE_STREAM_ONCE_MIN_BYTES");
+    const double min_bytes = env ? atof(env) : 48.0 * 1048576.0;
+    return (double)bytes >= min_bytes;
+}
 
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.v) << 16); }

@@ -1033,6 +1033,37 @@ def test_layer_parity(name):
         assert same.all()
 
 
+@pytest.mark.parametrize("name", ["bf16_ragged", "lm"])
+def test_cache_hints_do_not_change_results(name, monkeypatch):
+    """The non-temporal stores and residual reads that the size rule reserves for tensors of 48 MB and more,
+    forced on for a small shape: the layer's output, the SMHA output u and both backward passes' results must be
+    bit-identical to the plain accesses (the hints only say where the bytes should not be cached)."""
+    cfg = get_cfg(name)
+    inp = synth.make_inputs(cfg, w_std=w_std_for(name))
+
+    def run():
+        dev = DeviceLayer(inp, R | GE | GP, R | GE)
+        dev.layer_forward()
+        dev.smha_forward()
+        torch.cuda.synchronize()
+        return dev.out.clone(), dev.u.clone()
+
+    out_plain, u_plain = run()
+    monkeypatch.setenv("UOE_STREAM_ONCE_MIN_BYTES", "0")
+    out_hint, u_hint = run()
+    assert torch.equal(out_plain.view(torch.int16), out_hint.view(torch.int16))
+    assert torch.equal(u_plain.view(torch.int16), u_hint.view(torch.int16))
+
+
+def test_cache_hints_backward_parity(monkeypatch):
+    """The backward pass with the hinted accesses forced on (W_E and its gradient in the routers' backward, Z and dH
+    in the UoME backward, the d_x epilogues): the same oracle parity as with the plain ones, on a small shape where
+    the oracle covers every element."""
+    monkeypatch.setenv("UOE_STREAM_ONCE_MIN_BYTES", "0")
+    run_layer_backward("lm", R | GE | GP | CA, 32)
+    test_route_backward_parity("bf16_noise")
+
+
 def test_layer_is_deterministic_and_reusable():
     """Two calls on the same buffers give bit-identical results (no atomics, no stale scratch)."""
     cfg = get_cfg("bf16_ragged")
