@@ -25,7 +25,10 @@
  *   - Environment: UOE_ROUTE_STREAM_MIN_BYTES (read at every routing call) moves the input size, in
  *     bytes of x plus the expert router's weights, from which the routers run as one streaming
  *     pass over x (default 100e6; 0 = whenever that kernel applies).  Results do not depend on it
- *     beyond the summation order of the router logits.
+ *     beyond the summation order of the router logits.  UOE_STREAM_ONCE_MIN_BYTES (read at every call)
+ *     moves the tensor size, in bytes, from which outputs that a call writes once and residuals at
+ *     their last use are accessed with the non-temporal hint (default 48 MiB; 0 = always).  Results
+ *     do not depend on it at all.
  *   - Shape limits, all checked on the host before anything is launched (a valid request outside
  *     them returns UOE_ERR_UNSUPPORTED): d % 8 == 0, width % 8 == 0, l % m == 0, 1 <= n <= 32,
  *     1 <= k <= n, 1 <= c <= m, m <= 1024, n*m <= 8192, width <= 128 for SMHA, b*m <= 65535 and
