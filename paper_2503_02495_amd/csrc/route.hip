@@ -585,7 +585,7 @@ __device__ __forceinline__ void rs_wait(int n)
 }
 
 template <int RT, int CT, int RB, bool HAS_D>
-__global__ __launch_bounds__(256) void route_stream_kernel(RouteArgs a, int ipw)
+__global__ __launch_bounds__(256) void route_stream_kernel(RouteArgs a, int ipw, int once)
 {
     constexpr int STAGES = 3, SE = RB / 2, SPS = SE / 32, LPR = RB / 16, RPI = 64 / LPR;
     constexpr int NP = CT * 16, ROWB = NP * 2, BLK = 8 * ROWB + (NP == 16 ? 128 : 32);
@@ -619,7 +619,7 @@ __global__ __launch_bounds__(256) void route_stream_kernel(RouteArgs a, int ipw)
                                            : static_cast<const uint16_t *>(a.w_e) + (size_t)(rc - bg) * ld;
             long e = c0 + (long)st * SE + (((lane % LPR) ^ (row & 15)) * 8);
             e = e < ld - 8 ? e : ld - 8;           // past the end of the row: any valid address (never used)
-            if (ins * RPI >= bg) rs_dma16_once(base + e, lds_base + buf * SB + ins * 1024);   // all rows of the instruction are W_E's (wave-uniform)
+            if (once && ins * RPI >= bg) rs_dma16_once(base + e, lds_base + buf * SB + ins * 1024);   // all rows of the instruction are W_E's (wave-uniform)
             else rs_dma16(base + e, lds_base + buf * SB + ins * 1024);
         }
     };
@@ -1211,7 +1211,9 @@ static hipError_t launch_stream(const RouteArgs &a, const RouteStreamPlan &sp, d
         if (err != hipSuccess) return err;
         allowed[dev] = true;
     }
-    hipLaunchKernelGGL((route_stream_kernel<RT, CT, RB, HAS_D>), grid, dim3(256), sp.lds, st, a, sp.ipw);
+    // W_E is read once per call: non-temporal from the size on that stream_once names (always, at the sizes this kernel is chosen for)
+    const int once = stream_once((size_t)a.n * a.l * a.d * 2) ? 1 : 0;
+    hipLaunchKernelGGL((route_stream_kernel<RT, CT, RB, HAS_D>), grid, dim3(256), sp.lds, st, a, sp.ipw, once);
     return hipGetLastError();
 }
 
